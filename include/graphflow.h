@@ -1,0 +1,208 @@
+/*
+ * graphflow.h -- C ABI of the MI355X (gfx950) graph-KV attention library.
+ *
+ * The operation (paper: "Topology-Aware State Management"): every operation
+ * node of the wGraph (paper: "Overview", G_op = (V_op, E_op)) owns one
+ * precomputed KV segment, stored ONCE in a paged block pool and shared by all
+ * requests whose workflow passes through the node.  A request's context is the
+ * prefix path P of nodes (paper: Eq. 7, taken with a zero residual), its KV is
+ * assembled from those nodes' blocks through a per-request block table, and
+ * new prefill tokens / decode steps attend to it without recomputing or
+ * copying the shared part.
+ *
+ * Conventions
+ *   - Every call returns int32: GF_OK (0) or a negative GF_ERR_* code.  No
+ *     exception crosses the boundary.  gf_strerror() names a code.
+ *   - All data pointers are DEVICE pointers owned by the caller, unless a
+ *     parameter says "host".  The gf_graph / gf_attn_params / gf_kv_pool /
+ *     gf_tables structs themselves are small HOST structs read during the call.
+ *   - Calls are asynchronous on the caller's HIP stream (`stream`, a
+ *     hipStream_t passed as void*; NULL = the default stream).  Nothing is
+ *     synchronised inside.  Data-dependent failures are reported per request
+ *     in the device array status[] (GF_ST_*), not through the return value.
+ *   - The library owns only a gf_ctx: device workspace for split-KV partials,
+ *     grown on demand by gf_attn_decode (which may therefore call hipMalloc)
+ *     and released by gf_destroy.  A gf_ctx must not be used from two streams
+ *     at once.
+ *   - Index arrays are int32.  Block size is 16 tokens.
+ *
+ * Pool layout (one layer), block size B = 16, element = bf16 or e4m3 byte:
+ *     K[num_blocks][num_kv_heads][B][head_dim]      token-major inside a block
+ *     V[num_blocks][num_kv_heads][head_dim][B]      head-dim-major inside a block
+ *   Token t of a node lives in that node's block t/16, slot t%16.  Slots at or
+ *   beyond a block's token count hold finite, unspecified values; NaN/Inf there
+ *   is a contract violation.  With GF_FP8_E4M3 (OCP E4M3, finite-only, max 448)
+ *   every block has one fp32 scale per tensor: value = decode(code) * scale[blk].
+ *
+ * Supported shapes: head_dim in {64,128}; block_size 16; num_q_heads a
+ * multiple of num_kv_heads with group size in {1,2,4,8}.  Anything else
+ * returns GF_ERR_UNSUPPORTED; there is no fallback path.
+ */
+#ifndef GRAPHFLOW_H
+#define GRAPHFLOW_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* return codes */
+#define GF_OK               0
+#define GF_ERR_NULL        -1   /* a required pointer is NULL                   */
+#define GF_ERR_BAD_SHAPE   -2   /* negative / inconsistent sizes                */
+#define GF_ERR_UNSUPPORTED -3   /* shape or dtype outside the supported set     */
+#define GF_ERR_WORKSPACE   -4   /* device workspace could not be (re)allocated  */
+#define GF_ERR_HIP         -5   /* a HIP runtime call or kernel launch failed   */
+
+/* per-request status words written by gf_resolve_path */
+#define GF_ST_OK         0
+#define GF_ST_BAD_NODE   1   /* a path entry is not a node id                        */
+#define GF_ST_BAD_EDGE   2   /* consecutive path nodes are not joined by an edge     */
+#define GF_ST_BAD_TAIL   3   /* fewer tail blocks than ceil(new_len/16), or new_len<0 */
+#define GF_ST_BAD_BLOCK  4   /* a node owns too few blocks, or a block id is outside the pool */
+#define GF_ST_OVERFLOW   5   /* the request needs more than max_blocks table entries */
+
+/* kv_dtype */
+#define GF_BF16     0
+#define GF_FP8_E4M3 1
+
+typedef struct gf_ctx gf_ctx;
+
+/* wGraph as CSR arrays (device).  Node v owns the token segment of length
+ * node_len[v] stored in blocks node_blocks[node_block_ptr[v] .. node_block_ptr[v+1]).
+ * edge_dst[edge_ptr[v] .. edge_ptr[v+1]) are v's valid successors; edge_ptr and
+ * edge_dst may both be NULL, which skips edge validation. */
+typedef struct {
+    int32_t        num_nodes;
+    const int32_t *node_len;        /* [num_nodes]     */
+    const int32_t *node_block_ptr;  /* [num_nodes + 1] */
+    const int32_t *node_blocks;     /* [node_block_ptr[num_nodes]] */
+    const int32_t *edge_ptr;        /* [num_nodes + 1] or NULL */
+    const int32_t *edge_dst;        /* [edge_ptr[num_nodes]] or NULL */
+} gf_graph;
+
+typedef struct {
+    int32_t num_q_heads;
+    int32_t num_kv_heads;
+    int32_t head_dim;
+    int32_t block_size;   /* must be 16 */
+    int32_t kv_dtype;     /* GF_BF16 | GF_FP8_E4M3 */
+    float   sm_scale;     /* softmax scale; 0 selects 1/sqrt(head_dim); must not be negative */
+} gf_attn_params;
+
+typedef struct {
+    const void  *k;        /* K pool, layout above (device) */
+    const void  *v;        /* V pool, layout above (device) */
+    const float *k_scale;  /* [num_blocks] fp32, GF_FP8_E4M3 only, else NULL */
+    const float *v_scale;  /* [num_blocks] fp32, GF_FP8_E4M3 only, else NULL */
+    int32_t      num_blocks;
+} gf_kv_pool;
+
+/* The outputs of gf_resolve_path, handed to the attention calls (device). */
+typedef struct {
+    const int32_t *block_table;  /* [num_req][max_blocks], pad -1 */
+    const int32_t *block_ntok;   /* [num_req][max_blocks], pad 0  */
+    const int32_t *num_blocks;   /* [num_req] */
+    const int32_t *ctx_lens;     /* [num_req] */
+    const int32_t *seq_lens;     /* [num_req] */
+    const int32_t *status;       /* [num_req] or NULL (all requests taken as valid) */
+    int32_t        num_req;
+    int32_t        max_blocks;
+} gf_tables;
+
+/* Create / destroy a context on HIP device `device`.  gf_create makes that
+ * device current for the calling thread. */
+int32_t gf_create(gf_ctx **out, int32_t device);
+int32_t gf_destroy(gf_ctx *ctx);
+
+/* Text for a GF_ERR_* code (static string, host). */
+const char *gf_strerror(int32_t code);
+
+/* Text of the last HIP error seen by this context (host string owned by ctx). */
+const char *gf_last_hip_error(const gf_ctx *ctx);
+
+/*
+ * gf_resolve_path -- wGraph node path -> block table + lengths.
+ * (Paper: the KV of a workflow is assembled from its selected operation nodes;
+ *  P in Eq. 7 is the prefix path; E_op holds the valid transitions.)
+ *
+ * Request r has the node path path_nodes[path_ptr[r] .. path_ptr[r+1]) (may be
+ * empty), new_lens[r] new tokens (new_lens NULL = 0 for all) whose K/V live in
+ * the private tail blocks tail_blocks[tail_ptr[r] .. tail_ptr[r+1]) (tail_ptr
+ * and tail_blocks NULL = no tail blocks; then new_lens must be 0).
+ * For a valid request it writes
+ *   block_table[r][:]  the nodes' block lists in path order, then the first
+ *                      ceil(new_len/16) tail blocks, then -1 up to max_blocks
+ *   block_ntok[r][:]   valid tokens per entry: 16, except the last block of
+ *                      each segment (remainder); 0 in the padding
+ *   num_blocks[r], ctx_lens[r] = sum node_len, seq_lens[r] = ctx + new_len,
+ *   status[r] = GF_ST_OK.
+ * For an invalid request it writes status[r] = the first failing class in the
+ * order BAD_NODE, BAD_EDGE, BAD_TAIL, BAD_BLOCK, OVERFLOW, and pad outputs
+ * (table -1, ntok 0, num_blocks 0, both lengths 0).
+ * Integer work only; results are exact.  Every output array is fully written.
+ */
+int32_t gf_resolve_path(gf_ctx *ctx, const gf_graph *graph, int32_t num_req,
+                        const int32_t *path_ptr,    /* [num_req+1] device */
+                        const int32_t *path_nodes,  /* device */
+                        const int32_t *new_lens,    /* [num_req] device or NULL */
+                        const int32_t *tail_ptr,    /* [num_req+1] device or NULL */
+                        const int32_t *tail_blocks, /* device or NULL */
+                        int32_t max_blocks, int32_t num_pool_blocks,
+                        int32_t *block_table,       /* [num_req][max_blocks] device, out */
+                        int32_t *block_ntok,        /* [num_req][max_blocks] device, out */
+                        int32_t *num_blocks,        /* [num_req] device, out */
+                        int32_t *ctx_lens,          /* [num_req] device, out */
+                        int32_t *seq_lens,          /* [num_req] device, out */
+                        int32_t *status,            /* [num_req] device, out */
+                        void *stream);
+
+/*
+ * gf_attn_prefill -- new tokens attend to the ancestor-node KV (and causally
+ * to each other) through the block table, "without repeated prefill" of the
+ * shared prefix; it is also the on-the-fly fallback of the paper's "Effective
+ * Path Pruning".
+ *
+ * Request r owns query rows q_ptr[r] .. q_ptr[r+1) (n_r = seq_lens[r] -
+ * ctx_lens[r] of them; the K/V of those new tokens are already in the tail
+ * blocks).  For row i and query head h (kv head h / G):
+ *   o[i,h,:] = sum_j softmax_j( sm_scale * <q[i,h,:], K_j> ) V_j
+ * over j in {all ctx_lens[r] context tokens} U {new tokens 0..i}.
+ *   q   [total_q][num_q_heads][head_dim] bf16 (device, in)
+ *   o   same shape, bf16 round-to-nearest-even (device, out)
+ *   lse [total_q][num_q_heads] fp32 natural-log log-sum-exp of the scaled
+ *       scores, or NULL (device, out)
+ *   max_q  an upper bound on n_r over the batch (host value; sizes the grid).
+ * Rows of requests whose status is non-zero are left untouched.
+ * Accumulation and softmax are fp32.
+ */
+int32_t gf_attn_prefill(gf_ctx *ctx, const gf_attn_params *params, const gf_kv_pool *pool,
+                        const gf_tables *tables,
+                        const void *q, const int32_t *q_ptr /* [num_req+1] device */,
+                        int32_t total_q, int32_t max_q,
+                        void *o, float *lse, void *stream);
+
+/*
+ * gf_attn_decode -- one decode step per request: the query of request r is the
+ * last of its seq_lens[r] tokens and attends to all of them (all context
+ * tokens of the path plus every token in its tail blocks), by the same formula.
+ *   q   [num_req][num_q_heads][head_dim] bf16 (device, in)
+ *   o   same shape bf16 (device, out);  lse [num_req][num_q_heads] fp32 or NULL
+ * The context is cut into chunks of blocks that are reduced independently
+ * (fp32 partial max / sum / weighted values in the context's workspace) and
+ * merged with the log-sum-exp rule.  Requests whose status is non-zero, or
+ * whose seq_len is 0, get zero rows (lse -inf).
+ */
+int32_t gf_attn_decode(gf_ctx *ctx, const gf_attn_params *params, const gf_kv_pool *pool,
+                       const gf_tables *tables,
+                       const void *q, void *o, float *lse, void *stream);
+
+/* Tuning knob (host): table entries (16-token blocks) per split-KV chunk in
+ * gf_attn_decode; 0 restores the built-in choice.  Must be even. */
+int32_t gf_set_decode_chunk_blocks(gf_ctx *ctx, int32_t chunk_blocks);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GRAPHFLOW_H */

@@ -1,0 +1,168 @@
+"""ctypes binding of libgraphflow.so: argument marshalling only.
+
+Every function here has the name and the arguments of the C entry point it
+calls (include/graphflow.h); tensors are torch tensors that already live on the
+GPU and are passed as raw device pointers, and the HIP stream is torch's
+current stream.  Nothing is computed in Python and there is no fallback: if the
+library is not built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libgraphflow.so")
+
+GF_OK = 0
+GF_ERR_NULL, GF_ERR_BAD_SHAPE, GF_ERR_UNSUPPORTED, GF_ERR_WORKSPACE, GF_ERR_HIP = -1, -2, -3, -4, -5
+GF_ST_OK, GF_ST_BAD_NODE, GF_ST_BAD_EDGE, GF_ST_BAD_TAIL, GF_ST_BAD_BLOCK, GF_ST_OVERFLOW = 0, 1, 2, 3, 4, 5
+GF_BF16, GF_FP8_E4M3 = 0, 1
+
+EXPORTS = ["gf_create", "gf_destroy", "gf_strerror", "gf_last_hip_error", "gf_resolve_path",
+           "gf_attn_prefill", "gf_attn_decode", "gf_set_decode_chunk_blocks"]
+
+_i32p = C.c_void_p  # device pointers travel as plain addresses
+
+
+class gf_graph(C.Structure):
+    _fields_ = [("num_nodes", C.c_int32), ("node_len", _i32p), ("node_block_ptr", _i32p),
+                ("node_blocks", _i32p), ("edge_ptr", _i32p), ("edge_dst", _i32p)]
+
+
+class gf_attn_params(C.Structure):
+    _fields_ = [("num_q_heads", C.c_int32), ("num_kv_heads", C.c_int32), ("head_dim", C.c_int32),
+                ("block_size", C.c_int32), ("kv_dtype", C.c_int32), ("sm_scale", C.c_float)]
+
+
+class gf_kv_pool(C.Structure):
+    _fields_ = [("k", C.c_void_p), ("v", C.c_void_p), ("k_scale", C.c_void_p), ("v_scale", C.c_void_p),
+                ("num_blocks", C.c_int32)]
+
+
+class gf_tables(C.Structure):
+    _fields_ = [("block_table", _i32p), ("block_ntok", _i32p), ("num_blocks", _i32p), ("ctx_lens", _i32p),
+                ("seq_lens", _i32p), ("status", _i32p), ("num_req", C.c_int32), ("max_blocks", C.c_int32)]
+
+
+class GraphFlowError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"libgraphflow error {code}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+
+def load_library(path: Optional[str] = None):
+    """Load libgraphflow.so (built in-tree by paper_2605_22566_amd/build.py)."""
+    global _lib
+    if _lib is not None and path is None:
+        return _lib
+    p = path or LIB_PATH
+    if not os.path.exists(p):
+        raise FileNotFoundError(
+            f"{p} is missing: build it with `python paper_2605_22566_amd/build.py` "
+            "(or __graft_entry__.build()); there is no fallback path")
+    lib = C.CDLL(p)
+    lib.gf_create.argtypes = [C.POINTER(C.c_void_p), C.c_int32]
+    lib.gf_create.restype = C.c_int32
+    lib.gf_destroy.argtypes = [C.c_void_p]
+    lib.gf_destroy.restype = C.c_int32
+    lib.gf_strerror.argtypes = [C.c_int32]
+    lib.gf_strerror.restype = C.c_char_p
+    lib.gf_last_hip_error.argtypes = [C.c_void_p]
+    lib.gf_last_hip_error.restype = C.c_char_p
+    lib.gf_set_decode_chunk_blocks.argtypes = [C.c_void_p, C.c_int32]
+    lib.gf_set_decode_chunk_blocks.restype = C.c_int32
+    lib.gf_resolve_path.argtypes = [C.c_void_p, C.POINTER(gf_graph), C.c_int32] + [C.c_void_p] * 5 + \
+        [C.c_int32, C.c_int32] + [C.c_void_p] * 6 + [C.c_void_p]
+    lib.gf_resolve_path.restype = C.c_int32
+    lib.gf_attn_prefill.argtypes = [C.c_void_p, C.POINTER(gf_attn_params), C.POINTER(gf_kv_pool),
+                                    C.POINTER(gf_tables), C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
+                                    C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.gf_attn_prefill.restype = C.c_int32
+    lib.gf_attn_decode.argtypes = [C.c_void_p, C.POINTER(gf_attn_params), C.POINTER(gf_kv_pool),
+                                   C.POINTER(gf_tables), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    lib.gf_attn_decode.restype = C.c_int32
+    if path is None:
+        _lib = lib
+    return lib
+
+
+def _ptr(t) -> Optional[int]:
+    """Device address of a torch tensor (None -> NULL)."""
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous(), "device-resident contiguous tensors only"
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    import torch
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _check(ctx, rc: int):
+    if rc != GF_OK:
+        lib = load_library()
+        msg = lib.gf_strerror(rc).decode()
+        if rc == GF_ERR_HIP and ctx:
+            msg += " / " + lib.gf_last_hip_error(ctx).decode()
+        raise GraphFlowError(rc, msg)
+
+
+def gf_create(device: int = 0) -> int:
+    lib = load_library()
+    h = C.c_void_p()
+    _check(None, lib.gf_create(C.byref(h), device))
+    return h.value
+
+
+def gf_destroy(ctx: int) -> None:
+    _check(None, load_library().gf_destroy(ctx))
+
+
+def gf_set_decode_chunk_blocks(ctx: int, chunk_blocks: int) -> None:
+    _check(ctx, load_library().gf_set_decode_chunk_blocks(ctx, chunk_blocks))
+
+
+def make_graph(num_nodes, node_len, node_block_ptr, node_blocks, edge_ptr=None, edge_dst=None) -> gf_graph:
+    return gf_graph(num_nodes, _ptr(node_len), _ptr(node_block_ptr), _ptr(node_blocks), _ptr(edge_ptr),
+                    _ptr(edge_dst))
+
+
+def gf_resolve_path(ctx, graph: gf_graph, num_req, path_ptr, path_nodes, new_lens, tail_ptr, tail_blocks,
+                    max_blocks, num_pool_blocks, block_table, block_ntok, num_blocks, ctx_lens, seq_lens,
+                    status) -> None:
+    rc = load_library().gf_resolve_path(
+        ctx, C.byref(graph), num_req, _ptr(path_ptr), _ptr(path_nodes), _ptr(new_lens), _ptr(tail_ptr),
+        _ptr(tail_blocks), max_blocks, num_pool_blocks, _ptr(block_table), _ptr(block_ntok),
+        _ptr(num_blocks), _ptr(ctx_lens), _ptr(seq_lens), _ptr(status), _stream())
+    _check(ctx, rc)
+
+
+def make_params(num_q_heads, num_kv_heads, head_dim, kv_dtype=GF_BF16, sm_scale=0.0, block_size=16):
+    return gf_attn_params(num_q_heads, num_kv_heads, head_dim, block_size, kv_dtype, sm_scale)
+
+
+def make_pool(k, v, num_blocks, k_scale=None, v_scale=None) -> gf_kv_pool:
+    return gf_kv_pool(_ptr(k), _ptr(v), _ptr(k_scale), _ptr(v_scale), num_blocks)
+
+
+def make_tables(block_table, block_ntok, num_blocks, ctx_lens, seq_lens, status, num_req, max_blocks):
+    return gf_tables(_ptr(block_table), _ptr(block_ntok), _ptr(num_blocks), _ptr(ctx_lens), _ptr(seq_lens),
+                     _ptr(status), num_req, max_blocks)
+
+
+def gf_attn_prefill(ctx, params, pool, tables, q, q_ptr, total_q, max_q, o, lse=None) -> None:
+    rc = load_library().gf_attn_prefill(ctx, C.byref(params), C.byref(pool), C.byref(tables), _ptr(q),
+                                        _ptr(q_ptr), total_q, max_q, _ptr(o), _ptr(lse), _stream())
+    _check(ctx, rc)
+
+
+def gf_attn_decode(ctx, params, pool, tables, q, o, lse=None) -> None:
+    rc = load_library().gf_attn_decode(ctx, C.byref(params), C.byref(pool), C.byref(tables), _ptr(q),
+                                       _ptr(o), _ptr(lse), _stream())
+    _check(ctx, rc)

@@ -1,0 +1,199 @@
+// C ABI of libgraphflow: argument checks on the host, then kernel launches on
+// the caller's stream.  Nothing here computes; see the kernel files.
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "gf_internal.h"
+
+struct gf_ctx {
+    int device = 0;
+    void *workspace = nullptr;
+    size_t workspace_bytes = 0;
+    int32_t decode_chunk_blocks = 0;   // 0 = built-in choice
+    char hip_err[256] = {0};
+};
+
+namespace {
+
+int32_t fail_hip(gf_ctx *ctx, hipError_t e, const char *where) {
+    if (ctx) snprintf(ctx->hip_err, sizeof(ctx->hip_err), "%s: %s", where, hipGetErrorString(e));
+    return GF_ERR_HIP;
+}
+
+// Shape checks shared by both attention calls.  Returns GF_OK and fills `a`.
+int32_t check_attn(const gf_attn_params *p, const gf_kv_pool *pool, const gf_tables *t, const void *q, void *o,
+                   float *lse, gf::AttnArgs &a, int &group) {
+    if (!p || !pool || !t) return GF_ERR_NULL;
+    if (t->num_req < 0 || t->max_blocks < 0 || pool->num_blocks < 0) return GF_ERR_BAD_SHAPE;
+    if (p->num_q_heads <= 0 || p->num_kv_heads <= 0 || p->head_dim <= 0) return GF_ERR_BAD_SHAPE;
+    if (p->num_q_heads % p->num_kv_heads != 0) return GF_ERR_BAD_SHAPE;
+    if (!(p->sm_scale >= 0.f) || !std::isfinite(p->sm_scale)) return GF_ERR_BAD_SHAPE;
+    group = p->num_q_heads / p->num_kv_heads;
+    if (p->block_size != gf::kBlock) return GF_ERR_UNSUPPORTED;
+    if (p->head_dim != 64 && p->head_dim != 128) return GF_ERR_UNSUPPORTED;
+    if (group != 1 && group != 2 && group != 4 && group != 8) return GF_ERR_UNSUPPORTED;
+    if (p->kv_dtype != GF_BF16 && p->kv_dtype != GF_FP8_E4M3) return GF_ERR_UNSUPPORTED;
+    if (t->num_req > 0) {
+        if (!pool->k || !pool->v || !q || !o) return GF_ERR_NULL;
+        if (!t->block_table || !t->block_ntok || !t->num_blocks || !t->ctx_lens || !t->seq_lens)
+            return GF_ERR_NULL;
+        if (p->kv_dtype == GF_FP8_E4M3 && (!pool->k_scale || !pool->v_scale)) return GF_ERR_NULL;
+        if (pool->num_blocks < 1 || t->max_blocks < 1) return GF_ERR_BAD_SHAPE;
+    }
+    const float scale = p->sm_scale > 0.f ? p->sm_scale : 1.0f / std::sqrt((float)p->head_dim);
+    a.k = pool->k;
+    a.v = pool->v;
+    a.k_scale = pool->k_scale;
+    a.v_scale = pool->v_scale;
+    a.pool_blocks = pool->num_blocks;
+    a.block_table = t->block_table;
+    a.block_ntok = t->block_ntok;
+    a.num_blocks = t->num_blocks;
+    a.ctx_lens = t->ctx_lens;
+    a.seq_lens = t->seq_lens;
+    a.status = t->status;
+    a.num_req = t->num_req;
+    a.max_blocks = t->max_blocks;
+    a.hq = p->num_q_heads;
+    a.hkv = p->num_kv_heads;
+    a.scale_log2 = scale * 1.4426950408889634f;
+    a.q = q;
+    a.o = o;
+    a.lse = lse;
+    return GF_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t gf_create(gf_ctx **out, int32_t device) {
+    if (!out) return GF_ERR_NULL;
+    *out = nullptr;
+    int count = 0;
+    hipError_t e = hipGetDeviceCount(&count);
+    if (e != hipSuccess) return GF_ERR_HIP;
+    if (device < 0 || device >= count) return GF_ERR_BAD_SHAPE;
+    e = hipSetDevice(device);
+    if (e != hipSuccess) return GF_ERR_HIP;
+    gf_ctx *c = new (std::nothrow) gf_ctx();
+    if (!c) return GF_ERR_WORKSPACE;
+    c->device = device;
+    *out = c;
+    return GF_OK;
+}
+
+int32_t gf_destroy(gf_ctx *ctx) {
+    if (!ctx) return GF_ERR_NULL;
+    int32_t rc = GF_OK;
+    if (ctx->workspace && hipFree(ctx->workspace) != hipSuccess) rc = GF_ERR_HIP;
+    delete ctx;
+    return rc;
+}
+
+const char *gf_strerror(int32_t code) {
+    switch (code) {
+        case GF_OK: return "ok";
+        case GF_ERR_NULL: return "a required pointer is NULL";
+        case GF_ERR_BAD_SHAPE: return "negative or inconsistent sizes";
+        case GF_ERR_UNSUPPORTED: return "shape or dtype outside the supported set";
+        case GF_ERR_WORKSPACE: return "device workspace allocation failed";
+        case GF_ERR_HIP: return "HIP runtime error (see gf_last_hip_error)";
+        default: return "unknown error code";
+    }
+}
+
+const char *gf_last_hip_error(const gf_ctx *ctx) { return ctx ? ctx->hip_err : ""; }
+
+int32_t gf_set_decode_chunk_blocks(gf_ctx *ctx, int32_t chunk_blocks) {
+    if (!ctx) return GF_ERR_NULL;
+    if (chunk_blocks < 0 || (chunk_blocks & 1)) return GF_ERR_BAD_SHAPE;
+    ctx->decode_chunk_blocks = chunk_blocks;
+    return GF_OK;
+}
+
+int32_t gf_resolve_path(gf_ctx *ctx, const gf_graph *graph, int32_t num_req, const int32_t *path_ptr,
+                        const int32_t *path_nodes, const int32_t *new_lens, const int32_t *tail_ptr,
+                        const int32_t *tail_blocks, int32_t max_blocks, int32_t num_pool_blocks,
+                        int32_t *block_table, int32_t *block_ntok, int32_t *num_blocks, int32_t *ctx_lens,
+                        int32_t *seq_lens, int32_t *status, void *stream) {
+    if (!ctx || !graph) return GF_ERR_NULL;
+    if (num_req < 0 || max_blocks < 0 || num_pool_blocks < 0 || graph->num_nodes < 0) return GF_ERR_BAD_SHAPE;
+    if (num_req == 0) return GF_OK;
+    if (!path_ptr || !num_blocks || !ctx_lens || !seq_lens || !status) return GF_ERR_NULL;
+    if (max_blocks > 0 && (!block_table || !block_ntok)) return GF_ERR_NULL;
+    if (graph->num_nodes > 0 && (!graph->node_len || !graph->node_block_ptr || !graph->node_blocks))
+        return GF_ERR_NULL;
+    if ((graph->edge_ptr == nullptr) != (graph->edge_dst == nullptr)) return GF_ERR_NULL;
+    if ((tail_ptr == nullptr) != (tail_blocks == nullptr)) return GF_ERR_NULL;
+    // path_nodes may be NULL only if every path is empty, which the host cannot see: require it
+    if (!path_nodes) return GF_ERR_NULL;
+    hipError_t e = gf::launch_resolve(*graph, num_req, path_ptr, path_nodes, new_lens, tail_ptr, tail_blocks,
+                                      max_blocks, num_pool_blocks, block_table, block_ntok, num_blocks,
+                                      ctx_lens, seq_lens, status, (hipStream_t)stream);
+    if (e != hipSuccess) return fail_hip(ctx, e, "gf_resolve_path launch");
+    return GF_OK;
+}
+
+int32_t gf_attn_prefill(gf_ctx *ctx, const gf_attn_params *params, const gf_kv_pool *pool,
+                        const gf_tables *tables, const void *q, const int32_t *q_ptr, int32_t total_q,
+                        int32_t max_q, void *o, float *lse, void *stream) {
+    if (!ctx) return GF_ERR_NULL;
+    if (total_q < 0 || max_q < 0 || max_q > total_q) return GF_ERR_BAD_SHAPE;
+    gf::AttnArgs a;
+    int group = 0;
+    // q/o may be NULL when there are no rows at all
+    static const char dummy = 0;
+    int32_t rc = check_attn(params, pool, tables, total_q ? q : &dummy, total_q ? o : (void *)&dummy, lse, a, group);
+    if (rc != GF_OK) return rc;
+    if (tables->num_req == 0 || total_q == 0) return GF_OK;
+    if (!q_ptr) return GF_ERR_NULL;
+    hipError_t e = gf::launch_prefill(a, params->head_dim, group, params->kv_dtype, q_ptr, total_q, max_q,
+                                      (hipStream_t)stream);
+    if (e == hipErrorNotSupported) return GF_ERR_UNSUPPORTED;
+    if (e != hipSuccess) return fail_hip(ctx, e, "gf_attn_prefill launch");
+    return GF_OK;
+}
+
+int32_t gf_attn_decode(gf_ctx *ctx, const gf_attn_params *params, const gf_kv_pool *pool,
+                       const gf_tables *tables, const void *q, void *o, float *lse, void *stream) {
+    if (!ctx) return GF_ERR_NULL;
+    gf::AttnArgs a;
+    int group = 0;
+    int32_t rc = check_attn(params, pool, tables, q, o, lse, a, group);
+    if (rc != GF_OK) return rc;
+    if (tables->num_req == 0) return GF_OK;
+    // chunk size: explicit knob, else keep the number of items moderate while
+    // leaving each item at least 32 blocks (512 tokens) of streaming work
+    int32_t chunk = ctx->decode_chunk_blocks;
+    if (chunk <= 0) chunk = 32;
+    const int32_t splits = (tables->max_blocks + chunk - 1) / chunk;
+    const size_t need = gf::decode_workspace_bytes(a.num_req, a.hkv, group, params->head_dim, splits);
+    if (need > ctx->workspace_bytes) {
+        // growing the workspace: the old buffer may still be in use on the stream
+        hipError_t e = hipStreamSynchronize((hipStream_t)stream);
+        if (e != hipSuccess) return fail_hip(ctx, e, "gf_attn_decode sync before workspace growth");
+        if (ctx->workspace) {
+            e = hipFree(ctx->workspace);
+            ctx->workspace = nullptr;
+            ctx->workspace_bytes = 0;
+            if (e != hipSuccess) return fail_hip(ctx, e, "gf_attn_decode workspace free");
+        }
+        e = hipMalloc(&ctx->workspace, need);
+        if (e != hipSuccess) {
+            ctx->workspace = nullptr;
+            fail_hip(ctx, e, "gf_attn_decode workspace alloc");
+            return GF_ERR_WORKSPACE;
+        }
+        ctx->workspace_bytes = need;
+    }
+    hipError_t e = gf::launch_decode(a, params->head_dim, group, params->kv_dtype, chunk, splits,
+                                     ctx->workspace, (hipStream_t)stream);
+    if (e == hipErrorNotSupported) return GF_ERR_UNSUPPORTED;
+    if (e != hipSuccess) return fail_hip(ctx, e, "gf_attn_decode launch");
+    return GF_OK;
+}
+
+}  // extern "C"

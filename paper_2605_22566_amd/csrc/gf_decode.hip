@@ -1,0 +1,244 @@
+// gf_attn_decode: one query token per request attends to the whole KV of its
+// node path through the block table (paper, Topology-Aware State Management:
+// decode steps reuse the per-node KV instead of recomputing past context).
+//
+// Bandwidth path.  The table of a request is cut into chunks of `chunk_blocks`
+// entries; one wavefront reduces one (request, kv head, chunk) item for all G
+// query heads of the group at once, streaming K and V blocks straight from HBM
+// into MFMA operand registers (16 B per lane, two blocks = 32 keys per step,
+// the next step's loads in flight while the current one is reduced), and
+// leaves an fp32 partial (max, sum, weighted values).  A second kernel merges
+// the partials of a request with the log-sum-exp rule and rounds to bf16.
+//
+// MFMA use (v_mfma_f32_16x16x32_bf16, D = A(16x32) * B(32x16)):
+//   S^T[key][head]  = K[key][d]   * Q^T[d][head]       (A = K rows, B = Q)
+//   O^T[d][head]   += V^T[d][key] * P^T[key][head]     (A = V^T rows, B = P)
+// Lane l holds operand row/col l%16 and the 8 contraction elements of group
+// l/16; an accumulator lane holds column l%16, rows 4*(l/16)+i.  The K rows of
+// the two score tiles are chosen so that after both tiles lane group q4 holds
+// the 8 consecutive slots 8*(q4%2)..+7 of block q4/2: exactly the contraction
+// group the V^T operand reads as one 16-byte load from the [d][slot] V layout.
+#include "gf_internal.h"
+
+namespace gf {
+
+constexpr int kDecodeThreads = 256;          // 4 independent waves
+constexpr int kWavesPerWg = kDecodeThreads / 64;
+
+template <int D, bool FP8>
+struct PairRegs {
+    // K: 2 tiles x D/32 steps, V: D/16 tiles; each a 16-byte (bf16) fragment
+    u32x4 k[2][D / 32];
+    u32x4 v[D / 16];
+    int n0, n1;   // valid tokens in the two blocks
+};
+
+template <int D>
+__device__ __forceinline__ void load_pair(PairRegs<D, false> &p, const AttnArgs &a, const int32_t *tab,
+                                          const int32_t *ntk, int e, int e_end, int kvh, int lane) {
+    int b0 = tab[e];
+    p.n0 = ntk[e];
+    int b1 = b0;
+    p.n1 = 0;
+    if (e + 1 < e_end) {
+        b1 = tab[e + 1];
+        p.n1 = ntk[e + 1];
+    }
+    b0 = min(max(b0, 0), a.pool_blocks - 1);
+    b1 = min(max(b1, 0), a.pool_blocks - 1);
+    const size_t blk_bytes = (size_t)kBlock * D * 2;
+    const char *k0 = (const char *)a.k + ((size_t)b0 * a.hkv + kvh) * blk_bytes;
+    const char *k1 = (const char *)a.k + ((size_t)b1 * a.hkv + kvh) * blk_bytes;
+    const char *v0 = (const char *)a.v + ((size_t)b0 * a.hkv + kvh) * blk_bytes;
+    const char *v1 = (const char *)a.v + ((size_t)b1 * a.hkv + kvh) * blk_bytes;
+    const int m = lane & 15, q4 = lane >> 4;
+    // K operand row m of tile T: block (m>=8), slot 8*((m/4)&1) + 4T + m%4
+    const char *kb = (m >= 8) ? k1 : k0;
+    const int slot0 = 8 * ((m >> 2) & 1) + (m & 3);
+#pragma unroll
+    for (int T = 0; T < 2; ++T)
+#pragma unroll
+        for (int t = 0; t < D / 32; ++t)
+            p.k[T][t] = *(const u32x4 *)(kb + (size_t)(slot0 + 4 * T) * D * 2 + (32 * t + 8 * q4) * 2);
+    // V^T operand row m (d = 16dt + m): block (q4>=2), slots 8*(q4&1)..+7
+    const char *vb = (q4 >= 2) ? v1 : v0;
+#pragma unroll
+    for (int dt = 0; dt < D / 16; ++dt)
+        p.v[dt] = *(const u32x4 *)(vb + (size_t)(16 * dt + m) * (kBlock * 2) + (q4 & 1) * 16);
+}
+
+template <int D, int G, bool FP8>
+__global__ __launch_bounds__(kDecodeThreads) void decode_split_kernel(AttnArgs a, int chunk_blocks, int splits,
+                                                                     float *__restrict__ part_o,
+                                                                     float *__restrict__ part_ml) {
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int pairs = a.num_req * a.hkv;
+    const long item = (long)blockIdx.x * kWavesPerWg + wave;
+    if (item >= (long)pairs * splits) return;
+    const int s = (int)(item / pairs);
+    const int rem = (int)(item % pairs);
+    const int r = rem / a.hkv, kvh = rem % a.hkv;
+    if (a.status && a.status[r] != 0) return;
+    const int nb = a.num_blocks[r];
+    const int e0 = s * chunk_blocks;
+    const int e1 = min(nb, e0 + chunk_blocks);
+    if (e0 >= e1) return;
+    const int32_t *tab = a.block_table + (size_t)r * a.max_blocks;
+    const int32_t *ntk = a.block_ntok + (size_t)r * a.max_blocks;
+
+    const int n = lane & 15, q4 = lane >> 4;
+    // Q^T operand: column n = query head of the group (zero beyond G)
+    bf16x8 qf[D / 32];
+#pragma unroll
+    for (int t = 0; t < D / 32; ++t) {
+        u32x4 raw = {0, 0, 0, 0};
+        if (n < G)
+            raw = *(const u32x4 *)((const char *)a.q +
+                                   (((size_t)r * a.hq + kvh * G + n) * D + 32 * t + 8 * q4) * 2);
+        qf[t] = __builtin_bit_cast(bf16x8, raw);
+    }
+
+    const float c = a.scale_log2;
+    float m_run = -1.0e30f;   // running max of raw scores (finite sentinel)
+    float l_run = 0.f;        // lane-local partial sum of exp
+    f32x4 oacc[D / 16];
+#pragma unroll
+    for (int dt = 0; dt < D / 16; ++dt) oacc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    PairRegs<D, FP8> cur, nxt;
+    load_pair<D>(cur, a, tab, ntk, e0, e1, kvh, lane);
+    for (int e = e0; e < e1; e += 2) {
+        const bool more = e + 2 < e1;
+        if (more) load_pair<D>(nxt, a, tab, ntk, e + 2, e1, kvh, lane);
+
+        f32x4 sT[2];
+#pragma unroll
+        for (int T = 0; T < 2; ++T) {
+            sT[T] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int t = 0; t < D / 32; ++t)
+                sT[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, cur.k[T][t]), qf[t],
+                                                                 sT[T], 0, 0, 0);
+        }
+        if (cur.n0 < kBlock || cur.n1 < kBlock) {
+            const int lim = ((q4 >= 2) ? cur.n1 : cur.n0) - 8 * (q4 & 1);
+#pragma unroll
+            for (int T = 0; T < 2; ++T)
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (4 * T + i >= lim) sT[T][i] = -INFINITY;
+        }
+        float mx = fmaxf(fmaxf(fmaxf(sT[0][0], sT[0][1]), fmaxf(sT[0][2], sT[0][3])),
+                         fmaxf(fmaxf(sT[1][0], sT[1][1]), fmaxf(sT[1][2], sT[1][3])));
+        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+        const float m_new = fmaxf(m_run, mx);
+        const float alpha = fast_exp2((m_run - m_new) * c);
+        const float mc = m_new * c;
+        m_run = m_new;
+        f32x8 p;
+        float psum = 0.f;
+#pragma unroll
+        for (int T = 0; T < 2; ++T)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float e2 = fast_exp2(sT[T][i] * c - mc);
+                p[4 * T + i] = e2;
+                psum += e2;
+            }
+        l_run = l_run * alpha + psum;
+        const bf16x8 pb = __builtin_convertvector(p, bf16x8);
+#pragma unroll
+        for (int dt = 0; dt < D / 16; ++dt) {
+            oacc[dt] *= alpha;
+            oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, cur.v[dt]), pb,
+                                                                oacc[dt], 0, 0, 0);
+        }
+        if (more) cur = nxt;
+    }
+
+    l_run += __shfl_xor(l_run, 16, 64);
+    l_run += __shfl_xor(l_run, 32, 64);
+    if (n < G) {
+        const size_t pi = ((size_t)rem * splits + s) * G + n;
+        if (q4 == 0) {
+            part_ml[pi * 2 + 0] = m_run * c;   // max in log2 units
+            part_ml[pi * 2 + 1] = l_run;
+        }
+#pragma unroll
+        for (int dt = 0; dt < D / 16; ++dt) *(f32x4 *)(part_o + pi * D + 16 * dt + 4 * q4) = oacc[dt];
+    }
+}
+
+// One wave per (request, query head): combine the partials of the request's
+// chunks.  m_s are in log2 units: w_s = 2^(m_s - M), L = sum w_s l_s,
+// O = sum w_s O_s / L, lse = (M + log2 L) * ln 2.
+template <int D, int G>
+__global__ __launch_bounds__(256) void decode_merge_kernel(AttnArgs a, int chunk_blocks, int splits,
+                                                           const float *__restrict__ part_o,
+                                                           const float *__restrict__ part_ml) {
+    const int lane = threadIdx.x & 63;
+    const long idx = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (idx >= (long)a.num_req * a.hq) return;
+    const int r = (int)(idx / a.hq), h = (int)(idx % a.hq);
+    const int kvh = h / G, g = h % G;
+    const bool ok = !(a.status && a.status[r] != 0);
+    const int nb = ok ? a.num_blocks[r] : 0;
+    const int ns = (nb + chunk_blocks - 1) / chunk_blocks;
+    __bf16 *out = (__bf16 *)a.o + ((size_t)r * a.hq + h) * D;
+    constexpr int PER = D / 64;
+    float acc[PER];
+#pragma unroll
+    for (int i = 0; i < PER; ++i) acc[i] = 0.f;
+    float M = -INFINITY, L = 0.f;
+    const size_t base = ((size_t)(r * a.hkv + kvh) * splits) * G + g;
+    for (int s = 0; s < ns; ++s) M = fmaxf(M, part_ml[(base + (size_t)s * G) * 2]);
+    for (int s = 0; s < ns; ++s) {
+        const size_t pi = base + (size_t)s * G;
+        const float w = fast_exp2(part_ml[pi * 2] - M);
+        L += w * part_ml[pi * 2 + 1];
+#pragma unroll
+        for (int i = 0; i < PER; ++i) acc[i] += w * part_o[pi * D + lane + 64 * i];
+    }
+    const float inv = ns > 0 ? 1.f / L : 0.f;
+#pragma unroll
+    for (int i = 0; i < PER; ++i) out[lane + 64 * i] = (__bf16)(acc[i] * inv);
+    if (a.lse && lane == 0)
+        a.lse[(size_t)r * a.hq + h] = ns > 0 ? (M + __builtin_log2f(L)) * 0.6931471805599453f : -INFINITY;
+}
+
+size_t decode_workspace_bytes(int32_t num_req, int32_t hkv, int32_t group, int32_t head_dim, int32_t splits) {
+    return (size_t)num_req * hkv * splits * group * (head_dim + 2) * sizeof(float);
+}
+
+template <int D, int G>
+static hipError_t launch_decode_t(const AttnArgs &a, int kv_dtype, int32_t chunk_blocks, int32_t splits,
+                                  void *workspace, hipStream_t s) {
+    const size_t n_items = (size_t)a.num_req * a.hkv * splits;
+    float *part_o = (float *)workspace;
+    float *part_ml = part_o + n_items * G * D;
+    const unsigned grid = (unsigned)((n_items + kWavesPerWg - 1) / kWavesPerWg);
+    if (kv_dtype != GF_BF16) return hipErrorNotSupported;
+    hipLaunchKernelGGL((decode_split_kernel<D, G, false>), dim3(grid), dim3(kDecodeThreads), 0, s, a,
+                       chunk_blocks, splits, part_o, part_ml);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const size_t rows = (size_t)a.num_req * a.hq;
+    hipLaunchKernelGGL((decode_merge_kernel<D, G>), dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, a,
+                       chunk_blocks, splits, part_o, part_ml);
+    return hipGetLastError();
+}
+
+hipError_t launch_decode(const AttnArgs &a, int head_dim, int group, int kv_dtype, int32_t chunk_blocks,
+                         int32_t splits, void *workspace, hipStream_t s) {
+    if (a.num_req == 0) return hipSuccess;
+#define GF_CASE(DD, GG) \
+    if (head_dim == DD && group == GG) return launch_decode_t<DD, GG>(a, kv_dtype, chunk_blocks, splits, workspace, s);
+    GF_CASE(64, 1) GF_CASE(64, 2) GF_CASE(64, 4) GF_CASE(64, 8)
+    GF_CASE(128, 1) GF_CASE(128, 2) GF_CASE(128, 4) GF_CASE(128, 8)
+#undef GF_CASE
+    return hipErrorNotSupported;
+}
+
+}  // namespace gf

@@ -1,0 +1,54 @@
+// Internal declarations shared by the translation units of libgraphflow.
+// Device helpers for gfx950 (wave64, MFMA) and the host-side launcher
+// prototypes the C ABI entry points call.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "graphflow.h"
+
+namespace gf {
+
+constexpr int kBlock = 16;  // tokens per pool block
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+struct AttnArgs {
+    const void *k, *v;
+    const float *k_scale, *v_scale;
+    int32_t pool_blocks;
+    const int32_t *block_table, *block_ntok, *num_blocks, *ctx_lens, *seq_lens, *status;
+    int32_t num_req, max_blocks;
+    int32_t hq, hkv;
+    float scale_log2;  // sm_scale * log2(e)
+    const void *q;
+    void *o;
+    float *lse;
+};
+
+// launchers (return hipError_t of the launch)
+hipError_t launch_resolve(const gf_graph &g, int32_t num_req, const int32_t *path_ptr,
+                          const int32_t *path_nodes, const int32_t *new_lens, const int32_t *tail_ptr,
+                          const int32_t *tail_blocks, int32_t max_blocks, int32_t num_pool_blocks,
+                          int32_t *block_table, int32_t *block_ntok, int32_t *num_blocks,
+                          int32_t *ctx_lens, int32_t *seq_lens, int32_t *status, hipStream_t s);
+
+hipError_t launch_prefill(const AttnArgs &a, int head_dim, int group, int kv_dtype, const int32_t *q_ptr,
+                          int32_t total_q, int32_t max_q, hipStream_t s);
+
+// workspace floats needed by decode for (num_req, hkv, group, head_dim, splits)
+size_t decode_workspace_bytes(int32_t num_req, int32_t hkv, int32_t group, int32_t head_dim, int32_t splits);
+hipError_t launch_decode(const AttnArgs &a, int head_dim, int group, int kv_dtype, int32_t chunk_blocks,
+                         int32_t splits, void *workspace, hipStream_t s);
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// value held by the lane 32 away (the other half of the wave)
+__device__ __forceinline__ float other_half(float x) { return __shfl_xor(x, 32, 64); }
+
+}  // namespace gf

@@ -1,0 +1,146 @@
+"""Device-side plumbing around the binding: upload a workload's index arrays,
+allocate outputs, call the three entry points.  No arithmetic of the method
+happens here; pools and queries are inputs (uploaded from the host generator or
+filled by torch's device RNG for the large configurations)."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from . import binding as B
+from . import workload as W
+
+
+def bits_to_device(bits: np.ndarray, device) -> torch.Tensor:
+    """uint16 bf16 bit patterns -> bf16 tensor; uint8 e4m3 codes -> uint8 tensor."""
+    if bits.dtype == np.uint16:
+        return torch.from_numpy(bits.view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(bits).to(device)
+
+
+def bf16_to_bits(t: torch.Tensor) -> np.ndarray:
+    return t.detach().contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+class DevicePool:
+    """K/V pool resident on the GPU (+ per-block scales for e4m3)."""
+
+    def __init__(self, k, v, num_blocks, k_scale=None, v_scale=None):
+        self.k, self.v, self.k_scale, self.v_scale, self.num_blocks = k, v, k_scale, v_scale, num_blocks
+
+    @classmethod
+    def from_host(cls, t: W.Tensors, device):
+        ks = None if t.k_scale is None else torch.from_numpy(t.k_scale).to(device)
+        vs = None if t.v_scale is None else torch.from_numpy(t.v_scale).to(device)
+        return cls(bits_to_device(t.k_pool, device), bits_to_device(t.v_pool, device), t.k_pool.shape[0], ks, vs)
+
+    @classmethod
+    def random(cls, wl: W.Workload, device, seed=None, chunk_blocks=1 << 14):
+        """Fill the whole pool with N(0,1) on the device (pad slots included:
+        finite garbage).  e4m3 pools are quantised per block: scale = amax/448."""
+        sh = wl.shape
+        nb, hkv, d = wl.num_pool_blocks, sh.num_kv_heads, sh.head_dim
+        gen = torch.Generator(device=device)
+        gen.manual_seed(wl.seed if seed is None else seed)
+        fp8 = sh.kv_dtype == W.KV_FP8_E4M3
+        dt = torch.uint8 if fp8 else torch.bfloat16
+        k = torch.empty((nb, hkv, W.BLOCK, d), dtype=dt, device=device)
+        v = torch.empty((nb, hkv, d, W.BLOCK), dtype=dt, device=device)
+        ks = torch.empty(nb, dtype=torch.float32, device=device) if fp8 else None
+        vs = torch.empty(nb, dtype=torch.float32, device=device) if fp8 else None
+        for dst, sc in ((k, ks), (v, vs)):
+            for lo in range(0, nb, chunk_blocks):
+                hi = min(nb, lo + chunk_blocks)
+                x = torch.randn((hi - lo,) + tuple(dst.shape[1:]), generator=gen, device=device,
+                                dtype=torch.float32)
+                if fp8:
+                    amax = x.abs().amax(dim=(1, 2, 3))
+                    s = torch.where(amax > 0, amax / 448.0, torch.ones_like(amax))
+                    y = (x / s[:, None, None, None]).clamp_(-448.0, 448.0)
+                    dst[lo:hi] = y.to(torch.float8_e4m3fn).view(torch.uint8)
+                    sc[lo:hi] = s
+                else:
+                    dst[lo:hi] = x.to(torch.bfloat16)
+                del x
+        return cls(k, v, nb, ks, vs)
+
+    def gather_host(self, block_ids: np.ndarray):
+        """Copy the given blocks back to the host in the oracle's input format."""
+        idx = torch.from_numpy(np.asarray(block_ids, dtype=np.int64)).to(self.k.device)
+        kk, vv = self.k[idx], self.v[idx]
+        if kk.dtype == torch.bfloat16:
+            return bf16_to_bits(kk), bf16_to_bits(vv), None, None
+        return (kk.cpu().numpy(), vv.cpu().numpy(), self.k_scale[idx].cpu().numpy(),
+                self.v_scale[idx].cpu().numpy())
+
+
+class Session:
+    """One gf_ctx + the device copies of a workload's graph."""
+
+    def __init__(self, wl: W.Workload, device="cuda:0"):
+        self.wl = wl
+        self.device = torch.device(device)
+        torch.cuda.set_device(self.device)
+        self.ctx = B.gf_create(self.device.index or 0)
+        g = wl.graph
+        up = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(self.device)
+        self.node_len, self.node_block_ptr, self.node_blocks = up(g.node_len), up(g.node_block_ptr), up(g.node_blocks)
+        self.edge_ptr, self.edge_dst = up(g.edge_ptr), up(g.edge_dst)
+        self._up = up
+
+    def close(self):
+        if self.ctx:
+            B.gf_destroy(self.ctx)
+            self.ctx = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def upload_batch(self, batch: W.Batch):
+        up = self._up
+        return dict(path_ptr=up(batch.path_ptr), path_nodes=up(batch.path_nodes if len(batch.path_nodes) else [0]),
+                    new_lens=up(batch.new_lens), tail_ptr=up(batch.tail_ptr),
+                    tail_blocks=up(batch.tail_blocks if len(batch.tail_blocks) else [0]), num_req=batch.num_req)
+
+    def alloc_tables(self, num_req, max_blocks):
+        z = lambda *s: torch.empty(s, dtype=torch.int32, device=self.device)
+        return dict(block_table=z(num_req, max_blocks), block_ntok=z(num_req, max_blocks), num_blocks=z(num_req),
+                    ctx_lens=z(num_req), seq_lens=z(num_req), status=z(num_req), num_req=num_req,
+                    max_blocks=max_blocks)
+
+    def resolve(self, dbatch, tables, with_edges=True, num_pool_blocks=None):
+        graph = B.make_graph(self.wl.graph.num_nodes, self.node_len, self.node_block_ptr, self.node_blocks,
+                             self.edge_ptr if with_edges else None, self.edge_dst if with_edges else None)
+        B.gf_resolve_path(self.ctx, graph, dbatch["num_req"], dbatch["path_ptr"], dbatch["path_nodes"],
+                          dbatch["new_lens"], dbatch["tail_ptr"], dbatch["tail_blocks"], tables["max_blocks"],
+                          self.wl.num_pool_blocks if num_pool_blocks is None else num_pool_blocks,
+                          tables["block_table"], tables["block_ntok"], tables["num_blocks"], tables["ctx_lens"],
+                          tables["seq_lens"], tables["status"])
+        return tables
+
+    def _common(self, pool: DevicePool, tables, sm_scale):
+        sh = self.wl.shape
+        params = B.make_params(sh.num_q_heads, sh.num_kv_heads, sh.head_dim, sh.kv_dtype, sm_scale)
+        dpool = B.make_pool(pool.k, pool.v, pool.num_blocks, pool.k_scale, pool.v_scale)
+        dt = B.make_tables(tables["block_table"], tables["block_ntok"], tables["num_blocks"], tables["ctx_lens"],
+                           tables["seq_lens"], tables["status"], tables["num_req"], tables["max_blocks"])
+        return params, dpool, dt
+
+    def prefill(self, pool, tables, q, q_ptr, total_q, max_q, o, lse=None, sm_scale=0.0):
+        params, dpool, dt = self._common(pool, tables, sm_scale)
+        B.gf_attn_prefill(self.ctx, params, dpool, dt, q, q_ptr, total_q, max_q, o, lse)
+
+    def decode(self, pool, tables, q, o, lse=None, sm_scale=0.0):
+        params, dpool, dt = self._common(pool, tables, sm_scale)
+        B.gf_attn_decode(self.ctx, params, dpool, dt, q, o, lse)
+
+
+def tables_to_host(tables) -> dict:
+    """Device tables -> dict of Python lists (the oracle resolver's format)."""
+    out = {}
+    for k in ("block_table", "block_ntok", "num_blocks", "ctx_lens", "seq_lens", "status"):
+        out[k] = tables[k].cpu().numpy().tolist()
+    return out
