@@ -174,7 +174,8 @@ int32_t gf_resolve_path(gf_ctx *ctx, const gf_graph *graph, int32_t num_req,
  *   lse [total_q][num_q_heads] fp32 natural-log log-sum-exp of the scaled
  *       scores, or NULL (device, out)
  *   max_q  an upper bound on n_r over the batch (host value; sizes the grid).
- * Rows of requests whose status is non-zero are left untouched.
+ * Rows of requests whose status is non-zero, or whose row count
+ * q_ptr[r+1]-q_ptr[r] differs from seq_lens[r]-ctx_lens[r], are left untouched.
  * Accumulation and softmax are fp32.
  */
 int32_t gf_attn_prefill(gf_ctx *ctx, const gf_attn_params *params, const gf_kv_pool *pool,

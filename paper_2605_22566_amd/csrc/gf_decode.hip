@@ -80,7 +80,7 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_split_kernel(AttnArgs a
     const int rem = (int)(item % pairs);
     const int r = rem / a.hkv, kvh = rem % a.hkv;
     if (a.status && a.status[r] != 0) return;
-    const int nb = a.num_blocks[r];
+    const int nb = min(a.num_blocks[r], a.max_blocks);
     const int e0 = s * chunk_blocks;
     const int e1 = min(nb, e0 + chunk_blocks);
     if (e0 >= e1) return;
@@ -184,7 +184,7 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(AttnArgs a, int chunk
     const int r = (int)(idx / a.hq), h = (int)(idx % a.hq);
     const int kvh = h / G, g = h % G;
     const bool ok = !(a.status && a.status[r] != 0);
-    const int nb = ok ? a.num_blocks[r] : 0;
+    const int nb = ok ? min(a.num_blocks[r], a.max_blocks) : 0;
     const int ns = (nb + chunk_blocks - 1) / chunk_blocks;
     __bf16 *out = (__bf16 *)a.o + ((size_t)r * a.hq + h) * D;
     constexpr int PER = D / 64;

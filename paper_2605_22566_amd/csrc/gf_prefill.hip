@@ -47,7 +47,7 @@ struct PrefillCfg {
 
 template <int D, int G, int NW, int MT, bool FP8>
 __global__ __launch_bounds__(NW * 64) void prefill_kernel(AttnArgs a, const int32_t *__restrict__ q_ptr,
-                                                          int q_tiles) {
+                                                          int q_tiles, int total_q) {
     using C = PrefillCfg<D, G, NW, MT>;
     extern __shared__ __attribute__((aligned(16))) char lds[];
 
@@ -66,14 +66,16 @@ __global__ __launch_bounds__(NW * 64) void prefill_kernel(AttnArgs a, const int3
     const int n_new = a.seq_lens[r] - ctx;
     const int i0 = qt * C::kBM;
     if (i0 >= n_new) return;
-    const int nb = a.num_blocks[r];
-    const int ncb = nb - (n_new + kBlock - 1) / kBlock;          // context entries
+    const int q0 = q_ptr[r];
+    // a request whose query rows do not match its table is skipped, never read out of bounds
+    if (q_ptr[r + 1] - q0 != n_new || q0 < 0 || q0 + n_new > total_q) return;
+    const int nb = min(a.num_blocks[r], a.max_blocks);
+    const int ncb = max(nb - (n_new + kBlock - 1) / kBlock, 0);  // context entries
     const int rows_end = min(n_new, i0 + C::kBM);
     const int e_end = min(nb, ncb + (rows_end + kBlock - 1) / kBlock);
     const int ntiles = (e_end + C::kEntries - 1) / C::kEntries;
     const int32_t *tab = a.block_table + (size_t)r * a.max_blocks;
     const int32_t *ntk = a.block_ntok + (size_t)r * a.max_blocks;
-    const int q0 = q_ptr[r];
 
     // ---- Q^T operand fragments (registers, whole kernel) ----------------------
     bf16x8 qf[MT][D / 16];
@@ -263,8 +265,8 @@ __global__ __launch_bounds__(NW * 64) void prefill_kernel(AttnArgs a, const int3
 }
 
 template <int D, int G, int NW, int MT>
-static hipError_t launch_prefill_t(const AttnArgs &a, int kv_dtype, const int32_t *q_ptr, int32_t max_q,
-                                   hipStream_t s) {
+static hipError_t launch_prefill_t(const AttnArgs &a, int kv_dtype, const int32_t *q_ptr, int32_t total_q,
+                                   int32_t max_q, hipStream_t s) {
     using C = PrefillCfg<D, G, NW, MT>;
     if (kv_dtype != GF_BF16) return hipErrorNotSupported;
     auto kern = prefill_kernel<D, G, NW, MT, false>;
@@ -278,7 +280,7 @@ static hipError_t launch_prefill_t(const AttnArgs &a, int kv_dtype, const int32_
     const size_t grid = (size_t)a.num_req * a.hkv * q_tiles;
     if (grid == 0) return hipSuccess;
     if (grid > 0x7fffffffu) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(C::kThreads), C::kLds, s, a, q_ptr, q_tiles);
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(C::kThreads), C::kLds, s, a, q_ptr, q_tiles, total_q);
     return hipGetLastError();
 }
 
@@ -286,7 +288,7 @@ hipError_t launch_prefill(const AttnArgs &a, int head_dim, int group, int kv_dty
                           int32_t total_q, int32_t max_q, hipStream_t s) {
     if (a.num_req == 0 || total_q == 0 || max_q == 0) return hipSuccess;
 #define GF_CASE(DD, GG) \
-    if (head_dim == DD && group == GG) return launch_prefill_t<DD, GG, 8, 1>(a, kv_dtype, q_ptr, max_q, s);
+    if (head_dim == DD && group == GG) return launch_prefill_t<DD, GG, 8, 1>(a, kv_dtype, q_ptr, total_q, max_q, s);
     GF_CASE(64, 1) GF_CASE(64, 2) GF_CASE(64, 4) GF_CASE(64, 8)
     GF_CASE(128, 1) GF_CASE(128, 2) GF_CASE(128, 4) GF_CASE(128, 8)
 #undef GF_CASE
