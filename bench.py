@@ -1,0 +1,303 @@
+#!/usr/bin/env python3
+"""Benchmark of the graph-KV attention hot path on one MI355X.
+
+One "step" is one pass of the whole path over one batch of a synthetic wGraph
+workload: gf_resolve_path -> gf_attn_prefill (requests with new tokens) ->
+gf_attn_decode (one decode step for the decode requests; for a prefill-only
+workload, the step after prefill: every request decodes with its last token),
+split-KV merge included.  Inputs are resident in HBM before the timed region.
+
+Prints ONE JSON line.  `value` is the headline metric of the chosen workload
+over the whole step; `roofline` describes the dominant kernel, timed live with
+HIP events on the launch stream; `cpu_baseline` is the fp64 oracle timed on the
+host cores on a bounded sample of the same workload (and used to check the GPU
+outputs of that sample); `extra` carries the other workloads' figures.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_MFMA_BF16_TFLOPS = 2500.0   # MI355X dense bf16 MFMA
+PEAK_HBM_GBS = 8000.0            # MI355X HBM3E
+
+
+def _event_ms(fn, torch, iters):
+    """Average duration of fn() in ms with HIP events on the current stream."""
+    s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    s.record()
+    for _ in range(iters):
+        fn()
+    e.record()
+    e.synchronize()
+    return s.elapsed_time(e) / iters
+
+
+def _read_traffic(name):
+    """HBM bytes per launch from the committed rocprofv3 --pmc summary, if any."""
+    p = os.path.join(ROOT, "profiles", f"{name}_traffic.txt")
+    if not os.path.exists(p):
+        return None
+    vals = {}
+    for line in open(p):
+        if "=" in line and not line.lstrip().startswith("#"):
+            k, v = line.split("=", 1)
+            try:
+                vals[k.strip()] = float(v.split()[0])
+            except ValueError:
+                pass
+    if "FETCH_BYTES_PER_LAUNCH" in vals and "WRITE_BYTES_PER_LAUNCH" in vals:
+        return vals["FETCH_BYTES_PER_LAUNCH"] + vals["WRITE_BYTES_PER_LAUNCH"]
+    return None
+
+
+class Job:
+    """A workload set up on the device: tables, pool, queries, outputs."""
+
+    def __init__(self, name, torch, R, W, decode_after_prefill=True):
+        self.torch, self.R, self.W = torch, R, W
+        self.wl = wl = W.CONFIGS[name]()
+        self.name = name
+        dev = torch.device("cuda:0")
+        self.sess = R.Session(wl, dev)
+        b = wl.batch
+        self.dbatch = self.sess.upload_batch(b)
+        g = wl.graph
+        nbl = ((g.node_len.astype(np.int64) + 15) // 16)
+        self.max_blocks = int(max(int(nbl[b.path_nodes[b.path_ptr[r]:b.path_ptr[r + 1]]].sum())
+                                  + (int(b.new_lens[r]) + 15) // 16 for r in range(b.num_req)))
+        self.tables = self.sess.alloc_tables(b.num_req, self.max_blocks)
+        self.pool = R.DevicePool.random(wl, dev)
+        sh = wl.shape
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(wl.seed + 1)
+        self.total_q = int(b.new_lens.sum())
+        self.max_q = int(b.new_lens.max())
+        self.q = torch.randn((self.total_q, sh.num_q_heads, sh.head_dim), generator=gen, device=dev,
+                             dtype=torch.float32).to(torch.bfloat16)
+        self.q_ptr = torch.from_numpy(np.concatenate([[0], np.cumsum(b.new_lens)]).astype(np.int32)).to(dev)
+        self.o = torch.zeros_like(self.q)
+        self.has_prefill = len(wl.prefill_req) > 0
+        self.has_decode = len(wl.decode_req) > 0 or decode_after_prefill
+        # decode queries: the last new token of every request
+        last = torch.from_numpy((np.cumsum(b.new_lens) - 1).astype(np.int64)).to(dev)
+        self.qd = self.q[last].contiguous()
+        self.od = torch.zeros_like(self.qd)
+        self.last = last
+        # request classes: the generator puts the prefill requests first.  A prefill-only workload
+        # decodes all its requests after prefill; a mixed batch prefills [0, P) and decodes [P, R).
+        P = len(wl.prefill_req)
+        Rn = b.num_req
+        self.pf_rng = (0, P)
+        self.dec_rng = (P, Rn) if len(wl.decode_req) > 0 else (0, Rn)
+        self.pf_rows = int(b.new_lens[:P].sum())
+        self.pf_max_q = int(b.new_lens[:P].max()) if P else 0
+        self.resolve()
+        torch.cuda.synchronize()
+
+    def _slice(self, lo, hi):
+        t = self.tables
+        out = {k: t[k][lo:hi] for k in ("block_table", "block_ntok", "num_blocks", "ctx_lens", "seq_lens", "status")}
+        out["num_req"], out["max_blocks"] = hi - lo, t["max_blocks"]
+        return out
+
+    def resolve(self):
+        self.sess.resolve(self.dbatch, self.tables)
+
+    def prefill(self):
+        lo, hi = self.pf_rng
+        self.sess.prefill(self.pool, self._slice(lo, hi), self.q, self.q_ptr[lo:hi + 1], self.pf_rows,
+                          self.pf_max_q, self.o)
+
+    def decode(self):
+        lo, hi = self.dec_rng
+        self.sess.decode(self.pool, self._slice(lo, hi), self.qd[lo:hi], self.od[lo:hi])
+
+    def step(self):
+        self.resolve()
+        if self.has_prefill:
+            self.prefill()
+        if self.has_decode:
+            self.decode()
+
+    # ---- algorithmic work -------------------------------------------------------
+    def prefill_flops(self):
+        return self.W.prefill_flops(self.wl, np.arange(*self.pf_rng)) if self.has_prefill else 0.0
+
+    def decode_bytes(self):
+        return self.W.decode_bytes(self.wl, np.arange(*self.dec_rng))
+
+
+def measure(job, steps, warmup):
+    torch = job.torch
+    for _ in range(warmup):
+        job.step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        job.step()
+    torch.cuda.synchronize()
+    ms_step = (time.perf_counter() - t0) * 1e3 / steps
+    out = {"ms_per_step": ms_step}
+    it = max(steps, 5)
+    out["resolve_ms"] = _event_ms(job.resolve, torch, it)
+    if job.has_prefill:
+        out["prefill_ms"] = _event_ms(job.prefill, torch, it)
+        out["prefill_tflops_kernel"] = job.prefill_flops() / (out["prefill_ms"] * 1e-3) / 1e12
+    if job.has_decode:
+        out["decode_ms"] = _event_ms(job.decode, torch, it)
+        out["decode_gbs_kernel"] = job.decode_bytes() / (out["decode_ms"] * 1e-3) / 1e9
+    return out
+
+
+def cpu_baseline(job, budget_s=20.0):
+    """Time the fp64 oracle on a bounded sample of the workload's requests and
+    check the GPU outputs of the sample against it."""
+    from oracle import attention as OA
+    from oracle import resolve as ORS
+    torch, R, W = job.torch, job.R, job.W
+    wl = job.wl
+    b, g = wl.batch, wl.graph
+    sh = wl.shape
+    tables = ORS.resolve_paths(g.num_nodes, g.node_len, g.node_block_ptr, g.node_blocks, g.edge_ptr, g.edge_dst,
+                               b.path_ptr, b.path_nodes, b.new_lens, b.tail_ptr, b.tail_blocks, job.max_blocks,
+                               wl.num_pool_blocks)
+    # GPU tables must be bit-exact
+    dev_tables = R.tables_to_host(job.tables)
+    tables_exact = all(dev_tables[k] == tables[k] for k in tables)
+    L = W.context_lens(wl)
+    n = b.new_lens.astype(np.int64)
+    prefill_mode = job.has_prefill
+    lo_r, hi_r = job.pf_rng if prefill_mode else job.dec_rng
+    order = lo_r + np.random.default_rng(wl.seed + 9).permutation(hi_r - lo_r)
+    q_host = R.bf16_to_bits(job.q)
+    o_gpu = job.o.double().cpu().numpy() if prefill_mode else job.od.double().cpu().numpy()
+    atol, rtol = (1e-2, 1e-2) if sh.kv_dtype == W.KV_BF16 else (5e-2, 5e-2)
+    spent, work, used, max_err, ok = 0.0, 0.0, 0, 0.0, True
+    for r in order:
+        r = int(r)
+        nb = tables["num_blocks"][r]
+        ids = np.array(tables["block_table"][r][:nb], dtype=np.int64)
+        kk, vv, ks, vs = job.pool.gather_host(ids)
+        local = {k_: [v_[r]] for k_, v_ in tables.items()}
+        local["block_table"] = [list(range(nb))]
+        lo, hi = int(job.q_ptr[r]), int(job.q_ptr[r + 1])
+        t0 = time.perf_counter()
+        if prefill_mode:
+            O, _ = OA.prefill(q_host[lo:hi], np.array([0, hi - lo]), kk, vv, local, ks, vs)
+            got = o_gpu[lo:hi]
+            work += W.prefill_flops(wl, [r])
+        else:
+            O, _ = OA.decode(q_host[hi - 1:hi], kk, vv, local, ks, vs)
+            got = o_gpu[r:r + 1]
+            work += W.decode_bytes(wl, [r])
+        spent += time.perf_counter() - t0
+        err = np.abs(got - O)
+        max_err = max(max_err, float(err.max()))
+        ok = ok and bool((err <= atol + rtol * np.abs(O)).all())
+        used += 1
+        if spent > budget_s:
+            break
+    try:
+        import threadpoolctl
+        threads = max(i["num_threads"] for i in threadpoolctl.threadpool_info())
+    except Exception:
+        threads = os.cpu_count()
+    unit = "TFLOP/s" if prefill_mode else "GB/s"
+    value = work / spent / (1e12 if prefill_mode else 1e9)
+    return {"value": value, "unit": unit, "cores": int(threads), "kind": "oracle",
+            "sample": f"{used} of {b.num_req} requests of {wl.name} (seeded order), {spent:.1f} s of numpy fp64",
+            "gpu_matches_oracle_on_sample": ok, "max_abs_err": max_err, "tables_bit_exact": tables_exact}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="prefill_8b",
+                    choices=["tiny", "prefill_8b", "decode_8b", "decode_70b", "mixed_fp8"])
+    ap.add_argument("--extra", default="decode_8b", help="comma list of further workloads reported under 'extra'")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-budget", type=float, default=20.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2605_22566_amd import binding as B
+    from paper_2605_22566_amd import runner as R
+    from paper_2605_22566_amd import workload as W
+    B.load_library()           # fails loudly if the HIP library is not built
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+
+    job = Job(args.workload, torch, R, W)
+    m = measure(job, args.steps, args.warmup)
+    wl = job.wl
+    if job.has_prefill:
+        metric, unit = "prefill_tflops", "TFLOP/s"
+        value = job.prefill_flops() / (m["ms_per_step"] * 1e-3) / 1e12
+        roof = {"bound": "mfma", "kernel": "prefill_kernel", "achieved": m["prefill_tflops_kernel"],
+                "peak": PEAK_MFMA_BF16_TFLOPS, "unit": "TFLOP/s",
+                "frac": m["prefill_tflops_kernel"] / PEAK_MFMA_BF16_TFLOPS,
+                "traffic": _read_traffic(f"prefill_{args.workload}"),
+                "kernel_ms": m["prefill_ms"], "algorithmic_flops_per_launch": job.prefill_flops()}
+    else:
+        metric, unit = "decode_hbm_gbs", "GB/s"
+        value = job.decode_bytes() / (m["ms_per_step"] * 1e-3) / 1e9
+        roof = {"bound": "hbm", "kernel": "decode_split_kernel(+merge)", "achieved": m["decode_gbs_kernel"],
+                "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": m["decode_gbs_kernel"] / PEAK_HBM_GBS,
+                "traffic": _read_traffic(f"decode_{args.workload}"),
+                "kernel_ms": m["decode_ms"], "algorithmic_bytes_per_launch": job.decode_bytes()}
+    res = {
+        "metric": metric, "value": value, "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": m["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if wl.shape.kv_dtype == W.KV_BF16 else "fp8_e4m3 KV / bf16 Q, fp32 accumulate",
+        "data": "synthetic",
+        "config": {"workload": args.workload, "requests": wl.batch.num_req, "q_heads": wl.shape.num_q_heads,
+                   "kv_heads": wl.shape.num_kv_heads, "head_dim": wl.shape.head_dim, "block": 16,
+                   "nodes": wl.graph.num_nodes, "pool_blocks": wl.num_pool_blocks,
+                   "new_tokens": int(wl.batch.new_lens.sum()), "ctx_tokens": int(W.context_lens(wl).sum()),
+                   "sharing_factor": W.sharing_stats(wl)["sharing_factor"], "seed": wl.seed,
+                   "step": "resolve+prefill+decode(+merge)"},
+        "roofline": roof,
+        "breakdown_ms": {k: v for k, v in m.items() if k.endswith("_ms")},
+    }
+    if job.has_prefill and job.has_decode:
+        res["decode_gbs_kernel"] = m["decode_gbs_kernel"]
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(job, args.cpu_budget)
+    extra = {}
+    del job
+    torch.cuda.empty_cache()
+    for name in [x for x in args.extra.split(",") if x and x != args.workload]:
+        j = Job(name, torch, R, W, decode_after_prefill=False)
+        mm = measure(j, max(5, args.steps // 2), 3)
+        ent = {"ms_per_step": mm["ms_per_step"], "breakdown_ms": {k: v for k, v in mm.items() if k.endswith("_ms")}}
+        if j.has_prefill:
+            ent["prefill_tflops_kernel"] = mm["prefill_tflops_kernel"]
+            ent["prefill_frac_of_mfma_peak"] = mm["prefill_tflops_kernel"] / PEAK_MFMA_BF16_TFLOPS
+        if j.has_decode:
+            ent["decode_gbs_kernel"] = mm["decode_gbs_kernel"]
+            ent["decode_frac_of_hbm_peak"] = mm["decode_gbs_kernel"] / PEAK_HBM_GBS
+            ent["algorithmic_bytes_per_launch"] = j.decode_bytes()
+        extra[name] = ent
+        del j
+        torch.cuda.empty_cache()
+    if extra:
+        res["extra"] = extra
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()
