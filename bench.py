@@ -226,6 +226,9 @@ def main():
     ap.add_argument("--extra", default="decode_8b", help="comma list of further workloads reported under 'extra'")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=20.0)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="first run three plain 1 GiB device copies (known traffic, for scaling rocprofv3 "
+                         "FETCH_SIZE / WRITE_SIZE readings)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); --gpus must be 1",
@@ -240,6 +243,15 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
         sys.exit(2)
+
+    if args.copy_calibration:
+        src = torch.ones(1 << 29, dtype=torch.bfloat16, device="cuda:0")   # 1 GiB
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
 
     job = Job(args.workload, torch, R, W)
     m = measure(job, args.steps, args.warmup)

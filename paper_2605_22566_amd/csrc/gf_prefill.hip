@@ -5,10 +5,11 @@
 // on-the-fly fallback of Effective Path Pruning).
 //
 // MFMA path.  One workgroup owns (request, kv head, tile of BM new tokens) and
-// all G query heads of the group: BM*G score rows share every K/V tile that is
-// staged through LDS, so each byte fetched feeds G times the flops.  Each wave
-// owns MT 32-row tiles (one query head, 32 tokens).  Scores are computed
-// transposed so the softmax statistics of a row live in one lane pair:
+// all G query heads of the group: BM*G = 256 score rows share every K/V tile
+// that is staged through LDS, so each byte fetched feeds G times the flops.
+// Each of the 8 waves owns one 32-row tile (one query head, 32 tokens).
+// Scores are computed transposed so the softmax statistics of a row live in
+// one lane pair:
 //   S^T[key][row]  = K[key][d]   * Q^T[d][row]      (A = K from LDS, B = Q regs)
 //   O^T[d][row]   += V^T[d][key] * P^T[key][row]    (A = V^T from LDS, B = P regs)
 // with v_mfma_f32_32x32x16_bf16: operand lane l holds row/col l%32 and the 8
@@ -19,16 +20,35 @@
 // the contraction group the V^T operand reads as one 16-byte LDS load from the
 // pool's [d][slot] V layout.  P never leaves registers.
 //
-// KV tiles are 64 keys (4 table entries); per-entry token counts mask partial
-// blocks anywhere in the sequence, and tail entries are masked causally.
+// Pipeline.  KV tiles are 64 keys (4 table entries), double buffered in LDS
+// with K staged one tile ahead of V.  Inside a wave the scores run one tile
+// ahead of the softmax: iteration t issues, as one straight-line stream of 32
+// slots, the 16 score MFMAs of tile t+1 and the 16 P*V MFMAs of tile t, and in
+// the shadow of every MFMA a fixed share of the vector work (exponentials, row
+// sums and bf16 packing of tile t; row maximum of tile t+1) and one LDS operand
+// fetch, four slots ahead of its use.  Scheduling barriers pin that order.
+// The reference row maximum is refreshed (and O rescaled) only when some row's
+// new maximum exceeds it by more than 2^8; the final normalisation uses the
+// same reference, so the result is unchanged.  Per-entry token counts mask
+// partial blocks anywhere in the sequence and tail entries causally, in a side
+// path taken only by tiles that need it.
+#include <algorithm>
+#include <cstdio>
+#include <cstdlib>
+#include <vector>
+
 #include "gf_internal.h"
 
 namespace gf {
 
-template <int D, int G, int NW, int MT>
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+
+template <int D, int G>
 struct PrefillCfg {
-    static constexpr int kThreads = NW * 64;
-    static constexpr int kRows = 32 * NW * MT;       // score rows per workgroup
+    static constexpr int kWaves = 8;
+    static constexpr int kThreads = kWaves * 64;
+    static constexpr int kRows = 32 * kWaves;        // score rows per workgroup
     static constexpr int kBM = kRows / G;            // new tokens per workgroup
     static constexpr int kBN = 64;                   // keys per KV tile
     static constexpr int kEntries = kBN / kBlock;    // table entries per tile (4)
@@ -36,29 +56,47 @@ struct PrefillCfg {
     static constexpr int kKTile = kBN * kKStride;
     static constexpr int kVBlk = D * kBlock * 2;     // one V block in LDS (bytes)
     static constexpr int kVTile = kEntries * kVBlk;
-    static constexpr int kStage = kKTile + kVTile;
-    static constexpr int kLds = 2 * kStage;
+    static constexpr int kLds = 2 * kKTile + 2 * kVTile;
     static constexpr int kChunks = kEntries * 2 * D; // 16-byte chunks per tensor per tile
     static constexpr int kLoads = kChunks / kThreads;  // per thread per tensor
-    static_assert(kRows % G == 0 && (NW * MT) % G == 0, "row tiles must split evenly over heads");
+    static constexpr int kKS = D / 16;               // contraction steps of the score MFMAs
+    static constexpr int kDT = D / 32;               // 32-wide output tiles of P*V
+    static constexpr int kQK = 2 * kKS;              // score MFMAs per tile
+    static constexpr int kPV = kDT * kEntries;       // P*V MFMAs per tile
+    static_assert(kRows % G == 0 && kWaves % G == 0, "row tiles must split evenly over heads");
     static_assert(kChunks % kThreads == 0, "staging must divide evenly");
     static_assert((2 * D) % 64 == 0, "a wave must stay inside one block while staging");
 };
 
-template <int D, int G, int NW, int MT, bool FP8>
-__global__ __launch_bounds__(NW * 64) void prefill_kernel(AttnArgs a, const int32_t *__restrict__ q_ptr,
-                                                          int q_tiles, int total_q) {
-    using C = PrefillCfg<D, G, NW, MT>;
+constexpr float kRescaleSlack = 8.0f;   // log2 units a row max may exceed its reference
+constexpr int kAhead = 4;               // LDS operand fragments in flight ahead of their MFMA
+
+template <int D, int G, bool FP8>
+__global__ __launch_bounds__(512) void prefill_kernel(AttnArgs a, const int32_t *__restrict__ tab_base,
+                                                      const int32_t *__restrict__ ntk_base,
+                                                      const int32_t *__restrict__ q_ptr, int q_tiles,
+                                                      int total_q, int dbg, unsigned long long *dbuf) {
+    using C = PrefillCfg<D, G>;
+    const unsigned long long t_start = __builtin_readcyclecounter();
+    const unsigned long long r_start = wall_clock64();
     extern __shared__ __attribute__((aligned(16))) char lds[];
+    char *const kbuf = lds;                       // [2][kKTile]
+    char *const vbuf = lds + 2 * C::kKTile;       // [2][kVTile]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int m = lane & 31, hh = lane >> 5;
 
-    // work item: q tile fastest, then kv head, then request
-    const int qt = blockIdx.x % q_tiles;
-    const int rk = blockIdx.x / q_tiles;
+    // Work item.  Workgroups are dealt to the 8 XCDs round-robin by id, and each XCD has
+    // its own L2: (request, kv head) pair p goes to XCD p % 8 with all its q tiles queued
+    // back to back there, so the tiles of a pair stream the same K/V through one L2 and
+    // (with 8 kv heads) every XCD carries exactly one head of every request.
+    const int xcd = blockIdx.x & 7;
+    const int slot = blockIdx.x >> 3;
+    const int qt = q_tiles - 1 - slot % q_tiles;       // longest (most causal tail) first
+    const int rk = (slot / q_tiles) * 8 + xcd;
+    if (rk >= a.num_req * a.hkv) return;
     const int kvh = rk % a.hkv;
     const int r = rk / a.hkv;
     if (a.status && a.status[r] != 0) return;
@@ -74,202 +112,266 @@ __global__ __launch_bounds__(NW * 64) void prefill_kernel(AttnArgs a, const int3
     const int rows_end = min(n_new, i0 + C::kBM);
     const int e_end = min(nb, ncb + (rows_end + kBlock - 1) / kBlock);
     const int ntiles = (e_end + C::kEntries - 1) / C::kEntries;
-    const int32_t *tab = a.block_table + (size_t)r * a.max_blocks;
-    const int32_t *ntk = a.block_ntok + (size_t)r * a.max_blocks;
+    const int32_t *__restrict__ tab = tab_base + (size_t)r * a.max_blocks;
+    const int32_t *__restrict__ ntk = ntk_base + (size_t)r * a.max_blocks;
 
     // ---- Q^T operand fragments (registers, whole kernel) ----------------------
-    bf16x8 qf[MT][D / 16];
-    int row_tok[MT];
-    int row_head[MT];
+    bf16x8 qf[C::kKS];
+    const int g = wave % G, tt = wave / G;
+    const int row_tok = i0 + 32 * tt + m;
+    const int row_head = kvh * G + g;
+    {
+        const int tokc = min(row_tok, n_new - 1);
+        const char *qp = (const char *)a.q + (((size_t)(q0 + tokc)) * a.hq + row_head) * (D * 2);
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        const int tile = wave * MT + mt;
-        const int g = tile % G, tt = tile / G;
-        const int tok = i0 + 32 * tt + m;
-        row_tok[mt] = tok;
-        row_head[mt] = kvh * G + g;
-        const int tokc = min(tok, n_new - 1);
-        const char *qp = (const char *)a.q + (((size_t)(q0 + tokc)) * a.hq + row_head[mt]) * (D * 2);
-#pragma unroll
-        for (int ks = 0; ks < D / 16; ++ks)
-            qf[mt][ks] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(qp + (16 * ks + 8 * hh) * 2));
+        for (int ks = 0; ks < C::kKS; ++ks)
+            qf[ks] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(qp + (16 * ks + 8 * hh) * 2));
     }
 
-    // ---- staging helpers ----------------------------------------------------------
+    // ---- staging: global -> registers -> LDS -------------------------------------
     u32x4 kst[C::kLoads], vst[C::kLoads];
     const size_t blk_bytes = (size_t)kBlock * D * 2;
-    auto issue_loads = [&](int tile) {
-        const int e = tile * C::kEntries;
-#pragma unroll
-        for (int i = 0; i < C::kLoads; ++i) {
-            const int u = tid + i * C::kThreads;
-            const int cb = __builtin_amdgcn_readfirstlane(u / (2 * D));   // entry within the tile
-            const int within = u % (2 * D);
-            int bid = (e + cb < e_end) ? tab[e + cb] : 0;
-            bid = min(max(bid, 0), a.pool_blocks - 1);
-            const size_t off = ((size_t)bid * a.hkv + kvh) * blk_bytes + (size_t)within * 16;
-            kst[i] = *(const u32x4 *)((const char *)a.k + off);
-            vst[i] = *(const u32x4 *)((const char *)a.v + off);
-        }
+    auto tile_offset = [&](int tile, int i) -> size_t {
+        const int u = tid + i * C::kThreads;
+        const int cb = __builtin_amdgcn_readfirstlane(u / (2 * D));   // entry within the tile
+        const int within = u % (2 * D);
+        const int ent = tile * C::kEntries + cb;
+        int bid = (ent < e_end) ? tab[ent] : 0;
+        bid = min(max(bid, 0), a.pool_blocks - 1);
+        return ((size_t)bid * a.hkv + kvh) * blk_bytes + (size_t)within * 16;
     };
-    auto store_stage = [&](int buf) {
-        char *base = lds + buf * C::kStage;
+    auto issue_k = [&](int tile) {
+#pragma unroll
+        for (int i = 0; i < C::kLoads; ++i) kst[i] = *(const u32x4 *)((const char *)a.k + tile_offset(tile, i));
+    };
+    auto issue_v = [&](int tile) {
+#pragma unroll
+        for (int i = 0; i < C::kLoads; ++i) vst[i] = *(const u32x4 *)((const char *)a.v + tile_offset(tile, i));
+    };
+    auto store_k = [&](int buf) {
 #pragma unroll
         for (int i = 0; i < C::kLoads; ++i) {
             const int u = tid + i * C::kThreads;
-            const int cb = u / (2 * D);
-            const int within = u % (2 * D);
+            const int cb = u / (2 * D), within = u % (2 * D);
             const int slot = within / (D / 8), dch = within % (D / 8);
-            *(u32x4 *)(base + (kBlock * cb + slot) * C::kKStride + dch * 16) = kst[i];
-            const int d = within >> 1, hv = within & 1;
-            *(u32x4 *)(base + C::kKTile + cb * C::kVBlk + hv * (D * 16) + d * 16) = vst[i];
+            *(u32x4 *)(kbuf + buf * C::kKTile + (kBlock * cb + slot) * C::kKStride + dch * 16) = kst[i];
         }
     };
-
-    // ---- running state --------------------------------------------------------------
-    const float c = a.scale_log2;
-    float m_run[MT], l_run[MT];
-    f32x16 o[MT][D / 32];
+    auto store_v = [&](int buf) {
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        m_run[mt] = -1.0e30f;
-        l_run[mt] = 0.f;
-#pragma unroll
-        for (int dt = 0; dt < D / 32; ++dt)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) o[mt][dt][i] = 0.f;
-    }
+        for (int i = 0; i < C::kLoads; ++i) {
+            const int u = tid + i * C::kThreads;
+            const int cb = u / (2 * D), within = u % (2 * D);
+            const int d = within >> 1, hv = within & 1;
+            *(u32x4 *)(vbuf + buf * C::kVTile + cb * C::kVBlk + hv * (D * 16) + d * 16) = vst[i];
+        }
+    };
 
     // K operand row m reads key (m with bits 2,3 swapped)
     const int krow = (m & 0x13) | ((m & 4) << 1) | ((m & 8) >> 1);
     const int k_lane_off = krow * C::kKStride + 8 * hh * 2;
-    const int v_lane_off = C::kKTile + hh * (D * 16) + m * 16;
+    const int v_lane_off = hh * (D * 16) + m * 16;
 
-    issue_loads(0);
-    store_stage(0);
-    __syncthreads();
+    // ---- running state --------------------------------------------------------------
+    const float c = a.scale_log2;
+    float m_ref = -1.0e30f, l_run = 0.f;
+    float mx = -INFINITY;             // row maximum (log2 units) of the tile whose scores are pending
+    f32x16 o[C::kDT];
+#pragma unroll
+    for (int dt = 0; dt < C::kDT; ++dt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[dt][i] = 0.f;
+    f32x16 s_a[2], s_b[2];            // score tiles, ping-pong (2 x 32 keys each)
 
-    for (int t = 0; t < ntiles; ++t) {
-        const int buf = t & 1;
-        const bool more = t + 1 < ntiles;
-        if (more) issue_loads(t + 1);
-        const char *sb = lds + buf * C::kStage;
-        const int e = t * C::kEntries;
-
-        // ---- S^T = K Q^T ----------------------------------------------------------
-        f32x16 s[MT][2];
+    auto row_max = [&](const f32x16 (&s)[2]) -> float {
+        float v = fmaxf(s[0][0], s[1][0]);
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-            for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) s[mt][kt][i] = 0.f;
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt)
-#pragma unroll
-            for (int ks = 0; ks < D / 16; ++ks) {
-                const bf16x8 kf = __builtin_bit_cast(
-                    bf16x8, *(const u32x4 *)(sb + k_lane_off + 32 * kt * C::kKStride + 16 * ks * 2));
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt)
-                    s[mt][kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[mt][ks], s[mt][kt], 0, 0, 0);
-            }
-
-        // ---- masks: partial blocks and the causal tail -------------------------------
+        for (int i = 1; i < 16; ++i) v = fmaxf(v, fmaxf(s[0][i], s[1][i]));
+        return fmaxf(v, other_half(v)) * c;
+    };
+    // uniform: does tile t hold a partial block or a causally cut tail entry?
+    auto tile_needs_mask = [&](int t) -> bool {
+        bool need = false;
 #pragma unroll
         for (int cb = 0; cb < C::kEntries; ++cb) {
-            const int ent = e + cb;
+            const int ent = t * C::kEntries + cb;
             const int nt = ent < e_end ? ntk[ent] : 0;
-            const bool tail = ent >= ncb;
-            if (nt < kBlock || tail) {
+            need |= (nt < kBlock) || (ent >= ncb && (ent - ncb) * kBlock + kBlock - 1 > i0);
+        }
+        return need;
+    };
+    auto apply_mask = [&](int t, f32x16 (&s)[2]) {
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt) {
-                    int lim = nt;
-                    if (tail) lim = min(lim, row_tok[mt] - (ent - ncb) * kBlock + 1);
-                    lim -= 8 * hh;
+        for (int cb = 0; cb < C::kEntries; ++cb) {
+            const int ent = t * C::kEntries + cb;
+            const int nt = ent < e_end ? ntk[ent] : 0;
+            const int tail_base = ent >= ncb ? (ent - ncb) * kBlock : -(1 << 28);
+            const int lim = min(nt, row_tok - tail_base + 1) - 8 * hh;
 #pragma unroll
-                    for (int j = 0; j < 8; ++j)
-                        if (j >= lim) s[mt][cb >> 1][8 * (cb & 1) + j] = -INFINITY;
-                }
+            for (int j = 0; j < 8; ++j) {
+                const float x = s[cb >> 1][8 * (cb & 1) + j];
+                s[cb >> 1][8 * (cb & 1) + j] = (j < lim) ? x : -INFINITY;
             }
         }
+    };
 
-        // ---- online softmax (fp32), P -> bf16 operand fragments ----------------------
-        bf16x8 pf[MT][C::kEntries];
+    // ---- prologue: K(0), V(0), K(1) into LDS; scores of tile 0 ---------------------------
+    issue_k(0);
+    issue_v(0);
+    store_k(0);
+    store_v(0);
+    if (ntiles > 1) {
+        issue_k(1);
+        store_k(1);
+    }
+    __syncthreads();
+    {
+        const char *kb = kbuf + k_lane_off;
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            float mx = s[mt][0][0];
+        for (int kt = 0; kt < 2; ++kt) {
 #pragma unroll
-            for (int kt = 0; kt < 2; ++kt)
+            for (int x = 0; x < 16; ++x) s_a[kt][x] = 0.f;
 #pragma unroll
-                for (int i = 0; i < 16; ++i) mx = fmaxf(mx, s[mt][kt][i]);
-            mx = fmaxf(mx, other_half(mx));
-            const float m_new = fmaxf(m_run[mt], mx);
-            const float alpha = fast_exp2((m_run[mt] - m_new) * c);
-            const float mc = m_new * c;
-            m_run[mt] = m_new;
-            float psum = 0.f;
-#pragma unroll
-            for (int cb = 0; cb < C::kEntries; ++cb) {
-                f32x8 p;
-#pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    p[j] = fast_exp2(s[mt][cb >> 1][8 * (cb & 1) + j] * c - mc);
-                    psum += p[j];
-                }
-                pf[mt][cb] = __builtin_convertvector(p, bf16x8);
+            for (int ks = 0; ks < C::kKS; ++ks) {
+                const bf16x8 kf =
+                    __builtin_bit_cast(bf16x8, *(const u32x4 *)(kb + 32 * kt * C::kKStride + 16 * ks * 2));
+                s_a[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s_a[kt], 0, 0, 0);
             }
-            l_run[mt] = l_run[mt] * alpha + psum;
+        }
+        mx = row_max(s_a);
+    }
+
+    // ---- one iteration: softmax + P*V of tile t (scores in sc), scores of tile t+1 -> sn ----
+    auto body = [&](int t, f32x16 (&sc)[2], f32x16 (&sn)[2]) {
+        const bool has_next = t + 1 < ntiles;
+        const bool k2 = t + 2 < ntiles;
+        if (!(dbg & 1)) {
+            if (k2) issue_k(t + 2);
+            if (has_next) issue_v(t + 1);
+        }
+        // side path: partial blocks / causal tail in tile t
+        if (tile_needs_mask(t)) {
+            apply_mask(t, sc);
+            mx = row_max(sc);
+        }
+        // refresh the reference maximum only when some row outgrew it
+        if (__builtin_amdgcn_ballot_w64(mx > m_ref + kRescaleSlack) != 0) {
+            const float m_new = fmaxf(m_ref, mx);
+            const float alpha = fast_exp2(m_ref - m_new);
+            m_ref = m_new;
+            l_run *= alpha;
 #pragma unroll
-            for (int dt = 0; dt < D / 32; ++dt) o[mt][dt] *= alpha;
+            for (int dt = 0; dt < C::kDT; ++dt) o[dt] *= alpha;
         }
 
-        // ---- O^T += V^T P^T ------------------------------------------------------------
+        // main stream: 32 slots of {MFMA, LDS fetch 4 ahead, vector share}
+        const char *kb = kbuf + ((t + 1) & 1) * C::kKTile + k_lane_off;
+        const char *vb = vbuf + (t & 1) * C::kVTile + v_lane_off;
+        auto frag = [&](int n) -> u32x4 {      // unified operand stream: K fragments then V fragments
+            if (n < C::kQK) return *(const u32x4 *)(kb + 32 * (n / C::kKS) * C::kKStride + 16 * (n % C::kKS) * 2);
+            const int j = n - C::kQK;
+            return *(const u32x4 *)(vb + (j / C::kDT) * C::kVBlk + 32 * (j % C::kDT) * 16);
+        };
+        constexpr int NSLOT = C::kQK + C::kPV;
+        constexpr int kExpPerSlot = 32 / C::kQK;     // exponentials in the shadow of one score MFMA
+        u32x4 f[kAhead];
 #pragma unroll
-        for (int dt = 0; dt < D / 32; ++dt)
+        for (int i = 0; i < kAhead; ++i) f[i] = frag(i);
+        uint32_t pw[C::kEntries][4];                 // P^T operand, 2 bf16 per word
+        float psum = 0.f;
+        float vmax = -INFINITY;
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int cb = 0; cb < C::kEntries; ++cb) {
-                const bf16x8 vf = __builtin_bit_cast(
-                    bf16x8, *(const u32x4 *)(sb + v_lane_off + cb * C::kVBlk + 32 * dt * 16));
+        for (int i = 0; i < NSLOT; ++i) {
+            if (i < C::kQK) {
+                const int kt = i / C::kKS, ks = i % C::kKS;
+                if (ks == 0) {
 #pragma unroll
-                for (int mt = 0; mt < MT; ++mt)
-                    o[mt][dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[mt][cb], o[mt][dt], 0, 0, 0);
+                    for (int x = 0; x < 16; ++x) sn[kt][x] = 0.f;
+                }
+                sn[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f[i % kAhead]), qf[ks],
+                                                                  sn[kt], 0, 0, 0);
+                // vector share: exponentials of tile t, kExpPerSlot per slot
+#pragma unroll
+                for (int e2 = 0; e2 < kExpPerSlot; e2 += 2) {
+                    const int idx = i * kExpPerSlot + e2;        // 0..31: score register pair
+                    const int kt2 = idx / 16, x = idx % 16;
+                    f32x2 p;
+                    p[0] = fast_exp2(sc[kt2][x] * c - m_ref);
+                    p[1] = fast_exp2(sc[kt2][x + 1] * c - m_ref);
+                    psum += p[0] + p[1];
+                    pw[idx / 8][(idx % 8) / 2] = __builtin_bit_cast(uint32_t, __builtin_convertvector(p, bf16x2));
+                }
+            } else {
+                const int j = i - C::kQK;
+                const int cb = j / C::kDT, dt = j % C::kDT;
+                u32x4 pq = {pw[cb][0], pw[cb][1], pw[cb][2], pw[cb][3]};
+                o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f[i % kAhead]),
+                                                                __builtin_bit_cast(bf16x8, pq), o[dt], 0, 0, 0);
+                // vector share: running maximum of the next tile's scores
+                constexpr int kMaxPerSlot = 32 / C::kPV;
+#pragma unroll
+                for (int e2 = 0; e2 < kMaxPerSlot; ++e2) {
+                    const int idx = j * kMaxPerSlot + e2;
+                    vmax = fmaxf(vmax, sn[idx / 16][idx % 16]);
+                }
             }
-
-        if (more) store_stage(buf ^ 1);
+            if (i + kAhead < NSLOT) f[i % kAhead] = frag(i + kAhead);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        l_run += psum;
+        mx = fmaxf(vmax, other_half(vmax)) * c;
+        if (has_next && !(dbg & 1)) {
+            if (k2) store_k(t & 1);          // K(t+2) replaces K(t), whose scores were computed last iteration
+            store_v((t + 1) & 1);            // V(t+1) replaces V(t-1)
+        }
         __syncthreads();
+    };
+
+    const unsigned long long t_loop0 = __builtin_readcyclecounter();
+    int t = 0;
+    for (; t + 2 <= ntiles; t += 2) {
+        body(t, s_a, s_b);
+        body(t + 1, s_b, s_a);
+    }
+    if (t < ntiles) body(t, s_a, s_b);
+    const unsigned long long t_loop1 = __builtin_readcyclecounter();
+    if (dbuf && tid == 0) {
+        dbuf[blockIdx.x * 8 + 0] = t_loop0 - t_start;
+        dbuf[blockIdx.x * 8 + 1] = t_loop1 - t_loop0;
+        dbuf[blockIdx.x * 8 + 2] = ntiles;
+        dbuf[blockIdx.x * 8 + 3] = r_start;
+        dbuf[blockIdx.x * 8 + 4] = wall_clock64();
     }
 
     // ---- epilogue: normalise, round to bf16, store ------------------------------------
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        const float l_tot = l_run[mt] + other_half(l_run[mt]);
-        const int tok = row_tok[mt];
-        if (tok < n_new) {
+    {
+        const float l_tot = l_run + other_half(l_run);
+        if (row_tok < n_new) {
             const float inv = 1.f / l_tot;
-            char *op = (char *)a.o + (((size_t)(q0 + tok)) * a.hq + row_head[mt]) * (D * 2);
+            char *op = (char *)a.o + (((size_t)(q0 + row_tok)) * a.hq + row_head) * (D * 2);
 #pragma unroll
-            for (int dt = 0; dt < D / 32; ++dt)
+            for (int dt = 0; dt < C::kDT; ++dt)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    f32x4 v4 = {o[mt][dt][4 * q] * inv, o[mt][dt][4 * q + 1] * inv, o[mt][dt][4 * q + 2] * inv,
-                                o[mt][dt][4 * q + 3] * inv};
+                    f32x4 v4 = {o[dt][4 * q] * inv, o[dt][4 * q + 1] * inv, o[dt][4 * q + 2] * inv,
+                                o[dt][4 * q + 3] * inv};
                     const bf16x4 b4 = __builtin_convertvector(v4, bf16x4);
                     *(bf16x4 *)(op + (32 * dt + 8 * q + 4 * hh) * 2) = b4;
                 }
             if (a.lse && hh == 0)
-                a.lse[(size_t)(q0 + tok) * a.hq + row_head[mt]] =
-                    (m_run[mt] * c + __builtin_log2f(l_tot)) * 0.6931471805599453f;
+                a.lse[(size_t)(q0 + row_tok) * a.hq + row_head] =
+                    (m_ref + __builtin_log2f(l_tot)) * 0.6931471805599453f;
         }
     }
 }
 
-template <int D, int G, int NW, int MT>
+template <int D, int G>
 static hipError_t launch_prefill_t(const AttnArgs &a, int kv_dtype, const int32_t *q_ptr, int32_t total_q,
                                    int32_t max_q, hipStream_t s) {
-    using C = PrefillCfg<D, G, NW, MT>;
+    using C = PrefillCfg<D, G>;
     if (kv_dtype != GF_BF16) return hipErrorNotSupported;
-    auto kern = prefill_kernel<D, G, NW, MT, false>;
+    auto kern = prefill_kernel<D, G, false>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, C::kLds);
@@ -277,10 +379,36 @@ static hipError_t launch_prefill_t(const AttnArgs &a, int kv_dtype, const int32_
         attr_set = true;
     }
     const int q_tiles = (max_q + C::kBM - 1) / C::kBM;
-    const size_t grid = (size_t)a.num_req * a.hkv * q_tiles;
+    const size_t pairs8 = ((size_t)a.num_req * a.hkv + 7) / 8 * 8;   // padded so that id % 8 is the XCD
+    const size_t grid = pairs8 * q_tiles;
     if (grid == 0) return hipSuccess;
     if (grid > 0x7fffffffu) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(C::kThreads), C::kLds, s, a, q_ptr, q_tiles, total_q);
+    unsigned long long *dbuf = nullptr;
+    static int calls = 0;
+    const bool want = getenv("GF_DBGBUF") && (++calls == 5);
+    if (want) {
+        hipMalloc(&dbuf, grid * 64);
+        hipMemset(dbuf, 0, grid * 64);
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(C::kThreads), C::kLds, s, a, a.block_table, a.block_ntok,
+                       q_ptr, q_tiles, total_q, getenv("GF_DBG") ? atoi(getenv("GF_DBG")) : 0, dbuf);
+    if (want) {
+        hipDeviceSynchronize();
+        std::vector<unsigned long long> h(grid * 8);
+        hipMemcpy(h.data(), dbuf, grid * 64, hipMemcpyDeviceToHost);
+        double pro = 0, loop = 0, tiles = 0, real = 0; size_t n = 0;
+        unsigned long long tmin = ~0ull, tmax = 0;
+        for (size_t i = 0; i < grid; ++i) if (h[i * 8 + 2]) {
+            pro += h[i * 8]; loop += h[i * 8 + 1]; tiles += h[i * 8 + 2]; ++n;
+            real += h[i * 8 + 4] - h[i * 8 + 3];
+            tmin = std::min(tmin, h[i * 8 + 3]); tmax = std::max(tmax, h[i * 8 + 4]);
+        }
+        fprintf(stderr, "DBGBUF wgs=%zu avg prologue ticks=%.0f loop ticks/tile=%.1f tiles/wg=%.1f | sum wg real(100MHz)=%.0f "
+                "ticks per real tick=%.2f span real=%llu (%.3f ms) busy frac=%.3f\n", n, pro / n,
+                loop / tiles, tiles / n, real, (pro + loop) / real, tmax - tmin, (tmax - tmin) / 1e5,
+                real / 256.0 / (tmax - tmin));
+        hipFree(dbuf);
+    }
     return hipGetLastError();
 }
 
@@ -288,7 +416,7 @@ hipError_t launch_prefill(const AttnArgs &a, int head_dim, int group, int kv_dty
                           int32_t total_q, int32_t max_q, hipStream_t s) {
     if (a.num_req == 0 || total_q == 0 || max_q == 0) return hipSuccess;
 #define GF_CASE(DD, GG) \
-    if (head_dim == DD && group == GG) return launch_prefill_t<DD, GG, 8, 1>(a, kv_dtype, q_ptr, total_q, max_q, s);
+    if (head_dim == DD && group == GG) return launch_prefill_t<DD, GG>(a, kv_dtype, q_ptr, total_q, max_q, s);
     GF_CASE(64, 1) GF_CASE(64, 2) GF_CASE(64, 4) GF_CASE(64, 8)
     GF_CASE(128, 1) GF_CASE(128, 2) GF_CASE(128, 4) GF_CASE(128, 8)
 #undef GF_CASE
