@@ -60,7 +60,7 @@ def load_library(path: Optional[str] = None):
     global _lib
     if _lib is not None and path is None:
         return _lib
-    p = path or LIB_PATH
+    p = path or os.environ.get("GRAPHFLOW_LIB") or LIB_PATH
     if not os.path.exists(p):
         raise FileNotFoundError(
             f"{p} is missing: build it with `python paper_2605_22566_amd/build.py` "

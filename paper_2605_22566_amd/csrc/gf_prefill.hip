@@ -20,8 +20,15 @@
 // the contraction group the V^T operand reads as one 16-byte LDS load from the
 // pool's [d][slot] V layout.  P never leaves registers.
 //
-// Pipeline.  KV tiles are 64 keys (4 table entries), double buffered in LDS
-// with K staged one tile ahead of V.  Inside a wave the scores run one tile
+// Staging.  KV tiles are 64 keys (4 table entries), double buffered in LDS with
+// K one tile ahead of V, and filled by 16-byte global->LDS direct loads (no
+// staging registers): lane l of a wave-wide load writes LDS bytes 16*l.. of a
+// 1 KB span, and picks its global source so that the LDS image is XOR-swizzled
+// (K: chunk position = chunk ^ row bits; V: the two 16-byte halves of a head-dim
+// row swap on every other group of 8 rows), which makes every 16-lane group of
+// an operand fetch hit 16 distinct 16-byte bank groups.
+//
+// Pipeline.  Inside a wave the scores run one tile
 // ahead of the softmax: iteration t issues, as one straight-line stream of 32
 // slots, the 16 score MFMAs of tile t+1 and the 16 P*V MFMAs of tile t, and in
 // the shadow of every MFMA a fixed share of the vector work (exponentials, row
@@ -39,47 +46,65 @@
 
 #include "gf_internal.h"
 
+#ifndef GF_ABL
+#define GF_ABL 0
+#endif
+
 namespace gf {
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
-template <int D, int G>
+template <int D, int G, int NW>
 struct PrefillCfg {
-    static constexpr int kWaves = 8;
+    static constexpr int kWaves = NW;
     static constexpr int kThreads = kWaves * 64;
     static constexpr int kRows = 32 * kWaves;        // score rows per workgroup
     static constexpr int kBM = kRows / G;            // new tokens per workgroup
     static constexpr int kBN = 64;                   // keys per KV tile
     static constexpr int kEntries = kBN / kBlock;    // table entries per tile (4)
-    static constexpr int kKStride = D * 2 + 16;      // padded K row in LDS (bytes)
-    static constexpr int kKTile = kBN * kKStride;
+    static constexpr int kRowBytes = D * 2;          // one K row
+    static constexpr int kCPR = D / 8;               // 16-byte chunks per K row
+    static constexpr int kKTile = kBN * kRowBytes;   // swizzled, unpadded
     static constexpr int kVBlk = D * kBlock * 2;     // one V block in LDS (bytes)
     static constexpr int kVTile = kEntries * kVBlk;
     static constexpr int kLds = 2 * kKTile + 2 * kVTile;
-    static constexpr int kChunks = kEntries * 2 * D; // 16-byte chunks per tensor per tile
-    static constexpr int kLoads = kChunks / kThreads;  // per thread per tensor
+    static constexpr int kDmaPerTile = kKTile / 1024;      // 1 KB wave-wide direct loads per tensor per tile
+    static constexpr int kDmaPerWave = kDmaPerTile / NW;
+    static constexpr int kDmaPerEntry = kDmaPerTile / kEntries;
     static constexpr int kKS = D / 16;               // contraction steps of the score MFMAs
     static constexpr int kDT = D / 32;               // 32-wide output tiles of P*V
     static constexpr int kQK = 2 * kKS;              // score MFMAs per tile
     static constexpr int kPV = kDT * kEntries;       // P*V MFMAs per tile
-    static_assert(kRows % G == 0 && kWaves % G == 0, "row tiles must split evenly over heads");
-    static_assert(kChunks % kThreads == 0, "staging must divide evenly");
-    static_assert((2 * D) % 64 == 0, "a wave must stay inside one block while staging");
+    static_assert(kRows % G == 0, "rows must split evenly over heads");
+    static_assert(kDmaPerTile % NW == 0 && kDmaPerWave >= 1, "staging must divide evenly over waves");
+    static_assert(kDmaPerEntry % kDmaPerWave == 0 || kDmaPerWave % kDmaPerEntry == 0, "a direct load stays in one block");
 };
 
 constexpr float kRescaleSlack = 8.0f;   // log2 units a row max may exceed its reference
 constexpr int kAhead = 4;               // LDS operand fragments in flight ahead of their MFMA
 
-template <int D, int G, bool FP8>
-__global__ __launch_bounds__(512) void prefill_kernel(AttnArgs a, const int32_t *__restrict__ tab_base,
-                                                      const int32_t *__restrict__ ntk_base,
-                                                      const int32_t *__restrict__ q_ptr, int q_tiles,
-                                                      int total_q, int dbg, unsigned long long *dbuf) {
-    using C = PrefillCfg<D, G>;
+typedef __attribute__((address_space(3))) void *lptr_t;
+
+// 16-byte-per-lane global -> LDS direct load: lane l writes LDS bytes [dst + 16 l, +16).
+// Issued through inline assembly so that it is ordered by hand: the kernel waits for its
+// own direct loads (dma_wait) right before the workgroup barrier that publishes a tile,
+// instead of before every LDS read that follows their issue.
+__device__ __forceinline__ void dma16(const void *src, void *lds_dst) {
+    const uint32_t dst = (uint32_t)(uintptr_t)(lptr_t)lds_dst;
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(src) : "memory", "m0");
+}
+__device__ __forceinline__ void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+template <int D, int G, int NW, bool FP8>
+__global__ __launch_bounds__(NW * 64, 2) void prefill_kernel(AttnArgs a, const int32_t *__restrict__ tab_base,
+                                                          const int32_t *__restrict__ ntk_base,
+                                                          const int32_t *__restrict__ q_ptr, int q_tiles,
+                                                          int total_q, int dbg, unsigned long long *dbuf) {
+    using C = PrefillCfg<D, G, NW>;
     const unsigned long long t_start = __builtin_readcyclecounter();
     const unsigned long long r_start = wall_clock64();
-    extern __shared__ __attribute__((aligned(16))) char lds[];
+    extern __shared__ __attribute__((aligned(1024))) char lds[];
     char *const kbuf = lds;                       // [2][kKTile]
     char *const vbuf = lds + 2 * C::kKTile;       // [2][kVTile]
 
@@ -116,10 +141,10 @@ __global__ __launch_bounds__(512) void prefill_kernel(AttnArgs a, const int32_t 
     const int32_t *__restrict__ ntk = ntk_base + (size_t)r * a.max_blocks;
 
     // ---- Q^T operand fragments (registers, whole kernel) ----------------------
+    // score row R = 32*wave + m of the workgroup is (token i0 + R/G, head R%G of the group)
     bf16x8 qf[C::kKS];
-    const int g = wave % G, tt = wave / G;
-    const int row_tok = i0 + 32 * tt + m;
-    const int row_head = kvh * G + g;
+    const int row_tok = i0 + (32 * wave + m) / G;
+    const int row_head = kvh * G + (32 * wave + m) % G;
     {
         const int tokc = min(row_tok, n_new - 1);
         const char *qp = (const char *)a.q + (((size_t)(q0 + tokc)) * a.hq + row_head) * (D * 2);
@@ -128,49 +153,73 @@ __global__ __launch_bounds__(512) void prefill_kernel(AttnArgs a, const int32_t 
             qf[ks] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(qp + (16 * ks + 8 * hh) * 2));
     }
 
-    // ---- staging: global -> registers -> LDS -------------------------------------
-    u32x4 kst[C::kLoads], vst[C::kLoads];
+    // ---- table window: lane l of every wave caches entry 64*w + l (block id, token count) of
+    // window w and of window w+1; the loop reads them with v_readlane (uniform index), so no
+    // memory load sits between a tile and its addresses.  Entries beyond e_end read as (0, 0).
+    int win = 0;
+    int id_cur, nt_cur, id_nxt, nt_nxt, id_new = 0, nt_new = 0;
+    auto load_window = [&](int w, int &id, int &nt) {
+        const int e = 64 * w + lane;
+        const bool ok = e < e_end;
+        id = ok ? tab[ok ? e : 0] : 0;      // clamped into the pool when the window is adopted
+        nt = ok ? ntk[ok ? e : 0] : 0;
+    };
+    load_window(0, id_cur, nt_cur);
+    load_window(1, id_nxt, nt_nxt);
+    id_cur = min(max(id_cur, 0), a.pool_blocks - 1);
+    id_nxt = min(max(id_nxt, 0), a.pool_blocks - 1);
+    auto entry_id = [&](int e) -> int {       // e uniform, within the two cached windows
+        const int a0 = __builtin_amdgcn_readlane(id_cur, e & 63), a1 = __builtin_amdgcn_readlane(id_nxt, e & 63);
+        return (e >> 6) == win ? a0 : a1;
+    };
+    auto entry_nt = [&](int e) -> int {
+        const int a0 = __builtin_amdgcn_readlane(nt_cur, e & 63), a1 = __builtin_amdgcn_readlane(nt_nxt, e & 63);
+        return (e >> 6) == win ? a0 : a1;
+    };
+
+    // ---- staging: global -> LDS direct loads -----------------------------------------
     const size_t blk_bytes = (size_t)kBlock * D * 2;
-    auto tile_offset = [&](int tile, int i) -> size_t {
-        const int u = tid + i * C::kThreads;
-        const int cb = __builtin_amdgcn_readfirstlane(u / (2 * D));   // entry within the tile
-        const int within = u % (2 * D);
-        const int ent = tile * C::kEntries + cb;
-        int bid = (ent < e_end) ? tab[ent] : 0;
-        bid = min(max(bid, 0), a.pool_blocks - 1);
-        return ((size_t)bid * a.hkv + kvh) * blk_bytes + (size_t)within * 16;
-    };
-    auto issue_k = [&](int tile) {
+    // K: lane l of direct load i lands at tile row 4i + l/CPR (D=128), chunk position l%CPR, and
+    // fetches the chunk (position ^ swizzle(row)) of that row
+    constexpr int kRPI = 1024 / C::kRowBytes;            // K rows per direct load
+    int k_src_off[C::kDmaPerWave], v_src_off[C::kDmaPerWave];
 #pragma unroll
-        for (int i = 0; i < C::kLoads; ++i) kst[i] = *(const u32x4 *)((const char *)a.k + tile_offset(tile, i));
-    };
-    auto issue_v = [&](int tile) {
+    for (int j = 0; j < C::kDmaPerWave; ++j) {
+        const int i = wave * C::kDmaPerWave + j;         // direct load index within the tile
+        const int rho = i * kRPI + lane / C::kCPR;       // tile row
+        const int pos = lane % C::kCPR;
+        const int sw = (C::kCPR == 16) ? (rho & 15) : ((rho >> 1) & 7);
+        k_src_off[j] = (rho % kBlock) * C::kRowBytes + ((pos ^ sw) * 16);
+        const int q = (i % C::kDmaPerEntry) * 64 + lane;  // 16-byte chunk within the V block image
+        const int d = q >> 1, vpos = q & 1;
+        v_src_off[j] = d * 32 + ((vpos ^ ((d >> 3) & 1)) * 16);
+    }
+    auto issue_k = [&](int tile, int buf) {
 #pragma unroll
-        for (int i = 0; i < C::kLoads; ++i) vst[i] = *(const u32x4 *)((const char *)a.v + tile_offset(tile, i));
-    };
-    auto store_k = [&](int buf) {
-#pragma unroll
-        for (int i = 0; i < C::kLoads; ++i) {
-            const int u = tid + i * C::kThreads;
-            const int cb = u / (2 * D), within = u % (2 * D);
-            const int slot = within / (D / 8), dch = within % (D / 8);
-            *(u32x4 *)(kbuf + buf * C::kKTile + (kBlock * cb + slot) * C::kKStride + dch * 16) = kst[i];
+        for (int j = 0; j < C::kDmaPerWave; ++j) {
+            const int i = wave * C::kDmaPerWave + j;
+            const int bid = entry_id(tile * C::kEntries + i / C::kDmaPerEntry);
+            const char *src = (const char *)a.k + ((size_t)bid * a.hkv + kvh) * blk_bytes + k_src_off[j];
+            dma16(src, kbuf + buf * C::kKTile + i * 1024);
         }
     };
-    auto store_v = [&](int buf) {
+    auto issue_v = [&](int tile, int buf) {
 #pragma unroll
-        for (int i = 0; i < C::kLoads; ++i) {
-            const int u = tid + i * C::kThreads;
-            const int cb = u / (2 * D), within = u % (2 * D);
-            const int d = within >> 1, hv = within & 1;
-            *(u32x4 *)(vbuf + buf * C::kVTile + cb * C::kVBlk + hv * (D * 16) + d * 16) = vst[i];
+        for (int j = 0; j < C::kDmaPerWave; ++j) {
+            const int i = wave * C::kDmaPerWave + j;
+            const int bid = entry_id(tile * C::kEntries + i / C::kDmaPerEntry);
+            const char *src = (const char *)a.v + ((size_t)bid * a.hkv + kvh) * blk_bytes + v_src_off[j];
+            dma16(src, vbuf + buf * C::kVTile + i * 1024);
         }
     };
 
-    // K operand row m reads key (m with bits 2,3 swapped)
+    // K operand row m reads key row (m with bits 2,3 swapped); chunk c of row rho sits at
+    // position c ^ swizzle(rho)
     const int krow = (m & 0x13) | ((m & 4) << 1) | ((m & 8) >> 1);
-    const int k_lane_off = krow * C::kKStride + 8 * hh * 2;
-    const int v_lane_off = hh * (D * 16) + m * 16;
+    const int k_sw = (C::kCPR == 16) ? (krow & 15) : ((krow >> 1) & 7);
+    const int k_row_off = krow * C::kRowBytes;
+    const int k_x = (hh ^ k_sw) * 16;        // chunk 2ks+hh -> position (2ks) ^ (hh ^ sw)
+    const int v_lane_off = m * 32 + ((hh ^ ((m >> 3) & 1)) * 16);
 
     // ---- running state --------------------------------------------------------------
     const float c = a.scale_log2;
@@ -195,7 +244,7 @@ __global__ __launch_bounds__(512) void prefill_kernel(AttnArgs a, const int32_t 
 #pragma unroll
         for (int cb = 0; cb < C::kEntries; ++cb) {
             const int ent = t * C::kEntries + cb;
-            const int nt = ent < e_end ? ntk[ent] : 0;
+            const int nt = entry_nt(ent);
             need |= (nt < kBlock) || (ent >= ncb && (ent - ncb) * kBlock + kBlock - 1 > i0);
         }
         return need;
@@ -204,7 +253,7 @@ __global__ __launch_bounds__(512) void prefill_kernel(AttnArgs a, const int32_t 
 #pragma unroll
         for (int cb = 0; cb < C::kEntries; ++cb) {
             const int ent = t * C::kEntries + cb;
-            const int nt = ent < e_end ? ntk[ent] : 0;
+            const int nt = entry_nt(ent);
             const int tail_base = ent >= ncb ? (ent - ncb) * kBlock : -(1 << 28);
             const int lim = min(nt, row_tok - tail_base + 1) - 8 * hh;
 #pragma unroll
@@ -214,29 +263,26 @@ __global__ __launch_bounds__(512) void prefill_kernel(AttnArgs a, const int32_t 
             }
         }
     };
+    auto k_frag = [&](const char *kb, int n) -> u32x4 {      // n = kt * kKS + ks
+        const int kt = n / C::kKS, ks = n % C::kKS;
+        return *(const u32x4 *)(kb + 32 * kt * C::kRowBytes + k_row_off + ((32 * ks) ^ k_x));
+    };
 
     // ---- prologue: K(0), V(0), K(1) into LDS; scores of tile 0 ---------------------------
-    issue_k(0);
-    issue_v(0);
-    store_k(0);
-    store_v(0);
-    if (ntiles > 1) {
-        issue_k(1);
-        store_k(1);
-    }
+    issue_k(0, 0);
+    issue_v(0, 0);
+    if (ntiles > 1) issue_k(1, 1);
+    dma_wait();
     __syncthreads();
     {
-        const char *kb = kbuf + k_lane_off;
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt) {
 #pragma unroll
             for (int x = 0; x < 16; ++x) s_a[kt][x] = 0.f;
 #pragma unroll
-            for (int ks = 0; ks < C::kKS; ++ks) {
-                const bf16x8 kf =
-                    __builtin_bit_cast(bf16x8, *(const u32x4 *)(kb + 32 * kt * C::kKStride + 16 * ks * 2));
-                s_a[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s_a[kt], 0, 0, 0);
-            }
+            for (int ks = 0; ks < C::kKS; ++ks)
+                s_a[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    __builtin_bit_cast(bf16x8, k_frag(kbuf, kt * C::kKS + ks)), qf[ks], s_a[kt], 0, 0, 0);
         }
         mx = row_max(s_a);
     }
@@ -245,9 +291,13 @@ __global__ __launch_bounds__(512) void prefill_kernel(AttnArgs a, const int32_t 
     auto body = [&](int t, f32x16 (&sc)[2], f32x16 (&sn)[2]) {
         const bool has_next = t + 1 < ntiles;
         const bool k2 = t + 2 < ntiles;
+        // the table window slides at the end of this iteration if the next tile opens a new one:
+        // fetch the window after next now, adopt it after the wait that precedes the barrier
+        const bool slide = (t + 1) * C::kEntries == 64 * (win + 1);
+        if (slide) load_window(win + 2, id_new, nt_new);
         if (!(dbg & 1)) {
-            if (k2) issue_k(t + 2);
-            if (has_next) issue_v(t + 1);
+            if (k2) issue_k(t + 2, t & 1);             // K(t+2) replaces K(t), read last iteration
+            if (has_next) issue_v(t + 1, (t + 1) & 1); // V(t+1) replaces V(t-1)
         }
         // side path: partial blocks / causal tail in tile t
         if (tile_needs_mask(t)) {
@@ -265,12 +315,12 @@ __global__ __launch_bounds__(512) void prefill_kernel(AttnArgs a, const int32_t 
         }
 
         // main stream: 32 slots of {MFMA, LDS fetch 4 ahead, vector share}
-        const char *kb = kbuf + ((t + 1) & 1) * C::kKTile + k_lane_off;
+        const char *kb = kbuf + ((t + 1) & 1) * C::kKTile;
         const char *vb = vbuf + (t & 1) * C::kVTile + v_lane_off;
         auto frag = [&](int n) -> u32x4 {      // unified operand stream: K fragments then V fragments
-            if (n < C::kQK) return *(const u32x4 *)(kb + 32 * (n / C::kKS) * C::kKStride + 16 * (n % C::kKS) * 2);
+            if (n < C::kQK) return k_frag(kb, n);
             const int j = n - C::kQK;
-            return *(const u32x4 *)(vb + (j / C::kDT) * C::kVBlk + 32 * (j % C::kDT) * 16);
+            return *(const u32x4 *)(vb + (j / C::kDT) * C::kVBlk + 32 * (j % C::kDT) * 32);
         };
         constexpr int NSLOT = C::kQK + C::kPV;
         constexpr int kExpPerSlot = 32 / C::kQK;     // exponentials in the shadow of one score MFMA
@@ -297,8 +347,8 @@ __global__ __launch_bounds__(512) void prefill_kernel(AttnArgs a, const int32_t 
                     const int idx = i * kExpPerSlot + e2;        // 0..31: score register pair
                     const int kt2 = idx / 16, x = idx % 16;
                     f32x2 p;
-                    p[0] = fast_exp2(sc[kt2][x] * c - m_ref);
-                    p[1] = fast_exp2(sc[kt2][x + 1] * c - m_ref);
+                    p[0] = (GF_ABL & 2) ? sc[kt2][x] : fast_exp2(sc[kt2][x] * c - m_ref);
+                    p[1] = (GF_ABL & 2) ? sc[kt2][x + 1] : fast_exp2(sc[kt2][x + 1] * c - m_ref);
                     psum += p[0] + p[1];
                     pw[idx / 8][(idx % 8) / 2] = __builtin_bit_cast(uint32_t, __builtin_convertvector(p, bf16x2));
                 }
@@ -316,16 +366,21 @@ __global__ __launch_bounds__(512) void prefill_kernel(AttnArgs a, const int32_t 
                     vmax = fmaxf(vmax, sn[idx / 16][idx % 16]);
                 }
             }
-            if (i + kAhead < NSLOT) f[i % kAhead] = frag(i + kAhead);
+            if (!(GF_ABL & 1) && i + kAhead < NSLOT) f[i % kAhead] = frag(i + kAhead);
             __builtin_amdgcn_sched_barrier(0);
         }
         l_run += psum;
         mx = fmaxf(vmax, other_half(vmax)) * c;
-        if (has_next && !(dbg & 1)) {
-            if (k2) store_k(t & 1);          // K(t+2) replaces K(t), whose scores were computed last iteration
-            store_v((t + 1) & 1);            // V(t+1) replaces V(t-1)
+        dma_wait();                              // this wave's direct loads have landed ...
+        asm volatile("" : "+v"(id_new), "+v"(nt_new));   // (the window fetch is waited for here, nowhere earlier)
+        if (slide) {
+            id_cur = id_nxt;
+            nt_cur = nt_nxt;
+            id_nxt = min(max(id_new, 0), a.pool_blocks - 1);
+            nt_nxt = nt_new;
+            ++win;
         }
-        __syncthreads();
+        if (!(GF_ABL & 4)) __syncthreads();      // ... and every wave's are visible
     };
 
     const unsigned long long t_loop0 = __builtin_readcyclecounter();
@@ -366,12 +421,12 @@ __global__ __launch_bounds__(512) void prefill_kernel(AttnArgs a, const int32_t 
     }
 }
 
-template <int D, int G>
+template <int D, int G, int NW>
 static hipError_t launch_prefill_t(const AttnArgs &a, int kv_dtype, const int32_t *q_ptr, int32_t total_q,
                                    int32_t max_q, hipStream_t s) {
-    using C = PrefillCfg<D, G>;
+    using C = PrefillCfg<D, G, NW>;
     if (kv_dtype != GF_BF16) return hipErrorNotSupported;
-    auto kern = prefill_kernel<D, G, false>;
+    auto kern = prefill_kernel<D, G, NW, false>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, C::kLds);
@@ -415,8 +470,11 @@ static hipError_t launch_prefill_t(const AttnArgs &a, int kv_dtype, const int32_
 hipError_t launch_prefill(const AttnArgs &a, int head_dim, int group, int kv_dtype, const int32_t *q_ptr,
                           int32_t total_q, int32_t max_q, hipStream_t s) {
     if (a.num_req == 0 || total_q == 0 || max_q == 0) return hipSuccess;
-#define GF_CASE(DD, GG) \
-    if (head_dim == DD && group == GG) return launch_prefill_t<DD, GG>(a, kv_dtype, q_ptr, total_q, max_q, s);
+    const int nw = getenv("GF_NW") ? atoi(getenv("GF_NW")) : 4;
+#define GF_CASE(DD, GG)                                                                                   \
+    if (head_dim == DD && group == GG)                                                                    \
+        return nw == 8 ? launch_prefill_t<DD, GG, 8>(a, kv_dtype, q_ptr, total_q, max_q, s)               \
+                       : launch_prefill_t<DD, GG, 4>(a, kv_dtype, q_ptr, total_q, max_q, s);
     GF_CASE(64, 1) GF_CASE(64, 2) GF_CASE(64, 4) GF_CASE(64, 8)
     GF_CASE(128, 1) GF_CASE(128, 2) GF_CASE(128, 4) GF_CASE(128, 8)
 #undef GF_CASE
