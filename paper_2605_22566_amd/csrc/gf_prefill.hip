@@ -39,16 +39,8 @@
 // same reference, so the result is unchanged.  Per-entry token counts mask
 // partial blocks anywhere in the sequence and tail entries causally, in a side
 // path taken only by tiles that need it.
-#include <algorithm>
-#include <cstdio>
-#include <cstdlib>
-#include <vector>
 
 #include "gf_internal.h"
-
-#ifndef GF_ABL
-#define GF_ABL 0
-#endif
 
 namespace gf {
 
@@ -100,10 +92,8 @@ template <int D, int G, int NW, bool FP8>
 __global__ __launch_bounds__(NW * 64, 2) void prefill_kernel(AttnArgs a, const int32_t *__restrict__ tab_base,
                                                           const int32_t *__restrict__ ntk_base,
                                                           const int32_t *__restrict__ q_ptr, int q_tiles,
-                                                          int total_q, int dbg, unsigned long long *dbuf) {
+                                                          int total_q) {
     using C = PrefillCfg<D, G, NW>;
-    const unsigned long long t_start = __builtin_readcyclecounter();
-    const unsigned long long r_start = wall_clock64();
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     char *const kbuf = lds;                       // [2][kKTile]
     char *const vbuf = lds + 2 * C::kKTile;       // [2][kVTile]
@@ -295,10 +285,8 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_kernel(AttnArgs a, const i
         // fetch the window after next now, adopt it after the wait that precedes the barrier
         const bool slide = (t + 1) * C::kEntries == 64 * (win + 1);
         if (slide) load_window(win + 2, id_new, nt_new);
-        if (!(dbg & 1)) {
-            if (k2) issue_k(t + 2, t & 1);             // K(t+2) replaces K(t), read last iteration
-            if (has_next) issue_v(t + 1, (t + 1) & 1); // V(t+1) replaces V(t-1)
-        }
+        if (k2) issue_k(t + 2, t & 1);             // K(t+2) replaces K(t), read last iteration
+        if (has_next) issue_v(t + 1, (t + 1) & 1); // V(t+1) replaces V(t-1)
         // side path: partial blocks / causal tail in tile t
         if (tile_needs_mask(t)) {
             apply_mask(t, sc);
@@ -347,11 +335,12 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_kernel(AttnArgs a, const i
                     const int idx = i * kExpPerSlot + e2;        // 0..31: score register pair
                     const int kt2 = idx / 16, x = idx % 16;
                     f32x2 p;
-                    p[0] = (GF_ABL & 2) ? sc[kt2][x] : fast_exp2(sc[kt2][x] * c - m_ref);
-                    p[1] = (GF_ABL & 2) ? sc[kt2][x + 1] : fast_exp2(sc[kt2][x + 1] * c - m_ref);
+                    p[0] = fast_exp2(sc[kt2][x] * c - m_ref);
+                    p[1] = fast_exp2(sc[kt2][x + 1] * c - m_ref);
                     psum += p[0] + p[1];
                     pw[idx / 8][(idx % 8) / 2] = __builtin_bit_cast(uint32_t, __builtin_convertvector(p, bf16x2));
                 }
+                asm volatile("" : "+v"(psum));      // keep the row-sum adds in this slot
             } else {
                 const int j = i - C::kQK;
                 const int cb = j / C::kDT, dt = j % C::kDT;
@@ -365,8 +354,9 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_kernel(AttnArgs a, const i
                     const int idx = j * kMaxPerSlot + e2;
                     vmax = fmaxf(vmax, sn[idx / 16][idx % 16]);
                 }
+                asm volatile("" : "+v"(vmax));      // keep the running maximum in this slot
             }
-            if (!(GF_ABL & 1) && i + kAhead < NSLOT) f[i % kAhead] = frag(i + kAhead);
+            if (i + kAhead < NSLOT) f[i % kAhead] = frag(i + kAhead);
             __builtin_amdgcn_sched_barrier(0);
         }
         l_run += psum;
@@ -380,25 +370,15 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_kernel(AttnArgs a, const i
             nt_nxt = nt_new;
             ++win;
         }
-        if (!(GF_ABL & 4)) __syncthreads();      // ... and every wave's are visible
+        __syncthreads();                             // ... and every wave's are visible
     };
 
-    const unsigned long long t_loop0 = __builtin_readcyclecounter();
     int t = 0;
     for (; t + 2 <= ntiles; t += 2) {
         body(t, s_a, s_b);
         body(t + 1, s_b, s_a);
     }
     if (t < ntiles) body(t, s_a, s_b);
-    const unsigned long long t_loop1 = __builtin_readcyclecounter();
-    if (dbuf && tid == 0) {
-        dbuf[blockIdx.x * 8 + 0] = t_loop0 - t_start;
-        dbuf[blockIdx.x * 8 + 1] = t_loop1 - t_loop0;
-        dbuf[blockIdx.x * 8 + 2] = ntiles;
-        dbuf[blockIdx.x * 8 + 3] = r_start;
-        dbuf[blockIdx.x * 8 + 4] = wall_clock64();
-    }
-
     // ---- epilogue: normalise, round to bf16, store ------------------------------------
     {
         const float l_tot = l_run + other_half(l_run);
@@ -438,43 +418,18 @@ static hipError_t launch_prefill_t(const AttnArgs &a, int kv_dtype, const int32_
     const size_t grid = pairs8 * q_tiles;
     if (grid == 0) return hipSuccess;
     if (grid > 0x7fffffffu) return hipErrorInvalidValue;
-    unsigned long long *dbuf = nullptr;
-    static int calls = 0;
-    const bool want = getenv("GF_DBGBUF") && (++calls == 5);
-    if (want) {
-        hipMalloc(&dbuf, grid * 64);
-        hipMemset(dbuf, 0, grid * 64);
-    }
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(C::kThreads), C::kLds, s, a, a.block_table, a.block_ntok,
-                       q_ptr, q_tiles, total_q, getenv("GF_DBG") ? atoi(getenv("GF_DBG")) : 0, dbuf);
-    if (want) {
-        hipDeviceSynchronize();
-        std::vector<unsigned long long> h(grid * 8);
-        hipMemcpy(h.data(), dbuf, grid * 64, hipMemcpyDeviceToHost);
-        double pro = 0, loop = 0, tiles = 0, real = 0; size_t n = 0;
-        unsigned long long tmin = ~0ull, tmax = 0;
-        for (size_t i = 0; i < grid; ++i) if (h[i * 8 + 2]) {
-            pro += h[i * 8]; loop += h[i * 8 + 1]; tiles += h[i * 8 + 2]; ++n;
-            real += h[i * 8 + 4] - h[i * 8 + 3];
-            tmin = std::min(tmin, h[i * 8 + 3]); tmax = std::max(tmax, h[i * 8 + 4]);
-        }
-        fprintf(stderr, "DBGBUF wgs=%zu avg prologue ticks=%.0f loop ticks/tile=%.1f tiles/wg=%.1f | sum wg real(100MHz)=%.0f "
-                "ticks per real tick=%.2f span real=%llu (%.3f ms) busy frac=%.3f\n", n, pro / n,
-                loop / tiles, tiles / n, real, (pro + loop) / real, tmax - tmin, (tmax - tmin) / 1e5,
-                real / 256.0 / (tmax - tmin));
-        hipFree(dbuf);
-    }
+                       q_ptr, q_tiles, total_q);
     return hipGetLastError();
 }
 
 hipError_t launch_prefill(const AttnArgs &a, int head_dim, int group, int kv_dtype, const int32_t *q_ptr,
                           int32_t total_q, int32_t max_q, hipStream_t s) {
     if (a.num_req == 0 || total_q == 0 || max_q == 0) return hipSuccess;
-    const int nw = getenv("GF_NW") ? atoi(getenv("GF_NW")) : 4;
-#define GF_CASE(DD, GG)                                                                                   \
-    if (head_dim == DD && group == GG)                                                                    \
-        return nw == 8 ? launch_prefill_t<DD, GG, 8>(a, kv_dtype, q_ptr, total_q, max_q, s)               \
-                       : launch_prefill_t<DD, GG, 4>(a, kv_dtype, q_ptr, total_q, max_q, s);
+    // 4-wave workgroups, two resident per CU: their barriers stay local to one wave per SIMD and
+    // the two workgroups drift apart, so one's vector phases fall under the other's MFMAs
+#define GF_CASE(DD, GG) \
+    if (head_dim == DD && group == GG) return launch_prefill_t<DD, GG, 4>(a, kv_dtype, q_ptr, total_q, max_q, s);
     GF_CASE(64, 1) GF_CASE(64, 2) GF_CASE(64, 4) GF_CASE(64, 8)
     GF_CASE(128, 1) GF_CASE(128, 2) GF_CASE(128, 4) GF_CASE(128, 8)
 #undef GF_CASE
