@@ -32,6 +32,14 @@ struct PairRegs {
     u32x4 v[D / 16];
     int n0, n1;   // valid tokens in the two blocks
 };
+template <int D>
+struct PairRegs<D, true> {
+    // e4m3 pool: 8-byte fragments (8 codes each) and this lane's K / V block scales
+    u32x2 k[2][D / 32];
+    u32x2 v[D / 16];
+    float ks, vs;
+    int n0, n1;
+};
 
 template <int D>
 __device__ __forceinline__ void load_pair(PairRegs<D, false> &p, const AttnArgs &a, const int32_t *tab,
@@ -65,6 +73,53 @@ __device__ __forceinline__ void load_pair(PairRegs<D, false> &p, const AttnArgs 
 #pragma unroll
     for (int dt = 0; dt < D / 16; ++dt)
         p.v[dt] = *(const u32x4 *)(vb + (size_t)(16 * dt + m) * (kBlock * 2) + (q4 & 1) * 16);
+}
+
+// e4m3 pool: same operand geometry with one byte per element; the scales of the lane's block
+// (K operand rows and score rows of lane group q4 belong to block q4/2) ride along.
+template <int D>
+__device__ __forceinline__ void load_pair(PairRegs<D, true> &p, const AttnArgs &a, const int32_t *tab,
+                                          const int32_t *ntk, int e, int e_end, int kvh, int lane) {
+    int b0 = tab[e];
+    p.n0 = ntk[e];
+    int b1 = b0;
+    p.n1 = 0;
+    if (e + 1 < e_end) {
+        b1 = tab[e + 1];
+        p.n1 = ntk[e + 1];
+    }
+    b0 = min(max(b0, 0), a.pool_blocks - 1);
+    b1 = min(max(b1, 0), a.pool_blocks - 1);
+    const size_t blk_bytes = (size_t)kBlock * D;
+    const char *k0 = (const char *)a.k + ((size_t)b0 * a.hkv + kvh) * blk_bytes;
+    const char *k1 = (const char *)a.k + ((size_t)b1 * a.hkv + kvh) * blk_bytes;
+    const char *v0 = (const char *)a.v + ((size_t)b0 * a.hkv + kvh) * blk_bytes;
+    const char *v1 = (const char *)a.v + ((size_t)b1 * a.hkv + kvh) * blk_bytes;
+    const int m = lane & 15, q4 = lane >> 4;
+    const char *kb = (m >= 8) ? k1 : k0;
+    const int slot0 = 8 * ((m >> 2) & 1) + (m & 3);
+#pragma unroll
+    for (int T = 0; T < 2; ++T)
+#pragma unroll
+        for (int t = 0; t < D / 32; ++t)
+            p.k[T][t] = *(const u32x2 *)(kb + (size_t)(slot0 + 4 * T) * D + (32 * t + 8 * q4));
+    const char *vb = (q4 >= 2) ? v1 : v0;
+#pragma unroll
+    for (int dt = 0; dt < D / 16; ++dt)
+        p.v[dt] = *(const u32x2 *)(vb + (size_t)(16 * dt + m) * kBlock + (q4 & 1) * 8);
+    p.ks = a.k_scale[(q4 >= 2) ? b1 : b0];
+    p.vs = a.v_scale[(q4 >= 2) ? b1 : b0];
+}
+
+template <int D, bool FP8>
+__device__ __forceinline__ bf16x8 k_operand(const PairRegs<D, FP8> &p, int T, int t) {
+    if constexpr (FP8) return fp8x8_to_bf16x8(p.k[T][t]);
+    else return __builtin_bit_cast(bf16x8, p.k[T][t]);
+}
+template <int D, bool FP8>
+__device__ __forceinline__ bf16x8 v_operand(const PairRegs<D, FP8> &p, int dt) {
+    if constexpr (FP8) return fp8x8_to_bf16x8(p.v[dt]);
+    else return __builtin_bit_cast(bf16x8, p.v[dt]);
 }
 
 template <int D, int G, bool FP8>
@@ -107,10 +162,10 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_split_kernel(AttnArgs a
     for (int dt = 0; dt < D / 16; ++dt) oacc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     PairRegs<D, FP8> cur, nxt;
-    load_pair<D>(cur, a, tab, ntk, e0, e1, kvh, lane);
+    load_pair(cur, a, tab, ntk, e0, e1, kvh, lane);
     for (int e = e0; e < e1; e += 2) {
         const bool more = e + 2 < e1;
-        if (more) load_pair<D>(nxt, a, tab, ntk, e + 2, e1, kvh, lane);
+        if (more) load_pair(nxt, a, tab, ntk, e + 2, e1, kvh, lane);
 
         f32x4 sT[2];
 #pragma unroll
@@ -118,8 +173,8 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_split_kernel(AttnArgs a
             sT[T] = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int t = 0; t < D / 32; ++t)
-                sT[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, cur.k[T][t]), qf[t],
-                                                                 sT[T], 0, 0, 0);
+                sT[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k_operand<D, FP8>(cur, T, t), qf[t], sT[T], 0, 0, 0);
+            if constexpr (FP8) sT[T] *= cur.ks;      // scores of this lane's keys, in the block's K scale
         }
         if (cur.n0 < kBlock || cur.n1 < kBlock) {
             const int lim = ((q4 >= 2) ? cur.n1 : cur.n0) - 8 * (q4 & 1);
@@ -148,12 +203,12 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_split_kernel(AttnArgs a
                 psum += e2;
             }
         l_run = l_run * alpha + psum;
+        if constexpr (FP8) p *= cur.vs;              // V scale of this lane's keys rides on P; the row sum does not
         const bf16x8 pb = __builtin_convertvector(p, bf16x8);
 #pragma unroll
         for (int dt = 0; dt < D / 16; ++dt) {
             oacc[dt] *= alpha;
-            oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, cur.v[dt]), pb,
-                                                                oacc[dt], 0, 0, 0);
+            oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v_operand<D, FP8>(cur, dt), pb, oacc[dt], 0, 0, 0);
         }
         if (more) cur = nxt;
     }
@@ -219,9 +274,12 @@ static hipError_t launch_decode_t(const AttnArgs &a, int kv_dtype, int32_t chunk
     float *part_o = (float *)workspace;
     float *part_ml = part_o + n_items * G * D;
     const unsigned grid = (unsigned)((n_items + kWavesPerWg - 1) / kWavesPerWg);
-    if (kv_dtype != GF_BF16) return hipErrorNotSupported;
-    hipLaunchKernelGGL((decode_split_kernel<D, G, false>), dim3(grid), dim3(kDecodeThreads), 0, s, a,
-                       chunk_blocks, splits, part_o, part_ml);
+    if (kv_dtype == GF_FP8_E4M3)
+        hipLaunchKernelGGL((decode_split_kernel<D, G, true>), dim3(grid), dim3(kDecodeThreads), 0, s, a,
+                           chunk_blocks, splits, part_o, part_ml);
+    else
+        hipLaunchKernelGGL((decode_split_kernel<D, G, false>), dim3(grid), dim3(kDecodeThreads), 0, s, a,
+                           chunk_blocks, splits, part_o, part_ml);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     const size_t rows = (size_t)a.num_req * a.hq;

@@ -48,6 +48,17 @@ hipError_t launch_decode(const AttnArgs &a, int head_dim, int group, int kv_dtyp
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+
+// 8 OCP e4m3 bytes (two dwords, element j in byte j) -> 8 bf16, exact (every e4m3 value is a bf16 value)
+__device__ __forceinline__ bf16x8 fp8x8_to_bf16x8(u32x2 w) {
+    const bf16x2 a = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[0], 1.0f, false);
+    const bf16x2 b = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[0], 1.0f, true);
+    const bf16x2 c = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[1], 1.0f, false);
+    const bf16x2 d = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[1], 1.0f, true);
+    return bf16x8{a[0], a[1], b[0], b[1], c[0], c[1], d[0], d[1]};
+}
+
 // value held by the lane 32 away (the other half of the wave)
 __device__ __forceinline__ float other_half(float x) { return __shfl_xor(x, 32, 64); }
 

@@ -44,10 +44,9 @@
 
 namespace gf {
 
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
-template <int D, int G, int NW>
+template <int D, int G, int NW, int ES>   // ES = bytes per pool element (2 bf16, 1 e4m3)
 struct PrefillCfg {
     static constexpr int kWaves = NW;
     static constexpr int kThreads = kWaves * 64;
@@ -55,10 +54,11 @@ struct PrefillCfg {
     static constexpr int kBM = kRows / G;            // new tokens per workgroup
     static constexpr int kBN = 64;                   // keys per KV tile
     static constexpr int kEntries = kBN / kBlock;    // table entries per tile (4)
-    static constexpr int kRowBytes = D * 2;          // one K row
-    static constexpr int kCPR = D / 8;               // 16-byte chunks per K row
+    static constexpr int kRowBytes = D * ES;         // one K row
+    static constexpr int kCPR = kRowBytes / 16;      // 16-byte chunks per K row
     static constexpr int kKTile = kBN * kRowBytes;   // swizzled, unpadded
-    static constexpr int kVBlk = D * kBlock * 2;     // one V block in LDS (bytes)
+    static constexpr int kVBlk = D * kBlock * ES;    // one V block in LDS (bytes)
+    static constexpr int kVRow = kBlock * ES;        // one head-dim row of a V block (bytes)
     static constexpr int kVTile = kEntries * kVBlk;
     static constexpr int kLds = 2 * kKTile + 2 * kVTile;
     static constexpr int kDmaPerTile = kKTile / 1024;      // 1 KB wave-wide direct loads per tensor per tile
@@ -91,9 +91,12 @@ __device__ __forceinline__ void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" :
 template <int D, int G, int NW, bool FP8>
 __global__ __launch_bounds__(NW * 64, 2) void prefill_kernel(AttnArgs a, const int32_t *__restrict__ tab_base,
                                                           const int32_t *__restrict__ ntk_base,
-                                                          const int32_t *__restrict__ q_ptr, int q_tiles,
+                                                          const int32_t *__restrict__ q_ptr,
+                                                          const float *__restrict__ k_scale,
+                                                          const float *__restrict__ v_scale, int q_tiles,
                                                           int total_q) {
-    using C = PrefillCfg<D, G, NW>;
+    constexpr int ES = FP8 ? 1 : 2;
+    using C = PrefillCfg<D, G, NW, ES>;
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     char *const kbuf = lds;                       // [2][kKTile]
     char *const vbuf = lds + 2 * C::kKTile;       // [2][kVTile]
@@ -147,42 +150,67 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_kernel(AttnArgs a, const i
     // window w and of window w+1; the loop reads them with v_readlane (uniform index), so no
     // memory load sits between a tile and its addresses.  Entries beyond e_end read as (0, 0).
     int win = 0;
-    int id_cur, nt_cur, id_nxt, nt_nxt, id_new = 0, nt_new = 0;
-    auto load_window = [&](int w, int &id, int &nt) {
+    // With an e4m3 pool the window also carries the entry's K scale, log2 of its V scale and
+    // the reciprocal of its V scale.
+    struct Win {
+        int id, nt;
+        float ks, lvs, ivs;
+    };
+    Win w_cur, w_nxt, w_new = {0, 0, 1.f, 0.f, 1.f};
+    auto load_window = [&](int w, Win &x) {
         const int e = 64 * w + lane;
         const bool ok = e < e_end;
-        id = ok ? tab[ok ? e : 0] : 0;      // clamped into the pool when the window is adopted
-        nt = ok ? ntk[ok ? e : 0] : 0;
+        int id = ok ? tab[ok ? e : 0] : 0;
+        x.nt = ok ? ntk[ok ? e : 0] : 0;
+        if constexpr (FP8) {
+            id = min(max(id, 0), a.pool_blocks - 1);
+            x.ks = k_scale[id];
+            const float vs = v_scale[id];
+            x.lvs = __builtin_log2f(vs);
+            x.ivs = 1.0f / vs;
+        }
+        x.id = id;                           // (bf16 pool: clamped into the pool when the window is adopted)
     };
-    load_window(0, id_cur, nt_cur);
-    load_window(1, id_nxt, nt_nxt);
-    id_cur = min(max(id_cur, 0), a.pool_blocks - 1);
-    id_nxt = min(max(id_nxt, 0), a.pool_blocks - 1);
+    load_window(0, w_cur);
+    load_window(1, w_nxt);
+    w_cur.id = min(max(w_cur.id, 0), a.pool_blocks - 1);
+    w_nxt.id = min(max(w_nxt.id, 0), a.pool_blocks - 1);
     auto entry_id = [&](int e) -> int {       // e uniform, within the two cached windows
-        const int a0 = __builtin_amdgcn_readlane(id_cur, e & 63), a1 = __builtin_amdgcn_readlane(id_nxt, e & 63);
+        const int a0 = __builtin_amdgcn_readlane(w_cur.id, e & 63), a1 = __builtin_amdgcn_readlane(w_nxt.id, e & 63);
         return (e >> 6) == win ? a0 : a1;
     };
     auto entry_nt = [&](int e) -> int {
-        const int a0 = __builtin_amdgcn_readlane(nt_cur, e & 63), a1 = __builtin_amdgcn_readlane(nt_nxt, e & 63);
+        const int a0 = __builtin_amdgcn_readlane(w_cur.nt, e & 63), a1 = __builtin_amdgcn_readlane(w_nxt.nt, e & 63);
         return (e >> 6) == win ? a0 : a1;
+    };
+    auto entry_f = [&](float Win::*f, int e) -> float {
+        const int a0 = __builtin_amdgcn_readlane(__float_as_int(w_cur.*f), e & 63);
+        const int a1 = __builtin_amdgcn_readlane(__float_as_int(w_nxt.*f), e & 63);
+        return __int_as_float((e >> 6) == win ? a0 : a1);
     };
 
     // ---- staging: global -> LDS direct loads -----------------------------------------
-    const size_t blk_bytes = (size_t)kBlock * D * 2;
+    const size_t blk_bytes = (size_t)kBlock * D * ES;
     // K: lane l of direct load i lands at tile row 4i + l/CPR (D=128), chunk position l%CPR, and
     // fetches the chunk (position ^ swizzle(row)) of that row
     constexpr int kRPI = 1024 / C::kRowBytes;            // K rows per direct load
+    auto k_swizzle = [](int rho) -> int {
+        return C::kCPR == 16 ? (rho & 15) : C::kCPR == 8 ? ((rho >> 1) & 7) : ((rho >> 2) & 3);
+    };
     int k_src_off[C::kDmaPerWave], v_src_off[C::kDmaPerWave];
 #pragma unroll
     for (int j = 0; j < C::kDmaPerWave; ++j) {
         const int i = wave * C::kDmaPerWave + j;         // direct load index within the tile
         const int rho = i * kRPI + lane / C::kCPR;       // tile row
         const int pos = lane % C::kCPR;
-        const int sw = (C::kCPR == 16) ? (rho & 15) : ((rho >> 1) & 7);
-        k_src_off[j] = (rho % kBlock) * C::kRowBytes + ((pos ^ sw) * 16);
+        k_src_off[j] = (rho % kBlock) * C::kRowBytes + ((pos ^ k_swizzle(rho)) * 16);
         const int q = (i % C::kDmaPerEntry) * 64 + lane;  // 16-byte chunk within the V block image
-        const int d = q >> 1, vpos = q & 1;
-        v_src_off[j] = d * 32 + ((vpos ^ ((d >> 3) & 1)) * 16);
+        if constexpr (FP8) {
+            v_src_off[j] = q * 16;                        // one chunk per head-dim row: image = pool block
+        } else {
+            const int d = q >> 1, vpos = q & 1;
+            v_src_off[j] = d * 32 + ((vpos ^ ((d >> 3) & 1)) * 16);
+        }
     }
     auto issue_k = [&](int tile, int buf) {
 #pragma unroll
@@ -206,10 +234,17 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_kernel(AttnArgs a, const i
     // K operand row m reads key row (m with bits 2,3 swapped); chunk c of row rho sits at
     // position c ^ swizzle(rho)
     const int krow = (m & 0x13) | ((m & 4) << 1) | ((m & 8) >> 1);
-    const int k_sw = (C::kCPR == 16) ? (krow & 15) : ((krow >> 1) & 7);
-    const int k_row_off = krow * C::kRowBytes;
-    const int k_x = (hh ^ k_sw) * 16;        // chunk 2ks+hh -> position (2ks) ^ (hh ^ sw)
-    const int v_lane_off = m * 32 + ((hh ^ ((m >> 3) & 1)) * 16);
+    // bf16: contraction step ks of half hh is chunk 2ks+hh, at position (2ks) ^ (hh ^ swizzle);
+    // e4m3: it is the half hh of chunk ks, at position ks ^ swizzle
+    const int k_sw = k_swizzle(krow);
+    const int k_row_off = krow * C::kRowBytes + (FP8 ? 8 * hh : 0);
+    const int k_x = FP8 ? k_sw * 16 : (hh ^ k_sw) * 16;
+    const int v_lane_off = FP8 ? m * 16 + 8 * hh : m * 32 + ((hh ^ ((m >> 3) & 1)) * 16);
+    using frag_t = std::conditional_t<FP8, u32x2, u32x4>;
+    auto to_operand = [](frag_t f) -> bf16x8 {
+        if constexpr (FP8) return fp8x8_to_bf16x8(f);
+        else return __builtin_bit_cast(bf16x8, f);
+    };
 
     // ---- running state --------------------------------------------------------------
     const float c = a.scale_log2;
@@ -222,11 +257,40 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_kernel(AttnArgs a, const i
         for (int i = 0; i < 16; ++i) o[dt][i] = 0.f;
     f32x16 s_a[2], s_b[2];            // score tiles, ping-pong (2 x 32 keys each)
 
-    auto row_max = [&](const f32x16 (&s)[2]) -> float {
-        float v = fmaxf(s[0][0], s[1][0]);
+    // Per-chunk exponent constants of tile t.  A raw score of chunk cb becomes
+    //   2^(s * mult[cb] + addc[cb]),  mult = sm_scale*log2(e) [* K scale],  addc = -m_ref [+ log2(V scale)]
+    // (the V scale rides on P so that P*V needs no further scaling; the row sum divides it out again).
+    struct TileScale {
+        float mult[C::kEntries], lvs[C::kEntries], ivs[C::kEntries];
+    };
+    auto tile_scale = [&](int t) -> TileScale {
+        TileScale ts;
 #pragma unroll
-        for (int i = 1; i < 16; ++i) v = fmaxf(v, fmaxf(s[0][i], s[1][i]));
-        return fmaxf(v, other_half(v)) * c;
+        for (int cb = 0; cb < C::kEntries; ++cb) {
+            if constexpr (FP8) {
+                const int ent = t * C::kEntries + cb;
+                ts.mult[cb] = c * entry_f(&Win::ks, ent);
+                ts.lvs[cb] = entry_f(&Win::lvs, ent);
+                ts.ivs[cb] = entry_f(&Win::ivs, ent);
+            } else {
+                ts.mult[cb] = c;
+                ts.lvs[cb] = 0.f;
+                ts.ivs[cb] = 1.f;
+            }
+        }
+        return ts;
+    };
+    // row maximum of a score tile in log2 units (identical in both lanes of a row)
+    auto row_max = [&](const f32x16 (&s)[2], const TileScale &ts) -> float {
+        float best = -INFINITY;
+#pragma unroll
+        for (int cb = 0; cb < C::kEntries; ++cb) {
+            float v = s[cb >> 1][8 * (cb & 1)];
+#pragma unroll
+            for (int j = 1; j < 8; ++j) v = fmaxf(v, s[cb >> 1][8 * (cb & 1) + j]);
+            best = fmaxf(best, v * ts.mult[cb]);
+        }
+        return fmaxf(best, other_half(best));
     };
     // uniform: does tile t hold a partial block or a causally cut tail entry?
     auto tile_needs_mask = [&](int t) -> bool {
@@ -253,9 +317,9 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_kernel(AttnArgs a, const i
             }
         }
     };
-    auto k_frag = [&](const char *kb, int n) -> u32x4 {      // n = kt * kKS + ks
+    auto k_frag = [&](const char *kb, int n) -> frag_t {     // n = kt * kKS + ks
         const int kt = n / C::kKS, ks = n % C::kKS;
-        return *(const u32x4 *)(kb + 32 * kt * C::kRowBytes + k_row_off + ((32 * ks) ^ k_x));
+        return *(const frag_t *)(kb + 32 * kt * C::kRowBytes + k_row_off + (((FP8 ? 16 : 32) * ks) ^ k_x));
     };
 
     // ---- prologue: K(0), V(0), K(1) into LDS; scores of tile 0 ---------------------------
@@ -271,10 +335,10 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_kernel(AttnArgs a, const i
             for (int x = 0; x < 16; ++x) s_a[kt][x] = 0.f;
 #pragma unroll
             for (int ks = 0; ks < C::kKS; ++ks)
-                s_a[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                    __builtin_bit_cast(bf16x8, k_frag(kbuf, kt * C::kKS + ks)), qf[ks], s_a[kt], 0, 0, 0);
+                s_a[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(to_operand(k_frag(kbuf, kt * C::kKS + ks)), qf[ks],
+                                                                   s_a[kt], 0, 0, 0);
         }
-        mx = row_max(s_a);
+        mx = row_max(s_a, tile_scale(0));
     }
 
     // ---- one iteration: softmax + P*V of tile t (scores in sc), scores of tile t+1 -> sn ----
@@ -284,13 +348,15 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_kernel(AttnArgs a, const i
         // the table window slides at the end of this iteration if the next tile opens a new one:
         // fetch the window after next now, adopt it after the wait that precedes the barrier
         const bool slide = (t + 1) * C::kEntries == 64 * (win + 1);
-        if (slide) load_window(win + 2, id_new, nt_new);
+        if (slide) load_window(win + 2, w_new);
+        const TileScale ts = tile_scale(t);          // constants of this tile ...
+        const TileScale tn = tile_scale(t + 1);      // ... and of the next (for its row maximum)
         if (k2) issue_k(t + 2, t & 1);             // K(t+2) replaces K(t), read last iteration
         if (has_next) issue_v(t + 1, (t + 1) & 1); // V(t+1) replaces V(t-1)
         // side path: partial blocks / causal tail in tile t
         if (tile_needs_mask(t)) {
             apply_mask(t, sc);
-            mx = row_max(sc);
+            mx = row_max(sc, ts);
         }
         // refresh the reference maximum only when some row outgrew it
         if (__builtin_amdgcn_ballot_w64(mx > m_ref + kRescaleSlack) != 0) {
@@ -305,19 +371,24 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_kernel(AttnArgs a, const i
         // main stream: 32 slots of {MFMA, LDS fetch 4 ahead, vector share}
         const char *kb = kbuf + ((t + 1) & 1) * C::kKTile;
         const char *vb = vbuf + (t & 1) * C::kVTile + v_lane_off;
-        auto frag = [&](int n) -> u32x4 {      // unified operand stream: K fragments then V fragments
+        auto frag = [&](int n) -> frag_t {     // unified operand stream: K fragments then V fragments
             if (n < C::kQK) return k_frag(kb, n);
             const int j = n - C::kQK;
-            return *(const u32x4 *)(vb + (j / C::kDT) * C::kVBlk + 32 * (j % C::kDT) * 32);
+            return *(const frag_t *)(vb + (j / C::kDT) * C::kVBlk + 32 * (j % C::kDT) * C::kVRow);
         };
         constexpr int NSLOT = C::kQK + C::kPV;
         constexpr int kExpPerSlot = 32 / C::kQK;     // exponentials in the shadow of one score MFMA
-        u32x4 f[kAhead];
+        frag_t f[kAhead];
 #pragma unroll
         for (int i = 0; i < kAhead; ++i) f[i] = frag(i);
         uint32_t pw[C::kEntries][4];                 // P^T operand, 2 bf16 per word
-        float psum = 0.f;
-        float vmax = -INFINITY;
+        float addc[C::kEntries], psum[C::kEntries], vmax[C::kEntries];
+#pragma unroll
+        for (int cb = 0; cb < C::kEntries; ++cb) {
+            addc[cb] = ts.lvs[cb] - m_ref;
+            psum[cb] = 0.f;
+            vmax[cb] = -INFINITY;
+        }
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int i = 0; i < NSLOT; ++i) {
@@ -327,47 +398,54 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_kernel(AttnArgs a, const i
 #pragma unroll
                     for (int x = 0; x < 16; ++x) sn[kt][x] = 0.f;
                 }
-                sn[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f[i % kAhead]), qf[ks],
-                                                                  sn[kt], 0, 0, 0);
+                sn[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(to_operand(f[i % kAhead]), qf[ks], sn[kt], 0, 0, 0);
                 // vector share: exponentials of tile t, kExpPerSlot per slot
 #pragma unroll
                 for (int e2 = 0; e2 < kExpPerSlot; e2 += 2) {
                     const int idx = i * kExpPerSlot + e2;        // 0..31: score register pair
                     const int kt2 = idx / 16, x = idx % 16;
+                    const int cb = idx / 8;                      // 16-key chunk = table entry
                     f32x2 p;
-                    p[0] = fast_exp2(sc[kt2][x] * c - m_ref);
-                    p[1] = fast_exp2(sc[kt2][x + 1] * c - m_ref);
-                    psum += p[0] + p[1];
-                    pw[idx / 8][(idx % 8) / 2] = __builtin_bit_cast(uint32_t, __builtin_convertvector(p, bf16x2));
+                    p[0] = fast_exp2(sc[kt2][x] * ts.mult[cb] + addc[cb]);
+                    p[1] = fast_exp2(sc[kt2][x + 1] * ts.mult[cb] + addc[cb]);
+                    psum[cb] += p[0] + p[1];
+                    pw[cb][(idx % 8) / 2] = __builtin_bit_cast(uint32_t, __builtin_convertvector(p, bf16x2));
+                    asm volatile("" : "+v"(psum[cb]));           // keep the row-sum adds in this slot
                 }
-                asm volatile("" : "+v"(psum));      // keep the row-sum adds in this slot
             } else {
                 const int j = i - C::kQK;
                 const int cb = j / C::kDT, dt = j % C::kDT;
                 u32x4 pq = {pw[cb][0], pw[cb][1], pw[cb][2], pw[cb][3]};
-                o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, f[i % kAhead]),
+                o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(to_operand(f[i % kAhead]),
                                                                 __builtin_bit_cast(bf16x8, pq), o[dt], 0, 0, 0);
                 // vector share: running maximum of the next tile's scores
                 constexpr int kMaxPerSlot = 32 / C::kPV;
 #pragma unroll
                 for (int e2 = 0; e2 < kMaxPerSlot; ++e2) {
                     const int idx = j * kMaxPerSlot + e2;
-                    vmax = fmaxf(vmax, sn[idx / 16][idx % 16]);
+                    vmax[idx / 8] = fmaxf(vmax[idx / 8], sn[idx / 16][idx % 16]);
+                    asm volatile("" : "+v"(vmax[idx / 8]));      // keep the running maximum in this slot
                 }
-                asm volatile("" : "+v"(vmax));      // keep the running maximum in this slot
             }
             if (i + kAhead < NSLOT) f[i % kAhead] = frag(i + kAhead);
             __builtin_amdgcn_sched_barrier(0);
         }
-        l_run += psum;
-        mx = fmaxf(vmax, other_half(vmax)) * c;
+        {
+            float best = -INFINITY;
+#pragma unroll
+            for (int cb = 0; cb < C::kEntries; ++cb) {
+                l_run += psum[cb] * ts.ivs[cb];
+                best = fmaxf(best, vmax[cb] * tn.mult[cb]);
+            }
+            mx = fmaxf(best, other_half(best));
+        }
         dma_wait();                              // this wave's direct loads have landed ...
-        asm volatile("" : "+v"(id_new), "+v"(nt_new));   // (the window fetch is waited for here, nowhere earlier)
+        // (the window fetch is waited for here, nowhere earlier)
+        asm volatile("" : "+v"(w_new.id), "+v"(w_new.nt), "+v"(w_new.ks), "+v"(w_new.lvs), "+v"(w_new.ivs));
         if (slide) {
-            id_cur = id_nxt;
-            nt_cur = nt_nxt;
-            id_nxt = min(max(id_new, 0), a.pool_blocks - 1);
-            nt_nxt = nt_new;
+            w_cur = w_nxt;
+            w_nxt = w_new;
+            w_nxt.id = min(max(w_nxt.id, 0), a.pool_blocks - 1);
             ++win;
         }
         __syncthreads();                             // ... and every wave's are visible
@@ -401,12 +479,22 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_kernel(AttnArgs a, const i
     }
 }
 
+template <int D, int G, int NW, bool FP8>
+static hipError_t launch_prefill_k(const AttnArgs &a, const int32_t *q_ptr, int32_t total_q, int32_t max_q,
+                                   hipStream_t s);
+
 template <int D, int G, int NW>
 static hipError_t launch_prefill_t(const AttnArgs &a, int kv_dtype, const int32_t *q_ptr, int32_t total_q,
                                    int32_t max_q, hipStream_t s) {
-    using C = PrefillCfg<D, G, NW>;
-    if (kv_dtype != GF_BF16) return hipErrorNotSupported;
-    auto kern = prefill_kernel<D, G, NW, false>;
+    if (kv_dtype == GF_FP8_E4M3) return launch_prefill_k<D, G, NW, true>(a, q_ptr, total_q, max_q, s);
+    return launch_prefill_k<D, G, NW, false>(a, q_ptr, total_q, max_q, s);
+}
+
+template <int D, int G, int NW, bool FP8>
+static hipError_t launch_prefill_k(const AttnArgs &a, const int32_t *q_ptr, int32_t total_q, int32_t max_q,
+                                   hipStream_t s) {
+    using C = PrefillCfg<D, G, NW, FP8 ? 1 : 2>;
+    auto kern = prefill_kernel<D, G, NW, FP8>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, C::kLds);
@@ -419,7 +507,7 @@ static hipError_t launch_prefill_t(const AttnArgs &a, int kv_dtype, const int32_
     if (grid == 0) return hipSuccess;
     if (grid > 0x7fffffffu) return hipErrorInvalidValue;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(C::kThreads), C::kLds, s, a, a.block_table, a.block_ntok,
-                       q_ptr, q_tiles, total_q);
+                       q_ptr, a.k_scale, a.v_scale, q_tiles, total_q);
     return hipGetLastError();
 }
 

@@ -11,7 +11,12 @@ from tests.gpu_common import (assert_close, oracle_decode, oracle_prefill, run_d
 
 pytestmark = pytest.mark.gpu
 
-SHAPES = [W.Shape(4, 4, 64), W.Shape(8, 2, 64), W.Shape(32, 8, 128), W.Shape(16, 2, 128), W.Shape(4, 2, 128)]
+SHAPES = [W.Shape(4, 4, 64), W.Shape(8, 2, 64), W.Shape(32, 8, 128), W.Shape(16, 2, 128), W.Shape(4, 2, 128),
+          W.Shape(32, 8, 128, W.KV_FP8_E4M3), W.Shape(8, 1, 128, W.KV_FP8_E4M3), W.Shape(8, 2, 64, W.KV_FP8_E4M3)]
+
+
+def _sid(s):
+    return f"hq{s.num_q_heads}kv{s.num_kv_heads}d{s.head_dim}" + ("fp8" if s.kv_dtype == W.KV_FP8_E4M3 else "")
 
 
 def test_tiny_config_prefill_and_decode():
@@ -27,11 +32,11 @@ def test_tiny_config_prefill_and_decode():
     assert np.abs(lsed - LSEd).max() < 1e-2
 
 
-@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: f"hq{s.num_q_heads}kv{s.num_kv_heads}d{s.head_dim}")
+@pytest.mark.parametrize("shape", SHAPES, ids=_sid)
 def test_prefill_ragged_small(shape):
     """Ragged node segments (partial blocks mid-sequence), several KV tiles, q
     tiles with a ragged tail, shuffled pool, N(0,100) garbage in pad slots."""
-    wl = W.small_layered(100 + shape.num_q_heads + shape.head_dim, shape, num_nodes=30, num_layers=6, len_lo=3,
+    wl = W.small_layered(100 + shape.num_q_heads + shape.head_dim + shape.kv_dtype, shape, num_nodes=30, num_layers=6, len_lo=3,
                          len_hi=150, num_req=5, hops=(1, 6), new_lo=1, new_hi=150)
     t = W.make_tensors(wl)
     o, lse, _, _ = run_prefill(wl, t)
@@ -41,10 +46,10 @@ def test_prefill_ragged_small(shape):
     assert np.abs(lse - LSE).max() < 1e-2
 
 
-@pytest.mark.parametrize("shape", SHAPES, ids=lambda s: f"hq{s.num_q_heads}kv{s.num_kv_heads}d{s.head_dim}")
+@pytest.mark.parametrize("shape", SHAPES, ids=_sid)
 @pytest.mark.parametrize("chunk", [0, 2, 6])
 def test_decode_ragged_small(shape, chunk):
-    wl = W.small_layered(200 + shape.num_q_heads + shape.head_dim, shape, num_nodes=30, num_layers=6, len_lo=3,
+    wl = W.small_layered(200 + shape.num_q_heads + shape.head_dim + shape.kv_dtype, shape, num_nodes=30, num_layers=6, len_lo=3,
                          len_hi=150, num_req=7, hops=(1, 6), new_lo=1, new_hi=40)
     t = W.make_tensors(wl)
     od, lsed, _, _, last = run_decode(wl, t, chunk_blocks=chunk)
@@ -124,3 +129,22 @@ def test_failed_requests_are_skipped():
     assert_close(o[keep], O[keep], sh.kv_dtype, "prefill others")
     od, lsed, _, _, last = run_decode(wl, t)
     assert (od[1] == 0).all() and np.isneginf(lsed[1]).all()
+
+
+def test_fp8_block_scales_differ_widely():
+    """e4m3 pool whose blocks have very different magnitudes (scales spread over 2^6): the per-block
+    K and V scales must be applied per 16-key chunk."""
+    sh = W.Shape(8, 2, 128, W.KV_FP8_E4M3)
+    wl = W.small_layered(901, sh, num_nodes=20, num_layers=5, len_lo=10, len_hi=120, num_req=4, hops=(2, 5),
+                         new_lo=3, new_hi=70)
+    t = W.make_tensors(wl)
+    rng = np.random.default_rng(4)
+    f = (2.0 ** rng.integers(-3, 4, size=t.k_scale.shape[0])).astype(np.float32)
+    t.k_scale *= f
+    t.v_scale *= f[::-1].copy()
+    o, lse, _, _ = run_prefill(wl, t)
+    O, LSE = oracle_prefill(wl, t)
+    assert_close(o, O, sh.kv_dtype, "fp8 prefill, spread scales")
+    od, _, _, _, last = run_decode(wl, t)
+    Od, _ = oracle_decode(wl, t, last)
+    assert_close(od, Od, sh.kv_dtype, "fp8 decode, spread scales")
