@@ -9,8 +9,10 @@
 
 struct gf_ctx {
     int device = 0;
-    void *workspace = nullptr;
+    void *workspace = nullptr;       // decode: split-KV partials
     size_t workspace_bytes = 0;
+    void *plan = nullptr;            // prefill: work list
+    size_t plan_bytes = 0;
     int32_t decode_chunk_blocks = 0;   // 0 = built-in choice
     char hip_err[256] = {0};
 };
@@ -65,6 +67,28 @@ int32_t check_attn(const gf_attn_params *p, const gf_kv_pool *pool, const gf_tab
     return GF_OK;
 }
 
+// Make a context-owned device buffer at least `need` bytes.  Growing frees the old buffer, which
+// kernels already enqueued may still use: the stream is synchronised first.
+int32_t ensure_buffer(gf_ctx *ctx, void **buf, size_t *have, size_t need, hipStream_t stream, const char *what) {
+    if (need <= *have) return GF_OK;
+    hipError_t e = hipStreamSynchronize(stream);
+    if (e != hipSuccess) return fail_hip(ctx, e, what);
+    if (*buf) {
+        e = hipFree(*buf);
+        *buf = nullptr;
+        *have = 0;
+        if (e != hipSuccess) return fail_hip(ctx, e, what);
+    }
+    e = hipMalloc(buf, need);
+    if (e != hipSuccess) {
+        *buf = nullptr;
+        fail_hip(ctx, e, what);
+        return GF_ERR_WORKSPACE;
+    }
+    *have = need;
+    return GF_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -89,6 +113,7 @@ int32_t gf_destroy(gf_ctx *ctx) {
     if (!ctx) return GF_ERR_NULL;
     int32_t rc = GF_OK;
     if (ctx->workspace && hipFree(ctx->workspace) != hipSuccess) rc = GF_ERR_HIP;
+    if (ctx->plan && hipFree(ctx->plan) != hipSuccess) rc = GF_ERR_HIP;
     delete ctx;
     return rc;
 }
@@ -150,8 +175,11 @@ int32_t gf_attn_prefill(gf_ctx *ctx, const gf_attn_params *params, const gf_kv_p
     if (rc != GF_OK) return rc;
     if (tables->num_req == 0 || total_q == 0) return GF_OK;
     if (!q_ptr) return GF_ERR_NULL;
-    hipError_t e = gf::launch_prefill(a, params->head_dim, group, params->kv_dtype, q_ptr, total_q, max_q,
-                                      (hipStream_t)stream);
+    rc = ensure_buffer(ctx, &ctx->plan, &ctx->plan_bytes, gf::prefill_plan_bytes(total_q, a.num_req, group),
+                       (hipStream_t)stream, "gf_attn_prefill work-list buffer");
+    if (rc != GF_OK) return rc;
+    hipError_t e = gf::launch_prefill(a, params->head_dim, group, params->kv_dtype, q_ptr, total_q,
+                                      (int32_t *)ctx->plan, (hipStream_t)stream);
     if (e == hipErrorNotSupported) return GF_ERR_UNSUPPORTED;
     if (e != hipSuccess) return fail_hip(ctx, e, "gf_attn_prefill launch");
     return GF_OK;
@@ -171,24 +199,9 @@ int32_t gf_attn_decode(gf_ctx *ctx, const gf_attn_params *params, const gf_kv_po
     if (chunk <= 0) chunk = 32;
     const int32_t splits = (tables->max_blocks + chunk - 1) / chunk;
     const size_t need = gf::decode_workspace_bytes(a.num_req, a.hkv, group, params->head_dim, splits);
-    if (need > ctx->workspace_bytes) {
-        // growing the workspace: the old buffer may still be in use on the stream
-        hipError_t e = hipStreamSynchronize((hipStream_t)stream);
-        if (e != hipSuccess) return fail_hip(ctx, e, "gf_attn_decode sync before workspace growth");
-        if (ctx->workspace) {
-            e = hipFree(ctx->workspace);
-            ctx->workspace = nullptr;
-            ctx->workspace_bytes = 0;
-            if (e != hipSuccess) return fail_hip(ctx, e, "gf_attn_decode workspace free");
-        }
-        e = hipMalloc(&ctx->workspace, need);
-        if (e != hipSuccess) {
-            ctx->workspace = nullptr;
-            fail_hip(ctx, e, "gf_attn_decode workspace alloc");
-            return GF_ERR_WORKSPACE;
-        }
-        ctx->workspace_bytes = need;
-    }
+    rc = ensure_buffer(ctx, &ctx->workspace, &ctx->workspace_bytes, need, (hipStream_t)stream,
+                       "gf_attn_decode workspace");
+    if (rc != GF_OK) return rc;
     hipError_t e = gf::launch_decode(a, params->head_dim, group, params->kv_dtype, chunk, splits,
                                      ctx->workspace, (hipStream_t)stream);
     if (e == hipErrorNotSupported) return GF_ERR_UNSUPPORTED;

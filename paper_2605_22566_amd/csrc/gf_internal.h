@@ -38,8 +38,10 @@ hipError_t launch_resolve(const gf_graph &g, int32_t num_req, const int32_t *pat
                           int32_t *block_table, int32_t *block_ntok, int32_t *num_blocks,
                           int32_t *ctx_lens, int32_t *seq_lens, int32_t *status, hipStream_t s);
 
+// bytes of the work-list buffer a prefill call needs, and the launcher (plan kernel + attention kernel)
+size_t prefill_plan_bytes(int32_t total_q, int32_t num_req, int group);
 hipError_t launch_prefill(const AttnArgs &a, int head_dim, int group, int kv_dtype, const int32_t *q_ptr,
-                          int32_t total_q, int32_t max_q, hipStream_t s);
+                          int32_t total_q, int32_t *plan, hipStream_t s);
 
 // workspace floats needed by decode for (num_req, hkv, group, head_dim, splits)
 size_t decode_workspace_bytes(int32_t num_req, int32_t hkv, int32_t group, int32_t head_dim, int32_t splits);

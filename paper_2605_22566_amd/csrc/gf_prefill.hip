@@ -93,8 +93,8 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_kernel(AttnArgs a, const i
                                                           const int32_t *__restrict__ ntk_base,
                                                           const int32_t *__restrict__ q_ptr,
                                                           const float *__restrict__ k_scale,
-                                                          const float *__restrict__ v_scale, int q_tiles,
-                                                          int total_q) {
+                                                          const float *__restrict__ v_scale,
+                                                          const int32_t *__restrict__ plan, int total_q) {
     constexpr int ES = FP8 ? 1 : 2;
     using C = PrefillCfg<D, G, NW, ES>;
     extern __shared__ __attribute__((aligned(1024))) char lds[];
@@ -106,17 +106,18 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_kernel(AttnArgs a, const i
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int m = lane & 31, hh = lane >> 5;
 
-    // Work item.  Workgroups are dealt to the 8 XCDs round-robin by id, and each XCD has
-    // its own L2: (request, kv head) pair p goes to XCD p % 8 with all its q tiles queued
-    // back to back there, so the tiles of a pair stream the same K/V through one L2 and
-    // (with 8 kv heads) every XCD carries exactly one head of every request.
-    const int xcd = blockIdx.x & 7;
-    const int slot = blockIdx.x >> 3;
-    const int qt = q_tiles - 1 - slot % q_tiles;       // longest (most causal tail) first
-    const int rk = (slot / q_tiles) * 8 + xcd;
-    if (rk >= a.num_req * a.hkv) return;
-    const int kvh = rk % a.hkv;
-    const int r = rk / a.hkv;
+    // Work item.  The plan kernel lists the (request, q tile) items of the batch, heaviest
+    // request first and the q tiles of a request back to back; workgroup id u takes item
+    // u / Hkv for kv head u % Hkv.  Workgroups are dealt to the 8 XCDs round-robin by id and
+    // each XCD has its own L2: with 8 kv heads XCD x carries head x of every request, so the
+    // q tiles of a (request, head) pair stream the same K/V through one L2, one after the
+    // other, and the work is balanced across XCDs by symmetry.
+    const int item = blockIdx.x / a.hkv;
+    const int kvh = blockIdx.x % a.hkv;
+    if (item >= plan[0]) return;
+    const int r = plan[2 + 2 * item];
+    const int qt = plan[3 + 2 * item];
+    if (r < 0 || r >= a.num_req) return;
     if (a.status && a.status[r] != 0) return;
     const int ctx = a.ctx_lens[r];
     const int n_new = a.seq_lens[r] - ctx;
@@ -479,19 +480,86 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_kernel(AttnArgs a, const i
     }
 }
 
+// Work list of a prefill call.  plan[0] = number of items, plan[2 + 2w], plan[3 + 2w] = (request,
+// q tile) of item w.  Valid requests only (status 0, query rows matching the table); requests
+// are ranked by tokens to attend (context + new, descending; up to kPlanSortMax requests, beyond
+// that in batch order) so that the long ones start first; a request's tiles are listed last tile
+// (most causal tail) first.  One workgroup; integer work only.
+size_t prefill_plan_items(int32_t total_q, int32_t num_req, int bm);
+constexpr int kPlanThreads = 256;
+constexpr int kPlanSortMax = 2048;
+
+__global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(
+    int num_req, int bm, int total_q, int cap, const int32_t *__restrict__ q_ptr,
+    const int32_t *__restrict__ ctx_lens, const int32_t *__restrict__ seq_lens,
+    const int32_t *__restrict__ status, int32_t *__restrict__ plan) {
+    __shared__ int cost[kPlanSortMax];
+    __shared__ int order[kPlanSortMax];
+    __shared__ int part[kPlanThreads];
+    const int tid = threadIdx.x;
+    const bool sorted = num_req <= kPlanSortMax;
+    auto tiles_of = [&](int r) -> int {
+        if (status && status[r] != 0) return 0;
+        const int n = seq_lens[r] - ctx_lens[r];
+        const int q0 = q_ptr[r];
+        if (n <= 0 || q_ptr[r + 1] - q0 != n || q0 < 0 || q0 + n > total_q) return 0;
+        return (n + bm - 1) / bm;
+    };
+    if (sorted) {
+        for (int r = tid; r < num_req; r += kPlanThreads) cost[r] = tiles_of(r) ? seq_lens[r] : -1;
+        __syncthreads();
+        for (int r = tid; r < num_req; r += kPlanThreads) {
+            const int c = cost[r];
+            int rank = 0;
+            for (int x = 0; x < num_req; ++x) rank += (cost[x] > c) || (cost[x] == c && x < r);
+            order[rank] = r;
+        }
+        __syncthreads();
+    }
+    // two-level exclusive scan of the tile counts in list order
+    const int per = (num_req + kPlanThreads - 1) / kPlanThreads;
+    const int k0 = min(tid * per, num_req), k1 = min(k0 + per, num_req);
+    int sum = 0;
+    for (int k = k0; k < k1; ++k) sum += tiles_of(sorted ? order[k] : k);
+    part[tid] = sum;
+    __syncthreads();
+    if (tid == 0) {
+        int run = 0;
+        for (int i = 0; i < kPlanThreads; ++i) {
+            const int v = part[i];
+            part[i] = run;
+            run += v;
+        }
+        plan[0] = min(run, cap);
+        plan[1] = 0;
+    }
+    __syncthreads();
+    int off = part[tid];
+    for (int k = k0; k < k1; ++k) {
+        const int r = sorted ? order[k] : k;
+        const int nt = tiles_of(r);
+        for (int j = 0; j < nt; ++j)
+            if (off + j < cap) {
+                plan[2 + 2 * (off + j)] = r;
+                plan[3 + 2 * (off + j)] = nt - 1 - j;
+            }
+        off += nt;
+    }
+}
+
 template <int D, int G, int NW, bool FP8>
-static hipError_t launch_prefill_k(const AttnArgs &a, const int32_t *q_ptr, int32_t total_q, int32_t max_q,
+static hipError_t launch_prefill_k(const AttnArgs &a, const int32_t *q_ptr, int32_t total_q, int32_t *plan,
                                    hipStream_t s);
 
 template <int D, int G, int NW>
 static hipError_t launch_prefill_t(const AttnArgs &a, int kv_dtype, const int32_t *q_ptr, int32_t total_q,
-                                   int32_t max_q, hipStream_t s) {
-    if (kv_dtype == GF_FP8_E4M3) return launch_prefill_k<D, G, NW, true>(a, q_ptr, total_q, max_q, s);
-    return launch_prefill_k<D, G, NW, false>(a, q_ptr, total_q, max_q, s);
+                                   int32_t *plan, hipStream_t s) {
+    if (kv_dtype == GF_FP8_E4M3) return launch_prefill_k<D, G, NW, true>(a, q_ptr, total_q, plan, s);
+    return launch_prefill_k<D, G, NW, false>(a, q_ptr, total_q, plan, s);
 }
 
 template <int D, int G, int NW, bool FP8>
-static hipError_t launch_prefill_k(const AttnArgs &a, const int32_t *q_ptr, int32_t total_q, int32_t max_q,
+static hipError_t launch_prefill_k(const AttnArgs &a, const int32_t *q_ptr, int32_t total_q, int32_t *plan,
                                    hipStream_t s) {
     using C = PrefillCfg<D, G, NW, FP8 ? 1 : 2>;
     auto kern = prefill_kernel<D, G, NW, FP8>;
@@ -501,23 +569,34 @@ static hipError_t launch_prefill_k(const AttnArgs &a, const int32_t *q_ptr, int3
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    const int q_tiles = (max_q + C::kBM - 1) / C::kBM;
-    const size_t pairs8 = ((size_t)a.num_req * a.hkv + 7) / 8 * 8;   // padded so that id % 8 is the XCD
-    const size_t grid = pairs8 * q_tiles;
+    // sum_r ceil(n_r / BM) <= total_q / BM + num_req: the item capacity the host can know
+    const size_t cap = prefill_plan_items(total_q, a.num_req, C::kBM);
+    const size_t grid = cap * a.hkv;
     if (grid == 0) return hipSuccess;
     if (grid > 0x7fffffffu) return hipErrorInvalidValue;
+    hipLaunchKernelGGL(prefill_plan_kernel, dim3(1), dim3(kPlanThreads), 0, s, a.num_req, C::kBM, total_q, (int)cap,
+                       q_ptr, a.ctx_lens, a.seq_lens, a.status, plan);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(C::kThreads), C::kLds, s, a, a.block_table, a.block_ntok,
-                       q_ptr, a.k_scale, a.v_scale, q_tiles, total_q);
+                       q_ptr, a.k_scale, a.v_scale, plan, total_q);
     return hipGetLastError();
 }
 
+size_t prefill_plan_items(int32_t total_q, int32_t num_req, int bm) { return (size_t)total_q / bm + num_req; }
+
+size_t prefill_plan_bytes(int32_t total_q, int32_t num_req, int group) {
+    // 4-wave workgroups: 128 score rows = 128 / group new tokens per item
+    return (2 + 2 * prefill_plan_items(total_q, num_req, 128 / group)) * sizeof(int32_t);
+}
+
 hipError_t launch_prefill(const AttnArgs &a, int head_dim, int group, int kv_dtype, const int32_t *q_ptr,
-                          int32_t total_q, int32_t max_q, hipStream_t s) {
-    if (a.num_req == 0 || total_q == 0 || max_q == 0) return hipSuccess;
+                          int32_t total_q, int32_t *plan, hipStream_t s) {
+    if (a.num_req == 0 || total_q == 0) return hipSuccess;
     // 4-wave workgroups, two resident per CU: their barriers stay local to one wave per SIMD and
     // the two workgroups drift apart, so one's vector phases fall under the other's MFMAs
 #define GF_CASE(DD, GG) \
-    if (head_dim == DD && group == GG) return launch_prefill_t<DD, GG, 4>(a, kv_dtype, q_ptr, total_q, max_q, s);
+    if (head_dim == DD && group == GG) return launch_prefill_t<DD, GG, 4>(a, kv_dtype, q_ptr, total_q, plan, s);
     GF_CASE(64, 1) GF_CASE(64, 2) GF_CASE(64, 4) GF_CASE(64, 8)
     GF_CASE(128, 1) GF_CASE(128, 2) GF_CASE(128, 4) GF_CASE(128, 8)
 #undef GF_CASE
