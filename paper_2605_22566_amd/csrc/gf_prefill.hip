@@ -378,11 +378,18 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_kernel(AttnArgs a, const i
             return *(const frag_t *)(vb + (j / C::kDT) * C::kVBlk + 32 * (j % C::kDT) * C::kVRow);
         };
         constexpr int NSLOT = C::kQK + C::kPV;
-        constexpr int kExpPerSlot = 32 / C::kQK;     // exponentials in the shadow of one score MFMA
+        constexpr int kHalf = C::kQK / 2;            // score MFMAs per 32 keys
+        constexpr int kExpEnd = NSLOT - 5;           // last slot that may carry an exponential
+        auto exp_slot = [](int e) -> int {
+            return e < 16 ? (e * kHalf) / 16 : kHalf + ((e - 16) * (kExpEnd - kHalf)) / 16;
+        };
+        static_assert(kHalf + (15 * (kExpEnd - kHalf)) / 16 + 1 < C::kQK + 3 * C::kDT,
+                      "last chunk packed before its P*V MFMA");
         frag_t f[kAhead];
 #pragma unroll
         for (int i = 0; i < kAhead; ++i) f[i] = frag(i);
         uint32_t pw[C::kEntries][4];                 // P^T operand, 2 bf16 per word
+        float pe[32];                                // exponentials awaiting their bf16 pack
         float addc[C::kEntries], psum[C::kEntries], vmax[C::kEntries];
 #pragma unroll
         for (int cb = 0; cb < C::kEntries; ++cb) {
@@ -400,19 +407,6 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_kernel(AttnArgs a, const i
                     for (int x = 0; x < 16; ++x) sn[kt][x] = 0.f;
                 }
                 sn[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(to_operand(f[i % kAhead]), qf[ks], sn[kt], 0, 0, 0);
-                // vector share: exponentials of tile t, kExpPerSlot per slot
-#pragma unroll
-                for (int e2 = 0; e2 < kExpPerSlot; e2 += 2) {
-                    const int idx = i * kExpPerSlot + e2;        // 0..31: score register pair
-                    const int kt2 = idx / 16, x = idx % 16;
-                    const int cb = idx / 8;                      // 16-key chunk = table entry
-                    f32x2 p;
-                    p[0] = fast_exp2(sc[kt2][x] * ts.mult[cb] + addc[cb]);
-                    p[1] = fast_exp2(sc[kt2][x + 1] * ts.mult[cb] + addc[cb]);
-                    psum[cb] += p[0] + p[1];
-                    pw[cb][(idx % 8) / 2] = __builtin_bit_cast(uint32_t, __builtin_convertvector(p, bf16x2));
-                    asm volatile("" : "+v"(psum[cb]));           // keep the row-sum adds in this slot
-                }
             } else {
                 const int j = i - C::kQK;
                 const int cb = j / C::kDT, dt = j % C::kDT;
@@ -426,6 +420,24 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_kernel(AttnArgs a, const i
                     const int idx = j * kMaxPerSlot + e2;
                     vmax[idx / 8] = fmaxf(vmax[idx / 8], sn[idx / 16][idx % 16]);
                     asm volatile("" : "+v"(vmax[idx / 8]));      // keep the running maximum in this slot
+                }
+            }
+            // vector share of every slot: the exponentials of the first 32 keys of tile t go two per
+            // slot under the first half of the score MFMAs (their registers are free when the second
+            // half of the next tile's scores starts to accumulate), those of the last 32 keys are
+            // spread over the slots up to kExpEnd; each pair is packed to bf16 one slot after its
+            // second exponential, and chunk c is complete before its first P*V MFMA
+#pragma unroll
+            for (int e2 = 0; e2 < 32; ++e2) {
+                if (exp_slot(e2) == i) {
+                    const int cb = e2 / 8;
+                    pe[e2] = fast_exp2(sc[e2 / 16][e2 % 16] * ts.mult[cb] + addc[cb]);
+                    psum[cb] += pe[e2];
+                    asm volatile("" : "+v"(psum[cb]), "+v"(pe[e2]));   // keep them in this slot
+                }
+                if ((e2 & 1) && exp_slot(e2) + 1 == i) {
+                    const f32x2 p = {pe[e2 - 1], pe[e2]};
+                    pw[e2 / 8][(e2 % 8) / 2] = __builtin_bit_cast(uint32_t, __builtin_convertvector(p, bf16x2));
                 }
             }
             if (i + kAhead < NSLOT) f[i % kAhead] = frag(i + kAhead);
