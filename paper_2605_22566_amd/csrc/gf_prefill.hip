@@ -41,6 +41,8 @@
 // path taken only by tiles that need it.
 
 #include "gf_internal.h"
+#include <type_traits>
+#include <utility>
 
 namespace gf {
 
@@ -74,9 +76,25 @@ struct PrefillCfg {
 };
 
 constexpr float kRescaleSlack = 8.0f;   // log2 units a row max may exceed its reference
-constexpr int kAhead = 4;               // LDS operand fragments in flight ahead of their MFMA
+constexpr int kGroup = 4;               // LDS operand fragments fetched (and waited for) together
+constexpr int kWaitLds = 0xC07F;        // s_waitcnt lgkmcnt(0), other counters untouched
+#ifndef GF_ABL
+#define GF_ABL 0
+#endif
 
 typedef __attribute__((address_space(3))) void *lptr_t;
+
+// compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>), in order.
+// The slot schedule of the main loop is written with it, so that "which slot carries which piece
+// of vector work" is decided by if constexpr and never exists as a runtime branch.
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, I...>) {
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f) {
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
 
 // 16-byte-per-lane global -> LDS direct load: lane l writes LDS bytes [dst + 16 l, +16).
 // Issued through inline assembly so that it is ordered by hand: the kernel waits for its
@@ -147,17 +165,20 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_kernel(AttnArgs a, const i
             qf[ks] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(qp + (16 * ks + 8 * hh) * 2));
     }
 
-    // ---- table window: lane l of every wave caches entry 64*w + l (block id, token count) of
-    // window w and of window w+1; the loop reads them with v_readlane (uniform index), so no
-    // memory load sits between a tile and its addresses.  Entries beyond e_end read as (0, 0).
+    // ---- table window: lane l of every wave caches entry 64*w + l of window w and of window w+1:
+    // the pool index of the (block, kv head) tile and the entry's token count; the loop reads them
+    // with v_readlane (uniform index), so no memory load sits between a tile and its addresses.
+    // Entries beyond e_end read as block 0 with 0 tokens.  One bit per entry says whether the entry
+    // needs masking (partial block, causal cut, or beyond the end); a tile tests its 4 bits at once.
+    // With an e4m3 pool the window also carries the entry's K scale, log2 of its V scale and the
+    // reciprocal of its V scale.
     int win = 0;
-    // With an e4m3 pool the window also carries the entry's K scale, log2 of its V scale and
-    // the reciprocal of its V scale.
     struct Win {
-        int id, nt;
+        int idx, nt;
         float ks, lvs, ivs;
     };
     Win w_cur, w_nxt, w_new = {0, 0, 1.f, 0.f, 1.f};
+    uint64_t mbits_cur, mbits_nxt;
     auto load_window = [&](int w, Win &x) {
         const int e = 64 * w + lane;
         const bool ok = e < e_end;
@@ -170,18 +191,21 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_kernel(AttnArgs a, const i
             x.lvs = __builtin_log2f(vs);
             x.ivs = 1.0f / vs;
         }
-        x.id = id;                           // (bf16 pool: clamped into the pool when the window is adopted)
+        x.idx = id;                          // block id until the window is adopted
+    };
+    // block id (clamped into the pool) -> index of the (block, kv head) tile; mask bits of the window
+    auto adopt_window = [&](int w, Win &x) -> uint64_t {
+        const int e = 64 * w + lane;
+        x.idx = min(max(x.idx, 0), a.pool_blocks - 1) * a.hkv + kvh;
+        const bool need = x.nt < kBlock || (e >= ncb && (e - ncb) * kBlock + kBlock - 1 > i0);
+        return __builtin_amdgcn_ballot_w64(need);
     };
     load_window(0, w_cur);
     load_window(1, w_nxt);
-    w_cur.id = min(max(w_cur.id, 0), a.pool_blocks - 1);
-    w_nxt.id = min(max(w_nxt.id, 0), a.pool_blocks - 1);
-    auto entry_id = [&](int e) -> int {       // e uniform, within the two cached windows
-        const int a0 = __builtin_amdgcn_readlane(w_cur.id, e & 63), a1 = __builtin_amdgcn_readlane(w_nxt.id, e & 63);
-        return (e >> 6) == win ? a0 : a1;
-    };
-    auto entry_nt = [&](int e) -> int {
-        const int a0 = __builtin_amdgcn_readlane(w_cur.nt, e & 63), a1 = __builtin_amdgcn_readlane(w_nxt.nt, e & 63);
+    mbits_cur = adopt_window(0, w_cur);
+    mbits_nxt = adopt_window(1, w_nxt);
+    auto entry_i = [&](int Win::*f, int e) -> int {       // e uniform, within the two cached windows
+        const int a0 = __builtin_amdgcn_readlane(w_cur.*f, e & 63), a1 = __builtin_amdgcn_readlane(w_nxt.*f, e & 63);
         return (e >> 6) == win ? a0 : a1;
     };
     auto entry_f = [&](float Win::*f, int e) -> float {
@@ -191,45 +215,41 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_kernel(AttnArgs a, const i
     };
 
     // ---- staging: global -> LDS direct loads -----------------------------------------
-    const size_t blk_bytes = (size_t)kBlock * D * ES;
+    // Wave w stages table entry w of every tile (K rows / V block image of one pool block).
+    static_assert(C::kDmaPerWave == C::kDmaPerEntry && NW == C::kEntries, "one table entry per wave");
+    constexpr size_t blk_bytes = (size_t)kBlock * D * ES;
     // K: lane l of direct load i lands at tile row 4i + l/CPR (D=128), chunk position l%CPR, and
     // fetches the chunk (position ^ swizzle(row)) of that row
     constexpr int kRPI = 1024 / C::kRowBytes;            // K rows per direct load
     auto k_swizzle = [](int rho) -> int {
         return C::kCPR == 16 ? (rho & 15) : C::kCPR == 8 ? ((rho >> 1) & 7) : ((rho >> 2) & 3);
     };
-    int k_src_off[C::kDmaPerWave], v_src_off[C::kDmaPerWave];
+    const char *k_src[C::kDmaPerWave], *v_src[C::kDmaPerWave];   // kv head 0 of block 0, this lane's chunk
 #pragma unroll
     for (int j = 0; j < C::kDmaPerWave; ++j) {
         const int i = wave * C::kDmaPerWave + j;         // direct load index within the tile
         const int rho = i * kRPI + lane / C::kCPR;       // tile row
         const int pos = lane % C::kCPR;
-        k_src_off[j] = (rho % kBlock) * C::kRowBytes + ((pos ^ k_swizzle(rho)) * 16);
-        const int q = (i % C::kDmaPerEntry) * 64 + lane;  // 16-byte chunk within the V block image
+        k_src[j] = (const char *)a.k + (rho % kBlock) * C::kRowBytes + ((pos ^ k_swizzle(rho)) * 16);
+        const int q = j * 64 + lane;                     // 16-byte chunk within the V block image
         if constexpr (FP8) {
-            v_src_off[j] = q * 16;                        // one chunk per head-dim row: image = pool block
+            v_src[j] = (const char *)a.v + q * 16;       // one chunk per head-dim row: image = pool block
         } else {
             const int d = q >> 1, vpos = q & 1;
-            v_src_off[j] = d * 32 + ((vpos ^ ((d >> 3) & 1)) * 16);
+            v_src[j] = (const char *)a.v + d * 32 + ((vpos ^ ((d >> 3) & 1)) * 16);
         }
     }
     auto issue_k = [&](int tile, int buf) {
+        const size_t off = (size_t)(uint32_t)entry_i(&Win::idx, tile * C::kEntries + wave) * blk_bytes;
 #pragma unroll
-        for (int j = 0; j < C::kDmaPerWave; ++j) {
-            const int i = wave * C::kDmaPerWave + j;
-            const int bid = entry_id(tile * C::kEntries + i / C::kDmaPerEntry);
-            const char *src = (const char *)a.k + ((size_t)bid * a.hkv + kvh) * blk_bytes + k_src_off[j];
-            dma16(src, kbuf + buf * C::kKTile + i * 1024);
-        }
+        for (int j = 0; j < C::kDmaPerWave; ++j)
+            dma16(k_src[j] + off, kbuf + buf * C::kKTile + (wave * C::kDmaPerWave + j) * 1024);
     };
     auto issue_v = [&](int tile, int buf) {
+        const size_t off = (size_t)(uint32_t)entry_i(&Win::idx, tile * C::kEntries + wave) * blk_bytes;
 #pragma unroll
-        for (int j = 0; j < C::kDmaPerWave; ++j) {
-            const int i = wave * C::kDmaPerWave + j;
-            const int bid = entry_id(tile * C::kEntries + i / C::kDmaPerEntry);
-            const char *src = (const char *)a.v + ((size_t)bid * a.hkv + kvh) * blk_bytes + v_src_off[j];
-            dma16(src, vbuf + buf * C::kVTile + i * 1024);
-        }
+        for (int j = 0; j < C::kDmaPerWave; ++j)
+            dma16(v_src[j] + off, vbuf + buf * C::kVTile + (wave * C::kDmaPerWave + j) * 1024);
     };
 
     // K operand row m reads key row (m with bits 2,3 swapped); chunk c of row rho sits at
@@ -248,9 +268,11 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_kernel(AttnArgs a, const i
     };
 
     // ---- running state --------------------------------------------------------------
+    // m_ref is the same in the two lanes of a row; mx, l_run, the per-tile sums and maxima are
+    // per-lane partials over the keys of the lane's half and are combined only when needed.
     const float c = a.scale_log2;
     float m_ref = -1.0e30f, l_run = 0.f;
-    float mx = -INFINITY;             // row maximum (log2 units) of the tile whose scores are pending
+    float mx = -INFINITY;             // partial row maximum (log2 units) of the tile whose scores are pending
     f32x16 o[C::kDT];
 #pragma unroll
     for (int dt = 0; dt < C::kDT; ++dt)
@@ -261,13 +283,16 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_kernel(AttnArgs a, const i
     // Per-chunk exponent constants of tile t.  A raw score of chunk cb becomes
     //   2^(s * mult[cb] + addc[cb]),  mult = sm_scale*log2(e) [* K scale],  addc = -m_ref [+ log2(V scale)]
     // (the V scale rides on P so that P*V needs no further scaling; the row sum divides it out again).
+    // A bf16 pool has one set of constants, so one running sum and one running maximum serve the tile.
+    constexpr int kAcc = FP8 ? C::kEntries : 1;
+    auto acc_of = [](int cb) constexpr -> int { return FP8 ? cb : 0; };
     struct TileScale {
-        float mult[C::kEntries], lvs[C::kEntries], ivs[C::kEntries];
+        float mult[kAcc], lvs[kAcc], ivs[kAcc];
     };
     auto tile_scale = [&](int t) -> TileScale {
         TileScale ts;
 #pragma unroll
-        for (int cb = 0; cb < C::kEntries; ++cb) {
+        for (int cb = 0; cb < kAcc; ++cb) {
             if constexpr (FP8) {
                 const int ent = t * C::kEntries + cb;
                 ts.mult[cb] = c * entry_f(&Win::ks, ent);
@@ -281,7 +306,7 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_kernel(AttnArgs a, const i
         }
         return ts;
     };
-    // row maximum of a score tile in log2 units (identical in both lanes of a row)
+    // partial row maximum of a score tile in log2 units (this lane's half of the keys)
     auto row_max = [&](const f32x16 (&s)[2], const TileScale &ts) -> float {
         float best = -INFINITY;
 #pragma unroll
@@ -289,26 +314,15 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_kernel(AttnArgs a, const i
             float v = s[cb >> 1][8 * (cb & 1)];
 #pragma unroll
             for (int j = 1; j < 8; ++j) v = fmaxf(v, s[cb >> 1][8 * (cb & 1) + j]);
-            best = fmaxf(best, v * ts.mult[cb]);
+            best = fmaxf(best, v * ts.mult[acc_of(cb)]);
         }
-        return fmaxf(best, other_half(best));
-    };
-    // uniform: does tile t hold a partial block or a causally cut tail entry?
-    auto tile_needs_mask = [&](int t) -> bool {
-        bool need = false;
-#pragma unroll
-        for (int cb = 0; cb < C::kEntries; ++cb) {
-            const int ent = t * C::kEntries + cb;
-            const int nt = entry_nt(ent);
-            need |= (nt < kBlock) || (ent >= ncb && (ent - ncb) * kBlock + kBlock - 1 > i0);
-        }
-        return need;
+        return best;
     };
     auto apply_mask = [&](int t, f32x16 (&s)[2]) {
 #pragma unroll
         for (int cb = 0; cb < C::kEntries; ++cb) {
             const int ent = t * C::kEntries + cb;
-            const int nt = entry_nt(ent);
+            const int nt = entry_i(&Win::nt, ent);
             const int tail_base = ent >= ncb ? (ent - ncb) * kBlock : -(1 << 28);
             const int lim = min(nt, row_tok - tail_base + 1) - 8 * hh;
 #pragma unroll
@@ -346,22 +360,38 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_kernel(AttnArgs a, const i
     auto body = [&](int t, f32x16 (&sc)[2], f32x16 (&sn)[2]) {
         const bool has_next = t + 1 < ntiles;
         const bool k2 = t + 2 < ntiles;
+        // operand stream of this iteration: the K fragments of tile t+1, then the V fragments of tile t,
+        // fetched from LDS in groups of kGroup, one group ahead (one wait per group, not per MFMA)
+        constexpr int NSLOT = C::kQK + C::kPV;
+        static_assert(NSLOT % kGroup == 0, "whole groups");
+        const char *kb = kbuf + ((t + 1) & 1) * C::kKTile;
+        const char *vb = vbuf + (t & 1) * C::kVTile + v_lane_off;
+        auto frag = [&](int n) -> frag_t {
+            if (n < C::kQK) return k_frag(kb, n);
+            const int j = n - C::kQK;
+            return *(const frag_t *)(vb + (j / C::kDT) * C::kVBlk + 32 * (j % C::kDT) * C::kVRow);
+        };
+        frag_t f[2][kGroup];
+        if constexpr (!(GF_ABL & 1)) {
+#pragma unroll
+            for (int i = 0; i < kGroup; ++i) f[0][i] = frag(i);
+        }
         // the table window slides at the end of this iteration if the next tile opens a new one:
         // fetch the window after next now, adopt it after the wait that precedes the barrier
         const bool slide = (t + 1) * C::kEntries == 64 * (win + 1);
         if (slide) load_window(win + 2, w_new);
         const TileScale ts = tile_scale(t);          // constants of this tile ...
         const TileScale tn = tile_scale(t + 1);      // ... and of the next (for its row maximum)
-        if (k2) issue_k(t + 2, t & 1);             // K(t+2) replaces K(t), read last iteration
-        if (has_next) issue_v(t + 1, (t + 1) & 1); // V(t+1) replaces V(t-1)
-        // side path: partial blocks / causal tail in tile t
-        if (tile_needs_mask(t)) {
+        if (!(GF_ABL & 8) && k2) issue_k(t + 2, t & 1);             // K(t+2) replaces K(t), read last iteration
+        if (!(GF_ABL & 8) && has_next) issue_v(t + 1, (t + 1) & 1); // V(t+1) replaces V(t-1)
+        // side path: partial blocks / causal tail / end of the sequence in tile t
+        if (!(GF_ABL & 32) && ((mbits_cur >> ((t * C::kEntries) & 63)) & ((1u << C::kEntries) - 1)) != 0) {
             apply_mask(t, sc);
             mx = row_max(sc, ts);
         }
         // refresh the reference maximum only when some row outgrew it
         if (__builtin_amdgcn_ballot_w64(mx > m_ref + kRescaleSlack) != 0) {
-            const float m_new = fmaxf(m_ref, mx);
+            const float m_new = fmaxf(m_ref, fmaxf(mx, other_half(mx)));
             const float alpha = fast_exp2(m_ref - m_new);
             m_ref = m_new;
             l_run *= alpha;
@@ -369,99 +399,97 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_kernel(AttnArgs a, const i
             for (int dt = 0; dt < C::kDT; ++dt) o[dt] *= alpha;
         }
 
-        // main stream: 32 slots of {MFMA, LDS fetch 4 ahead, vector share}
-        const char *kb = kbuf + ((t + 1) & 1) * C::kKTile;
-        const char *vb = vbuf + (t & 1) * C::kVTile + v_lane_off;
-        auto frag = [&](int n) -> frag_t {     // unified operand stream: K fragments then V fragments
-            if (n < C::kQK) return k_frag(kb, n);
-            const int j = n - C::kQK;
-            return *(const frag_t *)(vb + (j / C::kDT) * C::kVBlk + 32 * (j % C::kDT) * C::kVRow);
-        };
-        constexpr int NSLOT = C::kQK + C::kPV;
-        constexpr int kHalf = C::kQK / 2;            // score MFMAs per 32 keys
+        // main stream: NSLOT slots of {MFMA, its share of the vector work}
         constexpr int kExpEnd = NSLOT - 5;           // last slot that may carry an exponential
-        auto exp_slot = [](int e) -> int {
-            return e < 16 ? (e * kHalf) / 16 : kHalf + ((e - 16) * (kExpEnd - kHalf)) / 16;
-        };
-        static_assert(kHalf + (15 * (kExpEnd - kHalf)) / 16 + 1 < C::kQK + 3 * C::kDT,
-                      "last chunk packed before its P*V MFMA");
-        frag_t f[kAhead];
-#pragma unroll
-        for (int i = 0; i < kAhead; ++i) f[i] = frag(i);
+        constexpr auto exp_slot = [](int e) constexpr -> int { return (e * kExpEnd) / 32; };
+        static_assert((7 * kExpEnd) / 32 + 1 < C::kQK && (15 * kExpEnd) / 32 + 1 < C::kQK + C::kDT &&
+                          (23 * kExpEnd) / 32 + 1 < C::kQK + 2 * C::kDT && (31 * kExpEnd) / 32 + 1 < C::kQK + 3 * C::kDT,
+                      "every chunk is packed before its P*V MFMA");
         uint32_t pw[C::kEntries][4];                 // P^T operand, 2 bf16 per word
         float pe[32];                                // exponentials awaiting their bf16 pack
-        float addc[C::kEntries], psum[C::kEntries], vmax[C::kEntries];
+        float addc[kAcc], psum[kAcc], vmax[kAcc];
 #pragma unroll
-        for (int cb = 0; cb < C::kEntries; ++cb) {
+        for (int cb = 0; cb < kAcc; ++cb) {
             addc[cb] = ts.lvs[cb] - m_ref;
             psum[cb] = 0.f;
             vmax[cb] = -INFINITY;
         }
+        __builtin_amdgcn_s_waitcnt(kWaitLds);        // group 0 has arrived
         __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int i = 0; i < NSLOT; ++i) {
-            if (i < C::kQK) {
-                const int kt = i / C::kKS, ks = i % C::kKS;
-                if (ks == 0) {
+        static_for<NSLOT>([&](auto slot_c) {
+            constexpr int i = decltype(slot_c)::value;
+            constexpr int g = i / kGroup;
+            if constexpr (i < C::kQK) {
+                constexpr int kt = i / C::kKS, ks = i % C::kKS;
+                if constexpr (ks == 0) {
 #pragma unroll
                     for (int x = 0; x < 16; ++x) sn[kt][x] = 0.f;
                 }
-                sn[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(to_operand(f[i % kAhead]), qf[ks], sn[kt], 0, 0, 0);
+                sn[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(to_operand(f[g & 1][i % kGroup]), qf[ks], sn[kt], 0, 0, 0);
             } else {
-                const int j = i - C::kQK;
-                const int cb = j / C::kDT, dt = j % C::kDT;
+                constexpr int j = i - C::kQK;
+                constexpr int cb = j / C::kDT, dt = j % C::kDT;
                 u32x4 pq = {pw[cb][0], pw[cb][1], pw[cb][2], pw[cb][3]};
-                o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(to_operand(f[i % kAhead]),
+                o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(to_operand(f[g & 1][i % kGroup]),
                                                                 __builtin_bit_cast(bf16x8, pq), o[dt], 0, 0, 0);
-                // vector share: running maximum of the next tile's scores
+                // vector share: running maximum of the next tile's scores, two elements per v_max3
                 constexpr int kMaxPerSlot = 32 / C::kPV;
-#pragma unroll
-                for (int e2 = 0; e2 < kMaxPerSlot; ++e2) {
-                    const int idx = j * kMaxPerSlot + e2;
-                    vmax[idx / 8] = fmaxf(vmax[idx / 8], sn[idx / 16][idx % 16]);
-                    asm volatile("" : "+v"(vmax[idx / 8]));      // keep the running maximum in this slot
-                }
+                static_assert(kMaxPerSlot % 2 == 0, "maximum taken in pairs");
+                static_for<kMaxPerSlot / 2>([&](auto e_c) {
+                    constexpr int idx = j * kMaxPerSlot + 2 * decltype(e_c)::value;
+                    float &vm = vmax[acc_of(idx / 8)];
+                    vm = fmaxf(fmaxf(vm, sn[idx / 16][idx % 16]), sn[idx / 16][idx % 16 + 1]);
+                    asm volatile("" : "+v"(vm));      // keep the running maximum in this slot
+                });
             }
-            // vector share of every slot: the exponentials of the first 32 keys of tile t go two per
-            // slot under the first half of the score MFMAs (their registers are free when the second
-            // half of the next tile's scores starts to accumulate), those of the last 32 keys are
-            // spread over the slots up to kExpEnd; each pair is packed to bf16 one slot after its
-            // second exponential, and chunk c is complete before its first P*V MFMA
+            // the first MFMA of a group is followed by the fetch of the next group
+            if constexpr (!(GF_ABL & 1) && i % kGroup == 0 && i + kGroup < NSLOT) {
 #pragma unroll
-            for (int e2 = 0; e2 < 32; ++e2) {
-                if (exp_slot(e2) == i) {
-                    const int cb = e2 / 8;
-                    pe[e2] = fast_exp2(sc[e2 / 16][e2 % 16] * ts.mult[cb] + addc[cb]);
-                    psum[cb] += pe[e2];
-                    asm volatile("" : "+v"(psum[cb]), "+v"(pe[e2]));   // keep them in this slot
+                for (int x = 0; x < kGroup; ++x) f[(g + 1) & 1][x] = frag(i + kGroup + x);
+            }
+            // vector share of every slot: the 32 exponentials of tile t are spread evenly over the
+            // slots up to kExpEnd.  An exponential joins the row sum one step later (its consumer
+            // is never the next instruction), each pair is packed to bf16 one slot after its second
+            // exponential, and chunk c is complete before its first P*V MFMA.
+            static_for<32>([&](auto e_c) {
+                constexpr int e2 = decltype(e_c)::value;
+                if constexpr (exp_slot(e2) == i) {
+                    constexpr int cb = acc_of(e2 / 8);
+                    const float x = sc[e2 / 16][e2 % 16];
+                    pe[e2] = (GF_ABL & 2) ? x * ts.mult[cb] + addc[cb] : fast_exp2(x * ts.mult[cb] + addc[cb]);
+                    if constexpr (e2 > 0) psum[acc_of((e2 - 1) / 8)] += pe[e2 - 1];
+                    asm volatile("" : "+v"(psum[acc_of(e2 > 0 ? (e2 - 1) / 8 : 0)]), "+v"(pe[e2]));   // stay in this slot
                 }
-                if ((e2 & 1) && exp_slot(e2) + 1 == i) {
+                if constexpr ((e2 & 1) && exp_slot(e2) + 1 == i) {
                     const f32x2 p = {pe[e2 - 1], pe[e2]};
                     pw[e2 / 8][(e2 % 8) / 2] = __builtin_bit_cast(uint32_t, __builtin_convertvector(p, bf16x2));
+                    if constexpr (e2 == 31) psum[acc_of(3)] += pe[31];
                 }
-            }
-            if (i + kAhead < NSLOT) f[i % kAhead] = frag(i + kAhead);
+            });
+            // one wait per group, at the end of the slot before it: the whole group has arrived
+            if constexpr ((i + 1) % kGroup == 0 && i + 1 < NSLOT) __builtin_amdgcn_s_waitcnt(kWaitLds);
             __builtin_amdgcn_sched_barrier(0);
-        }
+        });
         {
             float best = -INFINITY;
 #pragma unroll
-            for (int cb = 0; cb < C::kEntries; ++cb) {
+            for (int cb = 0; cb < kAcc; ++cb) {
                 l_run += psum[cb] * ts.ivs[cb];
                 best = fmaxf(best, vmax[cb] * tn.mult[cb]);
             }
-            mx = fmaxf(best, other_half(best));
+            mx = best;
         }
-        dma_wait();                              // this wave's direct loads have landed ...
+        if (!(GF_ABL & 16)) dma_wait();                              // this wave's direct loads have landed ...
         // (the window fetch is waited for here, nowhere earlier)
-        asm volatile("" : "+v"(w_new.id), "+v"(w_new.nt), "+v"(w_new.ks), "+v"(w_new.lvs), "+v"(w_new.ivs));
+        asm volatile("" : "+v"(w_new.idx), "+v"(w_new.nt), "+v"(w_new.ks), "+v"(w_new.lvs), "+v"(w_new.ivs));
         if (slide) {
             w_cur = w_nxt;
+            mbits_cur = mbits_nxt;
             w_nxt = w_new;
-            w_nxt.id = min(max(w_nxt.id, 0), a.pool_blocks - 1);
+            mbits_nxt = adopt_window(win + 2, w_nxt);
             ++win;
         }
-        __syncthreads();                             // ... and every wave's are visible
+        if (!(GF_ABL & 4)) __syncthreads();                             // ... and every wave's are visible
     };
 
     int t = 0;
