@@ -48,11 +48,14 @@ namespace gf {
 
 typedef float f32x2 __attribute__((ext_vector_type(2)));
 
-template <int D, int G, int NW, int ES>   // ES = bytes per pool element (2 bf16, 1 e4m3)
+// RS = 32-row score tiles ("row sets") per wave.  Every K / V fragment a wave fetches from LDS
+// feeds RS MFMAs, so RS = 2 halves the LDS and staging traffic per flop; it needs the register
+// budget of one wave per SIMD.
+template <int D, int G, int NW, int RS, int ES>   // ES = bytes per pool element (2 bf16, 1 e4m3)
 struct PrefillCfg {
     static constexpr int kWaves = NW;
     static constexpr int kThreads = kWaves * 64;
-    static constexpr int kRows = 32 * kWaves;        // score rows per workgroup
+    static constexpr int kRows = 32 * kWaves * RS;   // score rows per workgroup
     static constexpr int kBM = kRows / G;            // new tokens per workgroup
     static constexpr int kBN = 64;                   // keys per KV tile
     static constexpr int kEntries = kBN / kBlock;    // table entries per tile (4)
@@ -68,16 +71,30 @@ struct PrefillCfg {
     static constexpr int kDmaPerEntry = kDmaPerTile / kEntries;
     static constexpr int kKS = D / 16;               // contraction steps of the score MFMAs
     static constexpr int kDT = D / 32;               // 32-wide output tiles of P*V
-    static constexpr int kQK = 2 * kKS;              // score MFMAs per tile
-    static constexpr int kPV = kDT * kEntries;       // P*V MFMAs per tile
+    static constexpr int kQK = 2 * kKS;              // K fragments (score MFMAs per row set) per tile
+    static constexpr int kPV = kDT * kEntries;       // V fragments (P*V MFMAs per row set) per tile
+    static constexpr int kFrags = kQK + kPV;
+    static constexpr int kSlots = kFrags * RS;       // MFMAs per tile and wave
     static_assert(kRows % G == 0, "rows must split evenly over heads");
     static_assert(kDmaPerTile % NW == 0 && kDmaPerWave >= 1, "staging must divide evenly over waves");
-    static_assert(kDmaPerEntry % kDmaPerWave == 0 || kDmaPerWave % kDmaPerEntry == 0, "a direct load stays in one block");
+    static_assert(kDmaPerWave == kDmaPerEntry && NW == kEntries, "one table entry per wave");
 };
+
+constexpr int kPrefillWaves = 4;
+#ifndef GF_RS
+#define GF_RS 2
+#endif
+constexpr int kPrefillRowSets = GF_RS;
+constexpr int kPrefillRows = 32 * kPrefillWaves * kPrefillRowSets;   // score rows per workgroup
 
 constexpr float kRescaleSlack = 8.0f;   // log2 units a row max may exceed its reference
 constexpr int kGroup = 4;               // LDS operand fragments fetched (and waited for) together
-constexpr int kWaitLds = 0xC07F;        // s_waitcnt lgkmcnt(0), other counters untouched
+#ifndef GF_DEPTH
+#define GF_DEPTH 2
+#endif
+constexpr int kDepth = GF_DEPTH;        // fragment groups in registers (kDepth - 1 in flight behind the one in use)
+// s_waitcnt lgkmcnt(n), other counters untouched
+constexpr int wait_lds(int n) { return 0xC07F | (n << 8); }
 #ifndef GF_ABL
 #define GF_ABL 0
 #endif
@@ -96,25 +113,86 @@ __device__ __forceinline__ void static_for(F &&f) {
     static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
 
-// 16-byte-per-lane global -> LDS direct load: lane l writes LDS bytes [dst + 16 l, +16).
-// Issued through inline assembly so that it is ordered by hand: the kernel waits for its
-// own direct loads (dma_wait) right before the workgroup barrier that publishes a tile,
-// instead of before every LDS read that follows their issue.
-__device__ __forceinline__ void dma16(const void *src, void *lds_dst) {
+// 16-byte-per-lane global -> LDS direct loads: lane l of load j fetches the 16 bytes at
+// base + off[j] + 1024 j (uniform base in SGPRs, 32-bit lane offset) and writes LDS bytes
+// [dst + 1024 j + 16 l, +16): the instruction's immediate offset is added to both addresses, so one
+// M0 value serves the N loads of a block.  Issued through inline assembly so that they are ordered
+// by hand: the kernel waits for its own direct loads (dma_wait) right before the workgroup barrier
+// that publishes a tile, instead of before every LDS read that follows their issue.
+template <int N>
+__device__ __forceinline__ void dma_block(const void *base, const uint32_t (&off)[N], void *lds_dst) {
+    static_assert(N == 1 || N == 2 || N == 4, "1 KB loads per block and wave");
     const uint32_t dst = (uint32_t)(uintptr_t)(lptr_t)lds_dst;
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(src) : "memory", "m0");
+    if constexpr (N == 1)
+        asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %2, %1" ::"s"(dst), "s"(base), "v"(off[0]) : "memory", "m0");
+    if constexpr (N == 2)
+        asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %2, %1\n\tglobal_load_lds_dwordx4 %3, %1 offset:1024"
+                     ::"s"(dst), "s"(base), "v"(off[0]), "v"(off[1]) : "memory", "m0");
+    if constexpr (N == 4)
+        asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %2, %1\n\tglobal_load_lds_dwordx4 %3, %1 offset:1024\n\t"
+                     "global_load_lds_dwordx4 %4, %1 offset:2048\n\tglobal_load_lds_dwordx4 %5, %1 offset:3072"
+                     ::"s"(dst), "s"(base), "v"(off[0]), "v"(off[1]), "v"(off[2]), "v"(off[3]) : "memory", "m0");
 }
 __device__ __forceinline__ void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
-template <int D, int G, int NW, bool FP8>
-__global__ __launch_bounds__(NW * 64, 2) void prefill_kernel(AttnArgs a, const int32_t *__restrict__ tab_base,
-                                                          const int32_t *__restrict__ ntk_base,
-                                                          const int32_t *__restrict__ q_ptr,
-                                                          const float *__restrict__ k_scale,
-                                                          const float *__restrict__ v_scale,
-                                                          const int32_t *__restrict__ plan, int total_q) {
+// MFMA issue of the main loop.  With one row set per wave the compiler's builtin is used.  With
+// two, the wave owns the whole register file of its SIMD lane (256 VGPRs + 256 accumulation
+// registers) and the operands are placed by hand: O accumulators and the Q fragments live in
+// accumulation registers (only MFMAs touch them in the loop), scores and P in VGPRs (the vector
+// unit reads and writes them).  The instruction is then issued through inline assembly, which the
+// compiler's hazard recogniser does not see through: the one software-managed hazard that applies,
+// "MFMA writes VGPRs -> vector instruction reads them" (passes + 3 wait states), is kept by the
+// slot schedule itself, which never reads a score tile within kScoreReadGap slots of the MFMA
+// that completes it.
+constexpr int kScoreReadGap = 4;
+template <bool HAND, bool ZERO>
+__device__ __forceinline__ void mma_scores(f32x16 &d, bf16x8 kf, bf16x8 qf) {
+    if constexpr (!HAND) {
+        if constexpr (ZERO) {
+#pragma unroll
+            for (int x = 0; x < 16; ++x) d[x] = 0.f;
+        }
+        d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf, d, 0, 0, 0);
+    } else if constexpr (ZERO) {
+        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(d) : "v"(kf), "a"(qf));
+    } else {
+        asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(d) : "v"(kf), "a"(qf));
+    }
+}
+// Element access to an O accumulator outside the MFMA stream (rescale, epilogue).  With hand-placed
+// operands the accumulator is never used as a whole by the vector unit: its elements are moved one
+// by one, so the tuple itself stays an accumulation-register value everywhere.
+template <bool HAND>
+__device__ __forceinline__ float acc_get(const f32x16 &v, int i) {
+    if constexpr (!HAND) return v[i];
+    const float e = v[i];
+    float t;
+    asm volatile("v_accvgpr_read_b32 %0, %1" : "=v"(t) : "a"(e));
+    return t;
+}
+template <bool HAND>
+__device__ __forceinline__ void acc_set(f32x16 &v, int i, float t) {
+    if constexpr (!HAND) {
+        v[i] = t;
+    } else {
+        float e;
+        asm volatile("v_accvgpr_write_b32 %0, %1" : "=a"(e) : "v"(t));
+        v[i] = e;
+    }
+}
+template <bool HAND>
+__device__ __forceinline__ void mma_out(f32x16 &d, bf16x8 vf, bf16x8 pf) {
+    if constexpr (!HAND) d = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf, d, 0, 0, 0);
+    else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(d) : "v"(vf), "v"(pf));
+}
+
+template <int D, int G, int NW, int RS, bool FP8>
+__global__ __launch_bounds__(NW * 64, RS == 1 ? 2 : 1) void prefill_kernel(
+    AttnArgs a, const int32_t *__restrict__ tab_base, const int32_t *__restrict__ ntk_base,
+    const int32_t *__restrict__ q_ptr, const float *__restrict__ k_scale, const float *__restrict__ v_scale,
+    const int32_t *__restrict__ plan, int total_q) {
     constexpr int ES = FP8 ? 1 : 2;
-    using C = PrefillCfg<D, G, NW, ES>;
+    using C = PrefillCfg<D, G, NW, RS, ES>;
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     char *const kbuf = lds;                       // [2][kKTile]
     char *const vbuf = lds + 2 * C::kKTile;       // [2][kVTile]
@@ -153,16 +231,23 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_kernel(AttnArgs a, const i
     const int32_t *__restrict__ ntk = ntk_base + (size_t)r * a.max_blocks;
 
     // ---- Q^T operand fragments (registers, whole kernel) ----------------------
-    // score row R = 32*wave + m of the workgroup is (token i0 + R/G, head R%G of the group)
-    bf16x8 qf[C::kKS];
-    const int row_tok = i0 + (32 * wave + m) / G;
-    const int row_head = kvh * G + (32 * wave + m) % G;
-    {
-        const int tokc = min(row_tok, n_new - 1);
-        const char *qp = (const char *)a.q + (((size_t)(q0 + tokc)) * a.hq + row_head) * (D * 2);
+    // score row R = 32*(RS*wave + rs) + m of the workgroup is (token i0 + R/G, head R%G of the group)
+    bf16x8 qf[RS][C::kKS];
+    int row_tok[RS], row_head[RS];
+#pragma unroll
+    for (int rs = 0; rs < RS; ++rs) {
+        const int R = 32 * (RS * wave + rs) + m;
+        row_tok[rs] = i0 + R / G;
+        row_head[rs] = kvh * G + R % G;
+        const int tokc = min(row_tok[rs], n_new - 1);
+        const char *qp = (const char *)a.q + (((size_t)(q0 + tokc)) * a.hq + row_head[rs]) * (D * 2);
 #pragma unroll
         for (int ks = 0; ks < C::kKS; ++ks)
-            qf[ks] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(qp + (16 * ks + 8 * hh) * 2));
+            qf[rs][ks] = __builtin_bit_cast(bf16x8, *(const u32x4 *)(qp + (16 * ks + 8 * hh) * 2));
+        if constexpr (RS > 1) {                          // from here on they live in accumulation registers
+#pragma unroll
+            for (int ks = 0; ks < C::kKS; ++ks) asm volatile("" : "+a"(qf[rs][ks]));
+        }
     }
 
     // ---- table window: lane l of every wave caches entry 64*w + l of window w and of window w+1:
@@ -216,7 +301,6 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_kernel(AttnArgs a, const i
 
     // ---- staging: global -> LDS direct loads -----------------------------------------
     // Wave w stages table entry w of every tile (K rows / V block image of one pool block).
-    static_assert(C::kDmaPerWave == C::kDmaPerEntry && NW == C::kEntries, "one table entry per wave");
     constexpr size_t blk_bytes = (size_t)kBlock * D * ES;
     // K: lane l of direct load i lands at tile row 4i + l/CPR (D=128), chunk position l%CPR, and
     // fetches the chunk (position ^ swizzle(row)) of that row
@@ -224,32 +308,29 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_kernel(AttnArgs a, const i
     auto k_swizzle = [](int rho) -> int {
         return C::kCPR == 16 ? (rho & 15) : C::kCPR == 8 ? ((rho >> 1) & 7) : ((rho >> 2) & 3);
     };
-    const char *k_src[C::kDmaPerWave], *v_src[C::kDmaPerWave];   // kv head 0 of block 0, this lane's chunk
+    // lane offsets inside a pool block, less the 1024 j that load j's immediate offset adds
+    uint32_t k_off[C::kDmaPerWave], v_off[C::kDmaPerWave];
 #pragma unroll
     for (int j = 0; j < C::kDmaPerWave; ++j) {
         const int i = wave * C::kDmaPerWave + j;         // direct load index within the tile
         const int rho = i * kRPI + lane / C::kCPR;       // tile row
         const int pos = lane % C::kCPR;
-        k_src[j] = (const char *)a.k + (rho % kBlock) * C::kRowBytes + ((pos ^ k_swizzle(rho)) * 16);
+        k_off[j] = (rho % kBlock) * C::kRowBytes + ((pos ^ k_swizzle(rho)) * 16) - 1024 * j;
         const int q = j * 64 + lane;                     // 16-byte chunk within the V block image
         if constexpr (FP8) {
-            v_src[j] = (const char *)a.v + q * 16;       // one chunk per head-dim row: image = pool block
+            v_off[j] = q * 16 - 1024 * j;                // one chunk per head-dim row: image = pool block
         } else {
             const int d = q >> 1, vpos = q & 1;
-            v_src[j] = (const char *)a.v + d * 32 + ((vpos ^ ((d >> 3) & 1)) * 16);
+            v_off[j] = d * 32 + ((vpos ^ ((d >> 3) & 1)) * 16) - 1024 * j;
         }
     }
     auto issue_k = [&](int tile, int buf) {
         const size_t off = (size_t)(uint32_t)entry_i(&Win::idx, tile * C::kEntries + wave) * blk_bytes;
-#pragma unroll
-        for (int j = 0; j < C::kDmaPerWave; ++j)
-            dma16(k_src[j] + off, kbuf + buf * C::kKTile + (wave * C::kDmaPerWave + j) * 1024);
+        dma_block<C::kDmaPerWave>((const char *)a.k + off, k_off, kbuf + buf * C::kKTile + wave * C::kDmaPerWave * 1024);
     };
     auto issue_v = [&](int tile, int buf) {
         const size_t off = (size_t)(uint32_t)entry_i(&Win::idx, tile * C::kEntries + wave) * blk_bytes;
-#pragma unroll
-        for (int j = 0; j < C::kDmaPerWave; ++j)
-            dma16(v_src[j] + off, vbuf + buf * C::kVTile + (wave * C::kDmaPerWave + j) * 1024);
+        dma_block<C::kDmaPerWave>((const char *)a.v + off, v_off, vbuf + buf * C::kVTile + wave * C::kDmaPerWave * 1024);
     };
 
     // K operand row m reads key row (m with bits 2,3 swapped); chunk c of row rho sits at
@@ -263,22 +344,39 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_kernel(AttnArgs a, const i
     const int v_lane_off = FP8 ? m * 16 + 8 * hh : m * 32 + ((hh ^ ((m >> 3) & 1)) * 16);
     using frag_t = std::conditional_t<FP8, u32x2, u32x4>;
     auto to_operand = [](frag_t f) -> bf16x8 {
-        if constexpr (FP8) return fp8x8_to_bf16x8(f);
-        else return __builtin_bit_cast(bf16x8, f);
+        if constexpr (FP8) {
+            bf16x8 x = fp8x8_to_bf16x8(f);
+            // the result of a scaled conversion must not be consumed by the next instruction; the
+            // compiler keeps that distance for instructions it issues itself, not for hand-issued MFMAs
+            if constexpr (RS > 1) asm volatile("s_nop 1" : "+v"(x));
+            return x;
+        } else {
+            return __builtin_bit_cast(bf16x8, f);
+        }
     };
 
-    // ---- running state --------------------------------------------------------------
+    // ---- running state (per row set) ---------------------------------------------------
     // m_ref is the same in the two lanes of a row; mx, l_run, the per-tile sums and maxima are
     // per-lane partials over the keys of the lane's half and are combined only when needed.
     const float c = a.scale_log2;
-    float m_ref = -1.0e30f, l_run = 0.f;
-    float mx = -INFINITY;             // partial row maximum (log2 units) of the tile whose scores are pending
-    f32x16 o[C::kDT];
+    float m_ref[RS], l_run[RS];
+    float mx[RS];                     // partial row maximum (log2 units) of the tile whose scores are pending
+    f32x16 o[RS][C::kDT];
 #pragma unroll
-    for (int dt = 0; dt < C::kDT; ++dt)
+    for (int rs = 0; rs < RS; ++rs) {
+        m_ref[rs] = -1.0e30f;
+        l_run[rs] = 0.f;
+        mx[rs] = -INFINITY;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) o[dt][i] = 0.f;
-    f32x16 s_a[2], s_b[2];            // score tiles, ping-pong (2 x 32 keys each)
+        for (int dt = 0; dt < C::kDT; ++dt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) o[rs][dt][i] = 0.f;
+        if constexpr (RS > 1) {
+#pragma unroll
+            for (int dt = 0; dt < C::kDT; ++dt) asm volatile("" : "+a"(o[rs][dt]));   // home: accumulation registers
+        }
+    }
+    f32x16 s_a[RS][2], s_b[RS][2];    // score tiles, ping-pong (2 x 32 keys each)
 
     // Per-chunk exponent constants of tile t.  A raw score of chunk cb becomes
     //   2^(s * mult[cb] + addc[cb]),  mult = sm_scale*log2(e) [* K scale],  addc = -m_ref [+ log2(V scale)]
@@ -318,13 +416,13 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_kernel(AttnArgs a, const i
         }
         return best;
     };
-    auto apply_mask = [&](int t, f32x16 (&s)[2]) {
+    auto apply_mask = [&](int t, f32x16 (&s)[2], int tok) {
 #pragma unroll
         for (int cb = 0; cb < C::kEntries; ++cb) {
             const int ent = t * C::kEntries + cb;
             const int nt = entry_i(&Win::nt, ent);
             const int tail_base = ent >= ncb ? (ent - ncb) * kBlock : -(1 << 28);
-            const int lim = min(nt, row_tok - tail_base + 1) - 8 * hh;
+            const int lim = min(nt, tok - tail_base + 1) - 8 * hh;
 #pragma unroll
             for (int j = 0; j < 8; ++j) {
                 const float x = s[cb >> 1][8 * (cb & 1) + j];
@@ -344,26 +442,84 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_kernel(AttnArgs a, const i
     dma_wait();
     __syncthreads();
     {
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt) {
-#pragma unroll
-            for (int x = 0; x < 16; ++x) s_a[kt][x] = 0.f;
-#pragma unroll
-            for (int ks = 0; ks < C::kKS; ++ks)
-                s_a[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(to_operand(k_frag(kbuf, kt * C::kKS + ks)), qf[ks],
-                                                                   s_a[kt], 0, 0, 0);
+        const TileScale t0 = tile_scale(0);
+        constexpr bool kHand = RS > 1;
+        static_for<2 * C::kKS>([&](auto n_c) {
+            constexpr int n = decltype(n_c)::value;
+            constexpr int kt = n / C::kKS, ks = n % C::kKS;
+            const bf16x8 kf = to_operand(k_frag(kbuf, n));
+            static_for<RS>([&](auto r_c) {
+                constexpr int rs = decltype(r_c)::value;
+                mma_scores<kHand, ks == 0>(s_a[rs][kt], kf, qf[rs][ks]);
+            });
+        });
+        if constexpr (kHand) {
+            // scores written by hand-issued MFMAs: the wait states the vector unit needs before it may
+            // read them; the tiles pass through the statement so that every read is ordered behind it
+            static_for<RS>([&](auto r_c) {
+                constexpr int rs = decltype(r_c)::value;
+                f32x16 &t0 = s_a[rs][0], &t1 = s_a[rs][1];
+                asm volatile("s_nop 7\n\ts_nop 7" : "+v"(t0), "+v"(t1));
+            });
         }
-        mx = row_max(s_a, tile_scale(0));
+#pragma unroll
+        for (int rs = 0; rs < RS; ++rs) mx[rs] = row_max(s_a[rs], t0);
     }
 
+    // The reference maxima are refreshed (and O, l rescaled) only when some row's pending maximum
+    // outgrew its reference by more than the slack: a cold path.
+    // Side path, before tile t is taken up: partial blocks / causal tail / end of the sequence in it
+    // (pad slots may hold any finite value, so the pending maxima are taken again after masking).
+    auto premask = [&](int t, f32x16 (&sc)[RS][2]) {
+        if (!(GF_ABL & 32) && ((mbits_cur >> ((t * C::kEntries) & 63)) & ((1u << C::kEntries) - 1)) != 0) {
+            const TileScale ts = tile_scale(t);
+#pragma unroll
+            for (int rs = 0; rs < RS; ++rs) {
+                apply_mask(t, sc[rs], row_tok[rs]);
+                mx[rs] = row_max(sc[rs], ts);
+            }
+        }
+    };
+    auto need_rescale = [&]() -> bool {
+        bool grow = false;
+#pragma unroll
+        for (int rs = 0; rs < RS; ++rs) grow |= mx[rs] > m_ref[rs] + kRescaleSlack;
+        return __builtin_amdgcn_ballot_w64(grow) != 0;
+    };
+    auto rescale = [&]() {
+        if constexpr (RS > 1) asm volatile("s_nop 7\n\ts_nop 7" ::: "memory");   // O written by hand-issued MFMAs
+#pragma unroll
+        for (int rs = 0; rs < RS; ++rs) {
+            const float m_new = fmaxf(m_ref[rs], fmaxf(mx[rs], other_half(mx[rs])));
+            const float alpha = fast_exp2(m_ref[rs] - m_new);
+            m_ref[rs] = m_new;
+            l_run[rs] *= alpha;
+#pragma unroll
+            for (int dt = 0; dt < C::kDT; ++dt)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc_set<(RS > 1)>(o[rs][dt], i, acc_get<(RS > 1)>(o[rs][dt], i) * alpha);
+        }
+    };
+
     // ---- one iteration: softmax + P*V of tile t (scores in sc), scores of tile t+1 -> sn ----
-    auto body = [&](int t, f32x16 (&sc)[2], f32x16 (&sn)[2]) {
+#ifdef GF_PROF
+    unsigned long long pf_pre = 0, pf_str = 0, pf_end = 0, pf_mid = 0;
+    const unsigned long long pf_start = __builtin_readcyclecounter();
+#endif
+    auto body = [&](int t, f32x16 (&sc)[RS][2], f32x16 (&sn)[RS][2]) {
+#ifdef GF_PROF
+        const unsigned long long pf_a = __builtin_readcyclecounter();
+#endif
         const bool has_next = t + 1 < ntiles;
         const bool k2 = t + 2 < ntiles;
         // operand stream of this iteration: the K fragments of tile t+1, then the V fragments of tile t,
-        // fetched from LDS in groups of kGroup, one group ahead (one wait per group, not per MFMA)
-        constexpr int NSLOT = C::kQK + C::kPV;
-        static_assert(NSLOT % kGroup == 0, "whole groups");
+        // fetched from LDS in groups of kGroup, ahead of their use (one wait per group, not per MFMA);
+        // every fragment feeds one MFMA per row set
+        constexpr int NSLOT = C::kSlots;
+        constexpr bool kHand = RS > 1;
+        constexpr int kGroups = C::kFrags / kGroup;
+        constexpr int kLdsPerFrag = 1;               // LDS operations per fragment
+        static_assert(C::kFrags % kGroup == 0, "whole groups");
         const char *kb = kbuf + ((t + 1) & 1) * C::kKTile;
         const char *vb = vbuf + (t & 1) * C::kVTile + v_lane_off;
         auto frag = [&](int n) -> frag_t {
@@ -371,10 +527,12 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_kernel(AttnArgs a, const i
             const int j = n - C::kQK;
             return *(const frag_t *)(vb + (j / C::kDT) * C::kVBlk + 32 * (j % C::kDT) * C::kVRow);
         };
-        frag_t f[2][kGroup];
+        frag_t f[kDepth][kGroup];
         if constexpr (!(GF_ABL & 1)) {
 #pragma unroll
-            for (int i = 0; i < kGroup; ++i) f[0][i] = frag(i);
+            for (int gg = 0; gg < kDepth - 1; ++gg)
+#pragma unroll
+                for (int i = 0; i < kGroup; ++i) f[gg][i] = frag(gg * kGroup + i);
         }
         // the table window slides at the end of this iteration if the next tile opens a new one:
         // fetch the window after next now, adopt it after the wait that precedes the barrier
@@ -384,100 +542,121 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_kernel(AttnArgs a, const i
         const TileScale tn = tile_scale(t + 1);      // ... and of the next (for its row maximum)
         if (!(GF_ABL & 8) && k2) issue_k(t + 2, t & 1);             // K(t+2) replaces K(t), read last iteration
         if (!(GF_ABL & 8) && has_next) issue_v(t + 1, (t + 1) & 1); // V(t+1) replaces V(t-1)
-        // side path: partial blocks / causal tail / end of the sequence in tile t
-        if (!(GF_ABL & 32) && ((mbits_cur >> ((t * C::kEntries) & 63)) & ((1u << C::kEntries) - 1)) != 0) {
-            apply_mask(t, sc);
-            mx = row_max(sc, ts);
-        }
-        // refresh the reference maximum only when some row outgrew it
-        if (__builtin_amdgcn_ballot_w64(mx > m_ref + kRescaleSlack) != 0) {
-            const float m_new = fmaxf(m_ref, fmaxf(mx, other_half(mx)));
-            const float alpha = fast_exp2(m_ref - m_new);
-            m_ref = m_new;
-            l_run *= alpha;
-#pragma unroll
-            for (int dt = 0; dt < C::kDT; ++dt) o[dt] *= alpha;
-        }
+        premask(t, sc);
+        if (need_rescale()) rescale();
 
-        // main stream: NSLOT slots of {MFMA, its share of the vector work}
-        constexpr int kExpEnd = NSLOT - 5;           // last slot that may carry an exponential
-        constexpr auto exp_slot = [](int e) constexpr -> int { return (e * kExpEnd) / 32; };
-        static_assert((7 * kExpEnd) / 32 + 1 < C::kQK && (15 * kExpEnd) / 32 + 1 < C::kQK + C::kDT &&
-                          (23 * kExpEnd) / 32 + 1 < C::kQK + 2 * C::kDT && (31 * kExpEnd) / 32 + 1 < C::kQK + 3 * C::kDT,
-                      "every chunk is packed before its P*V MFMA");
-        uint32_t pw[C::kEntries][4];                 // P^T operand, 2 bf16 per word
-        float pe[32];                                // exponentials awaiting their bf16 pack
-        float addc[kAcc], psum[kAcc], vmax[kAcc];
+        // main stream: NSLOT slots of {MFMA, its share of the vector work}; slot i uses fragment
+        // i / RS for row set i % RS
+        constexpr int kExps = 32 * RS;               // exponentials per tile, in the order (key, row set)
+        constexpr int kExpEnd = NSLOT - 4 * RS - 1;  // last slot that may carry an exponential
+        constexpr auto exp_slot = [](int x) constexpr -> int { return (x * kExpEnd) / kExps; };
+        constexpr auto packed_in_time = [exp_slot]() constexpr -> bool {
+            for (int cb = 0; cb < C::kEntries; ++cb)
+                for (int rs = 0; rs < RS; ++rs)
+                    if (exp_slot((8 * cb + 7) * RS + rs) + 1 >= RS * (C::kQK + cb * C::kDT) + rs) return false;
+            return true;
+        };
+        static_assert(packed_in_time(), "every chunk is packed before its first P*V MFMA");
+        bf16x8 opnd;                                 // the fragment in use, as an MFMA operand
+        uint32_t pw[RS][C::kEntries][4];             // P^T operands, 2 bf16 per word
+        float pe[RS][32];                            // exponentials awaiting their bf16 pack
+        float addc[RS][kAcc], psum[RS][kAcc], vmax[RS][kAcc];
 #pragma unroll
-        for (int cb = 0; cb < kAcc; ++cb) {
-            addc[cb] = ts.lvs[cb] - m_ref;
-            psum[cb] = 0.f;
-            vmax[cb] = -INFINITY;
-        }
-        __builtin_amdgcn_s_waitcnt(kWaitLds);        // group 0 has arrived
+        for (int rs = 0; rs < RS; ++rs)
+#pragma unroll
+            for (int cb = 0; cb < kAcc; ++cb) {
+                addc[rs][cb] = ts.lvs[cb] - m_ref[rs];
+                psum[rs][cb] = 0.f;
+                vmax[rs][cb] = -INFINITY;
+            }
+#ifdef GF_PROF
+        const unsigned long long pf_b = __builtin_readcyclecounter();
+#endif
+        __builtin_amdgcn_s_waitcnt(wait_lds((kDepth - 2) * kGroup * kLdsPerFrag));        // group 0 has arrived
         __builtin_amdgcn_sched_barrier(0);
         static_for<NSLOT>([&](auto slot_c) {
             constexpr int i = decltype(slot_c)::value;
-            constexpr int g = i / kGroup;
-            if constexpr (i < C::kQK) {
-                constexpr int kt = i / C::kKS, ks = i % C::kKS;
-                if constexpr (ks == 0) {
-#pragma unroll
-                    for (int x = 0; x < 16; ++x) sn[kt][x] = 0.f;
-                }
-                sn[kt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(to_operand(f[g & 1][i % kGroup]), qf[ks], sn[kt], 0, 0, 0);
+            constexpr int n = i / RS, rs = i % RS;   // fragment, row set
+            constexpr int g = n / kGroup;
+            if constexpr (n < C::kQK) {
+                constexpr int kt = n / C::kKS, ks = n % C::kKS;
+                if constexpr (rs == 0) opnd = to_operand(f[g % kDepth][n % kGroup]);
+                mma_scores<kHand, ks == 0>(sn[rs][kt], opnd, qf[rs][ks]);
             } else {
-                constexpr int j = i - C::kQK;
+                if constexpr (kHand && i == C::kQK * RS) {
+                    // no read of the new score tiles is placed ahead of the P*V phase (the schedule keeps
+                    // kScoreReadGap slots between a hand-issued MFMA and the first read of its result)
+                    static_for<RS>([&](auto r_c) {
+                        constexpr int r2 = decltype(r_c)::value;
+                        f32x16 &t0 = sn[r2][0], &t1 = sn[r2][1];
+                        asm volatile("" : "+v"(t0), "+v"(t1));
+                    });
+                }
+                constexpr int j = n - C::kQK;
                 constexpr int cb = j / C::kDT, dt = j % C::kDT;
-                u32x4 pq = {pw[cb][0], pw[cb][1], pw[cb][2], pw[cb][3]};
-                o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(to_operand(f[g & 1][i % kGroup]),
-                                                                __builtin_bit_cast(bf16x8, pq), o[dt], 0, 0, 0);
-                // vector share: running maximum of the next tile's scores, two elements per v_max3
+                u32x4 pq = {pw[rs][cb][0], pw[rs][cb][1], pw[rs][cb][2], pw[rs][cb][3]};
+                if constexpr (rs == 0) opnd = to_operand(f[g % kDepth][n % kGroup]);
+                mma_out<kHand>(o[rs][dt], opnd, __builtin_bit_cast(bf16x8, pq));
+                // vector share: running maxima of the next tile's scores, two elements per v_max3
                 constexpr int kMaxPerSlot = 32 / C::kPV;
                 static_assert(kMaxPerSlot % 2 == 0, "maximum taken in pairs");
-                static_for<kMaxPerSlot / 2>([&](auto e_c) {
-                    constexpr int idx = j * kMaxPerSlot + 2 * decltype(e_c)::value;
-                    float &vm = vmax[acc_of(idx / 8)];
-                    vm = fmaxf(fmaxf(vm, sn[idx / 16][idx % 16]), sn[idx / 16][idx % 16 + 1]);
+                if constexpr (!(GF_ABL & 128)) static_for<kMaxPerSlot / 2>([&](auto e_c) {
+                    constexpr int y = (i - C::kQK * RS) * kMaxPerSlot + 2 * decltype(e_c)::value;   // in [0, 32 RS)
+                    constexpr int r2 = y / 32, idx = y % 32;
+                    // the score tile read here was completed by slot RS * kKS * (idx / 16 + 1) - RS + r2
+                    static_assert(i - (RS * C::kKS * (idx / 16 + 1) - RS + r2) >= kScoreReadGap, "MFMA result read too early");
+                    float &vm = vmax[r2][acc_of(idx / 8)];
+                    vm = fmaxf(fmaxf(vm, sn[r2][idx / 16][idx % 16]), sn[r2][idx / 16][idx % 16 + 1]);
                     asm volatile("" : "+v"(vm));      // keep the running maximum in this slot
                 });
             }
-            // the first MFMA of a group is followed by the fetch of the next group
-            if constexpr (!(GF_ABL & 1) && i % kGroup == 0 && i + kGroup < NSLOT) {
+            // the first MFMA of a group is followed by the fetch of a later group
+            if constexpr (!(GF_ABL & 1) && rs == 0 && n % kGroup == 0 && g + kDepth - 1 < kGroups) {
 #pragma unroll
-                for (int x = 0; x < kGroup; ++x) f[(g + 1) & 1][x] = frag(i + kGroup + x);
+                for (int x = 0; x < kGroup; ++x) f[(g + kDepth - 1) % kDepth][x] = frag((g + kDepth - 1) * kGroup + x);
             }
-            // vector share of every slot: the 32 exponentials of tile t are spread evenly over the
+            // vector share of every slot: the exponentials of tile t are spread evenly over the
             // slots up to kExpEnd.  An exponential joins the row sum one step later (its consumer
             // is never the next instruction), each pair is packed to bf16 one slot after its second
-            // exponential, and chunk c is complete before its first P*V MFMA.
-            static_for<32>([&](auto e_c) {
-                constexpr int e2 = decltype(e_c)::value;
-                if constexpr (exp_slot(e2) == i) {
+            // exponential, and chunk c of a row set is complete before its first P*V MFMA.
+            if constexpr (!(GF_ABL & 128)) static_for<kExps>([&](auto e_c) {
+                constexpr int x = decltype(e_c)::value;
+                constexpr int e2 = x / RS, r2 = x % RS;
+                if constexpr (exp_slot(x) == i) {
                     constexpr int cb = acc_of(e2 / 8);
-                    const float x = sc[e2 / 16][e2 % 16];
-                    pe[e2] = (GF_ABL & 2) ? x * ts.mult[cb] + addc[cb] : fast_exp2(x * ts.mult[cb] + addc[cb]);
-                    if constexpr (e2 > 0) psum[acc_of((e2 - 1) / 8)] += pe[e2 - 1];
-                    asm volatile("" : "+v"(psum[acc_of(e2 > 0 ? (e2 - 1) / 8 : 0)]), "+v"(pe[e2]));   // stay in this slot
+                    const float sv = sc[r2][e2 / 16][e2 % 16];
+                    const float arg = sv * ts.mult[cb] + addc[r2][cb];
+                    pe[r2][e2] = (GF_ABL & 2) ? arg : fast_exp2(arg);
+                    constexpr int xp = x > 0 ? x - 1 : 0;                  // the exponential before this one
+                    if constexpr (x > 0) psum[xp % RS][acc_of(xp / RS / 8)] += pe[xp % RS][xp / RS];
+                    asm volatile("" : "+v"(psum[xp % RS][acc_of(xp / RS / 8)]), "+v"(pe[r2][e2]));   // stay in this slot
                 }
-                if constexpr ((e2 & 1) && exp_slot(e2) + 1 == i) {
-                    const f32x2 p = {pe[e2 - 1], pe[e2]};
-                    pw[e2 / 8][(e2 % 8) / 2] = __builtin_bit_cast(uint32_t, __builtin_convertvector(p, bf16x2));
-                    if constexpr (e2 == 31) psum[acc_of(3)] += pe[31];
+                if constexpr ((e2 & 1) && exp_slot(x) + 1 == i) {
+                    const f32x2 p = {pe[r2][e2 - 1], pe[r2][e2]};
+                    pw[r2][e2 / 8][(e2 % 8) / 2] = __builtin_bit_cast(uint32_t, __builtin_convertvector(p, bf16x2));
+                    if constexpr (x == kExps - 1) psum[r2][acc_of(3)] += pe[r2][31];
                 }
             });
             // one wait per group, at the end of the slot before it: the whole group has arrived
-            if constexpr ((i + 1) % kGroup == 0 && i + 1 < NSLOT) __builtin_amdgcn_s_waitcnt(kWaitLds);
+            if constexpr (rs == RS - 1 && (n + 1) % kGroup == 0 && n + 1 < C::kFrags) {
+                // groups still in flight after group g+1: those fetched behind it
+                constexpr int behind = (g + kDepth - 1 < kGroups ? g + kDepth - 1 : kGroups - 1) - (g + 1);
+                __builtin_amdgcn_s_waitcnt(wait_lds(behind * kGroup * kLdsPerFrag));
+            }
             __builtin_amdgcn_sched_barrier(0);
         });
-        {
+#ifdef GF_PROF
+        const unsigned long long pf_c = __builtin_readcyclecounter();
+#endif
+#pragma unroll
+        for (int rs = 0; rs < RS; ++rs) {
             float best = -INFINITY;
 #pragma unroll
             for (int cb = 0; cb < kAcc; ++cb) {
-                l_run += psum[cb] * ts.ivs[cb];
-                best = fmaxf(best, vmax[cb] * tn.mult[cb]);
+                l_run[rs] += psum[rs][cb] * ts.ivs[cb];
+                best = fmaxf(best, vmax[rs][cb] * tn.mult[cb]);
             }
-            mx = best;
+            mx[rs] = best;
         }
         if (!(GF_ABL & 16)) dma_wait();                              // this wave's direct loads have landed ...
         // (the window fetch is waited for here, nowhere earlier)
@@ -489,7 +668,14 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_kernel(AttnArgs a, const i
             mbits_nxt = adopt_window(win + 2, w_nxt);
             ++win;
         }
+#ifdef GF_PROF
+        const unsigned long long pf_d = __builtin_readcyclecounter();
+#endif
         if (!(GF_ABL & 4)) __syncthreads();                             // ... and every wave's are visible
+#ifdef GF_PROF
+        const unsigned long long pf_e = __builtin_readcyclecounter();
+        pf_pre += pf_b - pf_a; pf_str += pf_c - pf_b; pf_mid += pf_d - pf_c; pf_end += pf_e - pf_d;
+#endif
     };
 
     int t = 0;
@@ -498,24 +684,37 @@ __global__ __launch_bounds__(NW * 64, 2) void prefill_kernel(AttnArgs a, const i
         body(t + 1, s_b, s_a);
     }
     if (t < ntiles) body(t, s_a, s_b);
+#ifdef GF_PROF
+    if (a.lse && lane == 0) {
+        float *pf = a.lse + ((size_t)blockIdx.x * NW + wave) * 8;
+        pf[0] = (float)ntiles; pf[1] = (float)pf_pre; pf[2] = (float)pf_str; pf[3] = (float)pf_mid; pf[4] = (float)pf_end;
+        pf[5] = (float)(__builtin_readcyclecounter() - pf_start);
+    }
+    const bool pf_skip_lse = true;
+#else
+    const bool pf_skip_lse = false;
+#endif
     // ---- epilogue: normalise, round to bf16, store ------------------------------------
-    {
-        const float l_tot = l_run + other_half(l_run);
-        if (row_tok < n_new) {
+    if constexpr (RS > 1) asm volatile("s_nop 7\n\ts_nop 7" ::: "memory");   // O written by hand-issued MFMAs
+#pragma unroll
+    for (int rs = 0; rs < RS; ++rs) {
+        const float l_tot = l_run[rs] + other_half(l_run[rs]);
+        if (row_tok[rs] < n_new) {
             const float inv = 1.f / l_tot;
-            char *op = (char *)a.o + (((size_t)(q0 + row_tok)) * a.hq + row_head) * (D * 2);
+            char *op = (char *)a.o + (((size_t)(q0 + row_tok[rs])) * a.hq + row_head[rs]) * (D * 2);
 #pragma unroll
             for (int dt = 0; dt < C::kDT; ++dt)
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
-                    f32x4 v4 = {o[dt][4 * q] * inv, o[dt][4 * q + 1] * inv, o[dt][4 * q + 2] * inv,
-                                o[dt][4 * q + 3] * inv};
+                    f32x4 v4;
+#pragma unroll
+                    for (int x = 0; x < 4; ++x) v4[x] = acc_get<(RS > 1)>(o[rs][dt], 4 * q + x) * inv;
                     const bf16x4 b4 = __builtin_convertvector(v4, bf16x4);
                     *(bf16x4 *)(op + (32 * dt + 8 * q + 4 * hh) * 2) = b4;
                 }
-            if (a.lse && hh == 0)
-                a.lse[(size_t)(q0 + row_tok) * a.hq + row_head] =
-                    (m_ref + __builtin_log2f(l_tot)) * 0.6931471805599453f;
+            if (a.lse && hh == 0 && !pf_skip_lse)
+                a.lse[(size_t)(q0 + row_tok[rs]) * a.hq + row_head[rs]] =
+                    (m_ref[rs] + __builtin_log2f(l_tot)) * 0.6931471805599453f;
         }
     }
 }
@@ -601,8 +800,10 @@ static hipError_t launch_prefill_t(const AttnArgs &a, int kv_dtype, const int32_
 template <int D, int G, int NW, bool FP8>
 static hipError_t launch_prefill_k(const AttnArgs &a, const int32_t *q_ptr, int32_t total_q, int32_t *plan,
                                    hipStream_t s) {
-    using C = PrefillCfg<D, G, NW, FP8 ? 1 : 2>;
-    auto kern = prefill_kernel<D, G, NW, FP8>;
+    constexpr int RS = kPrefillRowSets;
+    using C = PrefillCfg<D, G, NW, RS, FP8 ? 1 : 2>;
+    static_assert(C::kRows == kPrefillRows, "work list and kernel agree on the tile height");
+    auto kern = prefill_kernel<D, G, NW, RS, FP8>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, C::kLds);
@@ -626,8 +827,8 @@ static hipError_t launch_prefill_k(const AttnArgs &a, const int32_t *q_ptr, int3
 size_t prefill_plan_items(int32_t total_q, int32_t num_req, int bm) { return (size_t)total_q / bm + num_req; }
 
 size_t prefill_plan_bytes(int32_t total_q, int32_t num_req, int group) {
-    // 4-wave workgroups: 128 score rows = 128 / group new tokens per item
-    return (2 + 2 * prefill_plan_items(total_q, num_req, 128 / group)) * sizeof(int32_t);
+    // one item = kPrefillRows score rows = kPrefillRows / group new tokens
+    return (2 + 2 * prefill_plan_items(total_q, num_req, kPrefillRows / group)) * sizeof(int32_t);
 }
 
 hipError_t launch_prefill(const AttnArgs &a, int head_dim, int group, int kv_dtype, const int32_t *q_ptr,
@@ -636,7 +837,7 @@ hipError_t launch_prefill(const AttnArgs &a, int head_dim, int group, int kv_dty
     // 4-wave workgroups, two resident per CU: their barriers stay local to one wave per SIMD and
     // the two workgroups drift apart, so one's vector phases fall under the other's MFMAs
 #define GF_CASE(DD, GG) \
-    if (head_dim == DD && group == GG) return launch_prefill_t<DD, GG, 4>(a, kv_dtype, q_ptr, total_q, plan, s);
+    if (head_dim == DD && group == GG) return launch_prefill_t<DD, GG, kPrefillWaves>(a, kv_dtype, q_ptr, total_q, plan, s);
     GF_CASE(64, 1) GF_CASE(64, 2) GF_CASE(64, 4) GF_CASE(64, 8)
     GF_CASE(128, 1) GF_CASE(128, 2) GF_CASE(128, 4) GF_CASE(128, 8)
 #undef GF_CASE
