@@ -65,7 +65,8 @@ struct PrefillCfg {
     static constexpr int kVBlk = D * kBlock * ES;    // one V block in LDS (bytes)
     static constexpr int kVRow = kBlock * ES;        // one head-dim row of a V block (bytes)
     static constexpr int kVTile = kEntries * kVBlk;
-    static constexpr int kLds = 2 * kKTile + 2 * kVTile;
+    static constexpr int kVBufs = 3;                 // V tiles in LDS (see the pipeline notes in the kernel)
+    static constexpr int kLds = 2 * kKTile + kVBufs * kVTile;
     static constexpr int kDmaPerTile = kKTile / 1024;      // 1 KB wave-wide direct loads per tensor per tile
     static constexpr int kDmaPerWave = kDmaPerTile / NW;
     static constexpr int kDmaPerEntry = kDmaPerTile / kEntries;
@@ -81,18 +82,27 @@ struct PrefillCfg {
 };
 
 constexpr int kPrefillWaves = 4;
-#ifndef GF_RS
-#define GF_RS 2
+// Row sets per wave.  A bf16 pool runs one (two workgroups per CU cover each other's stalls; measured
+// faster there); an e4m3 pool runs two, where every fragment converted to bf16 serves two MFMAs.
+#ifdef GF_RS
+constexpr int prefill_row_sets(bool) { return GF_RS; }
+#else
+constexpr int prefill_row_sets(bool fp8) { return fp8 ? 2 : 1; }
 #endif
-constexpr int kPrefillRowSets = GF_RS;
-constexpr int kPrefillRows = 32 * kPrefillWaves * kPrefillRowSets;   // score rows per workgroup
+constexpr int kPrefillRowsMin = 32 * kPrefillWaves;   // fewest score rows a workgroup covers (sizes the work list)
 
 constexpr float kRescaleSlack = 8.0f;   // log2 units a row max may exceed its reference
-constexpr int kGroup = 4;               // LDS operand fragments fetched (and waited for) together
-#ifndef GF_DEPTH
-#define GF_DEPTH 2
+// LDS operand fragments live in a ring of kRing register sets.  The fetches of fragments
+// n + kAhead .. n + kAhead + kFetch - 1 are issued right behind the first MFMA of fragment n
+// (n a multiple of kFetch), and the wave waits once per kFetch fragments, for exactly those.
+#ifndef GF_AHEAD
+#define GF_AHEAD 4
 #endif
-constexpr int kDepth = GF_DEPTH;        // fragment groups in registers (kDepth - 1 in flight behind the one in use)
+#ifndef GF_FETCH
+#define GF_FETCH 4
+#endif
+constexpr int kRing = 8, kAhead = GF_AHEAD, kFetch = GF_FETCH;
+static_assert(kAhead % kFetch == 0 && kAhead + kFetch <= kRing, "a fetch never lands in a register set still to be used");
 // s_waitcnt lgkmcnt(n), other counters untouched
 constexpr int wait_lds(int n) { return 0xC07F | (n << 8); }
 #ifndef GF_ABL
@@ -113,25 +123,17 @@ __device__ __forceinline__ void static_for(F &&f) {
     static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
 
-// 16-byte-per-lane global -> LDS direct loads: lane l of load j fetches the 16 bytes at
-// base + off[j] + 1024 j (uniform base in SGPRs, 32-bit lane offset) and writes LDS bytes
-// [dst + 1024 j + 16 l, +16): the instruction's immediate offset is added to both addresses, so one
-// M0 value serves the N loads of a block.  Issued through inline assembly so that they are ordered
-// by hand: the kernel waits for its own direct loads (dma_wait) right before the workgroup barrier
-// that publishes a tile, instead of before every LDS read that follows their issue.
-template <int N>
-__device__ __forceinline__ void dma_block(const void *base, const uint32_t (&off)[N], void *lds_dst) {
-    static_assert(N == 1 || N == 2 || N == 4, "1 KB loads per block and wave");
+// 16-byte-per-lane global -> LDS direct load: lane l of load J of a block fetches the 16 bytes at
+// base + off + 1024 J (uniform base in SGPRs, 32-bit lane offset) and writes LDS bytes
+// [dst + 1024 J + 16 l, +16): the instruction's immediate offset is added to both addresses, so one
+// base and one M0 value serve all loads of a block.  Issued through inline assembly so that they
+// are ordered by hand: the kernel waits for its own direct loads (dma_wait) right before the
+// workgroup barrier that publishes a tile, instead of before every LDS read that follows them.
+template <int J>
+__device__ __forceinline__ void dma_load(const void *base, uint32_t off, void *lds_dst) {
     const uint32_t dst = (uint32_t)(uintptr_t)(lptr_t)lds_dst;
-    if constexpr (N == 1)
-        asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %2, %1" ::"s"(dst), "s"(base), "v"(off[0]) : "memory", "m0");
-    if constexpr (N == 2)
-        asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %2, %1\n\tglobal_load_lds_dwordx4 %3, %1 offset:1024"
-                     ::"s"(dst), "s"(base), "v"(off[0]), "v"(off[1]) : "memory", "m0");
-    if constexpr (N == 4)
-        asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %2, %1\n\tglobal_load_lds_dwordx4 %3, %1 offset:1024\n\t"
-                     "global_load_lds_dwordx4 %4, %1 offset:2048\n\tglobal_load_lds_dwordx4 %5, %1 offset:3072"
-                     ::"s"(dst), "s"(base), "v"(off[0]), "v"(off[1]), "v"(off[2]), "v"(off[3]) : "memory", "m0");
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %2, %1 offset:%3"
+                 ::"s"(dst), "s"(base), "v"(off), "n"(1024 * J) : "memory", "m0");
 }
 __device__ __forceinline__ void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
@@ -195,7 +197,7 @@ __global__ __launch_bounds__(NW * 64, RS == 1 ? 2 : 1) void prefill_kernel(
     using C = PrefillCfg<D, G, NW, RS, ES>;
     extern __shared__ __attribute__((aligned(1024))) char lds[];
     char *const kbuf = lds;                       // [2][kKTile]
-    char *const vbuf = lds + 2 * C::kKTile;       // [2][kVTile]
+    char *const vbuf = lds + 2 * C::kKTile;       // [kVBufs][kVTile]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -324,13 +326,23 @@ __global__ __launch_bounds__(NW * 64, RS == 1 ? 2 : 1) void prefill_kernel(
             v_off[j] = d * 32 + ((vpos ^ ((d >> 3) & 1)) * 16) - 1024 * j;
         }
     }
+    // address of the pool block behind table entry (tile, this wave), for K or V
+    auto block_of = [&](const void *pool, int tile) -> const char * {
+        return (const char *)pool + (size_t)(uint32_t)entry_i(&Win::idx, tile * C::kEntries + wave) * blk_bytes;
+    };
     auto issue_k = [&](int tile, int buf) {
-        const size_t off = (size_t)(uint32_t)entry_i(&Win::idx, tile * C::kEntries + wave) * blk_bytes;
-        dma_block<C::kDmaPerWave>((const char *)a.k + off, k_off, kbuf + buf * C::kKTile + wave * C::kDmaPerWave * 1024);
+        const char *src = block_of(a.k, tile);
+        static_for<C::kDmaPerWave>([&](auto j_c) {
+            constexpr int j = decltype(j_c)::value;
+            dma_load<j>(src, k_off[j], kbuf + buf * C::kKTile + wave * C::kDmaPerWave * 1024);
+        });
     };
     auto issue_v = [&](int tile, int buf) {
-        const size_t off = (size_t)(uint32_t)entry_i(&Win::idx, tile * C::kEntries + wave) * blk_bytes;
-        dma_block<C::kDmaPerWave>((const char *)a.v + off, v_off, vbuf + buf * C::kVTile + wave * C::kDmaPerWave * 1024);
+        const char *src = block_of(a.v, tile);
+        static_for<C::kDmaPerWave>([&](auto j_c) {
+            constexpr int j = decltype(j_c)::value;
+            dma_load<j>(src, v_off[j], vbuf + buf * C::kVTile + wave * C::kDmaPerWave * 1024);
+        });
     };
 
     // K operand row m reads key row (m with bits 2,3 swapped); chunk c of row rho sits at
@@ -505,7 +517,13 @@ __global__ __launch_bounds__(NW * 64, RS == 1 ? 2 : 1) void prefill_kernel(
 #ifdef GF_PROF
     unsigned long long pf_pre = 0, pf_str = 0, pf_end = 0, pf_mid = 0;
     const unsigned long long pf_start = __builtin_readcyclecounter();
+    const unsigned long long pf_rt0 = __builtin_amdgcn_s_memrealtime();
 #endif
+    frag_t f[kRing];                  // operand fragments; the first kAhead of an iteration are fetched by the one before
+    if constexpr (!(GF_ABL & 1)) {
+#pragma unroll
+        for (int x = 0; x < kAhead; ++x) f[x] = k_frag(kbuf + C::kKTile, x);   // K(1), staged by the prologue
+    }
     auto body = [&](int t, f32x16 (&sc)[RS][2], f32x16 (&sn)[RS][2]) {
 #ifdef GF_PROF
         const unsigned long long pf_a = __builtin_readcyclecounter();
@@ -513,37 +531,42 @@ __global__ __launch_bounds__(NW * 64, RS == 1 ? 2 : 1) void prefill_kernel(
         const bool has_next = t + 1 < ntiles;
         const bool k2 = t + 2 < ntiles;
         // operand stream of this iteration: the K fragments of tile t+1, then the V fragments of tile t,
-        // fetched from LDS in groups of kGroup, ahead of their use (one wait per group, not per MFMA);
+        // fetched from LDS kAhead fragments ahead of their use;
         // every fragment feeds one MFMA per row set
         constexpr int NSLOT = C::kSlots;
         constexpr bool kHand = RS > 1;
-        constexpr int kGroups = C::kFrags / kGroup;
         constexpr int kLdsPerFrag = 1;               // LDS operations per fragment
-        static_assert(C::kFrags % kGroup == 0, "whole groups");
+        // Pipeline of one iteration (slots of the MFMA stream):
+        //   kStageKSlot..  direct loads of K(t+2), one per slot, into the buffer K(t) left (its readers
+        //                  passed the barrier of the iteration before)
+        //   kStageVSlot..  direct loads of V(t+1) into the buffer V(t-2) left: V(t-1) may still be read
+        //                  by a wave that is behind this one's last barrier, hence three V buffers
+        //   kSyncSlot      wait for this wave's loads, workgroup barrier: K(t+2) and V(t+1) are published;
+        //                  it comes after the last read of K(t+1) and before the first read of K(t+2)
+        //   from fragment kFirstNext on, the fetches are those of the next iteration's first fragments
+        constexpr int kStageKSlot = RS, kStageVSlot = RS * (1 + C::kDmaPerWave);
+        constexpr int kFirstNext = C::kFrags - kAhead;
+        constexpr int kSyncSlot = RS * (C::kQK + C::kPV / 2 < kFirstNext ? C::kQK + C::kPV / 2 : kFirstNext);
+        static_assert(C::kFrags % kRing == 0 && kAhead <= C::kQK, "the ring position of a fragment is the same in every iteration");
+        static_assert(kSyncSlot >= RS * C::kQK && kSyncSlot <= RS * kFirstNext, "barrier between the K reads");
+        static_assert(kStageVSlot + RS * C::kDmaPerWave <= kSyncSlot, "loads issued before the wait");
+        static_assert(C::kFrags % kFetch == 0, "whole wait groups");
         const char *kb = kbuf + ((t + 1) & 1) * C::kKTile;
-        const char *vb = vbuf + (t & 1) * C::kVTile + v_lane_off;
+        const char *vb = vbuf + (t % C::kVBufs) * C::kVTile + v_lane_off;
+        const char *kb_next = kbuf + (t & 1) * C::kKTile;          // K(t+2), once this iteration's barrier is passed
         auto frag = [&](int n) -> frag_t {
             if (n < C::kQK) return k_frag(kb, n);
             const int j = n - C::kQK;
             return *(const frag_t *)(vb + (j / C::kDT) * C::kVBlk + 32 * (j % C::kDT) * C::kVRow);
         };
-        frag_t f[kDepth][kGroup];
-        if constexpr (!(GF_ABL & 1)) {
-#pragma unroll
-            for (int gg = 0; gg < kDepth - 1; ++gg)
-#pragma unroll
-                for (int i = 0; i < kGroup; ++i) f[gg][i] = frag(gg * kGroup + i);
-        }
-        // the table window slides at the end of this iteration if the next tile opens a new one:
-        // fetch the window after next now, adopt it after the wait that precedes the barrier
+        // the table window slides in this iteration if the next tile opens a new one: fetch the
+        // window after next now, adopt it after the wait that precedes the barrier
         const bool slide = (t + 1) * C::kEntries == 64 * (win + 1);
         if (slide) load_window(win + 2, w_new);
         const TileScale ts = tile_scale(t);          // constants of this tile ...
         const TileScale tn = tile_scale(t + 1);      // ... and of the next (for its row maximum)
-        if (!(GF_ABL & 8) && k2) issue_k(t + 2, t & 1);             // K(t+2) replaces K(t), read last iteration
-        if (!(GF_ABL & 8) && has_next) issue_v(t + 1, (t + 1) & 1); // V(t+1) replaces V(t-1)
         premask(t, sc);
-        if (need_rescale()) rescale();
+        if ((!(GF_ABL & 64) || t == 0) && need_rescale()) rescale();
 
         // main stream: NSLOT slots of {MFMA, its share of the vector work}; slot i uses fragment
         // i / RS for row set i % RS
@@ -558,6 +581,7 @@ __global__ __launch_bounds__(NW * 64, RS == 1 ? 2 : 1) void prefill_kernel(
         };
         static_assert(packed_in_time(), "every chunk is packed before its first P*V MFMA");
         bf16x8 opnd;                                 // the fragment in use, as an MFMA operand
+        const char *stage_src = nullptr;              // pool block being staged (uniform)
         uint32_t pw[RS][C::kEntries][4];             // P^T operands, 2 bf16 per word
         float pe[RS][32];                            // exponentials awaiting their bf16 pack
         float addc[RS][kAcc], psum[RS][kAcc], vmax[RS][kAcc];
@@ -572,15 +596,28 @@ __global__ __launch_bounds__(NW * 64, RS == 1 ? 2 : 1) void prefill_kernel(
 #ifdef GF_PROF
         const unsigned long long pf_b = __builtin_readcyclecounter();
 #endif
-        __builtin_amdgcn_s_waitcnt(wait_lds((kDepth - 2) * kGroup * kLdsPerFrag));        // group 0 has arrived
+        __builtin_amdgcn_s_waitcnt(wait_lds((kAhead - kFetch) * kLdsPerFrag));        // the first fragments have arrived
         __builtin_amdgcn_sched_barrier(0);
         static_for<NSLOT>([&](auto slot_c) {
             constexpr int i = decltype(slot_c)::value;
             constexpr int n = i / RS, rs = i % RS;   // fragment, row set
-            constexpr int g = n / kGroup;
+            if constexpr (i == kSyncSlot) {
+                if (!(GF_ABL & 16)) dma_wait();                      // this wave's direct loads have landed ...
+                // (the window fetch is waited for here, nowhere earlier)
+                asm volatile("" : "+v"(w_new.idx), "+v"(w_new.nt), "+v"(w_new.ks), "+v"(w_new.lvs), "+v"(w_new.ivs));
+                if (slide) {
+                    w_cur = w_nxt;
+                    mbits_cur = mbits_nxt;
+                    w_nxt = w_new;
+                    mbits_nxt = adopt_window(win + 2, w_nxt);
+                    ++win;
+                }
+                if (!(GF_ABL & 4)) __syncthreads();                  // ... and every wave's are visible
+                __builtin_amdgcn_sched_barrier(0);
+            }
             if constexpr (n < C::kQK) {
                 constexpr int kt = n / C::kKS, ks = n % C::kKS;
-                if constexpr (rs == 0) opnd = to_operand(f[g % kDepth][n % kGroup]);
+                if constexpr (rs == 0) opnd = to_operand(f[n % kRing]);
                 mma_scores<kHand, ks == 0>(sn[rs][kt], opnd, qf[rs][ks]);
             } else {
                 if constexpr (kHand && i == C::kQK * RS) {
@@ -595,7 +632,7 @@ __global__ __launch_bounds__(NW * 64, RS == 1 ? 2 : 1) void prefill_kernel(
                 constexpr int j = n - C::kQK;
                 constexpr int cb = j / C::kDT, dt = j % C::kDT;
                 u32x4 pq = {pw[rs][cb][0], pw[rs][cb][1], pw[rs][cb][2], pw[rs][cb][3]};
-                if constexpr (rs == 0) opnd = to_operand(f[g % kDepth][n % kGroup]);
+                if constexpr (rs == 0) opnd = to_operand(f[n % kRing]);
                 mma_out<kHand>(o[rs][dt], opnd, __builtin_bit_cast(bf16x8, pq));
                 // vector share: running maxima of the next tile's scores, two elements per v_max3
                 constexpr int kMaxPerSlot = 32 / C::kPV;
@@ -610,10 +647,27 @@ __global__ __launch_bounds__(NW * 64, RS == 1 ? 2 : 1) void prefill_kernel(
                     asm volatile("" : "+v"(vm));      // keep the running maximum in this slot
                 });
             }
-            // the first MFMA of a group is followed by the fetch of a later group
-            if constexpr (!(GF_ABL & 1) && rs == 0 && n % kGroup == 0 && g + kDepth - 1 < kGroups) {
-#pragma unroll
-                for (int x = 0; x < kGroup; ++x) f[(g + kDepth - 1) % kDepth][x] = frag((g + kDepth - 1) * kGroup + x);
+            // the first MFMA of a fetch group is followed by the fetch of the group kAhead fragments on;
+            // near the end of the iteration those are K fragments of tile t+2, for the next iteration
+            if constexpr (!(GF_ABL & 1) && rs == 0 && n % kFetch == 0) {
+                static_for<kFetch>([&](auto x_c) {
+                    constexpr int nn = n + kAhead + decltype(x_c)::value;
+                    if constexpr (nn < C::kFrags) f[nn % kRing] = frag(nn);
+                    else f[nn % kRing] = k_frag(kb_next, nn - C::kFrags);
+                });
+            }
+            // staging for the coming iterations rides in early slots, one direct load per slot
+            if constexpr (i >= kStageKSlot && i < kStageKSlot + RS * C::kDmaPerWave && (i - kStageKSlot) % RS == 0) {
+                constexpr int j = (i - kStageKSlot) / RS;
+                if constexpr (j == 0) stage_src = block_of(a.k, t + 2);
+                if (!(GF_ABL & 8) && k2)                                               // K(t+2) replaces K(t)
+                    dma_load<j>(stage_src, k_off[j], kbuf + (t & 1) * C::kKTile + wave * C::kDmaPerWave * 1024);
+            }
+            if constexpr (i >= kStageVSlot && i < kStageVSlot + RS * C::kDmaPerWave && (i - kStageVSlot) % RS == 0) {
+                constexpr int j = (i - kStageVSlot) / RS;
+                if constexpr (j == 0) stage_src = block_of(a.v, t + 1);
+                if (!(GF_ABL & 8) && has_next)                                         // V(t+1) replaces V(t-2)
+                    dma_load<j>(stage_src, v_off[j], vbuf + ((t + 1) % C::kVBufs) * C::kVTile + wave * C::kDmaPerWave * 1024);
             }
             // vector share of every slot: the exponentials of tile t are spread evenly over the
             // slots up to kExpEnd.  An exponential joins the row sum one step later (its consumer
@@ -637,12 +691,10 @@ __global__ __launch_bounds__(NW * 64, RS == 1 ? 2 : 1) void prefill_kernel(
                     if constexpr (x == kExps - 1) psum[r2][acc_of(3)] += pe[r2][31];
                 }
             });
-            // one wait per group, at the end of the slot before it: the whole group has arrived
-            if constexpr (rs == RS - 1 && (n + 1) % kGroup == 0 && n + 1 < C::kFrags) {
-                // groups still in flight after group g+1: those fetched behind it
-                constexpr int behind = (g + kDepth - 1 < kGroups ? g + kDepth - 1 : kGroups - 1) - (g + 1);
-                __builtin_amdgcn_s_waitcnt(wait_lds(behind * kGroup * kLdsPerFrag));
-            }
+            // one wait per kFetch fragments, at the end of the slot before them: they have arrived
+            // (the fetches issued behind them stay in flight)
+            if constexpr (rs == RS - 1 && (n + 1) % kFetch == 0 && n + 1 < C::kFrags)
+                __builtin_amdgcn_s_waitcnt(wait_lds((kAhead - kFetch) * kLdsPerFrag));
             __builtin_amdgcn_sched_barrier(0);
         });
 #ifdef GF_PROF
@@ -658,23 +710,9 @@ __global__ __launch_bounds__(NW * 64, RS == 1 ? 2 : 1) void prefill_kernel(
             }
             mx[rs] = best;
         }
-        if (!(GF_ABL & 16)) dma_wait();                              // this wave's direct loads have landed ...
-        // (the window fetch is waited for here, nowhere earlier)
-        asm volatile("" : "+v"(w_new.idx), "+v"(w_new.nt), "+v"(w_new.ks), "+v"(w_new.lvs), "+v"(w_new.ivs));
-        if (slide) {
-            w_cur = w_nxt;
-            mbits_cur = mbits_nxt;
-            w_nxt = w_new;
-            mbits_nxt = adopt_window(win + 2, w_nxt);
-            ++win;
-        }
-#ifdef GF_PROF
-        const unsigned long long pf_d = __builtin_readcyclecounter();
-#endif
-        if (!(GF_ABL & 4)) __syncthreads();                             // ... and every wave's are visible
 #ifdef GF_PROF
         const unsigned long long pf_e = __builtin_readcyclecounter();
-        pf_pre += pf_b - pf_a; pf_str += pf_c - pf_b; pf_mid += pf_d - pf_c; pf_end += pf_e - pf_d;
+        pf_pre += pf_b - pf_a; pf_str += pf_c - pf_b; pf_mid += pf_e - pf_c;
 #endif
     };
 
@@ -689,6 +727,7 @@ __global__ __launch_bounds__(NW * 64, RS == 1 ? 2 : 1) void prefill_kernel(
         float *pf = a.lse + ((size_t)blockIdx.x * NW + wave) * 8;
         pf[0] = (float)ntiles; pf[1] = (float)pf_pre; pf[2] = (float)pf_str; pf[3] = (float)pf_mid; pf[4] = (float)pf_end;
         pf[5] = (float)(__builtin_readcyclecounter() - pf_start);
+        pf[6] = (float)(__builtin_amdgcn_s_memrealtime() - pf_rt0);
     }
     const bool pf_skip_lse = true;
 #else
@@ -800,9 +839,9 @@ static hipError_t launch_prefill_t(const AttnArgs &a, int kv_dtype, const int32_
 template <int D, int G, int NW, bool FP8>
 static hipError_t launch_prefill_k(const AttnArgs &a, const int32_t *q_ptr, int32_t total_q, int32_t *plan,
                                    hipStream_t s) {
-    constexpr int RS = kPrefillRowSets;
+    constexpr int RS = prefill_row_sets(FP8);
     using C = PrefillCfg<D, G, NW, RS, FP8 ? 1 : 2>;
-    static_assert(C::kRows == kPrefillRows, "work list and kernel agree on the tile height");
+    static_assert(C::kRows >= kPrefillRowsMin, "the work list is sized for the smallest tile height");
     auto kern = prefill_kernel<D, G, NW, RS, FP8>;
     static bool attr_set = false;
     if (!attr_set) {
@@ -827,8 +866,8 @@ static hipError_t launch_prefill_k(const AttnArgs &a, const int32_t *q_ptr, int3
 size_t prefill_plan_items(int32_t total_q, int32_t num_req, int bm) { return (size_t)total_q / bm + num_req; }
 
 size_t prefill_plan_bytes(int32_t total_q, int32_t num_req, int group) {
-    // one item = kPrefillRows score rows = kPrefillRows / group new tokens
-    return (2 + 2 * prefill_plan_items(total_q, num_req, kPrefillRows / group)) * sizeof(int32_t);
+    // one item covers at least kPrefillRowsMin score rows = kPrefillRowsMin / group new tokens
+    return (2 + 2 * prefill_plan_items(total_q, num_req, kPrefillRowsMin / group)) * sizeof(int32_t);
 }
 
 hipError_t launch_prefill(const AttnArgs &a, int head_dim, int group, int kv_dtype, const int32_t *q_ptr,
