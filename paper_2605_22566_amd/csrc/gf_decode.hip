@@ -34,8 +34,11 @@ struct PairRegs {
 };
 template <int D>
 struct PairRegs<D, true> {
-    // e4m3 pool: 8-byte fragments (8 codes each) and this lane's K / V block scales
-    u32x2 k[2][D / 32];
+    // e4m3 pool: this lane's K / V block scales ride along.  K is fetched 16 bytes at a time: the
+    // contraction elements of lane group q4 in MFMA step t are d = 64 (t/2) + 16 q4 + 8 (t%2) .. +7
+    // (Q uses the same assignment), so one load carries the operands of two steps and a wave-wide
+    // load reads 64 contiguous bytes of every K row.  V fragments are 8 bytes (8 slots of one d row).
+    u32x4 k[2][D / 64];
     u32x2 v[D / 16];
     float ks, vs;
     int n0, n1;
@@ -101,8 +104,8 @@ __device__ __forceinline__ void load_pair(PairRegs<D, true> &p, const AttnArgs &
 #pragma unroll
     for (int T = 0; T < 2; ++T)
 #pragma unroll
-        for (int t = 0; t < D / 32; ++t)
-            p.k[T][t] = *(const u32x2 *)(kb + (size_t)(slot0 + 4 * T) * D + (32 * t + 8 * q4));
+        for (int tp = 0; tp < D / 64; ++tp)
+            p.k[T][tp] = *(const u32x4 *)(kb + (size_t)(slot0 + 4 * T) * D + (64 * tp + 16 * q4));
     const char *vb = (q4 >= 2) ? v1 : v0;
 #pragma unroll
     for (int dt = 0; dt < D / 16; ++dt)
@@ -113,7 +116,7 @@ __device__ __forceinline__ void load_pair(PairRegs<D, true> &p, const AttnArgs &
 
 template <int D, bool FP8>
 __device__ __forceinline__ bf16x8 k_operand(const PairRegs<D, FP8> &p, int T, int t) {
-    if constexpr (FP8) return fp8x8_to_bf16x8(p.k[T][t]);
+    if constexpr (FP8) return fp8x8_to_bf16x8(u32x2{p.k[T][t / 2][2 * (t % 2)], p.k[T][t / 2][2 * (t % 2) + 1]});
     else return __builtin_bit_cast(bf16x8, p.k[T][t]);
 }
 template <int D, bool FP8>
@@ -148,9 +151,10 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_split_kernel(AttnArgs a
 #pragma unroll
     for (int t = 0; t < D / 32; ++t) {
         u32x4 raw = {0, 0, 0, 0};
+        // contraction elements of lane group q4 in step t (the e4m3 path pairs steps, see PairRegs)
+        const int d0 = FP8 ? 64 * (t / 2) + 16 * q4 + 8 * (t % 2) : 32 * t + 8 * q4;
         if (n < G)
-            raw = *(const u32x4 *)((const char *)a.q +
-                                   (((size_t)r * a.hq + kvh * G + n) * D + 32 * t + 8 * q4) * 2);
+            raw = *(const u32x4 *)((const char *)a.q + (((size_t)r * a.hq + kvh * G + n) * D + d0) * 2);
         qf[t] = __builtin_bit_cast(bf16x8, raw);
     }
 
