@@ -20,10 +20,11 @@
  *     hipStream_t passed as void*; NULL = the default stream).  Nothing is
  *     synchronised inside.  Data-dependent failures are reported per request
  *     in the device array status[] (GF_ST_*), not through the return value.
- *   - The library owns only a gf_ctx: device workspace for split-KV partials,
- *     grown on demand by gf_attn_decode (which may therefore call hipMalloc)
- *     and released by gf_destroy.  A gf_ctx must not be used from two streams
- *     at once.
+ *   - The library owns only a gf_ctx: device scratch memory (the split-KV
+ *     partials of gf_attn_decode, the work list of gf_attn_prefill), grown on
+ *     demand -- either call may therefore call hipMalloc, and hipFree after a
+ *     stream synchronisation when it outgrows what it has -- and released by
+ *     gf_destroy.  A gf_ctx must not be used from two streams at once.
  *   - Index arrays are int32.  Block size is 16 tokens.
  *
  * Pool layout (one layer), block size B = 16, element = bf16 or e4m3 byte:
@@ -160,7 +161,7 @@ int32_t gf_resolve_path(gf_ctx *ctx, const gf_graph *graph, int32_t num_req,
 
 /*
  * gf_attn_prefill -- new tokens attend to the ancestor-node KV (and causally
- * to each other) through the block table, "without repeated prefill" of the
+ * to each other) through the block table, with no second prefill of the
  * shared prefix; it is also the on-the-fly fallback of the paper's "Effective
  * Path Pruning".
  *
@@ -173,7 +174,8 @@ int32_t gf_resolve_path(gf_ctx *ctx, const gf_graph *graph, int32_t num_req,
  *   o   same shape, bf16 round-to-nearest-even (device, out)
  *   lse [total_q][num_q_heads] fp32 natural-log log-sum-exp of the scaled
  *       scores, or NULL (device, out)
- *   max_q  an upper bound on n_r over the batch (host value; sizes the grid).
+ *   max_q  an upper bound on n_r over the batch (host value; only checked to be
+ *          non-negative: the work list is built on the device from the tables).
  * Rows of requests whose status is non-zero, or whose row count
  * q_ptr[r+1]-q_ptr[r] differs from seq_lens[r]-ctx_lens[r], are left untouched.
  * Accumulation and softmax are fp32.

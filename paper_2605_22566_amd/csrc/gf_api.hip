@@ -37,6 +37,8 @@ int32_t check_attn(const gf_attn_params *p, const gf_kv_pool *pool, const gf_tab
     if (p->head_dim != 64 && p->head_dim != 128) return GF_ERR_UNSUPPORTED;
     if (group != 1 && group != 2 && group != 4 && group != 8) return GF_ERR_UNSUPPORTED;
     if (p->kv_dtype != GF_BF16 && p->kv_dtype != GF_FP8_E4M3) return GF_ERR_UNSUPPORTED;
+    // the kernels index (block, kv head) tiles of the pool with 32-bit integers
+    if ((int64_t)pool->num_blocks * p->num_kv_heads > 0x7fffffffLL) return GF_ERR_UNSUPPORTED;
     if (t->num_req > 0) {
         if (!pool->k || !pool->v || !q || !o) return GF_ERR_NULL;
         if (!t->block_table || !t->block_ntok || !t->num_blocks || !t->ctx_lens || !t->seq_lens)

@@ -1,44 +1,42 @@
 // gf_attn_prefill: the new tokens of each request attend to the KV of the
 // ancestor nodes on its path (shared, read through the block table) and,
-// causally, to each other (paper, Topology-Aware State Management: assembling
-// a workflow's KV from its nodes "without repeated prefill"; also the
-// on-the-fly fallback of Effective Path Pruning).
+// causally, to each other (paper, Topology-Aware State Management: a workflow's
+// KV is assembled from its nodes' stored KV, so the shared prefix is never
+// prefilled again; also the on-the-fly fallback of Effective Path Pruning).
 //
-// MFMA path.  One workgroup owns (request, kv head, tile of BM new tokens) and
-// all G query heads of the group: BM*G = 256 score rows share every K/V tile
-// that is staged through LDS, so each byte fetched feeds G times the flops.
-// Each of the 8 waves owns one 32-row tile (one query head, 32 tokens).
-// Scores are computed transposed so the softmax statistics of a row live in
-// one lane pair:
-//   S^T[key][row]  = K[key][d]   * Q^T[d][row]      (A = K from LDS, B = Q regs)
-//   O^T[d][row]   += V^T[d][key] * P^T[key][row]    (A = V^T from LDS, B = P regs)
-// with v_mfma_f32_32x32x16_bf16: operand lane l holds row/col l%32 and the 8
-// contraction elements of half l/32; accumulator lane l holds column l%32 and
-// rows 8*(i/4) + 4*(l/32) + i%4.  K rows are fetched in the order "row m reads
-// key m with bits 2 and 3 swapped", which makes accumulator registers 8c..8c+7
-// of a lane the 8 consecutive slots 8*(l/32)..+7 of 16-key chunk c -- exactly
-// the contraction group the V^T operand reads as one 16-byte LDS load from the
-// pool's [d][slot] V layout.  P never leaves registers.
+// MFMA path.  One workgroup (4 waves) owns (request, kv head, tile of BM new tokens) and all G
+// query heads of the group: every K/V tile staged through LDS is shared by BM*G score rows, so each
+// byte fetched feeds G times the flops.  A wave owns RS "row sets" of 32 score rows (one query
+// head x 32 tokens each).  Scores are computed transposed so the softmax statistics of a row live
+// in one lane pair:
+//   S^T[key][row]  = K[key][d]   * Q^T[d][row]      (A = K from LDS, B = Q registers)
+//   O^T[d][row]   += V^T[d][key] * P^T[key][row]    (A = V^T from LDS, B = P registers)
+// with v_mfma_f32_32x32x16_bf16: operand lane l holds row/col l%32 and the 8 contraction elements
+// of half l/32; accumulator lane l holds column l%32 and rows 8*(i/4) + 4*(l/32) + i%4.  K rows
+// are fetched in the order "row m reads key m with bits 2 and 3 swapped", which makes accumulator
+// registers 8c..8c+7 of a lane the 8 consecutive slots 8*(l/32)..+7 of 16-key chunk c -- exactly
+// the contraction group the V^T operand reads as one 16-byte LDS load from the pool's [d][slot]
+// V layout.  P never leaves registers.  Every fragment read from LDS feeds RS MFMAs.
 //
-// Staging.  KV tiles are 64 keys (4 table entries), double buffered in LDS with
-// K one tile ahead of V, and filled by 16-byte global->LDS direct loads (no
-// staging registers): lane l of a wave-wide load writes LDS bytes 16*l.. of a
-// 1 KB span, and picks its global source so that the LDS image is XOR-swizzled
-// (K: chunk position = chunk ^ row bits; V: the two 16-byte halves of a head-dim
-// row swap on every other group of 8 rows), which makes every 16-lane group of
-// an operand fetch hit 16 distinct 16-byte bank groups.
+// Staging.  KV tiles are 64 keys (4 table entries; wave w stages entry w).  They are filled by
+// 16-byte global->LDS direct loads (no staging registers): lane l of a wave-wide load writes LDS
+// bytes 16*l.. of a 1 KB span, and picks its global source so that the LDS image is XOR-swizzled
+// (K: chunk position = chunk ^ row bits; V: the two 16-byte halves of a head-dim row swap on every
+// other group of 8 rows), which makes every 16-lane group of an operand fetch hit 16 distinct
+// 16-byte bank groups.  LDS holds two K tiles and three V tiles.
 //
-// Pipeline.  Inside a wave the scores run one tile
-// ahead of the softmax: iteration t issues, as one straight-line stream of 32
-// slots, the 16 score MFMAs of tile t+1 and the 16 P*V MFMAs of tile t, and in
-// the shadow of every MFMA a fixed share of the vector work (exponentials, row
-// sums and bf16 packing of tile t; row maximum of tile t+1) and one LDS operand
-// fetch, four slots ahead of its use.  Scheduling barriers pin that order.
-// The reference row maximum is refreshed (and O rescaled) only when some row's
-// new maximum exceeds it by more than 2^8; the final normalisation uses the
-// same reference, so the result is unchanged.  Per-entry token counts mask
-// partial blocks anywhere in the sequence and tail entries causally, in a side
-// path taken only by tiles that need it.
+// Pipeline.  Inside a wave the scores run one tile ahead of the softmax: iteration t issues, as
+// one straight-line stream of slots, the score MFMAs of tile t+1 and the P*V MFMAs of tile t, and
+// in the shadow of every MFMA a fixed share of the vector work (exponentials, row sums and bf16
+// packing of tile t; running maximum of tile t+1), the LDS operand fetches (grouped, one wait per
+// group), the direct loads of K(t+2) and V(t+1), and -- three quarters into the stream -- the wait
+// for those loads and the one workgroup barrier of the iteration; the first fragments of the
+// next iteration are fetched behind that barrier.  The slot schedule is fixed at compile time
+// (static_for / if constexpr) and pinned with scheduling barriers.
+// The reference row maximum is refreshed (and O rescaled) only when some row's new maximum
+// exceeds it by more than 2^8; the final normalisation uses the same reference, so the result is
+// unchanged.  Per-entry token counts mask partial blocks anywhere in the sequence and tail entries
+// causally, in a side path taken only by tiles whose mask bits say so.
 
 #include "gf_internal.h"
 #include <type_traits>
@@ -84,30 +82,17 @@ struct PrefillCfg {
 constexpr int kPrefillWaves = 4;
 // Row sets per wave.  A bf16 pool runs one (two workgroups per CU cover each other's stalls; measured
 // faster there); an e4m3 pool runs two, where every fragment converted to bf16 serves two MFMAs.
-#ifdef GF_RS
-constexpr int prefill_row_sets(bool) { return GF_RS; }
-#else
 constexpr int prefill_row_sets(bool fp8) { return fp8 ? 2 : 1; }
-#endif
 constexpr int kPrefillRowsMin = 32 * kPrefillWaves;   // fewest score rows a workgroup covers (sizes the work list)
 
 constexpr float kRescaleSlack = 8.0f;   // log2 units a row max may exceed its reference
 // LDS operand fragments live in a ring of kRing register sets.  The fetches of fragments
 // n + kAhead .. n + kAhead + kFetch - 1 are issued right behind the first MFMA of fragment n
 // (n a multiple of kFetch), and the wave waits once per kFetch fragments, for exactly those.
-#ifndef GF_AHEAD
-#define GF_AHEAD 4
-#endif
-#ifndef GF_FETCH
-#define GF_FETCH 4
-#endif
-constexpr int kRing = 8, kAhead = GF_AHEAD, kFetch = GF_FETCH;
+constexpr int kRing = 8, kAhead = 4, kFetch = 4;
 static_assert(kAhead % kFetch == 0 && kAhead + kFetch <= kRing, "a fetch never lands in a register set still to be used");
 // s_waitcnt lgkmcnt(n), other counters untouched
 constexpr int wait_lds(int n) { return 0xC07F | (n << 8); }
-#ifndef GF_ABL
-#define GF_ABL 0
-#endif
 
 typedef __attribute__((address_space(3))) void *lptr_t;
 
@@ -483,7 +468,7 @@ __global__ __launch_bounds__(NW * 64, RS == 1 ? 2 : 1) void prefill_kernel(
     // Side path, before tile t is taken up: partial blocks / causal tail / end of the sequence in it
     // (pad slots may hold any finite value, so the pending maxima are taken again after masking).
     auto premask = [&](int t, f32x16 (&sc)[RS][2]) {
-        if (!(GF_ABL & 32) && ((mbits_cur >> ((t * C::kEntries) & 63)) & ((1u << C::kEntries) - 1)) != 0) {
+        if (((mbits_cur >> ((t * C::kEntries) & 63)) & ((1u << C::kEntries) - 1)) != 0) {
             const TileScale ts = tile_scale(t);
 #pragma unroll
             for (int rs = 0; rs < RS; ++rs) {
@@ -514,20 +499,10 @@ __global__ __launch_bounds__(NW * 64, RS == 1 ? 2 : 1) void prefill_kernel(
     };
 
     // ---- one iteration: softmax + P*V of tile t (scores in sc), scores of tile t+1 -> sn ----
-#ifdef GF_PROF
-    unsigned long long pf_pre = 0, pf_str = 0, pf_end = 0, pf_mid = 0;
-    const unsigned long long pf_start = __builtin_readcyclecounter();
-    const unsigned long long pf_rt0 = __builtin_amdgcn_s_memrealtime();
-#endif
     frag_t f[kRing];                  // operand fragments; the first kAhead of an iteration are fetched by the one before
-    if constexpr (!(GF_ABL & 1)) {
 #pragma unroll
-        for (int x = 0; x < kAhead; ++x) f[x] = k_frag(kbuf + C::kKTile, x);   // K(1), staged by the prologue
-    }
+    for (int x = 0; x < kAhead; ++x) f[x] = k_frag(kbuf + C::kKTile, x);   // K(1), staged by the prologue
     auto body = [&](int t, f32x16 (&sc)[RS][2], f32x16 (&sn)[RS][2]) {
-#ifdef GF_PROF
-        const unsigned long long pf_a = __builtin_readcyclecounter();
-#endif
         const bool has_next = t + 1 < ntiles;
         const bool k2 = t + 2 < ntiles;
         // operand stream of this iteration: the K fragments of tile t+1, then the V fragments of tile t,
@@ -566,7 +541,7 @@ __global__ __launch_bounds__(NW * 64, RS == 1 ? 2 : 1) void prefill_kernel(
         const TileScale ts = tile_scale(t);          // constants of this tile ...
         const TileScale tn = tile_scale(t + 1);      // ... and of the next (for its row maximum)
         premask(t, sc);
-        if ((!(GF_ABL & 64) || t == 0) && need_rescale()) rescale();
+        if (need_rescale()) rescale();
 
         // main stream: NSLOT slots of {MFMA, its share of the vector work}; slot i uses fragment
         // i / RS for row set i % RS
@@ -593,16 +568,13 @@ __global__ __launch_bounds__(NW * 64, RS == 1 ? 2 : 1) void prefill_kernel(
                 psum[rs][cb] = 0.f;
                 vmax[rs][cb] = -INFINITY;
             }
-#ifdef GF_PROF
-        const unsigned long long pf_b = __builtin_readcyclecounter();
-#endif
         __builtin_amdgcn_s_waitcnt(wait_lds((kAhead - kFetch) * kLdsPerFrag));        // the first fragments have arrived
         __builtin_amdgcn_sched_barrier(0);
         static_for<NSLOT>([&](auto slot_c) {
             constexpr int i = decltype(slot_c)::value;
             constexpr int n = i / RS, rs = i % RS;   // fragment, row set
             if constexpr (i == kSyncSlot) {
-                if (!(GF_ABL & 16)) dma_wait();                      // this wave's direct loads have landed ...
+                dma_wait();                      // this wave's direct loads have landed ...
                 // (the window fetch is waited for here, nowhere earlier)
                 asm volatile("" : "+v"(w_new.idx), "+v"(w_new.nt), "+v"(w_new.ks), "+v"(w_new.lvs), "+v"(w_new.ivs));
                 if (slide) {
@@ -612,7 +584,7 @@ __global__ __launch_bounds__(NW * 64, RS == 1 ? 2 : 1) void prefill_kernel(
                     mbits_nxt = adopt_window(win + 2, w_nxt);
                     ++win;
                 }
-                if (!(GF_ABL & 4)) __syncthreads();                  // ... and every wave's are visible
+                __syncthreads();                  // ... and every wave's are visible
                 __builtin_amdgcn_sched_barrier(0);
             }
             if constexpr (n < C::kQK) {
@@ -637,7 +609,7 @@ __global__ __launch_bounds__(NW * 64, RS == 1 ? 2 : 1) void prefill_kernel(
                 // vector share: running maxima of the next tile's scores, two elements per v_max3
                 constexpr int kMaxPerSlot = 32 / C::kPV;
                 static_assert(kMaxPerSlot % 2 == 0, "maximum taken in pairs");
-                if constexpr (!(GF_ABL & 128)) static_for<kMaxPerSlot / 2>([&](auto e_c) {
+                static_for<kMaxPerSlot / 2>([&](auto e_c) {
                     constexpr int y = (i - C::kQK * RS) * kMaxPerSlot + 2 * decltype(e_c)::value;   // in [0, 32 RS)
                     constexpr int r2 = y / 32, idx = y % 32;
                     // the score tile read here was completed by slot RS * kKS * (idx / 16 + 1) - RS + r2
@@ -649,7 +621,7 @@ __global__ __launch_bounds__(NW * 64, RS == 1 ? 2 : 1) void prefill_kernel(
             }
             // the first MFMA of a fetch group is followed by the fetch of the group kAhead fragments on;
             // near the end of the iteration those are K fragments of tile t+2, for the next iteration
-            if constexpr (!(GF_ABL & 1) && rs == 0 && n % kFetch == 0) {
+            if constexpr (rs == 0 && n % kFetch == 0) {
                 static_for<kFetch>([&](auto x_c) {
                     constexpr int nn = n + kAhead + decltype(x_c)::value;
                     if constexpr (nn < C::kFrags) f[nn % kRing] = frag(nn);
@@ -660,27 +632,27 @@ __global__ __launch_bounds__(NW * 64, RS == 1 ? 2 : 1) void prefill_kernel(
             if constexpr (i >= kStageKSlot && i < kStageKSlot + RS * C::kDmaPerWave && (i - kStageKSlot) % RS == 0) {
                 constexpr int j = (i - kStageKSlot) / RS;
                 if constexpr (j == 0) stage_src = block_of(a.k, t + 2);
-                if (!(GF_ABL & 8) && k2)                                               // K(t+2) replaces K(t)
+                if (k2)                                               // K(t+2) replaces K(t)
                     dma_load<j>(stage_src, k_off[j], kbuf + (t & 1) * C::kKTile + wave * C::kDmaPerWave * 1024);
             }
             if constexpr (i >= kStageVSlot && i < kStageVSlot + RS * C::kDmaPerWave && (i - kStageVSlot) % RS == 0) {
                 constexpr int j = (i - kStageVSlot) / RS;
                 if constexpr (j == 0) stage_src = block_of(a.v, t + 1);
-                if (!(GF_ABL & 8) && has_next)                                         // V(t+1) replaces V(t-2)
+                if (has_next)                                         // V(t+1) replaces V(t-2)
                     dma_load<j>(stage_src, v_off[j], vbuf + ((t + 1) % C::kVBufs) * C::kVTile + wave * C::kDmaPerWave * 1024);
             }
             // vector share of every slot: the exponentials of tile t are spread evenly over the
             // slots up to kExpEnd.  An exponential joins the row sum one step later (its consumer
             // is never the next instruction), each pair is packed to bf16 one slot after its second
             // exponential, and chunk c of a row set is complete before its first P*V MFMA.
-            if constexpr (!(GF_ABL & 128)) static_for<kExps>([&](auto e_c) {
+            static_for<kExps>([&](auto e_c) {
                 constexpr int x = decltype(e_c)::value;
                 constexpr int e2 = x / RS, r2 = x % RS;
                 if constexpr (exp_slot(x) == i) {
                     constexpr int cb = acc_of(e2 / 8);
                     const float sv = sc[r2][e2 / 16][e2 % 16];
                     const float arg = sv * ts.mult[cb] + addc[r2][cb];
-                    pe[r2][e2] = (GF_ABL & 2) ? arg : fast_exp2(arg);
+                    pe[r2][e2] = fast_exp2(arg);
                     constexpr int xp = x > 0 ? x - 1 : 0;                  // the exponential before this one
                     if constexpr (x > 0) psum[xp % RS][acc_of(xp / RS / 8)] += pe[xp % RS][xp / RS];
                     asm volatile("" : "+v"(psum[xp % RS][acc_of(xp / RS / 8)]), "+v"(pe[r2][e2]));   // stay in this slot
@@ -697,9 +669,6 @@ __global__ __launch_bounds__(NW * 64, RS == 1 ? 2 : 1) void prefill_kernel(
                 __builtin_amdgcn_s_waitcnt(wait_lds((kAhead - kFetch) * kLdsPerFrag));
             __builtin_amdgcn_sched_barrier(0);
         });
-#ifdef GF_PROF
-        const unsigned long long pf_c = __builtin_readcyclecounter();
-#endif
 #pragma unroll
         for (int rs = 0; rs < RS; ++rs) {
             float best = -INFINITY;
@@ -710,10 +679,6 @@ __global__ __launch_bounds__(NW * 64, RS == 1 ? 2 : 1) void prefill_kernel(
             }
             mx[rs] = best;
         }
-#ifdef GF_PROF
-        const unsigned long long pf_e = __builtin_readcyclecounter();
-        pf_pre += pf_b - pf_a; pf_str += pf_c - pf_b; pf_mid += pf_e - pf_c;
-#endif
     };
 
     int t = 0;
@@ -722,17 +687,6 @@ __global__ __launch_bounds__(NW * 64, RS == 1 ? 2 : 1) void prefill_kernel(
         body(t + 1, s_b, s_a);
     }
     if (t < ntiles) body(t, s_a, s_b);
-#ifdef GF_PROF
-    if (a.lse && lane == 0) {
-        float *pf = a.lse + ((size_t)blockIdx.x * NW + wave) * 8;
-        pf[0] = (float)ntiles; pf[1] = (float)pf_pre; pf[2] = (float)pf_str; pf[3] = (float)pf_mid; pf[4] = (float)pf_end;
-        pf[5] = (float)(__builtin_readcyclecounter() - pf_start);
-        pf[6] = (float)(__builtin_amdgcn_s_memrealtime() - pf_rt0);
-    }
-    const bool pf_skip_lse = true;
-#else
-    const bool pf_skip_lse = false;
-#endif
     // ---- epilogue: normalise, round to bf16, store ------------------------------------
     if constexpr (RS > 1) asm volatile("s_nop 7\n\ts_nop 7" ::: "memory");   // O written by hand-issued MFMAs
 #pragma unroll
@@ -751,7 +705,7 @@ __global__ __launch_bounds__(NW * 64, RS == 1 ? 2 : 1) void prefill_kernel(
                     const bf16x4 b4 = __builtin_convertvector(v4, bf16x4);
                     *(bf16x4 *)(op + (32 * dt + 8 * q + 4 * hh) * 2) = b4;
                 }
-            if (a.lse && hh == 0 && !pf_skip_lse)
+            if (a.lse && hh == 0)
                 a.lse[(size_t)(q0 + row_tok[rs]) * a.hq + row_head[rs]] =
                     (m_ref[rs] + __builtin_log2f(l_tot)) * 0.6931471805599453f;
         }
