@@ -280,7 +280,9 @@ def main():
                    "kv_heads": wl.shape.num_kv_heads, "head_dim": wl.shape.head_dim, "block": 16,
                    "nodes": wl.graph.num_nodes, "pool_blocks": wl.num_pool_blocks,
                    "new_tokens": int(wl.batch.new_lens.sum()), "ctx_tokens": int(W.context_lens(wl).sum()),
-                   "sharing_factor": W.sharing_stats(wl)["sharing_factor"], "seed": wl.seed,
+                   "sharing_factor": W.sharing_stats(wl)["sharing_factor"],
+                   "stateful_over_shared_kv_bytes": W.sharing_stats(wl)["stateful_kv_bytes"]
+                   / W.sharing_stats(wl)["shared_kv_bytes"], "seed": wl.seed,
                    "step": "resolve+prefill+decode(+merge)"},
         "roofline": roof,
         "breakdown_ms": {k: v for k, v in m.items() if k.endswith("_ms")},
@@ -303,6 +305,10 @@ def main():
             ent["decode_gbs_kernel"] = mm["decode_gbs_kernel"]
             ent["decode_frac_of_hbm_peak"] = mm["decode_gbs_kernel"] / PEAK_HBM_GBS
             ent["algorithmic_bytes_per_launch"] = j.decode_bytes()
+            # what a kernel that read every shared node once per batch would have to move, at the HBM peak
+            ent["unique_kv_bytes"] = W.sharing_stats(j.wl)["shared_kv_bytes"]
+            ent["unique_bytes_time_bound_ms"] = ent["unique_kv_bytes"] / (PEAK_HBM_GBS * 1e9) * 1e3
+            ent["hbm_bytes_per_launch_rocprof"] = _read_traffic(f"decode_{name}")
         extra[name] = ent
         del j
         torch.cuda.empty_cache()

@@ -472,5 +472,12 @@ def sharing_stats(wl: Workload) -> dict:
     L = context_lens(wl)
     used = np.unique(wl.batch.path_nodes)
     uniq = int(wl.graph.node_len[used].astype(np.int64).sum())
+    sh = wl.shape
+    esz = 2 if sh.kv_dtype == KV_BF16 else 1
+    per_tok = 2 * sh.num_kv_heads * sh.head_dim * esz            # K and V bytes of one token, one layer
+    tail = int(wl.batch.new_lens.astype(np.int64).sum())
     return {"sum_ctx_tokens": int(L.sum()), "unique_ctx_tokens": uniq,
-            "sharing_factor": float(L.sum()) / max(uniq, 1)}
+            "sharing_factor": float(L.sum()) / max(uniq, 1),
+            # what per-request (stateful) KV copies would hold vs what the shared pool holds for this batch
+            "stateful_kv_bytes": float(L.sum() + tail) * per_tok,
+            "shared_kv_bytes": float(uniq + tail) * per_tok}
