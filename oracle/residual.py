@@ -1,0 +1,100 @@
+"""Oracle for the differential KV cache (paper, "Differential-based KV Cache", Eq. 7):
+
+    KV(P, v) = KV_base(v) + dKV(P, v)
+
+the KV state of operation node v under prefix path P is its base KV plus a sparse,
+prefix-specific residual.  TEST INFRASTRUCTURE ONLY (see the package header).
+
+What is computed here, block by block of the paged pool:
+  * reconstruct(): copy the base blocks of a node to destination blocks and add the
+    residual entries.  A residual entry addresses the LOGICAL element
+        i = ((t * Hkv + h) * 16 + slot) * D + d,   t = 0 for K, 1 for V,
+    whatever the physical layout of the tensor inside the block (K is stored
+    [h][slot][d], V is stored [h][d][slot]).  The sum is taken in fp32 and rounded
+    to bf16 round-to-nearest-even -- the stored code is a quantisation decision, so
+    the oracle takes it in the kernel's precision (fp32), not in fp64.
+  * select_by_energy(): the offline selection rule of the paper's appendix (keep the
+    largest-magnitude entries that hold a given share, 95 %, of the Frobenius energy
+    of the dense difference).  Not on the GPU path; kept as the reference of how a
+    residual is obtained.
+
+Readings: the paper does not fix the storage format of a residual (coordinate list
+here, one CSR row per pool block), its value precision (bf16 here, like the pool), or
+what happens to malformed input (a block id outside the pool skips the item, an
+element index outside the block is ignored; both are reported per item).
+
+Pins (tests/test_oracle_residual.py): the bf16 rounding against torch's cast on
+random values, ties and extremes; an empty residual is the identity; the residual
+-base gives all zeros; a full-density residual equals torch's element-wise bf16 add;
+single entries land on the hand-indexed physical element of K and of V; a node
+reconstructed block by block equals base + delta formed on the [token][head][dim]
+segment without any block arithmetic; select_by_energy against brute force over all
+subsets on tiny inputs, plus its defining invariants.
+"""
+import numpy as np
+
+BLOCK = 16
+ST_OK, ST_BAD_BLOCK, ST_BAD_INDEX = 0, 1, 2
+
+
+def f32_to_bf16_bits_rne(x: np.ndarray) -> np.ndarray:
+    """fp32 -> bf16 bits, round to nearest, ties to even (finite inputs)."""
+    u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    lsb = (u >> np.uint64(16)) & np.uint64(1)
+    return ((u + np.uint64(0x7FFF) + lsb) >> np.uint64(16)).astype(np.uint16)
+
+
+def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
+    return (np.ascontiguousarray(bits).astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def logical_index(t: int, h: int, slot: int, d: int, hkv: int, dim: int) -> int:
+    return ((t * hkv + h) * BLOCK + slot) * dim + d
+
+
+def reconstruct(k_pool: np.ndarray, v_pool: np.ndarray, src_blocks, dst_blocks, res_ptr, res_idx, res_val):
+    """k_pool uint16 [nb, Hkv, 16, D], v_pool uint16 [nb, Hkv, D, 16] (bf16 bits).
+    Returns (k_pool', v_pool', status[num_items]); the inputs are not modified."""
+    k_out, v_out = k_pool.copy(), v_pool.copy()
+    nb, hkv, _, dim = k_pool.shape
+    per_tensor = hkv * BLOCK * dim
+    n_items = len(src_blocks)
+    status = np.zeros(n_items, dtype=np.int32)
+    for b in range(n_items):
+        s, t = int(src_blocks[b]), int(dst_blocks[b])
+        if not (0 <= s < nb and 0 <= t < nb):
+            status[b] = ST_BAD_BLOCK
+            continue
+        kb = bf16_bits_to_f32(k_pool[s]).copy()          # [Hkv, 16, D]
+        vb = bf16_bits_to_f32(v_pool[s]).copy()          # [Hkv, D, 16]
+        for e in range(int(res_ptr[b]), int(res_ptr[b + 1])):
+            i = int(res_idx[e])
+            if not (0 <= i < 2 * per_tensor):
+                status[b] = ST_BAD_INDEX
+                continue
+            val = bf16_bits_to_f32(np.array([res_val[e]], dtype=np.uint16))[0]
+            tensor, rem = divmod(i, per_tensor)
+            h, rem = divmod(rem, BLOCK * dim)
+            slot, d = divmod(rem, dim)
+            if tensor == 0:
+                kb[h, slot, d] = np.float32(kb[h, slot, d]) + np.float32(val)
+            else:
+                vb[h, d, slot] = np.float32(vb[h, d, slot]) + np.float32(val)
+        k_out[t] = f32_to_bf16_bits_rne(kb)
+        v_out[t] = f32_to_bf16_bits_rne(vb)
+    return k_out, v_out, status
+
+
+def select_by_energy(delta: np.ndarray, share: float = 0.95) -> np.ndarray:
+    """Indices (into delta.ravel()) of the fewest largest-magnitude entries whose
+    squared sum is at least `share` of the total; ties broken by lower index.
+    An all-zero difference keeps nothing."""
+    flat = np.ascontiguousarray(delta, dtype=np.float64).ravel()
+    energy = flat * flat
+    total = energy.sum()
+    if total == 0.0:
+        return np.zeros(0, dtype=np.int64)
+    order = np.lexsort((np.arange(flat.size), -energy))    # by energy descending, then index
+    cum = np.cumsum(energy[order])
+    keep = int(np.searchsorted(cum, share * total, side="left")) + 1
+    return np.sort(order[:min(keep, flat.size)])

@@ -1,0 +1,157 @@
+"""Pins of oracle/residual.py against things other than itself: torch's bf16 cast
+and element-wise add, hand-indexed physical elements, a block-free construction
+of base + delta on the token-major segment, and brute force over subsets."""
+import itertools
+
+import numpy as np
+import torch
+
+from oracle import attention as OA
+from oracle import residual as OR
+
+
+def _torch_bf16_bits(x):
+    t = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(torch.bfloat16)
+    return t.view(torch.int16).numpy().view(np.uint16)
+
+
+def test_bf16_rounding_matches_torch_on_random_ties_and_extremes():
+    rng = np.random.default_rng(3)
+    x = rng.standard_normal(200000).astype(np.float32) * np.float32(10.0) ** rng.integers(-20, 20, 200000)
+    assert np.array_equal(OR.f32_to_bf16_bits_rne(x), _torch_bf16_bits(x))
+    # exact ties: low 16 bits = 0x8000, both parities of the kept lsb
+    hi = rng.integers(0x0080, 0x7F00, 5000).astype(np.uint32)
+    ties = ((hi << 16) | 0x8000).view(np.float32)
+    assert np.array_equal(OR.f32_to_bf16_bits_rne(ties), _torch_bf16_bits(ties))
+    assert np.array_equal(OR.f32_to_bf16_bits_rne(-ties), _torch_bf16_bits(-ties))
+    ext = np.array([0.0, -0.0, 1.0, 3.3895314e38, 1e-40, -1e-40, 1.17549435e-38], dtype=np.float32)
+    assert np.array_equal(OR.f32_to_bf16_bits_rne(ext), _torch_bf16_bits(ext))
+
+
+def _pool(rng, nb, hkv, dim):
+    k = _torch_bf16_bits(rng.standard_normal((nb, hkv, 16, dim)).astype(np.float32)).copy()
+    v = _torch_bf16_bits(rng.standard_normal((nb, hkv, dim, 16)).astype(np.float32)).copy()
+    return k, v
+
+
+def test_empty_residual_is_identity_and_minus_base_gives_zero():
+    rng = np.random.default_rng(4)
+    hkv, dim = 2, 64
+    k, v = _pool(rng, 4, hkv, dim)
+    k2, v2, st = OR.reconstruct(k, v, [0, 1], [2, 3], [0, 0, 0], np.zeros(0, np.uint32), np.zeros(0, np.uint16))
+    assert st.tolist() == [0, 0]
+    assert np.array_equal(k2[2], k[0]) and np.array_equal(v2[3], v[1])
+    assert np.array_equal(k2[:2], k[:2]) and np.array_equal(v2[:2], v[:2])       # sources untouched
+    # residual = -base on every element of block 0 (logical order: K [h][slot][d], V [h][slot][d])
+    per = hkv * 16 * dim
+    vals = np.concatenate([k[0].ravel() ^ 0x8000, np.transpose(v[0], (0, 2, 1)).ravel() ^ 0x8000]).astype(np.uint16)
+    k3, v3, st = OR.reconstruct(k, v, [0], [2], [0, 2 * per], np.arange(2 * per, dtype=np.uint32), vals)
+    assert st.tolist() == [0]
+    assert not (k3[2] & 0x7FFF).any() and not (v3[2] & 0x7FFF).any()
+
+
+def test_full_density_equals_torch_elementwise_add():
+    rng = np.random.default_rng(5)
+    hkv, dim = 2, 128
+    k, v = _pool(rng, 3, hkv, dim)
+    per = hkv * 16 * dim
+    dk = _torch_bf16_bits((rng.standard_normal((hkv, 16, dim)) * 0.3).astype(np.float32))
+    dv = _torch_bf16_bits((rng.standard_normal((hkv, 16, dim)) * 0.3).astype(np.float32))   # logical [h][slot][d]
+    vals = np.concatenate([dk.ravel(), dv.ravel()])
+    k2, v2, _ = OR.reconstruct(k, v, [1], [2], [0, 2 * per], np.arange(2 * per, dtype=np.uint32), vals)
+
+    def tb(bits):
+        return torch.from_numpy(bits.astype(np.int16)).view(torch.bfloat16)
+    want_k = (tb(k[1]).float() + tb(dk).float()).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16)
+    want_v = (tb(v[1]).float() + tb(np.transpose(dv, (0, 2, 1)).copy()).float()).to(torch.bfloat16)
+    want_v = want_v.view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(k2[2], want_k)
+    assert np.array_equal(v2[2], want_v)
+
+
+def test_single_entries_land_on_the_hand_indexed_physical_element():
+    rng = np.random.default_rng(6)
+    hkv, dim = 4, 64
+    k, v = _pool(rng, 2, hkv, dim)
+    two = np.array([0x4000], np.uint16)                       # bf16 2.0
+    for (t, h, slot, d) in [(0, 0, 0, 0), (0, 3, 15, 63), (0, 1, 7, 20), (1, 0, 0, 0), (1, 2, 9, 33), (1, 3, 15, 63)]:
+        i = ((t * hkv + h) * 16 + slot) * dim + d             # written out, not via the oracle's helper
+        k2, v2, st = OR.reconstruct(k, v, [0], [1], [0, 1], np.array([i], np.uint32), two)
+        assert st.tolist() == [0]
+        dk = k2[1] != k[0]
+        dv = v2[1] != v[0]
+        if t == 0:
+            assert dk.sum() == 1 and dk[h, slot, d] and not dv.any()
+            got = OR.bf16_bits_to_f32(k2[1][h, slot, d:d + 1])[0]
+            assert got == OR.bf16_bits_to_f32(OR.f32_to_bf16_bits_rne(OR.bf16_bits_to_f32(k[0][h, slot, d:d + 1]) + 2))[0]
+        else:
+            assert dv.sum() == 1 and dv[h, d, slot] and not dk.any()
+
+
+def test_bad_block_and_bad_index_are_reported():
+    rng = np.random.default_rng(7)
+    hkv, dim = 1, 64
+    k, v = _pool(rng, 3, hkv, dim)
+    per = hkv * 16 * dim
+    idx = np.array([5, 2 * per, 7], np.uint32)                # the middle one is outside the block
+    val = np.array([0x3F80, 0x3F80, 0x3F80], np.uint16)
+    k2, v2, st = OR.reconstruct(k, v, [0, 9, 1], [1, 2, -1], [0, 3, 3, 3], idx, val)
+    assert st.tolist() == [OR.ST_BAD_INDEX, OR.ST_BAD_BLOCK, OR.ST_BAD_BLOCK]
+    assert (k2[1] != k[0]).sum() == 2                          # the two valid entries were applied
+    assert np.array_equal(k2[2], k[2]) and np.array_equal(v2[2], v[2])
+
+
+def test_node_reconstruction_equals_segment_level_base_plus_delta():
+    """Blocks of a ragged node, reconstructed one by one, then read back through the
+    attention oracle's table walk, equal base + delta formed on the [token][head][dim]
+    arrays directly (token = 16 * block + slot is the only bridge)."""
+    rng = np.random.default_rng(8)
+    hkv, dim, length = 2, 64, 41                               # 3 blocks, the last with 9 tokens
+    nblk = 3
+    k, v = _pool(rng, 8, hkv, dim)
+    src, dst = [5, 0, 3], [1, 6, 2]
+    base_k = np.concatenate([np.transpose(OR.bf16_bits_to_f32(k[b]), (1, 0, 2)) for b in src])[:length]   # [tok][h][d]
+    base_v = np.concatenate([np.transpose(OR.bf16_bits_to_f32(v[b]), (2, 0, 1)) for b in src])[:length]
+    mask = rng.random((2, length, hkv, dim)) < 0.2
+    delta = OR.bf16_bits_to_f32(_torch_bf16_bits((rng.standard_normal((2, length, hkv, dim)) * 0.5).astype(np.float32)))
+    delta = np.where(mask, delta, np.float32(0))
+    ptr, idx, val = [0], [], []
+    for bi in range(nblk):
+        for t, tok, h, d in zip(*np.nonzero(mask)):
+            if tok // 16 == bi:
+                idx.append(((t * hkv + h) * 16 + tok % 16) * dim + d)
+                val.append(delta[t, tok, h, d])
+        ptr.append(len(idx))
+    val_bits = _torch_bf16_bits(np.array(val, np.float32))
+    k2, v2, st = OR.reconstruct(k, v, src, dst, ptr, np.array(idx, np.uint32), val_bits)
+    assert st.tolist() == [0, 0, 0]
+    K, V = OA.materialize_kv(k2, v2, dst, [16, 16, 9], 3)
+    want_k = OR.bf16_bits_to_f32(_torch_bf16_bits(base_k + delta[0])).astype(np.float64)
+    want_v = OR.bf16_bits_to_f32(_torch_bf16_bits(base_v + delta[1])).astype(np.float64)
+    assert K.shape == (length, hkv, dim)
+    assert np.array_equal(K, want_k) and np.array_equal(V, want_v)
+
+
+def test_select_by_energy_matches_brute_force_and_its_invariants():
+    rng = np.random.default_rng(9)
+    for trial in range(30):
+        n = int(rng.integers(1, 11))
+        x = rng.standard_normal(n) * rng.choice([0.01, 1.0, 5.0], n)
+        total = float((x * x).sum())
+        keep = OR.select_by_energy(x, 0.95)
+        # brute force: the smallest subset size that reaches the share, and the best energy at that size
+        best_size = None
+        for size in range(1, n + 1):
+            best = max(float((x[list(c)] ** 2).sum()) for c in itertools.combinations(range(n), size))
+            if best >= 0.95 * total:
+                best_size, best_energy = size, best
+                break
+        assert len(keep) == best_size
+        assert np.isclose(float((x[keep] ** 2).sum()), best_energy)
+    y = rng.standard_normal((4, 50)) * (rng.random((4, 50)) < 0.25)
+    keep = OR.select_by_energy(y)
+    e = (y.ravel() ** 2)
+    assert e[keep].sum() >= 0.95 * e.sum()
+    assert e[keep].sum() - e[keep].min() < 0.95 * e.sum()      # dropping the smallest kept entry falls short
+    assert e[keep].min() >= np.delete(e, keep).max()           # nothing larger was left out
+    assert OR.select_by_energy(np.zeros(7)).size == 0
