@@ -201,6 +201,47 @@ int32_t gf_attn_decode(gf_ctx *ctx, const gf_attn_params *params, const gf_kv_po
                        const gf_tables *tables,
                        const void *q, void *o, float *lse, void *stream);
 
+/* per-block status words written by gf_kv_apply_residual */
+#define GF_RS_OK         0
+#define GF_RS_BAD_BLOCK  1   /* source or destination block id outside the pool: block skipped */
+#define GF_RS_BAD_INDEX  2   /* a residual entry addresses an element outside the block: entry ignored */
+
+/*
+ * gf_kv_apply_residual -- reconstruct prefix-conditioned KV blocks from base
+ * blocks and sparse residuals (paper, "Differential-based KV Cache", Eq. 7:
+ * KV(P, v) = KV_base(v) + dKV(P, v): the base KV of an operation node is loaded
+ * and the residual of the current prefix is applied to it).
+ *
+ * Item b (one 16-token pool block, all kv heads, K and V):
+ *   block dst_blocks[b]  <-  block src_blocks[b]  +  its residual entries
+ *   res_idx[res_ptr[b] .. res_ptr[b+1]), res_val[...]
+ * A residual entry adds the bf16 value res_val[e] to the LOGICAL element
+ *   res_idx[e] = ((t * num_kv_heads + h) * 16 + slot) * head_dim + d
+ * with t = 0 for K and 1 for V, whatever the physical layout of the tensor inside
+ * the block.  Each sum is taken in fp32 and rounded to bf16 (nearest even); the
+ * elements no entry names are copied bit for bit.  The base blocks are not
+ * modified.  The caller then lists the destination blocks as the block list of
+ * a prefix-conditioned instance of the node in the wGraph handed to
+ * gf_resolve_path; the attention calls read them like any other block.
+ *
+ * Contract: the destination blocks are distinct from each other and from every
+ * source block of the call; the entries of one block name distinct elements
+ * (a repeated element is a race); res_ptr is non-decreasing from 0.
+ * GF_BF16 pools only (GF_FP8_E4M3 returns GF_ERR_UNSUPPORTED: a sum would have
+ * to be re-quantised under a new block scale).
+ *   k_pool, v_pool  the pool tensors (device, read and written)
+ *   status          [num_items] device, out, or NULL: GF_RS_* per item
+ */
+int32_t gf_kv_apply_residual(gf_ctx *ctx, const gf_attn_params *params,
+                             void *k_pool, void *v_pool, int32_t num_pool_blocks,
+                             int32_t num_items,
+                             const int32_t *src_blocks,  /* [num_items] device */
+                             const int32_t *dst_blocks,  /* [num_items] device */
+                             const int32_t *res_ptr,     /* [num_items + 1] device */
+                             const uint32_t *res_idx,    /* [res_ptr[num_items]] device */
+                             const uint16_t *res_val,    /* [res_ptr[num_items]] device, bf16 bits */
+                             int32_t *status, void *stream);
+
 /* Tuning knob (host): table entries (16-token blocks) per split-KV chunk in
  * gf_attn_decode; 0 restores the built-in choice.  Must be even. */
 int32_t gf_set_decode_chunk_blocks(gf_ctx *ctx, int32_t chunk_blocks);

@@ -19,9 +19,10 @@ GF_OK = 0
 GF_ERR_NULL, GF_ERR_BAD_SHAPE, GF_ERR_UNSUPPORTED, GF_ERR_WORKSPACE, GF_ERR_HIP = -1, -2, -3, -4, -5
 GF_ST_OK, GF_ST_BAD_NODE, GF_ST_BAD_EDGE, GF_ST_BAD_TAIL, GF_ST_BAD_BLOCK, GF_ST_OVERFLOW = 0, 1, 2, 3, 4, 5
 GF_BF16, GF_FP8_E4M3 = 0, 1
+GF_RS_OK, GF_RS_BAD_BLOCK, GF_RS_BAD_INDEX = 0, 1, 2
 
 EXPORTS = ["gf_create", "gf_destroy", "gf_strerror", "gf_last_hip_error", "gf_resolve_path",
-           "gf_attn_prefill", "gf_attn_decode", "gf_set_decode_chunk_blocks"]
+           "gf_attn_prefill", "gf_attn_decode", "gf_set_decode_chunk_blocks", "gf_kv_apply_residual"]
 
 _i32p = C.c_void_p  # device pointers travel as plain addresses
 
@@ -86,6 +87,9 @@ def load_library(path: Optional[str] = None):
     lib.gf_attn_decode.argtypes = [C.c_void_p, C.POINTER(gf_attn_params), C.POINTER(gf_kv_pool),
                                    C.POINTER(gf_tables), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.gf_attn_decode.restype = C.c_int32
+    lib.gf_kv_apply_residual.argtypes = [C.c_void_p, C.POINTER(gf_attn_params), C.c_void_p, C.c_void_p, C.c_int32,
+                                         C.c_int32] + [C.c_void_p] * 6 + [C.c_void_p]
+    lib.gf_kv_apply_residual.restype = C.c_int32
     if path is None:
         _lib = lib
     return lib
@@ -165,4 +169,12 @@ def gf_attn_prefill(ctx, params, pool, tables, q, q_ptr, total_q, max_q, o, lse=
 def gf_attn_decode(ctx, params, pool, tables, q, o, lse=None) -> None:
     rc = load_library().gf_attn_decode(ctx, C.byref(params), C.byref(pool), C.byref(tables), _ptr(q),
                                        _ptr(o), _ptr(lse), _stream())
+    _check(ctx, rc)
+
+
+def gf_kv_apply_residual(ctx, params, k_pool, v_pool, num_pool_blocks, num_items, src_blocks, dst_blocks, res_ptr,
+                         res_idx, res_val, status=None) -> None:
+    rc = load_library().gf_kv_apply_residual(ctx, C.byref(params), _ptr(k_pool), _ptr(v_pool), num_pool_blocks,
+                                             num_items, _ptr(src_blocks), _ptr(dst_blocks), _ptr(res_ptr),
+                                             _ptr(res_idx), _ptr(res_val), _ptr(status), _stream())
     _check(ctx, rc)

@@ -133,6 +133,22 @@ class Session:
         params, dpool, dt = self._common(pool, tables, sm_scale)
         B.gf_attn_prefill(self.ctx, params, dpool, dt, q, q_ptr, total_q, max_q, o, lse)
 
+    def upload_residuals(self, res: W.Residuals):
+        dev = self.device
+        i32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(dev)
+        idx = res.res_idx if res.res_idx.size else np.zeros(1, np.uint32)
+        val = res.res_val if res.res_val.size else np.zeros(1, np.uint16)
+        return dict(src=i32(res.src_blocks if res.num_items else [0]), dst=i32(res.dst_blocks if res.num_items else [0]),
+                    ptr=i32(res.res_ptr), idx=torch.from_numpy(idx.view(np.int32)).to(dev),
+                    val=torch.from_numpy(val.view(np.int16)).to(dev), num_items=res.num_items,
+                    status=torch.full((max(res.num_items, 1),), -77, dtype=torch.int32, device=dev))
+
+    def apply_residual(self, pool, dres):
+        sh = self.wl.shape
+        params = B.make_params(sh.num_q_heads, sh.num_kv_heads, sh.head_dim, sh.kv_dtype)
+        B.gf_kv_apply_residual(self.ctx, params, pool.k, pool.v, pool.num_blocks, dres["num_items"], dres["src"],
+                               dres["dst"], dres["ptr"], dres["idx"], dres["val"], dres["status"])
+
     def decode(self, pool, tables, q, o, lse=None, sm_scale=0.0):
         params, dpool, dt = self._common(pool, tables, sm_scale)
         B.gf_attn_decode(self.ctx, params, dpool, dt, q, o, lse)

@@ -430,6 +430,95 @@ def make_tensors(wl: Workload, pad_std: float = 10.0, value_mode: str = "normal"
 
 
 # --------------------------------------------------------------------------- #
+# prefix-conditioned node instances with sparse residuals (differential KV cache)
+# --------------------------------------------------------------------------- #
+@dataclasses.dataclass
+class Residuals:
+    """One item per pool block of every instance: copy block src to block dst and
+    add the entries res_idx/res_val[res_ptr[b]:res_ptr[b+1]] (logical element
+    index ((t*Hkv + h)*16 + slot)*D + d, bf16 bits)."""
+    src_blocks: np.ndarray   # int32 [items]
+    dst_blocks: np.ndarray   # int32 [items]
+    res_ptr: np.ndarray      # int32 [items + 1]
+    res_idx: np.ndarray      # uint32
+    res_val: np.ndarray      # uint16
+
+    @property
+    def num_items(self) -> int:
+        return int(self.src_blocks.shape[0])
+
+    def bytes_moved(self, shape: Shape) -> float:
+        """Algorithmic bytes of one application: base block read, reconstructed
+        block written (K and V, all kv heads), entries (4 B index + 2 B value) and
+        8 B of block ids + 4 B of row pointer per item."""
+        blk = 2 * shape.num_kv_heads * BLOCK * shape.head_dim * 2
+        return float(self.num_items) * (2 * blk + 12) + 6.0 * float(self.res_idx.shape[0])
+
+
+def add_residual_instances(wl: Workload, last_nodes: int = 1, density_k: float = 0.25, density_v: float = 0.30,
+                           std: float = 0.3, seed: int = 11) -> tuple:
+    """Give every request private, prefix-conditioned instances of the last
+    ``last_nodes`` nodes of its path: new node ids with their own (new) pool
+    blocks, an edge from the predecessor, and a sparse residual against the
+    original node's blocks (entries on valid token slots only; a share
+    density_k / density_v of the K / V elements, values N(0, std^2) in bf16 --
+    the paper reports that more than 75 % of key and 70 % of value entries of a
+    prefix-induced difference are negligible).  Returns (workload', Residuals);
+    the pool of the new workload is larger by the instance blocks, which hold
+    nothing until the residuals are applied."""
+    rng = np.random.default_rng([wl.seed, seed])
+    g, b, sh = wl.graph, wl.batch, wl.shape
+    hkv, dim = sh.num_kv_heads, sh.head_dim
+    node_len = list(g.node_len)
+    node_blocks = [list(g.node_blocks[g.node_block_ptr[v]:g.node_block_ptr[v + 1]]) for v in range(g.num_nodes)]
+    edges = [(v, int(d)) for v in range(g.num_nodes) for d in g.edge_dst[g.edge_ptr[v]:g.edge_ptr[v + 1]]]
+    path_nodes = b.path_nodes.copy()
+    next_block = wl.num_pool_blocks
+    src, dst, ptr, idx, val = [], [], [0], [], []
+    per_tensor = hkv * BLOCK * dim
+    for r in range(b.num_req):
+        p0, p1 = int(b.path_ptr[r]), int(b.path_ptr[r + 1])
+        for pos in range(max(p0, p1 - last_nodes), p1):
+            v = int(path_nodes[pos])
+            inst = len(node_len)
+            node_len.append(node_len[v])
+            nb = _nblk(node_len[v])
+            blocks = list(range(next_block, next_block + nb))
+            next_block += nb
+            node_blocks.append(blocks)
+            if pos > p0:
+                edges.append((int(path_nodes[pos - 1]), inst))
+            if pos + 1 < p1:
+                edges.append((inst, int(path_nodes[pos + 1])))
+            path_nodes[pos] = inst
+            for bi in range(nb):
+                ntok = min(BLOCK, int(node_len[v]) - bi * BLOCK)
+                ent = []
+                for t, dens in ((0, density_k), (1, density_v)):
+                    m = rng.random((hkv, ntok, dim)) < dens
+                    h, slot, d = np.nonzero(m)
+                    ent.append(((t * hkv + h) * BLOCK + slot) * dim + d)
+                e = np.concatenate(ent).astype(np.uint32)
+                assert e.size == 0 or e.max() < 2 * per_tensor
+                src.append(node_blocks[v][bi])
+                dst.append(blocks[bi])
+                idx.append(e)
+                val.append(f32_to_bf16_bits((rng.standard_normal(e.size) * std).astype(np.float32)))
+                ptr.append(ptr[-1] + e.size)
+    n = len(node_len)
+    edge_ptr, edge_dst = edges_to_csr(n, sorted(set(edges)))
+    nbp = np.concatenate([[0], np.cumsum([len(x) for x in node_blocks])])
+    graph = WGraph(n, _i32(node_len), _i32(nbp), _i32([x for bl in node_blocks for x in bl]), edge_ptr, edge_dst)
+    batch = Batch(b.path_ptr.copy(), _i32(path_nodes), b.new_lens.copy(), b.tail_ptr.copy(), b.tail_blocks.copy())
+    wl2 = Workload(wl.name + "+residual", sh, graph, batch, next_block, wl.seed, wl.prefill_req.copy(),
+                   wl.decode_req.copy(), wl.zipf_s)
+    res = Residuals(_i32(src), _i32(dst), _i32(ptr),
+                    np.concatenate(idx).astype(np.uint32) if idx else np.zeros(0, np.uint32),
+                    np.concatenate(val).astype(np.uint16) if val else np.zeros(0, np.uint16))
+    return wl2, res
+
+
+# --------------------------------------------------------------------------- #
 # accounting (pure counting; used by bench and docs)
 # --------------------------------------------------------------------------- #
 def context_lens(wl: Workload) -> np.ndarray:

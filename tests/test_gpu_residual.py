@@ -1,0 +1,117 @@
+"""gf_kv_apply_residual through the C ABI vs oracle/residual.py (bit-exact), and
+attention over the reconstructed blocks vs the attention oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import attention as OA
+from oracle import residual as OR
+from paper_2605_22566_amd import binding as B
+from paper_2605_22566_amd import runner as R
+from paper_2605_22566_amd import workload as W
+from tests.gpu_common import assert_close, bf16_out_to_f64, run_resolve
+from tests.helpers import oracle_resolve
+
+pytestmark = pytest.mark.gpu
+
+
+def _setup(shape, seed, last_nodes=2, **kw):
+    wl = W.small_layered(seed, shape, num_nodes=24, num_layers=5, len_lo=3, len_hi=90, num_req=5, hops=(1, 5),
+                         new_lo=1, new_hi=40)
+    t = W.make_tensors(wl)
+    wl2, res = W.add_residual_instances(wl, last_nodes=last_nodes, **kw)
+    extra = wl2.num_pool_blocks - wl.num_pool_blocks
+    nan_k = np.full((extra,) + t.k_pool.shape[1:], 0x7FC0, np.uint16)      # must be overwritten completely
+    nan_v = np.full((extra,) + t.v_pool.shape[1:], 0x7FC0, np.uint16)
+    t.k_pool = np.concatenate([t.k_pool, nan_k])
+    t.v_pool = np.concatenate([t.v_pool, nan_v])
+    return wl2, t, res
+
+
+def _apply_on_gpu(wl2, t, res):
+    sess, tables = run_resolve(wl2)
+    pool = R.DevicePool.from_host(t, sess.device)
+    dres = sess.upload_residuals(res)
+    sess.apply_residual(pool, dres)
+    torch.cuda.synchronize()
+    return sess, tables, pool, dres
+
+
+@pytest.mark.parametrize("shape", [W.Shape(8, 2, 64), W.Shape(32, 8, 128), W.Shape(4, 1, 128)],
+                         ids=lambda s: f"kv{s.num_kv_heads}d{s.head_dim}")
+def test_reconstruction_is_bit_exact(shape):
+    wl2, t, res = _setup(shape, 300 + shape.head_dim + shape.num_kv_heads)
+    want_k, want_v, want_st = OR.reconstruct(t.k_pool, t.v_pool, res.src_blocks, res.dst_blocks, res.res_ptr,
+                                             res.res_idx, res.res_val)
+    sess, _, pool, dres = _apply_on_gpu(wl2, t, res)
+    assert dres["status"].cpu().numpy().tolist() == want_st.tolist() == [0] * res.num_items
+    assert np.array_equal(R.bf16_to_bits(pool.k), want_k)
+    assert np.array_equal(R.bf16_to_bits(pool.v), want_v)
+    assert not np.isnan(OR.bf16_bits_to_f32(want_k[res.dst_blocks])).any()
+
+
+def test_densities_zero_and_one_and_no_items():
+    shape = W.Shape(8, 2, 64)
+    for dk, dv in ((0.0, 0.0), (1.0, 1.0)):
+        wl2, t, res = _setup(shape, 41, last_nodes=1, density_k=dk, density_v=dv)
+        want_k, want_v, _ = OR.reconstruct(t.k_pool, t.v_pool, res.src_blocks, res.dst_blocks, res.res_ptr,
+                                           res.res_idx, res.res_val)
+        _, _, pool, _ = _apply_on_gpu(wl2, t, res)
+        assert np.array_equal(R.bf16_to_bits(pool.k), want_k) and np.array_equal(R.bf16_to_bits(pool.v), want_v)
+    wl2, t, res = _setup(shape, 42, last_nodes=1)
+    empty = W.Residuals(res.src_blocks[:0], res.dst_blocks[:0], res.res_ptr[:1], res.res_idx[:0], res.res_val[:0])
+    _, _, pool, _ = _apply_on_gpu(wl2, t, empty)
+    assert np.array_equal(R.bf16_to_bits(pool.k), t.k_pool)
+
+
+def test_bad_block_and_bad_index_are_reported_and_contained():
+    shape = W.Shape(8, 2, 64)
+    wl2, t, res = _setup(shape, 43, last_nodes=1)
+    per = shape.num_kv_heads * 16 * shape.head_dim
+    res.src_blocks[1] = wl2.num_pool_blocks + 5             # outside the pool
+    res.dst_blocks[2] = -1
+    e = int(res.res_ptr[0])
+    res.res_idx[e] = 2 * per                                 # first entry of item 0: outside the block
+    want_k, want_v, want_st = OR.reconstruct(t.k_pool, t.v_pool, res.src_blocks, res.dst_blocks, res.res_ptr,
+                                             res.res_idx, res.res_val)
+    assert want_st[:3].tolist() == [OR.ST_BAD_INDEX, OR.ST_BAD_BLOCK, OR.ST_BAD_BLOCK]
+    _, _, pool, dres = _apply_on_gpu(wl2, t, res)
+    assert dres["status"].cpu().numpy().tolist() == want_st.tolist()
+    got_k, got_v = R.bf16_to_bits(pool.k), R.bf16_to_bits(pool.v)
+    assert np.array_equal(got_k, want_k) and np.array_equal(got_v, want_v)
+
+
+def test_fp8_pool_is_refused():
+    shape = W.Shape(8, 2, 64, W.KV_FP8_E4M3)
+    wl = W.small_layered(44, shape, num_req=2)
+    sess = R.Session(wl)
+    params = B.make_params(8, 2, 64, W.KV_FP8_E4M3)
+    z = torch.zeros(4, dtype=torch.int32, device=sess.device)
+    with pytest.raises(B.GraphFlowError) as ei:
+        B.gf_kv_apply_residual(sess.ctx, params, z, z, 1, 1, z, z, z, z, z, None)
+    assert ei.value.code == B.GF_ERR_UNSUPPORTED
+
+
+def test_attention_over_reconstructed_instances_matches_the_oracle():
+    """base + residual -> instance blocks -> resolve (instances on the paths) -> prefill and decode."""
+    shape = W.Shape(32, 8, 128)
+    wl2, t, res = _setup(shape, 45, last_nodes=2)
+    want_k, want_v, _ = OR.reconstruct(t.k_pool, t.v_pool, res.src_blocks, res.dst_blocks, res.res_ptr,
+                                       res.res_idx, res.res_val)
+    sess, tables, pool, _ = _apply_on_gpu(wl2, t, res)
+    assert tables["status"].cpu().numpy().tolist() == [0] * wl2.batch.num_req
+    dev = sess.device
+    q = R.bits_to_device(t.q, dev)
+    q_ptr = torch.from_numpy(t.q_ptr).to(dev)
+    o = torch.full(q.shape, float("nan"), dtype=torch.bfloat16, device=dev)
+    sess.prefill(pool, tables, q, q_ptr, int(t.q.shape[0]), int(wl2.batch.new_lens.max()), o)
+    last = (t.q_ptr[1:] - 1).astype(np.int64)
+    qd = R.bits_to_device(np.ascontiguousarray(t.q[last]), dev)
+    od = torch.full(qd.shape, float("nan"), dtype=torch.bfloat16, device=dev)
+    sess.decode(pool, tables, qd, od)
+    torch.cuda.synchronize()
+    ot = oracle_resolve(wl2)
+    O, _ = OA.prefill(t.q, t.q_ptr, want_k, want_v, ot)
+    Od, _ = OA.decode(np.ascontiguousarray(t.q[last]), want_k, want_v, ot)
+    assert_close(bf16_out_to_f64(o), O, W.KV_BF16, "prefill over instances")
+    assert_close(bf16_out_to_f64(od), Od, W.KV_BF16, "decode over instances")
