@@ -156,6 +156,34 @@ def measure(job, steps, warmup):
     return out
 
 
+def measure_residual(torch, R, W, num_items=8192, iters=20):
+    """gf_kv_apply_residual on the 8B head shape: num_items pool blocks reconstructed from base
+    blocks and residuals of the density the paper reports (25 % of K, 30 % of V elements)."""
+    sh = W.Shape(32, 8, 128)
+    dev = torch.device("cuda:0")
+    wl = W.small_layered(1, sh, num_req=1)                    # only carries the shape for the session
+    sess = R.Session(wl, dev)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(5)
+    nb = 2 * num_items
+    k = torch.randn((nb, sh.num_kv_heads, W.BLOCK, sh.head_dim), generator=gen, device=dev).to(torch.bfloat16)
+    v = torch.randn((nb, sh.num_kv_heads, sh.head_dim, W.BLOCK), generator=gen, device=dev).to(torch.bfloat16)
+    pool = R.DevicePool(k, v, nb)
+    dres, nnz = R.random_residuals(sh, num_items, dev)
+    fn = lambda: sess.apply_residual(pool, dres)
+    for _ in range(3):
+        fn()
+    torch.cuda.synchronize()
+    ms = _event_ms(fn, torch, iters)
+    blk = 2 * sh.num_kv_heads * W.BLOCK * sh.head_dim * 2
+    nbytes = num_items * (2 * blk + 8 + 4 * 2 * sh.num_kv_heads) + 4.0 * nnz
+    ok = bool((dres["status"] == 0).all().item())
+    return {"kernel": "residual_kernel", "kernel_ms": ms, "blocks": num_items, "entries": nnz,
+            "algorithmic_bytes_per_launch": nbytes, "gbs_kernel": nbytes / (ms * 1e-3) / 1e9,
+            "frac_of_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "all_items_ok": ok,
+            "hbm_bytes_per_launch_rocprof": _read_traffic("residual_kv_residual")}
+
+
 def cpu_baseline(job, budget_s=20.0):
     """Time the fp64 oracle on a bounded sample of the workload's requests and
     check the GPU outputs of the sample against it."""
@@ -223,7 +251,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="prefill_8b",
                     choices=["tiny", "prefill_8b", "decode_8b", "decode_70b", "mixed_fp8"])
-    ap.add_argument("--extra", default="decode_8b", help="comma list of further workloads reported under 'extra'")
+    ap.add_argument("--extra", default="decode_8b,kv_residual",
+                    help="comma list of further workloads reported under 'extra' (the five configs, kv_residual)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=20.0)
     ap.add_argument("--copy-calibration", action="store_true",
@@ -294,7 +323,12 @@ def main():
     extra = {}
     del job
     torch.cuda.empty_cache()
-    for name in [x for x in args.extra.split(",") if x and x != args.workload]:
+    names = [x for x in args.extra.split(",") if x and x != args.workload]
+    if "kv_residual" in names:
+        names.remove("kv_residual")
+        extra["kv_residual"] = measure_residual(torch, R, W)
+        torch.cuda.empty_cache()
+    for name in names:
         j = Job(name, torch, R, W, decode_after_prefill=False)
         mm = measure(j, max(5, args.steps // 2), 3)
         ent = {"ms_per_step": mm["ms_per_step"], "breakdown_ms": {k: v for k, v in mm.items() if k.endswith("_ms")}}

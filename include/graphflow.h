@@ -204,7 +204,7 @@ int32_t gf_attn_decode(gf_ctx *ctx, const gf_attn_params *params, const gf_kv_po
 /* per-block status words written by gf_kv_apply_residual */
 #define GF_RS_OK         0
 #define GF_RS_BAD_BLOCK  1   /* source or destination block id outside the pool: block skipped */
-#define GF_RS_BAD_INDEX  2   /* a residual entry addresses an element outside the block: entry ignored */
+#define GF_RS_BAD_INDEX  2   /* a residual entry addresses an element outside its image: entry ignored */
 
 /*
  * gf_kv_apply_residual -- reconstruct prefix-conditioned KV blocks from base
@@ -213,19 +213,21 @@ int32_t gf_attn_decode(gf_ctx *ctx, const gf_attn_params *params, const gf_kv_po
  * and the residual of the current prefix is applied to it).
  *
  * Item b (one 16-token pool block, all kv heads, K and V):
- *   block dst_blocks[b]  <-  block src_blocks[b]  +  its residual entries
- *   res_idx[res_ptr[b] .. res_ptr[b+1]), res_val[...]
- * A residual entry adds the bf16 value res_val[e] to the LOGICAL element
- *   res_idx[e] = ((t * num_kv_heads + h) * 16 + slot) * head_dim + d
- * with t = 0 for K and 1 for V, whatever the physical layout of the tensor inside
- * the block.  Each sum is taken in fp32 and rounded to bf16 (nearest even); the
- * elements no entry names are copied bit for bit.  The base blocks are not
- * modified.  The caller then lists the destination blocks as the block list of
- * a prefix-conditioned instance of the node in the wGraph handed to
+ *   block dst_blocks[b]  <-  block src_blocks[b]  +  its residual entries.
+ * The residual is a CSR with one row per (item, tensor, kv head) "image" of
+ * 16 x head_dim elements: row r = (b * 2 + t) * num_kv_heads + h, t = 0 for K and
+ * 1 for V, holds the entries res_idx[res_ptr[r] .. res_ptr[r+1]), res_val[...].
+ * An entry adds the bf16 value res_val[e] to the LOGICAL element
+ *   res_idx[e] = slot * head_dim + d          (token slot 0..15 of the block)
+ * of its image, whatever the physical layout of the tensor inside the block.
+ * Each sum is taken in fp32 and rounded to bf16 (nearest even); the elements no
+ * entry names are copied bit for bit.  The base blocks are not modified.  The
+ * caller then lists the destination blocks as the block list of a
+ * prefix-conditioned instance of the node in the wGraph handed to
  * gf_resolve_path; the attention calls read them like any other block.
  *
  * Contract: the destination blocks are distinct from each other and from every
- * source block of the call; the entries of one block name distinct elements
+ * source block of the call; the entries of one row name distinct elements
  * (a repeated element is a race); res_ptr is non-decreasing from 0.
  * GF_BF16 pools only (GF_FP8_E4M3 returns GF_ERR_UNSUPPORTED: a sum would have
  * to be re-quantised under a new block scale).
@@ -237,9 +239,9 @@ int32_t gf_kv_apply_residual(gf_ctx *ctx, const gf_attn_params *params,
                              int32_t num_items,
                              const int32_t *src_blocks,  /* [num_items] device */
                              const int32_t *dst_blocks,  /* [num_items] device */
-                             const int32_t *res_ptr,     /* [num_items + 1] device */
-                             const uint32_t *res_idx,    /* [res_ptr[num_items]] device */
-                             const uint16_t *res_val,    /* [res_ptr[num_items]] device, bf16 bits */
+                             const int32_t *res_ptr,     /* [num_items * 2 * num_kv_heads + 1] device */
+                             const uint16_t *res_idx,    /* [res_ptr[last]] device */
+                             const uint16_t *res_val,    /* [res_ptr[last]] device, bf16 bits */
                              int32_t *status, void *stream);
 
 /* Tuning knob (host): table entries (16-token blocks) per split-KV chunk in

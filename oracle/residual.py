@@ -7,8 +7,9 @@ prefix-specific residual.  TEST INFRASTRUCTURE ONLY (see the package header).
 
 What is computed here, block by block of the paged pool:
   * reconstruct(): copy the base blocks of a node to destination blocks and add the
-    residual entries.  A residual entry addresses the LOGICAL element
-        i = ((t * Hkv + h) * 16 + slot) * D + d,   t = 0 for K, 1 for V,
+    residual entries.  The residual is a CSR with one row per (item, tensor, kv
+    head) image of 16 x D elements, row = (item * 2 + t) * Hkv + h with t = 0 for K
+    and 1 for V; an entry addresses the LOGICAL element slot * D + d of its image,
     whatever the physical layout of the tensor inside the block (K is stored
     [h][slot][d], V is stored [h][d][slot]).  The sum is taken in fp32 and rounded
     to bf16 round-to-nearest-even -- the stored code is a quantisation decision, so
@@ -19,9 +20,10 @@ What is computed here, block by block of the paged pool:
     residual is obtained.
 
 Readings: the paper does not fix the storage format of a residual (coordinate list
-here, one CSR row per pool block), its value precision (bf16 here, like the pool), or
-what happens to malformed input (a block id outside the pool skips the item, an
-element index outside the block is ignored; both are reported per item).
+here, one CSR row per block, tensor and kv head, 16-bit element index), its value
+precision (bf16 here, like the pool), or what happens to malformed input (a block
+id outside the pool skips the item, an element index outside the image is ignored;
+both are reported per item).
 
 Pins (tests/test_oracle_residual.py): the bf16 rounding against torch's cast on
 random values, ties and extremes; an empty residual is the identity; the residual
@@ -48,8 +50,8 @@ def bf16_bits_to_f32(bits: np.ndarray) -> np.ndarray:
     return (np.ascontiguousarray(bits).astype(np.uint32) << np.uint32(16)).view(np.float32)
 
 
-def logical_index(t: int, h: int, slot: int, d: int, hkv: int, dim: int) -> int:
-    return ((t * hkv + h) * BLOCK + slot) * dim + d
+def csr_row(item: int, t: int, h: int, hkv: int) -> int:
+    return (item * 2 + t) * hkv + h
 
 
 def reconstruct(k_pool: np.ndarray, v_pool: np.ndarray, src_blocks, dst_blocks, res_ptr, res_idx, res_val):
@@ -57,7 +59,6 @@ def reconstruct(k_pool: np.ndarray, v_pool: np.ndarray, src_blocks, dst_blocks, 
     Returns (k_pool', v_pool', status[num_items]); the inputs are not modified."""
     k_out, v_out = k_pool.copy(), v_pool.copy()
     nb, hkv, _, dim = k_pool.shape
-    per_tensor = hkv * BLOCK * dim
     n_items = len(src_blocks)
     status = np.zeros(n_items, dtype=np.int32)
     for b in range(n_items):
@@ -67,19 +68,20 @@ def reconstruct(k_pool: np.ndarray, v_pool: np.ndarray, src_blocks, dst_blocks, 
             continue
         kb = bf16_bits_to_f32(k_pool[s]).copy()          # [Hkv, 16, D]
         vb = bf16_bits_to_f32(v_pool[s]).copy()          # [Hkv, D, 16]
-        for e in range(int(res_ptr[b]), int(res_ptr[b + 1])):
-            i = int(res_idx[e])
-            if not (0 <= i < 2 * per_tensor):
-                status[b] = ST_BAD_INDEX
-                continue
-            val = bf16_bits_to_f32(np.array([res_val[e]], dtype=np.uint16))[0]
-            tensor, rem = divmod(i, per_tensor)
-            h, rem = divmod(rem, BLOCK * dim)
-            slot, d = divmod(rem, dim)
-            if tensor == 0:
-                kb[h, slot, d] = np.float32(kb[h, slot, d]) + np.float32(val)
-            else:
-                vb[h, d, slot] = np.float32(vb[h, d, slot]) + np.float32(val)
+        for tensor in (0, 1):
+            for h in range(hkv):
+                r = (b * 2 + tensor) * hkv + h
+                for e in range(int(res_ptr[r]), int(res_ptr[r + 1])):
+                    i = int(res_idx[e])
+                    if not (0 <= i < BLOCK * dim):
+                        status[b] = ST_BAD_INDEX
+                        continue
+                    val = bf16_bits_to_f32(np.array([res_val[e]], dtype=np.uint16))[0]
+                    slot, d = divmod(i, dim)
+                    if tensor == 0:
+                        kb[h, slot, d] = np.float32(kb[h, slot, d]) + np.float32(val)
+                    else:
+                        vb[h, d, slot] = np.float32(vb[h, d, slot]) + np.float32(val)
         k_out[t] = f32_to_bf16_bits_rne(kb)
         v_out[t] = f32_to_bf16_bits_rne(vb)
     return k_out, v_out, status

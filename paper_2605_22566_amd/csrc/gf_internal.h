@@ -51,7 +51,7 @@ hipError_t launch_decode(const AttnArgs &a, int head_dim, int group, int kv_dtyp
 // residual application: one workgroup per pool block
 hipError_t launch_residual(void *k_pool, void *v_pool, int32_t num_pool_blocks, int32_t hkv, int32_t head_dim,
                            int32_t num_items, const int32_t *src_blocks, const int32_t *dst_blocks,
-                           const int32_t *res_ptr, const uint32_t *res_idx, const uint16_t *res_val,
+                           const int32_t *res_ptr, const uint16_t *res_idx, const uint16_t *res_val,
                            int32_t *status, hipStream_t s);
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }

@@ -74,6 +74,36 @@ class DevicePool:
                 self.v_scale[idx].cpu().numpy())
 
 
+def random_residuals(shape: W.Shape, num_items: int, device, density_k=0.25, density_v=0.30, std=0.3, seed=1):
+    """Synthetic residuals for `num_items` blocks, generated on the device: item b
+    copies block b (source half of a pool of 2*num_items blocks) to block
+    num_items + b and carries a random share of the K / V elements of every
+    (tensor, kv head) image (N(0, std^2) values in bf16).  Returns the dict that
+    Session.apply_residual takes, plus the number of entries."""
+    gen = torch.Generator(device=device)
+    gen.manual_seed(seed)
+    rows, img = 2 * shape.num_kv_heads, W.BLOCK * shape.head_dim      # images per block, elements per image
+    thr = torch.cat([torch.full((shape.num_kv_heads, 1), density_k, device=device),
+                     torch.full((shape.num_kv_heads, 1), density_v, device=device)])
+    counts, idx_parts = [], []
+    step = 512
+    for lo in range(0, num_items, step):
+        n = min(step, num_items - lo)
+        m = torch.rand((n, rows, img), generator=gen, device=device) < thr
+        counts.append(m.sum(dim=2, dtype=torch.int32).reshape(-1))
+        idx_parts.append(m.nonzero()[:, 2].to(torch.int16))
+        del m
+    counts = torch.cat(counts)
+    idx = torch.cat(idx_parts)
+    ptr = torch.zeros(num_items * rows + 1, dtype=torch.int32, device=device)
+    ptr[1:] = torch.cumsum(counts, 0)
+    val = (torch.randn(idx.numel(), generator=gen, device=device) * std).to(torch.bfloat16).view(torch.int16)
+    src = torch.randperm(num_items, generator=gen, device=device).to(torch.int32)
+    dst = torch.arange(num_items, 2 * num_items, dtype=torch.int32, device=device)
+    return dict(src=src, dst=dst, ptr=ptr, idx=idx, val=val, num_items=num_items,
+                status=torch.full((num_items,), -77, dtype=torch.int32, device=device)), int(idx.numel())
+
+
 class Session:
     """One gf_ctx + the device copies of a workload's graph."""
 
@@ -136,10 +166,10 @@ class Session:
     def upload_residuals(self, res: W.Residuals):
         dev = self.device
         i32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(dev)
-        idx = res.res_idx if res.res_idx.size else np.zeros(1, np.uint32)
+        idx = res.res_idx if res.res_idx.size else np.zeros(1, np.uint16)
         val = res.res_val if res.res_val.size else np.zeros(1, np.uint16)
         return dict(src=i32(res.src_blocks if res.num_items else [0]), dst=i32(res.dst_blocks if res.num_items else [0]),
-                    ptr=i32(res.res_ptr), idx=torch.from_numpy(idx.view(np.int32)).to(dev),
+                    ptr=i32(res.res_ptr), idx=torch.from_numpy(idx.view(np.int16)).to(dev),
                     val=torch.from_numpy(val.view(np.int16)).to(dev), num_items=res.num_items,
                     status=torch.full((max(res.num_items, 1),), -77, dtype=torch.int32, device=dev))
 

@@ -435,12 +435,13 @@ def make_tensors(wl: Workload, pad_std: float = 10.0, value_mode: str = "normal"
 @dataclasses.dataclass
 class Residuals:
     """One item per pool block of every instance: copy block src to block dst and
-    add the entries res_idx/res_val[res_ptr[b]:res_ptr[b+1]] (logical element
-    index ((t*Hkv + h)*16 + slot)*D + d, bf16 bits)."""
+    add the residual entries.  CSR with one row per (item, tensor, kv head):
+    row (b*2 + t)*Hkv + h (t = 0 K, 1 V) holds res_idx/res_val[res_ptr[row]:
+    res_ptr[row+1]], res_idx = slot*D + d inside that 16 x D image, bf16 bits."""
     src_blocks: np.ndarray   # int32 [items]
     dst_blocks: np.ndarray   # int32 [items]
-    res_ptr: np.ndarray      # int32 [items + 1]
-    res_idx: np.ndarray      # uint32
+    res_ptr: np.ndarray      # int32 [items * 2 * Hkv + 1]
+    res_idx: np.ndarray      # uint16
     res_val: np.ndarray      # uint16
 
     @property
@@ -449,10 +450,11 @@ class Residuals:
 
     def bytes_moved(self, shape: Shape) -> float:
         """Algorithmic bytes of one application: base block read, reconstructed
-        block written (K and V, all kv heads), entries (4 B index + 2 B value) and
-        8 B of block ids + 4 B of row pointer per item."""
+        block written (K and V, all kv heads), entries (2 B index + 2 B value),
+        8 B of block ids per item and 4 B of row pointer per image."""
         blk = 2 * shape.num_kv_heads * BLOCK * shape.head_dim * 2
-        return float(self.num_items) * (2 * blk + 12) + 6.0 * float(self.res_idx.shape[0])
+        return (float(self.num_items) * (2 * blk + 8 + 4 * 2 * shape.num_kv_heads)
+                + 4.0 * float(self.res_idx.shape[0]))
 
 
 def add_residual_instances(wl: Workload, last_nodes: int = 1, density_k: float = 0.25, density_v: float = 0.30,
@@ -475,7 +477,6 @@ def add_residual_instances(wl: Workload, last_nodes: int = 1, density_k: float =
     path_nodes = b.path_nodes.copy()
     next_block = wl.num_pool_blocks
     src, dst, ptr, idx, val = [], [], [0], [], []
-    per_tensor = hkv * BLOCK * dim
     for r in range(b.num_req):
         p0, p1 = int(b.path_ptr[r]), int(b.path_ptr[r + 1])
         for pos in range(max(p0, p1 - last_nodes), p1):
@@ -493,18 +494,16 @@ def add_residual_instances(wl: Workload, last_nodes: int = 1, density_k: float =
             path_nodes[pos] = inst
             for bi in range(nb):
                 ntok = min(BLOCK, int(node_len[v]) - bi * BLOCK)
-                ent = []
-                for t, dens in ((0, density_k), (1, density_v)):
-                    m = rng.random((hkv, ntok, dim)) < dens
-                    h, slot, d = np.nonzero(m)
-                    ent.append(((t * hkv + h) * BLOCK + slot) * dim + d)
-                e = np.concatenate(ent).astype(np.uint32)
-                assert e.size == 0 or e.max() < 2 * per_tensor
                 src.append(node_blocks[v][bi])
                 dst.append(blocks[bi])
-                idx.append(e)
-                val.append(f32_to_bf16_bits((rng.standard_normal(e.size) * std).astype(np.float32)))
-                ptr.append(ptr[-1] + e.size)
+                for t, dens in ((0, density_k), (1, density_v)):
+                    for h in range(hkv):
+                        m = rng.random((ntok, dim)) < dens
+                        slot, d = np.nonzero(m)
+                        e = (slot * dim + d).astype(np.uint16)
+                        idx.append(e)
+                        val.append(f32_to_bf16_bits((rng.standard_normal(e.size) * std).astype(np.float32)))
+                        ptr.append(ptr[-1] + e.size)
     n = len(node_len)
     edge_ptr, edge_dst = edges_to_csr(n, sorted(set(edges)))
     nbp = np.concatenate([[0], np.cumsum([len(x) for x in node_blocks])])
@@ -513,7 +512,7 @@ def add_residual_instances(wl: Workload, last_nodes: int = 1, density_k: float =
     wl2 = Workload(wl.name + "+residual", sh, graph, batch, next_block, wl.seed, wl.prefill_req.copy(),
                    wl.decode_req.copy(), wl.zipf_s)
     res = Residuals(_i32(src), _i32(dst), _i32(ptr),
-                    np.concatenate(idx).astype(np.uint32) if idx else np.zeros(0, np.uint32),
+                    np.concatenate(idx).astype(np.uint16) if idx else np.zeros(0, np.uint16),
                     np.concatenate(val).astype(np.uint16) if val else np.zeros(0, np.uint16))
     return wl2, res
 

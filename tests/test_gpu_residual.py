@@ -67,11 +67,10 @@ def test_densities_zero_and_one_and_no_items():
 def test_bad_block_and_bad_index_are_reported_and_contained():
     shape = W.Shape(8, 2, 64)
     wl2, t, res = _setup(shape, 43, last_nodes=1)
-    per = shape.num_kv_heads * 16 * shape.head_dim
     res.src_blocks[1] = wl2.num_pool_blocks + 5             # outside the pool
     res.dst_blocks[2] = -1
     e = int(res.res_ptr[0])
-    res.res_idx[e] = 2 * per                                 # first entry of item 0: outside the block
+    res.res_idx[e] = 16 * shape.head_dim                     # first entry of item 0: outside its image
     want_k, want_v, want_st = OR.reconstruct(t.k_pool, t.v_pool, res.src_blocks, res.dst_blocks, res.res_ptr,
                                              res.res_idx, res.res_val)
     assert want_st[:3].tolist() == [OR.ST_BAD_INDEX, OR.ST_BAD_BLOCK, OR.ST_BAD_BLOCK]

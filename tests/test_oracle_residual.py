@@ -38,14 +38,16 @@ def test_empty_residual_is_identity_and_minus_base_gives_zero():
     rng = np.random.default_rng(4)
     hkv, dim = 2, 64
     k, v = _pool(rng, 4, hkv, dim)
-    k2, v2, st = OR.reconstruct(k, v, [0, 1], [2, 3], [0, 0, 0], np.zeros(0, np.uint32), np.zeros(0, np.uint16))
+    k2, v2, st = OR.reconstruct(k, v, [0, 1], [2, 3], [0] * (2 * 2 * hkv + 1), np.zeros(0, np.uint16), np.zeros(0, np.uint16))
     assert st.tolist() == [0, 0]
     assert np.array_equal(k2[2], k[0]) and np.array_equal(v2[3], v[1])
     assert np.array_equal(k2[:2], k[:2]) and np.array_equal(v2[:2], v[:2])       # sources untouched
-    # residual = -base on every element of block 0 (logical order: K [h][slot][d], V [h][slot][d])
-    per = hkv * 16 * dim
+    # residual = -base on every element of block 0 (rows: K heads then V heads; inside a row [slot][d])
+    img = 16 * dim
     vals = np.concatenate([k[0].ravel() ^ 0x8000, np.transpose(v[0], (0, 2, 1)).ravel() ^ 0x8000]).astype(np.uint16)
-    k3, v3, st = OR.reconstruct(k, v, [0], [2], [0, 2 * per], np.arange(2 * per, dtype=np.uint32), vals)
+    full_ptr = np.arange(2 * hkv + 1) * img
+    full_idx = np.tile(np.arange(img, dtype=np.uint16), 2 * hkv)
+    k3, v3, st = OR.reconstruct(k, v, [0], [2], full_ptr, full_idx, vals)
     assert st.tolist() == [0]
     assert not (k3[2] & 0x7FFF).any() and not (v3[2] & 0x7FFF).any()
 
@@ -54,11 +56,11 @@ def test_full_density_equals_torch_elementwise_add():
     rng = np.random.default_rng(5)
     hkv, dim = 2, 128
     k, v = _pool(rng, 3, hkv, dim)
-    per = hkv * 16 * dim
+    img = 16 * dim
     dk = _torch_bf16_bits((rng.standard_normal((hkv, 16, dim)) * 0.3).astype(np.float32))
     dv = _torch_bf16_bits((rng.standard_normal((hkv, 16, dim)) * 0.3).astype(np.float32))   # logical [h][slot][d]
     vals = np.concatenate([dk.ravel(), dv.ravel()])
-    k2, v2, _ = OR.reconstruct(k, v, [1], [2], [0, 2 * per], np.arange(2 * per, dtype=np.uint32), vals)
+    k2, v2, _ = OR.reconstruct(k, v, [1], [2], np.arange(2 * hkv + 1) * img, np.tile(np.arange(img, dtype=np.uint16), 2 * hkv), vals)
 
     def tb(bits):
         return torch.from_numpy(bits.astype(np.int16)).view(torch.bfloat16)
@@ -75,8 +77,9 @@ def test_single_entries_land_on_the_hand_indexed_physical_element():
     k, v = _pool(rng, 2, hkv, dim)
     two = np.array([0x4000], np.uint16)                       # bf16 2.0
     for (t, h, slot, d) in [(0, 0, 0, 0), (0, 3, 15, 63), (0, 1, 7, 20), (1, 0, 0, 0), (1, 2, 9, 33), (1, 3, 15, 63)]:
-        i = ((t * hkv + h) * 16 + slot) * dim + d             # written out, not via the oracle's helper
-        k2, v2, st = OR.reconstruct(k, v, [0], [1], [0, 1], np.array([i], np.uint32), two)
+        row = t * hkv + h                                     # written out, not via the oracle's helper
+        ptr = [0] * (row + 1) + [1] * (2 * hkv - row)
+        k2, v2, st = OR.reconstruct(k, v, [0], [1], ptr, np.array([slot * dim + d], np.uint16), two)
         assert st.tolist() == [0]
         dk = k2[1] != k[0]
         dv = v2[1] != v[0]
@@ -92,10 +95,10 @@ def test_bad_block_and_bad_index_are_reported():
     rng = np.random.default_rng(7)
     hkv, dim = 1, 64
     k, v = _pool(rng, 3, hkv, dim)
-    per = hkv * 16 * dim
-    idx = np.array([5, 2 * per, 7], np.uint32)                # the middle one is outside the block
+    idx = np.array([5, 16 * dim, 7], np.uint16)              # the middle one is outside the image
     val = np.array([0x3F80, 0x3F80, 0x3F80], np.uint16)
-    k2, v2, st = OR.reconstruct(k, v, [0, 9, 1], [1, 2, -1], [0, 3, 3, 3], idx, val)
+    # rows per item: K h0, V h0; all three entries sit in the K row of item 0
+    k2, v2, st = OR.reconstruct(k, v, [0, 9, 1], [1, 2, -1], [0, 3, 3, 3, 3, 3, 3], idx, val)
     assert st.tolist() == [OR.ST_BAD_INDEX, OR.ST_BAD_BLOCK, OR.ST_BAD_BLOCK]
     assert (k2[1] != k[0]).sum() == 2                          # the two valid entries were applied
     assert np.array_equal(k2[2], k[2]) and np.array_equal(v2[2], v[2])
@@ -117,13 +120,15 @@ def test_node_reconstruction_equals_segment_level_base_plus_delta():
     delta = np.where(mask, delta, np.float32(0))
     ptr, idx, val = [0], [], []
     for bi in range(nblk):
-        for t, tok, h, d in zip(*np.nonzero(mask)):
-            if tok // 16 == bi:
-                idx.append(((t * hkv + h) * 16 + tok % 16) * dim + d)
-                val.append(delta[t, tok, h, d])
-        ptr.append(len(idx))
+        for t in (0, 1):
+            for h in range(hkv):
+                for tok, d in zip(*np.nonzero(mask[t, :, h, :])):
+                    if tok // 16 == bi:
+                        idx.append((tok % 16) * dim + d)
+                        val.append(delta[t, tok, h, d])
+                ptr.append(len(idx))
     val_bits = _torch_bf16_bits(np.array(val, np.float32))
-    k2, v2, st = OR.reconstruct(k, v, src, dst, ptr, np.array(idx, np.uint32), val_bits)
+    k2, v2, st = OR.reconstruct(k, v, src, dst, ptr, np.array(idx, np.uint16), val_bits)
     assert st.tolist() == [0, 0, 0]
     K, V = OA.materialize_kv(k2, v2, dst, [16, 16, 9], 3)
     want_k = OR.bf16_bits_to_f32(_torch_bf16_bits(base_k + delta[0])).astype(np.float64)
