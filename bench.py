@@ -156,6 +156,21 @@ def measure(job, steps, warmup):
     return out
 
 
+def measure_stream_copy(torch, iters=10):
+    """What a plain device-to-device copy of 1 GiB reaches on this machine (bytes read + bytes written
+    per second): the practical streaming ceiling next to the 8 TB/s on paper."""
+    src = torch.ones(1 << 29, dtype=torch.bfloat16, device="cuda:0")
+    dst = torch.empty_like(src)
+    fn = lambda: dst.copy_(src)
+    for _ in range(3):
+        fn()
+    torch.cuda.synchronize()
+    ms = _event_ms(fn, torch, iters)
+    del src, dst
+    torch.cuda.empty_cache()
+    return {"kernel": "torch copy_ (1 GiB)", "kernel_ms": ms, "gbs_read_plus_write": 2.0 * (1 << 30) / (ms * 1e-3) / 1e9}
+
+
 def measure_residual(torch, R, W, num_items=8192, iters=20):
     """gf_kv_apply_residual on the 8B head shape: num_items pool blocks reconstructed from base
     blocks and residuals of the density the paper reports (25 % of K, 30 % of V elements)."""
@@ -251,8 +266,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="prefill_8b",
                     choices=["tiny", "prefill_8b", "decode_8b", "decode_70b", "mixed_fp8"])
-    ap.add_argument("--extra", default="decode_8b,kv_residual",
-                    help="comma list of further workloads reported under 'extra' (the five configs, kv_residual)")
+    ap.add_argument("--extra", default="decode_8b,kv_residual,stream_copy",
+                    help="comma list of further workloads reported under 'extra' (the five configs, kv_residual, stream_copy)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=20.0)
     ap.add_argument("--copy-calibration", action="store_true",
@@ -324,6 +339,9 @@ def main():
     del job
     torch.cuda.empty_cache()
     names = [x for x in args.extra.split(",") if x and x != args.workload]
+    if "stream_copy" in names:
+        names.remove("stream_copy")
+        extra["stream_copy"] = measure_stream_copy(torch)
     if "kv_residual" in names:
         names.remove("kv_residual")
         extra["kv_residual"] = measure_residual(torch, R, W)

@@ -81,3 +81,43 @@ def test_decode_full_size_sampled(name):
     L = W.context_lens(wl)
     for r in (int(np.argmin(L)), int(np.argmax(L)), wl.batch.num_req - 1):
         _check_rows(wl, pool, want, qb[r:r + 1], og[r:r + 1], r, decode=True)
+
+
+def test_kv_residual_bench_size_sampled_blocks():
+    """The residual launch bench.py times (8192 blocks of the 8B head shape, device-generated
+    residuals): sampled items are reconstructed by the oracle from copies of their base blocks and
+    CSR rows; every other destination block is checked for being written (no NaN fill left)."""
+    from oracle import residual as OR
+    sh = W.Shape(32, 8, 128)
+    n_items = 8192
+    wl = W.small_layered(1, sh, num_req=1)
+    sess = R.Session(wl)
+    dev = sess.device
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(5)
+    nb = 2 * n_items
+    k = torch.randn((nb, sh.num_kv_heads, W.BLOCK, sh.head_dim), generator=gen, device=dev).to(torch.bfloat16)
+    v = torch.randn((nb, sh.num_kv_heads, sh.head_dim, W.BLOCK), generator=gen, device=dev).to(torch.bfloat16)
+    k[n_items:] = float("nan")
+    v[n_items:] = float("nan")
+    pool = R.DevicePool(k, v, nb)
+    dres, nnz = R.random_residuals(sh, n_items, dev)
+    sess.apply_residual(pool, dres)
+    torch.cuda.synchronize()
+    assert bool((dres["status"] == 0).all().item())
+    assert not bool(torch.isnan(pool.k[n_items:]).any().item()) and not bool(torch.isnan(pool.v[n_items:]).any().item())
+    rows = 2 * sh.num_kv_heads
+    ptr = dres["ptr"].cpu().numpy()
+    src = dres["src"].cpu().numpy()
+    dst = dres["dst"].cpu().numpy()
+    rng = np.random.default_rng(3)
+    for b in [0, n_items - 1] + rng.integers(0, n_items, 6).tolist():
+        lo, hi = int(ptr[b * rows]), int(ptr[(b + 1) * rows])
+        idx = dres["idx"][lo:hi].cpu().numpy().view(np.uint16)
+        val = dres["val"][lo:hi].cpu().numpy().view(np.uint16)
+        kk, vv, _, _ = pool.gather_host(np.array([src[b], dst[b]]))
+        base_k = np.stack([kk[0], np.zeros_like(kk[0])])
+        base_v = np.stack([vv[0], np.zeros_like(vv[0])])
+        want_k, want_v, st = OR.reconstruct(base_k, base_v, [0], [1], ptr[b * rows:(b + 1) * rows + 1] - lo, idx, val)
+        assert st.tolist() == [0]
+        assert np.array_equal(want_k[1], kk[1]) and np.array_equal(want_v[1], vv[1]), f"item {b}"
