@@ -244,6 +244,38 @@ int32_t gf_kv_apply_residual(gf_ctx *ctx, const gf_attn_params *params,
                              const uint16_t *res_val,    /* [res_ptr[last]] device, bf16 bits */
                              int32_t *status, void *stream);
 
+/*
+ * gf_kv_append -- write the K/V of every request's new tokens into its private
+ * tail blocks (paper, "Topology-Aware State Management": states produced at run
+ * time extend the KV assembled from the operation nodes; "Effective Path
+ * Pruning": a state that is not stored is computed on the fly and must then be
+ * put where attention reads it).  It closes the loop resolve -> append ->
+ * prefill / decode.
+ *
+ * Request r has n_r = seq_lens[r] - ctx_lens[r] new tokens, rows q_ptr[r] ..
+ * q_ptr[r+1) of k_new / v_new; its tail blocks are the last ceil(n_r/16) entries of
+ * its block table.  Token i goes to tail block i/16, slot i%16:
+ *   K[block][h][slot][d] = k_new[i][h][d]      V[block][h][d][slot] = v_new[i][h][d]
+ * and the slots beyond the block's token count are written as zero.  A call
+ * writes the whole tail of every request (a block is never grown in place).
+ * GF_BF16: the bf16 bits are copied.  GF_FP8_E4M3: per block and tensor,
+ *   scale = amax / 448 (amax over the block's valid tokens, all kv heads; 1.0 if 0),
+ *   code  = e4m3(clamp(x / scale, -448, 448)), fp32 division, round to nearest even,
+ * and k_scale[block] / v_scale[block] are written.
+ * Requests with a non-zero status, or whose row count differs from n_r, are
+ * skipped; so is a tail entry whose block id is outside the pool.
+ *   k_new, v_new  [total_q][num_kv_heads][head_dim] bf16 (device, in)
+ *   max_q         an upper bound on n_r over the batch (host value; sizes the grid;
+ *                 tokens of a request beyond it are not written)
+ * Of `tables`, block_table, num_blocks, ctx_lens, seq_lens and status are read.
+ */
+int32_t gf_kv_append(gf_ctx *ctx, const gf_attn_params *params,
+                     void *k_pool, void *v_pool, float *k_scale, float *v_scale,
+                     int32_t num_pool_blocks, const gf_tables *tables,
+                     const void *k_new, const void *v_new,
+                     const int32_t *q_ptr /* [num_req+1] device */,
+                     int32_t total_q, int32_t max_q, void *stream);
+
 /* Tuning knob (host): table entries (16-token blocks) per split-KV chunk in
  * gf_attn_decode; 0 restores the built-in choice.  Must be even. */
 int32_t gf_set_decode_chunk_blocks(gf_ctx *ctx, int32_t chunk_blocks);

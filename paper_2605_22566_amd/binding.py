@@ -22,7 +22,8 @@ GF_BF16, GF_FP8_E4M3 = 0, 1
 GF_RS_OK, GF_RS_BAD_BLOCK, GF_RS_BAD_INDEX = 0, 1, 2
 
 EXPORTS = ["gf_create", "gf_destroy", "gf_strerror", "gf_last_hip_error", "gf_resolve_path",
-           "gf_attn_prefill", "gf_attn_decode", "gf_set_decode_chunk_blocks", "gf_kv_apply_residual"]
+           "gf_attn_prefill", "gf_attn_decode", "gf_set_decode_chunk_blocks", "gf_kv_apply_residual",
+           "gf_kv_append"]
 
 _i32p = C.c_void_p  # device pointers travel as plain addresses
 
@@ -90,6 +91,9 @@ def load_library(path: Optional[str] = None):
     lib.gf_kv_apply_residual.argtypes = [C.c_void_p, C.POINTER(gf_attn_params), C.c_void_p, C.c_void_p, C.c_int32,
                                          C.c_int32] + [C.c_void_p] * 6 + [C.c_void_p]
     lib.gf_kv_apply_residual.restype = C.c_int32
+    lib.gf_kv_append.argtypes = [C.c_void_p, C.POINTER(gf_attn_params)] + [C.c_void_p] * 4 + [C.c_int32,
+                                 C.POINTER(gf_tables)] + [C.c_void_p] * 3 + [C.c_int32, C.c_int32, C.c_void_p]
+    lib.gf_kv_append.restype = C.c_int32
     if path is None:
         _lib = lib
     return lib
@@ -177,4 +181,12 @@ def gf_kv_apply_residual(ctx, params, k_pool, v_pool, num_pool_blocks, num_items
     rc = load_library().gf_kv_apply_residual(ctx, C.byref(params), _ptr(k_pool), _ptr(v_pool), num_pool_blocks,
                                              num_items, _ptr(src_blocks), _ptr(dst_blocks), _ptr(res_ptr),
                                              _ptr(res_idx), _ptr(res_val), _ptr(status), _stream())
+    _check(ctx, rc)
+
+
+def gf_kv_append(ctx, params, k_pool, v_pool, k_scale, v_scale, num_pool_blocks, tables, k_new, v_new, q_ptr,
+                 total_q, max_q) -> None:
+    rc = load_library().gf_kv_append(ctx, C.byref(params), _ptr(k_pool), _ptr(v_pool), _ptr(k_scale), _ptr(v_scale),
+                                     num_pool_blocks, C.byref(tables), _ptr(k_new), _ptr(v_new), _ptr(q_ptr),
+                                     total_q, max_q, _stream())
     _check(ctx, rc)

@@ -1,0 +1,168 @@
+// gf_kv_append: write the K/V of every request's new tokens into its private tail
+// blocks (paper, Topology-Aware State Management: the states produced at run time
+// extend the KV assembled from the operation nodes; Effective Path Pruning: a state
+// that is not stored is computed on the fly and then put where attention reads it).
+//
+// One workgroup per (request, tail block).  K keeps its token-major order inside the
+// block, so its rows are copied with 16-byte loads and stores.  V is stored
+// head-dim-major: one kv head at a time, the 16 x D tile of the new tokens goes
+// through LDS and comes out as D rows of 16 slots.  Slots beyond the block's token
+// count are written as zero.  With an e4m3 pool the block's two scales come first
+// (amax over the block's valid tokens / 448, workgroup reduction), then every value
+// is divided by its scale in fp32, clamped to +-448 and rounded to e4m3.
+#include "gf_internal.h"
+
+namespace gf {
+
+constexpr int kAppendThreads = 256;
+
+__device__ __forceinline__ float bf16_bits_to_float(uint32_t b) { return __uint_as_float(b << 16); }
+
+// 8 bf16 (one 16-byte chunk) -> 8 e4m3 codes (two dwords), x / scale clamped to the finite range
+__device__ __forceinline__ u32x2 quantize8(u32x4 raw, float scale) {
+    float x[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        x[2 * i] = bf16_bits_to_float(raw[i] & 0xffffu);
+        x[2 * i + 1] = bf16_bits_to_float(raw[i] >> 16);
+    }
+#pragma unroll
+    for (int i = 0; i < 8; ++i) x[i] = fminf(fmaxf(x[i] / scale, -448.0f), 448.0f);
+    u32x2 out;
+    int w = 0;
+    w = __builtin_amdgcn_cvt_pk_fp8_f32(x[0], x[1], w, false);
+    w = __builtin_amdgcn_cvt_pk_fp8_f32(x[2], x[3], w, true);
+    out[0] = (uint32_t)w;
+    w = 0;
+    w = __builtin_amdgcn_cvt_pk_fp8_f32(x[4], x[5], w, false);
+    w = __builtin_amdgcn_cvt_pk_fp8_f32(x[6], x[7], w, true);
+    out[1] = (uint32_t)w;
+    return out;
+}
+
+template <int D, bool FP8>
+__global__ __launch_bounds__(kAppendThreads) void append_kernel(
+    void *__restrict__ k_pool, void *__restrict__ v_pool, float *__restrict__ k_scale, float *__restrict__ v_scale,
+    int pool_blocks, int hkv, const int32_t *__restrict__ block_table, const int32_t *__restrict__ num_blocks,
+    const int32_t *__restrict__ ctx_lens, const int32_t *__restrict__ seq_lens, const int32_t *__restrict__ status,
+    int max_blocks, const uint16_t *__restrict__ k_new, const uint16_t *__restrict__ v_new,
+    const int32_t *__restrict__ q_ptr, int total_q) {
+    __shared__ __attribute__((aligned(16))) uint16_t tile[kBlock][D];      // one kv head of V, token-major
+    __shared__ float red[2][kAppendThreads / 64];
+    const int r = blockIdx.x, j = blockIdx.y;
+    const int tid = threadIdx.x;
+    if (status && status[r] != 0) return;
+    const int n = seq_lens[r] - ctx_lens[r];
+    if (n <= 0 || kBlock * j >= n) return;
+    const int q0 = q_ptr[r];
+    if (q_ptr[r + 1] - q0 != n || q0 < 0 || q0 + n > total_q) return;
+    const int nb = min(num_blocks[r], max_blocks);
+    const int ntail = (n + kBlock - 1) / kBlock;
+    const int e = nb - ntail + j;
+    if (e < 0) return;
+    const int blk = block_table[(size_t)r * max_blocks + e];
+    if (blk < 0 || blk >= pool_blocks) return;
+    const int ntok = min(kBlock, n - kBlock * j);
+    const size_t row_elems = (size_t)hkv * D;                               // elements of one token
+    const uint16_t *ksrc = k_new + (size_t)(q0 + kBlock * j) * row_elems;
+    const uint16_t *vsrc = v_new + (size_t)(q0 + kBlock * j) * row_elems;
+
+    float sk = 1.f, sv = 1.f;
+    if constexpr (FP8) {
+        // block scales: amax over the valid tokens of the block (rows of a token are contiguous)
+        float ak = 0.f, av = 0.f;
+        const size_t chunks = (size_t)ntok * row_elems / 8;
+        for (size_t c = tid; c < chunks; c += kAppendThreads) {
+            const u32x4 a = *(const u32x4 *)(ksrc + 8 * c), b = *(const u32x4 *)(vsrc + 8 * c);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                ak = fmaxf(ak, fmaxf(fabsf(bf16_bits_to_float(a[i] & 0xffffu)), fabsf(bf16_bits_to_float(a[i] >> 16))));
+                av = fmaxf(av, fmaxf(fabsf(bf16_bits_to_float(b[i] & 0xffffu)), fabsf(bf16_bits_to_float(b[i] >> 16))));
+            }
+        }
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) {
+            ak = fmaxf(ak, __shfl_xor(ak, o, 64));
+            av = fmaxf(av, __shfl_xor(av, o, 64));
+        }
+        if ((tid & 63) == 0) {
+            red[0][tid >> 6] = ak;
+            red[1][tid >> 6] = av;
+        }
+        __syncthreads();
+        ak = fmaxf(fmaxf(red[0][0], red[0][1]), fmaxf(red[0][2], red[0][3]));
+        av = fmaxf(fmaxf(red[1][0], red[1][1]), fmaxf(red[1][2], red[1][3]));
+        sk = ak > 0.f ? ak / 448.0f : 1.0f;
+        sv = av > 0.f ? av / 448.0f : 1.0f;
+        if (tid == 0) {
+            k_scale[blk] = sk;
+            v_scale[blk] = sv;
+        }
+    }
+
+    // K: destination image [h][slot][d]; chunk c = ((h * 16 + slot) * D + d8) / 8
+    {
+        const int chunks = hkv * kBlock * D / 8;
+        for (int c = tid; c < chunks; c += kAppendThreads) {
+            const int d8 = (c % (D / 8)) * 8, slot = (c / (D / 8)) % kBlock, h = c / (D / 8 * kBlock);
+            u32x4 raw = {0, 0, 0, 0};
+            if (slot < ntok) raw = *(const u32x4 *)(ksrc + (size_t)slot * row_elems + h * D + d8);
+            if constexpr (FP8) {
+                u32x2 q = {0, 0};
+                if (slot < ntok) q = quantize8(raw, sk);
+                *(u32x2 *)((uint8_t *)k_pool + (size_t)blk * hkv * kBlock * D + (size_t)c * 8) = q;
+            } else {
+                *(u32x4 *)((uint16_t *)k_pool + (size_t)blk * hkv * kBlock * D + (size_t)c * 8) = raw;
+            }
+        }
+    }
+    // V: destination image [h][d][slot], one kv head at a time through LDS
+    for (int h = 0; h < hkv; ++h) {
+        __syncthreads();
+        for (int c = tid; c < kBlock * D / 8; c += kAppendThreads) {
+            const int d8 = (c % (D / 8)) * 8, slot = c / (D / 8);
+            u32x4 raw = {0, 0, 0, 0};
+            if (slot < ntok) raw = *(const u32x4 *)(vsrc + (size_t)slot * row_elems + h * D + d8);
+            *(u32x4 *)(&tile[slot][d8]) = raw;
+        }
+        __syncthreads();
+        // thread (d, half) gathers slots 8 half .. 8 half + 7 of head-dim row d
+        for (int t = tid; t < 2 * D; t += kAppendThreads) {
+            const int d = t % D, half = t / D;
+            u32x4 raw;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                raw[i] = (uint32_t)tile[8 * half + 2 * i][d] | ((uint32_t)tile[8 * half + 2 * i + 1][d] << 16);
+            const size_t row = ((size_t)blk * hkv + h) * D + d;             // head-dim row of the V pool
+            if constexpr (FP8) {
+                // pad slots hold zero bits: they quantise to code 0 under any scale
+                *(u32x2 *)((uint8_t *)v_pool + row * kBlock + 8 * half) = quantize8(raw, sv);
+            } else {
+                *(u32x4 *)((uint16_t *)v_pool + row * kBlock + 8 * half) = raw;
+            }
+        }
+    }
+}
+
+hipError_t launch_append(void *k_pool, void *v_pool, float *k_scale, float *v_scale, int32_t pool_blocks, int32_t hkv,
+                         int32_t head_dim, int kv_dtype, const gf_tables &t, const void *k_new, const void *v_new,
+                         const int32_t *q_ptr, int32_t total_q, int32_t max_q, hipStream_t s) {
+    if (t.num_req == 0 || total_q == 0 || max_q == 0) return hipSuccess;
+    const unsigned by = (unsigned)((max_q + kBlock - 1) / kBlock);
+    if (by > 65535u) return hipErrorInvalidValue;
+    const dim3 grid((unsigned)t.num_req, by);
+#define GF_APPEND(DD, FF)                                                                                           \
+    hipLaunchKernelGGL((append_kernel<DD, FF>), grid, dim3(kAppendThreads), 0, s, k_pool, v_pool, k_scale, v_scale, \
+                       pool_blocks, hkv, t.block_table, t.num_blocks, t.ctx_lens, t.seq_lens, t.status,            \
+                       t.max_blocks, (const uint16_t *)k_new, (const uint16_t *)v_new, q_ptr, total_q)
+    const bool fp8 = kv_dtype == GF_FP8_E4M3;
+    if (head_dim == 128 && fp8) GF_APPEND(128, true);
+    else if (head_dim == 128) GF_APPEND(128, false);
+    else if (head_dim == 64 && fp8) GF_APPEND(64, true);
+    else if (head_dim == 64) GF_APPEND(64, false);
+    else return hipErrorNotSupported;
+#undef GF_APPEND
+    return hipGetLastError();
+}
+
+}  // namespace gf

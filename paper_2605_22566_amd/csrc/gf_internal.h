@@ -54,6 +54,11 @@ hipError_t launch_residual(void *k_pool, void *v_pool, int32_t num_pool_blocks, 
                            const int32_t *res_ptr, const uint16_t *res_idx, const uint16_t *res_val,
                            int32_t *status, hipStream_t s);
 
+// KV write path: one workgroup per (request, tail block); max_q bounds the new tokens of a request
+hipError_t launch_append(void *k_pool, void *v_pool, float *k_scale, float *v_scale, int32_t pool_blocks, int32_t hkv,
+                         int32_t head_dim, int kv_dtype, const gf_tables &t, const void *k_new, const void *v_new,
+                         const int32_t *q_ptr, int32_t total_q, int32_t max_q, hipStream_t s);
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));

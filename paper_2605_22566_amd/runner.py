@@ -179,6 +179,11 @@ class Session:
         B.gf_kv_apply_residual(self.ctx, params, pool.k, pool.v, pool.num_blocks, dres["num_items"], dres["src"],
                                dres["dst"], dres["ptr"], dres["idx"], dres["val"], dres["status"])
 
+    def append(self, pool, tables, k_new, v_new, q_ptr, total_q, max_q):
+        params, _, dt = self._common(pool, tables, 0.0)
+        B.gf_kv_append(self.ctx, params, pool.k, pool.v, pool.k_scale, pool.v_scale, pool.num_blocks, dt, k_new,
+                       v_new, q_ptr, total_q, max_q)
+
     def decode(self, pool, tables, q, o, lse=None, sm_scale=0.0):
         params, dpool, dt = self._common(pool, tables, sm_scale)
         B.gf_attn_decode(self.ctx, params, dpool, dt, q, o, lse)
