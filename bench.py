@@ -98,7 +98,13 @@ class Job:
         self.dec_rng = (P, Rn) if len(wl.decode_req) > 0 else (0, Rn)
         self.pf_rows = int(b.new_lens[:P].sum())
         self.pf_max_q = int(b.new_lens[:P].max()) if P else 0
+        # K/V of the new tokens, as the write path receives them
+        self.k_new = torch.randn((self.total_q, sh.num_kv_heads, sh.head_dim), generator=gen, device=dev,
+                                 dtype=torch.float32).to(torch.bfloat16)
+        self.v_new = torch.randn((self.total_q, sh.num_kv_heads, sh.head_dim), generator=gen, device=dev,
+                                 dtype=torch.float32).to(torch.bfloat16)
         self.resolve()
+        self.append()          # the tail blocks hold the new tokens' K/V from here on (every later call rewrites the same)
         torch.cuda.synchronize()
 
     def _slice(self, lo, hi):
@@ -114,6 +120,17 @@ class Job:
         lo, hi = self.pf_rng
         self.sess.prefill(self.pool, self._slice(lo, hi), self.q, self.q_ptr[lo:hi + 1], self.pf_rows,
                           self.pf_max_q, self.o)
+
+    def append(self):
+        self.sess.append(self.pool, self.tables, self.k_new, self.v_new, self.q_ptr, self.total_q, self.max_q)
+
+    def append_bytes(self):
+        sh = self.wl.shape
+        esz = 2 if sh.kv_dtype == self.W.KV_BF16 else 1
+        per_tok = 2 * sh.num_kv_heads * sh.head_dim
+        nblk = int(((self.wl.batch.new_lens.astype(np.int64) + 15) // 16).sum())
+        # new K/V read once (bf16), tail blocks written whole (pad slots included), 4 B of table per block
+        return float(self.total_q) * per_tok * 2 + float(nblk) * 16 * per_tok * esz + 4.0 * nblk
 
     def decode(self):
         lo, hi = self.dec_rng
@@ -153,6 +170,9 @@ def measure(job, steps, warmup):
     if job.has_decode:
         out["decode_ms"] = _event_ms(job.decode, torch, it)
         out["decode_gbs_kernel"] = job.decode_bytes() / (out["decode_ms"] * 1e-3) / 1e9
+    # the write path (not part of the step): it rewrites the tail blocks with the same new-token K/V every time
+    out["append_ms"] = _event_ms(job.append, torch, it)
+    out["append_gbs_kernel"] = job.append_bytes() / (out["append_ms"] * 1e-3) / 1e9
     return out
 
 
@@ -333,6 +353,10 @@ def main():
     }
     if job.has_prefill and job.has_decode:
         res["decode_gbs_kernel"] = m["decode_gbs_kernel"]
+    res["kv_append"] = {"kernel": "append_kernel", "kernel_ms": m["append_ms"], "gbs_kernel": m["append_gbs_kernel"],
+                        "frac_of_hbm_peak": m["append_gbs_kernel"] / PEAK_HBM_GBS,
+                        "algorithmic_bytes_per_launch": job.append_bytes(),
+                        "hbm_bytes_per_launch_rocprof": _read_traffic(f"append_{args.workload}")}
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(job, args.cpu_budget)
     extra = {}
