@@ -276,8 +276,36 @@ int32_t gf_kv_append(gf_ctx *ctx, const gf_attn_params *params,
                      const int32_t *q_ptr /* [num_req+1] device */,
                      int32_t total_q, int32_t max_q, void *stream);
 
+/*
+ * gf_attn_decode_shared -- the same decode step as gf_attn_decode (same inputs,
+ * same outputs, same skipping of failed requests), computed node by node: the
+ * KV of an operation node is read once for a group of requests that pass
+ * through it instead of once per request (paper: "Topology-Aware State
+ * Management" stores a node's KV once for all workflows through it; here the
+ * reads are shared as well as the storage).
+ *
+ * `graph`, path_ptr and path_nodes are the ones `tables` was resolved from
+ * (gf_resolve_path): request r's table must be the block lists of its path
+ * nodes in path order (ceil(node_len/16) entries each) followed by its tail
+ * entries, which is what gf_resolve_path writes for a request with status 0.
+ *   num_path_entries  the length of path_nodes, i.e. path_ptr[num_req] (HOST value)
+ * The batch's node -> requests lists are built on the device inside the call.
+ * One partial (max, sum, weighted values; fp32) is kept per (request, path
+ * node, chunk of the node's blocks) and per chunk of tail entries, and a
+ * request's partials are merged in path order: the result equals
+ * gf_attn_decode's up to fp32 summation order and does not depend on the order
+ * in which the device builds the lists.  Workspace: the context's (grown on
+ * demand like gf_attn_decode's).
+ */
+int32_t gf_attn_decode_shared(gf_ctx *ctx, const gf_attn_params *params, const gf_kv_pool *pool,
+                              const gf_graph *graph,
+                              const int32_t *path_ptr   /* [num_req+1] device */,
+                              const int32_t *path_nodes /* [num_path_entries] device */,
+                              int32_t num_path_entries,
+                              const gf_tables *tables, const void *q, void *o, float *lse, void *stream);
+
 /* Tuning knob (host): table entries (16-token blocks) per split-KV chunk in
- * gf_attn_decode; 0 restores the built-in choice.  Must be even. */
+ * gf_attn_decode and gf_attn_decode_shared; 0 restores the built-in choice.  Must be even. */
 int32_t gf_set_decode_chunk_blocks(gf_ctx *ctx, int32_t chunk_blocks);
 
 #ifdef __cplusplus

@@ -211,6 +211,34 @@ int32_t gf_attn_decode(gf_ctx *ctx, const gf_attn_params *params, const gf_kv_po
     return GF_OK;
 }
 
+int32_t gf_attn_decode_shared(gf_ctx *ctx, const gf_attn_params *params, const gf_kv_pool *pool,
+                              const gf_graph *graph, const int32_t *path_ptr, const int32_t *path_nodes,
+                              int32_t num_path_entries, const gf_tables *tables, const void *q, void *o, float *lse,
+                              void *stream) {
+    if (!ctx || !graph) return GF_ERR_NULL;
+    if (num_path_entries < 0 || graph->num_nodes < 0) return GF_ERR_BAD_SHAPE;
+    gf::AttnArgs a;
+    int group = 0;
+    int32_t rc = check_attn(params, pool, tables, q, o, lse, a, group);
+    if (rc != GF_OK) return rc;
+    if (tables->num_req == 0) return GF_OK;
+    if (!path_ptr || !path_nodes) return GF_ERR_NULL;
+    if (graph->num_nodes > 0 && (!graph->node_len || !graph->node_block_ptr || !graph->node_blocks))
+        return GF_ERR_NULL;
+    int32_t chunk = ctx->decode_chunk_blocks;
+    if (chunk <= 0) chunk = 32;
+    const size_t need = gf::shared_workspace_bytes(graph->num_nodes, a.num_req, num_path_entries, a.max_blocks, chunk,
+                                                   a.hq, params->head_dim);
+    rc = ensure_buffer(ctx, &ctx->workspace, &ctx->workspace_bytes, need, (hipStream_t)stream,
+                       "gf_attn_decode_shared workspace");
+    if (rc != GF_OK) return rc;
+    hipError_t e = gf::launch_decode_shared(a, params->head_dim, group, params->kv_dtype, *graph, path_ptr, path_nodes,
+                                            num_path_entries, chunk, ctx->workspace, (hipStream_t)stream);
+    if (e == hipErrorNotSupported || e == hipErrorInvalidValue) return GF_ERR_UNSUPPORTED;
+    if (e != hipSuccess) return fail_hip(ctx, e, "gf_attn_decode_shared launch");
+    return GF_OK;
+}
+
 int32_t gf_kv_apply_residual(gf_ctx *ctx, const gf_attn_params *params, void *k_pool, void *v_pool,
                              int32_t num_pool_blocks, int32_t num_items, const int32_t *src_blocks,
                              const int32_t *dst_blocks, const int32_t *res_ptr, const uint16_t *res_idx,

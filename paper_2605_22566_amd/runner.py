@@ -133,7 +133,8 @@ class Session:
         up = self._up
         return dict(path_ptr=up(batch.path_ptr), path_nodes=up(batch.path_nodes if len(batch.path_nodes) else [0]),
                     new_lens=up(batch.new_lens), tail_ptr=up(batch.tail_ptr),
-                    tail_blocks=up(batch.tail_blocks if len(batch.tail_blocks) else [0]), num_req=batch.num_req)
+                    tail_blocks=up(batch.tail_blocks if len(batch.tail_blocks) else [0]), num_req=batch.num_req,
+                    num_path_entries=int(len(batch.path_nodes)))
 
     def alloc_tables(self, num_req, max_blocks):
         z = lambda *s: torch.empty(s, dtype=torch.int32, device=self.device)
@@ -187,6 +188,13 @@ class Session:
     def decode(self, pool, tables, q, o, lse=None, sm_scale=0.0):
         params, dpool, dt = self._common(pool, tables, sm_scale)
         B.gf_attn_decode(self.ctx, params, dpool, dt, q, o, lse)
+
+    def decode_shared(self, pool, dbatch, tables, q, o, lse=None, sm_scale=0.0):
+        """Node-centric decode; `dbatch` is the uploaded batch `tables` was resolved from."""
+        params, dpool, dt = self._common(pool, tables, sm_scale)
+        graph = B.make_graph(self.wl.graph.num_nodes, self.node_len, self.node_block_ptr, self.node_blocks)
+        B.gf_attn_decode_shared(self.ctx, params, dpool, graph, dbatch["path_ptr"], dbatch["path_nodes"],
+                                dbatch["num_path_entries"], dt, q, o, lse)
 
 
 def tables_to_host(tables) -> dict:

@@ -59,10 +59,10 @@ def run_prefill(wl, t, sm_scale=0.0, want_lse=True, tables=None, sess=None):
     return bf16_out_to_f64(o), (None if lse is None else lse.double().cpu().numpy()), tables, sess
 
 
-def run_decode(wl, t, sm_scale=0.0, chunk_blocks=0, tables=None, sess=None):
-    """Decode with each request's LAST new token as the query."""
+def run_decode(wl, t, sm_scale=0.0, chunk_blocks=0, tables=None, sess=None, shared=False, with_edges=True):
+    """Decode with each request's LAST new token as the query (shared: the node-centric entry point)."""
     if sess is None:
-        sess, tables = run_resolve(wl)
+        sess, tables = run_resolve(wl, with_edges=with_edges)
     dev = sess.device
     from paper_2605_22566_amd import binding as B
     B.gf_set_decode_chunk_blocks(sess.ctx, chunk_blocks)
@@ -71,7 +71,10 @@ def run_decode(wl, t, sm_scale=0.0, chunk_blocks=0, tables=None, sess=None):
     qd = R.bits_to_device(np.ascontiguousarray(t.q[last]), dev)
     o = torch.full(qd.shape, float("nan"), dtype=torch.bfloat16, device=dev)
     lse = torch.full(qd.shape[:2], float("nan"), dtype=torch.float32, device=dev)
-    sess.decode(pool, tables, qd, o, lse, sm_scale)
+    if shared:
+        sess.decode_shared(pool, sess.upload_batch(wl.batch), tables, qd, o, lse, sm_scale)
+    else:
+        sess.decode(pool, tables, qd, o, lse, sm_scale)
     torch.cuda.synchronize()
     return bf16_out_to_f64(o), lse.double().cpu().numpy(), tables, sess, last
 

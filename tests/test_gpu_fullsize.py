@@ -18,7 +18,8 @@ def _setup(name):
     sess = R.Session(wl)
     dev = sess.device
     b = wl.batch
-    tables = sess.resolve(sess.upload_batch(b), sess.alloc_tables(b.num_req, max_blocks_of(wl)))
+    sess.dbatch = sess.upload_batch(b)
+    tables = sess.resolve(sess.dbatch, sess.alloc_tables(b.num_req, max_blocks_of(wl)))
     pool = R.DevicePool.random(wl, dev)
     gen = torch.Generator(device=dev)
     gen.manual_seed(wl.seed + 1)
@@ -61,15 +62,19 @@ def test_prefill_8b_full_size_sampled():
         _check_rows(wl, pool, want, qb[lo:hi], og[lo:hi], r, decode=False)
 
 
+@pytest.mark.parametrize("shared", [False, True], ids=["per_request", "per_node"])
 @pytest.mark.parametrize("name", ["decode_8b", "mixed_fp8"])
-def test_decode_full_size_sampled(name):
+def test_decode_full_size_sampled(name, shared):
     wl, sess, tables, pool, q, q_ptr = _setup(name)
     want = oracle_resolve(wl)
     last = torch.from_numpy((q_ptr[1:] - 1).astype(np.int64)).to(sess.device)
     qd = q[last].contiguous()
     od = torch.full_like(qd, float("nan"))
     lse = torch.empty(qd.shape[:2], dtype=torch.float32, device=sess.device)
-    sess.decode(pool, tables, qd, od, lse)
+    if shared:
+        sess.decode_shared(pool, sess.dbatch, tables, qd, od, lse)
+    else:
+        sess.decode(pool, tables, qd, od, lse)
     torch.cuda.synchronize()
     og = od.double().cpu().numpy()
     assert np.isfinite(og).all()
