@@ -89,6 +89,7 @@ class Job:
         last = torch.from_numpy((np.cumsum(b.new_lens) - 1).astype(np.int64)).to(dev)
         self.qd = self.q[last].contiguous()
         self.od = torch.zeros_like(self.qd)
+        self.od_shared = torch.zeros_like(self.qd)
         self.last = last
         # request classes: the generator puts the prefill requests first.  A prefill-only workload
         # decodes all its requests after prefill; a mixed batch prefills [0, P) and decodes [P, R).
@@ -136,6 +137,33 @@ class Job:
         lo, hi = self.dec_rng
         self.sess.decode(self.pool, self._slice(lo, hi), self.qd[lo:hi], self.od[lo:hi])
 
+    def decode_shared(self):
+        """The same decode step through the node-centric entry point."""
+        lo, hi = self.dec_rng
+        db = dict(self.dbatch)
+        db["path_ptr"] = self.dbatch["path_ptr"][lo:hi + 1]
+        self.sess.decode_shared(self.pool, db, self._slice(lo, hi), self.qd[lo:hi], self.od_shared[lo:hi])
+
+    def decode_shared_bytes(self, chunk_blocks=32):
+        """What the node-centric decode has to move: every node the decode requests touch once, their
+        tails, one fp32 partial (max, sum, values) per (request, path node, chunk) written and read
+        back, the block lists, q and o."""
+        wl, sh = self.wl, self.wl.shape
+        b, g = wl.batch, wl.graph
+        lo, hi = self.dec_rng
+        esz = 2 if sh.kv_dtype == self.W.KV_BF16 else 1
+        per_blk = 2 * sh.num_kv_heads * 16 * sh.head_dim * esz + (8 if esz == 1 else 0)
+        nbl = (g.node_len.astype(np.int64) + 15) // 16
+        nodes = b.path_nodes[b.path_ptr[lo]:b.path_ptr[hi]]
+        tail_blk = (b.new_lens[lo:hi].astype(np.int64) + 15) // 16
+        uniq_blocks = int(nbl[np.unique(nodes)].sum()) + int(tail_blk.sum())
+        slots = int(((nbl[nodes] + chunk_blocks - 1) // chunk_blocks).sum()) \
+            + int(((tail_blk + chunk_blocks - 1) // chunk_blocks).sum())
+        partial = slots * sh.num_q_heads * (sh.head_dim + 2) * 4
+        qo = 2 * (hi - lo) * sh.num_q_heads * sh.head_dim * 2
+        return {"unique_blocks": uniq_blocks, "partial_slots": slots,
+                "bytes": float(uniq_blocks) * (per_blk + 4) + 2.0 * partial + qo}
+
     def step(self):
         self.resolve()
         if self.has_prefill:
@@ -170,10 +198,31 @@ def measure(job, steps, warmup):
     if job.has_decode:
         out["decode_ms"] = _event_ms(job.decode, torch, it)
         out["decode_gbs_kernel"] = job.decode_bytes() / (out["decode_ms"] * 1e-3) / 1e9
+        # the same step computed node by node (shared KV read once per group of requests)
+        job.decode()
+        job.decode_shared()
+        torch.cuda.synchronize()
+        out["decode_shared_max_abs_diff"] = float((job.od.float() - job.od_shared.float()).abs().max().item())
+        out["decode_shared_ms"] = _event_ms(job.decode_shared, torch, it)
     # the write path (not part of the step): it rewrites the tail blocks with the same new-token K/V every time
     out["append_ms"] = _event_ms(job.append, torch, it)
     out["append_gbs_kernel"] = job.append_bytes() / (out["append_ms"] * 1e-3) / 1e9
     return out
+
+
+def decode_shared_entry(job, m):
+    """Figures of gf_attn_decode_shared beside gf_attn_decode on the same decode step."""
+    alg = job.decode_shared_bytes()
+    sec = m["decode_shared_ms"] * 1e-3
+    return {"kernel": "shared_node_kernel(+list building, tails, merge)", "kernel_ms": m["decode_shared_ms"],
+            "speedup_over_decode": m["decode_ms"] / m["decode_shared_ms"],
+            "max_abs_diff_to_decode": m["decode_shared_max_abs_diff"],
+            # the per-request kernel's bytes over this call's time: what the sharing is worth, not an HBM rate
+            "per_request_bytes_rate_gbs": job.decode_bytes() / sec / 1e9,
+            "algorithmic_bytes_per_launch": alg["bytes"], "unique_blocks": alg["unique_blocks"],
+            "partial_slots": alg["partial_slots"], "gbs_kernel": alg["bytes"] / sec / 1e9,
+            "frac_of_hbm_peak": alg["bytes"] / sec / 1e9 / PEAK_HBM_GBS,
+            "hbm_bytes_per_launch_rocprof": _read_traffic(f"decode_shared_{job.name}")}
 
 
 def measure_stream_copy(torch, iters=10):
@@ -353,6 +402,8 @@ def main():
     }
     if job.has_prefill and job.has_decode:
         res["decode_gbs_kernel"] = m["decode_gbs_kernel"]
+    if job.has_decode:
+        res["decode_shared"] = decode_shared_entry(job, m)
     res["kv_append"] = {"kernel": "append_kernel", "kernel_ms": m["append_ms"], "gbs_kernel": m["append_gbs_kernel"],
                         "frac_of_hbm_peak": m["append_gbs_kernel"] / PEAK_HBM_GBS,
                         "algorithmic_bytes_per_launch": job.append_bytes(),
@@ -385,6 +436,7 @@ def main():
             ent["unique_kv_bytes"] = W.sharing_stats(j.wl)["shared_kv_bytes"]
             ent["unique_bytes_time_bound_ms"] = ent["unique_kv_bytes"] / (PEAK_HBM_GBS * 1e9) * 1e3
             ent["hbm_bytes_per_launch_rocprof"] = _read_traffic(f"decode_{name}")
+            ent["decode_shared"] = decode_shared_entry(j, mm)
         extra[name] = ent
         del j
         torch.cuda.empty_cache()

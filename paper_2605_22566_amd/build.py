@@ -17,6 +17,11 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
          # packed fp32 VALU ops are kept out of the generated code on purpose
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I" + os.path.join(ROOT, "include"), "-I" + CSRC]
+# Per-file flags.  The decode kernels rescale their MFMA accumulators with vector multiplies every step:
+# keep those accumulators in ordinary VGPRs (the default choice, accumulation registers, costs a copy out
+# and a copy back per element and step).
+FILE_FLAGS = {"gf_decode.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"],
+              "gf_decode_shared.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form"]}
 
 
 def hipcc() -> str:
@@ -36,7 +41,7 @@ def build(verbose: bool = True, extra_flags=()) -> str:
     for src in SOURCES:
         obj = os.path.join(bdir, src.replace(".hip", ".o"))
         objs.append(obj)
-        cmd = [cc, *FLAGS, *extra_flags, "-c", os.path.join(CSRC, src), "-o", obj]
+        cmd = [cc, *FLAGS, *FILE_FLAGS.get(src, []), *extra_flags, "-c", os.path.join(CSRC, src), "-o", obj]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))

@@ -27,15 +27,16 @@
 namespace gf {
 
 constexpr int kSharedThreads = 256;
-constexpr int kSharedWaves = kSharedThreads / 64;
 constexpr int kScanThreads = 1024;
+constexpr int kXcds = 8;                 // workgroups are dealt to the XCDs round robin
 
 struct SharedPlan {
     // graph and batch (device, caller's)
     const int32_t *node_len, *node_block_ptr, *node_blocks, *path_ptr, *path_nodes;
     int32_t num_nodes, num_entries;
     // scratch (device, context's)
-    int32_t *cnt, *cursor, *node_ptr, *item_ptr, *entry_req, *entry_slot, *inv_entry, *slot_ptr, *totals;
+    int32_t *cnt, *cursor, *node_ptr, *item_ptr, *entry_slot, *row_req, *row_slot, *slot_ptr, *tail_ptr, *totals;
+    int2 *item_rec;
     int32_t chunk_blocks, item_cap, slot_cap;
 };
 
@@ -74,7 +75,6 @@ __global__ void shared_count_kernel(SharedPlan p, AttnArgs a) {
     if (r >= a.num_req) return;
     const bool ok = request_ok(a, r);
     for (int e = path_lo(p, r); e < path_hi(p, r); ++e) {
-        p.entry_req[e] = r;
         const int v = p.path_nodes[e];
         if (ok && v >= 0 && v < p.num_nodes) atomicAdd(&p.cnt[v], 1);
     }
@@ -104,11 +104,11 @@ __device__ void block_exscan(int n, F f, int32_t *out, int32_t *sh) {
     __syncthreads();
 }
 
-__global__ __launch_bounds__(kScanThreads) void shared_scan_kernel(SharedPlan p, AttnArgs a, int group) {
+__global__ __launch_bounds__(kScanThreads) void shared_scan_kernel(SharedPlan p, AttnArgs a, int group, int item_cols) {
     __shared__ int32_t sh[kScanThreads];
     auto chunks_of = [&](int v) -> int { return node_chunks_of(p, v); };
     block_exscan(p.num_nodes, [&](int v) { return p.cnt[v]; }, p.node_ptr, sh);
-    block_exscan(p.num_nodes, [&](int v) { return chunks_of(v) * ((p.cnt[v] * group + 15) / 16); }, p.item_ptr, sh);
+    block_exscan(p.num_nodes, [&](int v) { return chunks_of(v) * ((p.cnt[v] * group + item_cols - 1) / item_cols); }, p.item_ptr, sh);
     // partial slots per request: its path nodes' chunks, then the chunks of its tail
     auto tail_chunks = [&](int r) -> int { return (tail_blocks_of(a, r) + p.chunk_blocks - 1) / p.chunk_blocks; };
     block_exscan(a.num_req, [&](int r) {
@@ -125,169 +125,367 @@ __global__ __launch_bounds__(kScanThreads) void shared_scan_kernel(SharedPlan p,
             s += chunks_of(p.path_nodes[e]);
         }
     }
-    if (threadIdx.x == 0) p.totals[0] = min(p.item_ptr[p.num_nodes], p.item_cap);
+    block_exscan(a.num_req, [&](int r) { return request_ok(a, r) ? tail_chunks(r) : 0; }, p.tail_ptr, sh);
+    if (threadIdx.x == 0) {
+        p.totals[0] = min(p.item_ptr[p.num_nodes], p.item_cap);     // node items
+        p.totals[1] = min(p.tail_ptr[a.num_req], p.item_cap - p.totals[0]);   // tail items
+    }
 }
 
+// Threads [0, num_req): the rows of the node lists (request and first partial slot of every path entry) and
+// the request's tail items.  Threads [num_req, num_req + num_nodes): the node's items.  An item record is
+// (node, index among the node's chunk x column-quad items) or (-(request + 1), tail chunk).
 __global__ void shared_fill_kernel(SharedPlan p, AttnArgs a) {
-    const int r = blockIdx.x * blockDim.x + threadIdx.x;
-    if (r >= a.num_req || !request_ok(a, r)) return;
-    for (int e = path_lo(p, r); e < path_hi(p, r); ++e) {
-        const int v = p.path_nodes[e];
-        if (v < 0 || v >= p.num_nodes) continue;
-        const int pos = atomicAdd(&p.cursor[v], 1);
-        if (p.node_ptr[v] + pos < p.num_entries) p.inv_entry[p.node_ptr[v] + pos] = e;   // always, unless paths overlap
-    }
-}
-
-// One (segment, kv head, chunk, 16 columns) reduction.  Column n of the wave is the pair
-// (request col_req, query head kvh*G + col_head) or nothing (col_req < 0); its partial goes to
-// slot col_slot.  `tab` lists the segment's blocks; token counts come from ntk or from seg_len.
-template <int D, int G, bool FP8>
-__device__ __forceinline__ void reduce_chunk(const AttnArgs &a, const int32_t *tab, const int32_t *ntk, int seg_len,
-                                             int e0, int e1, int kvh, int lane, int col_req, int col_head,
-                                             int col_slot, float *__restrict__ part_o, float *__restrict__ part_ml) {
-    const int q4 = lane >> 4;
-    bf16x8 qf[D / 32];
-#pragma unroll
-    for (int t = 0; t < D / 32; ++t) {
-        const int d0 = FP8 ? 64 * (t / 2) + 16 * q4 + 8 * (t % 2) : 32 * t + 8 * q4;
-        u32x4 raw = {0, 0, 0, 0};
-        if (col_req >= 0)
-            raw = *(const u32x4 *)((const char *)a.q + (((size_t)col_req * a.hq + kvh * G + col_head) * D + d0) * 2);
-        qf[t] = __builtin_bit_cast(bf16x8, raw);
-    }
-    const float c = a.scale_log2;
-    float m_run = -1.0e30f, l_run = 0.f;
-    f32x4 oacc[D / 16];
-#pragma unroll
-    for (int dt = 0; dt < D / 16; ++dt) oacc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    PairRegs<D, FP8> cur, nxt;
-    load_pair(cur, a, tab, ntk, e0, e1, kvh, lane, seg_len);
-    for (int e = e0; e < e1; e += 2) {
-        const bool more = e + 2 < e1;
-        if (more) load_pair(nxt, a, tab, ntk, e + 2, e1, kvh, lane, seg_len);
-        f32x4 sT[2];
-#pragma unroll
-        for (int T = 0; T < 2; ++T) {
-            sT[T] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-            for (int t = 0; t < D / 32; ++t)
-                sT[T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k_operand<D, FP8>(cur, T, t), qf[t], sT[T], 0, 0, 0);
-            if constexpr (FP8) sT[T] *= cur.ks;
-        }
-        if (cur.n0 < kBlock || cur.n1 < kBlock) {
-            const int lim = ((q4 >= 2) ? cur.n1 : cur.n0) - 8 * (q4 & 1);
-#pragma unroll
-            for (int T = 0; T < 2; ++T)
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    if (4 * T + i >= lim) sT[T][i] = -INFINITY;
-        }
-        float mx = fmaxf(fmaxf(fmaxf(sT[0][0], sT[0][1]), fmaxf(sT[0][2], sT[0][3])),
-                         fmaxf(fmaxf(sT[1][0], sT[1][1]), fmaxf(sT[1][2], sT[1][3])));
-        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m_run, mx);
-        const float alpha = fast_exp2((m_run - m_new) * c);
-        const float mc = m_new * c;
-        m_run = m_new;
-        f32x8 p;
-        float psum = 0.f;
-#pragma unroll
-        for (int T = 0; T < 2; ++T)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float e2 = fast_exp2(sT[T][i] * c - mc);
-                p[4 * T + i] = e2;
-                psum += e2;
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < a.num_req) {
+        const int r = i;
+        if (!request_ok(a, r)) return;
+        for (int e = path_lo(p, r); e < path_hi(p, r); ++e) {
+            const int v = p.path_nodes[e];
+            if (v < 0 || v >= p.num_nodes) continue;
+            const int row = p.node_ptr[v] + atomicAdd(&p.cursor[v], 1);
+            if (row < p.num_entries) {                         // always, unless paths overlap
+                p.row_req[row] = r;
+                p.row_slot[row] = p.entry_slot[e];
             }
-        l_run = l_run * alpha + psum;
-        if constexpr (FP8) p *= cur.vs;
-        const bf16x8 pb = __builtin_convertvector(p, bf16x8);
-#pragma unroll
-        for (int dt = 0; dt < D / 16; ++dt) {
-            oacc[dt] *= alpha;
-            oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v_operand<D, FP8>(cur, dt), pb, oacc[dt], 0, 0, 0);
         }
-        if (more) cur = nxt;
-    }
-    l_run += __shfl_xor(l_run, 16, 64);
-    l_run += __shfl_xor(l_run, 32, 64);
-    if (col_req >= 0) {
-        const size_t pi = (size_t)col_slot * a.hq + kvh * G + col_head;
-        if (q4 == 0) {
-            part_ml[pi * 2 + 0] = m_run * c;   // max in log2 units
-            part_ml[pi * 2 + 1] = l_run;
-        }
-#pragma unroll
-        for (int dt = 0; dt < D / 16; ++dt) *(f32x4 *)(part_o + pi * D + 16 * dt + 4 * q4) = oacc[dt];
+        const int base = p.totals[0] + p.tail_ptr[r];
+        for (int j = 0; j < p.tail_ptr[r + 1] - p.tail_ptr[r] && base + j < p.item_cap; ++j)
+            p.item_rec[base + j] = make_int2(-(r + 1), j);
+    } else if (i < a.num_req + p.num_nodes) {
+        const int v = i - a.num_req;
+        const int base = p.item_ptr[v];
+        for (int j = 0; j < p.item_ptr[v + 1] - base && base + j < p.totals[0]; ++j) p.item_rec[base + j] = make_int2(v, j);
     }
 }
 
-// node-centric items: work id w -> (item, kv head); item -> (node, chunk, column group)
-template <int D, int G, bool FP8>
-__global__ __launch_bounds__(kSharedThreads) void shared_node_kernel(AttnArgs a, SharedPlan p, float *__restrict__ part_o,
-                                                                      float *__restrict__ part_ml) {
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const long w = (long)blockIdx.x * kSharedWaves + wave;
-    const int item = (int)(w / a.hkv), kvh = (int)(w % a.hkv);
-    if (item >= p.totals[0]) return;
-    // node of the item: last v with item_ptr[v] <= item
-    int lo = 0, hi = p.num_nodes;
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (p.item_ptr[mid] <= item) lo = mid;
-        else hi = mid;
-    }
-    const int v = lo;
-    const int cnt = p.cnt[v];
-    const int groups = (cnt * G + 15) / 16;
-    if (groups <= 0) return;
-    const int local = item - p.item_ptr[v];
-    const int chunk = local / groups, cg = local % groups;      // column groups of a chunk run back to back
-    const int seg_len = p.node_len[v];
-    const int nblk = node_blocks_of(p, v);
-    const int e0 = chunk * p.chunk_blocks, e1 = min(nblk, e0 + p.chunk_blocks);
-    if (e0 >= e1) return;
-    const int col = cg * 16 + (lane & 15);
-    const int row = col / G;
-    int col_req = -1, col_slot = 0;
-    if (row < cnt && p.node_ptr[v] + row < p.num_entries) {
-        const int e = p.inv_entry[p.node_ptr[v] + row];
-        col_req = p.entry_req[e];
-        col_slot = p.entry_slot[e] + chunk;
-        if (col_slot >= p.slot_cap) col_req = -1;   // only with tables that break the resolve contract
-    }
-    reduce_chunk<D, G, FP8>(a, p.node_blocks + p.node_block_ptr[v], nullptr, seg_len, e0, e1, kvh, lane, col_req,
-                            col % G, col_slot, part_o, part_ml);
+// ---- the attention kernel -------------------------------------------------------------------------
+// One workgroup (4 waves) reduces one item: a chunk of one segment's blocks for one kv head and up to
+// 64 * kColGroups score columns.  The chunk's K/V blocks go HBM -> registers -> LDS once per workgroup,
+// two blocks (32 keys) per step, double buffered; every wave reads its MFMA operand fragments from LDS
+// and applies them to its kColGroups groups of 16 columns, so a block read from HBM once serves up to
+// 128 (request, head) columns.  Items are node items (columns = the requests through the node, a
+// quarter-wave of 16 columns = 16/G requests) followed by tail items (a request's own tail blocks, G
+// columns).  Workgroups loop over the item list with the grid as stride.
+constexpr int kColGroups = 1;                        // groups of 16 columns per wave
+constexpr int kItemCols = 64 * kColGroups;           // columns per workgroup item
+constexpr int kLdsPerWg = 53 * 1024;                    // LDS bytes one workgroup may take
+constexpr int kMaxChunk = 64;                        // table entries per item: one per lane of a wave
+
+template <int D, bool FP8>
+struct StageCfg {
+    static constexpr int ES = FP8 ? 1 : 2;                      // bytes per pool element
+    static constexpr int kRowB = D * ES;                        // K row
+    static constexpr int kCPR = kRowB / 16;                     // 16-byte chunks per K row: 16, 8 or 4
+    static constexpr int kBlkB = kBlock * D * ES;               // one (block, kv head) image of K or of V
+    static constexpr int kLoads = kBlkB / 1024;                 // wave-wide direct loads per image
+    static constexpr int kVOff = 2 * kBlkB;
+    static constexpr int kBuf = 4 * kBlkB;                      // one step: K of two blocks, V of two blocks
+    // step buffers: kRing - 1 steps are in flight per workgroup.  Sized so that two workgroups fill a CU's LDS
+    static constexpr int kRing = (kLdsPerWg / kBuf) < 9 ? (kLdsPerWg / kBuf) : 9;
+};
+
+// 16-byte-per-lane global -> LDS direct load: lane l fetches the 16 bytes at base + off (uniform base, 32-bit
+// lane offset) and writes LDS bytes [dst + 16 l, +16).  Issued through inline assembly and waited for by
+// hand (dma_wait<N>: at most N of this wave's vector memory operations still in flight), so that several
+// steps can be in flight; the compiler's own waits do not know these loads and can only over-wait.
+typedef __attribute__((address_space(3))) void *lds_ptr_t;
+__device__ __forceinline__ void dma_load(const void *base, uint32_t off, void *lds_dst) {
+    const uint32_t dst = (uint32_t)(uintptr_t)(lds_ptr_t)lds_dst;
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %2, %1" ::"s"(dst), "s"(base), "v"(off) : "memory", "m0");
+}
+template <int N>
+__device__ __forceinline__ void dma_wait() {
+    static_assert(N >= 0 && N < 64, "vmcnt range");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-// tails: one wave per (request, kv head, chunk of the request's tail entries), G columns in use
 template <int D, int G, bool FP8>
-__global__ __launch_bounds__(kSharedThreads) void shared_tail_kernel(AttnArgs a, SharedPlan p, int tail_splits,
-                                                                      float *__restrict__ part_o,
+__global__ __launch_bounds__(kSharedThreads) void shared_attn_kernel(AttnArgs a, SharedPlan p, float *__restrict__ part_o,
                                                                       float *__restrict__ part_ml) {
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const long w = (long)blockIdx.x * kSharedWaves + wave;
-    const long pairs = (long)a.num_req * a.hkv;
-    if (w >= pairs * tail_splits) return;
-    const int s = (int)(w / pairs);
-    const int rem = (int)(w % pairs);
-    const int r = rem / a.hkv, kvh = rem % a.hkv;
-    if (!request_ok(a, r)) return;
-    const int nb = max(min(a.num_blocks[r], a.max_blocks), 0);
-    const int ntail = tail_blocks_of(a, r);
-    const int e0 = nb - ntail + s * p.chunk_blocks;
-    const int e1 = min(nb, e0 + p.chunk_blocks);
-    if (e0 >= e1) return;
-    const int tail_chunks = (ntail + p.chunk_blocks - 1) / p.chunk_blocks;
-    const int n16 = lane & 15;
-    const int slot = p.slot_ptr[r + 1] - tail_chunks + s;
-    reduce_chunk<D, G, FP8>(a, a.block_table + (size_t)r * a.max_blocks, a.block_ntok + (size_t)r * a.max_blocks, 0, e0,
-                            e1, kvh, lane, (n16 < G && slot < p.slot_cap) ? r : -1, n16 % G, slot, part_o, part_ml);
+    using C = StageCfg<D, FP8>;
+    __shared__ __attribute__((aligned(1024))) char lds[C::kRing * C::kBuf];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n16 = lane & 15, q4 = lane >> 4;
+    const long total_w = ((long)p.totals[0] + p.totals[1]) * a.hkv;
+    // neighbours in the item list (same K/V blocks, other columns) run on the same XCD at the same time
+    const int grid = gridDim.x;
+    const int first = (grid % kXcds == 0) ? (int)(blockIdx.x % kXcds) * (grid / kXcds) + (int)(blockIdx.x / kXcds)
+                                          : (int)blockIdx.x;
+    const float c = a.scale_log2;
+
+    for (long w = first; w < total_w; w += grid) {
+        // ---- which item (workgroup-uniform) ----
+        const int2 rec = p.item_rec[w / a.hkv];
+        const int kvh = (int)(w % a.hkv);
+        const int32_t *tab, *ntk;
+        int seg_len = 0, e0, e1, chunk, slot0 = 0;
+        int v = -1, cnt = 0, quad = 0, groups = 0, row0 = 0;   // node items
+        int r_tail = -1;                                       // tail items
+        if (rec.x >= 0) {
+            v = rec.x;
+            cnt = p.cnt[v];
+            groups = (cnt * G + 15) / 16;
+            const int quads = max((groups + 4 * kColGroups - 1) / (4 * kColGroups), 1);
+            quad = rec.y % quads;
+            chunk = rec.y / quads;
+            row0 = p.node_ptr[v];
+            seg_len = p.node_len[v];
+            tab = p.node_blocks + p.node_block_ptr[v];
+            ntk = nullptr;
+            e0 = chunk * p.chunk_blocks;
+            e1 = min(node_blocks_of(p, v), e0 + p.chunk_blocks);
+        } else {
+            const int r = -rec.x - 1;
+            r_tail = r;
+            chunk = rec.y;
+            const int nb = max(min(a.num_blocks[r], a.max_blocks), 0);
+            const int ntail = tail_blocks_of(a, r);
+            const int tail_chunks = (ntail + p.chunk_blocks - 1) / p.chunk_blocks;
+            tab = a.block_table + (size_t)r * a.max_blocks;
+            ntk = a.block_ntok + (size_t)r * a.max_blocks;
+            e0 = nb - ntail + chunk * p.chunk_blocks;
+            e1 = (chunk < tail_chunks && request_ok(a, r)) ? min(nb, e0 + p.chunk_blocks) : e0;
+            slot0 = p.slot_ptr[r + 1] - tail_chunks + chunk;
+        }
+        if (e0 >= e1) continue;                                // workgroup-uniform
+        // ---- staging: HBM -> LDS direct loads ----
+        // the chunk's table entries (at most kMaxChunk = 64) live in lane registers, lane j = entry e0 + j: block id
+        // (clamped into the pool), token count and, for an e4m3 pool, the block's two scales.  The step loop
+        // reads them with v_readlane and touches memory only through the K/V requests and LDS.
+        int lane_blk = 0, lane_ntok = 0;
+        float lane_ks = 1.f, lane_vs = 1.f;
+        if (e0 + lane < e1) {
+            lane_blk = min(max(tab[e0 + lane], 0), a.pool_blocks - 1);
+            lane_ntok = ntk ? ntk[e0 + lane] : min(kBlock, seg_len - kBlock * (e0 + lane));
+            if constexpr (FP8) {
+                lane_ks = a.k_scale[lane_blk];
+                lane_vs = a.v_scale[lane_blk];
+            }
+        }
+        // Wave w brings in one of the four images of a step: K of block w & 1 (w < 2) or V of block w & 1.
+        // Lane l of load i fills LDS chunk q = 64 i + l of the image and picks its source so that the image is
+        // XOR-swizzled: K row (q / CPR) holds chunk c at position c ^ k_swz(block, row); the two halves of a
+        // bf16 V row swap on every other group of 8 rows.  Every 16-lane group of an operand fetch then hits
+        // 16 different 16-byte bank groups.
+        auto k_swz = [](int blk, int slot) -> int {
+            const int bits = (slot & 3) | (((slot >> 3) & 1) << 2) | (blk << 3);     // the 16 rows a tile reads
+            return C::kCPR == 16 ? bits : C::kCPR == 8 ? bits >> 1 : bits >> 2;
+        };
+        uint32_t src_off[C::kLoads];
+#pragma unroll
+        for (int i = 0; i < C::kLoads; ++i) {
+            const int q = 64 * i + lane;
+            if (wave < 2) {
+                const int row = q / C::kCPR, pos = q % C::kCPR;
+                src_off[i] = row * C::kRowB + ((pos ^ k_swz(wave & 1, row)) * 16);
+            } else if constexpr (FP8) {
+                src_off[i] = q * 16;
+            } else {
+                const int d = q >> 1;
+                src_off[i] = d * 32 + (((q & 1) ^ ((d >> 3) & 1)) * 16);
+            }
+        }
+        const int nsteps = (e1 - e0 + 1) / 2;
+        auto issue = [&](int step, int buf) {
+            const int j = 2 * step + (wave & 1);
+            const int b = __builtin_amdgcn_readlane(lane_blk, e0 + j < e1 ? j : 2 * step);   // odd tail: block 0 again
+            const uintptr_t addr = (uintptr_t)(wave < 2 ? a.k : a.v) + ((size_t)b * a.hkv + kvh) * C::kBlkB;
+            // wave-uniform by construction; said explicitly so that the address lives in scalar registers
+            const char *src = (const char *)(((uintptr_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(addr >> 32)) << 32) |
+                                             (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)addr));
+            char *dst = lds + buf * C::kBuf + wave * C::kBlkB;
+#pragma unroll
+            for (int i = 0; i < C::kLoads; ++i) dma_load(src, src_off[i], dst + 1024 * i);
+        };
+        // operand fragments out of LDS (same geometry as the per-request kernel reads from HBM)
+        const int k_slot = 8 * ((n16 >> 2) & 1) + (n16 & 3);
+        const int k_row = (n16 >= 8 ? C::kBlkB : 0) + k_slot * C::kRowB;
+        const int k_x = (q4 ^ k_swz(n16 >= 8 ? 1 : 0, k_slot)) * 16;            // chunk (4 t + q4) sits at k_x ^ 64 t
+        const int v_frag = C::kVOff + (q4 >= 2 ? C::kBlkB : 0) +
+                           (FP8 ? n16 * 16 + (q4 & 1) * 8 : n16 * 32 + (((q4 & 1) ^ ((n16 >> 3) & 1)) * 16));
+
+#pragma unroll
+        for (int j = 0; j < C::kRing - 1; ++j)
+            if (j < nsteps) issue(j, j);
+        // ---- the columns of this wave: (request, query head, partial slot) per lane ----
+        int col_req[kColGroups], col_head[kColGroups], col_slot[kColGroups];
+        int my_groups = 0;                                     // groups of this wave that hold columns
+#pragma unroll
+        for (int g = 0; g < kColGroups; ++g) {
+            col_req[g] = -1;
+            col_head[g] = n16 % G;
+            col_slot[g] = 0;
+            if (v >= 0) {
+                const int cg = quad * 4 * kColGroups + g * 4 + wave;   // groups dealt to the waves round robin
+                if (cg < groups) my_groups = g + 1;
+                const int col = cg * 16 + n16;
+                const int row = col / G;
+                col_head[g] = col % G;
+                if (row < cnt && row0 + row < p.num_entries) {
+                    col_req[g] = p.row_req[row0 + row];
+                    col_slot[g] = p.row_slot[row0 + row] + chunk;
+                }
+            } else if (g == 0 && wave == 0) {
+                my_groups = 1;
+                if (n16 < G) {
+                    col_req[g] = r_tail;
+                    col_slot[g] = slot0;
+                }
+            }
+            if (col_slot[g] < 0 || col_slot[g] >= p.slot_cap) col_req[g] = -1;   // only with tables that break the resolve contract
+        }
+        my_groups = __builtin_amdgcn_readfirstlane(my_groups);
+
+        // ---- Q^T operands of this wave's columns ----
+        bf16x8 qf[kColGroups][D / 32];
+#pragma unroll
+        for (int g = 0; g < kColGroups; ++g)
+#pragma unroll
+            for (int t = 0; t < D / 32; ++t) {
+                const int d0 = FP8 ? 64 * (t / 2) + 16 * q4 + 8 * (t % 2) : 32 * t + 8 * q4;
+                u32x4 raw = {0, 0, 0, 0};
+                if (col_req[g] >= 0)
+                    raw = *(const u32x4 *)((const char *)a.q +
+                                           (((size_t)col_req[g] * a.hq + kvh * G + col_head[g]) * D + d0) * 2);
+                qf[g][t] = __builtin_bit_cast(bf16x8, raw);
+            }
+        float m_run[kColGroups], l_run[kColGroups];
+        f32x4 oacc[kColGroups][D / 16];
+#pragma unroll
+        for (int g = 0; g < kColGroups; ++g) {
+            m_run[g] = -1.0e30f;
+            l_run[g] = 0.f;
+#pragma unroll
+            for (int dt = 0; dt < D / 16; ++dt) oacc[g][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+
+        // Everything this item loaded through the compiler (table entries, Q) is waited for here, once: a wait
+        // the compiler placed at the first use inside the loop would be a vmcnt(0) in every step and drain the ring.
+        __builtin_amdgcn_s_waitcnt(0x0F70);                    // vmcnt(0), other counters untouched
+        int buf = 0;
+        for (int step = 0; step < nsteps; ++step) {
+            // this wave's image of `step` has landed when at most the younger requests are outstanding
+            if (step + C::kRing - 2 < nsteps) dma_wait<(C::kRing - 2) * C::kLoads>();
+            else dma_wait<0>();
+            __syncthreads();           // all four images of `step` are in LDS; everybody is done with step - 1
+            if (step + C::kRing - 1 < nsteps) issue(step + C::kRing - 1, buf == 0 ? C::kRing - 1 : buf - 1);
+            const bool two = e0 + 2 * step + 1 < e1;
+            const int n0 = __builtin_amdgcn_readlane(lane_ntok, 2 * step);
+            const int n1 = two ? __builtin_amdgcn_readlane(lane_ntok, 2 * step + 1) : 0;
+            float ks = 1.f, vs = 1.f;
+            if constexpr (FP8) {
+                const int jj = 2 * step + (q4 >= 2 && two ? 1 : 0);        // this lane's keys: block q4 / 2 of the step
+                ks = __shfl(lane_ks, jj, 64);
+                vs = __shfl(lane_vs, jj, 64);
+            }
+            const char *base = lds + buf * C::kBuf;
+            if (my_groups > 0) {
+                f32x4 sT[kColGroups][2];
+#pragma unroll
+                for (int T = 0; T < 2; ++T) {
+#pragma unroll
+                    for (int g = 0; g < kColGroups; ++g) sT[g][T] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    if constexpr (FP8) {
+#pragma unroll
+                        for (int tp = 0; tp < D / 64; ++tp) {
+                            const u32x4 raw = *(const u32x4 *)(base + k_row + 4 * T * C::kRowB + (k_x ^ (64 * tp)));
+                            const bf16x8 k0 = fp8x8_to_bf16x8(u32x2{raw[0], raw[1]});
+                            const bf16x8 k1 = fp8x8_to_bf16x8(u32x2{raw[2], raw[3]});
+#pragma unroll
+                            for (int g = 0; g < kColGroups; ++g)
+                                if (g < my_groups) {
+                                    sT[g][T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k0, qf[g][2 * tp], sT[g][T], 0, 0, 0);
+                                    sT[g][T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(k1, qf[g][2 * tp + 1], sT[g][T], 0, 0, 0);
+                                }
+                        }
+                    } else {
+#pragma unroll
+                        for (int t = 0; t < D / 32; ++t) {
+                            const bf16x8 kf = __builtin_bit_cast(
+                                bf16x8, *(const u32x4 *)(base + k_row + 4 * T * C::kRowB + (k_x ^ (64 * t))));
+#pragma unroll
+                            for (int g = 0; g < kColGroups; ++g)
+                                if (g < my_groups)
+                                    sT[g][T] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[g][t], sT[g][T], 0, 0, 0);
+                        }
+                    }
+                }
+                bf16x8 pb[kColGroups];
+                float alpha[kColGroups];
+#pragma unroll
+                for (int g = 0; g < kColGroups; ++g) {
+                    alpha[g] = 1.f;
+                    pb[g] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+                    if (g < my_groups) {
+                        if constexpr (FP8) { sT[g][0] *= ks; sT[g][1] *= ks; }
+                        if (n0 < kBlock || n1 < kBlock) {
+                            const int lim = ((q4 >= 2) ? n1 : n0) - 8 * (q4 & 1);
+#pragma unroll
+                            for (int T = 0; T < 2; ++T)
+#pragma unroll
+                                for (int i = 0; i < 4; ++i)
+                                    if (4 * T + i >= lim) sT[g][T][i] = -INFINITY;
+                        }
+                        float mx = fmaxf(fmaxf(fmaxf(sT[g][0][0], sT[g][0][1]), fmaxf(sT[g][0][2], sT[g][0][3])),
+                                         fmaxf(fmaxf(sT[g][1][0], sT[g][1][1]), fmaxf(sT[g][1][2], sT[g][1][3])));
+                        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+                        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+                        const float m_new = fmaxf(m_run[g], mx);
+                        alpha[g] = fast_exp2((m_run[g] - m_new) * c);
+                        const float mc = m_new * c;
+                        m_run[g] = m_new;
+                        f32x8 pr;
+                        float psum = 0.f;
+#pragma unroll
+                        for (int T = 0; T < 2; ++T)
+#pragma unroll
+                            for (int i = 0; i < 4; ++i) {
+                                const float e2 = fast_exp2(sT[g][T][i] * c - mc);
+                                pr[4 * T + i] = e2;
+                                psum += e2;
+                            }
+                        l_run[g] = l_run[g] * alpha[g] + psum;
+                        if constexpr (FP8) pr *= vs;
+                        pb[g] = __builtin_convertvector(pr, bf16x8);
+                    }
+                }
+#pragma unroll
+                for (int dt = 0; dt < D / 16; ++dt) {
+                    bf16x8 vf;
+                    if constexpr (FP8) vf = fp8x8_to_bf16x8(*(const u32x2 *)(base + v_frag + dt * 256));
+                    else vf = __builtin_bit_cast(bf16x8, *(const u32x4 *)(base + v_frag + dt * 512));
+#pragma unroll
+                    for (int g = 0; g < kColGroups; ++g)
+                        if (g < my_groups) {
+                            oacc[g][dt] *= alpha[g];
+                            oacc[g][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pb[g], oacc[g][dt], 0, 0, 0);
+                        }
+                }
+            }
+            buf = buf + 1 == C::kRing ? 0 : buf + 1;
+        }
+        __syncthreads();               // the ring is free again before the next item writes into it
+
+        // ---- partials of this wave's columns ----
+#pragma unroll
+        for (int g = 0; g < kColGroups; ++g) {
+            float l = l_run[g];
+            l += __shfl_xor(l, 16, 64);
+            l += __shfl_xor(l, 32, 64);
+            if (g < my_groups && col_req[g] >= 0) {
+                const size_t pi = (size_t)col_slot[g] * a.hq + kvh * G + col_head[g];
+                if (q4 == 0) {
+                    part_ml[pi * 2 + 0] = m_run[g] * c;   // max in log2 units
+                    part_ml[pi * 2 + 1] = l;
+                }
+#pragma unroll
+                for (int dt = 0; dt < D / 16; ++dt) *(f32x4 *)(part_o + pi * D + 16 * dt + 4 * q4) = oacc[g][dt];
+            }
+        }
+    }
 }
 
 // One wave per (request, query head): combine the request's partial slots.
@@ -328,38 +526,50 @@ size_t shared_slot_cap(int32_t num_req, int32_t num_entries, int32_t max_blocks,
 }
 
 size_t shared_int_words(int32_t num_nodes, int32_t num_req, int32_t num_entries) {
-    return 4 * ((size_t)num_nodes + 1) + 3 * ((size_t)num_entries + 1) + ((size_t)num_req + 2) + 8;
+    return 4 * ((size_t)num_nodes + 1) + 3 * ((size_t)num_entries + 1) + 2 * ((size_t)num_req + 2) + 8;
 }
+// + one 8-byte item record per partial slot (items <= slots: a node item serves at least one request)
 
 size_t shared_workspace_bytes(int32_t num_nodes, int32_t num_req, int32_t num_entries, int32_t max_blocks,
                               int32_t chunk_blocks, int32_t hq, int32_t head_dim) {
     const size_t slots = shared_slot_cap(num_req, num_entries, max_blocks, chunk_blocks);
-    return shared_int_words(num_nodes, num_req, num_entries) * sizeof(int32_t) + 256 +
+    return shared_int_words(num_nodes, num_req, num_entries) * sizeof(int32_t) + 8 + slots * sizeof(int2) + 256 +
            slots * hq * ((size_t)head_dim + 2) * sizeof(float);
 }
 
+// resident workgroups of the attention kernel on the whole device (the item loop strides by the grid, so
+// every workgroup of the grid has to be resident from the start), a multiple of the XCD count
+template <class K>
+static int resident_grid(K kernel) {
+    int dev = 0, cus = 0, per_cu = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, kernel, kSharedThreads, 0) != hipSuccess) return 0;
+    const int g = cus * per_cu;
+    return g >= kXcds ? g / kXcds * kXcds : g;
+}
+
+template <int D, int G, bool FP8>
+static hipError_t launch_attn(const AttnArgs &a, SharedPlan p, float *part_o, float *part_ml, hipStream_t s) {
+    static int grid = resident_grid(shared_attn_kernel<D, G, FP8>);       // one device per process
+    if (grid <= 0) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((shared_attn_kernel<D, G, FP8>), dim3(grid), dim3(kSharedThreads), 0, s, a, p, part_o, part_ml);
+    return hipGetLastError();
+}
+
 template <int D, int G>
-static hipError_t launch_shared_t(const AttnArgs &a, int kv_dtype, SharedPlan p, int tail_splits, float *part_o,
-                                  float *part_ml, hipStream_t s) {
+static hipError_t launch_shared_t(const AttnArgs &a, int kv_dtype, SharedPlan p, float *part_o, float *part_ml,
+                                  hipStream_t s) {
     const unsigned nz = (unsigned)((p.num_nodes + 255) / 256), nr = (unsigned)((a.num_req + 255) / 256);
     hipLaunchKernelGGL(shared_zero_kernel, dim3(nz ? nz : 1), dim3(256), 0, s, p);
     hipLaunchKernelGGL(shared_count_kernel, dim3(nr), dim3(256), 0, s, p, a);
-    hipLaunchKernelGGL(shared_scan_kernel, dim3(1), dim3(kScanThreads), 0, s, p, a, G);
-    hipLaunchKernelGGL(shared_fill_kernel, dim3(nr), dim3(256), 0, s, p, a);
+    hipLaunchKernelGGL(shared_scan_kernel, dim3(1), dim3(kScanThreads), 0, s, p, a, G, kItemCols);
+    const unsigned nf = (unsigned)(((size_t)a.num_req + p.num_nodes + 255) / 256);
+    hipLaunchKernelGGL(shared_fill_kernel, dim3(nf), dim3(256), 0, s, p, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    const size_t node_waves = (size_t)p.item_cap * a.hkv;
-    const size_t tail_waves = (size_t)a.num_req * a.hkv * tail_splits;
-    const unsigned g_node = (unsigned)((node_waves + kSharedWaves - 1) / kSharedWaves);
-    const unsigned g_tail = (unsigned)((tail_waves + kSharedWaves - 1) / kSharedWaves);
-    if (kv_dtype == GF_FP8_E4M3) {
-        if (g_node) hipLaunchKernelGGL((shared_node_kernel<D, G, true>), dim3(g_node), dim3(kSharedThreads), 0, s, a, p, part_o, part_ml);
-        if (g_tail) hipLaunchKernelGGL((shared_tail_kernel<D, G, true>), dim3(g_tail), dim3(kSharedThreads), 0, s, a, p, tail_splits, part_o, part_ml);
-    } else {
-        if (g_node) hipLaunchKernelGGL((shared_node_kernel<D, G, false>), dim3(g_node), dim3(kSharedThreads), 0, s, a, p, part_o, part_ml);
-        if (g_tail) hipLaunchKernelGGL((shared_tail_kernel<D, G, false>), dim3(g_tail), dim3(kSharedThreads), 0, s, a, p, tail_splits, part_o, part_ml);
-    }
-    e = hipGetLastError();
+    e = kv_dtype == GF_FP8_E4M3 ? launch_attn<D, G, true>(a, p, part_o, part_ml, s)
+                                : launch_attn<D, G, false>(a, p, part_o, part_ml, s);
     if (e != hipSuccess) return e;
     const size_t rows = (size_t)a.num_req * a.hq;
     hipLaunchKernelGGL((shared_merge_kernel<D>), dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, a, p, part_o, part_ml);
@@ -378,17 +588,18 @@ hipError_t launch_decode_shared(const AttnArgs &a, int head_dim, int group, int 
     p.path_nodes = path_nodes;
     p.num_nodes = g.num_nodes;
     p.num_entries = num_entries;
-    p.chunk_blocks = chunk_blocks;
+    p.chunk_blocks = chunk_blocks < kMaxChunk ? chunk_blocks : kMaxChunk;
     int32_t *w = (int32_t *)workspace;
     const size_t n1 = (size_t)g.num_nodes + 1, e1 = (size_t)num_entries + 1;
     p.cnt = w;            w += n1;
     p.cursor = w;         w += n1;
     p.node_ptr = w;       w += n1;
     p.item_ptr = w;       w += n1;
-    p.entry_req = w;      w += e1;
     p.entry_slot = w;     w += e1;
-    p.inv_entry = w;      w += e1;
+    p.row_req = w;        w += e1;
+    p.row_slot = w;       w += e1;
     p.slot_ptr = w;       w += (size_t)a.num_req + 2;
+    p.tail_ptr = w;       w += (size_t)a.num_req + 2;
     p.totals = w;         w += 8;
     const size_t slots = shared_slot_cap(a.num_req, num_entries, a.max_blocks, chunk_blocks);
     // node items: sum over (request, path entry) of chunks * column groups <= the slot bound (a column group
@@ -396,12 +607,11 @@ hipError_t launch_decode_shared(const AttnArgs &a, int head_dim, int group, int 
     if (slots > 0x7fffffffu / (size_t)(a.hkv > 0 ? a.hkv : 1)) return hipErrorInvalidValue;
     p.item_cap = (int32_t)slots;
     p.slot_cap = (int32_t)slots;
-    float *part_o = (float *)(((uintptr_t)w + 255) & ~(uintptr_t)255);
+    p.item_rec = (int2 *)(((uintptr_t)w + 7) & ~(uintptr_t)7);
+    float *part_o = (float *)(((uintptr_t)(p.item_rec + slots) + 255) & ~(uintptr_t)255);
     float *part_ml = part_o + slots * a.hq * (size_t)head_dim;
-    // the host does not know how long the tails are: bound their chunks by the table width
-    const int tail_splits = (a.max_blocks + chunk_blocks - 1) / chunk_blocks;
 #define GF_CASE(DD, GG) \
-    if (head_dim == DD && group == GG) return launch_shared_t<DD, GG>(a, kv_dtype, p, tail_splits, part_o, part_ml, s);
+    if (head_dim == DD && group == GG) return launch_shared_t<DD, GG>(a, kv_dtype, p, part_o, part_ml, s);
     GF_CASE(64, 1) GF_CASE(64, 2) GF_CASE(64, 4) GF_CASE(64, 8)
     GF_CASE(128, 1) GF_CASE(128, 2) GF_CASE(128, 4) GF_CASE(128, 8)
 #undef GF_CASE
