@@ -144,7 +144,7 @@ class Job:
         db["path_ptr"] = self.dbatch["path_ptr"][lo:hi + 1]
         self.sess.decode_shared(self.pool, db, self._slice(lo, hi), self.qd[lo:hi], self.od_shared[lo:hi])
 
-    def decode_shared_bytes(self, chunk_blocks=32):
+    def decode_shared_bytes(self, chunk_blocks=64):
         """What the node-centric decode has to move: every node the decode requests touch once, their
         tails, one fp32 partial (max, sum, values) per (request, path node, chunk) written and read
         back, the block lists, q and o."""
@@ -335,6 +335,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="prefill_8b",
                     choices=["tiny", "prefill_8b", "decode_8b", "decode_70b", "mixed_fp8"])
+    ap.add_argument("--decode-chunk", type=int, default=0,
+                    help="table entries per split-KV chunk of the decode kernels (0 = the library's choice)")
     ap.add_argument("--extra", default="decode_8b,kv_residual,stream_copy",
                     help="comma list of further workloads reported under 'extra' (the five configs, kv_residual, stream_copy)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -367,6 +369,8 @@ def main():
         torch.cuda.empty_cache()
 
     job = Job(args.workload, torch, R, W)
+    if args.decode_chunk:
+        B.gf_set_decode_chunk_blocks(job.sess.ctx, args.decode_chunk)
     m = measure(job, args.steps, args.warmup)
     wl = job.wl
     if job.has_prefill:

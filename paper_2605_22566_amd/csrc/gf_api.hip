@@ -226,8 +226,8 @@ int32_t gf_attn_decode_shared(gf_ctx *ctx, const gf_attn_params *params, const g
     if (graph->num_nodes > 0 && (!graph->node_len || !graph->node_block_ptr || !graph->node_blocks))
         return GF_ERR_NULL;
     int32_t chunk = ctx->decode_chunk_blocks;
-    if (chunk <= 0) chunk = 32;
-    if (chunk > 64) chunk = 64;      // the node-centric kernel keeps a chunk's table entries in one wave's lanes
+    // the node-centric kernel keeps a chunk's table entries in one wave's lanes: 64 at most, and by default
+    if (chunk <= 0 || chunk > 64) chunk = 64;
     const size_t need = gf::shared_workspace_bytes(graph->num_nodes, a.num_req, num_path_entries, a.max_blocks, chunk,
                                                    a.hq, params->head_dim);
     rc = ensure_buffer(ctx, &ctx->workspace, &ctx->workspace_bytes, need, (hipStream_t)stream,

@@ -167,13 +167,17 @@ __global__ void shared_fill_kernel(SharedPlan p, AttnArgs a) {
 // 128 (request, head) columns.  Items are node items (columns = the requests through the node, a
 // quarter-wave of 16 columns = 16/G requests) followed by tail items (a request's own tail blocks, G
 // columns).  Workgroups loop over the item list with the grid as stride.
-constexpr int kColGroups = 1;                        // groups of 16 columns per wave
-constexpr int kItemCols = 64 * kColGroups;           // columns per workgroup item
-constexpr int kLdsPerWg = 53 * 1024;                    // LDS bytes one workgroup may take
+// groups of 16 columns per wave: two when a request brings 8 heads per kv head (its node lists are twice as
+// wide in columns, and a fragment read from LDS then feeds two MFMAs), else one (more workgroups per CU)
+constexpr int col_groups(int G) { return G >= 8 ? 2 : 1; }
+// workgroups per CU the kernel is built for: registers and the LDS ring are sized to it
+constexpr int wgs_per_cu(int G) { return col_groups(G) == 1 ? 4 : 3; }
+constexpr int kLdsPerCu = 160 * 1024;
 constexpr int kMaxChunk = 64;                        // table entries per item: one per lane of a wave
 
-template <int D, bool FP8>
+template <int D, bool FP8, int WGS>
 struct StageCfg {
+    static constexpr int kLdsPerWg = kLdsPerCu / WGS;           // LDS bytes one workgroup may take
     static constexpr int ES = FP8 ? 1 : 2;                      // bytes per pool element
     static constexpr int kRowB = D * ES;                        // K row
     static constexpr int kCPR = kRowB / 16;                     // 16-byte chunks per K row: 16, 8 or 4
@@ -181,7 +185,7 @@ struct StageCfg {
     static constexpr int kLoads = kBlkB / 1024;                 // wave-wide direct loads per image
     static constexpr int kVOff = 2 * kBlkB;
     static constexpr int kBuf = 4 * kBlkB;                      // one step: K of two blocks, V of two blocks
-    // step buffers: kRing - 1 steps are in flight per workgroup.  Sized so that two workgroups fill a CU's LDS
+    // step buffers: kRing - 1 steps are in flight per workgroup
     static constexpr int kRing = (kLdsPerWg / kBuf) < 9 ? (kLdsPerWg / kBuf) : 9;
 };
 
@@ -201,9 +205,10 @@ __device__ __forceinline__ void dma_wait() {
 }
 
 template <int D, int G, bool FP8>
-__global__ __launch_bounds__(kSharedThreads) void shared_attn_kernel(AttnArgs a, SharedPlan p, float *__restrict__ part_o,
+__global__ __launch_bounds__(kSharedThreads, wgs_per_cu(G)) void shared_attn_kernel(AttnArgs a, SharedPlan p, float *__restrict__ part_o,
                                                                       float *__restrict__ part_ml) {
-    using C = StageCfg<D, FP8>;
+    constexpr int kColGroups = col_groups(G);
+    using C = StageCfg<D, FP8, wgs_per_cu(G)>;
     __shared__ __attribute__((aligned(1024))) char lds[C::kRing * C::kBuf];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -215,6 +220,7 @@ __global__ __launch_bounds__(kSharedThreads) void shared_attn_kernel(AttnArgs a,
     const int first = (grid % kXcds == 0) ? (int)(blockIdx.x % kXcds) * (grid / kXcds) + (int)(blockIdx.x / kXcds)
                                           : (int)blockIdx.x;
     const float c = a.scale_log2;
+    const float slack = 8.f / c;                               // 2^8 in the exponent, in score units (inf for a zero scale)
 
     for (long w = first; w < total_w; w += grid) {
         // ---- which item (workgroup-uniform) ----
@@ -414,10 +420,8 @@ __global__ __launch_bounds__(kSharedThreads) void shared_attn_kernel(AttnArgs a,
                     }
                 }
                 bf16x8 pb[kColGroups];
-                float alpha[kColGroups];
 #pragma unroll
                 for (int g = 0; g < kColGroups; ++g) {
-                    alpha[g] = 1.f;
                     pb[g] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
                     if (g < my_groups) {
                         if constexpr (FP8) { sT[g][0] *= ks; sT[g][1] *= ks; }
@@ -431,12 +435,22 @@ __global__ __launch_bounds__(kSharedThreads) void shared_attn_kernel(AttnArgs a,
                         }
                         float mx = fmaxf(fmaxf(fmaxf(sT[g][0][0], sT[g][0][1]), fmaxf(sT[g][0][2], sT[g][0][3])),
                                          fmaxf(fmaxf(sT[g][1][0], sT[g][1][1]), fmaxf(sT[g][1][2], sT[g][1][3])));
-                        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-                        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-                        const float m_new = fmaxf(m_run[g], mx);
-                        alpha[g] = fast_exp2((m_run[g] - m_new) * c);
-                        const float mc = m_new * c;
-                        m_run[g] = m_new;
+                        // m_run is the reference the exponentials are taken against, the same in the four lanes
+                        // of a column, not the exact running maximum: it is only moved (and sums and values
+                        // rescaled) when some score outgrows it by more than 2^8 in the exponent, which keeps
+                        // everything well inside fp32 and bf16 range.  Most steps therefore need neither the
+                        // cross-lane maximum nor the rescaling multiplies.
+                        if (__builtin_amdgcn_ballot_w64(mx > m_run[g] + slack) != 0) {
+                            mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+                            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+                            const float m_new = fmaxf(m_run[g], mx);
+                            const float al = fast_exp2((m_run[g] - m_new) * c);
+                            m_run[g] = m_new;
+                            l_run[g] *= al;
+#pragma unroll
+                            for (int dt = 0; dt < D / 16; ++dt) oacc[g][dt] *= al;
+                        }
+                        const float mc = m_run[g] * c;
                         f32x8 pr;
                         float psum = 0.f;
 #pragma unroll
@@ -447,7 +461,7 @@ __global__ __launch_bounds__(kSharedThreads) void shared_attn_kernel(AttnArgs a,
                                 pr[4 * T + i] = e2;
                                 psum += e2;
                             }
-                        l_run[g] = l_run[g] * alpha[g] + psum;
+                        l_run[g] += psum;
                         if constexpr (FP8) pr *= vs;
                         pb[g] = __builtin_convertvector(pr, bf16x8);
                     }
@@ -460,7 +474,6 @@ __global__ __launch_bounds__(kSharedThreads) void shared_attn_kernel(AttnArgs a,
 #pragma unroll
                     for (int g = 0; g < kColGroups; ++g)
                         if (g < my_groups) {
-                            oacc[g][dt] *= alpha[g];
                             oacc[g][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pb[g], oacc[g][dt], 0, 0, 0);
                         }
                 }
@@ -563,7 +576,7 @@ static hipError_t launch_shared_t(const AttnArgs &a, int kv_dtype, SharedPlan p,
     const unsigned nz = (unsigned)((p.num_nodes + 255) / 256), nr = (unsigned)((a.num_req + 255) / 256);
     hipLaunchKernelGGL(shared_zero_kernel, dim3(nz ? nz : 1), dim3(256), 0, s, p);
     hipLaunchKernelGGL(shared_count_kernel, dim3(nr), dim3(256), 0, s, p, a);
-    hipLaunchKernelGGL(shared_scan_kernel, dim3(1), dim3(kScanThreads), 0, s, p, a, G, kItemCols);
+    hipLaunchKernelGGL(shared_scan_kernel, dim3(1), dim3(kScanThreads), 0, s, p, a, G, 64 * col_groups(G));
     const unsigned nf = (unsigned)(((size_t)a.num_req + p.num_nodes + 255) / 256);
     hipLaunchKernelGGL(shared_fill_kernel, dim3(nf), dim3(256), 0, s, p, a);
     hipError_t e = hipGetLastError();
