@@ -4,21 +4,24 @@
 // that pass through it -- here the sharing is used for the reads as well as for the storage).
 //
 // Node-centric order.  The batch's path lists are inverted on the device into node -> requests
-// lists.  One wavefront then reduces one (node, kv head, chunk of the node's blocks, group of 16
-// score columns), where a column is a (request through that node, query head of the group) pair:
-// the K/V blocks it loads feed 16/G requests at once (v_mfma_f32_16x16x32_bf16 with all 16
-// columns in use, where the request-centric kernel pads G heads to 16).  It leaves one fp32
-// partial (max, sum, weighted values) per (request, path node, chunk).  The private tail blocks
-// of a request (its new tokens) are reduced request by request as before, and one merge kernel
-// combines a request's partials -- path nodes in order, then tail -- with the log-sum-exp rule.
-// The result is the request-centric one up to fp32 summation order.
+// lists.  A score column is a (request through the node, query head of a kv head's group) pair;
+// one workgroup reduces one item = (node, chunk of the node's blocks, kv head, up to 64 or 128
+// columns): the chunk's K/V blocks are staged through LDS once and feed every column of the item
+// (v_mfma_f32_16x16x32_bf16 with all 16 columns of a tile in use, where the request-centric kernel
+// pads G heads to 16).  An item leaves one fp32 partial (reference max, sum, weighted values) per
+// (request, path node, chunk).  The private tail blocks of a request (its new tokens) are items of
+// their own with G columns, and one merge kernel combines a request's partials -- path nodes in
+// order, then tail -- with the log-sum-exp rule.  The result is the request-centric one up to
+// fp32 summation order.
 //
 // Integer preparation (all on the device, no host round trip):
-//   count   per request: its path entries -> cnt[node] (atomics), request of every entry
-//   scan    one workgroup: node_ptr = scan(cnt); items per node = chunks * column groups ->
-//           item_ptr; partial slots per request = sum over its path of chunks(node) + tail
-//           chunks -> slot_ptr, and the first slot of every path entry
-//   fill    per request: row of each of its path entries in the node's list (atomic cursor)
+//   count   per path entry: cnt[node] (atomics) and the entry's number of chunks
+//   scan    one workgroup: node_ptr = scan(cnt); item_ptr = scan(chunks * column quads per node);
+//           entry_slot = scan(chunks per path entry): the partial slots of a request's nodes are
+//           contiguous, in path order; tail_ptr = scan(tail chunks per request), the tail slots
+//           follow all node slots
+//   fill    per path entry: its row in the node's list (atomic cursor) = (request, first slot);
+//           per node and per request: the item records
 // The order in which requests land in a node's list depends on the atomics, the values do not:
 // a column's result does not depend on which column it is.
 #include "gf_internal.h"
@@ -35,7 +38,7 @@ struct SharedPlan {
     const int32_t *node_len, *node_block_ptr, *node_blocks, *path_ptr, *path_nodes;
     int32_t num_nodes, num_entries;
     // scratch (device, context's)
-    int32_t *cnt, *cursor, *node_ptr, *item_ptr, *entry_slot, *row_req, *row_slot, *slot_ptr, *tail_ptr, *totals;
+    int32_t *cnt, *cursor, *node_ptr, *item_ptr, *entry_slot, *row_req, *row_slot, *tail_ptr, *totals;
     int2 *item_rec;
     int32_t chunk_blocks, item_cap, slot_cap;
 };
@@ -70,14 +73,29 @@ __global__ void shared_zero_kernel(SharedPlan p) {
     }
 }
 
-__global__ void shared_count_kernel(SharedPlan p, AttnArgs a) {
-    const int r = blockIdx.x * blockDim.x + threadIdx.x;
-    if (r >= a.num_req) return;
-    const bool ok = request_ok(a, r);
-    for (int e = path_lo(p, r); e < path_hi(p, r); ++e) {
-        const int v = p.path_nodes[e];
-        if (ok && v >= 0 && v < p.num_nodes) atomicAdd(&p.cnt[v], 1);
+// request that owns path entry e: the last r with path_ptr[r] <= e (-1 if none does)
+__device__ __forceinline__ int request_of_entry(const SharedPlan &p, const AttnArgs &a, int e) {
+    int lo = 0, hi = a.num_req;
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (p.path_ptr[mid] <= e) lo = mid;
+        else hi = mid;
     }
+    return (e >= p.path_ptr[lo] && e < p.path_ptr[lo + 1]) ? lo : -1;
+}
+
+// one thread per path entry: count it for its node, note its chunks (0 for an entry that does not take part)
+__global__ void shared_count_kernel(SharedPlan p, AttnArgs a) {
+    const int e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= p.num_entries) return;
+    const int r = request_of_entry(p, a, e);
+    const int v = p.path_nodes[e];
+    int chunks = 0;
+    if (r >= 0 && request_ok(a, r) && v >= 0 && v < p.num_nodes) {
+        atomicAdd(&p.cnt[v], 1);
+        chunks = node_chunks_of(p, v);
+    }
+    p.row_slot[e] = chunks;            // scratch until the fill kernel writes the rows
 }
 
 // exclusive scan of f(i), i in [0, n), by one workgroup; out[n] = total
@@ -106,56 +124,49 @@ __device__ void block_exscan(int n, F f, int32_t *out, int32_t *sh) {
 
 __global__ __launch_bounds__(kScanThreads) void shared_scan_kernel(SharedPlan p, AttnArgs a, int group, int item_cols) {
     __shared__ int32_t sh[kScanThreads];
-    auto chunks_of = [&](int v) -> int { return node_chunks_of(p, v); };
     block_exscan(p.num_nodes, [&](int v) { return p.cnt[v]; }, p.node_ptr, sh);
-    block_exscan(p.num_nodes, [&](int v) { return chunks_of(v) * ((p.cnt[v] * group + item_cols - 1) / item_cols); }, p.item_ptr, sh);
-    // partial slots per request: its path nodes' chunks, then the chunks of its tail
-    auto tail_chunks = [&](int r) -> int { return (tail_blocks_of(a, r) + p.chunk_blocks - 1) / p.chunk_blocks; };
+    block_exscan(p.num_nodes, [&](int v) {
+        return node_chunks_of(p, v) * ((p.cnt[v] * group + item_cols - 1) / item_cols);
+    }, p.item_ptr, sh);
+    block_exscan(p.num_entries, [&](int e) { return p.row_slot[e]; }, p.entry_slot, sh);
     block_exscan(a.num_req, [&](int r) {
-        if (!request_ok(a, r)) return 0;
-        int s = tail_chunks(r);
-        for (int e = path_lo(p, r); e < path_hi(p, r); ++e) s += chunks_of(p.path_nodes[e]);
-        return s;
-    }, p.slot_ptr, sh);
-    for (int r = threadIdx.x; r < a.num_req; r += kScanThreads) {
-        if (!request_ok(a, r)) continue;
-        int s = p.slot_ptr[r];
-        for (int e = path_lo(p, r); e < path_hi(p, r); ++e) {
-            p.entry_slot[e] = s;
-            s += chunks_of(p.path_nodes[e]);
-        }
-    }
-    block_exscan(a.num_req, [&](int r) { return request_ok(a, r) ? tail_chunks(r) : 0; }, p.tail_ptr, sh);
+        return request_ok(a, r) ? (tail_blocks_of(a, r) + p.chunk_blocks - 1) / p.chunk_blocks : 0;
+    }, p.tail_ptr, sh);
     if (threadIdx.x == 0) {
-        p.totals[0] = min(p.item_ptr[p.num_nodes], p.item_cap);     // node items
-        p.totals[1] = min(p.tail_ptr[a.num_req], p.item_cap - p.totals[0]);   // tail items
+        p.totals[0] = min(p.item_ptr[p.num_nodes], p.item_cap);                  // node items
+        p.totals[1] = min(p.tail_ptr[a.num_req], p.item_cap - p.totals[0]);       // tail items
+        p.totals[2] = min(p.entry_slot[p.num_entries], p.slot_cap);              // node slots; tail slots follow
     }
 }
 
-// Threads [0, num_req): the rows of the node lists (request and first partial slot of every path entry) and
-// the request's tail items.  Threads [num_req, num_req + num_nodes): the node's items.  An item record is
-// (node, index among the node's chunk x column-quad items) or (-(request + 1), tail chunk).
+// Threads [0, E): the rows of the node lists (request and first partial slot of every path entry).
+// Threads [E, E + N): a node's item records.  Threads [E + N, E + N + R): a request's tail item records.
+// An item record is (node, index among the node's chunk x column-quad items) or (-(request + 1), tail chunk).
 __global__ void shared_fill_kernel(SharedPlan p, AttnArgs a) {
-    const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < a.num_req) {
-        const int r = i;
-        if (!request_ok(a, r)) return;
-        for (int e = path_lo(p, r); e < path_hi(p, r); ++e) {
-            const int v = p.path_nodes[e];
-            if (v < 0 || v >= p.num_nodes) continue;
-            const int row = p.node_ptr[v] + atomicAdd(&p.cursor[v], 1);
-            if (row < p.num_entries) {                         // always, unless paths overlap
-                p.row_req[row] = r;
-                p.row_slot[row] = p.entry_slot[e];
-            }
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < p.num_entries) {
+        const int e = i;
+        const int r = request_of_entry(p, a, e);
+        const int v = p.path_nodes[e];
+        if (r < 0 || !request_ok(a, r) || v < 0 || v >= p.num_nodes) return;
+        const int row = p.node_ptr[v] + atomicAdd(&p.cursor[v], 1);
+        if (row < p.num_entries) {                             // always, unless paths overlap
+            p.row_req[row] = r;
+            p.row_slot[row] = p.entry_slot[e];
         }
-        const int base = p.totals[0] + p.tail_ptr[r];
-        for (int j = 0; j < p.tail_ptr[r + 1] - p.tail_ptr[r] && base + j < p.item_cap; ++j)
-            p.item_rec[base + j] = make_int2(-(r + 1), j);
-    } else if (i < a.num_req + p.num_nodes) {
-        const int v = i - a.num_req;
-        const int base = p.item_ptr[v];
+        return;
+    }
+    i -= p.num_entries;
+    if (i < p.num_nodes) {
+        const int v = i, base = p.item_ptr[v];
         for (int j = 0; j < p.item_ptr[v + 1] - base && base + j < p.totals[0]; ++j) p.item_rec[base + j] = make_int2(v, j);
+        return;
+    }
+    i -= p.num_nodes;
+    if (i < a.num_req) {
+        const int r = i, base = p.totals[0] + p.tail_ptr[r];
+        for (int j = 0; j < p.tail_ptr[r + 1] - p.tail_ptr[r] && base + j < p.totals[0] + p.totals[1]; ++j)
+            p.item_rec[base + j] = make_int2(-(r + 1), j);
     }
 }
 
@@ -254,7 +265,7 @@ __global__ __launch_bounds__(kSharedThreads, wgs_per_cu(G)) void shared_attn_ker
             ntk = a.block_ntok + (size_t)r * a.max_blocks;
             e0 = nb - ntail + chunk * p.chunk_blocks;
             e1 = (chunk < tail_chunks && request_ok(a, r)) ? min(nb, e0 + p.chunk_blocks) : e0;
-            slot0 = p.slot_ptr[r + 1] - tail_chunks + chunk;
+            slot0 = p.totals[2] + p.tail_ptr[r] + chunk;
         }
         if (e0 >= e1) continue;                                // workgroup-uniform
         // ---- staging: HBM -> LDS direct loads ----
@@ -501,7 +512,10 @@ __global__ __launch_bounds__(kSharedThreads, wgs_per_cu(G)) void shared_attn_ker
     }
 }
 
-// One wave per (request, query head): combine the request's partial slots.
+// One wave per (request, query head): combine the request's partial slots -- those of its path entries, which
+// are contiguous and in path order, then those of its tail.  The maxima are in log2 units: w_s = 2^(m_s - M),
+// L = sum w_s l_s, O = sum w_s O_s / L, lse = (M + log2 L) ln 2.  Lanes first work slot-parallel (maximum,
+// weights), then each lane owns D/64 output elements and the weights go round by v_readlane.
 template <int D>
 __global__ __launch_bounds__(256) void shared_merge_kernel(AttnArgs a, SharedPlan p, const float *__restrict__ part_o,
                                                            const float *__restrict__ part_ml) {
@@ -509,27 +523,60 @@ __global__ __launch_bounds__(256) void shared_merge_kernel(AttnArgs a, SharedPla
     const long idx = (long)blockIdx.x * 4 + (threadIdx.x >> 6);
     if (idx >= (long)a.num_req * a.hq) return;
     const int r = (int)(idx / a.hq), h = (int)(idx % a.hq);
-    const bool ok = request_ok(a, r);
-    const int s0 = ok ? p.slot_ptr[r] : 0, s1 = ok ? min(p.slot_ptr[r + 1], p.slot_cap) : 0;
+    int s0[2] = {0, 0}, n[2] = {0, 0};                           // the two slot ranges
+    if (request_ok(a, r)) {
+        const int lo = path_lo(p, r), hi = max(path_hi(p, r), lo);
+        s0[0] = min(p.entry_slot[lo], p.slot_cap);
+        n[0] = max(min(p.entry_slot[hi], p.slot_cap) - s0[0], 0);
+        s0[1] = min(p.totals[2] + p.tail_ptr[r], p.slot_cap);
+        n[1] = max(min(p.totals[2] + p.tail_ptr[r + 1], p.slot_cap) - s0[1], 0);
+    }
+    const int ns = n[0] + n[1];
+    auto slot_of = [&](int i) -> int { return i < n[0] ? s0[0] + i : s0[1] + (i - n[0]); };
     __bf16 *out = (__bf16 *)a.o + ((size_t)r * a.hq + h) * D;
     constexpr int PER = D / 64;
     float acc[PER];
 #pragma unroll
     for (int i = 0; i < PER; ++i) acc[i] = 0.f;
     float M = -INFINITY, L = 0.f;
-    for (int s = s0; s < s1; ++s) M = fmaxf(M, part_ml[((size_t)s * a.hq + h) * 2]);
-    for (int s = s0; s < s1; ++s) {
-        const size_t pi = (size_t)s * a.hq + h;
-        const float wgt = fast_exp2(part_ml[pi * 2] - M);
-        L += wgt * part_ml[pi * 2 + 1];
+    for (int base = 0; base < ns; base += 64)
+        if (base + lane < ns) M = fmaxf(M, part_ml[((size_t)slot_of(base + lane) * a.hq + h) * 2]);
 #pragma unroll
-        for (int i = 0; i < PER; ++i) acc[i] += wgt * part_o[pi * D + lane + 64 * i];
+    for (int off = 32; off > 0; off >>= 1) M = fmaxf(M, __shfl_xor(M, off, 64));
+    for (int base = 0; base < ns; base += 64) {
+        float wgt = 0.f;
+        int slot = 0;
+        if (base + lane < ns) {
+            slot = slot_of(base + lane);
+            const size_t pi = (size_t)slot * a.hq + h;
+            wgt = fast_exp2(part_ml[pi * 2] - M);
+            L += wgt * part_ml[pi * 2 + 1];
+        }
+        const int m = min(64, ns - base);
+        for (int j0 = 0; j0 < m; j0 += 4) {                     // four slots' loads in flight together
+            float x[4][PER];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int j = min(j0 + u, m - 1);
+                const size_t pj = (size_t)__builtin_amdgcn_readlane(slot, j) * a.hq + h;
+#pragma unroll
+                for (int i = 0; i < PER; ++i) x[u][i] = part_o[pj * D + lane + 64 * i];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float wj = j0 + u < m ? __int_as_float(__builtin_amdgcn_readlane(__float_as_int(wgt), min(j0 + u, m - 1))) : 0.f;
+#pragma unroll
+                for (int i = 0; i < PER; ++i) acc[i] += wj * x[u][i];
+            }
+        }
     }
-    const float inv = s1 > s0 ? 1.f / L : 0.f;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) L += __shfl_xor(L, off, 64);
+    const float inv = ns > 0 ? 1.f / L : 0.f;
 #pragma unroll
     for (int i = 0; i < PER; ++i) out[lane + 64 * i] = (__bf16)(acc[i] * inv);
     if (a.lse && lane == 0)
-        a.lse[(size_t)r * a.hq + h] = s1 > s0 ? (M + __builtin_log2f(L)) * 0.6931471805599453f : -INFINITY;
+        a.lse[(size_t)r * a.hq + h] = ns > 0 ? (M + __builtin_log2f(L)) * 0.6931471805599453f : -INFINITY;
 }
 
 // ---- host side ---------------------------------------------------------------------------------
@@ -539,7 +586,7 @@ size_t shared_slot_cap(int32_t num_req, int32_t num_entries, int32_t max_blocks,
 }
 
 size_t shared_int_words(int32_t num_nodes, int32_t num_req, int32_t num_entries) {
-    return 4 * ((size_t)num_nodes + 1) + 3 * ((size_t)num_entries + 1) + 2 * ((size_t)num_req + 2) + 8;
+    return 4 * ((size_t)num_nodes + 1) + 3 * ((size_t)num_entries + 1) + ((size_t)num_req + 2) + 8;
 }
 // + one 8-byte item record per partial slot (items <= slots: a node item serves at least one request)
 
@@ -573,11 +620,11 @@ static hipError_t launch_attn(const AttnArgs &a, SharedPlan p, float *part_o, fl
 template <int D, int G>
 static hipError_t launch_shared_t(const AttnArgs &a, int kv_dtype, SharedPlan p, float *part_o, float *part_ml,
                                   hipStream_t s) {
-    const unsigned nz = (unsigned)((p.num_nodes + 255) / 256), nr = (unsigned)((a.num_req + 255) / 256);
+    const unsigned nz = (unsigned)((p.num_nodes + 255) / 256), ne = (unsigned)((p.num_entries + 255) / 256);
     hipLaunchKernelGGL(shared_zero_kernel, dim3(nz ? nz : 1), dim3(256), 0, s, p);
-    hipLaunchKernelGGL(shared_count_kernel, dim3(nr), dim3(256), 0, s, p, a);
+    if (ne) hipLaunchKernelGGL(shared_count_kernel, dim3(ne), dim3(256), 0, s, p, a);
     hipLaunchKernelGGL(shared_scan_kernel, dim3(1), dim3(kScanThreads), 0, s, p, a, G, 64 * col_groups(G));
-    const unsigned nf = (unsigned)(((size_t)a.num_req + p.num_nodes + 255) / 256);
+    const unsigned nf = (unsigned)(((size_t)p.num_entries + p.num_nodes + a.num_req + 255) / 256);
     hipLaunchKernelGGL(shared_fill_kernel, dim3(nf), dim3(256), 0, s, p, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
@@ -611,7 +658,6 @@ hipError_t launch_decode_shared(const AttnArgs &a, int head_dim, int group, int 
     p.entry_slot = w;     w += e1;
     p.row_req = w;        w += e1;
     p.row_slot = w;       w += e1;
-    p.slot_ptr = w;       w += (size_t)a.num_req + 2;
     p.tail_ptr = w;       w += (size_t)a.num_req + 2;
     p.totals = w;         w += 8;
     const size_t slots = shared_slot_cap(a.num_req, num_entries, a.max_blocks, chunk_blocks);
