@@ -172,12 +172,13 @@ __global__ void shared_fill_kernel(SharedPlan p, AttnArgs a) {
 
 // ---- the attention kernel -------------------------------------------------------------------------
 // One workgroup (4 waves) reduces one item: a chunk of one segment's blocks for one kv head and up to
-// 64 * kColGroups score columns.  The chunk's K/V blocks go HBM -> registers -> LDS once per workgroup,
-// two blocks (32 keys) per step, double buffered; every wave reads its MFMA operand fragments from LDS
-// and applies them to its kColGroups groups of 16 columns, so a block read from HBM once serves up to
-// 128 (request, head) columns.  Items are node items (columns = the requests through the node, a
-// quarter-wave of 16 columns = 16/G requests) followed by tail items (a request's own tail blocks, G
-// columns).  Workgroups loop over the item list with the grid as stride.
+// 64 * col_groups(G) score columns.  The chunk's K/V blocks go HBM -> LDS once per workgroup through direct
+// loads, two blocks (32 keys) per step, into a ring of step buffers that keeps the next steps in flight;
+// every wave reads its MFMA operand fragments from LDS and applies them to its groups of 16 columns, so a
+// block read from HBM once serves up to 128 (request, head) columns.  Items are node items (columns = the
+// requests through the node; 16 columns = 16/G requests) followed by tail items (a request's own tail
+// blocks, G columns).  The grid is as large as fits on the device at once, and workgroups loop over the item
+// list with the grid as stride.
 // groups of 16 columns per wave: two when a request brings 8 heads per kv head (its node lists are twice as
 // wide in columns, and a fragment read from LDS then feeds two MFMAs), else one (more workgroups per CU)
 constexpr int col_groups(int G) { return G >= 8 ? 2 : 1; }
@@ -198,6 +199,7 @@ struct StageCfg {
     static constexpr int kBuf = 4 * kBlkB;                      // one step: K of two blocks, V of two blocks
     // step buffers: kRing - 1 steps are in flight per workgroup
     static constexpr int kRing = (kLdsPerWg / kBuf) < 9 ? (kLdsPerWg / kBuf) : 9;
+    static_assert(kRing >= 2 && (kRing - 2) * kLoads < 64, "ring depth: two buffers at least, and a wait count that vmcnt can hold");
 };
 
 // 16-byte-per-lane global -> LDS direct load: lane l fetches the 16 bytes at base + off (uniform base, 32-bit
