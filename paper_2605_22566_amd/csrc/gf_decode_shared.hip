@@ -39,7 +39,7 @@ struct SharedPlan {
     int32_t num_nodes, num_entries;
     // scratch (device, context's)
     int32_t *cnt, *cursor, *node_ptr, *item_ptr, *entry_slot, *row_req, *row_slot, *tail_ptr, *totals;
-    int2 *item_rec;
+    int4 *item_rec;   // two per item, see ItemRec
     int32_t chunk_blocks, item_cap, slot_cap;
 };
 
@@ -139,10 +139,27 @@ __global__ __launch_bounds__(kScanThreads) void shared_scan_kernel(SharedPlan p,
     }
 }
 
+// What the attention kernel needs to know of an item, written once by the fill kernel (8 ints):
+struct ItemRec {
+    int32_t seg;        // node id, or -(request + 1) for a tail item
+    int32_t tab_off;    // first table entry of the chunk: index into node_blocks (node) or block_table (tail)
+    int32_t entries;    // table entries of the chunk (1 .. 64)
+    int32_t tokens;     // tokens in those entries (all blocks full but possibly the last)
+    int32_t row0;       // node: first row of the node's request list
+    int32_t cnt;        // node: requests in that list
+    int32_t quad;       // node: which group of 64 * col_groups columns
+    int32_t slot;       // node: chunk index, added to a row's first slot; tail: the partial slot itself
+};
+static_assert(sizeof(ItemRec) == 2 * sizeof(int4), "item record = two 16-byte words");
+
+__device__ __forceinline__ void store_rec(const SharedPlan &p, int item, const ItemRec &r) {
+    p.item_rec[2 * (size_t)item] = make_int4(r.seg, r.tab_off, r.entries, r.tokens);
+    p.item_rec[2 * (size_t)item + 1] = make_int4(r.row0, r.cnt, r.quad, r.slot);
+}
+
 // Threads [0, E): the rows of the node lists (request and first partial slot of every path entry).
 // Threads [E, E + N): a node's item records.  Threads [E + N, E + N + R): a request's tail item records.
-// An item record is (node, index among the node's chunk x column-quad items) or (-(request + 1), tail chunk).
-__global__ void shared_fill_kernel(SharedPlan p, AttnArgs a) {
+__global__ void shared_fill_kernel(SharedPlan p, AttnArgs a, int group, int item_cols) {
     int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < p.num_entries) {
         const int e = i;
@@ -158,15 +175,44 @@ __global__ void shared_fill_kernel(SharedPlan p, AttnArgs a) {
     }
     i -= p.num_entries;
     if (i < p.num_nodes) {
-        const int v = i, base = p.item_ptr[v];
-        for (int j = 0; j < p.item_ptr[v + 1] - base && base + j < p.totals[0]; ++j) p.item_rec[base + j] = make_int2(v, j);
+        const int v = i, base = p.item_ptr[v], n = p.item_ptr[v + 1] - base;
+        if (n <= 0) return;
+        const int cnt = p.cnt[v], nblk = node_blocks_of(p, v);
+        const int quads = max((cnt * group + item_cols - 1) / item_cols, 1);
+        for (int j = 0; j < n && base + j < p.totals[0]; ++j) {
+            const int chunk = j / quads, e0 = chunk * p.chunk_blocks, e1 = min(nblk, e0 + p.chunk_blocks);
+            ItemRec rec;
+            rec.seg = v;
+            rec.tab_off = p.node_block_ptr[v] + e0;
+            rec.entries = max(e1 - e0, 0);
+            rec.tokens = max(min(p.node_len[v] - kBlock * e0, kBlock * (e1 - e0)), 0);
+            rec.row0 = p.node_ptr[v];
+            rec.cnt = cnt;
+            rec.quad = j % quads;
+            rec.slot = chunk;
+            store_rec(p, base + j, rec);
+        }
         return;
     }
     i -= p.num_nodes;
     if (i < a.num_req) {
-        const int r = i, base = p.totals[0] + p.tail_ptr[r];
-        for (int j = 0; j < p.tail_ptr[r + 1] - p.tail_ptr[r] && base + j < p.totals[0] + p.totals[1]; ++j)
-            p.item_rec[base + j] = make_int2(-(r + 1), j);
+        const int r = i, base = p.totals[0] + p.tail_ptr[r], n = p.tail_ptr[r + 1] - p.tail_ptr[r];
+        if (n <= 0) return;
+        const int nb = max(min(a.num_blocks[r], a.max_blocks), 0), ntail = tail_blocks_of(a, r);
+        const int n_new = max(a.seq_lens[r] - a.ctx_lens[r], 0);
+        for (int j = 0; j < n && base + j < p.totals[0] + p.totals[1]; ++j) {
+            const int e0 = nb - ntail + j * p.chunk_blocks, e1 = min(nb, e0 + p.chunk_blocks);
+            ItemRec rec;
+            rec.seg = -(r + 1);
+            rec.tab_off = r * a.max_blocks + e0;
+            rec.entries = max(e1 - e0, 0);
+            rec.tokens = max(min(n_new - kBlock * j * p.chunk_blocks, kBlock * (e1 - e0)), 0);
+            rec.row0 = 0;
+            rec.cnt = 0;
+            rec.quad = 0;
+            rec.slot = p.totals[2] + p.tail_ptr[r] + j;
+            store_rec(p, base + j, rec);
+        }
     }
 }
 
@@ -195,11 +241,12 @@ struct StageCfg {
     static constexpr int kCPR = kRowB / 16;                     // 16-byte chunks per K row: 16, 8 or 4
     static constexpr int kBlkB = kBlock * D * ES;               // one (block, kv head) image of K or of V
     static constexpr int kLoads = kBlkB / 1024;                 // wave-wide direct loads per image
-    static constexpr int kVOff = 2 * kBlkB;
-    static constexpr int kBuf = 4 * kBlkB;                      // one step: K of two blocks, V of two blocks
-    // step buffers: kRing - 1 steps are in flight per workgroup
-    static constexpr int kRing = (kLdsPerWg / kBuf) < 9 ? (kLdsPerWg / kBuf) : 9;
-    static_assert(kRing >= 2 && (kRing - 2) * kLoads < 64, "ring depth: two buffers at least, and a wait count that vmcnt can hold");
+    static constexpr int kPair = 2 * kBlkB;                     // the K (or V) images of one step: two blocks
+    // a ring of step buffers (K pair + V pair each): kRing - 1 steps are in flight per workgroup
+    static constexpr int kRing = (kLdsPerWg / (2 * kPair)) < 9 ? (kLdsPerWg / (2 * kPair)) : 9;
+    static constexpr int kVBase = kRing * kPair;                // K pairs first, then V pairs
+    static constexpr int kLds = 2 * kRing * kPair;
+    static_assert(kRing >= 2 && (kRing - 1) * kLoads < 64, "ring depth: two buffers at least, and wait counts that vmcnt can hold");
 };
 
 // 16-byte-per-lane global -> LDS direct load: lane l fetches the 16 bytes at base + off (uniform base, 32-bit
@@ -222,7 +269,7 @@ __global__ __launch_bounds__(kSharedThreads, wgs_per_cu(G)) void shared_attn_ker
                                                                       float *__restrict__ part_ml) {
     constexpr int kColGroups = col_groups(G);
     using C = StageCfg<D, FP8, wgs_per_cu(G)>;
-    __shared__ __attribute__((aligned(1024))) char lds[C::kRing * C::kBuf];
+    __shared__ __attribute__((aligned(1024))) char lds[C::kLds];
     const int tid = threadIdx.x;
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -235,129 +282,137 @@ __global__ __launch_bounds__(kSharedThreads, wgs_per_cu(G)) void shared_attn_ker
     const float c = a.scale_log2;
     const float slack = 8.f / c;                               // 2^8 in the exponent, in score units (inf for a zero scale)
 
-    for (long w = first; w < total_w; w += grid) {
-        // ---- which item (workgroup-uniform) ----
-        const int2 rec = p.item_rec[w / a.hkv];
-        const int kvh = (int)(w % a.hkv);
-        const int32_t *tab, *ntk;
-        int seg_len = 0, e0, e1, chunk, slot0 = 0;
-        int v = -1, cnt = 0, quad = 0, groups = 0, row0 = 0;   // node items
-        int r_tail = -1;                                       // tail items
-        if (rec.x >= 0) {
-            v = rec.x;
-            cnt = p.cnt[v];
-            groups = (cnt * G + 15) / 16;
-            const int quads = max((groups + 4 * kColGroups - 1) / (4 * kColGroups), 1);
-            quad = rec.y % quads;
-            chunk = rec.y / quads;
-            row0 = p.node_ptr[v];
-            seg_len = p.node_len[v];
-            tab = p.node_blocks + p.node_block_ptr[v];
-            ntk = nullptr;
-            e0 = chunk * p.chunk_blocks;
-            e1 = min(node_blocks_of(p, v), e0 + p.chunk_blocks);
-        } else {
-            const int r = -rec.x - 1;
-            r_tail = r;
-            chunk = rec.y;
-            const int nb = max(min(a.num_blocks[r], a.max_blocks), 0);
-            const int ntail = tail_blocks_of(a, r);
-            const int tail_chunks = (ntail + p.chunk_blocks - 1) / p.chunk_blocks;
-            tab = a.block_table + (size_t)r * a.max_blocks;
-            ntk = a.block_ntok + (size_t)r * a.max_blocks;
-            e0 = nb - ntail + chunk * p.chunk_blocks;
-            e1 = (chunk < tail_chunks && request_ok(a, r)) ? min(nb, e0 + p.chunk_blocks) : e0;
-            slot0 = p.totals[2] + p.tail_ptr[r] + chunk;
-        }
-        if (e0 >= e1) continue;                                // workgroup-uniform
-        // ---- staging: HBM -> LDS direct loads ----
-        // the chunk's table entries (at most kMaxChunk = 64) live in lane registers, lane j = entry e0 + j: block id
-        // (clamped into the pool), token count and, for an e4m3 pool, the block's two scales.  The step loop
-        // reads them with v_readlane and touches memory only through the K/V requests and LDS.
-        int lane_blk = 0, lane_ntok = 0;
-        float lane_ks = 1.f, lane_vs = 1.f;
-        if (e0 + lane < e1) {
-            lane_blk = min(max(tab[e0 + lane], 0), a.pool_blocks - 1);
-            lane_ntok = ntk ? ntk[e0 + lane] : min(kBlock, seg_len - kBlock * (e0 + lane));
-            if constexpr (FP8) {
-                lane_ks = a.k_scale[lane_blk];
-                lane_vs = a.v_scale[lane_blk];
-            }
-        }
-        // Wave w brings in one of the four images of a step: K of block w & 1 (w < 2) or V of block w & 1.
-        // Lane l of load i fills LDS chunk q = 64 i + l of the image and picks its source so that the image is
-        // XOR-swizzled: K row (q / CPR) holds chunk c at position c ^ k_swz(block, row); the two halves of a
-        // bf16 V row swap on every other group of 8 rows.  Every 16-lane group of an operand fetch then hits
-        // 16 different 16-byte bank groups.
-        auto k_swz = [](int blk, int slot) -> int {
-            const int bits = (slot & 3) | (((slot >> 3) & 1) << 2) | (blk << 3);     // the 16 rows a tile reads
-            return C::kCPR == 16 ? bits : C::kCPR == 8 ? bits >> 1 : bits >> 2;
-        };
-        uint32_t src_off[C::kLoads];
+    // ---- per-kernel constants of the staging and of the operand fetches ----
+    // Wave w brings in one of the four images of a step: K of block w & 1 (w < 2) or V of block w & 1.
+    // Lane l of load i fills LDS chunk q = 64 i + l of the image and picks its source so that the image is
+    // XOR-swizzled: K row (q / CPR) holds chunk c at position c ^ k_swz(block, row); the two halves of a
+    // bf16 V row swap on every other group of 8 rows.  Every 16-lane group of an operand fetch then hits
+    // 16 different 16-byte bank groups.
+    auto k_swz = [](int blk, int slot) -> int {
+        const int bits = (slot & 3) | (((slot >> 3) & 1) << 2) | (blk << 3);     // the 16 rows a tile reads
+        return C::kCPR == 16 ? bits : C::kCPR == 8 ? bits >> 1 : bits >> 2;
+    };
+    uint32_t src_off[C::kLoads];
 #pragma unroll
-        for (int i = 0; i < C::kLoads; ++i) {
-            const int q = 64 * i + lane;
-            if (wave < 2) {
-                const int row = q / C::kCPR, pos = q % C::kCPR;
-                src_off[i] = row * C::kRowB + ((pos ^ k_swz(wave & 1, row)) * 16);
-            } else if constexpr (FP8) {
-                src_off[i] = q * 16;
-            } else {
-                const int d = q >> 1;
-                src_off[i] = d * 32 + (((q & 1) ^ ((d >> 3) & 1)) * 16);
+    for (int i = 0; i < C::kLoads; ++i) {
+        const int q = 64 * i + lane;
+        if (wave < 2) {
+            const int row = q / C::kCPR, pos = q % C::kCPR;
+            src_off[i] = row * C::kRowB + ((pos ^ k_swz(wave & 1, row)) * 16);
+        } else if constexpr (FP8) {
+            src_off[i] = q * 16;
+        } else {
+            const int d = q >> 1;
+            src_off[i] = d * 32 + (((q & 1) ^ ((d >> 3) & 1)) * 16);
+        }
+    }
+    // operand fragments out of LDS (same geometry as the per-request kernel reads from HBM)
+    const int k_slot = 8 * ((n16 >> 2) & 1) + (n16 & 3);
+    const int k_row = (n16 >= 8 ? C::kBlkB : 0) + k_slot * C::kRowB;
+    const int k_x = (q4 ^ k_swz(n16 >= 8 ? 1 : 0, k_slot)) * 16;                // chunk (4 t + q4) sits at k_x ^ 64 t
+    const int v_frag = (q4 >= 2 ? C::kBlkB : 0) +
+                       (FP8 ? n16 * 16 + (q4 & 1) * 8 : n16 * 32 + (((q4 & 1) ^ ((n16 >> 3) & 1)) * 16));
+
+    // ---- items, two in flight: while item i is reduced, the per-lane data of item i + 1 is on its way ----
+    // Per-lane data of an item.  The chunk's table entries (at most kMaxChunk = 64) live in lane registers,
+    // lane j = entry j of the chunk: block id (clamped into the pool), token count and, for an e4m3 pool, the
+    // block's two scales; the step loop reads them with v_readlane and touches memory only through the K/V
+    // requests and LDS.  The columns of this wave: (request, query head, partial slot) per lane.
+    struct LaneData {
+        int blk, ntok;
+        float ks, vs;
+        int col_req[kColGroups], col_head[kColGroups], col_slot[kColGroups];
+        int my_groups;                                         // groups of this wave that hold columns
+    };
+    auto load_rec = [&](long w) -> ItemRec {
+        ItemRec r;
+        if (w < total_w) {
+            const int4 x = p.item_rec[2 * (w / a.hkv)], y = p.item_rec[2 * (w / a.hkv) + 1];
+            r.seg = x.x; r.tab_off = x.y; r.entries = min(x.z, kMaxChunk); r.tokens = x.w;
+            r.row0 = y.x; r.cnt = y.y; r.quad = y.z; r.slot = y.w;
+        } else {
+            r.seg = 0; r.tab_off = 0; r.entries = 0; r.tokens = 0; r.row0 = 0; r.cnt = 0; r.quad = 0; r.slot = 0;
+        }
+        return r;
+    };
+    auto load_lane = [&](const ItemRec &rec) -> LaneData {
+        LaneData d;
+        d.blk = 0;
+        d.ks = d.vs = 1.f;
+        d.ntok = min(max(rec.tokens - kBlock * lane, 0), kBlock);
+        if (lane < rec.entries) {
+            const int32_t *tab = rec.seg >= 0 ? p.node_blocks : a.block_table;
+            d.blk = min(max(tab[(size_t)rec.tab_off + lane], 0), a.pool_blocks - 1);
+            if constexpr (FP8) {
+                d.ks = a.k_scale[d.blk];
+                d.vs = a.v_scale[d.blk];
             }
         }
-        const int nsteps = (e1 - e0 + 1) / 2;
-        auto issue = [&](int step, int buf) {
+        const int groups = (rec.cnt * G + 15) / 16;
+        d.my_groups = 0;
+#pragma unroll
+        for (int g = 0; g < kColGroups; ++g) {
+            d.col_req[g] = -1;
+            d.col_head[g] = n16 % G;
+            d.col_slot[g] = 0;
+            if (rec.seg >= 0) {
+                const int cg = rec.quad * 4 * kColGroups + g * 4 + wave;   // groups dealt to the waves round robin
+                if (cg < groups) d.my_groups = g + 1;
+                const int col = cg * 16 + n16;
+                const int row = col / G;
+                d.col_head[g] = col % G;
+                if (row < rec.cnt && rec.row0 + row < p.num_entries) {
+                    d.col_req[g] = p.row_req[rec.row0 + row];
+                    d.col_slot[g] = p.row_slot[rec.row0 + row] + rec.slot;
+                }
+            } else if (g == 0 && wave == 0) {
+                d.my_groups = 1;
+                if (n16 < G) {
+                    d.col_req[g] = -rec.seg - 1;
+                    d.col_slot[g] = rec.slot;
+                }
+            }
+            if (d.col_slot[g] < 0 || d.col_slot[g] >= p.slot_cap) d.col_req[g] = -1;   // only with tables that break the resolve contract
+        }
+        return d;
+    };
+
+    ItemRec rec = load_rec(first);
+    LaneData cur = load_lane(rec);
+    ItemRec rec_next = load_rec((long)first + grid);
+    for (long w = first; w < total_w; w += grid) {
+        const int kvh = (int)(w % a.hkv);
+        const int entries = rec.entries;
+        const int nsteps = (entries + 1) / 2;
+        const int lane_blk = cur.blk, lane_ntok = cur.ntok;
+        const float lane_ks = cur.ks, lane_vs = cur.vs;
+        int col_req[kColGroups], col_head[kColGroups], col_slot[kColGroups];
+#pragma unroll
+        for (int g = 0; g < kColGroups; ++g) {
+            col_req[g] = cur.col_req[g];
+            col_head[g] = cur.col_head[g];
+            col_slot[g] = cur.col_slot[g];
+        }
+        const int my_groups = __builtin_amdgcn_readfirstlane(cur.my_groups);
+
+        // ---- staging: HBM -> LDS direct loads ----
+        // wave w < 2 requests the K image of block w & 1 of a step, wave w >= 2 the V image; `slot` is the
+        // buffer of the wave's own ring
+        auto issue = [&](int step, int slot) {
             const int j = 2 * step + (wave & 1);
-            const int b = __builtin_amdgcn_readlane(lane_blk, e0 + j < e1 ? j : 2 * step);   // odd tail: block 0 again
+            const int b = __builtin_amdgcn_readlane(lane_blk, j < entries ? j : 2 * step);   // odd tail: block 0 again
             const uintptr_t addr = (uintptr_t)(wave < 2 ? a.k : a.v) + ((size_t)b * a.hkv + kvh) * C::kBlkB;
             // wave-uniform by construction; said explicitly so that the address lives in scalar registers
             const char *src = (const char *)(((uintptr_t)(uint32_t)__builtin_amdgcn_readfirstlane((int)(addr >> 32)) << 32) |
                                              (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)addr));
-            char *dst = lds + buf * C::kBuf + wave * C::kBlkB;
+            char *dst = lds + (wave < 2 ? 0 : C::kVBase) + slot * C::kPair + (wave & 1) * C::kBlkB;
 #pragma unroll
             for (int i = 0; i < C::kLoads; ++i) dma_load(src, src_off[i], dst + 1024 * i);
         };
-        // operand fragments out of LDS (same geometry as the per-request kernel reads from HBM)
-        const int k_slot = 8 * ((n16 >> 2) & 1) + (n16 & 3);
-        const int k_row = (n16 >= 8 ? C::kBlkB : 0) + k_slot * C::kRowB;
-        const int k_x = (q4 ^ k_swz(n16 >= 8 ? 1 : 0, k_slot)) * 16;            // chunk (4 t + q4) sits at k_x ^ 64 t
-        const int v_frag = C::kVOff + (q4 >= 2 ? C::kBlkB : 0) +
-                           (FP8 ? n16 * 16 + (q4 & 1) * 8 : n16 * 32 + (((q4 & 1) ^ ((n16 >> 3) & 1)) * 16));
-
+        constexpr int my_ring = C::kRing;
 #pragma unroll
         for (int j = 0; j < C::kRing - 1; ++j)
-            if (j < nsteps) issue(j, j);
-        // ---- the columns of this wave: (request, query head, partial slot) per lane ----
-        int col_req[kColGroups], col_head[kColGroups], col_slot[kColGroups];
-        int my_groups = 0;                                     // groups of this wave that hold columns
-#pragma unroll
-        for (int g = 0; g < kColGroups; ++g) {
-            col_req[g] = -1;
-            col_head[g] = n16 % G;
-            col_slot[g] = 0;
-            if (v >= 0) {
-                const int cg = quad * 4 * kColGroups + g * 4 + wave;   // groups dealt to the waves round robin
-                if (cg < groups) my_groups = g + 1;
-                const int col = cg * 16 + n16;
-                const int row = col / G;
-                col_head[g] = col % G;
-                if (row < cnt && row0 + row < p.num_entries) {
-                    col_req[g] = p.row_req[row0 + row];
-                    col_slot[g] = p.row_slot[row0 + row] + chunk;
-                }
-            } else if (g == 0 && wave == 0) {
-                my_groups = 1;
-                if (n16 < G) {
-                    col_req[g] = r_tail;
-                    col_slot[g] = slot0;
-                }
-            }
-            if (col_slot[g] < 0 || col_slot[g] >= p.slot_cap) col_req[g] = -1;   // only with tables that break the resolve contract
-        }
-        my_groups = __builtin_amdgcn_readfirstlane(my_groups);
-
+            if (j < nsteps && j < my_ring - 1) issue(j, j);
         // ---- Q^T operands of this wave's columns ----
         bf16x8 qf[kColGroups][D / 32];
 #pragma unroll
@@ -383,15 +438,17 @@ __global__ __launch_bounds__(kSharedThreads, wgs_per_cu(G)) void shared_attn_ker
 
         // Everything this item loaded through the compiler (table entries, Q) is waited for here, once: a wait
         // the compiler placed at the first use inside the loop would be a vmcnt(0) in every step and drain the ring.
-        __builtin_amdgcn_s_waitcnt(0x0F70);                    // vmcnt(0), other counters untouched
-        int buf = 0;
+        __builtin_amdgcn_s_waitcnt(0x0070);                    // vmcnt(0) lgkmcnt(0)
+        int slot = 0;
         for (int step = 0; step < nsteps; ++step) {
-            // this wave's image of `step` has landed when at most the younger requests are outstanding
+            // this wave's image of `step` has landed when at most its younger requests are outstanding
             if (step + C::kRing - 2 < nsteps) dma_wait<(C::kRing - 2) * C::kLoads>();
             else dma_wait<0>();
             __syncthreads();           // all four images of `step` are in LDS; everybody is done with step - 1
-            if (step + C::kRing - 1 < nsteps) issue(step + C::kRing - 1, buf == 0 ? C::kRing - 1 : buf - 1);
-            const bool two = e0 + 2 * step + 1 < e1;
+            if (step + my_ring - 1 < nsteps) {
+                issue(step + my_ring - 1, slot == 0 ? my_ring - 1 : slot - 1);
+            }
+            const bool two = 2 * step + 1 < entries;
             const int n0 = __builtin_amdgcn_readlane(lane_ntok, 2 * step);
             const int n1 = two ? __builtin_amdgcn_readlane(lane_ntok, 2 * step + 1) : 0;
             float ks = 1.f, vs = 1.f;
@@ -400,7 +457,9 @@ __global__ __launch_bounds__(kSharedThreads, wgs_per_cu(G)) void shared_attn_ker
                 ks = __shfl(lane_ks, jj, 64);
                 vs = __shfl(lane_vs, jj, 64);
             }
-            const char *base = lds + buf * C::kBuf;
+            const char *base = lds + slot * C::kPair;
+            const char *vbase = lds + C::kVBase + slot * C::kPair;
+            bf16x8 pb[kColGroups];
             if (my_groups > 0) {
                 f32x4 sT[kColGroups][2];
 #pragma unroll
@@ -432,7 +491,6 @@ __global__ __launch_bounds__(kSharedThreads, wgs_per_cu(G)) void shared_attn_ker
                         }
                     }
                 }
-                bf16x8 pb[kColGroups];
 #pragma unroll
                 for (int g = 0; g < kColGroups; ++g) {
                     pb[g] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
@@ -482,8 +540,8 @@ __global__ __launch_bounds__(kSharedThreads, wgs_per_cu(G)) void shared_attn_ker
 #pragma unroll
                 for (int dt = 0; dt < D / 16; ++dt) {
                     bf16x8 vf;
-                    if constexpr (FP8) vf = fp8x8_to_bf16x8(*(const u32x2 *)(base + v_frag + dt * 256));
-                    else vf = __builtin_bit_cast(bf16x8, *(const u32x4 *)(base + v_frag + dt * 512));
+                    if constexpr (FP8) vf = fp8x8_to_bf16x8(*(const u32x2 *)(vbase + v_frag + dt * 256));
+                    else vf = __builtin_bit_cast(bf16x8, *(const u32x4 *)(vbase + v_frag + dt * 512));
 #pragma unroll
                     for (int g = 0; g < kColGroups; ++g)
                         if (g < my_groups) {
@@ -491,9 +549,14 @@ __global__ __launch_bounds__(kSharedThreads, wgs_per_cu(G)) void shared_attn_ker
                         }
                 }
             }
-            buf = buf + 1 == C::kRing ? 0 : buf + 1;
+            slot = slot + 1 == C::kRing ? 0 : slot + 1;
         }
         __syncthreads();               // the ring is free again before the next item writes into it
+
+        // the next item's per-lane data is requested now, ahead of this item's stores (which use the copies
+        // taken above), straight into the registers the next round reads; its successor's record follows
+        cur = load_lane(rec_next);
+        const ItemRec rec_after = load_rec(w + 2 * (long)grid);
 
         // ---- partials of this wave's columns ----
 #pragma unroll
@@ -501,7 +564,7 @@ __global__ __launch_bounds__(kSharedThreads, wgs_per_cu(G)) void shared_attn_ker
             float l = l_run[g];
             l += __shfl_xor(l, 16, 64);
             l += __shfl_xor(l, 32, 64);
-            if (g < my_groups && col_req[g] >= 0) {
+            if (g < my_groups && col_req[g] >= 0 && nsteps > 0) {
                 const size_t pi = (size_t)col_slot[g] * a.hq + kvh * G + col_head[g];
                 if (q4 == 0) {
                     part_ml[pi * 2 + 0] = m_run[g] * c;   // max in log2 units
@@ -511,6 +574,8 @@ __global__ __launch_bounds__(kSharedThreads, wgs_per_cu(G)) void shared_attn_ker
                 for (int dt = 0; dt < D / 16; ++dt) *(f32x4 *)(part_o + pi * D + 16 * dt + 4 * q4) = oacc[g][dt];
             }
         }
+        rec = rec_next;
+        rec_next = rec_after;
     }
 }
 
@@ -590,12 +655,12 @@ size_t shared_slot_cap(int32_t num_req, int32_t num_entries, int32_t max_blocks,
 size_t shared_int_words(int32_t num_nodes, int32_t num_req, int32_t num_entries) {
     return 4 * ((size_t)num_nodes + 1) + 3 * ((size_t)num_entries + 1) + ((size_t)num_req + 2) + 8;
 }
-// + one 8-byte item record per partial slot (items <= slots: a node item serves at least one request)
+// + one 32-byte item record per partial slot (items <= slots: a node item serves at least one request)
 
 size_t shared_workspace_bytes(int32_t num_nodes, int32_t num_req, int32_t num_entries, int32_t max_blocks,
                               int32_t chunk_blocks, int32_t hq, int32_t head_dim) {
     const size_t slots = shared_slot_cap(num_req, num_entries, max_blocks, chunk_blocks);
-    return shared_int_words(num_nodes, num_req, num_entries) * sizeof(int32_t) + 8 + slots * sizeof(int2) + 256 +
+    return shared_int_words(num_nodes, num_req, num_entries) * sizeof(int32_t) + 16 + slots * sizeof(ItemRec) + 256 +
            slots * hq * ((size_t)head_dim + 2) * sizeof(float);
 }
 
@@ -627,7 +692,7 @@ static hipError_t launch_shared_t(const AttnArgs &a, int kv_dtype, SharedPlan p,
     if (ne) hipLaunchKernelGGL(shared_count_kernel, dim3(ne), dim3(256), 0, s, p, a);
     hipLaunchKernelGGL(shared_scan_kernel, dim3(1), dim3(kScanThreads), 0, s, p, a, G, 64 * col_groups(G));
     const unsigned nf = (unsigned)(((size_t)p.num_entries + p.num_nodes + a.num_req + 255) / 256);
-    hipLaunchKernelGGL(shared_fill_kernel, dim3(nf), dim3(256), 0, s, p, a);
+    hipLaunchKernelGGL(shared_fill_kernel, dim3(nf), dim3(256), 0, s, p, a, G, 64 * col_groups(G));
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     e = kv_dtype == GF_FP8_E4M3 ? launch_attn<D, G, true>(a, p, part_o, part_ml, s)
@@ -666,10 +731,11 @@ hipError_t launch_decode_shared(const AttnArgs &a, int head_dim, int group, int 
     // node items: sum over (request, path entry) of chunks * column groups <= the slot bound (a column group
     // holds at least one request)
     if (slots > 0x7fffffffu / (size_t)(a.hkv > 0 ? a.hkv : 1)) return hipErrorInvalidValue;
+    if ((size_t)a.num_req * (size_t)a.max_blocks > 0x7fffffffu) return hipErrorInvalidValue;   // table offsets are int32
     p.item_cap = (int32_t)slots;
     p.slot_cap = (int32_t)slots;
-    p.item_rec = (int2 *)(((uintptr_t)w + 7) & ~(uintptr_t)7);
-    float *part_o = (float *)(((uintptr_t)(p.item_rec + slots) + 255) & ~(uintptr_t)255);
+    p.item_rec = (int4 *)(((uintptr_t)w + 15) & ~(uintptr_t)15);
+    float *part_o = (float *)(((uintptr_t)(p.item_rec + 2 * slots) + 255) & ~(uintptr_t)255);
     float *part_ml = part_o + slots * a.hq * (size_t)head_dim;
 #define GF_CASE(DD, GG) \
     if (head_dim == DD && group == GG) return launch_shared_t<DD, GG>(a, kv_dtype, p, part_o, part_ml, s);
