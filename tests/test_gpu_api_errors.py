@@ -1,0 +1,96 @@
+"""Argument checking of the C ABI: every malformed call is turned into an error code on the host,
+before anything is launched; empty batches are accepted by every entry point."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_22566_amd import binding as B
+from paper_2605_22566_amd import runner as R
+from paper_2605_22566_amd import workload as W
+from tests.gpu_common import run_resolve
+
+pytestmark = pytest.mark.gpu
+
+
+def _setup(shape=W.Shape(8, 2, 128)):
+    wl = W.small_layered(5, shape, num_req=3)
+    sess, tables = run_resolve(wl)
+    t = W.make_tensors(wl)
+    pool = R.DevicePool.from_host(t, sess.device)
+    qd = torch.zeros((wl.batch.num_req, shape.num_q_heads, shape.head_dim), dtype=torch.bfloat16, device=sess.device)
+    return wl, sess, tables, pool, qd
+
+
+def _code(fn):
+    with pytest.raises(B.GraphFlowError) as e:
+        fn()
+    return e.value.code
+
+
+def test_unsupported_shapes_and_bad_sizes_are_rejected():
+    wl, sess, tables, pool, qd = _setup()
+    od = torch.zeros_like(qd)
+    params, dpool, dt = sess._common(pool, tables, 0.0)
+    graph = B.make_graph(wl.graph.num_nodes, sess.node_len, sess.node_block_ptr, sess.node_blocks)
+    db = sess.upload_batch(wl.batch)
+    calls = {
+        "decode": lambda p: B.gf_attn_decode(sess.ctx, p, dpool, dt, qd, od),
+        "decode_shared": lambda p: B.gf_attn_decode_shared(sess.ctx, p, dpool, graph, db["path_ptr"], db["path_nodes"],
+                                                           db["num_path_entries"], dt, qd, od),
+    }
+    for name, call in calls.items():
+        assert _code(lambda: call(B.make_params(8, 2, 96))) == B.GF_ERR_UNSUPPORTED, name          # head_dim
+        assert _code(lambda: call(B.make_params(6, 2, 128))) == B.GF_ERR_UNSUPPORTED, name         # group of 3
+        assert _code(lambda: call(B.make_params(8, 3, 128))) == B.GF_ERR_BAD_SHAPE, name           # Hq % Hkv
+        assert _code(lambda: call(B.make_params(8, 2, 128, block_size=32))) == B.GF_ERR_UNSUPPORTED, name
+        assert _code(lambda: call(B.make_params(8, 2, 128, kv_dtype=7))) == B.GF_ERR_UNSUPPORTED, name
+        assert _code(lambda: call(B.make_params(8, 2, 128, sm_scale=-1.0))) == B.GF_ERR_BAD_SHAPE, name
+        # an e4m3 pool without scales
+        assert _code(lambda: call(B.make_params(8, 2, 128, kv_dtype=B.GF_FP8_E4M3))) == B.GF_ERR_NULL, name
+    assert _code(lambda: B.gf_attn_decode_shared(sess.ctx, params, dpool, graph, db["path_ptr"], db["path_nodes"], -1,
+                                                 dt, qd, od)) == B.GF_ERR_BAD_SHAPE
+    assert _code(lambda: B.gf_attn_decode_shared(sess.ctx, params, dpool, graph, None, db["path_nodes"],
+                                                 db["num_path_entries"], dt, qd, od)) == B.GF_ERR_NULL
+    assert _code(lambda: B.gf_attn_decode(sess.ctx, params, dpool, dt, None, od)) == B.GF_ERR_NULL
+    assert _code(lambda: B.gf_set_decode_chunk_blocks(sess.ctx, 3)) == B.GF_ERR_BAD_SHAPE            # odd
+    assert _code(lambda: B.gf_attn_prefill(sess.ctx, params, dpool, dt, qd, None, 5, 9, od)) == B.GF_ERR_BAD_SHAPE
+    # residual: bf16 pools only
+    fp8 = B.make_params(8, 2, 128, kv_dtype=B.GF_FP8_E4M3)
+    z = torch.zeros(4, dtype=torch.int32, device=sess.device)
+    z16 = torch.zeros(4, dtype=torch.int16, device=sess.device)
+    assert _code(lambda: B.gf_kv_apply_residual(sess.ctx, fp8, pool.k, pool.v, pool.num_blocks, 1, z, z, z, z16, z16)) \
+        == B.GF_ERR_UNSUPPORTED
+    assert _code(lambda: B.gf_kv_apply_residual(sess.ctx, params, pool.k, pool.v, pool.num_blocks, -1, z, z, z, z16,
+                                                z16)) == B.GF_ERR_BAD_SHAPE
+
+
+def test_empty_batches_are_accepted_everywhere():
+    wl, sess, tables, pool, qd = _setup()
+    params, dpool, _ = sess._common(pool, tables, 0.0)
+    empty = B.make_tables(None, None, None, None, None, None, 0, 0)
+    graph = B.make_graph(wl.graph.num_nodes, sess.node_len, sess.node_block_ptr, sess.node_blocks)
+    B.gf_attn_decode(sess.ctx, params, dpool, empty, None, None)
+    B.gf_attn_decode_shared(sess.ctx, params, dpool, graph, None, None, 0, empty, None, None)
+    B.gf_attn_prefill(sess.ctx, params, dpool, empty, None, None, 0, 0, None)
+    B.gf_kv_append(sess.ctx, params, pool.k, pool.v, None, None, pool.num_blocks, empty, None, None, None, 0, 0)
+    B.gf_kv_apply_residual(sess.ctx, params, pool.k, pool.v, pool.num_blocks, 0, None, None, None, None, None)
+    B.gf_resolve_path(sess.ctx, graph, 0, None, None, None, None, None, 0, pool.num_blocks, None, None, None, None,
+                      None, None)
+    torch.cuda.synchronize()
+
+
+def test_status_free_tables_and_no_lse():
+    """status may be NULL (all requests taken as valid) and lse may be NULL, for both decode paths."""
+    wl, sess, tables, pool, qd = _setup()
+    t = W.make_tensors(wl)
+    last = (t.q_ptr[1:] - 1).astype(np.int64)
+    q = R.bits_to_device(np.ascontiguousarray(t.q[last]), sess.device)
+    no_status = dict(tables)
+    no_status["status"] = None
+    o1, o2, o3 = torch.zeros_like(q), torch.zeros_like(q), torch.zeros_like(q)
+    sess.decode(pool, tables, q, o1)
+    sess.decode(pool, no_status, q, o2)
+    sess.decode_shared(pool, sess.upload_batch(wl.batch), no_status, q, o3)
+    torch.cuda.synchronize()
+    assert torch.equal(o1, o2)
+    assert (o1.float() - o3.float()).abs().max().item() <= 2.0 ** -7 * max(1.0, o1.float().abs().max().item())
