@@ -214,7 +214,7 @@ def decode_shared_entry(job, m):
     """Figures of gf_attn_decode_shared beside gf_attn_decode on the same decode step."""
     alg = job.decode_shared_bytes()
     sec = m["decode_shared_ms"] * 1e-3
-    return {"kernel": "shared_node_kernel(+list building, tails, merge)", "kernel_ms": m["decode_shared_ms"],
+    return {"kernel": "shared_attn_kernel(+list building, merge)", "kernel_ms": m["decode_shared_ms"],
             "speedup_over_decode": m["decode_ms"] / m["decode_shared_ms"],
             "max_abs_diff_to_decode": m["decode_shared_max_abs_diff"],
             # the per-request kernel's bytes over this call's time: what the sharing is worth, not an HBM rate
