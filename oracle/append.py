@@ -24,11 +24,28 @@ Readings: the paper does not describe the write path at all; the layout is the p
 with, and a call always writes a request's whole tail (growing a partly filled e4m3
 block would need its old codes re-quantised under a new scale -- not covered).
 
+Decode-step form, append_token(): only a request's newest token (index n-1 of its new
+tokens, the one seq_lens already counts) is written, into the last table entry's block at
+slot s = (n-1) % 16.  With s == 0 the block is fresh: it is zeroed and, for e4m3, gets the
+scale amax/448 of the token (1.0 if zero).  With s > 0 (e4m3) the block grows in place:
+      need = amax(token) / 448                    old = scale[block]
+      need <= old : the token is quantised with the old scale, nothing else changes
+      need >  old : scale[block] = need, and every code c in slots [0, s) is re-quantised,
+                    c' = e4m3( clamp( (decode(c) * old) / need ) ), fp32 product, fp32
+                    division, round to nearest even; the token is quantised with `need`
+(per tensor, K and V on their own).  Reading: the paper says nothing about growing a
+quantised block; this rule keeps one scale per block and tensor and pays one extra
+rounding of the older codes each time the scale has to grow.
+
 Pins (tests/test_oracle_append.py): e4m3 rounding against torch's float8_e4m3fn cast
 on random values and on every midpoint between neighbouring codes; append followed
 by the attention oracle's table walk returns the new tokens' K/V exactly (bf16) or
 within half a code step (e4m3), token by token; block scale and codes against torch's
 cast of the same block; pad slots zero; untouched blocks untouched; skipped requests.
+append_token: bf16 token by token equals the whole-tail append bit for bit; the table walk
+reads the token back; e4m3 without growth leaves scale and older codes alone and codes the
+token like torch's cast; e4m3 growth sets amax/448 and re-codes like torch's casts of the
+same products, within half a code step of the new grid; a fresh block is zero elsewhere.
 """
 import numpy as np
 
@@ -97,4 +114,57 @@ def append(k_pool, v_pool, k_scale, v_scale, tables, k_new_bits, v_new_bits, q_p
                     pool[blk][:, :, :ntok] = np.transpose(vals, (1, 2, 0))
                 else:
                     pool[blk][:, :ntok, :] = np.transpose(vals, (1, 0, 2))
+    return k_out, v_out, ks, vs
+
+
+def append_token(k_pool, v_pool, k_scale, v_scale, tables, k_tok_bits, v_tok_bits):
+    """Decode-step append: k_tok_bits / v_tok_bits uint16 [num_req, Hkv, D] hold the K/V of every
+    request's newest token.  Pools and scales as in append().  Returns new (k_pool, v_pool,
+    k_scale, v_scale); the inputs are not modified."""
+    fp8 = k_pool.dtype == np.uint8
+    k_out, v_out = k_pool.copy(), v_pool.copy()
+    ks = None if k_scale is None else k_scale.copy()
+    vs = None if v_scale is None else v_scale.copy()
+    nb = k_pool.shape[0]
+    for r in range(len(tables["status"])):
+        if tables["status"][r] != 0:
+            continue
+        n = tables["seq_lens"][r] - tables["ctx_lens"][r]
+        nblk = tables["num_blocks"][r]
+        if n <= 0 or nblk <= 0:
+            continue
+        blk = tables["block_table"][r][nblk - 1]
+        if not (0 <= blk < nb):
+            continue
+        slot = (n - 1) % BLOCK
+        for pool, scale, src, is_v in ((k_out, ks, k_tok_bits[r], False), (v_out, vs, v_tok_bits[r], True)):
+            if slot == 0:
+                pool[blk] = 0
+            if fp8:
+                x = _bf16_to_f32(src)                                      # [Hkv, D]
+                amax = np.float32(np.abs(x).max())
+                need = np.float32(amax / np.float32(448.0))
+                if slot == 0:
+                    sc = need if amax > 0 else np.float32(1.0)
+                else:
+                    old = np.float32(scale[blk])
+                    if need > old:
+                        sc = need
+                        codes = pool[blk][:, :, :slot] if is_v else pool[blk][:, :slot, :]
+                        y = (E4M3_TABLE[codes].astype(np.float32) * old).astype(np.float32)
+                        y = np.clip((y / sc).astype(np.float32), np.float32(-448.0), np.float32(448.0))
+                        if is_v:
+                            pool[blk][:, :, :slot] = f32_to_e4m3_codes(y)
+                        else:
+                            pool[blk][:, :slot, :] = f32_to_e4m3_codes(y)
+                    else:
+                        sc = old
+                scale[blk] = sc
+                vals = f32_to_e4m3_codes(np.clip((x / sc).astype(np.float32), np.float32(-448.0), np.float32(448.0)))
+            else:
+                vals = src
+            if is_v:
+                pool[blk][:, :, slot] = vals
+            else:
+                pool[blk][:, slot, :] = vals
     return k_out, v_out, ks, vs

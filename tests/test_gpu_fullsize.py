@@ -63,7 +63,7 @@ def test_prefill_8b_full_size_sampled():
 
 
 @pytest.mark.parametrize("shared", [False, True], ids=["per_request", "per_node"])
-@pytest.mark.parametrize("name", ["decode_8b", "mixed_fp8"])
+@pytest.mark.parametrize("name", ["decode_8b", "decode_70b", "mixed_fp8"])
 def test_decode_full_size_sampled(name, shared):
     wl, sess, tables, pool, q, q_ptr = _setup(name)
     want = oracle_resolve(wl)

@@ -109,3 +109,114 @@ def test_skipped_requests_and_all_zero_block():
     n2 = q1 - q0
     for blk in tables["block_table"][2][nb2 - (n2 + 15) // 16:nb2]:
         assert ks[blk] == 1.0 and not k2[blk].any()
+
+
+# ---- append_token: the decode-step form ---------------------------------------------------------
+def _tables_at(wl, lens):
+    """Resolved tables of the same batch when request r has lens[r] new tokens so far."""
+    import copy
+    w2 = copy.deepcopy(wl)
+    w2.batch.new_lens = np.asarray(lens, dtype=np.int32)
+    return oracle_resolve(w2)
+
+
+def _token_rows(t, kn, vn, lens):
+    idx = np.array([int(t.q_ptr[r]) + int(lens[r]) - 1 for r in range(len(lens))])
+    return kn[idx], vn[idx]
+
+
+def test_token_by_token_bf16_equals_the_whole_tail_append_and_reads_back():
+    shape = W.Shape(8, 2, 64)
+    wl, t, kn, vn = _case(shape, 31)
+    n = wl.batch.new_lens.astype(np.int64)
+    whole = OP.append(t.k_pool, t.v_pool, None, None, oracle_resolve(wl), kn, vn, t.q_ptr)
+    k, v = t.k_pool, t.v_pool
+    for i in range(int(n.max())):
+        lens = np.minimum(i + 1, n)
+        tables = _tables_at(wl, lens)
+        kt, vt = _token_rows(t, kn, vn, lens)
+        k, v, _, _ = OP.append_token(k, v, None, None, tables, kt, vt)
+        if i in (0, 16, 17):
+            for r in range(wl.batch.num_req):                 # the table walk finds the token where attention reads it
+                K, V = OA.materialize_kv(k, v, tables["block_table"][r], tables["block_ntok"][r], tables["num_blocks"][r])
+                assert np.array_equal(K[-1], W.bf16_bits_to_f32(kt[r]).astype(np.float64))
+                assert np.array_equal(V[-1], W.bf16_bits_to_f32(vt[r]).astype(np.float64))
+    assert np.array_equal(k, whole[0]) and np.array_equal(v, whole[1])
+
+
+def _deq(codes, scale):
+    return E4M3_TABLE[codes].astype(np.float64) * np.float64(scale)
+
+
+def test_token_e4m3_without_growth_with_growth_and_fresh_block():
+    shape = W.Shape(8, 2, 64, W.KV_FP8_E4M3)
+    wl, t, kn, vn = _case(shape, 32)
+    n = wl.batch.new_lens.astype(np.int64)
+    r = int(np.argmax(n))                                      # a request with at least 18 new tokens
+    assert n[r] >= 18
+    lens = np.minimum(5, n)                                    # 5 tokens in: slots 0..4 of the first tail block
+    tables = _tables_at(wl, lens)
+    q_ptr5 = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
+    rows = np.concatenate([np.arange(int(t.q_ptr[q]), int(t.q_ptr[q]) + int(lens[q])) for q in range(len(lens))])
+    k, v, ks, vs = OP.append(t.k_pool, t.v_pool, t.k_scale, t.v_scale, tables, kn[rows], vn[rows], q_ptr5)
+    blk = tables["block_table"][r][tables["num_blocks"][r] - 1]
+    lens6 = lens.copy()
+    lens6[r] = 6
+    tables6 = _tables_at(wl, lens6)
+    kt, vt = _token_rows(t, kn, vn, lens6)
+    # (a) a small token: no growth.  Scale and older codes keep their bits, the token is coded like torch's cast
+    kt_small = kt.copy()
+    kt_small[r] = W.f32_to_bf16_bits(W.bf16_bits_to_f32(kt[r]) * np.float32(0.25))
+    k2, v2, ks2, vs2 = OP.append_token(k, v, ks, vs, tables6, kt_small, vt)
+    assert ks2[blk] == ks[blk]
+    assert np.array_equal(k2[blk][:, :5, :], k[blk][:, :5, :]) and np.array_equal(k2[blk][:, 6:, :], k[blk][:, 6:, :])
+    x = torch.from_numpy(W.bf16_bits_to_f32(kt_small[r]))
+    want = (x / float(ks[blk])).clamp(-448, 448).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert np.array_equal(k2[blk][:, 5, :], want)
+    # (b) a large token: the scale grows to amax / 448 and the older codes are re-coded
+    kt_big = kt.copy()
+    kt_big[r] = W.f32_to_bf16_bits(W.bf16_bits_to_f32(kt[r]) * np.float32(8.0))
+    vt_small = vt.copy()
+    vt_small[r] = W.f32_to_bf16_bits(W.bf16_bits_to_f32(vt[r]) * np.float32(0.25))
+    k3, v3, ks3, vs3 = OP.append_token(k, v, ks, vs, tables6, kt_big, vt_small)
+    xb = torch.from_numpy(W.bf16_bits_to_f32(kt_big[r]))
+    s_new = (xb.abs().max() / 448.0).item()
+    assert np.float32(ks3[blk]) == np.float32(s_new) and ks3[blk] > ks[blk]
+    old = torch.from_numpy(k[blk][:, :5, :].copy()).view(torch.float8_e4m3fn).float()        # torch's own decode
+    want_old = ((old * float(ks[blk])) / s_new).clamp(-448, 448).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert np.array_equal(k3[blk][:, :5, :], want_old)
+    want_tok = (xb / s_new).clamp(-448, 448).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert np.array_equal(k3[blk][:, 5, :], want_tok)
+    before, after = _deq(k[blk][:, :5, :], ks[blk]), _deq(k3[blk][:, :5, :], ks3[blk])
+    half_step = np.maximum(np.abs(before) * 2.0 ** -4, 2.0 ** -10 * float(ks3[blk]))          # of the new grid
+    assert (np.abs(after - before) <= half_step * 1.0001).all()
+    assert np.array_equal(v3[blk][:, :, :5], v[blk][:, :, :5]) and vs3[blk] == vs[blk]       # V did not grow
+    others = [b for b in range(wl.num_pool_blocks) if b not in {tables6["block_table"][q][tables6["num_blocks"][q] - 1]
+                                                                for q in range(len(lens6))}]
+    assert np.array_equal(k3[others], k[others]) and np.array_equal(ks3[others], ks[others])
+    # (c) token 17 opens a fresh block: zero everywhere but slot 0, scale from the token alone
+    lens17 = lens.copy()
+    lens17[r] = 17
+    tables17 = _tables_at(wl, lens17)
+    kt17, vt17 = _token_rows(t, kn, vn, lens17)
+    k4, v4, ks4, vs4 = OP.append_token(k, v, ks, vs, tables17, kt17, vt17)
+    blk17 = tables17["block_table"][r][tables17["num_blocks"][r] - 1]
+    assert blk17 != blk
+    x17 = torch.from_numpy(W.bf16_bits_to_f32(kt17[r]))
+    assert np.float32(ks4[blk17]) == np.float32((x17.abs().max() / 448.0).item())
+    assert not k4[blk17][:, 1:, :].any() and not v4[blk17][:, :, 1:].any()
+    assert np.array_equal(k4[blk17][:, 0, :], (x17 / float(ks4[blk17])).clamp(-448, 448).to(torch.float8_e4m3fn).view(torch.uint8).numpy())
+
+
+def test_token_skips_failed_and_empty_requests():
+    shape = W.Shape(8, 2, 64)
+    wl, t, kn, vn = _case(shape, 33)
+    lens = np.minimum(3, wl.batch.new_lens)
+    tables = _tables_at(wl, lens)
+    tables["status"][0] = 2
+    kt, vt = _token_rows(t, kn, vn, lens)
+    k2, v2, _, _ = OP.append_token(t.k_pool, t.v_pool, None, None, tables, kt, vt)
+    tail0 = wl.batch.tail_blocks[wl.batch.tail_ptr[0]:wl.batch.tail_ptr[1]]
+    assert np.array_equal(k2[tail0], t.k_pool[tail0])
+    blk1 = tables["block_table"][1][tables["num_blocks"][1] - 1]
+    assert np.array_equal(k2[blk1][:, 2, :], kt[1]) and np.array_equal(v2[blk1][:, :, 2], vt[1])
