@@ -277,6 +277,28 @@ int32_t gf_kv_append(gf_ctx *ctx, const gf_attn_params *params,
                      int32_t total_q, int32_t max_q, void *stream);
 
 /*
+ * gf_kv_append_token -- the decode-step form of gf_kv_append: only the newest token of every
+ * request is written (paper: as gf_kv_append; a decode loop produces one token per step and must
+ * not rewrite the whole tail).  k_tok / v_tok [num_req][num_kv_heads][head_dim] bf16 hold that
+ * token's K and V; it is token n_r - 1 of the request's new tokens (seq_lens already counts it) and
+ * goes to slot s = (n_r - 1) % 16 of the block behind the request's LAST table entry.
+ *   s == 0: the block is fresh and is written whole: zeros beside the token; GF_FP8_E4M3: its scale
+ *           becomes amax(token) / 448 per tensor (1.0 if 0).
+ *   s  > 0: GF_BF16: the token's row / column is written, nothing else.  GF_FP8_E4M3: per tensor,
+ *           need = amax(token) / 448; if need <= scale[block] the token is coded with the block's
+ *           scale; otherwise scale[block] = need and the codes in slots [0, s) are decoded,
+ *           multiplied by the old scale, divided by the new one (fp32) and rounded to e4m3 again
+ *           before the token is coded.  Slots beyond s are left as they are.
+ * Requests with a non-zero status, without new tokens or without table entries are skipped, and so
+ * is a block id outside the pool.  Of `tables`, block_table, num_blocks, ctx_lens, seq_lens and
+ * status are read.  Two requests must not share a tail block.
+ */
+int32_t gf_kv_append_token(gf_ctx *ctx, const gf_attn_params *params,
+                           void *k_pool, void *v_pool, float *k_scale, float *v_scale,
+                           int32_t num_pool_blocks, const gf_tables *tables,
+                           const void *k_tok, const void *v_tok, void *stream);
+
+/*
  * gf_attn_decode_shared -- the same decode step as gf_attn_decode (same inputs,
  * same outputs, same skipping of failed requests), computed node by node: the
  * KV of an operation node is read once for a group of requests that pass

@@ -23,7 +23,7 @@ GF_RS_OK, GF_RS_BAD_BLOCK, GF_RS_BAD_INDEX = 0, 1, 2
 
 EXPORTS = ["gf_create", "gf_destroy", "gf_strerror", "gf_last_hip_error", "gf_resolve_path",
            "gf_attn_prefill", "gf_attn_decode", "gf_attn_decode_shared", "gf_set_decode_chunk_blocks", "gf_kv_apply_residual",
-           "gf_kv_append"]
+           "gf_kv_append", "gf_kv_append_token"]
 
 _i32p = C.c_void_p  # device pointers travel as plain addresses
 
@@ -98,6 +98,9 @@ def load_library(path: Optional[str] = None):
     lib.gf_kv_append.argtypes = [C.c_void_p, C.POINTER(gf_attn_params)] + [C.c_void_p] * 4 + [C.c_int32,
                                  C.POINTER(gf_tables)] + [C.c_void_p] * 3 + [C.c_int32, C.c_int32, C.c_void_p]
     lib.gf_kv_append.restype = C.c_int32
+    lib.gf_kv_append_token.argtypes = [C.c_void_p, C.POINTER(gf_attn_params)] + [C.c_void_p] * 4 + [C.c_int32,
+                                       C.POINTER(gf_tables)] + [C.c_void_p] * 3
+    lib.gf_kv_append_token.restype = C.c_int32
     if path is None:
         _lib = lib
     return lib
@@ -201,4 +204,11 @@ def gf_kv_append(ctx, params, k_pool, v_pool, k_scale, v_scale, num_pool_blocks,
     rc = load_library().gf_kv_append(ctx, C.byref(params), _ptr(k_pool), _ptr(v_pool), _ptr(k_scale), _ptr(v_scale),
                                      num_pool_blocks, C.byref(tables), _ptr(k_new), _ptr(v_new), _ptr(q_ptr),
                                      total_q, max_q, _stream())
+    _check(ctx, rc)
+
+
+def gf_kv_append_token(ctx, params, k_pool, v_pool, k_scale, v_scale, num_pool_blocks, tables, k_tok, v_tok) -> None:
+    rc = load_library().gf_kv_append_token(ctx, C.byref(params), _ptr(k_pool), _ptr(v_pool), _ptr(k_scale),
+                                           _ptr(v_scale), num_pool_blocks, C.byref(tables), _ptr(k_tok), _ptr(v_tok),
+                                           _stream())
     _check(ctx, rc)

@@ -288,4 +288,27 @@ int32_t gf_kv_append(gf_ctx *ctx, const gf_attn_params *params, void *k_pool, vo
     return GF_OK;
 }
 
+int32_t gf_kv_append_token(gf_ctx *ctx, const gf_attn_params *params, void *k_pool, void *v_pool, float *k_scale,
+                           float *v_scale, int32_t num_pool_blocks, const gf_tables *tables, const void *k_tok,
+                           const void *v_tok, void *stream) {
+    if (!ctx || !params || !tables) return GF_ERR_NULL;
+    if (tables->num_req < 0 || tables->max_blocks < 0 || num_pool_blocks < 0) return GF_ERR_BAD_SHAPE;
+    if (params->num_kv_heads <= 0 || params->head_dim <= 0) return GF_ERR_BAD_SHAPE;
+    if (params->block_size != gf::kBlock) return GF_ERR_UNSUPPORTED;
+    if (params->head_dim != 64 && params->head_dim != 128) return GF_ERR_UNSUPPORTED;
+    if (params->kv_dtype != GF_BF16 && params->kv_dtype != GF_FP8_E4M3) return GF_ERR_UNSUPPORTED;
+    if ((int64_t)num_pool_blocks * params->num_kv_heads > 0x7fffffffLL) return GF_ERR_UNSUPPORTED;
+    if (tables->num_req == 0) return GF_OK;
+    if (!k_pool || !v_pool || !k_tok || !v_tok) return GF_ERR_NULL;
+    if (!tables->block_table || !tables->num_blocks || !tables->ctx_lens || !tables->seq_lens) return GF_ERR_NULL;
+    if (params->kv_dtype == GF_FP8_E4M3 && (!k_scale || !v_scale)) return GF_ERR_NULL;
+    if (tables->max_blocks < 1 || num_pool_blocks < 1) return GF_ERR_BAD_SHAPE;
+    hipError_t e = gf::launch_append_token(k_pool, v_pool, k_scale, v_scale, num_pool_blocks, params->num_kv_heads,
+                                           params->head_dim, params->kv_dtype, *tables, k_tok, v_tok,
+                                           (hipStream_t)stream);
+    if (e == hipErrorNotSupported) return GF_ERR_UNSUPPORTED;
+    if (e != hipSuccess) return fail_hip(ctx, e, "gf_kv_append_token launch");
+    return GF_OK;
+}
+
 }  // extern "C"

@@ -66,6 +66,11 @@ hipError_t launch_append(void *k_pool, void *v_pool, float *k_scale, float *v_sc
                          int32_t head_dim, int kv_dtype, const gf_tables &t, const void *k_new, const void *v_new,
                          const int32_t *q_ptr, int32_t total_q, int32_t max_q, hipStream_t s);
 
+// decode-step KV write: one workgroup per request, its newest token into the last table entry's block
+hipError_t launch_append_token(void *k_pool, void *v_pool, float *k_scale, float *v_scale, int32_t pool_blocks,
+                               int32_t hkv, int32_t head_dim, int kv_dtype, const gf_tables &t, const void *k_tok,
+                               const void *v_tok, hipStream_t s);
+
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));

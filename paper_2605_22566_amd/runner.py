@@ -185,6 +185,11 @@ class Session:
         B.gf_kv_append(self.ctx, params, pool.k, pool.v, pool.k_scale, pool.v_scale, pool.num_blocks, dt, k_new,
                        v_new, q_ptr, total_q, max_q)
 
+    def append_token(self, pool, tables, k_tok, v_tok):
+        params, _, dt = self._common(pool, tables, 0.0)
+        B.gf_kv_append_token(self.ctx, params, pool.k, pool.v, pool.k_scale, pool.v_scale, pool.num_blocks, dt, k_tok,
+                             v_tok)
+
     def decode(self, pool, tables, q, o, lse=None, sm_scale=0.0):
         params, dpool, dt = self._common(pool, tables, sm_scale)
         B.gf_attn_decode(self.ctx, params, dpool, dt, q, o, lse)
