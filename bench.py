@@ -125,6 +125,13 @@ class Job:
     def append(self):
         self.sess.append(self.pool, self.tables, self.k_new, self.v_new, self.q_ptr, self.total_q, self.max_q)
 
+    def append_token(self):
+        """The decode-step write: every request's newest token once more (same bits, same slot)."""
+        if not hasattr(self, "k_tok"):
+            self.k_tok = self.k_new[self.last].contiguous()
+            self.v_tok = self.v_new[self.last].contiguous()
+        self.sess.append_token(self.pool, self.tables, self.k_tok, self.v_tok)
+
     def append_bytes(self):
         sh = self.wl.shape
         esz = 2 if sh.kv_dtype == self.W.KV_BF16 else 1
@@ -207,6 +214,7 @@ def measure(job, steps, warmup):
     # the write path (not part of the step): it rewrites the tail blocks with the same new-token K/V every time
     out["append_ms"] = _event_ms(job.append, torch, it)
     out["append_gbs_kernel"] = job.append_bytes() / (out["append_ms"] * 1e-3) / 1e9
+    out["append_token_ms"] = _event_ms(job.append_token, torch, it)
     return out
 
 
@@ -412,6 +420,8 @@ def main():
                         "frac_of_hbm_peak": m["append_gbs_kernel"] / PEAK_HBM_GBS,
                         "algorithmic_bytes_per_launch": job.append_bytes(),
                         "hbm_bytes_per_launch_rocprof": _read_traffic(f"append_{args.workload}")}
+    res["kv_append_token"] = {"kernel": "append_token_kernel", "kernel_ms": m["append_token_ms"],
+                              "requests": wl.batch.num_req, "bound": "latency (one small workgroup per request)"}
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(job, args.cpu_budget)
     extra = {}
