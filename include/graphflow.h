@@ -257,7 +257,7 @@ int32_t gf_kv_apply_residual(gf_ctx *ctx, const gf_attn_params *params,
  * its block table.  Token i goes to tail block i/16, slot i%16:
  *   K[block][h][slot][d] = k_new[i][h][d]      V[block][h][d][slot] = v_new[i][h][d]
  * and the slots beyond the block's token count are written as zero.  A call
- * writes the whole tail of every request (a block is never grown in place).
+ * writes the whole tail of every request (growing a block in place: gf_kv_append_token).
  * GF_BF16: the bf16 bits are copied.  GF_FP8_E4M3: per block and tensor,
  *   scale = amax / 448 (amax over the block's valid tokens, all kv heads; 1.0 if 0),
  *   code  = e4m3(clamp(x / scale, -448, 448)), fp32 division, round to nearest even,

@@ -21,8 +21,8 @@ does not match the table, are skipped; a tail block id outside the pool is skipp
 
 Readings: the paper does not describe the write path at all; the layout is the pool's
 (see oracle.attention), the scale rule is the one the synthetic e4m3 pools are built
-with, and a call always writes a request's whole tail (growing a partly filled e4m3
-block would need its old codes re-quantised under a new scale -- not covered).
+with, and append() always writes a request's whole tail (growing a block in place is
+append_token(), below).
 
 Decode-step form, append_token(): only a request's newest token (index n-1 of its new
 tokens, the one seq_lens already counts) is written, into the last table entry's block at
