@@ -422,6 +422,10 @@ def main():
                         "hbm_bytes_per_launch_rocprof": _read_traffic(f"append_{args.workload}")}
     res["kv_append_token"] = {"kernel": "append_token_kernel", "kernel_ms": m["append_token_ms"],
                               "requests": wl.batch.num_req, "bound": "latency (one small workgroup per request)"}
+    # host-side accounting (no GPU work): KV bytes held for the first 10..50 requests under the designs the
+    # paper compares, and with transition pruning
+    from paper_2605_22566_amd import footprint as FP
+    res["footprint"] = [{k: v for k, v in row.items()} for row in FP.footprint_by_batch_size(wl)]
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(job, args.cpu_budget)
     extra = {}
