@@ -1,4 +1,4 @@
-// Operand fragments of the decode kernels: two pool blocks (32 keys) of one kv head, loaded from
+// Operand fragments of the per-request decode kernel: two pool blocks (32 keys) of one kv head, loaded from
 // HBM straight into the registers the 16x16x32 MFMAs read (see gf_decode.hip for the geometry).
 #pragma once
 #include "gf_internal.h"
@@ -26,15 +26,14 @@ struct PairRegs<D, true> {
 
 template <int D>
 __device__ __forceinline__ void load_pair(PairRegs<D, false> &p, const AttnArgs &a, const int32_t *tab,
-                                          const int32_t *ntk, int e, int e_end, int kvh, int lane, int seg_len = 0) {
+                                          const int32_t *ntk, int e, int e_end, int kvh, int lane) {
     int b0 = tab[e];
-    // token counts come from the table, or (ntk == nullptr) from the length of the segment `tab` lists
-    p.n0 = ntk ? ntk[e] : min(kBlock, seg_len - kBlock * e);
+    p.n0 = ntk[e];
     int b1 = b0;
     p.n1 = 0;
     if (e + 1 < e_end) {
         b1 = tab[e + 1];
-        p.n1 = ntk ? ntk[e + 1] : min(kBlock, seg_len - kBlock * (e + 1));
+        p.n1 = ntk[e + 1];
     }
     b0 = min(max(b0, 0), a.pool_blocks - 1);
     b1 = min(max(b1, 0), a.pool_blocks - 1);
@@ -63,15 +62,14 @@ __device__ __forceinline__ void load_pair(PairRegs<D, false> &p, const AttnArgs 
 // (K operand rows and score rows of lane group q4 belong to block q4/2) ride along.
 template <int D>
 __device__ __forceinline__ void load_pair(PairRegs<D, true> &p, const AttnArgs &a, const int32_t *tab,
-                                          const int32_t *ntk, int e, int e_end, int kvh, int lane, int seg_len = 0) {
+                                          const int32_t *ntk, int e, int e_end, int kvh, int lane) {
     int b0 = tab[e];
-    // token counts come from the table, or (ntk == nullptr) from the length of the segment `tab` lists
-    p.n0 = ntk ? ntk[e] : min(kBlock, seg_len - kBlock * e);
+    p.n0 = ntk[e];
     int b1 = b0;
     p.n1 = 0;
     if (e + 1 < e_end) {
         b1 = tab[e + 1];
-        p.n1 = ntk ? ntk[e + 1] : min(kBlock, seg_len - kBlock * (e + 1));
+        p.n1 = ntk[e + 1];
     }
     b0 = min(max(b0, 0), a.pool_blocks - 1);
     b1 = min(max(b1, 0), a.pool_blocks - 1);

@@ -25,7 +25,6 @@
 // The order in which requests land in a node's list depends on the atomics, the values do not:
 // a column's result does not depend on which column it is.
 #include "gf_internal.h"
-#include "gf_decode_frag.h"
 
 namespace gf {
 
