@@ -151,6 +151,25 @@ class Job:
         db["path_ptr"] = self.dbatch["path_ptr"][lo:hi + 1]
         self.sess.decode_shared(self.pool, db, self._slice(lo, hi), self.qd[lo:hi], self.od_shared[lo:hi])
 
+    def _shared_args(self):
+        lo, hi = self.dec_rng
+        if not hasattr(self, "_shared_db"):
+            self._shared_db = dict(self.dbatch)
+            self._shared_db["path_ptr"] = self.dbatch["path_ptr"][lo:hi + 1]
+            self._shared_tables = self._slice(lo, hi)
+        return lo, hi
+
+    def decode_shared_plan(self):
+        """List building alone (once per batch and model step; every layer shares it)."""
+        self._shared_args()
+        self.sess.decode_shared_plan(self.pool, self._shared_db, self._shared_tables)
+
+    def decode_shared_planned(self):
+        """Attention + merge over lists built before (what one layer costs)."""
+        lo, hi = self._shared_args()
+        self.sess.decode_shared_planned(self.pool, self._shared_db, self._shared_tables, self.qd[lo:hi],
+                                        self.od_shared[lo:hi])
+
     def decode_shared_bytes(self, chunk_blocks=64):
         """What the node-centric decode has to move: every node the decode requests touch once, their
         tails, one fp32 partial (max, sum, values) per (request, path node, chunk) written and read
@@ -211,6 +230,8 @@ def measure(job, steps, warmup):
         torch.cuda.synchronize()
         out["decode_shared_max_abs_diff"] = float((job.od.float() - job.od_shared.float()).abs().max().item())
         out["decode_shared_ms"] = _event_ms(job.decode_shared, torch, it)
+        out["decode_shared_plan_ms"] = _event_ms(job.decode_shared_plan, torch, it)
+        out["decode_shared_planned_ms"] = _event_ms(job.decode_shared_planned, torch, it)   # after a plan call
     # the write path (not part of the step): it rewrites the tail blocks with the same new-token K/V every time
     out["append_ms"] = _event_ms(job.append, torch, it)
     out["append_gbs_kernel"] = job.append_bytes() / (out["append_ms"] * 1e-3) / 1e9
@@ -224,6 +245,9 @@ def decode_shared_entry(job, m):
     sec = m["decode_shared_ms"] * 1e-3
     return {"kernel": "shared_attn_kernel(+list building, merge)", "kernel_ms": m["decode_shared_ms"],
             "speedup_over_decode": m["decode_ms"] / m["decode_shared_ms"],
+            # the two halves on their own: the lists depend on the batch only, a model builds them once per step
+            "plan_ms": m["decode_shared_plan_ms"], "planned_ms": m["decode_shared_planned_ms"],
+            "speedup_over_decode_planned": m["decode_ms"] / m["decode_shared_planned_ms"],
             "max_abs_diff_to_decode": m["decode_shared_max_abs_diff"],
             # the per-request kernel's bytes over this call's time: what the sharing is worth, not an HBM rate
             "per_request_bytes_rate_gbs": job.decode_bytes() / sec / 1e9,

@@ -316,8 +316,8 @@ int32_t gf_kv_append_token(gf_ctx *ctx, const gf_attn_params *params,
  * node, chunk of the node's blocks) and per chunk of tail entries, and a
  * request's partials are merged in path order: the result equals
  * gf_attn_decode's up to fp32 summation order and does not depend on the order
- * in which the device builds the lists.  Workspace: the context's (grown on
- * demand like gf_attn_decode's).
+ * in which the device builds the lists.  Workspace: a buffer of the context's own
+ * (grown on demand like gf_attn_decode's).
  */
 int32_t gf_attn_decode_shared(gf_ctx *ctx, const gf_attn_params *params, const gf_kv_pool *pool,
                               const gf_graph *graph,
@@ -325,6 +325,26 @@ int32_t gf_attn_decode_shared(gf_ctx *ctx, const gf_attn_params *params, const g
                               const int32_t *path_nodes /* [num_path_entries] device */,
                               int32_t num_path_entries,
                               const gf_tables *tables, const void *q, void *o, float *lse, void *stream);
+
+/*
+ * gf_decode_shared_plan / gf_attn_decode_shared_planned -- gf_attn_decode_shared in two parts, for callers
+ * that run the same batch through many layers: the node -> requests lists and item records depend on the
+ * batch (graph, paths, tables) only, not on the pool or the queries, so they are built once
+ * (gf_decode_shared_plan) and every layer then calls gf_attn_decode_shared_planned with its own pool, q and o.
+ * Same arguments, same meaning and same result as gf_attn_decode_shared (which is the two in a row).
+ * The lists live in the context and stay valid until the next gf_decode_shared_plan or
+ * gf_attn_decode_shared on that context, as long as the graph, path and table arrays they were built from
+ * are not modified (a decode loop that grows the tails re-plans once per step).
+ * gf_attn_decode_shared_planned returns GF_ERR_BAD_SHAPE when the context holds no lists, or lists built for
+ * other arrays, sizes or head shape than the ones passed.  params->kv_dtype is ignored by the plan call.
+ */
+int32_t gf_decode_shared_plan(gf_ctx *ctx, const gf_attn_params *params, const gf_graph *graph,
+                              const int32_t *path_ptr, const int32_t *path_nodes, int32_t num_path_entries,
+                              const gf_tables *tables, void *stream);
+int32_t gf_attn_decode_shared_planned(gf_ctx *ctx, const gf_attn_params *params, const gf_kv_pool *pool,
+                                      const gf_graph *graph, const int32_t *path_ptr, const int32_t *path_nodes,
+                                      int32_t num_path_entries, const gf_tables *tables,
+                                      const void *q, void *o, float *lse, void *stream);
 
 /* Tuning knob (host): table entries (16-token blocks) per split-KV chunk in
  * gf_attn_decode and gf_attn_decode_shared; 0 restores the built-in choice.  Must be even. */

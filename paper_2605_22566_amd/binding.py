@@ -22,7 +22,8 @@ GF_BF16, GF_FP8_E4M3 = 0, 1
 GF_RS_OK, GF_RS_BAD_BLOCK, GF_RS_BAD_INDEX = 0, 1, 2
 
 EXPORTS = ["gf_create", "gf_destroy", "gf_strerror", "gf_last_hip_error", "gf_resolve_path",
-           "gf_attn_prefill", "gf_attn_decode", "gf_attn_decode_shared", "gf_set_decode_chunk_blocks", "gf_kv_apply_residual",
+           "gf_attn_prefill", "gf_attn_decode", "gf_attn_decode_shared", "gf_decode_shared_plan", "gf_attn_decode_shared_planned",
+           "gf_set_decode_chunk_blocks", "gf_kv_apply_residual",
            "gf_kv_append", "gf_kv_append_token"]
 
 _i32p = C.c_void_p  # device pointers travel as plain addresses
@@ -92,6 +93,11 @@ def load_library(path: Optional[str] = None):
                                           C.POINTER(gf_graph), C.c_void_p, C.c_void_p, C.c_int32,
                                           C.POINTER(gf_tables), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.gf_attn_decode_shared.restype = C.c_int32
+    lib.gf_attn_decode_shared_planned.argtypes = lib.gf_attn_decode_shared.argtypes
+    lib.gf_attn_decode_shared_planned.restype = C.c_int32
+    lib.gf_decode_shared_plan.argtypes = [C.c_void_p, C.POINTER(gf_attn_params), C.POINTER(gf_graph), C.c_void_p,
+                                          C.c_void_p, C.c_int32, C.POINTER(gf_tables), C.c_void_p]
+    lib.gf_decode_shared_plan.restype = C.c_int32
     lib.gf_kv_apply_residual.argtypes = [C.c_void_p, C.POINTER(gf_attn_params), C.c_void_p, C.c_void_p, C.c_int32,
                                          C.c_int32] + [C.c_void_p] * 6 + [C.c_void_p]
     lib.gf_kv_apply_residual.restype = C.c_int32
@@ -211,4 +217,18 @@ def gf_kv_append_token(ctx, params, k_pool, v_pool, k_scale, v_scale, num_pool_b
     rc = load_library().gf_kv_append_token(ctx, C.byref(params), _ptr(k_pool), _ptr(v_pool), _ptr(k_scale),
                                            _ptr(v_scale), num_pool_blocks, C.byref(tables), _ptr(k_tok), _ptr(v_tok),
                                            _stream())
+    _check(ctx, rc)
+
+
+def gf_decode_shared_plan(ctx, params, graph: gf_graph, path_ptr, path_nodes, num_path_entries, tables) -> None:
+    rc = load_library().gf_decode_shared_plan(ctx, C.byref(params), C.byref(graph), _ptr(path_ptr), _ptr(path_nodes),
+                                              num_path_entries, C.byref(tables), _stream())
+    _check(ctx, rc)
+
+
+def gf_attn_decode_shared_planned(ctx, params, pool, graph: gf_graph, path_ptr, path_nodes, num_path_entries, tables, q,
+                                  o, lse=None) -> None:
+    rc = load_library().gf_attn_decode_shared_planned(ctx, C.byref(params), C.byref(pool), C.byref(graph),
+                                                      _ptr(path_ptr), _ptr(path_nodes), num_path_entries,
+                                                      C.byref(tables), _ptr(q), _ptr(o), _ptr(lse), _stream())
     _check(ctx, rc)

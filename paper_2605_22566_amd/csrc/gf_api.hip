@@ -14,6 +14,20 @@ struct gf_ctx {
     void *plan = nullptr;            // prefill: work list
     size_t plan_bytes = 0;
     int32_t decode_chunk_blocks = 0;   // 0 = built-in choice
+    // node-centric decode: its own buffer (lists, item records, partials), and what the lists in it were built for
+    void *shared_ws = nullptr;
+    size_t shared_ws_bytes = 0;
+    struct SharedKey {
+        const void *graph_blocks, *path_ptr, *path_nodes, *block_table, *ws;
+        int32_t num_nodes, num_entries, num_req, max_blocks, chunk, hq, hkv, head_dim;
+        bool operator==(const SharedKey &o) const {
+            return graph_blocks == o.graph_blocks && path_ptr == o.path_ptr && path_nodes == o.path_nodes &&
+                   block_table == o.block_table && ws == o.ws && num_nodes == o.num_nodes &&
+                   num_entries == o.num_entries && num_req == o.num_req && max_blocks == o.max_blocks &&
+                   chunk == o.chunk && hq == o.hq && hkv == o.hkv && head_dim == o.head_dim;
+        }
+    } shared_key = {};
+    bool shared_planned = false;
     char hip_err[256] = {0};
 };
 
@@ -116,6 +130,7 @@ int32_t gf_destroy(gf_ctx *ctx) {
     int32_t rc = GF_OK;
     if (ctx->workspace && hipFree(ctx->workspace) != hipSuccess) rc = GF_ERR_HIP;
     if (ctx->plan && hipFree(ctx->plan) != hipSuccess) rc = GF_ERR_HIP;
+    if (ctx->shared_ws && hipFree(ctx->shared_ws) != hipSuccess) rc = GF_ERR_HIP;
     delete ctx;
     return rc;
 }
@@ -211,33 +226,78 @@ int32_t gf_attn_decode(gf_ctx *ctx, const gf_attn_params *params, const gf_kv_po
     return GF_OK;
 }
 
-int32_t gf_attn_decode_shared(gf_ctx *ctx, const gf_attn_params *params, const gf_kv_pool *pool,
-                              const gf_graph *graph, const int32_t *path_ptr, const int32_t *path_nodes,
-                              int32_t num_path_entries, const gf_tables *tables, const void *q, void *o, float *lse,
-                              void *stream) {
+// The three node-centric entry points: list building, attention over built lists, or both.
+static int32_t decode_shared_call(gf_ctx *ctx, const gf_attn_params *params, const gf_kv_pool *pool,
+                                  const gf_graph *graph, const int32_t *path_ptr, const int32_t *path_nodes,
+                                  int32_t num_path_entries, const gf_tables *tables, const void *q, void *o, float *lse,
+                                  int phases, void *stream, const char *what) {
     if (!ctx || !graph) return GF_ERR_NULL;
     if (num_path_entries < 0 || graph->num_nodes < 0) return GF_ERR_BAD_SHAPE;
     gf::AttnArgs a;
     int group = 0;
-    int32_t rc = check_attn(params, pool, tables, q, o, lse, a, group);
+    // list building touches neither the pool nor q / o: stand-ins pass the shared checks
+    static const char dummy = 0;
+    const gf_kv_pool no_pool = {&dummy, &dummy, nullptr, nullptr, 1};
+    const bool attend = phases & gf::kSharedAttend;
+    gf_attn_params checked;
+    if (params) {
+        checked = *params;
+        if (!attend) checked.kv_dtype = GF_BF16;               // the lists do not depend on the pool's element type
+    }
+    int32_t rc = check_attn(params ? &checked : nullptr, attend ? pool : &no_pool, tables, attend ? q : &dummy,
+                            attend ? o : (void *)&dummy, lse, a, group);
     if (rc != GF_OK) return rc;
     if (tables->num_req == 0) return GF_OK;
     if (!path_ptr || !path_nodes) return GF_ERR_NULL;
     if (graph->num_nodes > 0 && (!graph->node_len || !graph->node_block_ptr || !graph->node_blocks))
         return GF_ERR_NULL;
-    int32_t chunk = ctx->decode_chunk_blocks;
     // the node-centric kernel keeps a chunk's table entries in one wave's lanes: 64 at most, and by default
+    int32_t chunk = ctx->decode_chunk_blocks;
     if (chunk <= 0 || chunk > 64) chunk = 64;
     const size_t need = gf::shared_workspace_bytes(graph->num_nodes, a.num_req, num_path_entries, a.max_blocks, chunk,
                                                    a.hq, params->head_dim);
-    rc = ensure_buffer(ctx, &ctx->workspace, &ctx->workspace_bytes, need, (hipStream_t)stream,
-                       "gf_attn_decode_shared workspace");
-    if (rc != GF_OK) return rc;
+    if (phases & gf::kSharedBuildLists) {
+        ctx->shared_planned = false;
+        rc = ensure_buffer(ctx, &ctx->shared_ws, &ctx->shared_ws_bytes, need, (hipStream_t)stream, what);
+        if (rc != GF_OK) return rc;
+    }
+    const gf_ctx::SharedKey key = {graph->node_blocks, path_ptr, path_nodes, tables->block_table, ctx->shared_ws,
+                                   graph->num_nodes, num_path_entries, a.num_req, a.max_blocks, chunk, a.hq, a.hkv,
+                                   params->head_dim};
+    if (!(phases & gf::kSharedBuildLists) && !(ctx->shared_planned && ctx->shared_key == key && need <= ctx->shared_ws_bytes))
+        return GF_ERR_BAD_SHAPE;                               // no lists, or lists of another batch / shape
     hipError_t e = gf::launch_decode_shared(a, params->head_dim, group, params->kv_dtype, *graph, path_ptr, path_nodes,
-                                            num_path_entries, chunk, ctx->workspace, (hipStream_t)stream);
+                                            num_path_entries, chunk, ctx->shared_ws, phases, (hipStream_t)stream);
     if (e == hipErrorNotSupported || e == hipErrorInvalidValue) return GF_ERR_UNSUPPORTED;
-    if (e != hipSuccess) return fail_hip(ctx, e, "gf_attn_decode_shared launch");
+    if (e != hipSuccess) return fail_hip(ctx, e, what);
+    if (phases & gf::kSharedBuildLists) {
+        ctx->shared_key = key;
+        ctx->shared_planned = true;
+    }
     return GF_OK;
+}
+
+int32_t gf_attn_decode_shared(gf_ctx *ctx, const gf_attn_params *params, const gf_kv_pool *pool,
+                              const gf_graph *graph, const int32_t *path_ptr, const int32_t *path_nodes,
+                              int32_t num_path_entries, const gf_tables *tables, const void *q, void *o, float *lse,
+                              void *stream) {
+    return decode_shared_call(ctx, params, pool, graph, path_ptr, path_nodes, num_path_entries, tables, q, o, lse,
+                              gf::kSharedBuildLists | gf::kSharedAttend, stream, "gf_attn_decode_shared");
+}
+
+int32_t gf_decode_shared_plan(gf_ctx *ctx, const gf_attn_params *params, const gf_graph *graph,
+                              const int32_t *path_ptr, const int32_t *path_nodes, int32_t num_path_entries,
+                              const gf_tables *tables, void *stream) {
+    return decode_shared_call(ctx, params, nullptr, graph, path_ptr, path_nodes, num_path_entries, tables, nullptr,
+                              nullptr, nullptr, gf::kSharedBuildLists, stream, "gf_decode_shared_plan");
+}
+
+int32_t gf_attn_decode_shared_planned(gf_ctx *ctx, const gf_attn_params *params, const gf_kv_pool *pool,
+                                      const gf_graph *graph, const int32_t *path_ptr, const int32_t *path_nodes,
+                                      int32_t num_path_entries, const gf_tables *tables, const void *q, void *o,
+                                      float *lse, void *stream) {
+    return decode_shared_call(ctx, params, pool, graph, path_ptr, path_nodes, num_path_entries, tables, q, o, lse,
+                              gf::kSharedAttend, stream, "gf_attn_decode_shared_planned");
 }
 
 int32_t gf_kv_apply_residual(gf_ctx *ctx, const gf_attn_params *params, void *k_pool, void *v_pool,

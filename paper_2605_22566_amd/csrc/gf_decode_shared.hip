@@ -685,26 +685,31 @@ static hipError_t launch_attn(const AttnArgs &a, SharedPlan p, float *part_o, fl
 
 template <int D, int G>
 static hipError_t launch_shared_t(const AttnArgs &a, int kv_dtype, SharedPlan p, float *part_o, float *part_ml,
-                                  hipStream_t s) {
-    const unsigned nz = (unsigned)((p.num_nodes + 255) / 256), ne = (unsigned)((p.num_entries + 255) / 256);
-    hipLaunchKernelGGL(shared_zero_kernel, dim3(nz ? nz : 1), dim3(256), 0, s, p);
-    if (ne) hipLaunchKernelGGL(shared_count_kernel, dim3(ne), dim3(256), 0, s, p, a);
-    hipLaunchKernelGGL(shared_scan_kernel, dim3(1), dim3(kScanThreads), 0, s, p, a, G, 64 * col_groups(G));
-    const unsigned nf = (unsigned)(((size_t)p.num_entries + p.num_nodes + a.num_req + 255) / 256);
-    hipLaunchKernelGGL(shared_fill_kernel, dim3(nf), dim3(256), 0, s, p, a, G, 64 * col_groups(G));
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    e = kv_dtype == GF_FP8_E4M3 ? launch_attn<D, G, true>(a, p, part_o, part_ml, s)
-                                : launch_attn<D, G, false>(a, p, part_o, part_ml, s);
-    if (e != hipSuccess) return e;
-    const size_t rows = (size_t)a.num_req * a.hq;
-    hipLaunchKernelGGL((shared_merge_kernel<D>), dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, a, p, part_o, part_ml);
+                                  int phases, hipStream_t s) {
+    if (phases & kSharedBuildLists) {
+        const unsigned nz = (unsigned)((p.num_nodes + 255) / 256), ne = (unsigned)((p.num_entries + 255) / 256);
+        hipLaunchKernelGGL(shared_zero_kernel, dim3(nz ? nz : 1), dim3(256), 0, s, p);
+        if (ne) hipLaunchKernelGGL(shared_count_kernel, dim3(ne), dim3(256), 0, s, p, a);
+        hipLaunchKernelGGL(shared_scan_kernel, dim3(1), dim3(kScanThreads), 0, s, p, a, G, 64 * col_groups(G));
+        const unsigned nf = (unsigned)(((size_t)p.num_entries + p.num_nodes + a.num_req + 255) / 256);
+        hipLaunchKernelGGL(shared_fill_kernel, dim3(nf), dim3(256), 0, s, p, a, G, 64 * col_groups(G));
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
+    if (phases & kSharedAttend) {
+        const hipError_t e = kv_dtype == GF_FP8_E4M3 ? launch_attn<D, G, true>(a, p, part_o, part_ml, s)
+                                                     : launch_attn<D, G, false>(a, p, part_o, part_ml, s);
+        if (e != hipSuccess) return e;
+        const size_t rows = (size_t)a.num_req * a.hq;
+        hipLaunchKernelGGL((shared_merge_kernel<D>), dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, a, p, part_o,
+                           part_ml);
+    }
     return hipGetLastError();
 }
 
 hipError_t launch_decode_shared(const AttnArgs &a, int head_dim, int group, int kv_dtype, const gf_graph &g,
                                 const int32_t *path_ptr, const int32_t *path_nodes, int32_t num_entries,
-                                int32_t chunk_blocks, void *workspace, hipStream_t s) {
+                                int32_t chunk_blocks, void *workspace, int phases, hipStream_t s) {
     if (a.num_req == 0) return hipSuccess;
     SharedPlan p;
     p.node_len = g.node_len;
@@ -737,7 +742,7 @@ hipError_t launch_decode_shared(const AttnArgs &a, int head_dim, int group, int 
     float *part_o = (float *)(((uintptr_t)(p.item_rec + 2 * slots) + 255) & ~(uintptr_t)255);
     float *part_ml = part_o + slots * a.hq * (size_t)head_dim;
 #define GF_CASE(DD, GG) \
-    if (head_dim == DD && group == GG) return launch_shared_t<DD, GG>(a, kv_dtype, p, part_o, part_ml, s);
+    if (head_dim == DD && group == GG) return launch_shared_t<DD, GG>(a, kv_dtype, p, part_o, part_ml, phases, s);
     GF_CASE(64, 1) GF_CASE(64, 2) GF_CASE(64, 4) GF_CASE(64, 8)
     GF_CASE(128, 1) GF_CASE(128, 2) GF_CASE(128, 4) GF_CASE(128, 8)
 #undef GF_CASE

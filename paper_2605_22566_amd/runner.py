@@ -201,6 +201,19 @@ class Session:
         B.gf_attn_decode_shared(self.ctx, params, dpool, graph, dbatch["path_ptr"], dbatch["path_nodes"],
                                 dbatch["num_path_entries"], dt, q, o, lse)
 
+    def decode_shared_plan(self, pool, dbatch, tables):
+        """Build the node lists of a batch once; decode_shared_planned() then runs any number of layers on them."""
+        params, _, dt = self._common(pool, tables, 0.0)
+        graph = B.make_graph(self.wl.graph.num_nodes, self.node_len, self.node_block_ptr, self.node_blocks)
+        B.gf_decode_shared_plan(self.ctx, params, graph, dbatch["path_ptr"], dbatch["path_nodes"],
+                                dbatch["num_path_entries"], dt)
+
+    def decode_shared_planned(self, pool, dbatch, tables, q, o, lse=None, sm_scale=0.0):
+        params, dpool, dt = self._common(pool, tables, sm_scale)
+        graph = B.make_graph(self.wl.graph.num_nodes, self.node_len, self.node_block_ptr, self.node_blocks)
+        B.gf_attn_decode_shared_planned(self.ctx, params, dpool, graph, dbatch["path_ptr"], dbatch["path_nodes"],
+                                        dbatch["num_path_entries"], dt, q, o, lse)
+
 
 def tables_to_host(tables) -> dict:
     """Device tables -> dict of Python lists (the oracle resolver's format)."""

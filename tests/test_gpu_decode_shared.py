@@ -94,3 +94,41 @@ def test_bit_identical_run_to_run_and_close_to_the_per_request_kernel():
     assert np.array_equal(runs[0], runs[1]) and np.array_equal(runs[0], runs[2])
     per_request = run_decode(wl, t)[0]
     assert np.abs(runs[0] - per_request).max() <= 2.0 ** -7 * max(1.0, np.abs(per_request).max())
+
+
+def test_plan_once_then_several_layers():
+    """gf_decode_shared_plan + gf_attn_decode_shared_planned: the lists are built once and serve several
+    'layers' (other pools, other queries); each result is the one-shot call's, bit for bit.  Without lists,
+    or with lists of another batch, the planned call is refused."""
+    import torch
+    from paper_2605_22566_amd import binding as B
+    from paper_2605_22566_amd import runner as R
+    from tests.gpu_common import run_resolve
+    sh = W.Shape(32, 8, 128)
+    wl = W.small_layered(58, sh, num_nodes=12, num_layers=4, len_lo=10, len_hi=200, num_req=20, hops=(2, 4),
+                         new_lo=1, new_hi=30)
+    sess, tables = run_resolve(wl)
+    db = sess.upload_batch(wl.batch)
+    dev = sess.device
+    pool0 = R.DevicePool.from_host(W.make_tensors(wl), dev)
+    q0 = torch.zeros((wl.batch.num_req, sh.num_q_heads, sh.head_dim), dtype=torch.bfloat16, device=dev)
+    with pytest.raises(B.GraphFlowError) as e:
+        sess.decode_shared_planned(pool0, db, tables, q0, torch.zeros_like(q0))      # nothing planned yet
+    assert e.value.code == B.GF_ERR_BAD_SHAPE
+    sess.decode_shared_plan(pool0, db, tables)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(5)
+    oneshot = R.Session(wl)                                         # a context of its own: leaves the plan alone
+    db1 = oneshot.upload_batch(wl.batch)
+    for layer in range(3):
+        pool = R.DevicePool.random(wl, dev, seed=100 + layer) if layer else pool0
+        q = torch.randn((wl.batch.num_req, sh.num_q_heads, sh.head_dim), generator=gen, device=dev).to(torch.bfloat16)
+        o1, o2 = torch.zeros_like(q), torch.zeros_like(q)
+        sess.decode_shared_planned(pool, db, tables, q, o1)
+        oneshot.decode_shared(pool, db1, tables, q, o2)
+        torch.cuda.synchronize()
+        assert torch.equal(o1, o2), layer
+    other = sess.upload_batch(wl.batch)                             # same contents, other arrays: not the planned batch
+    with pytest.raises(B.GraphFlowError) as e:
+        sess.decode_shared_planned(pool0, other, tables, q0, torch.zeros_like(q0))
+    assert e.value.code == B.GF_ERR_BAD_SHAPE
