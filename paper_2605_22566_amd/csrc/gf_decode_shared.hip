@@ -323,14 +323,29 @@ __global__ __launch_bounds__(kSharedThreads, wgs_per_cu(G)) void shared_attn_ker
         int col_req[kColGroups], col_head[kColGroups], col_slot[kColGroups];
         int my_groups;                                         // groups of this wave that hold columns
     };
-    auto load_rec = [&](long w) -> ItemRec {
-        ItemRec r;
+    // Work id w -> item record + kv head.  The ids of one (node, chunk) run kv head by kv head, the column quads
+    // of a kv head back to back: they read the same K/V blocks, and neighbouring ids run on the same XCD at
+    // the same time, so those blocks are fetched from HBM once per XCD at most.  All quads of a (node, chunk)
+    // share their record but for the quad number, so any of them serves: the one at w / hkv is read and the
+    // quad and kv head follow from w's position in the group.
+    struct Item : ItemRec {
+        int kvh;
+    };
+    auto load_rec = [&](long w) -> Item {
+        Item r;
+        r.seg = 0; r.tab_off = 0; r.entries = 0; r.tokens = 0; r.row0 = 0; r.cnt = 0; r.quad = 0; r.slot = 0; r.kvh = 0;
         if (w < total_w) {
-            const int4 x = p.item_rec[2 * (w / a.hkv)], y = p.item_rec[2 * (w / a.hkv) + 1];
+            const long idx = w / a.hkv;
+            const int4 x = p.item_rec[2 * idx], y = p.item_rec[2 * idx + 1];
             r.seg = x.x; r.tab_off = x.y; r.entries = min(x.z, kMaxChunk); r.tokens = x.w;
             r.row0 = y.x; r.cnt = y.y; r.quad = y.z; r.slot = y.w;
-        } else {
-            r.seg = 0; r.tab_off = 0; r.entries = 0; r.tokens = 0; r.row0 = 0; r.cnt = 0; r.quad = 0; r.slot = 0;
+            r.kvh = (int)(w % a.hkv);
+            if (r.seg >= 0) {
+                const int quads = max((r.cnt * G + 64 * kColGroups - 1) / (64 * kColGroups), 1);
+                const long local = w - (idx - r.quad) * a.hkv;             // position among the group's quads * hkv ids
+                r.kvh = (int)(local / quads) % a.hkv;
+                r.quad = (int)(local % quads);
+            }
         }
         return r;
     };
@@ -376,11 +391,11 @@ __global__ __launch_bounds__(kSharedThreads, wgs_per_cu(G)) void shared_attn_ker
         return d;
     };
 
-    ItemRec rec = load_rec(first);
+    Item rec = load_rec(first);
     LaneData cur = load_lane(rec);
-    ItemRec rec_next = load_rec((long)first + grid);
+    Item rec_next = load_rec((long)first + grid);
     for (long w = first; w < total_w; w += grid) {
-        const int kvh = (int)(w % a.hkv);
+        const int kvh = rec.kvh;
         const int entries = rec.entries;
         const int nsteps = (entries + 1) / 2;
         const int lane_blk = cur.blk, lane_ntok = cur.ntok;
@@ -555,7 +570,7 @@ __global__ __launch_bounds__(kSharedThreads, wgs_per_cu(G)) void shared_attn_ker
         // the next item's per-lane data is requested now, ahead of this item's stores (which use the copies
         // taken above), straight into the registers the next round reads; its successor's record follows
         cur = load_lane(rec_next);
-        const ItemRec rec_after = load_rec(w + 2 * (long)grid);
+        const Item rec_after = load_rec(w + 2 * (long)grid);
 
         // ---- partials of this wave's columns ----
 #pragma unroll
