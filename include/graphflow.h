@@ -24,7 +24,9 @@
  *     partials of gf_attn_decode, the work list of gf_attn_prefill), grown on
  *     demand -- either call may therefore call hipMalloc, and hipFree after a
  *     stream synchronisation when it outgrows what it has -- and released by
- *     gf_destroy.  A gf_ctx must not be used from two streams at once.
+ *     gf_destroy.  A gf_ctx must not be used from two streams at once.  Once a
+ *     call has run with given sizes, repeating it allocates nothing, so a sequence
+ *     of calls can be recorded into a HIP graph after one warm-up pass.
  *   - Index arrays are int32.  Block size is 16 tokens.
  *
  * Pool layout (one layer), block size B = 16, element = bf16 or e4m3 byte:

@@ -1,0 +1,64 @@
+"""The calls can be recorded into a HIP graph once a warm-up call has sized the context's buffers (no call
+allocates or synchronises after that): a captured resolve -> prefill -> decode (both paths) sequence, replayed
+several times with inputs changed in place and eager work in between, gives the eager result bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_22566_amd import runner as R
+from paper_2605_22566_amd import workload as W
+from tests.helpers import max_blocks_of
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("shape", [W.Shape(32, 8, 128), W.Shape(8, 2, 64, W.KV_FP8_E4M3)],
+                         ids=["bf16", "fp8"])
+def test_captured_sequence_replays_like_eager(shape):
+    wl = W.small_layered(444 + shape.kv_dtype, shape, num_nodes=16, num_layers=4, len_lo=10, len_hi=150, num_req=12,
+                         hops=(2, 4), new_lo=1, new_hi=60)
+    t = W.make_tensors(wl)
+    sess = R.Session(wl)
+    dev = sess.device
+    pool = R.DevicePool.from_host(t, dev)
+    db = sess.upload_batch(wl.batch)
+    tables = sess.alloc_tables(wl.batch.num_req, max_blocks_of(wl))
+    q = R.bits_to_device(t.q, dev)
+    q_ptr = torch.from_numpy(t.q_ptr).to(dev)
+    last = torch.from_numpy((t.q_ptr[1:] - 1).astype(np.int64)).to(dev)
+    total_q, max_q = int(q.shape[0]), int(wl.batch.new_lens.max())
+    o = torch.zeros_like(q)
+    qd = q[last].contiguous()
+    od, ods = torch.zeros_like(qd), torch.zeros_like(qd)
+
+    def sequence():
+        sess.resolve(db, tables)
+        sess.prefill(pool, tables, q, q_ptr, total_q, max_q, o)
+        sess.decode(pool, tables, qd, od)
+        sess.decode_shared(pool, db, tables, qd, ods)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                       # warm-up: buffers sized, occupancy queried
+        sequence()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        sequence()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        q.mul_(-0.5 if rep == 1 else 1.5)               # new inputs in the same buffers
+        qd.copy_(q[last])
+        for buf in (o, od, ods):
+            buf.fill_(float("nan"))
+        graph.replay()
+        torch.cuda.synchronize()
+        got = [x.clone() for x in (o, od, ods)]
+        for buf in (o, od, ods):
+            buf.fill_(float("nan"))
+        sequence()                                      # the program's own eager work between replays
+        torch.cuda.synchronize()
+        for name, g, e in zip(("prefill", "decode", "decode_shared"), got, (o, od, ods)):
+            assert torch.equal(g, e), f"{name}, replay {rep}"
+            assert torch.isfinite(e.float()).all()
