@@ -25,15 +25,29 @@ precision (bf16 here, like the pool), or what happens to malformed input (a bloc
 id outside the pool skips the item, an element index outside the image is ignored;
 both are reported per item).
 
+e4m3 pools, reconstruct_e4m3(): the base block is widened (code -> value, times the source
+block's scale, one fp32 product), the residual entries are added in fp32 in row order, and the
+result is quantised again under a scale of its own: per tensor, scale = amax / 448 over the
+whole destination block (all kv heads, all 16 slots -- a block carries no token count, so pad
+slots take part; the write path leaves them zero), 1.0 for an all-zero block, code =
+e4m3(clamp(x / scale)), fp32 division, round to nearest even.  Reading: the paper keeps KV in
+16 bits; a quantised pool with a residual on top is this build's combination of the two.
+
 Pins (tests/test_oracle_residual.py): the bf16 rounding against torch's cast on
 random values, ties and extremes; an empty residual is the identity; the residual
 -base gives all zeros; a full-density residual equals torch's element-wise bf16 add;
 single entries land on the hand-indexed physical element of K and of V; a node
 reconstructed block by block equals base + delta formed on the [token][head][dim]
 segment without any block arithmetic; select_by_energy against brute force over all
-subsets on tiny inputs, plus its defining invariants.
+subsets on tiny inputs, plus its defining invariants.  reconstruct_e4m3: an empty residual
+re-codes a block onto itself (same codes, same scale) when its largest code is the largest
+finite one; codes and scales against torch's float8 casts of the same fp32 sums; the
+dequantised result within half a code step of base + delta; bad blocks and indices reported.
 """
 import numpy as np
+
+from .append import f32_to_e4m3_codes
+from .formats import E4M3_TABLE
 
 BLOCK = 16
 ST_OK, ST_BAD_BLOCK, ST_BAD_INDEX = 0, 1, 2
@@ -85,6 +99,44 @@ def reconstruct(k_pool: np.ndarray, v_pool: np.ndarray, src_blocks, dst_blocks, 
         k_out[t] = f32_to_bf16_bits_rne(kb)
         v_out[t] = f32_to_bf16_bits_rne(vb)
     return k_out, v_out, status
+
+
+def reconstruct_e4m3(k_pool, v_pool, k_scale, v_scale, src_blocks, dst_blocks, res_ptr, res_idx, res_val):
+    """k_pool uint8 [nb, Hkv, 16, D], v_pool uint8 [nb, Hkv, D, 16] (e4m3 codes), k_scale / v_scale fp32 [nb].
+    Returns (k_pool', v_pool', k_scale', v_scale', status[num_items]); the inputs are not modified."""
+    k_out, v_out = k_pool.copy(), v_pool.copy()
+    ks_out, vs_out = k_scale.copy(), v_scale.copy()
+    nb, hkv, _, dim = k_pool.shape
+    n_items = len(src_blocks)
+    status = np.zeros(n_items, dtype=np.int32)
+    for b in range(n_items):
+        s, t = int(src_blocks[b]), int(dst_blocks[b])
+        if not (0 <= s < nb and 0 <= t < nb):
+            status[b] = ST_BAD_BLOCK
+            continue
+        kb = (E4M3_TABLE[k_pool[s]].astype(np.float32) * np.float32(k_scale[s])).astype(np.float32)   # [Hkv, 16, D]
+        vb = (E4M3_TABLE[v_pool[s]].astype(np.float32) * np.float32(v_scale[s])).astype(np.float32)   # [Hkv, D, 16]
+        for tensor in (0, 1):
+            for h in range(hkv):
+                r = (b * 2 + tensor) * hkv + h
+                for e in range(int(res_ptr[r]), int(res_ptr[r + 1])):
+                    i = int(res_idx[e])
+                    if not (0 <= i < BLOCK * dim):
+                        status[b] = ST_BAD_INDEX
+                        continue
+                    val = bf16_bits_to_f32(np.array([res_val[e]], dtype=np.uint16))[0]
+                    slot, d = divmod(i, dim)
+                    if tensor == 0:
+                        kb[h, slot, d] = np.float32(kb[h, slot, d]) + np.float32(val)
+                    else:
+                        vb[h, d, slot] = np.float32(vb[h, d, slot]) + np.float32(val)
+        for x, pool, scale in ((kb, k_out, ks_out), (vb, v_out, vs_out)):
+            amax = np.float32(np.abs(x).max())
+            sc = np.float32(amax / np.float32(448.0)) if amax > 0 else np.float32(1.0)
+            y = np.clip((x / sc).astype(np.float32), np.float32(-448.0), np.float32(448.0))
+            pool[t] = f32_to_e4m3_codes(y)
+            scale[t] = sc
+    return k_out, v_out, ks_out, vs_out, status
 
 
 def select_by_energy(delta: np.ndarray, share: float = 0.95) -> np.ndarray:

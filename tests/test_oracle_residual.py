@@ -160,3 +160,71 @@ def test_select_by_energy_matches_brute_force_and_its_invariants():
     assert e[keep].sum() - e[keep].min() < 0.95 * e.sum()      # dropping the smallest kept entry falls short
     assert e[keep].min() >= np.delete(e, keep).max()           # nothing larger was left out
     assert OR.select_by_energy(np.zeros(7)).size == 0
+
+
+# ---- e4m3 pools ---------------------------------------------------------------------------------
+def _pool_e4m3(rng, nb, hkv, dim):
+    import torch
+    x = torch.from_numpy(rng.standard_normal((2, nb, hkv, 16, dim)).astype(np.float32))
+    scale = x.abs().amax(dim=(2, 3, 4)) / 448.0                       # [2, nb]
+    codes = (x / scale[:, :, None, None, None]).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    k = codes[0].copy()
+    v = np.ascontiguousarray(np.transpose(codes[1], (0, 1, 3, 2)))     # [nb, Hkv, D, 16]
+    return k, v, scale[0].numpy().copy(), scale[1].numpy().copy()
+
+
+def test_e4m3_empty_residual_recodes_a_block_onto_itself():
+    rng = np.random.default_rng(14)
+    hkv, dim = 2, 64
+    k, v, ks, vs = _pool_e4m3(rng, 4, hkv, dim)
+    k2, v2, ks2, vs2, st = OR.reconstruct_e4m3(k, v, ks, vs, [0, 1], [2, 3], [0] * (2 * 2 * hkv + 1),
+                                               np.zeros(0, np.uint16), np.zeros(0, np.uint16))
+    assert st.tolist() == [0, 0]
+    # the largest code of a block built with scale = amax / 448 is +-448: amax(deq) / 448 gives the scale back
+    assert (k[0] & 0x7F).max() == 0x7E and ks2[2] == ks[0] and vs2[3] == vs[1]
+    assert np.array_equal(k2[2], k[0]) and np.array_equal(v2[3], v[1])
+    assert np.array_equal(k2[:2], k[:2]) and np.array_equal(ks2[:2], ks[:2])
+
+
+def test_e4m3_codes_and_scales_match_torch_casts_of_the_same_sums():
+    import torch
+    rng = np.random.default_rng(15)
+    hkv, dim = 2, 128
+    k, v, ks, vs = _pool_e4m3(rng, 3, hkv, dim)
+    img = 16 * dim
+    mask = rng.random((2, hkv, img)) < 0.3
+    vals = _torch_bf16_bits((rng.standard_normal((2, hkv, img)) * 0.5).astype(np.float32))
+    ptr, idx, val = [0], [], []
+    for t in (0, 1):
+        for h in range(hkv):
+            ii = np.nonzero(mask[t, h])[0]
+            idx.extend(ii.tolist())
+            val.extend(vals[t, h][ii].tolist())
+            ptr.append(len(idx))
+    k2, v2, ks2, vs2, st = OR.reconstruct_e4m3(k, v, ks, vs, [1], [2], ptr, np.array(idx, np.uint16), np.array(val, np.uint16))
+    assert st.tolist() == [0]
+    delta = np.where(mask, OR.bf16_bits_to_f32(vals), np.float32(0)).reshape(2, hkv, 16, dim)        # logical [slot][d]
+    base_k = torch.from_numpy(k[1].copy()).view(torch.float8_e4m3fn).float() * float(ks[1])             # torch's own decode
+    base_v = torch.from_numpy(v[1].copy()).view(torch.float8_e4m3fn).float() * float(vs[1])
+    sum_k = base_k + torch.from_numpy(delta[0])
+    sum_v = base_v + torch.from_numpy(np.ascontiguousarray(np.transpose(delta[1], (0, 2, 1))))
+    for x, codes, scale in ((sum_k, k2[2], ks2[2]), (sum_v, v2[2], vs2[2])):
+        s = x.abs().max() / 448.0
+        assert np.float32(scale) == np.float32(s.item())
+        want = (x / s).clamp(-448, 448).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+        assert np.array_equal(codes, want)
+        deq = torch.from_numpy(codes.copy()).view(torch.float8_e4m3fn).float().numpy().astype(np.float64) * float(scale)
+        half = np.maximum(np.abs(x.numpy()) * 2.0 ** -4, 2.0 ** -10 * float(scale))
+        assert (np.abs(deq - x.numpy().astype(np.float64)) <= half * 1.0001).all()
+
+
+def test_e4m3_bad_block_and_bad_index_are_reported():
+    rng = np.random.default_rng(16)
+    hkv, dim = 1, 64
+    k, v, ks, vs = _pool_e4m3(rng, 3, hkv, dim)
+    idx = np.array([5, 16 * dim, 7], np.uint16)
+    val = np.array([0x3F80, 0x3F80, 0x3F80], np.uint16)
+    k2, v2, ks2, vs2, st = OR.reconstruct_e4m3(k, v, ks, vs, [0, 9, 1], [1, 2, -1], [0, 3, 3, 3, 3, 3, 3], idx, val)
+    assert st.tolist() == [OR.ST_BAD_INDEX, OR.ST_BAD_BLOCK, OR.ST_BAD_BLOCK]
+    assert np.array_equal(k2[2], k[2]) and ks2[2] == ks[2]
+    assert not np.array_equal(k2[1], k[1])
