@@ -294,10 +294,32 @@ def measure_residual(torch, R, W, num_items=8192, iters=20):
     blk = 2 * sh.num_kv_heads * W.BLOCK * sh.head_dim * 2
     nbytes = num_items * (2 * blk + 8 + 4 * 2 * sh.num_kv_heads) + 4.0 * nnz
     ok = bool((dres["status"] == 0).all().item())
-    return {"kernel": "residual_kernel", "kernel_ms": ms, "blocks": num_items, "entries": nnz,
-            "algorithmic_bytes_per_launch": nbytes, "gbs_kernel": nbytes / (ms * 1e-3) / 1e9,
-            "frac_of_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "all_items_ok": ok,
-            "hbm_bytes_per_launch_rocprof": _read_traffic("residual_kv_residual")}
+    out = {"kernel": "residual_kernel", "kernel_ms": ms, "blocks": num_items, "entries": nnz,
+           "algorithmic_bytes_per_launch": nbytes, "gbs_kernel": nbytes / (ms * 1e-3) / 1e9,
+           "frac_of_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "all_items_ok": ok,
+           "hbm_bytes_per_launch_rocprof": _read_traffic("residual_kv_residual")}
+    # the same items on an e4m3 pool (codes of N(0,1) blocks, scale amax / 448): half the block bytes, two passes
+    del pool, k, v
+    sh8 = W.Shape(32, 8, 128, W.KV_FP8_E4M3)
+    sess8 = R.Session(W.small_layered(1, sh8, num_req=1), dev)
+    x = torch.randn((2, nb, sh.num_kv_heads * W.BLOCK * sh.head_dim), generator=gen, device=dev)
+    sc = x.abs().amax(dim=2) / 448.0
+    codes = (x / sc[:, :, None]).to(torch.float8_e4m3fn).view(torch.uint8)
+    pool8 = R.DevicePool(codes[0].view(nb, sh.num_kv_heads, W.BLOCK, sh.head_dim).contiguous(),
+                         codes[1].view(nb, sh.num_kv_heads, sh.head_dim, W.BLOCK).contiguous(), nb,
+                         sc[0].contiguous(), sc[1].contiguous())
+    del x, codes
+    dres["status"].fill_(-77)
+    fn8 = lambda: sess8.apply_residual(pool8, dres)
+    for _ in range(3):
+        fn8()
+    torch.cuda.synchronize()
+    ms8 = _event_ms(fn8, torch, iters)
+    nbytes8 = num_items * (blk + 16 + 8 + 4 * 2 * sh.num_kv_heads) + 4.0 * nnz      # blk / 2 read + blk / 2 written, scales
+    out["e4m3"] = {"kernel": "residual_e4m3_kernel", "kernel_ms": ms8, "algorithmic_bytes_per_launch": nbytes8,
+                   "gbs_kernel": nbytes8 / (ms8 * 1e-3) / 1e9, "frac_of_hbm_peak": nbytes8 / (ms8 * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                   "all_items_ok": bool((dres["status"] == 0).all().item())}
+    return out
 
 
 def cpu_baseline(job, budget_s=20.0):

@@ -231,14 +231,19 @@ int32_t gf_attn_decode(gf_ctx *ctx, const gf_attn_params *params, const gf_kv_po
  * Contract: the destination blocks are distinct from each other and from every
  * source block of the call; the entries of one row name distinct elements
  * (a repeated element is a race); res_ptr is non-decreasing from 0.
- * GF_BF16 pools only (GF_FP8_E4M3 returns GF_ERR_UNSUPPORTED: a sum would have
- * to be re-quantised under a new block scale).
- *   k_pool, v_pool  the pool tensors (device, read and written)
+ * GF_FP8_E4M3 pools: the base block is widened (code -> value, times the source
+ * block's scale, fp32), the entries are added in fp32, and the destination block
+ * is quantised under a scale of its own, per tensor: scale = amax / 448 over the
+ * whole block (all kv heads, all 16 slots; 1.0 if 0), code = e4m3(clamp(x /
+ * scale, +-448)), fp32 division, nearest even; k_scale[dst] / v_scale[dst] are
+ * written.  There the destination may be the source block itself.
+ *   k_pool, v_pool    the pool tensors (device, read and written)
+ *   k_scale, v_scale  [num_pool_blocks] fp32 (device, read and written), GF_FP8_E4M3 only, else NULL
  *   status          [num_items] device, out, or NULL: GF_RS_* per item
  */
 int32_t gf_kv_apply_residual(gf_ctx *ctx, const gf_attn_params *params,
-                             void *k_pool, void *v_pool, int32_t num_pool_blocks,
-                             int32_t num_items,
+                             void *k_pool, void *v_pool, float *k_scale, float *v_scale,
+                             int32_t num_pool_blocks, int32_t num_items,
                              const int32_t *src_blocks,  /* [num_items] device */
                              const int32_t *dst_blocks,  /* [num_items] device */
                              const int32_t *res_ptr,     /* [num_items * 2 * num_kv_heads + 1] device */

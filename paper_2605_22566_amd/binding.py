@@ -98,7 +98,7 @@ def load_library(path: Optional[str] = None):
     lib.gf_decode_shared_plan.argtypes = [C.c_void_p, C.POINTER(gf_attn_params), C.POINTER(gf_graph), C.c_void_p,
                                           C.c_void_p, C.c_int32, C.POINTER(gf_tables), C.c_void_p]
     lib.gf_decode_shared_plan.restype = C.c_int32
-    lib.gf_kv_apply_residual.argtypes = [C.c_void_p, C.POINTER(gf_attn_params), C.c_void_p, C.c_void_p, C.c_int32,
+    lib.gf_kv_apply_residual.argtypes = [C.c_void_p, C.POINTER(gf_attn_params)] + [C.c_void_p] * 4 + [C.c_int32,
                                          C.c_int32] + [C.c_void_p] * 6 + [C.c_void_p]
     lib.gf_kv_apply_residual.restype = C.c_int32
     lib.gf_kv_append.argtypes = [C.c_void_p, C.POINTER(gf_attn_params)] + [C.c_void_p] * 4 + [C.c_int32,
@@ -198,9 +198,9 @@ def gf_attn_decode_shared(ctx, params, pool, graph: gf_graph, path_ptr, path_nod
 
 
 def gf_kv_apply_residual(ctx, params, k_pool, v_pool, num_pool_blocks, num_items, src_blocks, dst_blocks, res_ptr,
-                         res_idx, res_val, status=None) -> None:
-    rc = load_library().gf_kv_apply_residual(ctx, C.byref(params), _ptr(k_pool), _ptr(v_pool), num_pool_blocks,
-                                             num_items, _ptr(src_blocks), _ptr(dst_blocks), _ptr(res_ptr),
+                         res_idx, res_val, status=None, k_scale=None, v_scale=None) -> None:
+    rc = load_library().gf_kv_apply_residual(ctx, C.byref(params), _ptr(k_pool), _ptr(v_pool), _ptr(k_scale),
+                                             _ptr(v_scale), num_pool_blocks, num_items, _ptr(src_blocks), _ptr(dst_blocks), _ptr(res_ptr),
                                              _ptr(res_idx), _ptr(res_val), _ptr(status), _stream())
     _check(ctx, rc)
 

@@ -300,8 +300,8 @@ int32_t gf_attn_decode_shared_planned(gf_ctx *ctx, const gf_attn_params *params,
                               gf::kSharedAttend, stream, "gf_attn_decode_shared_planned");
 }
 
-int32_t gf_kv_apply_residual(gf_ctx *ctx, const gf_attn_params *params, void *k_pool, void *v_pool,
-                             int32_t num_pool_blocks, int32_t num_items, const int32_t *src_blocks,
+int32_t gf_kv_apply_residual(gf_ctx *ctx, const gf_attn_params *params, void *k_pool, void *v_pool, float *k_scale,
+                             float *v_scale, int32_t num_pool_blocks, int32_t num_items, const int32_t *src_blocks,
                              const int32_t *dst_blocks, const int32_t *res_ptr, const uint16_t *res_idx,
                              const uint16_t *res_val, int32_t *status, void *stream) {
     if (!ctx || !params) return GF_ERR_NULL;
@@ -309,15 +309,16 @@ int32_t gf_kv_apply_residual(gf_ctx *ctx, const gf_attn_params *params, void *k_
     if (params->num_kv_heads <= 0 || params->head_dim <= 0) return GF_ERR_BAD_SHAPE;
     if (params->block_size != gf::kBlock) return GF_ERR_UNSUPPORTED;
     if (params->head_dim != 64 && params->head_dim != 128) return GF_ERR_UNSUPPORTED;
-    if (params->kv_dtype != GF_BF16) return GF_ERR_UNSUPPORTED;
+    if (params->kv_dtype != GF_BF16 && params->kv_dtype != GF_FP8_E4M3) return GF_ERR_UNSUPPORTED;
     // rows of the residual CSR: num_items * 2 * num_kv_heads, indexed with 32-bit integers on the device
     if ((int64_t)num_items * 2 * params->num_kv_heads >= 0x7fffffffLL) return GF_ERR_UNSUPPORTED;
     if (num_items == 0) return GF_OK;
     if (!k_pool || !v_pool || !src_blocks || !dst_blocks || !res_ptr) return GF_ERR_NULL;
     // res_idx / res_val may be NULL only if no item has entries, which the host cannot see: require them
     if (!res_idx || !res_val) return GF_ERR_NULL;
-    hipError_t e = gf::launch_residual(k_pool, v_pool, num_pool_blocks, params->num_kv_heads, params->head_dim,
-                                       num_items, src_blocks, dst_blocks, res_ptr, res_idx, res_val, status,
+    if (params->kv_dtype == GF_FP8_E4M3 && (!k_scale || !v_scale)) return GF_ERR_NULL;
+    hipError_t e = gf::launch_residual(k_pool, v_pool, k_scale, v_scale, num_pool_blocks, params->num_kv_heads,
+                                       params->head_dim, params->kv_dtype, num_items, src_blocks, dst_blocks, res_ptr, res_idx, res_val, status,
                                        (hipStream_t)stream);
     if (e == hipErrorNotSupported) return GF_ERR_UNSUPPORTED;
     if (e != hipSuccess) return fail_hip(ctx, e, "gf_kv_apply_residual launch");

@@ -59,10 +59,10 @@ hipError_t launch_decode_shared(const AttnArgs &a, int head_dim, int group, int 
                                 int32_t chunk_blocks, void *workspace, int phases, hipStream_t s);
 
 // residual application: one workgroup per pool block
-hipError_t launch_residual(void *k_pool, void *v_pool, int32_t num_pool_blocks, int32_t hkv, int32_t head_dim,
-                           int32_t num_items, const int32_t *src_blocks, const int32_t *dst_blocks,
-                           const int32_t *res_ptr, const uint16_t *res_idx, const uint16_t *res_val,
-                           int32_t *status, hipStream_t s);
+hipError_t launch_residual(void *k_pool, void *v_pool, float *k_scale, float *v_scale, int32_t num_pool_blocks,
+                           int32_t hkv, int32_t head_dim, int kv_dtype, int32_t num_items, const int32_t *src_blocks,
+                           const int32_t *dst_blocks, const int32_t *res_ptr, const uint16_t *res_idx,
+                           const uint16_t *res_val, int32_t *status, hipStream_t s);
 
 // KV write path: one workgroup per (request, tail block); max_q bounds the new tokens of a request
 hipError_t launch_append(void *k_pool, void *v_pool, float *k_scale, float *v_scale, int32_t pool_blocks, int32_t hkv,

@@ -77,21 +77,142 @@ __global__ __launch_bounds__(kResidualThreads) void residual_kernel(
     if (status && tid == 0) status[item] = bad_index ? GF_RS_BAD_INDEX : GF_RS_OK;
 }
 
-hipError_t launch_residual(void *k_pool, void *v_pool, int32_t num_pool_blocks, int32_t hkv, int32_t head_dim,
-                           int32_t num_items, const int32_t *src_blocks, const int32_t *dst_blocks,
-                           const int32_t *res_ptr, const uint16_t *res_idx, const uint16_t *res_val,
-                           int32_t *status, hipStream_t s) {
+// e4m3 pool: the same reconstruction with a quantised base and a quantised result.  A base image is widened
+// (code -> value, times the source block's scale), the residual entries are added in fp32 (fp32 images in the
+// wave's LDS region), and the destination block gets a scale of its own: amax / 448 per tensor over the whole
+// block.  That maximum is only known once every image has been summed, so the block is walked twice: pass 1
+// leaves the two maxima, pass 2 repeats the sums (the base is still in L2) and writes the codes.
+template <int D>
+__global__ __launch_bounds__(kResidualThreads) void residual_e4m3_kernel(
+    uint8_t *__restrict__ k_pool, uint8_t *__restrict__ v_pool, float *__restrict__ k_scale,
+    float *__restrict__ v_scale, int num_pool_blocks, int hkv, const int32_t *__restrict__ src_blocks,
+    const int32_t *__restrict__ dst_blocks, const int32_t *__restrict__ res_ptr,
+    const uint16_t *__restrict__ res_idx, const uint16_t *__restrict__ res_val, int32_t *__restrict__ status) {
+    constexpr int kImg = kBlock * D;                       // elements (= bytes) of one image
+    __shared__ __attribute__((aligned(16))) float lds[kResidualWaves][kImg];
+    __shared__ float red[2][kResidualWaves];
+    __shared__ int bad_index;
+    const int item = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int src = src_blocks[item], dst = dst_blocks[item];
+    if (src < 0 || src >= num_pool_blocks || dst < 0 || dst >= num_pool_blocks) {
+        if (status && tid == 0) status[item] = GF_RS_BAD_BLOCK;
+        return;
+    }
+    const float src_scale[2] = {k_scale[src], v_scale[src]};   // read before the destination's are written (src may be dst)
+    if (tid == 0) bad_index = 0;
+    __syncthreads();
+    float *img = lds[wave];
+    const int rows = 2 * hkv;
+    bool bad = false;
+    float dst_scale[2] = {1.f, 1.f};
+    for (int pass = 0; pass < 2; ++pass) {
+        float amax[2] = {0.f, 0.f};
+        for (int row = wave; row < rows; row += kResidualWaves) {
+            const bool is_v = row >= hkv;
+            const int h = is_v ? row - hkv : row;
+            uint8_t *pool = is_v ? v_pool : k_pool;
+            const uint8_t *g_src = pool + ((size_t)src * hkv + h) * kImg;
+            uint8_t *g_dst = pool + ((size_t)dst * hkv + h) * kImg;
+            const float s_in = src_scale[is_v];
+            // 1. base image -> fp32 in LDS
+#pragma unroll
+            for (int c = 16 * lane; c < kImg; c += 16 * 64) {
+                const u32x4 w = *(const u32x4 *)(g_src + c);
+                const bf16x8 lo = fp8x8_to_bf16x8(u32x2{w[0], w[1]}), hi = fp8x8_to_bf16x8(u32x2{w[2], w[3]});
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    img[c + i] = __fmul_rn((float)lo[i], s_in);
+                    img[c + 8 + i] = __fmul_rn((float)hi[i], s_in);
+                }
+            }
+            __builtin_amdgcn_wave_barrier();
+            // 2. this image's residual entries
+            const size_t r = (size_t)item * rows + row;
+            const int e0 = res_ptr[r], e1 = res_ptr[r + 1];
+            for (int e = e0 + lane; e < e1; e += 64) {
+                const uint32_t i = res_idx[e];
+                if (i >= (uint32_t)kImg) {
+                    bad = true;
+                    continue;
+                }
+                const uint32_t phys = is_v ? (i % D) * kBlock + i / D : i;   // V image: [d][slot]
+                img[phys] = __fadd_rn(img[phys], __uint_as_float((uint32_t)res_val[e] << 16));
+            }
+            __builtin_amdgcn_wave_barrier();
+            if (pass == 0) {
+                // 3a. this image's share of the tensor's maximum
+                float m = 0.f;
+#pragma unroll 8
+                for (int c = lane; c < kImg; c += 64) m = fmaxf(m, fabsf(img[c]));
+                amax[is_v] = fmaxf(amax[is_v], m);
+            } else {
+                // 3b. quantise under the destination scale and write the image
+                const float s_out = dst_scale[is_v];
+#pragma unroll
+                for (int c = 8 * lane; c < kImg; c += 8 * 64) {
+                    float x[8];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) x[i] = fminf(fmaxf(img[c + i] / s_out, -448.0f), 448.0f);
+                    u32x2 out;
+                    int w = 0;
+                    w = __builtin_amdgcn_cvt_pk_fp8_f32(x[0], x[1], w, false);
+                    w = __builtin_amdgcn_cvt_pk_fp8_f32(x[2], x[3], w, true);
+                    out[0] = (uint32_t)w;
+                    w = 0;
+                    w = __builtin_amdgcn_cvt_pk_fp8_f32(x[4], x[5], w, false);
+                    w = __builtin_amdgcn_cvt_pk_fp8_f32(x[6], x[7], w, true);
+                    out[1] = (uint32_t)w;
+                    *(u32x2 *)(g_dst + c) = out;
+                }
+            }
+            __builtin_amdgcn_wave_barrier();                   // the image region is reused by the wave's next row
+        }
+        if (pass == 0) {
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+#pragma unroll
+                for (int o = 32; o >= 1; o >>= 1) amax[t] = fmaxf(amax[t], __shfl_xor(amax[t], o, 64));
+                if (lane == 0) red[t][wave] = amax[t];
+            }
+            __syncthreads();
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+                const float m = fmaxf(fmaxf(red[t][0], red[t][1]), fmaxf(red[t][2], red[t][3]));
+                dst_scale[t] = m > 0.f ? m / 448.0f : 1.0f;
+            }
+            if (tid == 0) {
+                k_scale[dst] = dst_scale[0];
+                v_scale[dst] = dst_scale[1];
+            }
+        }
+    }
+    if (bad) bad_index = 1;                                              // benign race: every writer stores 1
+    __syncthreads();
+    if (status && tid == 0) status[item] = bad_index ? GF_RS_BAD_INDEX : GF_RS_OK;
+}
+
+hipError_t launch_residual(void *k_pool, void *v_pool, float *k_scale, float *v_scale, int32_t num_pool_blocks,
+                           int32_t hkv, int32_t head_dim, int kv_dtype, int32_t num_items, const int32_t *src_blocks,
+                           const int32_t *dst_blocks, const int32_t *res_ptr, const uint16_t *res_idx,
+                           const uint16_t *res_val, int32_t *status, hipStream_t s) {
     if (num_items == 0) return hipSuccess;
-    if (head_dim == 128)
-        hipLaunchKernelGGL(residual_kernel<128>, dim3((unsigned)num_items), dim3(kResidualThreads), 0, s,
-                           (uint16_t *)k_pool, (uint16_t *)v_pool, num_pool_blocks, hkv, src_blocks, dst_blocks,
-                           res_ptr, res_idx, res_val, status);
-    else if (head_dim == 64)
-        hipLaunchKernelGGL(residual_kernel<64>, dim3((unsigned)num_items), dim3(kResidualThreads), 0, s,
-                           (uint16_t *)k_pool, (uint16_t *)v_pool, num_pool_blocks, hkv, src_blocks, dst_blocks,
-                           res_ptr, res_idx, res_val, status);
-    else
-        return hipErrorNotSupported;
+    const dim3 grid((unsigned)num_items), block(kResidualThreads);
+    const bool fp8 = kv_dtype == GF_FP8_E4M3;
+#define GF_RES_BF16(DD)                                                                                              \
+    hipLaunchKernelGGL(residual_kernel<DD>, grid, block, 0, s, (uint16_t *)k_pool, (uint16_t *)v_pool, num_pool_blocks, \
+                       hkv, src_blocks, dst_blocks, res_ptr, res_idx, res_val, status)
+#define GF_RES_E4M3(DD)                                                                                            \
+    hipLaunchKernelGGL(residual_e4m3_kernel<DD>, grid, block, 0, s, (uint8_t *)k_pool, (uint8_t *)v_pool, k_scale, \
+                       v_scale, num_pool_blocks, hkv, src_blocks, dst_blocks, res_ptr, res_idx, res_val, status)
+    if (head_dim == 128 && fp8) GF_RES_E4M3(128);
+    else if (head_dim == 128) GF_RES_BF16(128);
+    else if (head_dim == 64 && fp8) GF_RES_E4M3(64);
+    else if (head_dim == 64) GF_RES_BF16(64);
+    else return hipErrorNotSupported;
+#undef GF_RES_BF16
+#undef GF_RES_E4M3
     return hipGetLastError();
 }
 

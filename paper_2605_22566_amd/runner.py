@@ -178,7 +178,8 @@ class Session:
         sh = self.wl.shape
         params = B.make_params(sh.num_q_heads, sh.num_kv_heads, sh.head_dim, sh.kv_dtype)
         B.gf_kv_apply_residual(self.ctx, params, pool.k, pool.v, pool.num_blocks, dres["num_items"], dres["src"],
-                               dres["dst"], dres["ptr"], dres["idx"], dres["val"], dres["status"])
+                               dres["dst"], dres["ptr"], dres["idx"], dres["val"], dres["status"], pool.k_scale,
+                               pool.v_scale)
 
     def append(self, pool, tables, k_new, v_new, q_ptr, total_q, max_q):
         params, _, dt = self._common(pool, tables, 0.0)

@@ -54,12 +54,12 @@ def test_unsupported_shapes_and_bad_sizes_are_rejected():
     assert _code(lambda: B.gf_attn_decode(sess.ctx, params, dpool, dt, None, od)) == B.GF_ERR_NULL
     assert _code(lambda: B.gf_set_decode_chunk_blocks(sess.ctx, 3)) == B.GF_ERR_BAD_SHAPE            # odd
     assert _code(lambda: B.gf_attn_prefill(sess.ctx, params, dpool, dt, qd, None, 5, 9, od)) == B.GF_ERR_BAD_SHAPE
-    # residual: bf16 pools only
+    # residual on an e4m3 pool needs the block scales
     fp8 = B.make_params(8, 2, 128, kv_dtype=B.GF_FP8_E4M3)
     z = torch.zeros(4, dtype=torch.int32, device=sess.device)
     z16 = torch.zeros(4, dtype=torch.int16, device=sess.device)
     assert _code(lambda: B.gf_kv_apply_residual(sess.ctx, fp8, pool.k, pool.v, pool.num_blocks, 1, z, z, z, z16, z16)) \
-        == B.GF_ERR_UNSUPPORTED
+        == B.GF_ERR_NULL
     assert _code(lambda: B.gf_kv_apply_residual(sess.ctx, params, pool.k, pool.v, pool.num_blocks, -1, z, z, z, z16,
                                                 z16)) == B.GF_ERR_BAD_SHAPE
 
