@@ -21,8 +21,9 @@
  *     synchronised inside.  Data-dependent failures are reported per request
  *     in the device array status[] (GF_ST_*), not through the return value.
  *   - The library owns only a gf_ctx: device scratch memory (the split-KV
- *     partials of gf_attn_decode, the work list of gf_attn_prefill), grown on
- *     demand -- either call may therefore call hipMalloc, and hipFree after a
+ *     partials of gf_attn_decode, the work list of gf_attn_prefill, the lists and
+ *     partials of gf_attn_decode_shared / gf_decode_shared_plan), grown on
+ *     demand -- these calls may therefore call hipMalloc, and hipFree after a
  *     stream synchronisation when it outgrows what it has -- and released by
  *     gf_destroy.  A gf_ctx must not be used from two streams at once.  Once a
  *     call has run with given sizes, repeating it allocates nothing, so a sequence
@@ -354,7 +355,8 @@ int32_t gf_attn_decode_shared_planned(gf_ctx *ctx, const gf_attn_params *params,
                                       const void *q, void *o, float *lse, void *stream);
 
 /* Tuning knob (host): table entries (16-token blocks) per split-KV chunk in
- * gf_attn_decode and gf_attn_decode_shared; 0 restores the built-in choice.  Must be even. */
+ * gf_attn_decode (built-in choice 32) and gf_attn_decode_shared (built-in choice and upper limit 64);
+ * 0 restores the built-in choice.  Must be even. */
 int32_t gf_set_decode_chunk_blocks(gf_ctx *ctx, int32_t chunk_blocks);
 
 #ifdef __cplusplus
