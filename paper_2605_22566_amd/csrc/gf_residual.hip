@@ -193,6 +193,95 @@ __global__ __launch_bounds__(kResidualThreads) void residual_e4m3_kernel(
     if (status && tid == 0) status[item] = bad_index ? GF_RS_BAD_INDEX : GF_RS_OK;
 }
 
+// The same on a block whose kv heads fit LDS side by side (HKV fp32 images): one wave per kv head, one pass.
+// K first, then V: every wave sums its image, the workgroup reduces the tensor's maximum, every wave
+// quantises and writes its image.
+template <int D, int HKV>
+__global__ __launch_bounds__(64 * HKV) void residual_e4m3_onepass_kernel(
+    uint8_t *__restrict__ k_pool, uint8_t *__restrict__ v_pool, float *__restrict__ k_scale,
+    float *__restrict__ v_scale, int num_pool_blocks, const int32_t *__restrict__ src_blocks,
+    const int32_t *__restrict__ dst_blocks, const int32_t *__restrict__ res_ptr,
+    const uint16_t *__restrict__ res_idx, const uint16_t *__restrict__ res_val, int32_t *__restrict__ status) {
+    constexpr int kImg = kBlock * D;
+    __shared__ __attribute__((aligned(16))) float lds[HKV][kImg];
+    __shared__ float red[HKV];
+    __shared__ int bad_index;
+    const int item = blockIdx.x;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int h = __builtin_amdgcn_readfirstlane(tid >> 6);       // this wave's kv head
+    const int src = src_blocks[item], dst = dst_blocks[item];
+    if (src < 0 || src >= num_pool_blocks || dst < 0 || dst >= num_pool_blocks) {
+        if (status && tid == 0) status[item] = GF_RS_BAD_BLOCK;
+        return;
+    }
+    const float src_scale[2] = {k_scale[src], v_scale[src]};      // read before the destination's are written (src may be dst)
+    if (tid == 0) bad_index = 0;
+    __syncthreads();
+    float *img = lds[h];
+    bool bad = false;
+    for (int t = 0; t < 2; ++t) {
+        uint8_t *pool = t ? v_pool : k_pool;
+        const uint8_t *g_src = pool + ((size_t)src * HKV + h) * kImg;
+        uint8_t *g_dst = pool + ((size_t)dst * HKV + h) * kImg;
+        const float s_in = src_scale[t];
+#pragma unroll
+        for (int c = 16 * lane; c < kImg; c += 16 * 64) {
+            const u32x4 w = *(const u32x4 *)(g_src + c);
+            const bf16x8 lo = fp8x8_to_bf16x8(u32x2{w[0], w[1]}), hi = fp8x8_to_bf16x8(u32x2{w[2], w[3]});
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                img[c + i] = __fmul_rn((float)lo[i], s_in);
+                img[c + 8 + i] = __fmul_rn((float)hi[i], s_in);
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        const size_t r = ((size_t)item * 2 + t) * HKV + h;
+        const int e0 = res_ptr[r], e1 = res_ptr[r + 1];
+        for (int e = e0 + lane; e < e1; e += 64) {
+            const uint32_t i = res_idx[e];
+            if (i >= (uint32_t)kImg) {
+                bad = true;
+                continue;
+            }
+            const uint32_t phys = t ? (i % D) * kBlock + i / D : i;          // V image: [d][slot]
+            img[phys] = __fadd_rn(img[phys], __uint_as_float((uint32_t)res_val[e] << 16));
+        }
+        __builtin_amdgcn_wave_barrier();
+        float m = 0.f;
+#pragma unroll 8
+        for (int c = lane; c < kImg; c += 64) m = fmaxf(m, fabsf(img[c]));
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
+        if (lane == 0) red[h] = m;
+        __syncthreads();
+        float amax = 0.f;
+#pragma unroll
+        for (int i = 0; i < HKV; ++i) amax = fmaxf(amax, red[i]);
+        const float s_out = amax > 0.f ? amax / 448.0f : 1.0f;
+        if (tid == 0) (t ? v_scale : k_scale)[dst] = s_out;
+#pragma unroll
+        for (int c = 8 * lane; c < kImg; c += 8 * 64) {
+            float x[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) x[i] = fminf(fmaxf(img[c + i] / s_out, -448.0f), 448.0f);
+            u32x2 out;
+            int w = 0;
+            w = __builtin_amdgcn_cvt_pk_fp8_f32(x[0], x[1], w, false);
+            w = __builtin_amdgcn_cvt_pk_fp8_f32(x[2], x[3], w, true);
+            out[0] = (uint32_t)w;
+            w = 0;
+            w = __builtin_amdgcn_cvt_pk_fp8_f32(x[4], x[5], w, false);
+            w = __builtin_amdgcn_cvt_pk_fp8_f32(x[6], x[7], w, true);
+            out[1] = (uint32_t)w;
+            *(u32x2 *)(g_dst + c) = out;
+        }
+        __syncthreads();                                                     // red[] and the images are reused for V
+    }
+    if (bad) bad_index = 1;                                                  // benign race: every writer stores 1
+    __syncthreads();
+    if (status && tid == 0) status[item] = bad_index ? GF_RS_BAD_INDEX : GF_RS_OK;
+}
+
 hipError_t launch_residual(void *k_pool, void *v_pool, float *k_scale, float *v_scale, int32_t num_pool_blocks,
                            int32_t hkv, int32_t head_dim, int kv_dtype, int32_t num_items, const int32_t *src_blocks,
                            const int32_t *dst_blocks, const int32_t *res_ptr, const uint16_t *res_idx,
@@ -206,13 +295,27 @@ hipError_t launch_residual(void *k_pool, void *v_pool, float *k_scale, float *v_
 #define GF_RES_E4M3(DD)                                                                                            \
     hipLaunchKernelGGL(residual_e4m3_kernel<DD>, grid, block, 0, s, (uint8_t *)k_pool, (uint8_t *)v_pool, k_scale, \
                        v_scale, num_pool_blocks, hkv, src_blocks, dst_blocks, res_ptr, res_idx, res_val, status)
-    if (head_dim == 128 && fp8) GF_RES_E4M3(128);
+#define GF_RES_ONEPASS(DD, HH)                                                                                     \
+    hipLaunchKernelGGL((residual_e4m3_onepass_kernel<DD, HH>), grid, dim3(64 * HH), 0, s, (uint8_t *)k_pool,      \
+                       (uint8_t *)v_pool, k_scale, v_scale, num_pool_blocks, src_blocks, dst_blocks, res_ptr,     \
+                       res_idx, res_val, status)
+    // e4m3: one pass when a wave per kv head and the heads' fp32 images fit a workgroup (64 KB of LDS at most)
+    if (head_dim == 128 && fp8 && hkv == 8) GF_RES_ONEPASS(128, 8);
+    else if (head_dim == 128 && fp8 && hkv == 4) GF_RES_ONEPASS(128, 4);
+    else if (head_dim == 128 && fp8 && hkv == 2) GF_RES_ONEPASS(128, 2);
+    else if (head_dim == 128 && fp8 && hkv == 1) GF_RES_ONEPASS(128, 1);
+    else if (head_dim == 64 && fp8 && hkv == 8) GF_RES_ONEPASS(64, 8);
+    else if (head_dim == 64 && fp8 && hkv == 4) GF_RES_ONEPASS(64, 4);
+    else if (head_dim == 64 && fp8 && hkv == 2) GF_RES_ONEPASS(64, 2);
+    else if (head_dim == 64 && fp8 && hkv == 1) GF_RES_ONEPASS(64, 1);
+    else if (head_dim == 128 && fp8) GF_RES_E4M3(128);
     else if (head_dim == 128) GF_RES_BF16(128);
     else if (head_dim == 64 && fp8) GF_RES_E4M3(64);
     else if (head_dim == 64) GF_RES_BF16(64);
     else return hipErrorNotSupported;
 #undef GF_RES_BF16
 #undef GF_RES_E4M3
+#undef GF_RES_ONEPASS
     return hipGetLastError();
 }
 

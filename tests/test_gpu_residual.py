@@ -130,7 +130,9 @@ def _setup_e4m3(shape, seed, last_nodes=2, **kw):
     return wl2, t, res
 
 
-@pytest.mark.parametrize("shape", [W.Shape(8, 2, 64, W.KV_FP8_E4M3), W.Shape(32, 8, 128, W.KV_FP8_E4M3)],
+# 2 and 8 kv heads take the one-pass kernel (a wave per head), 3 the two-pass one
+@pytest.mark.parametrize("shape", [W.Shape(8, 2, 64, W.KV_FP8_E4M3), W.Shape(32, 8, 128, W.KV_FP8_E4M3),
+                                   W.Shape(6, 3, 64, W.KV_FP8_E4M3), W.Shape(12, 3, 128, W.KV_FP8_E4M3)],
                          ids=lambda s: f"kv{s.num_kv_heads}d{s.head_dim}fp8")
 def test_e4m3_reconstruction_is_bit_exact_and_attention_reads_it(shape):
     wl2, t, res = _setup_e4m3(shape, 500 + shape.head_dim)
@@ -154,7 +156,11 @@ def test_e4m3_reconstruction_is_bit_exact_and_attention_reads_it(shape):
 def test_e4m3_in_place_and_bad_items():
     """Source = destination is allowed on an e4m3 pool (an image is read before it is written, the source scale
     before the destination's); bad block ids and indices are reported as on bf16 pools."""
-    shape = W.Shape(8, 2, 64, W.KV_FP8_E4M3)
+    for shape in (W.Shape(8, 2, 64, W.KV_FP8_E4M3), W.Shape(6, 3, 64, W.KV_FP8_E4M3)):      # one-pass and two-pass kernel
+        _in_place_case(shape)
+
+
+def _in_place_case(shape):
     wl = W.small_layered(61, shape, num_req=3)
     t = W.make_tensors(wl)
     rng = np.random.default_rng(62)
