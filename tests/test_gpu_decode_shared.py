@@ -132,3 +132,14 @@ def test_plan_once_then_several_layers():
     with pytest.raises(B.GraphFlowError) as e:
         sess.decode_shared_planned(pool0, other, tables, q0, torch.zeros_like(q0))
     assert e.value.code == B.GF_ERR_BAD_SHAPE
+
+
+def test_long_nodes_and_an_oversized_chunk_setting():
+    """Nodes longer than a chunk (several chunks per node, ragged last one) at the default setting, and a
+    chunk setting above the kernel's limit of 64 entries, which the call clamps."""
+    sh = W.Shape(8, 2, 128)
+    wl = W.small_layered(91, sh, num_nodes=6, num_layers=3, len_lo=1030, len_hi=2300, num_req=6, hops=(1, 3),
+                         new_lo=1, new_hi=20)
+    t = W.make_tensors(wl)
+    _check(wl, t, "long nodes, default chunk")
+    _check(wl, t, "long nodes, chunk 128 asked", chunk_blocks=128)
