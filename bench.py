@@ -39,6 +39,22 @@ def _event_ms(fn, torch, iters):
     return s.elapsed_time(e) / iters
 
 
+def _event_median_ms(fn, torch, iters, before=None):
+    """Median over `iters` launches of fn(), each between its own pair of HIP events; `before()` runs ahead of
+    every launch outside the timed pair (a cache flush, for a cold figure)."""
+    times = []
+    for _ in range(iters):
+        if before is not None:
+            before()
+        s, e = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        s.record()
+        fn()
+        e.record()
+        e.synchronize()
+        times.append(s.elapsed_time(e))
+    return float(np.median(times))
+
+
 def _read_traffic(name):
     """HBM bytes per launch from the committed rocprofv3 --pmc summary, if any."""
     p = os.path.join(ROOT, "profiles", f"{name}_traffic.txt")
@@ -221,9 +237,15 @@ def measure(job, steps, warmup):
     if job.has_prefill:
         out["prefill_ms"] = _event_ms(job.prefill, torch, it)
         out["prefill_tflops_kernel"] = job.prefill_flops() / (out["prefill_ms"] * 1e-3) / 1e12
+        out["prefill_median_ms"] = _event_median_ms(job.prefill, torch, max(it, 20))
+        # cold: L2 and the 256 MB Infinity Cache are overwritten by a 1 GiB fill before every launch
+        flush = torch.empty(1 << 28, dtype=torch.float32, device="cuda:0")
+        out["prefill_cold_median_ms"] = _event_median_ms(job.prefill, torch, 7, before=lambda: flush.fill_(1.0))
+        del flush
     if job.has_decode:
         out["decode_ms"] = _event_ms(job.decode, torch, it)
         out["decode_gbs_kernel"] = job.decode_bytes() / (out["decode_ms"] * 1e-3) / 1e9
+        out["decode_median_ms"] = _event_median_ms(job.decode, torch, max(it, 20))
         # the same step computed node by node (shared KV read once per group of requests)
         job.decode()
         job.decode_shared()
@@ -434,14 +456,17 @@ def main():
                 "peak": PEAK_MFMA_BF16_TFLOPS, "unit": "TFLOP/s",
                 "frac": m["prefill_tflops_kernel"] / PEAK_MFMA_BF16_TFLOPS,
                 "traffic": _read_traffic(f"prefill_{args.workload}"),
-                "kernel_ms": m["prefill_ms"], "algorithmic_flops_per_launch": job.prefill_flops()}
+                "kernel_ms": m["prefill_ms"], "kernel_ms_median": m["prefill_median_ms"],
+                "kernel_ms_cold_cache_median": m["prefill_cold_median_ms"],
+                "algorithmic_flops_per_launch": job.prefill_flops()}
     else:
         metric, unit = "decode_hbm_gbs", "GB/s"
         value = job.decode_bytes() / (m["ms_per_step"] * 1e-3) / 1e9
         roof = {"bound": "hbm", "kernel": "decode_split_kernel(+merge)", "achieved": m["decode_gbs_kernel"],
                 "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": m["decode_gbs_kernel"] / PEAK_HBM_GBS,
                 "traffic": _read_traffic(f"decode_{args.workload}"),
-                "kernel_ms": m["decode_ms"], "algorithmic_bytes_per_launch": job.decode_bytes()}
+                "kernel_ms": m["decode_ms"], "kernel_ms_median": m["decode_median_ms"],
+                "algorithmic_bytes_per_launch": job.decode_bytes()}
     res = {
         "metric": metric, "value": value, "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": m["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
