@@ -407,8 +407,8 @@ def cpu_baseline(job, budget_s=20.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="prefill_8b",
                     choices=["tiny", "prefill_8b", "decode_8b", "decode_70b", "mixed_fp8"])
     ap.add_argument("--decode-chunk", type=int, default=0,
