@@ -512,7 +512,7 @@ def main():
         torch.cuda.empty_cache()
     for name in names:
         j = Job(name, torch, R, W, decode_after_prefill=False)
-        mm = measure(j, max(5, args.steps // 2), 3)
+        mm = measure(j, max(5, args.steps // 2), max(3, args.warmup // 2))
         ent = {"ms_per_step": mm["ms_per_step"], "breakdown_ms": {k: v for k, v in mm.items() if k.endswith("_ms")}}
         if j.has_prefill:
             ent["prefill_tflops_kernel"] = mm["prefill_tflops_kernel"]
