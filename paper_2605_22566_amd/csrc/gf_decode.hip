@@ -133,7 +133,9 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_split_kernel(AttnArgs a
 
 // One wave per (request, query head): combine the partials of the request's
 // chunks.  m_s are in log2 units: w_s = 2^(m_s - M), L = sum w_s l_s,
-// O = sum w_s O_s / L, lse = (M + log2 L) * ln 2.
+// O = sum w_s O_s / L, lse = (M + log2 L) * ln 2.  Lanes first work chunk-parallel
+// (maximum, weights), then each lane owns D/64 output elements, the weights go
+// round by v_readlane and four chunks' loads are in flight together.
 template <int D, int G>
 __global__ __launch_bounds__(256) void decode_merge_kernel(AttnArgs a, int chunk_blocks, int splits,
                                                            const float *__restrict__ part_o,
@@ -152,15 +154,37 @@ __global__ __launch_bounds__(256) void decode_merge_kernel(AttnArgs a, int chunk
 #pragma unroll
     for (int i = 0; i < PER; ++i) acc[i] = 0.f;
     float M = -INFINITY, L = 0.f;
-    const size_t base = ((size_t)(r * a.hkv + kvh) * splits) * G + g;
-    for (int s = 0; s < ns; ++s) M = fmaxf(M, part_ml[(base + (size_t)s * G) * 2]);
-    for (int s = 0; s < ns; ++s) {
-        const size_t pi = base + (size_t)s * G;
-        const float w = fast_exp2(part_ml[pi * 2] - M);
-        L += w * part_ml[pi * 2 + 1];
+    const size_t base = ((size_t)(r * a.hkv + kvh) * splits) * G + g;     // chunk s sits at base + s * G
+    for (int s0 = 0; s0 < ns; s0 += 64)
+        if (s0 + lane < ns) M = fmaxf(M, part_ml[(base + (size_t)(s0 + lane) * G) * 2]);
 #pragma unroll
-        for (int i = 0; i < PER; ++i) acc[i] += w * part_o[pi * D + lane + 64 * i];
+    for (int off = 32; off > 0; off >>= 1) M = fmaxf(M, __shfl_xor(M, off, 64));
+    for (int s0 = 0; s0 < ns; s0 += 64) {
+        float wgt = 0.f;
+        if (s0 + lane < ns) {
+            const size_t pi = base + (size_t)(s0 + lane) * G;
+            wgt = fast_exp2(part_ml[pi * 2] - M);
+            L += wgt * part_ml[pi * 2 + 1];
+        }
+        const int m = min(64, ns - s0);
+        for (int j0 = 0; j0 < m; j0 += 4) {
+            float x[4][PER];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const size_t pj = base + (size_t)(s0 + min(j0 + u, m - 1)) * G;
+#pragma unroll
+                for (int i = 0; i < PER; ++i) x[u][i] = part_o[pj * D + lane + 64 * i];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const float wj = j0 + u < m ? __int_as_float(__builtin_amdgcn_readlane(__float_as_int(wgt), min(j0 + u, m - 1))) : 0.f;
+#pragma unroll
+                for (int i = 0; i < PER; ++i) acc[i] += wj * x[u][i];
+            }
+        }
     }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) L += __shfl_xor(L, off, 64);
     const float inv = ns > 0 ? 1.f / L : 0.f;
 #pragma unroll
     for (int i = 0; i < PER; ++i) out[lane + 64 * i] = (__bf16)(acc[i] * inv);
