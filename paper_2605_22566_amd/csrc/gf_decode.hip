@@ -60,7 +60,8 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_split_kernel(AttnArgs a
     }
 
     const float c = a.scale_log2;
-    float m_run = -1.0e30f;   // running max of raw scores (finite sentinel)
+    const float slack = 8.f / c;     // 2^8 in the exponent, in score units (inf for a zero scale)
+    float m_run = -1.0e30f;   // reference max of raw scores (finite sentinel)
     float l_run = 0.f;        // lane-local partial sum of exp
     f32x4 oacc[D / 16];
 #pragma unroll
@@ -91,12 +92,20 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_split_kernel(AttnArgs a
         }
         float mx = fmaxf(fmaxf(fmaxf(sT[0][0], sT[0][1]), fmaxf(sT[0][2], sT[0][3])),
                          fmaxf(fmaxf(sT[1][0], sT[1][1]), fmaxf(sT[1][2], sT[1][3])));
-        mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-        mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-        const float m_new = fmaxf(m_run, mx);
-        const float alpha = fast_exp2((m_run - m_new) * c);
-        const float mc = m_new * c;
-        m_run = m_new;
+        // m_run is the reference the exponentials are taken against, the same in the four lanes of a column, not
+        // the exact running maximum: it moves (and sum and values are rescaled) only when some score outgrows it
+        // by more than 2^8 in the exponent, so most steps need neither the cross-lane maximum nor the rescaling
+        if (__builtin_amdgcn_ballot_w64(mx > m_run + slack) != 0) {
+            mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float m_new = fmaxf(m_run, mx);
+            const float alpha = fast_exp2((m_run - m_new) * c);
+            m_run = m_new;
+            l_run *= alpha;
+#pragma unroll
+            for (int dt = 0; dt < D / 16; ++dt) oacc[dt] *= alpha;
+        }
+        const float mc = m_run * c;
         f32x8 p;
         float psum = 0.f;
 #pragma unroll
@@ -107,12 +116,11 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_split_kernel(AttnArgs a
                 p[4 * T + i] = e2;
                 psum += e2;
             }
-        l_run = l_run * alpha + psum;
+        l_run += psum;
         if constexpr (FP8) p *= cur.vs;              // V scale of this lane's keys rides on P; the row sum does not
         const bf16x8 pb = __builtin_convertvector(p, bf16x8);
 #pragma unroll
         for (int dt = 0; dt < D / 16; ++dt) {
-            oacc[dt] *= alpha;
             oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v_operand<D, FP8>(cur, dt), pb, oacc[dt], 0, 0, 0);
         }
         if (more) cur = nxt;
