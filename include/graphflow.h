@@ -253,6 +253,36 @@ int32_t gf_kv_apply_residual(gf_ctx *ctx, const gf_attn_params *params,
                              int32_t *status, void *stream);
 
 /*
+ * gf_attn_decode_residual -- gf_attn_decode with the sparse residuals applied
+ * while the blocks are read, instead of being reconstructed into pool blocks
+ * first (paper, "Differential-based KV Cache", Eq. 7: only the base KV of a node
+ * is stored in full; the KV under a given prefix is the base plus that prefix's
+ * sparse residual).  The pool then holds base blocks only.
+ *
+ * res_handle[r * max_blocks + e] = b in [0, num_items) makes table entry e of
+ * request r read as  block_table[r][e] + residual item b  (the CSR of
+ * gf_kv_apply_residual: rows (b * 2 + t) * num_kv_heads + h, logical element
+ * indices, bf16 values); any other value (e.g. -1) reads the base block as it
+ * is.  The sum of an element is taken in fp32 and rounded to bf16 before it is
+ * used, so the result equals, bit for bit, gf_attn_decode over a table whose
+ * entries point at blocks reconstructed by gf_kv_apply_residual.  An entry that
+ * names an element outside its image is ignored; entries that name slots at or
+ * beyond the block's token count change nothing visible (those slots are
+ * masked).  The entries of one row name distinct elements.
+ *   res_handle  [num_req][max_blocks] int32 (device, in)
+ *   res_ptr     [num_items * 2 * num_kv_heads + 1], res_idx / res_val
+ *               [res_ptr[last]] (device, in); may be NULL when num_items is 0
+ * GF_BF16 pools only (GF_ERR_UNSUPPORTED otherwise: an e4m3 block reconstructed
+ * by gf_kv_apply_residual carries a scale of its own, which no read-time sum
+ * reproduces).  Everything else as in gf_attn_decode.
+ */
+int32_t gf_attn_decode_residual(gf_ctx *ctx, const gf_attn_params *params, const gf_kv_pool *pool,
+                                const gf_tables *tables,
+                                const int32_t *res_handle, int32_t num_items,
+                                const int32_t *res_ptr, const uint16_t *res_idx, const uint16_t *res_val,
+                                const void *q, void *o, float *lse, void *stream);
+
+/*
  * gf_kv_append -- write the K/V of every request's new tokens into its private
  * tail blocks (paper, "Topology-Aware State Management": states produced at run
  * time extend the KV assembled from the operation nodes; "Effective Path

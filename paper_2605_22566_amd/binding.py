@@ -22,7 +22,7 @@ GF_BF16, GF_FP8_E4M3 = 0, 1
 GF_RS_OK, GF_RS_BAD_BLOCK, GF_RS_BAD_INDEX = 0, 1, 2
 
 EXPORTS = ["gf_create", "gf_destroy", "gf_strerror", "gf_last_hip_error", "gf_resolve_path",
-           "gf_attn_prefill", "gf_attn_decode", "gf_attn_decode_shared", "gf_decode_shared_plan", "gf_attn_decode_shared_planned",
+           "gf_attn_prefill", "gf_attn_decode", "gf_attn_decode_residual", "gf_attn_decode_shared", "gf_decode_shared_plan", "gf_attn_decode_shared_planned",
            "gf_set_decode_chunk_blocks", "gf_kv_apply_residual",
            "gf_kv_append", "gf_kv_append_token"]
 
@@ -89,6 +89,9 @@ def load_library(path: Optional[str] = None):
     lib.gf_attn_decode.argtypes = [C.c_void_p, C.POINTER(gf_attn_params), C.POINTER(gf_kv_pool),
                                    C.POINTER(gf_tables), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.gf_attn_decode.restype = C.c_int32
+    lib.gf_attn_decode_residual.argtypes = [C.c_void_p, C.POINTER(gf_attn_params), C.POINTER(gf_kv_pool),
+                                            C.POINTER(gf_tables), C.c_void_p, C.c_int32] + [C.c_void_p] * 7
+    lib.gf_attn_decode_residual.restype = C.c_int32
     lib.gf_attn_decode_shared.argtypes = [C.c_void_p, C.POINTER(gf_attn_params), C.POINTER(gf_kv_pool),
                                           C.POINTER(gf_graph), C.c_void_p, C.c_void_p, C.c_int32,
                                           C.POINTER(gf_tables), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -186,6 +189,14 @@ def gf_attn_prefill(ctx, params, pool, tables, q, q_ptr, total_q, max_q, o, lse=
 def gf_attn_decode(ctx, params, pool, tables, q, o, lse=None) -> None:
     rc = load_library().gf_attn_decode(ctx, C.byref(params), C.byref(pool), C.byref(tables), _ptr(q),
                                        _ptr(o), _ptr(lse), _stream())
+    _check(ctx, rc)
+
+
+def gf_attn_decode_residual(ctx, params, pool, tables, res_handle, num_items, res_ptr, res_idx, res_val, q, o,
+                            lse=None) -> None:
+    rc = load_library().gf_attn_decode_residual(ctx, C.byref(params), C.byref(pool), C.byref(tables), _ptr(res_handle),
+                                                num_items, _ptr(res_ptr), _ptr(res_idx), _ptr(res_val), _ptr(q),
+                                                _ptr(o), _ptr(lse), _stream())
     _check(ctx, rc)
 
 

@@ -226,6 +226,34 @@ int32_t gf_attn_decode(gf_ctx *ctx, const gf_attn_params *params, const gf_kv_po
     return GF_OK;
 }
 
+int32_t gf_attn_decode_residual(gf_ctx *ctx, const gf_attn_params *params, const gf_kv_pool *pool,
+                                const gf_tables *tables, const int32_t *res_handle, int32_t num_items,
+                                const int32_t *res_ptr, const uint16_t *res_idx, const uint16_t *res_val,
+                                const void *q, void *o, float *lse, void *stream) {
+    if (!ctx) return GF_ERR_NULL;
+    gf::AttnArgs a;
+    int group = 0;
+    int32_t rc = check_attn(params, pool, tables, q, o, lse, a, group);
+    if (rc != GF_OK) return rc;
+    if (num_items < 0) return GF_ERR_BAD_SHAPE;
+    if (params->kv_dtype != GF_BF16) return GF_ERR_UNSUPPORTED;
+    if (tables->num_req == 0) return GF_OK;
+    if (!res_handle || (num_items > 0 && (!res_ptr || !res_idx || !res_val))) return GF_ERR_NULL;
+    int32_t chunk = ctx->decode_chunk_blocks;
+    if (chunk <= 0) chunk = 32;
+    const int32_t splits = (tables->max_blocks + chunk - 1) / chunk;
+    const size_t need = gf::decode_workspace_bytes(a.num_req, a.hkv, group, params->head_dim, splits);
+    rc = ensure_buffer(ctx, &ctx->workspace, &ctx->workspace_bytes, need, (hipStream_t)stream,
+                       "gf_attn_decode_residual workspace");
+    if (rc != GF_OK) return rc;
+    const gf::ResidualRefs rr = {res_handle, res_ptr, res_idx, res_val, num_items};
+    hipError_t e = gf::launch_decode_residual(a, rr, params->head_dim, group, params->kv_dtype, chunk, splits,
+                                              ctx->workspace, (hipStream_t)stream);
+    if (e == hipErrorNotSupported) return GF_ERR_UNSUPPORTED;
+    if (e != hipSuccess) return fail_hip(ctx, e, "gf_attn_decode_residual launch");
+    return GF_OK;
+}
+
 // The three node-centric entry points: list building, attention over built lists, or both.
 static int32_t decode_shared_call(gf_ctx *ctx, const gf_attn_params *params, const gf_kv_pool *pool,
                                   const gf_graph *graph, const int32_t *path_ptr, const int32_t *path_nodes,

@@ -26,10 +26,14 @@ namespace gf {
 constexpr int kDecodeThreads = 256;          // 4 independent waves
 constexpr int kWavesPerWg = kDecodeThreads / 64;
 
-template <int D, int G, bool FP8>
+// RES: table entries may carry a residual handle (ResidualRefs); a pair with one is patched in the wave's LDS
+// image before it is reduced (patch_pair), every other pair takes the plain path.
+template <int D, int G, bool FP8, bool RES = false>
 __global__ __launch_bounds__(kDecodeThreads) void decode_split_kernel(AttnArgs a, int chunk_blocks, int splits,
                                                                      float *__restrict__ part_o,
-                                                                     float *__restrict__ part_ml) {
+                                                                     float *__restrict__ part_ml,
+                                                                     ResidualRefs rr = ResidualRefs{}) {
+    static_assert(!(RES && FP8), "residuals are applied on the fly to bf16 pools only");
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int pairs = a.num_req * a.hkv;
@@ -67,11 +71,34 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_split_kernel(AttnArgs a
 #pragma unroll
     for (int dt = 0; dt < D / 16; ++dt) oacc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+    // residual handles of the pair in `cur` / `nxt` (-1: none, also for ids outside the CSR)
+    const int32_t *rh = RES ? rr.handle + (size_t)r * a.max_blocks : nullptr;
+    auto handle_of = [&](int e) -> int {
+        if (e >= e1) return -1;
+        const int h = rh[e];
+        return h >= 0 && h < rr.num_items ? h : -1;
+    };
+    int h0 = -1, h1 = -1, h0n = -1, h1n = -1;
+    if constexpr (RES) {
+        h0 = handle_of(e0);
+        h1 = handle_of(e0 + 1);
+    }
+
     PairRegs<D, FP8> cur, nxt;
     load_pair(cur, a, tab, ntk, e0, e1, kvh, lane);
     for (int e = e0; e < e1; e += 2) {
         const bool more = e + 2 < e1;
         if (more) load_pair(nxt, a, tab, ntk, e + 2, e1, kvh, lane);
+        if constexpr (RES) {
+            if (more) {
+                h0n = handle_of(e + 2);
+                h1n = handle_of(e + 3);
+            }
+            if (h0 >= 0 || h1 >= 0) {
+                __shared__ __attribute__((aligned(16))) uint16_t patch_img[kWavesPerWg][2 * kBlock * D];
+                patch_pair<D>(cur, patch_img[wave], rr, h0, h1, kvh, a.hkv, lane);
+            }
+        }
 
         f32x4 sT[2];
 #pragma unroll
@@ -124,6 +151,10 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_split_kernel(AttnArgs a
             oacc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(v_operand<D, FP8>(cur, dt), pb, oacc[dt], 0, 0, 0);
         }
         if (more) cur = nxt;
+        if constexpr (RES) {
+            h0 = h0n;
+            h1 = h1n;
+        }
     }
 
     l_run += __shfl_xor(l_run, 16, 64);
@@ -223,6 +254,35 @@ static hipError_t launch_decode_t(const AttnArgs &a, int kv_dtype, int32_t chunk
     hipLaunchKernelGGL((decode_merge_kernel<D, G>), dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, a,
                        chunk_blocks, splits, part_o, part_ml);
     return hipGetLastError();
+}
+
+template <int D, int G>
+static hipError_t launch_decode_residual_t(const AttnArgs &a, const ResidualRefs &rr, int32_t chunk_blocks,
+                                           int32_t splits, void *workspace, hipStream_t s) {
+    const size_t n_items = (size_t)a.num_req * a.hkv * splits;
+    float *part_o = (float *)workspace;
+    float *part_ml = part_o + n_items * G * D;
+    const unsigned grid = (unsigned)((n_items + kWavesPerWg - 1) / kWavesPerWg);
+    hipLaunchKernelGGL((decode_split_kernel<D, G, false, true>), dim3(grid), dim3(kDecodeThreads), 0, s, a,
+                       chunk_blocks, splits, part_o, part_ml, rr);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    const size_t rows = (size_t)a.num_req * a.hq;
+    hipLaunchKernelGGL((decode_merge_kernel<D, G>), dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, a,
+                       chunk_blocks, splits, part_o, part_ml);
+    return hipGetLastError();
+}
+
+hipError_t launch_decode_residual(const AttnArgs &a, const ResidualRefs &rr, int head_dim, int group, int kv_dtype,
+                                  int32_t chunk_blocks, int32_t splits, void *workspace, hipStream_t s) {
+    if (kv_dtype != GF_BF16) return hipErrorNotSupported;
+    if (a.num_req == 0) return hipSuccess;
+#define GF_CASE(DD, GG) \
+    if (head_dim == DD && group == GG) return launch_decode_residual_t<DD, GG>(a, rr, chunk_blocks, splits, workspace, s);
+    GF_CASE(64, 1) GF_CASE(64, 2) GF_CASE(64, 4) GF_CASE(64, 8)
+    GF_CASE(128, 1) GF_CASE(128, 2) GF_CASE(128, 4) GF_CASE(128, 8)
+#undef GF_CASE
+    return hipErrorNotSupported;
 }
 
 hipError_t launch_decode(const AttnArgs &a, int head_dim, int group, int kv_dtype, int32_t chunk_blocks,

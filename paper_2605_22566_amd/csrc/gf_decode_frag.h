@@ -1,5 +1,6 @@
 // Operand fragments of the per-request decode kernel: two pool blocks (32 keys) of one kv head, loaded from
-// HBM straight into the registers the 16x16x32 MFMAs read (see gf_decode.hip for the geometry).
+// HBM straight into the registers the 16x16x32 MFMAs read (see gf_decode.hip for the geometry), and the
+// on-the-fly application of sparse residuals to such a pair.
 #pragma once
 #include "gf_internal.h"
 
@@ -92,6 +93,76 @@ __device__ __forceinline__ void load_pair(PairRegs<D, true> &p, const AttnArgs &
         p.v[dt] = *(const u32x2 *)(vb + (size_t)(16 * dt + m) * kBlock + (q4 & 1) * 8);
     p.ks = a.k_scale[(q4 >= 2) ? b1 : b0];
     p.vs = a.v_scale[(q4 >= 2) ? b1 : b0];
+}
+
+// Differential KV (paper, "Differential-based KV Cache", Eq. 7) applied to a loaded pair of a bf16 pool: the
+// fragments go to the wave's LDS image `img` (2 * 16 * D elements: the two blocks back to back), the residual
+// entries of the blocks that have one (items h0 / h1 of the CSR, -1 = none) are added there -- fp32 sum rounded to
+// bf16, the arithmetic of gf_kv_apply_residual, so the operands equal a reconstructed block bit for bit -- and the
+// fragments are read back; first K, then V through the same image.  K rows keep the pool's [slot][d] order with the
+// 16-byte pieces of a row XOR-ed by the slot (fragment stores and loads then spread over the banks); V keeps
+// [d][slot].  Entries outside the image are ignored.  The LDS operations of one wave complete in order.
+// orders the LDS accesses of a wave's lanes before and after this point (for the compiler: a fence at
+// wavefront scope; the hardware runs one wave's LDS operations in order)
+__device__ __forceinline__ void wave_lds_order() {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
+template <int D>
+__device__ __forceinline__ void add_entries(uint16_t *img, const ResidualRefs &rr, int item, int tensor, int kvh,
+                                            int hkv, int lane) {
+    constexpr int kImg = kBlock * D;
+    const size_t row = ((size_t)item * 2 + tensor) * hkv + kvh;
+    const int e0 = rr.ptr[row], e1 = rr.ptr[row + 1];
+    for (int e = e0 + lane; e < e1; e += 64) {
+        const uint32_t i = rr.idx[e];
+        if (i >= (uint32_t)kImg) continue;
+        const uint32_t slot = i / D, d = i % D;
+        const uint32_t phys = tensor ? d * kBlock + slot : slot * D + ((((d >> 3) ^ slot) & (D / 8 - 1)) << 3) + (d & 7);
+        const float base = __uint_as_float((uint32_t)img[phys] << 16);
+        const float delta = __uint_as_float((uint32_t)rr.val[e] << 16);
+        const __bf16 sum = (__bf16)(base + delta);                       // round to nearest even
+        img[phys] = __builtin_bit_cast(uint16_t, sum);
+    }
+}
+
+template <int D>
+__device__ __forceinline__ void patch_pair(PairRegs<D, false> &p, uint16_t *img, const ResidualRefs &rr, int h0, int h1,
+                                           int kvh, int hkv, int lane) {
+    constexpr int kImg = kBlock * D;
+    const int m = lane & 15, q4 = lane >> 4;
+    uint16_t *kimg = img + (m >= 8 ? kImg : 0);
+    const int slot0 = 8 * ((m >> 2) & 1) + (m & 3);
+#pragma unroll
+    for (int T = 0; T < 2; ++T)
+#pragma unroll
+        for (int t = 0; t < D / 32; ++t) {
+            const int slot = slot0 + 4 * T;
+            *(u32x4 *)(kimg + slot * D + ((((4 * t + q4) ^ slot) & (D / 8 - 1)) << 3)) = p.k[T][t];
+        }
+    wave_lds_order();
+    if (h0 >= 0) add_entries<D>(img, rr, h0, 0, kvh, hkv, lane);
+    if (h1 >= 0) add_entries<D>(img + kImg, rr, h1, 0, kvh, hkv, lane);
+    wave_lds_order();
+#pragma unroll
+    for (int T = 0; T < 2; ++T)
+#pragma unroll
+        for (int t = 0; t < D / 32; ++t) {
+            const int slot = slot0 + 4 * T;
+            p.k[T][t] = *(const u32x4 *)(kimg + slot * D + ((((4 * t + q4) ^ slot) & (D / 8 - 1)) << 3));
+        }
+    wave_lds_order();
+    uint16_t *vimg = img + (q4 >= 2 ? kImg : 0);
+#pragma unroll
+    for (int dt = 0; dt < D / 16; ++dt) *(u32x4 *)(vimg + (16 * dt + m) * kBlock + (q4 & 1) * 8) = p.v[dt];
+    wave_lds_order();
+    if (h0 >= 0) add_entries<D>(img, rr, h0, 1, kvh, hkv, lane);
+    if (h1 >= 0) add_entries<D>(img + kImg, rr, h1, 1, kvh, hkv, lane);
+    wave_lds_order();
+#pragma unroll
+    for (int dt = 0; dt < D / 16; ++dt) p.v[dt] = *(const u32x4 *)(vimg + (16 * dt + m) * kBlock + (q4 & 1) * 8);
+    wave_lds_order();
 }
 
 template <int D, bool FP8>

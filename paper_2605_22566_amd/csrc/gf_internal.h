@@ -31,6 +31,15 @@ struct AttnArgs {
     float *lse;
 };
 
+// Sparse residuals applied while a decode step streams the pool (same CSR as gf_kv_apply_residual): table entry
+// (request, e) with handle[request * max_blocks + e] = b in [0, num_items) is read as base block + residual item b.
+struct ResidualRefs {
+    const int32_t *handle;
+    const int32_t *ptr;
+    const uint16_t *idx, *val;
+    int32_t num_items;
+};
+
 // launchers (return hipError_t of the launch)
 hipError_t launch_resolve(const gf_graph &g, int32_t num_req, const int32_t *path_ptr,
                           const int32_t *path_nodes, const int32_t *new_lens, const int32_t *tail_ptr,
@@ -47,6 +56,9 @@ hipError_t launch_prefill(const AttnArgs &a, int head_dim, int group, int kv_dty
 size_t decode_workspace_bytes(int32_t num_req, int32_t hkv, int32_t group, int32_t head_dim, int32_t splits);
 hipError_t launch_decode(const AttnArgs &a, int head_dim, int group, int kv_dtype, int32_t chunk_blocks,
                          int32_t splits, void *workspace, hipStream_t s);
+// the same step with residuals applied on the fly (bf16 pools; hipErrorNotSupported otherwise)
+hipError_t launch_decode_residual(const AttnArgs &a, const ResidualRefs &rr, int head_dim, int group, int kv_dtype,
+                                  int32_t chunk_blocks, int32_t splits, void *workspace, hipStream_t s);
 
 // node-centric decode: workspace bytes and the launcher (list building + node, tail and merge kernels)
 size_t shared_workspace_bytes(int32_t num_nodes, int32_t num_req, int32_t num_entries, int32_t max_blocks,

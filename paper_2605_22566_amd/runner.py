@@ -195,6 +195,13 @@ class Session:
         params, dpool, dt = self._common(pool, tables, sm_scale)
         B.gf_attn_decode(self.ctx, params, dpool, dt, q, o, lse)
 
+    def decode_residual(self, pool, tables, res_handle, dres, q, o, lse=None, sm_scale=0.0):
+        """Decode with residuals applied as the blocks are read: `res_handle` [R, max_blocks] int32 names, per table
+        entry, an item of the uploaded residual `dres` (upload_residual) or -1."""
+        params, dpool, dt = self._common(pool, tables, sm_scale)
+        B.gf_attn_decode_residual(self.ctx, params, dpool, dt, res_handle, dres["num_items"], dres["ptr"], dres["idx"],
+                                  dres["val"], q, o, lse)
+
     def decode_shared(self, pool, dbatch, tables, q, o, lse=None, sm_scale=0.0):
         """Node-centric decode; `dbatch` is the uploaded batch `tables` was resolved from."""
         params, dpool, dt = self._common(pool, tables, sm_scale)

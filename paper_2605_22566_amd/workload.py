@@ -517,6 +517,21 @@ def add_residual_instances(wl: Workload, last_nodes: int = 1, density_k: float =
     return wl2, res
 
 
+def residual_handles(base_table: np.ndarray, inst_table: np.ndarray, res: Residuals) -> np.ndarray:
+    """Per-table-entry residual handles for the read-time form: `base_table` is the block table resolved on the
+    workload WITHOUT instances, `inst_table` the one resolved on add_residual_instances' workload (same shape: an
+    instance has its base node's length).  Where the two differ the entry is an instance block, and its handle is
+    the residual item that writes that block; -1 everywhere else."""
+    item_of = {int(d): i for i, d in enumerate(res.dst_blocks)}
+    h = np.full(base_table.shape, -1, np.int32)
+    rr, ee = np.nonzero(base_table != inst_table)
+    for r, e in zip(rr, ee):
+        item = item_of[int(inst_table[r, e])]
+        assert int(res.src_blocks[item]) == int(base_table[r, e])
+        h[r, e] = item
+    return h
+
+
 # --------------------------------------------------------------------------- #
 # accounting (pure counting; used by bench and docs)
 # --------------------------------------------------------------------------- #
