@@ -279,6 +279,44 @@ def decode_shared_entry(job, m):
             "hbm_bytes_per_launch_rocprof": _read_traffic(f"decode_shared_{job.name}")}
 
 
+def measure_decode_residual(job, decode_ms, share=0.25, iters=20):
+    """gf_attn_decode_residual beside gf_attn_decode on the same decode step: the last `share` of every request's
+    table entries are read as base block + a residual item of their own (25 % of the K and 30 % of the V elements,
+    the density the paper reports), the pool holding base blocks only.  bf16 pools."""
+    torch, R, W = job.torch, job.R, job.W
+    sh = job.wl.shape
+    if sh.kv_dtype != W.KV_BF16:
+        return None
+    lo, hi = job.dec_rng
+    t = job._slice(lo, hi)
+    dev = job.qd.device
+    nb = t["num_blocks"].to(torch.int64)
+    first = nb - (nb.to(torch.float64) * share).to(torch.int64)
+    ar = torch.arange(job.max_blocks, device=dev)[None, :]
+    mask = (ar >= first[:, None]) & (ar < nb[:, None])
+    num_items = int(mask.sum().item())
+    handles = torch.full(mask.shape, -1, dtype=torch.int32, device=dev)
+    handles[mask] = torch.arange(num_items, dtype=torch.int32, device=dev)
+    dres, nnz = R.random_residuals(sh, num_items, dev)
+    o = torch.zeros_like(job.od[lo:hi])
+    fn = lambda: job.sess.decode_residual(job.pool, t, handles, dres, job.qd[lo:hi], o)
+    for _ in range(3):
+        fn()
+    torch.cuda.synchronize()
+    ms = _event_ms(fn, torch, iters)
+    changed = float((o.float() - job.od[lo:hi].float()).abs().max().item())
+    blk = 2 * sh.num_kv_heads * W.BLOCK * sh.head_dim * 2
+    nbytes = job.decode_bytes() + 4.0 * nnz + 4.0 * handles.numel() + 4.0 * 2 * sh.num_kv_heads * num_items
+    return {"kernel": "decode_split_kernel<RES>(+merge)", "kernel_ms": ms, "decode_ms": decode_ms,
+            "slowdown_over_decode": ms / decode_ms, "entries_with_residual": num_items,
+            "share_of_table_entries": num_items / max(1.0, float(nb.sum().item())), "residual_entries": nnz,
+            "algorithmic_bytes_per_launch": nbytes, "gbs_kernel": nbytes / (ms * 1e-3) / 1e9,
+            "frac_of_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+            # what the pool does not hold: the reconstructed copies of these blocks, against the sparse form kept
+            "dense_instance_bytes": float(num_items) * blk, "sparse_residual_bytes": 4.0 * nnz,
+            "max_abs_diff_to_base_decode": changed}
+
+
 def measure_stream_copy(torch, iters=10):
     """What a plain device-to-device copy of 1 GiB reaches on this machine (bytes read + bytes written
     per second): the practical streaming ceiling next to the 8 TB/s on paper."""
@@ -526,6 +564,9 @@ def main():
             ent["unique_bytes_time_bound_ms"] = ent["unique_kv_bytes"] / (PEAK_HBM_GBS * 1e9) * 1e3
             ent["hbm_bytes_per_launch_rocprof"] = _read_traffic(f"decode_{name}")
             ent["decode_shared"] = decode_shared_entry(j, mm)
+            dr = measure_decode_residual(j, mm["decode_ms"])
+            if dr is not None:
+                ent["decode_residual"] = dr
         extra[name] = ent
         del j
         torch.cuda.empty_cache()

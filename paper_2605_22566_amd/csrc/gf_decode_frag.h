@@ -109,21 +109,75 @@ __device__ __forceinline__ void wave_lds_order() {
     __builtin_amdgcn_wave_barrier();
 }
 
+// one residual entry: logical element i of the image (slot * D + d), bf16 bits in the low half of `bits`
+template <int D>
+__device__ __forceinline__ void add_entry(uint16_t *img, int tensor, uint32_t i, uint32_t bits) {
+    if (i >= (uint32_t)(kBlock * D)) return;
+    const uint32_t slot = i / D, d = i % D;
+    const uint32_t phys = tensor ? d * kBlock + slot : slot * D + ((((d >> 3) ^ slot) & (D / 8 - 1)) << 3) + (d & 7);
+    const float base = __uint_as_float((uint32_t)img[phys] << 16);
+    const float delta = __uint_as_float(bits << 16);
+    const __bf16 sum = (__bf16)(base + delta);                           // round to nearest even
+    img[phys] = __builtin_bit_cast(uint16_t, sum);
+}
+
+// A CSR row is read 8 entries (16 bytes of indices, 16 of values) per lane where the row covers whole aligned
+// groups of 8, and entry by entry at its two ends; all those loads are issued before the first sum, so a row of
+// the paper's density (about 512 of 2048 elements) costs one memory round trip, not one per 64 entries.
 template <int D>
 __device__ __forceinline__ void add_entries(uint16_t *img, const ResidualRefs &rr, int item, int tensor, int kvh,
                                             int hkv, int lane) {
-    constexpr int kImg = kBlock * D;
     const size_t row = ((size_t)item * 2 + tensor) * hkv + kvh;
     const int e0 = rr.ptr[row], e1 = rr.ptr[row + 1];
-    for (int e = e0 + lane; e < e1; e += 64) {
-        const uint32_t i = rr.idx[e];
-        if (i >= (uint32_t)kImg) continue;
-        const uint32_t slot = i / D, d = i % D;
-        const uint32_t phys = tensor ? d * kBlock + slot : slot * D + ((((d >> 3) ^ slot) & (D / 8 - 1)) << 3) + (d & 7);
-        const float base = __uint_as_float((uint32_t)img[phys] << 16);
-        const float delta = __uint_as_float((uint32_t)rr.val[e] << 16);
-        const __bf16 sum = (__bf16)(base + delta);                       // round to nearest even
-        img[phys] = __builtin_bit_cast(uint16_t, sum);
+    const bool vec = (((uintptr_t)rr.idx | (uintptr_t)rr.val) & 15) == 0;
+    const int a0 = vec ? min(e1, (e0 + 7) & ~7) : e1;        // [e0, a0) and [a1, e1): single entries
+    const int a1 = vec ? a0 + ((e1 - a0) & ~7) : e1;         // [a0, a1): aligned groups of 8
+    const int head = a0 - e0, singles = head + (e1 - a1);
+    const int es = lane < head ? e0 + lane : a1 + (lane - head);
+    uint32_t si = 0xFFFFFFFFu, sv = 0;
+    if (lane < singles) {
+        si = rr.idx[es];
+        sv = rr.val[es];
+    }
+    int g = a0 + 8 * lane;
+    u32x4 gi = {0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu}, gv = {0, 0, 0, 0};
+    if (g < a1) {
+        gi = *(const u32x4 *)(rr.idx + g);
+        gv = *(const u32x4 *)(rr.val + g);
+    }
+    add_entry<D>(img, tensor, si, sv);
+    for (int s = lane + 64; s < singles; s += 64) {          // only without the 16-byte alignment
+        const int e = s < head ? e0 + s : a1 + (s - head);
+        add_entry<D>(img, tensor, rr.idx[e], rr.val[e]);
+    }
+    while (true) {
+        // the 8 elements are distinct (contract of the CSR), so all are read before any is written
+        uint32_t phys[8];
+        uint16_t sum[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const uint32_t i = (gi[j / 2] >> (16 * (j % 2))) & 0xFFFFu;   // 0xFFFF (no load) is outside every image
+            const uint32_t slot = i / D, d = i % D;
+            phys[j] = i >= (uint32_t)(kBlock * D) ? 0xFFFFFFFFu
+                      : tensor ? d * kBlock + slot
+                               : slot * D + ((((d >> 3) ^ slot) & (D / 8 - 1)) << 3) + (d & 7);
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const float base = phys[j] != 0xFFFFFFFFu ? __uint_as_float((uint32_t)img[phys[j]] << 16) : 0.f;
+            const float delta = __uint_as_float((gv[j / 2] >> (16 * (j % 2))) << 16);
+            sum[j] = __builtin_bit_cast(uint16_t, (__bf16)(base + delta));
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            if (phys[j] != 0xFFFFFFFFu) img[phys[j]] = sum[j];
+        g += 512;
+        if (__builtin_amdgcn_ballot_w64(g < a1) == 0) break;
+        gi = u32x4{0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu};
+        if (g < a1) {
+            gi = *(const u32x4 *)(rr.idx + g);
+            gv = *(const u32x4 *)(rr.val + g);
+        }
     }
 }
 

@@ -35,12 +35,16 @@ def _case(shape, seed, last_nodes=2, num_req=5, len_hi=90, **kw):
     return wl, wl2, t, res, k2, v2, inst_tab, handles
 
 
-def _decode_fused(wl, t, res, handles, chunk_blocks=0, sm_scale=0.0):
+def _decode_fused(wl, t, res, handles, chunk_blocks=0, sm_scale=0.0, misalign=False):
     sess, tables = run_resolve(wl)
     dev = sess.device
     B.gf_set_decode_chunk_blocks(sess.ctx, chunk_blocks)
     pool = R.DevicePool.from_host(t, dev)
     dres = sess.upload_residuals(res)
+    if misalign:      # entry arrays that do not start on a 16-byte boundary take the entry-by-entry path
+        for key in ("idx", "val"):
+            dres[key] = torch.cat([torch.zeros(3, dtype=dres[key].dtype, device=dev), dres[key]])[3:]
+            assert dres[key].data_ptr() % 16 != 0
     dh = torch.from_numpy(np.ascontiguousarray(handles)).to(dev)
     last = (t.q_ptr[1:] - 1).astype(np.int64)
     qd = R.bits_to_device(np.ascontiguousarray(t.q[last]), dev)
@@ -81,6 +85,9 @@ def test_read_time_residual_matches_oracle_and_the_two_step_form(shape, chunk):
     o2, lse2 = _decode_two_step(wl2, t, k2, v2, res, chunk)
     assert torch.equal(o.view(torch.int16), o2.view(torch.int16))
     assert torch.equal(lse.view(torch.int32), lse2.view(torch.int32))
+    o3, lse3, _ = _decode_fused(wl, t, res, handles, chunk, misalign=True)
+    assert torch.equal(o3.view(torch.int16), o2.view(torch.int16))
+    assert torch.equal(lse3.view(torch.int32), lse2.view(torch.int32))
 
 
 def test_residual_changes_the_result_and_no_handles_is_plain_decode():
