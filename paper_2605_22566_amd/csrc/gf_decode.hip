@@ -29,7 +29,7 @@ constexpr int kWavesPerWg = kDecodeThreads / 64;
 // RES: table entries may carry a residual handle (ResidualRefs); a pair with one is patched in the wave's LDS
 // image before it is reduced (patch_pair), every other pair takes the plain path.
 template <int D, int G, bool FP8, bool RES = false>
-__global__ __launch_bounds__(kDecodeThreads) void decode_split_kernel(AttnArgs a, int chunk_blocks, int splits,
+__global__ __launch_bounds__(kDecodeThreads, RES ? 2 : 1) void decode_split_kernel(AttnArgs a, int chunk_blocks, int splits,
                                                                      float *__restrict__ part_o,
                                                                      float *__restrict__ part_ml,
                                                                      ResidualRefs rr = ResidualRefs{}) {
@@ -78,10 +78,14 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_split_kernel(AttnArgs a
         const int h = rh[e];
         return h >= 0 && h < rr.num_items ? h : -1;
     };
+    // ... and the entry ranges of their four CSR rows, fetched a pair ahead like the blocks themselves
     int h0 = -1, h1 = -1, h0n = -1, h1n = -1;
+    int rows[8] = {0, 0, 0, 0, 0, 0, 0, 0}, rows_n[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     if constexpr (RES) {
         h0 = handle_of(e0);
         h1 = handle_of(e0 + 1);
+        row_ranges(rr, h0, kvh, a.hkv, rows);
+        row_ranges(rr, h1, kvh, a.hkv, rows + 4);
     }
 
     PairRegs<D, FP8> cur, nxt;
@@ -93,10 +97,12 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_split_kernel(AttnArgs a
             if (more) {
                 h0n = handle_of(e + 2);
                 h1n = handle_of(e + 3);
+                row_ranges(rr, h0n, kvh, a.hkv, rows_n);
+                row_ranges(rr, h1n, kvh, a.hkv, rows_n + 4);
             }
             if (h0 >= 0 || h1 >= 0) {
                 __shared__ __attribute__((aligned(16))) uint16_t patch_img[kWavesPerWg][2 * kBlock * D];
-                patch_pair<D>(cur, patch_img[wave], rr, h0, h1, kvh, a.hkv, lane);
+                patch_pair<D>(cur, patch_img[wave], rr, rows, lane);
             }
         }
 
@@ -154,6 +160,8 @@ __global__ __launch_bounds__(kDecodeThreads) void decode_split_kernel(AttnArgs a
         if constexpr (RES) {
             h0 = h0n;
             h1 = h1n;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) rows[i] = rows_n[i];
         }
     }
 

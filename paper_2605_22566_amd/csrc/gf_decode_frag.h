@@ -121,70 +121,101 @@ __device__ __forceinline__ void add_entry(uint16_t *img, int tensor, uint32_t i,
     img[phys] = __builtin_bit_cast(uint16_t, sum);
 }
 
-// A CSR row is read 8 entries (16 bytes of indices, 16 of values) per lane where the row covers whole aligned
-// groups of 8, and entry by entry at its two ends; all those loads are issued before the first sum, so a row of
-// the paper's density (about 512 of 2048 elements) costs one memory round trip, not one per 64 entries.
+// The four CSR rows of a pair (K and V of the two blocks) as entry ranges: [2i], [2i+1] = first and end entry of
+// row i in the order K0, V0, K1, V1; an absent residual (item < 0) gives empty rows.  Wave-uniform values.
+__device__ __forceinline__ void row_ranges(const ResidualRefs &rr, int item, int kvh, int hkv, int *out) {
+    out[0] = out[1] = out[2] = out[3] = 0;
+    if (item < 0) return;
+    const int32_t *pk = rr.ptr + ((size_t)item * 2 + 0) * hkv + kvh;
+    const int32_t *pv = rr.ptr + ((size_t)item * 2 + 1) * hkv + kvh;
+    out[0] = pk[0];
+    out[1] = pk[1];
+    out[2] = pv[0];
+    out[3] = pv[1];
+}
+
+// A CSR row in flight.  It is read 8 entries (16 bytes of indices, 16 of values) per lane where it covers whole
+// aligned groups of 8, and entry by entry at its two ends (or everywhere, if the arrays do not start on a
+// 16-byte boundary); issue() starts the loads of the ends and of the first 512 grouped entries, apply() adds them
+// into the image and walks the rest of a longer row.  The two K rows of a pair are issued together, then the two
+// V rows, so a pair of the paper's density (about a quarter of the 2048 elements of an image) costs two memory
+// round trips (the row ranges come a pair ahead).
 template <int D>
-__device__ __forceinline__ void add_entries(uint16_t *img, const ResidualRefs &rr, int item, int tensor, int kvh,
-                                            int hkv, int lane) {
-    const size_t row = ((size_t)item * 2 + tensor) * hkv + kvh;
-    const int e0 = rr.ptr[row], e1 = rr.ptr[row + 1];
-    const bool vec = (((uintptr_t)rr.idx | (uintptr_t)rr.val) & 15) == 0;
-    const int a0 = vec ? min(e1, (e0 + 7) & ~7) : e1;        // [e0, a0) and [a1, e1): single entries
-    const int a1 = vec ? a0 + ((e1 - a0) & ~7) : e1;         // [a0, a1): aligned groups of 8
-    const int head = a0 - e0, singles = head + (e1 - a1);
-    const int es = lane < head ? e0 + lane : a1 + (lane - head);
-    uint32_t si = 0xFFFFFFFFu, sv = 0;
-    if (lane < singles) {
-        si = rr.idx[es];
-        sv = rr.val[es];
-    }
-    int g = a0 + 8 * lane;
-    u32x4 gi = {0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu}, gv = {0, 0, 0, 0};
-    if (g < a1) {
-        gi = *(const u32x4 *)(rr.idx + g);
-        gv = *(const u32x4 *)(rr.val + g);
-    }
-    add_entry<D>(img, tensor, si, sv);
-    for (int s = lane + 64; s < singles; s += 64) {          // only without the 16-byte alignment
-        const int e = s < head ? e0 + s : a1 + (s - head);
-        add_entry<D>(img, tensor, rr.idx[e], rr.val[e]);
-    }
-    while (true) {
-        // the 8 elements are distinct (contract of the CSR), so all are read before any is written
-        uint32_t phys[8];
-        uint16_t sum[8];
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const uint32_t i = (gi[j / 2] >> (16 * (j % 2))) & 0xFFFFu;   // 0xFFFF (no load) is outside every image
-            const uint32_t slot = i / D, d = i % D;
-            phys[j] = i >= (uint32_t)(kBlock * D) ? 0xFFFFFFFFu
-                      : tensor ? d * kBlock + slot
-                               : slot * D + ((((d >> 3) ^ slot) & (D / 8 - 1)) << 3) + (d & 7);
+struct RowLoad {
+    u32x4 gi, gv;
+    uint32_t si, sv;
+    int e0, a0, a1, e1;
+
+    __device__ __forceinline__ void issue(const ResidualRefs &rr, int first, int end, int lane) {
+        e0 = first;
+        e1 = end;
+        const bool vec = (((uintptr_t)rr.idx | (uintptr_t)rr.val) & 15) == 0;
+        a0 = vec ? min(e1, (e0 + 7) & ~7) : e1;        // [e0, a0) and [a1, e1): single entries
+        a1 = vec ? a0 + ((e1 - a0) & ~7) : e1;         // [a0, a1): aligned groups of 8
+        const int head = a0 - e0, singles = head + (e1 - a1);
+        const int es = lane < head ? e0 + lane : a1 + (lane - head);
+        si = 0xFFFFFFFFu;                              // an index outside every image: nothing to add
+        sv = 0;
+        if (lane < singles) {
+            si = rr.idx[es];
+            sv = rr.val[es];
         }
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const float base = phys[j] != 0xFFFFFFFFu ? __uint_as_float((uint32_t)img[phys[j]] << 16) : 0.f;
-            const float delta = __uint_as_float((gv[j / 2] >> (16 * (j % 2))) << 16);
-            sum[j] = __builtin_bit_cast(uint16_t, (__bf16)(base + delta));
-        }
-#pragma unroll
-        for (int j = 0; j < 8; ++j)
-            if (phys[j] != 0xFFFFFFFFu) img[phys[j]] = sum[j];
-        g += 512;
-        if (__builtin_amdgcn_ballot_w64(g < a1) == 0) break;
+        const int g = a0 + 8 * lane;
         gi = u32x4{0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu};
+        gv = u32x4{0, 0, 0, 0};
         if (g < a1) {
             gi = *(const u32x4 *)(rr.idx + g);
             gv = *(const u32x4 *)(rr.val + g);
         }
     }
-}
 
+    __device__ __forceinline__ void apply(uint16_t *img, int tensor, const ResidualRefs &rr, int lane) {
+        if (e0 >= e1) return;
+        add_entry<D>(img, tensor, si, sv);
+        const int head = a0 - e0, singles = head + (e1 - a1);
+        for (int s = lane + 64; s < singles; s += 64) {          // only without the 16-byte alignment
+            const int e = s < head ? e0 + s : a1 + (s - head);
+            add_entry<D>(img, tensor, rr.idx[e], rr.val[e]);
+        }
+        for (int g = a0 + 8 * lane;; g += 512) {
+            // the 8 elements are distinct (contract of the CSR), so all are read before any is written
+            uint32_t phys[8];
+            uint16_t sum[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const uint32_t i = (gi[j / 2] >> (16 * (j % 2))) & 0xFFFFu;   // 0xFFFF: not loaded
+                const uint32_t slot = i / D, d = i % D;
+                phys[j] = i >= (uint32_t)(kBlock * D) ? 0xFFFFFFFFu
+                          : tensor ? d * kBlock + slot
+                                   : slot * D + ((((d >> 3) ^ slot) & (D / 8 - 1)) << 3) + (d & 7);
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+                const float base = phys[j] != 0xFFFFFFFFu ? __uint_as_float((uint32_t)img[phys[j]] << 16) : 0.f;
+                const float delta = __uint_as_float((gv[j / 2] >> (16 * (j % 2))) << 16);
+                sum[j] = __builtin_bit_cast(uint16_t, (__bf16)(base + delta));
+            }
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                if (phys[j] != 0xFFFFFFFFu) img[phys[j]] = sum[j];
+            if (__builtin_amdgcn_ballot_w64(g + 512 < a1) == 0) break;
+            gi = u32x4{0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu};
+            if (g + 512 < a1) {
+                gi = *(const u32x4 *)(rr.idx + g + 512);
+                gv = *(const u32x4 *)(rr.val + g + 512);
+            }
+        }
+    }
+};
+
+// `rows`: row_ranges of the pair's two blocks (8 values: K0, V0, K1, V1)
 template <int D>
-__device__ __forceinline__ void patch_pair(PairRegs<D, false> &p, uint16_t *img, const ResidualRefs &rr, int h0, int h1,
-                                           int kvh, int hkv, int lane) {
+__device__ __forceinline__ void patch_pair(PairRegs<D, false> &p, uint16_t *img, const ResidualRefs &rr,
+                                           const int *rows, int lane) {
     constexpr int kImg = kBlock * D;
+    RowLoad<D> k0, v0, k1, v1;
+    k0.issue(rr, rows[0], rows[1], lane);
+    k1.issue(rr, rows[4], rows[5], lane);
     const int m = lane & 15, q4 = lane >> 4;
     uint16_t *kimg = img + (m >= 8 ? kImg : 0);
     const int slot0 = 8 * ((m >> 2) & 1) + (m & 3);
@@ -196,8 +227,10 @@ __device__ __forceinline__ void patch_pair(PairRegs<D, false> &p, uint16_t *img,
             *(u32x4 *)(kimg + slot * D + ((((4 * t + q4) ^ slot) & (D / 8 - 1)) << 3)) = p.k[T][t];
         }
     wave_lds_order();
-    if (h0 >= 0) add_entries<D>(img, rr, h0, 0, kvh, hkv, lane);
-    if (h1 >= 0) add_entries<D>(img + kImg, rr, h1, 0, kvh, hkv, lane);
+    k0.apply(img, 0, rr, lane);
+    k1.apply(img + kImg, 0, rr, lane);
+    v0.issue(rr, rows[2], rows[3], lane);             // in flight while the K fragments go back and V comes in
+    v1.issue(rr, rows[6], rows[7], lane);
     wave_lds_order();
 #pragma unroll
     for (int T = 0; T < 2; ++T)
@@ -211,8 +244,8 @@ __device__ __forceinline__ void patch_pair(PairRegs<D, false> &p, uint16_t *img,
 #pragma unroll
     for (int dt = 0; dt < D / 16; ++dt) *(u32x4 *)(vimg + (16 * dt + m) * kBlock + (q4 & 1) * 8) = p.v[dt];
     wave_lds_order();
-    if (h0 >= 0) add_entries<D>(img, rr, h0, 1, kvh, hkv, lane);
-    if (h1 >= 0) add_entries<D>(img + kImg, rr, h1, 1, kvh, hkv, lane);
+    v0.apply(img, 1, rr, lane);
+    v1.apply(img + kImg, 1, rr, lane);
     wave_lds_order();
 #pragma unroll
     for (int dt = 0; dt < D / 16; ++dt) p.v[dt] = *(const u32x4 *)(vimg + (16 * dt + m) * kBlock + (q4 & 1) * 8);
