@@ -33,8 +33,10 @@ def test_unsupported_shapes_and_bad_sizes_are_rejected():
     params, dpool, dt = sess._common(pool, tables, 0.0)
     graph = B.make_graph(wl.graph.num_nodes, sess.node_len, sess.node_block_ptr, sess.node_blocks)
     db = sess.upload_batch(wl.batch)
+    hnd = torch.full((wl.batch.num_req, int(tables["max_blocks"])), -1, dtype=torch.int32, device=sess.device)
     calls = {
         "decode": lambda p: B.gf_attn_decode(sess.ctx, p, dpool, dt, qd, od),
+        "decode_residual": lambda p: B.gf_attn_decode_residual(sess.ctx, p, dpool, dt, hnd, 0, None, None, None, qd, od),
         "decode_shared": lambda p: B.gf_attn_decode_shared(sess.ctx, p, dpool, graph, db["path_ptr"], db["path_nodes"],
                                                            db["num_path_entries"], dt, qd, od),
     }
@@ -52,6 +54,13 @@ def test_unsupported_shapes_and_bad_sizes_are_rejected():
     assert _code(lambda: B.gf_attn_decode_shared(sess.ctx, params, dpool, graph, None, db["path_nodes"],
                                                  db["num_path_entries"], dt, qd, od)) == B.GF_ERR_NULL
     assert _code(lambda: B.gf_attn_decode(sess.ctx, params, dpool, dt, None, od)) == B.GF_ERR_NULL
+    assert _code(lambda: B.gf_attn_decode_residual(sess.ctx, params, dpool, dt, None, 0, None, None, None, qd, od)) \
+        == B.GF_ERR_NULL                                                                              # no handles
+    assert _code(lambda: B.gf_attn_decode_residual(sess.ctx, params, dpool, dt, hnd, 2, None, None, None, qd, od)) \
+        == B.GF_ERR_NULL                                                                              # items, no CSR
+    assert _code(lambda: B.gf_attn_decode_residual(sess.ctx, params, dpool, dt, hnd, -1, None, None, None, qd, od)) \
+        == B.GF_ERR_BAD_SHAPE
+    B.gf_attn_decode_residual(sess.ctx, params, dpool, dt, hnd, 0, None, None, None, qd, od)          # no items: fine
     assert _code(lambda: B.gf_set_decode_chunk_blocks(sess.ctx, 3)) == B.GF_ERR_BAD_SHAPE            # odd
     assert _code(lambda: B.gf_attn_prefill(sess.ctx, params, dpool, dt, qd, None, 5, 9, od)) == B.GF_ERR_BAD_SHAPE
     # residual on an e4m3 pool needs the block scales
@@ -70,6 +79,7 @@ def test_empty_batches_are_accepted_everywhere():
     empty = B.make_tables(None, None, None, None, None, None, 0, 0)
     graph = B.make_graph(wl.graph.num_nodes, sess.node_len, sess.node_block_ptr, sess.node_blocks)
     B.gf_attn_decode(sess.ctx, params, dpool, empty, None, None)
+    B.gf_attn_decode_residual(sess.ctx, params, dpool, empty, None, 0, None, None, None, None, None)
     B.gf_attn_decode_shared(sess.ctx, params, dpool, graph, None, None, 0, empty, None, None)
     B.gf_attn_prefill(sess.ctx, params, dpool, empty, None, None, 0, 0, None)
     B.gf_kv_append(sess.ctx, params, pool.k, pool.v, None, None, pool.num_blocks, empty, None, None, None, 0, 0)

@@ -88,6 +88,59 @@ def test_decode_full_size_sampled(name, shared):
         _check_rows(wl, pool, want, qb[r:r + 1], og[r:r + 1], r, decode=True)
 
 
+def test_decode_8b_read_time_residual_full_size_sampled():
+    """gf_attn_decode_residual in the launch bench.py times (config 3, the last quarter of every request's table
+    entries carrying a device-generated residual item): sampled requests are checked against the oracle, which
+    reconstructs copies of the request's blocks from copies of its CSR rows and then attends."""
+    from oracle import residual as OR
+    wl, sess, tables, pool, q, q_ptr = _setup("decode_8b")
+    sh, dev = wl.shape, sess.device
+    want = oracle_resolve(wl)
+    nb = tables["num_blocks"].to(torch.int64)
+    first = nb - (nb.to(torch.float64) * 0.25).to(torch.int64)
+    ar = torch.arange(int(tables["max_blocks"]), device=dev)[None, :]
+    mask = (ar >= first[:, None]) & (ar < nb[:, None])
+    n_items = int(mask.sum().item())
+    handles = torch.full(mask.shape, -1, dtype=torch.int32, device=dev)
+    handles[mask] = torch.arange(n_items, dtype=torch.int32, device=dev)
+    dres, nnz = R.random_residuals(sh, n_items, dev)
+    last = torch.from_numpy((q_ptr[1:] - 1).astype(np.int64)).to(dev)
+    qd = q[last].contiguous()
+    od = torch.full_like(qd, float("nan"))
+    sess.decode_residual(pool, tables, handles, dres, qd, od)
+    torch.cuda.synchronize()
+    og = od.double().cpu().numpy()
+    assert np.isfinite(og).all()
+    qb = R.bf16_to_bits(qd)
+    L = W.context_lens(wl)
+    ptr = dres["ptr"].cpu().numpy().astype(np.int64)
+    rows = 2 * sh.num_kv_heads
+    for r in (int(np.argmin(L)), int(np.argsort(L)[8])):        # the entry-by-entry oracle bounds the sample
+        n = want["num_blocks"][r]
+        ids = np.array(want["block_table"][r][:n], dtype=np.int64)
+        kk, vv, _, _ = pool.gather_host(ids)
+        hr = handles[r, :n].cpu().numpy()
+        ents = np.nonzero(hr >= 0)[0]
+        assert ents.size >= n // 4 - 1 and ents.size > 0
+        lptr, lidx, lval = [0], [], []
+        for e in ents:
+            lo, hi = int(ptr[hr[e] * rows]), int(ptr[(hr[e] + 1) * rows])
+            lptr += list(ptr[hr[e] * rows + 1:(hr[e] + 1) * rows + 1] - lo + lptr[-1])
+            lidx.append(dres["idx"][lo:hi].cpu().numpy().view(np.uint16))
+            lval.append(dres["val"][lo:hi].cpu().numpy().view(np.uint16))
+        k2, v2, st = OR.reconstruct(kk, vv, ents, ents, np.array(lptr), np.concatenate(lidx), np.concatenate(lval))
+        assert (st == 0).all() and not np.array_equal(k2, kk)
+        local = {k: [v[r]] for k, v in want.items()}
+        local["block_table"] = [list(range(n))]
+        O, _ = OA.decode(qb[r:r + 1], k2, v2, local)
+        atol, rtol = TOL[sh.kv_dtype]
+        err = np.abs(og[r:r + 1] - O)
+        assert (err <= atol + rtol * np.abs(O)).all(), f"request {r}: max err {err.max()}"
+        # and the residual matters at this size: the plain step's answer is outside the tolerance somewhere
+        O0, _ = OA.decode(qb[r:r + 1], kk, vv, local)
+        assert np.abs(O0 - O).max() > 1e-3
+
+
 def test_kv_residual_bench_size_sampled_blocks():
     """The residual launch bench.py times (8192 blocks of the 8B head shape, device-generated
     residuals): sampled items are reconstructed by the oracle from copies of their base blocks and
