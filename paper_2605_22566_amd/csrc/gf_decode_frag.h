@@ -136,15 +136,27 @@ __device__ __forceinline__ void row_ranges(const ResidualRefs &rr, int item, int
 
 // A CSR row in flight.  It is read 8 entries (16 bytes of indices, 16 of values) per lane where it covers whole
 // aligned groups of 8, and entry by entry at its two ends (or everywhere, if the arrays do not start on a
-// 16-byte boundary); issue() starts the loads of the ends and of the first 512 grouped entries, apply() adds them
-// into the image and walks the rest of a longer row.  The two K rows of a pair are issued together, then the two
+// 16-byte boundary); issue() starts the loads of the ends and of the first 512 * NG grouped entries, apply() adds
+// them into the image and walks the rest of a longer row.  The two K rows of a pair are issued together, then the two
 // V rows, so a pair of the paper's density (about a quarter of the 2048 elements of an image) costs two memory
 // round trips (the row ranges come a pair ahead).
-template <int D>
+template <int D, int NG>
 struct RowLoad {
-    u32x4 gi, gv;
+    u32x4 gi[NG], gv[NG];        // NG groups of 8 entries per lane: 512 * NG entries per round trip
     uint32_t si, sv;
     int e0, a0, a1, e1;
+
+    __device__ __forceinline__ void load_groups(const ResidualRefs &rr, int g) {
+#pragma unroll
+        for (int n = 0; n < NG; ++n) {
+            gi[n] = u32x4{0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu};   // outside every image: nothing to add
+            gv[n] = u32x4{0, 0, 0, 0};
+            if (g + 512 * n < a1) {
+                gi[n] = *(const u32x4 *)(rr.idx + g + 512 * n);
+                gv[n] = *(const u32x4 *)(rr.val + g + 512 * n);
+            }
+        }
+    }
 
     __device__ __forceinline__ void issue(const ResidualRefs &rr, int first, int end, int lane) {
         e0 = first;
@@ -154,19 +166,13 @@ struct RowLoad {
         a1 = vec ? a0 + ((e1 - a0) & ~7) : e1;         // [a0, a1): aligned groups of 8
         const int head = a0 - e0, singles = head + (e1 - a1);
         const int es = lane < head ? e0 + lane : a1 + (lane - head);
-        si = 0xFFFFFFFFu;                              // an index outside every image: nothing to add
+        si = 0xFFFFFFFFu;
         sv = 0;
         if (lane < singles) {
             si = rr.idx[es];
             sv = rr.val[es];
         }
-        const int g = a0 + 8 * lane;
-        gi = u32x4{0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu};
-        gv = u32x4{0, 0, 0, 0};
-        if (g < a1) {
-            gi = *(const u32x4 *)(rr.idx + g);
-            gv = *(const u32x4 *)(rr.val + g);
-        }
+        load_groups(rr, a0 + 8 * lane);
     }
 
     __device__ __forceinline__ void apply(uint16_t *img, int tensor, const ResidualRefs &rr, int lane) {
@@ -177,33 +183,32 @@ struct RowLoad {
             const int e = s < head ? e0 + s : a1 + (s - head);
             add_entry<D>(img, tensor, rr.idx[e], rr.val[e]);
         }
-        for (int g = a0 + 8 * lane;; g += 512) {
-            // the 8 elements are distinct (contract of the CSR), so all are read before any is written
-            uint32_t phys[8];
-            uint16_t sum[8];
+        for (int g = a0 + 8 * lane;; g += 512 * NG) {
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const uint32_t i = (gi[j / 2] >> (16 * (j % 2))) & 0xFFFFu;   // 0xFFFF: not loaded
-                const uint32_t slot = i / D, d = i % D;
-                phys[j] = i >= (uint32_t)(kBlock * D) ? 0xFFFFFFFFu
-                          : tensor ? d * kBlock + slot
-                                   : slot * D + ((((d >> 3) ^ slot) & (D / 8 - 1)) << 3) + (d & 7);
-            }
+            for (int n = 0; n < NG; ++n) {
+                // the 8 elements are distinct (contract of the CSR), so all are read before any is written
+                uint32_t phys[8];
+                uint16_t sum[8];
 #pragma unroll
-            for (int j = 0; j < 8; ++j) {
-                const float base = phys[j] != 0xFFFFFFFFu ? __uint_as_float((uint32_t)img[phys[j]] << 16) : 0.f;
-                const float delta = __uint_as_float((gv[j / 2] >> (16 * (j % 2))) << 16);
-                sum[j] = __builtin_bit_cast(uint16_t, (__bf16)(base + delta));
-            }
+                for (int j = 0; j < 8; ++j) {
+                    const uint32_t i = (gi[n][j / 2] >> (16 * (j % 2))) & 0xFFFFu;
+                    const uint32_t slot = i / D, d = i % D;
+                    phys[j] = i >= (uint32_t)(kBlock * D) ? 0xFFFFFFFFu
+                              : tensor ? d * kBlock + slot
+                                       : slot * D + ((((d >> 3) ^ slot) & (D / 8 - 1)) << 3) + (d & 7);
+                }
 #pragma unroll
-            for (int j = 0; j < 8; ++j)
-                if (phys[j] != 0xFFFFFFFFu) img[phys[j]] = sum[j];
-            if (__builtin_amdgcn_ballot_w64(g + 512 < a1) == 0) break;
-            gi = u32x4{0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu};
-            if (g + 512 < a1) {
-                gi = *(const u32x4 *)(rr.idx + g + 512);
-                gv = *(const u32x4 *)(rr.val + g + 512);
+                for (int j = 0; j < 8; ++j) {
+                    const float base = phys[j] != 0xFFFFFFFFu ? __uint_as_float((uint32_t)img[phys[j]] << 16) : 0.f;
+                    const float delta = __uint_as_float((gv[n][j / 2] >> (16 * (j % 2))) << 16);
+                    sum[j] = __builtin_bit_cast(uint16_t, (__bf16)(base + delta));
+                }
+#pragma unroll
+                for (int j = 0; j < 8; ++j)
+                    if (phys[j] != 0xFFFFFFFFu) img[phys[j]] = sum[j];
             }
+            if (__builtin_amdgcn_ballot_w64(g + 512 * NG < a1) == 0) break;
+            load_groups(rr, g + 512 * NG);
         }
     }
 };
@@ -213,7 +218,8 @@ template <int D>
 __device__ __forceinline__ void patch_pair(PairRegs<D, false> &p, uint16_t *img, const ResidualRefs &rr,
                                            const int *rows, int lane) {
     constexpr int kImg = kBlock * D;
-    RowLoad<D> k0, v0, k1, v1;
+    RowLoad<D, 1> k0, k1;        // a K row of the paper's density fits 512 entries, a V row 1024
+    RowLoad<D, 2> v0, v1;
     k0.issue(rr, rows[0], rows[1], lane);
     k1.issue(rr, rows[4], rows[5], lane);
     const int m = lane & 15, q4 = lane >> 4;
