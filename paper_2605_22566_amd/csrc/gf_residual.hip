@@ -193,9 +193,11 @@ __global__ __launch_bounds__(kResidualThreads) void residual_e4m3_kernel(
     if (status && tid == 0) status[item] = bad_index ? GF_RS_BAD_INDEX : GF_RS_OK;
 }
 
-// The same on a block whose kv heads fit LDS side by side (HKV fp32 images): one wave per kv head, one pass.
-// K first, then V: every wave sums its image, the workgroup reduces the tensor's maximum, every wave
-// quantises and writes its image.
+// The same in one pass, one wave per kv head.  A wave keeps its image in registers (16 consecutive elements per
+// lane and 1 KB of codes) and only the residual goes through LDS: a 2-byte image per head, preset to a "no
+// entry" mark, into which the row's bf16 values are stored (plain stores: the entries of a row name distinct
+// elements), and from which every lane then reads the 16 values beside its 16 codes.  K first, then V: every wave
+// sums its image, the workgroup reduces the tensor's maximum, every wave quantises and writes its image.
 template <int D, int HKV>
 __global__ __launch_bounds__(64 * HKV) void residual_e4m3_onepass_kernel(
     uint8_t *__restrict__ k_pool, uint8_t *__restrict__ v_pool, float *__restrict__ k_scale,
@@ -203,8 +205,10 @@ __global__ __launch_bounds__(64 * HKV) void residual_e4m3_onepass_kernel(
     const int32_t *__restrict__ dst_blocks, const int32_t *__restrict__ res_ptr,
     const uint16_t *__restrict__ res_idx, const uint16_t *__restrict__ res_val, int32_t *__restrict__ status) {
     constexpr int kImg = kBlock * D;
-    __shared__ __attribute__((aligned(16))) float lds[HKV][kImg];
-    __shared__ float red[HKV];
+    constexpr int NJ = kImg / 1024;                               // 16-element pieces per lane
+    constexpr uint16_t kNone = 0xFFFFu;                           // a NaN pattern no stored entry keeps (see below)
+    __shared__ __attribute__((aligned(16))) uint16_t lds[HKV][kImg];
+    __shared__ float red[2][HKV];
     __shared__ int bad_index;
     const int item = blockIdx.x;
     const int tid = threadIdx.x, lane = tid & 63;
@@ -217,23 +221,20 @@ __global__ __launch_bounds__(64 * HKV) void residual_e4m3_onepass_kernel(
     const float src_scale[2] = {k_scale[src], v_scale[src]};      // read before the destination's are written (src may be dst)
     if (tid == 0) bad_index = 0;
     __syncthreads();
-    float *img = lds[h];
+    uint16_t *img = lds[h];
     bool bad = false;
     for (int t = 0; t < 2; ++t) {
         uint8_t *pool = t ? v_pool : k_pool;
         const uint8_t *g_src = pool + ((size_t)src * HKV + h) * kImg;
         uint8_t *g_dst = pool + ((size_t)dst * HKV + h) * kImg;
         const float s_in = src_scale[t];
+        u32x4 codes[NJ];
 #pragma unroll
-        for (int c = 16 * lane; c < kImg; c += 16 * 64) {
-            const u32x4 w = *(const u32x4 *)(g_src + c);
-            const bf16x8 lo = fp8x8_to_bf16x8(u32x2{w[0], w[1]}), hi = fp8x8_to_bf16x8(u32x2{w[2], w[3]});
+        for (int j = 0; j < NJ; ++j) codes[j] = *(const u32x4 *)(g_src + 16 * lane + 1024 * j);
+        const u32x4 none = {0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu};
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                img[c + i] = __fmul_rn((float)lo[i], s_in);
-                img[c + 8 + i] = __fmul_rn((float)hi[i], s_in);
-            }
-        }
+        for (int c = 8 * lane; c < kImg; c += 8 * 64) *(u32x4 *)(img + c) = none;
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
         const size_t r = ((size_t)item * 2 + t) * HKV + h;
         const int e0 = res_ptr[r], e1 = res_ptr[r + 1];
@@ -244,38 +245,56 @@ __global__ __launch_bounds__(64 * HKV) void residual_e4m3_onepass_kernel(
                 continue;
             }
             const uint32_t phys = t ? (i % D) * kBlock + i / D : i;          // V image: [d][slot]
-            img[phys] = __fadd_rn(img[phys], __uint_as_float((uint32_t)res_val[e] << 16));
+            const uint16_t v = res_val[e];
+            img[phys] = v == kNone ? (uint16_t)0xFFFEu : v;                  // still a negative NaN: the sum is one too
         }
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
+        float x[NJ][16];
         float m = 0.f;
-#pragma unroll 8
-        for (int c = lane; c < kImg; c += 64) m = fmaxf(m, fabsf(img[c]));
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+            const bf16x8 lo = fp8x8_to_bf16x8(u32x2{codes[j][0], codes[j][1]});
+            const bf16x8 hi = fp8x8_to_bf16x8(u32x2{codes[j][2], codes[j][3]});
+            const u32x4 d0 = *(const u32x4 *)(img + 16 * lane + 1024 * j);
+            const u32x4 d1 = *(const u32x4 *)(img + 16 * lane + 1024 * j + 8);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                float base = __fmul_rn(i < 8 ? (float)lo[i] : (float)hi[i - 8], s_in);
+                // the product is an fp32 value of its own (the oracle rounds it): nothing may fuse it with the sum
+                // below into one multiply-add -- the compiler does so even across the two rounding intrinsics
+                asm volatile("" : "+v"(base));
+                const uint32_t w = (i < 8 ? d0 : d1)[(i % 8) / 2];
+                const uint32_t bits = (i % 2) ? (w >> 16) : (w & 0xFFFFu);
+                // an element no entry names keeps its value bit for bit (a sum with zero would lose the sign of -0)
+                x[j][i] = bits == kNone ? base : __fadd_rn(base, __uint_as_float(bits << 16));
+                m = fmaxf(m, fabsf(x[j][i]));
+            }
+        }
 #pragma unroll
         for (int o = 32; o >= 1; o >>= 1) m = fmaxf(m, __shfl_xor(m, o, 64));
-        if (lane == 0) red[h] = m;
+        if (lane == 0) red[t][h] = m;
         __syncthreads();
         float amax = 0.f;
 #pragma unroll
-        for (int i = 0; i < HKV; ++i) amax = fmaxf(amax, red[i]);
+        for (int i = 0; i < HKV; ++i) amax = fmaxf(amax, red[t][i]);
         const float s_out = amax > 0.f ? amax / 448.0f : 1.0f;
         if (tid == 0) (t ? v_scale : k_scale)[dst] = s_out;
 #pragma unroll
-        for (int c = 8 * lane; c < kImg; c += 8 * 64) {
-            float x[8];
+        for (int j = 0; j < NJ; ++j) {
+            u32x4 out;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) x[i] = fminf(fmaxf(img[c + i] / s_out, -448.0f), 448.0f);
-            u32x2 out;
-            int w = 0;
-            w = __builtin_amdgcn_cvt_pk_fp8_f32(x[0], x[1], w, false);
-            w = __builtin_amdgcn_cvt_pk_fp8_f32(x[2], x[3], w, true);
-            out[0] = (uint32_t)w;
-            w = 0;
-            w = __builtin_amdgcn_cvt_pk_fp8_f32(x[4], x[5], w, false);
-            w = __builtin_amdgcn_cvt_pk_fp8_f32(x[6], x[7], w, true);
-            out[1] = (uint32_t)w;
-            *(u32x2 *)(g_dst + c) = out;
+            for (int q = 0; q < 4; ++q) {
+                float y[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) y[i] = fminf(fmaxf(x[j][4 * q + i] / s_out, -448.0f), 448.0f);
+                int w = 0;
+                w = __builtin_amdgcn_cvt_pk_fp8_f32(y[0], y[1], w, false);
+                w = __builtin_amdgcn_cvt_pk_fp8_f32(y[2], y[3], w, true);
+                out[q] = (uint32_t)w;
+            }
+            *(u32x4 *)(g_dst + 16 * lane + 1024 * j) = out;
         }
-        __syncthreads();                                                     // red[] and the images are reused for V
     }
     if (bad) bad_index = 1;                                                  // benign race: every writer stores 1
     __syncthreads();
@@ -299,7 +318,7 @@ hipError_t launch_residual(void *k_pool, void *v_pool, float *k_scale, float *v_
     hipLaunchKernelGGL((residual_e4m3_onepass_kernel<DD, HH>), grid, dim3(64 * HH), 0, s, (uint8_t *)k_pool,      \
                        (uint8_t *)v_pool, k_scale, v_scale, num_pool_blocks, src_blocks, dst_blocks, res_ptr,     \
                        res_idx, res_val, status)
-    // e4m3: one pass when a wave per kv head and the heads' fp32 images fit a workgroup (64 KB of LDS at most)
+    // e4m3: one pass with a wave per kv head (1024 threads at most)
     if (head_dim == 128 && fp8 && hkv == 8) GF_RES_ONEPASS(128, 8);
     else if (head_dim == 128 && fp8 && hkv == 4) GF_RES_ONEPASS(128, 4);
     else if (head_dim == 128 && fp8 && hkv == 2) GF_RES_ONEPASS(128, 2);
