@@ -228,3 +228,25 @@ def test_e4m3_bad_block_and_bad_index_are_reported():
     assert st.tolist() == [OR.ST_BAD_INDEX, OR.ST_BAD_BLOCK, OR.ST_BAD_BLOCK]
     assert np.array_equal(k2[2], k[2]) and ks2[2] == ks[2]
     assert not np.array_equal(k2[1], k[1])
+
+
+def test_residual_handles_name_the_item_of_every_instance_block_and_nothing_else():
+    """Host logic of the read-time form: per table entry, the residual item whose source is the entry's base block
+    and whose destination is the instance block that the two-step form would read there."""
+    from paper_2605_22566_amd import workload as W
+    from tests.helpers import oracle_resolve
+    wl = W.small_layered(71, W.Shape(8, 2, 64), num_nodes=24, num_layers=5, len_lo=3, len_hi=90, num_req=6, hops=(1, 5),
+                         new_lo=1, new_hi=40)
+    wl2, res = W.add_residual_instances(wl, last_nodes=2)
+    bt = np.asarray(oracle_resolve(wl)["block_table"], np.int32)
+    it = np.asarray(oracle_resolve(wl2)["block_table"], np.int32)
+    h = W.residual_handles(bt, it, res)
+    assert h.shape == bt.shape and h.dtype == np.int32
+    named = h >= 0
+    assert named.sum() == res.num_items and sorted(h[named].tolist()) == list(range(res.num_items))
+    assert (res.src_blocks[h[named]] == bt[named]).all() and (res.dst_blocks[h[named]] == it[named]).all()
+    assert (bt[~named] == it[~named]).all() and (h[~named] == -1).all()
+    # every request's handles sit on the entries of its last two nodes: a suffix of its context entries
+    for r in range(wl.batch.num_req):
+        cols = np.nonzero(named[r])[0]
+        assert cols.size > 0 and (np.diff(cols) == 1).all()
