@@ -279,7 +279,7 @@ def decode_shared_entry(job, m):
             "hbm_bytes_per_launch_rocprof": _read_traffic(f"decode_shared_{job.name}")}
 
 
-def measure_decode_residual(job, decode_ms, share=0.25, iters=20):
+def measure_decode_residual(job, decode_ms, share=0.25, density=(0.25, 0.30), iters=20):
     """gf_attn_decode_residual beside gf_attn_decode on the same decode step: the last `share` of every request's
     table entries are read as base block + a residual item of their own (25 % of the K and 30 % of the V elements,
     the density the paper reports), the pool holding base blocks only.  bf16 pools."""
@@ -297,7 +297,7 @@ def measure_decode_residual(job, decode_ms, share=0.25, iters=20):
     num_items = int(mask.sum().item())
     handles = torch.full(mask.shape, -1, dtype=torch.int32, device=dev)
     handles[mask] = torch.arange(num_items, dtype=torch.int32, device=dev)
-    dres, nnz = R.random_residuals(sh, num_items, dev)
+    dres, nnz = R.random_residuals(sh, num_items, dev, density_k=density[0], density_v=density[1])
     o = torch.zeros_like(job.od[lo:hi])
     fn = lambda: job.sess.decode_residual(job.pool, t, handles, dres, job.qd[lo:hi], o)
     for _ in range(3):
@@ -310,6 +310,7 @@ def measure_decode_residual(job, decode_ms, share=0.25, iters=20):
     return {"kernel": "decode_split_kernel<RES>(+merge)", "kernel_ms": ms, "decode_ms": decode_ms,
             "slowdown_over_decode": ms / decode_ms, "entries_with_residual": num_items,
             "share_of_table_entries": num_items / max(1.0, float(nb.sum().item())), "residual_entries": nnz,
+            "density_k_v": list(density),
             "algorithmic_bytes_per_launch": nbytes, "gbs_kernel": nbytes / (ms * 1e-3) / 1e9,
             "frac_of_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
             # what the pool does not hold: the reconstructed copies of these blocks, against the sparse form kept
@@ -453,6 +454,10 @@ def main():
                     help="table entries per split-KV chunk of the decode kernels (0 = the library's choice)")
     ap.add_argument("--extra", default="decode_8b,kv_residual,stream_copy",
                     help="comma list of further workloads reported under 'extra' (the five configs, kv_residual, stream_copy)")
+    ap.add_argument("--residual-share", type=float, default=0.25,
+                    help="decode_residual: share of every request's table entries (its last ones) that carry a residual")
+    ap.add_argument("--residual-density", default="0.25,0.30",
+                    help="decode_residual: share of the K,V elements of such an entry that the residual names (> 0)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=20.0)
     ap.add_argument("--copy-calibration", action="store_true",
@@ -564,7 +569,8 @@ def main():
             ent["unique_bytes_time_bound_ms"] = ent["unique_kv_bytes"] / (PEAK_HBM_GBS * 1e9) * 1e3
             ent["hbm_bytes_per_launch_rocprof"] = _read_traffic(f"decode_{name}")
             ent["decode_shared"] = decode_shared_entry(j, mm)
-            dr = measure_decode_residual(j, mm["decode_ms"])
+            dr = measure_decode_residual(j, mm["decode_ms"], args.residual_share,
+                                         tuple(float(x) for x in args.residual_density.split(",")))
             if dr is not None:
                 ent["decode_residual"] = dr
         extra[name] = ent
