@@ -101,7 +101,7 @@ __global__ __launch_bounds__(kDecodeThreads, RES ? 2 : 1) void decode_split_kern
                 row_ranges(rr, h1n, kvh, a.hkv, rows_n + 4);
             }
             if (h0 >= 0 || h1 >= 0) {
-                __shared__ __attribute__((aligned(16))) uint16_t patch_img[kWavesPerWg][2 * kBlock * D];
+                __shared__ __attribute__((aligned(16))) uint16_t patch_img[kWavesPerWg][2 * kBlock * D + kPatchSpare];
                 patch_pair<D>(cur, patch_img[wave], rr, rows, lane);
             }
         }

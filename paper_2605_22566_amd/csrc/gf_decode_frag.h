@@ -96,7 +96,8 @@ __device__ __forceinline__ void load_pair(PairRegs<D, true> &p, const AttnArgs &
 }
 
 // Differential KV (paper, "Differential-based KV Cache", Eq. 7) applied to a loaded pair of a bf16 pool: the
-// fragments go to the wave's LDS image `img` (2 * 16 * D elements: the two blocks back to back), the residual
+// fragments go to the wave's LDS image `img` (2 * 16 * D elements: the two blocks back to back, and kPatchSpare
+// spare elements behind them), the residual
 // entries of the blocks that have one (items h0 / h1 of the CSR, -1 = none) are added there -- fp32 sum rounded to
 // bf16, the arithmetic of gf_kv_apply_residual, so the operands equal a reconstructed block bit for bit -- and the
 // fragments are read back; first K, then V through the same image.  K rows keep the pool's [slot][d] order with the
@@ -110,11 +111,16 @@ __device__ __forceinline__ void wave_lds_order() {
 }
 
 // one residual entry: logical element i of the image (slot * D + d), bf16 bits in the low half of `bits`
+constexpr int kPatchSpare = 8;
+
 template <int D>
-__device__ __forceinline__ void add_entry(uint16_t *img, int tensor, uint32_t i, uint32_t bits) {
-    if (i >= (uint32_t)(kBlock * D)) return;
+__device__ __forceinline__ void add_entry(uint16_t *img, int tensor, uint32_t i, uint32_t bits, uint32_t spare) {
     const uint32_t slot = i / D, d = i % D;
-    const uint32_t phys = tensor ? d * kBlock + slot : slot * D + ((((d >> 3) ^ slot) & (D / 8 - 1)) << 3) + (d & 7);
+    // an entry outside the image lands on `spare`, an element beside the images that nothing reads: no lane
+    // has to be switched off for it
+    const uint32_t phys = i >= (uint32_t)(kBlock * D) ? spare
+                          : tensor ? d * kBlock + slot
+                                   : slot * D + ((((d >> 3) ^ slot) & (D / 8 - 1)) << 3) + (d & 7);
     const float base = __uint_as_float((uint32_t)img[phys] << 16);
     const float delta = __uint_as_float(bits << 16);
     const __bf16 sum = (__bf16)(base + delta);                           // round to nearest even
@@ -175,13 +181,13 @@ struct RowLoad {
         load_groups(rr, a0 + 8 * lane);
     }
 
-    __device__ __forceinline__ void apply(uint16_t *img, int tensor, const ResidualRefs &rr, int lane) {
+    __device__ __forceinline__ void apply(uint16_t *img, int tensor, const ResidualRefs &rr, int lane, uint32_t spare) {
         if (e0 >= e1) return;
-        add_entry<D>(img, tensor, si, sv);
+        add_entry<D>(img, tensor, si, sv, spare);
         const int head = a0 - e0, singles = head + (e1 - a1);
         for (int s = lane + 64; s < singles; s += 64) {          // only without the 16-byte alignment
             const int e = s < head ? e0 + s : a1 + (s - head);
-            add_entry<D>(img, tensor, rr.idx[e], rr.val[e]);
+            add_entry<D>(img, tensor, rr.idx[e], rr.val[e], spare);
         }
         for (int g = a0 + 8 * lane;; g += 512 * NG) {
 #pragma unroll
@@ -193,19 +199,19 @@ struct RowLoad {
                 for (int j = 0; j < 8; ++j) {
                     const uint32_t i = (gi[n][j / 2] >> (16 * (j % 2))) & 0xFFFFu;
                     const uint32_t slot = i / D, d = i % D;
-                    phys[j] = i >= (uint32_t)(kBlock * D) ? 0xFFFFFFFFu
+                    phys[j] = i >= (uint32_t)(kBlock * D) ? spare
                               : tensor ? d * kBlock + slot
                                        : slot * D + ((((d >> 3) ^ slot) & (D / 8 - 1)) << 3) + (d & 7);
                 }
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
-                    const float base = phys[j] != 0xFFFFFFFFu ? __uint_as_float((uint32_t)img[phys[j]] << 16) : 0.f;
+                    const float base = __uint_as_float((uint32_t)img[phys[j]] << 16);
                     const float delta = __uint_as_float((gv[n][j / 2] >> (16 * (j % 2))) << 16);
                     sum[j] = __builtin_bit_cast(uint16_t, (__bf16)(base + delta));
                 }
 #pragma unroll
                 for (int j = 0; j < 8; ++j)
-                    if (phys[j] != 0xFFFFFFFFu) img[phys[j]] = sum[j];
+                    img[phys[j]] = sum[j];
             }
             if (__builtin_amdgcn_ballot_w64(g + 512 * NG < a1) == 0) break;
             load_groups(rr, g + 512 * NG);
@@ -233,8 +239,8 @@ __device__ __forceinline__ void patch_pair(PairRegs<D, false> &p, uint16_t *img,
             *(u32x4 *)(kimg + slot * D + ((((4 * t + q4) ^ slot) & (D / 8 - 1)) << 3)) = p.k[T][t];
         }
     wave_lds_order();
-    k0.apply(img, 0, rr, lane);
-    k1.apply(img + kImg, 0, rr, lane);
+    k0.apply(img, 0, rr, lane, 2 * kImg);
+    k1.apply(img + kImg, 0, rr, lane, kImg);
     v0.issue(rr, rows[2], rows[3], lane);             // in flight while the K fragments go back and V comes in
     v1.issue(rr, rows[6], rows[7], lane);
     wave_lds_order();
@@ -250,8 +256,8 @@ __device__ __forceinline__ void patch_pair(PairRegs<D, false> &p, uint16_t *img,
 #pragma unroll
     for (int dt = 0; dt < D / 16; ++dt) *(u32x4 *)(vimg + (16 * dt + m) * kBlock + (q4 & 1) * 8) = p.v[dt];
     wave_lds_order();
-    v0.apply(img, 1, rr, lane);
-    v1.apply(img + kImg, 1, rr, lane);
+    v0.apply(img, 1, rr, lane, 2 * kImg);
+    v1.apply(img + kImg, 1, rr, lane, kImg);
     wave_lds_order();
 #pragma unroll
     for (int dt = 0; dt < D / 16; ++dt) p.v[dt] = *(const u32x4 *)(vimg + (16 * dt + m) * kBlock + (q4 & 1) * 8);
