@@ -113,14 +113,19 @@ __device__ __forceinline__ void wave_lds_order() {
 // one residual entry: logical element i of the image (slot * D + d), bf16 bits in the low half of `bits`
 constexpr int kPatchSpare = 8;
 
-template <int D>
-__device__ __forceinline__ void add_entry(uint16_t *img, int tensor, uint32_t i, uint32_t bits, uint32_t spare) {
+// LDS element of logical element i = slot * D + d of an image: K keeps [slot][d] with the 16-byte pieces of a row
+// XOR-ed by the slot, V is [d][slot].  An entry outside the image lands on `spare`, an element beside the images
+// that nothing reads: no lane has to be switched off for it.
+template <int D, int TENSOR>
+__device__ __forceinline__ uint32_t patch_elem(uint32_t i, uint32_t spare) {
     const uint32_t slot = i / D, d = i % D;
-    // an entry outside the image lands on `spare`, an element beside the images that nothing reads: no lane
-    // has to be switched off for it
-    const uint32_t phys = i >= (uint32_t)(kBlock * D) ? spare
-                          : tensor ? d * kBlock + slot
-                                   : slot * D + ((((d >> 3) ^ slot) & (D / 8 - 1)) << 3) + (d & 7);
+    const uint32_t phys = TENSOR ? d * kBlock + slot : i ^ ((slot & (D / 8 - 1)) << 3);
+    return i >= (uint32_t)(kBlock * D) ? spare : phys;
+}
+
+template <int D, int TENSOR>
+__device__ __forceinline__ void add_entry(uint16_t *img, uint32_t i, uint32_t bits, uint32_t spare) {
+    const uint32_t phys = patch_elem<D, TENSOR>(i, spare);
     const float base = __uint_as_float((uint32_t)img[phys] << 16);
     const float delta = __uint_as_float(bits << 16);
     const __bf16 sum = (__bf16)(base + delta);                           // round to nearest even
@@ -181,13 +186,14 @@ struct RowLoad {
         load_groups(rr, a0 + 8 * lane);
     }
 
-    __device__ __forceinline__ void apply(uint16_t *img, int tensor, const ResidualRefs &rr, int lane, uint32_t spare) {
+    template <int TENSOR>
+    __device__ __forceinline__ void apply(uint16_t *img, const ResidualRefs &rr, int lane, uint32_t spare) {
         if (e0 >= e1) return;
-        add_entry<D>(img, tensor, si, sv, spare);
+        add_entry<D, TENSOR>(img, si, sv, spare);
         const int head = a0 - e0, singles = head + (e1 - a1);
         for (int s = lane + 64; s < singles; s += 64) {          // only without the 16-byte alignment
             const int e = s < head ? e0 + s : a1 + (s - head);
-            add_entry<D>(img, tensor, rr.idx[e], rr.val[e], spare);
+            add_entry<D, TENSOR>(img, rr.idx[e], rr.val[e], spare);
         }
         for (int g = a0 + 8 * lane;; g += 512 * NG) {
 #pragma unroll
@@ -198,10 +204,7 @@ struct RowLoad {
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
                     const uint32_t i = (gi[n][j / 2] >> (16 * (j % 2))) & 0xFFFFu;
-                    const uint32_t slot = i / D, d = i % D;
-                    phys[j] = i >= (uint32_t)(kBlock * D) ? spare
-                              : tensor ? d * kBlock + slot
-                                       : slot * D + ((((d >> 3) ^ slot) & (D / 8 - 1)) << 3) + (d & 7);
+                    phys[j] = patch_elem<D, TENSOR>(i, spare);
                 }
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
@@ -239,8 +242,8 @@ __device__ __forceinline__ void patch_pair(PairRegs<D, false> &p, uint16_t *img,
             *(u32x4 *)(kimg + slot * D + ((((4 * t + q4) ^ slot) & (D / 8 - 1)) << 3)) = p.k[T][t];
         }
     wave_lds_order();
-    k0.apply(img, 0, rr, lane, 2 * kImg);
-    k1.apply(img + kImg, 0, rr, lane, kImg);
+    k0.template apply<0>(img, rr, lane, 2 * kImg);
+    k1.template apply<0>(img + kImg, rr, lane, kImg);
     v0.issue(rr, rows[2], rows[3], lane);             // in flight while the K fragments go back and V comes in
     v1.issue(rr, rows[6], rows[7], lane);
     wave_lds_order();
@@ -256,8 +259,8 @@ __device__ __forceinline__ void patch_pair(PairRegs<D, false> &p, uint16_t *img,
 #pragma unroll
     for (int dt = 0; dt < D / 16; ++dt) *(u32x4 *)(vimg + (16 * dt + m) * kBlock + (q4 & 1) * 8) = p.v[dt];
     wave_lds_order();
-    v0.apply(img, 1, rr, lane, 2 * kImg);
-    v1.apply(img + kImg, 1, rr, lane, kImg);
+    v0.template apply<1>(img, rr, lane, 2 * kImg);
+    v1.template apply<1>(img + kImg, rr, lane, kImg);
     wave_lds_order();
 #pragma unroll
     for (int dt = 0; dt < D / 16; ++dt) p.v[dt] = *(const u32x4 *)(vimg + (16 * dt + m) * kBlock + (q4 & 1) * 8);
