@@ -20,6 +20,48 @@ namespace gf {
 constexpr int kResidualThreads = 256;
 constexpr int kResidualWaves = kResidualThreads / 64;
 
+// Calls f(index, value bits) for every entry of the CSR row [e0, e1), 64 lanes sharing the row.  Where the row
+// covers whole aligned groups of 8 entries a lane reads a group with one 16-byte load of indices and one of
+// values (whole row by single entries if the arrays do not start on a 16-byte boundary); the loads of the two
+// ends and of the first 512 grouped entries are all issued before the first call, so a row of the paper's density
+// costs one memory round trip instead of one per 64 entries.
+template <typename F>
+__device__ __forceinline__ void for_row_entries(const uint16_t *__restrict__ idx, const uint16_t *__restrict__ val,
+                                                int e0, int e1, int lane, F f) {
+    if (e0 >= e1) return;
+    const bool vec = (((uintptr_t)idx | (uintptr_t)val) & 15) == 0;
+    const int a0 = vec ? min(e1, (e0 + 7) & ~7) : e1;        // [e0, a0) and [a1, e1): single entries
+    const int a1 = vec ? a0 + ((e1 - a0) & ~7) : e1;         // [a0, a1): aligned groups of 8
+    const int head = a0 - e0, singles = head + (e1 - a1);
+    uint32_t si = 0, sv = 0;
+    const bool has_single = lane < singles;
+    if (has_single) {
+        const int es = lane < head ? e0 + lane : a1 + (lane - head);
+        si = idx[es];
+        sv = val[es];
+    }
+    int g = a0 + 8 * lane;
+    u32x4 gi = {0, 0, 0, 0}, gv = {0, 0, 0, 0};
+    if (g < a1) {
+        gi = *(const u32x4 *)(idx + g);
+        gv = *(const u32x4 *)(val + g);
+    }
+    if (has_single) f(si, sv);
+    for (int s = lane + 64; s < singles; s += 64) {          // only without the 16-byte alignment
+        const int e = s < head ? e0 + s : a1 + (s - head);
+        f((uint32_t)idx[e], (uint32_t)val[e]);
+    }
+    while (g < a1) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) f((gi[j / 2] >> (16 * (j % 2))) & 0xFFFFu, (gv[j / 2] >> (16 * (j % 2))) & 0xFFFFu);
+        g += 512;
+        if (g < a1) {
+            gi = *(const u32x4 *)(idx + g);
+            gv = *(const u32x4 *)(val + g);
+        }
+    }
+}
+
 template <int D>
 __global__ __launch_bounds__(kResidualThreads) void residual_kernel(
     uint16_t *__restrict__ k_pool, uint16_t *__restrict__ v_pool, int num_pool_blocks, int hkv,
@@ -55,18 +97,17 @@ __global__ __launch_bounds__(kResidualThreads) void residual_kernel(
         // 2. this image's residual entries (LDS operations of one wave complete in order)
         const size_t r = (size_t)item * rows + row;
         const int e0 = res_ptr[r], e1 = res_ptr[r + 1];
-        for (int e = e0 + lane; e < e1; e += 64) {
-            const uint32_t i = res_idx[e];
+        for_row_entries(res_idx, res_val, e0, e1, lane, [&](uint32_t i, uint32_t bits) {
             if (i >= (uint32_t)kImg) {
                 bad = true;
-                continue;
+                return;
             }
             const uint32_t phys = is_v ? (i % D) * kBlock + i / D : i;   // V image: [d][slot]
             const float base = __uint_as_float((uint32_t)img[phys] << 16);
-            const float delta = __uint_as_float((uint32_t)res_val[e] << 16);
+            const float delta = __uint_as_float(bits << 16);
             const __bf16 sum = (__bf16)(base + delta);                   // round to nearest even
             img[phys] = __builtin_bit_cast(uint16_t, sum);
-        }
+        });
         __builtin_amdgcn_wave_barrier();
         // 3. LDS -> destination image
 #pragma unroll
@@ -131,15 +172,14 @@ __global__ __launch_bounds__(kResidualThreads) void residual_e4m3_kernel(
             // 2. this image's residual entries
             const size_t r = (size_t)item * rows + row;
             const int e0 = res_ptr[r], e1 = res_ptr[r + 1];
-            for (int e = e0 + lane; e < e1; e += 64) {
-                const uint32_t i = res_idx[e];
+            for_row_entries(res_idx, res_val, e0, e1, lane, [&](uint32_t i, uint32_t bits) {
                 if (i >= (uint32_t)kImg) {
                     bad = true;
-                    continue;
+                    return;
                 }
                 const uint32_t phys = is_v ? (i % D) * kBlock + i / D : i;   // V image: [d][slot]
-                img[phys] = __fadd_rn(img[phys], __uint_as_float((uint32_t)res_val[e] << 16));
-            }
+                img[phys] = __fadd_rn(img[phys], __uint_as_float(bits << 16));
+            });
             __builtin_amdgcn_wave_barrier();
             if (pass == 0) {
                 // 3a. this image's share of the tensor's maximum
@@ -238,16 +278,14 @@ __global__ __launch_bounds__(64 * HKV) void residual_e4m3_onepass_kernel(
         __builtin_amdgcn_wave_barrier();
         const size_t r = ((size_t)item * 2 + t) * HKV + h;
         const int e0 = res_ptr[r], e1 = res_ptr[r + 1];
-        for (int e = e0 + lane; e < e1; e += 64) {
-            const uint32_t i = res_idx[e];
+        for_row_entries(res_idx, res_val, e0, e1, lane, [&](uint32_t i, uint32_t bits) {
             if (i >= (uint32_t)kImg) {
                 bad = true;
-                continue;
+                return;
             }
             const uint32_t phys = t ? (i % D) * kBlock + i / D : i;          // V image: [d][slot]
-            const uint16_t v = res_val[e];
-            img[phys] = v == kNone ? (uint16_t)0xFFFEu : v;                  // still a negative NaN: the sum is one too
-        }
+            img[phys] = bits == kNone ? (uint16_t)0xFFFEu : (uint16_t)bits;  // still a negative NaN: the sum is one too
+        });
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
         __builtin_amdgcn_wave_barrier();
         float x[NJ][16];

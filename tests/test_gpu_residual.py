@@ -48,6 +48,17 @@ def test_reconstruction_is_bit_exact(shape):
     assert np.array_equal(R.bf16_to_bits(pool.k), want_k)
     assert np.array_equal(R.bf16_to_bits(pool.v), want_v)
     assert not np.isnan(OR.bf16_bits_to_f32(want_k[res.dst_blocks])).any()
+    # entry arrays off the 16-byte grid are read entry by entry: same blocks
+    pool2 = R.DevicePool.from_host(t, sess.device)
+    for key in ("idx", "val"):
+        dres[key] = torch.cat([torch.zeros(3, dtype=dres[key].dtype, device=sess.device), dres[key]])[3:]
+        assert dres[key].data_ptr() % 16 != 0
+    dres["status"].fill_(-77)
+    sess.apply_residual(pool2, dres)
+    torch.cuda.synchronize()
+    assert dres["status"].cpu().numpy().tolist() == [0] * res.num_items
+    assert torch.equal(pool2.k.view(torch.int16), pool.k.view(torch.int16))
+    assert torch.equal(pool2.v.view(torch.int16), pool.v.view(torch.int16))
 
 
 def test_densities_zero_and_one_and_no_items():
