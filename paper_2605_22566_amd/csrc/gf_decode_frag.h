@@ -97,21 +97,19 @@ __device__ __forceinline__ void load_pair(PairRegs<D, true> &p, const AttnArgs &
 
 // Differential KV (paper, "Differential-based KV Cache", Eq. 7) applied to a loaded pair of a bf16 pool: the
 // fragments go to the wave's LDS image `img` (2 * 16 * D elements: the two blocks back to back, and kPatchSpare
-// spare elements behind them), the residual
-// entries of the blocks that have one (items h0 / h1 of the CSR, -1 = none) are added there -- fp32 sum rounded to
-// bf16, the arithmetic of gf_kv_apply_residual, so the operands equal a reconstructed block bit for bit -- and the
-// fragments are read back; first K, then V through the same image.  K rows keep the pool's [slot][d] order with the
-// 16-byte pieces of a row XOR-ed by the slot (fragment stores and loads then spread over the banks); V keeps
-// [d][slot].  Entries outside the image are ignored.  The LDS operations of one wave complete in order.
+// spare elements behind them), the residual entries of the blocks that have one are added there -- fp32 sum
+// rounded to bf16, the arithmetic of gf_kv_apply_residual, so the operands equal a reconstructed block bit for
+// bit -- and the fragments are read back; first K, then V through the same image.  K rows keep the pool's
+// [slot][d] order with the 16-byte pieces of a row XOR-ed by the slot (fragment stores and loads then spread
+// over the banks); V keeps [d][slot].  Entries outside the image change nothing.
+constexpr int kPatchSpare = 8;
+
 // orders the LDS accesses of a wave's lanes before and after this point (for the compiler: a fence at
 // wavefront scope; the hardware runs one wave's LDS operations in order)
 __device__ __forceinline__ void wave_lds_order() {
     __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
     __builtin_amdgcn_wave_barrier();
 }
-
-// one residual entry: logical element i of the image (slot * D + d), bf16 bits in the low half of `bits`
-constexpr int kPatchSpare = 8;
 
 // LDS element of logical element i = slot * D + d of an image: K keeps [slot][d] with the 16-byte pieces of a row
 // XOR-ed by the slot, V is [d][slot].  An entry outside the image lands on `spare`, an element beside the images
@@ -123,6 +121,7 @@ __device__ __forceinline__ uint32_t patch_elem(uint32_t i, uint32_t spare) {
     return i >= (uint32_t)(kBlock * D) ? spare : phys;
 }
 
+// one residual entry: logical element i of the image, bf16 bits in the low half of `bits`
 template <int D, int TENSOR>
 __device__ __forceinline__ void add_entry(uint16_t *img, uint32_t i, uint32_t bits, uint32_t spare) {
     const uint32_t phys = patch_elem<D, TENSOR>(i, spare);
