@@ -78,14 +78,22 @@ __global__ __launch_bounds__(kDecodeThreads, RES ? 2 : 1) void decode_split_kern
         const int h = rh[e];
         return h >= 0 && h < rr.num_items ? h : -1;
     };
-    // ... and the entry ranges of their four CSR rows, fetched a pair ahead like the blocks themselves
-    int h0 = -1, h1 = -1, h0n = -1, h1n = -1;
-    int rows[8] = {0, 0, 0, 0, 0, 0, 0, 0}, rows_n[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    // ... and the entry ranges of the four CSR rows of a pair (empty without a residual), fetched two pairs ahead,
+    // so that the K rows of the next pair can be requested while the current pair is reduced
+    auto load_rows = [&](int e, int *out) {
+        row_ranges(rr, handle_of(e), kvh, a.hkv, out);
+        row_ranges(rr, handle_of(e + 1), kvh, a.hkv, out + 4);
+    };
+    auto rows_any = [](const int *x) {
+        return (x[1] - x[0]) + (x[3] - x[2]) + (x[5] - x[4]) + (x[7] - x[6]) > 0;
+    };
+    int rows[8] = {0, 0, 0, 0, 0, 0, 0, 0}, rows_n[8] = {0, 0, 0, 0, 0, 0, 0, 0}, rows_nn[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    RowLoad<D, 1> krow0, krow1;
     if constexpr (RES) {
-        h0 = handle_of(e0);
-        h1 = handle_of(e0 + 1);
-        row_ranges(rr, h0, kvh, a.hkv, rows);
-        row_ranges(rr, h1, kvh, a.hkv, rows + 4);
+        load_rows(e0, rows);
+        load_rows(e0 + 2, rows_n);
+        krow0.issue(rr, rows[0], rows[1], lane);
+        krow1.issue(rr, rows[4], rows[5], lane);
     }
 
     PairRegs<D, FP8> cur, nxt;
@@ -94,16 +102,13 @@ __global__ __launch_bounds__(kDecodeThreads, RES ? 2 : 1) void decode_split_kern
         const bool more = e + 2 < e1;
         if (more) load_pair(nxt, a, tab, ntk, e + 2, e1, kvh, lane);
         if constexpr (RES) {
-            if (more) {
-                h0n = handle_of(e + 2);
-                h1n = handle_of(e + 3);
-                row_ranges(rr, h0n, kvh, a.hkv, rows_n);
-                row_ranges(rr, h1n, kvh, a.hkv, rows_n + 4);
-            }
-            if (h0 >= 0 || h1 >= 0) {
+            load_rows(e + 4, rows_nn);
+            if (rows_any(rows)) {
                 __shared__ __attribute__((aligned(16))) uint16_t patch_img[kWavesPerWg][2 * kBlock * D + kPatchSpare];
-                patch_pair<D>(cur, patch_img[wave], rr, rows, lane);
+                patch_pair<D>(cur, patch_img[wave], rr, rows, krow0, krow1, lane);
             }
+            krow0.issue(rr, rows_n[0], rows_n[1], lane);      // empty rows (no residual, or no next pair): no loads
+            krow1.issue(rr, rows_n[4], rows_n[5], lane);
         }
 
         f32x4 sT[2];
@@ -158,10 +163,11 @@ __global__ __launch_bounds__(kDecodeThreads, RES ? 2 : 1) void decode_split_kern
         }
         if (more) cur = nxt;
         if constexpr (RES) {
-            h0 = h0n;
-            h1 = h1n;
 #pragma unroll
-            for (int i = 0; i < 8; ++i) rows[i] = rows_n[i];
+            for (int i = 0; i < 8; ++i) {
+                rows[i] = rows_n[i];
+                rows_n[i] = rows_nn[i];
+            }
         }
     }
 

@@ -221,15 +221,13 @@ struct RowLoad {
     }
 };
 
-// `rows`: row_ranges of the pair's two blocks (8 values: K0, V0, K1, V1)
+// `rows`: row_ranges of the pair's two blocks (8 values: K0, V0, K1, V1); k0, k1: the pair's two K rows, issued
+// by the caller a pair ahead (a K row of the paper's density fits 512 entries, a V row 1024)
 template <int D>
 __device__ __forceinline__ void patch_pair(PairRegs<D, false> &p, uint16_t *img, const ResidualRefs &rr,
-                                           const int *rows, int lane) {
+                                           const int *rows, RowLoad<D, 1> &k0, RowLoad<D, 1> &k1, int lane) {
     constexpr int kImg = kBlock * D;
-    RowLoad<D, 1> k0, k1;        // a K row of the paper's density fits 512 entries, a V row 1024
     RowLoad<D, 2> v0, v1;
-    k0.issue(rr, rows[0], rows[1], lane);
-    k1.issue(rr, rows[4], rows[5], lane);
     const int m = lane & 15, q4 = lane >> 4;
     uint16_t *kimg = img + (m >= 8 ? kImg : 0);
     const int slot0 = 8 * ((m >> 2) & 1) + (m & 3);
