@@ -1,5 +1,5 @@
 """The calls can be recorded into a HIP graph once a warm-up call has sized the context's buffers (no call
-allocates or synchronises after that): a captured resolve -> prefill -> decode (both paths) sequence, replayed
+allocates or synchronises after that): a captured resolve -> prefill -> decode (per request, per node, with read-time residuals) sequence, replayed
 several times with inputs changed in place and eager work in between, gives the eager result bit for bit."""
 import numpy as np
 import pytest
@@ -29,13 +29,20 @@ def test_captured_sequence_replays_like_eager(shape):
     total_q, max_q = int(q.shape[0]), int(wl.batch.new_lens.max())
     o = torch.zeros_like(q)
     qd = q[last].contiguous()
-    od, ods = torch.zeros_like(qd), torch.zeros_like(qd)
+    od, ods, odr = torch.zeros_like(qd), torch.zeros_like(qd), torch.zeros_like(qd)
+    # bf16 pools: the read-time residual step too (the first two table entries of every request carry an item)
+    bf16 = shape.kv_dtype == W.KV_BF16
+    handles = torch.full((wl.batch.num_req, max_blocks_of(wl)), -1, dtype=torch.int32, device=dev)
+    handles[:, :2] = torch.arange(2 * wl.batch.num_req, dtype=torch.int32, device=dev).view(-1, 2)
+    dres = R.random_residuals(shape, 2 * wl.batch.num_req, dev)[0] if bf16 else None
 
     def sequence():
         sess.resolve(db, tables)
         sess.prefill(pool, tables, q, q_ptr, total_q, max_q, o)
         sess.decode(pool, tables, qd, od)
         sess.decode_shared(pool, db, tables, qd, ods)
+        if bf16:
+            sess.decode_residual(pool, tables, handles, dres, qd, odr)
 
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
@@ -50,15 +57,19 @@ def test_captured_sequence_replays_like_eager(shape):
     for rep in range(3):
         q.mul_(-0.5 if rep == 1 else 1.5)               # new inputs in the same buffers
         qd.copy_(q[last])
-        for buf in (o, od, ods):
+        for buf in (o, od, ods, odr):
             buf.fill_(float("nan"))
         graph.replay()
         torch.cuda.synchronize()
-        got = [x.clone() for x in (o, od, ods)]
-        for buf in (o, od, ods):
+        got = [x.clone() for x in (o, od, ods, odr)]
+        for buf in (o, od, ods, odr):
             buf.fill_(float("nan"))
         sequence()                                      # the program's own eager work between replays
         torch.cuda.synchronize()
-        for name, g, e in zip(("prefill", "decode", "decode_shared"), got, (o, od, ods)):
+        for name, g, e in zip(("prefill", "decode", "decode_shared", "decode_residual"), got, (o, od, ods, odr)):
+            if name == "decode_residual" and not bf16:
+                continue
             assert torch.equal(g, e), f"{name}, replay {rep}"
             assert torch.isfinite(e.float()).all()
+        if bf16:
+            assert not torch.equal(odr, od)             # the residuals are seen
