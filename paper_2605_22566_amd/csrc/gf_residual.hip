@@ -20,6 +20,15 @@ namespace gf {
 constexpr int kResidualThreads = 256;
 constexpr int kResidualWaves = kResidualThreads / 64;
 
+// Orders the LDS accesses of a wave's lanes before and after this point: a wave's image is written with 16-byte
+// stores, patched element by element by other lanes, and read back with 16-byte loads.  For the compiler a fence
+// at wavefront scope (accesses of different types to the image must not pass each other); the hardware runs one
+// wave's LDS operations in order.
+__device__ __forceinline__ void wave_lds_order() {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+}
+
 // Calls f(index, value bits) for every entry of the CSR row [e0, e1), 64 lanes sharing the row.  Where the row
 // covers whole aligned groups of 8 entries a lane reads a group with one 16-byte load of indices and one of
 // values (whole row by single entries if the arrays do not start on a 16-byte boundary); the loads of the two
@@ -93,7 +102,7 @@ __global__ __launch_bounds__(kResidualThreads) void residual_kernel(
         // 1. base image -> LDS
 #pragma unroll
         for (int c = 8 * lane; c < kImg; c += 8 * 64) *(u32x4 *)(img + c) = *(const u32x4 *)(g_src + c);
-        __builtin_amdgcn_wave_barrier();
+        wave_lds_order();
         // 2. this image's residual entries (LDS operations of one wave complete in order)
         const size_t r = (size_t)item * rows + row;
         const int e0 = res_ptr[r], e1 = res_ptr[r + 1];
@@ -108,7 +117,7 @@ __global__ __launch_bounds__(kResidualThreads) void residual_kernel(
             const __bf16 sum = (__bf16)(base + delta);                   // round to nearest even
             img[phys] = __builtin_bit_cast(uint16_t, sum);
         });
-        __builtin_amdgcn_wave_barrier();
+        wave_lds_order();
         // 3. LDS -> destination image
 #pragma unroll
         for (int c = 8 * lane; c < kImg; c += 8 * 64) *(u32x4 *)(g_dst + c) = *(const u32x4 *)(img + c);
@@ -168,7 +177,7 @@ __global__ __launch_bounds__(kResidualThreads) void residual_e4m3_kernel(
                     img[c + 8 + i] = __fmul_rn((float)hi[i], s_in);
                 }
             }
-            __builtin_amdgcn_wave_barrier();
+            wave_lds_order();
             // 2. this image's residual entries
             const size_t r = (size_t)item * rows + row;
             const int e0 = res_ptr[r], e1 = res_ptr[r + 1];
@@ -180,7 +189,7 @@ __global__ __launch_bounds__(kResidualThreads) void residual_e4m3_kernel(
                 const uint32_t phys = is_v ? (i % D) * kBlock + i / D : i;   // V image: [d][slot]
                 img[phys] = __fadd_rn(img[phys], __uint_as_float(bits << 16));
             });
-            __builtin_amdgcn_wave_barrier();
+            wave_lds_order();
             if (pass == 0) {
                 // 3a. this image's share of the tensor's maximum
                 float m = 0.f;
@@ -207,7 +216,7 @@ __global__ __launch_bounds__(kResidualThreads) void residual_e4m3_kernel(
                     *(u32x2 *)(g_dst + c) = out;
                 }
             }
-            __builtin_amdgcn_wave_barrier();                   // the image region is reused by the wave's next row
+            wave_lds_order();                   // the image region is reused by the wave's next row
         }
         if (pass == 0) {
 #pragma unroll
@@ -274,8 +283,7 @@ __global__ __launch_bounds__(64 * HKV) void residual_e4m3_onepass_kernel(
         const u32x4 none = {0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu, 0xFFFFFFFFu};
 #pragma unroll
         for (int c = 8 * lane; c < kImg; c += 8 * 64) *(u32x4 *)(img + c) = none;
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        __builtin_amdgcn_wave_barrier();
+        wave_lds_order();
         const size_t r = ((size_t)item * 2 + t) * HKV + h;
         const int e0 = res_ptr[r], e1 = res_ptr[r + 1];
         for_row_entries(res_idx, res_val, e0, e1, lane, [&](uint32_t i, uint32_t bits) {
@@ -286,8 +294,7 @@ __global__ __launch_bounds__(64 * HKV) void residual_e4m3_onepass_kernel(
             const uint32_t phys = t ? (i % D) * kBlock + i / D : i;          // V image: [d][slot]
             img[phys] = bits == kNone ? (uint16_t)0xFFFEu : (uint16_t)bits;  // still a negative NaN: the sum is one too
         });
-        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-        __builtin_amdgcn_wave_barrier();
+        wave_lds_order();
         float x[NJ][16];
         float m = 0.f;
 #pragma unroll
