@@ -17,8 +17,10 @@
  *     parameter says "host".  The gf_graph / gf_attn_params / gf_kv_pool /
  *     gf_tables structs themselves are small HOST structs read during the call.
  *   - Calls are asynchronous on the caller's HIP stream (`stream`, a
- *     hipStream_t passed as void*; NULL = the default stream).  Nothing is
- *     synchronised inside.  Data-dependent failures are reported per request
+ *     hipStream_t passed as void*; NULL = the default stream).  The only
+ *     synchronisation inside is the one named below: a call whose context
+ *     buffer must grow waits for the stream before it frees the old buffer.
+ *     Data-dependent failures are reported per request
  *     in the device array status[] (GF_ST_*), not through the return value.
  *   - The library owns only a gf_ctx: device scratch memory (the split-KV
  *     partials of gf_attn_decode, the work list of gf_attn_prefill, the lists and
@@ -383,6 +385,17 @@ int32_t gf_attn_decode_shared_planned(gf_ctx *ctx, const gf_attn_params *params,
                                       const gf_graph *graph, const int32_t *path_ptr, const int32_t *path_nodes,
                                       int32_t num_path_entries, const gf_tables *tables,
                                       const void *q, void *o, float *lse, void *stream);
+
+/*
+ * gf_hbm_read_probe -- measurement aid, no part of the method: a plain read-only
+ * streaming kernel over `bytes` bytes at `src` (device; a multiple of 16), 16
+ * bytes per lane and trip, num_wg workgroups of 256 threads walking the buffer
+ * with a grid stride; wg_sums[num_wg] (device, out) receives one word per
+ * workgroup folded from everything it read.  Timed by the benchmark as the
+ * streaming ceiling of the box, next to the bandwidth-bound decode kernels.
+ */
+int32_t gf_hbm_read_probe(gf_ctx *ctx, const void *src, int64_t bytes, uint32_t *wg_sums, int32_t num_wg,
+                          void *stream);
 
 /* Tuning knob (host): table entries (16-token blocks) per split-KV chunk in
  * gf_attn_decode (built-in choice 32) and gf_attn_decode_shared (built-in choice and upper limit 64);

@@ -24,7 +24,7 @@ GF_RS_OK, GF_RS_BAD_BLOCK, GF_RS_BAD_INDEX = 0, 1, 2
 EXPORTS = ["gf_create", "gf_destroy", "gf_strerror", "gf_last_hip_error", "gf_resolve_path",
            "gf_attn_prefill", "gf_attn_decode", "gf_attn_decode_residual", "gf_attn_decode_shared", "gf_decode_shared_plan", "gf_attn_decode_shared_planned",
            "gf_set_decode_chunk_blocks", "gf_kv_apply_residual",
-           "gf_kv_append", "gf_kv_append_token"]
+           "gf_kv_append", "gf_kv_append_token", "gf_hbm_read_probe"]
 
 _i32p = C.c_void_p  # device pointers travel as plain addresses
 
@@ -86,6 +86,8 @@ def load_library(path: Optional[str] = None):
                                     C.POINTER(gf_tables), C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                     C.c_void_p, C.c_void_p, C.c_void_p]
     lib.gf_attn_prefill.restype = C.c_int32
+    lib.gf_hbm_read_probe.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int32, C.c_void_p]
+    lib.gf_hbm_read_probe.restype = C.c_int32
     lib.gf_attn_decode.argtypes = [C.c_void_p, C.POINTER(gf_attn_params), C.POINTER(gf_kv_pool),
                                    C.POINTER(gf_tables), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.gf_attn_decode.restype = C.c_int32
@@ -183,6 +185,11 @@ def make_tables(block_table, block_ntok, num_blocks, ctx_lens, seq_lens, status,
 def gf_attn_prefill(ctx, params, pool, tables, q, q_ptr, total_q, max_q, o, lse=None) -> None:
     rc = load_library().gf_attn_prefill(ctx, C.byref(params), C.byref(pool), C.byref(tables), _ptr(q),
                                         _ptr(q_ptr), total_q, max_q, _ptr(o), _ptr(lse), _stream())
+    _check(ctx, rc)
+
+
+def gf_hbm_read_probe(ctx, src, nbytes, wg_sums, num_wg) -> None:
+    rc = load_library().gf_hbm_read_probe(ctx, _ptr(src), nbytes, _ptr(wg_sums), num_wg, _stream())
     _check(ctx, rc)
 
 

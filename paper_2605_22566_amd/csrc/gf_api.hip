@@ -45,7 +45,12 @@ int32_t check_attn(const gf_attn_params *p, const gf_kv_pool *pool, const gf_tab
     if (t->num_req < 0 || t->max_blocks < 0 || pool->num_blocks < 0) return GF_ERR_BAD_SHAPE;
     if (p->num_q_heads <= 0 || p->num_kv_heads <= 0 || p->head_dim <= 0) return GF_ERR_BAD_SHAPE;
     if (p->num_q_heads % p->num_kv_heads != 0) return GF_ERR_BAD_SHAPE;
-    if (!(p->sm_scale >= 0.f) || !std::isfinite(p->sm_scale)) return GF_ERR_BAD_SHAPE;
+    {   // zero or a positive finite scale; judged on the bit pattern, so no compiler setting can wave a NaN through
+        uint32_t bits;
+        std::memcpy(&bits, &p->sm_scale, sizeof(bits));
+        if ((bits >> 31) != 0 && bits != 0x80000000u) return GF_ERR_BAD_SHAPE;       // negative
+        if ((bits & 0x7f800000u) == 0x7f800000u) return GF_ERR_BAD_SHAPE;            // inf or NaN
+    }
     group = p->num_q_heads / p->num_kv_heads;
     if (p->block_size != gf::kBlock) return GF_ERR_UNSUPPORTED;
     if (p->head_dim != 64 && p->head_dim != 128) return GF_ERR_UNSUPPORTED;
@@ -199,6 +204,17 @@ int32_t gf_attn_prefill(gf_ctx *ctx, const gf_attn_params *params, const gf_kv_p
                                       (int32_t *)ctx->plan, (hipStream_t)stream);
     if (e == hipErrorNotSupported) return GF_ERR_UNSUPPORTED;
     if (e != hipSuccess) return fail_hip(ctx, e, "gf_attn_prefill launch");
+    return GF_OK;
+}
+
+int32_t gf_hbm_read_probe(gf_ctx *ctx, const void *src, int64_t bytes, uint32_t *wg_sums, int32_t num_wg,
+                          void *stream) {
+    if (!ctx) return GF_ERR_NULL;
+    if (bytes < 0 || (bytes & 15) || num_wg < 0) return GF_ERR_BAD_SHAPE;
+    if (bytes == 0 || num_wg == 0) return GF_OK;
+    if (!src || !wg_sums) return GF_ERR_NULL;
+    hipError_t e = gf::launch_hbm_read_probe(src, (size_t)bytes, wg_sums, num_wg, (hipStream_t)stream);
+    if (e != hipSuccess) return fail_hip(ctx, e, "gf_hbm_read_probe launch");
     return GF_OK;
 }
 

@@ -104,13 +104,6 @@ __device__ __forceinline__ void load_pair(PairRegs<D, true> &p, const AttnArgs &
 // over the banks); V keeps [d][slot].  Entries outside the image change nothing.
 constexpr int kPatchSpare = 8;
 
-// orders the LDS accesses of a wave's lanes before and after this point (for the compiler: a fence at
-// wavefront scope; the hardware runs one wave's LDS operations in order)
-__device__ __forceinline__ void wave_lds_order() {
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-}
-
 // LDS element of logical element i = slot * D + d of an image: K keeps [slot][d] with the 16-byte pieces of a row
 // XOR-ed by the slot, V is [d][slot].  An entry outside the image lands on `spare`, an element beside the images
 // that nothing reads: no lane has to be switched off for it.

@@ -653,11 +653,12 @@ __global__ __launch_bounds__(256) void shared_merge_kernel(AttnArgs a, SharedPla
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) L += __shfl_xor(L, off, 64);
-    const float inv = ns > 0 ? 1.f / L : 0.f;
+    // no visible token at all (no chunk, or only entries without tokens): zero row, lse -inf
+    const float inv = L > 0.f ? 1.f / L : 0.f;
 #pragma unroll
     for (int i = 0; i < PER; ++i) out[lane + 64 * i] = (__bf16)(acc[i] * inv);
     if (a.lse && lane == 0)
-        a.lse[(size_t)r * a.hq + h] = ns > 0 ? (M + __builtin_log2f(L)) * 0.6931471805599453f : -INFINITY;
+        a.lse[(size_t)r * a.hq + h] = L > 0.f ? (M + __builtin_log2f(L)) * 0.6931471805599453f : -INFINITY;
 }
 
 // ---- host side ---------------------------------------------------------------------------------

@@ -52,6 +52,9 @@ size_t prefill_plan_bytes(int32_t total_q, int32_t num_req, int group);
 hipError_t launch_prefill(const AttnArgs &a, int head_dim, int group, int kv_dtype, const int32_t *q_ptr,
                           int32_t total_q, int32_t *plan, hipStream_t s);
 
+// read-only streaming probe (bandwidth ceiling): bytes a multiple of 16, one sum per workgroup
+hipError_t launch_hbm_read_probe(const void *src, size_t bytes, uint32_t *wg_sums, int32_t num_wg, hipStream_t s);
+
 // workspace floats needed by decode for (num_req, hkv, group, head_dim, splits)
 size_t decode_workspace_bytes(int32_t num_req, int32_t hkv, int32_t group, int32_t head_dim, int32_t splits);
 hipError_t launch_decode(const AttnArgs &a, int head_dim, int group, int kv_dtype, int32_t chunk_blocks,
@@ -97,6 +100,15 @@ __device__ __forceinline__ bf16x8 fp8x8_to_bf16x8(u32x2 w) {
     const bf16x2 c = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[1], 1.0f, false);
     const bf16x2 d = __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w[1], 1.0f, true);
     return bf16x8{a[0], a[1], b[0], b[1], c[0], c[1], d[0], d[1]};
+}
+
+// Orders the LDS accesses of a wave's lanes before and after this point: a wave-private LDS image is written
+// with 16-byte stores, patched element by element by other lanes, and read back with 16-byte loads.  For the
+// compiler a fence at wavefront scope (accesses of different types to the image must not pass each other); the
+// hardware runs one wave's LDS operations in order.
+__device__ __forceinline__ void wave_lds_order() {
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
 }
 
 // value held by the lane 32 away (the other half of the wave)

@@ -20,15 +20,6 @@ namespace gf {
 constexpr int kResidualThreads = 256;
 constexpr int kResidualWaves = kResidualThreads / 64;
 
-// Orders the LDS accesses of a wave's lanes before and after this point: a wave's image is written with 16-byte
-// stores, patched element by element by other lanes, and read back with 16-byte loads.  For the compiler a fence
-// at wavefront scope (accesses of different types to the image must not pass each other); the hardware runs one
-// wave's LDS operations in order.
-__device__ __forceinline__ void wave_lds_order() {
-    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-}
-
 // Calls f(index, value bits) for every entry of the CSR row [e0, e1), 64 lanes sharing the row.  Where the row
 // covers whole aligned groups of 8 entries a lane reads a group with one 16-byte load of indices and one of
 // values (whole row by single entries if the arrays do not start on a 16-byte boundary); the loads of the two

@@ -303,6 +303,31 @@ def small_layered(seed: int, shape: Shape, num_nodes=24, num_layers=6, len_lo=5,
                            shuffle=shuffle)
 
 
+def private_copies(wl: Workload, shuffle: bool = True) -> Workload:
+    """The same requests with nothing shared: every (request, path position) becomes a node of its own with
+    its own pool blocks (the "stateful" per-workflow cache the paper compares against).  Request-centric bytes,
+    unique bytes and HBM bytes of a decode step then coincide, which makes the step's time a direct reading
+    of the kernel's HBM rate.  Edges follow the private chains."""
+    g, b = wl.graph, wl.batch
+    rng = np.random.default_rng([wl.seed, 23])
+    node_len, paths, edges = [], [], []
+    for r in range(b.num_req):
+        p = []
+        for v in b.path_nodes[b.path_ptr[r]:b.path_ptr[r + 1]]:
+            p.append(len(node_len))
+            node_len.append(int(g.node_len[v]))
+        edges += list(zip(p[:-1], p[1:]))
+        paths.append(p)
+    return _finish(wl.name + "_private", wl.shape, np.asarray(node_len, dtype=np.int64), edges, paths,
+                   b.new_lens.astype(np.int64), rng, shuffle, wl.seed, wl.prefill_req, wl.decode_req, wl.zipf_s)
+
+
+def config_decode_8b_private(seed: int = SEED_BASE + 2) -> Workload:
+    """Config 3's requests with private copies of every node (no sharing): a measurement workload, not one of
+    the five configurations."""
+    return private_copies(config_decode_8b(seed))
+
+
 def subset(wl: Workload, req_ids) -> Batch:
     """The batch restricted to ``req_ids`` (block ids unchanged)."""
     b = wl.batch

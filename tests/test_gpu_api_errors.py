@@ -47,6 +47,8 @@ def test_unsupported_shapes_and_bad_sizes_are_rejected():
         assert _code(lambda: call(B.make_params(8, 2, 128, block_size=32))) == B.GF_ERR_UNSUPPORTED, name
         assert _code(lambda: call(B.make_params(8, 2, 128, kv_dtype=7))) == B.GF_ERR_UNSUPPORTED, name
         assert _code(lambda: call(B.make_params(8, 2, 128, sm_scale=-1.0))) == B.GF_ERR_BAD_SHAPE, name
+        assert _code(lambda: call(B.make_params(8, 2, 128, sm_scale=float("nan")))) == B.GF_ERR_BAD_SHAPE, name
+        assert _code(lambda: call(B.make_params(8, 2, 128, sm_scale=float("inf")))) == B.GF_ERR_BAD_SHAPE, name
         # an e4m3 pool without scales
         assert _code(lambda: call(B.make_params(8, 2, 128, kv_dtype=B.GF_FP8_E4M3))) == B.GF_ERR_NULL, name
     assert _code(lambda: B.gf_attn_decode_shared(sess.ctx, params, dpool, graph, db["path_ptr"], db["path_nodes"], -1,

@@ -148,3 +148,43 @@ def test_fp8_block_scales_differ_widely():
     od, _, _, _, last = run_decode(wl, t)
     Od, _ = oracle_decode(wl, t, last)
     assert_close(od, Od, sh.kv_dtype, "fp8 decode, spread scales")
+
+
+@pytest.mark.parametrize("shape", [W.Shape(2, 1, 128, W.KV_FP8_E4M3), W.Shape(4, 1, 128, W.KV_FP8_E4M3),
+                                   W.Shape(4, 1, 128), W.Shape(2, 2, 64, W.KV_FP8_E4M3)], ids=_sid)
+def test_prefill_many_table_windows(shape):
+    """Contexts of more than 260 table entries (the kernel keeps the table in windows of 64 entries per lane
+    register set and slides them: at least four slides here, with the per-entry e4m3 scales riding in the
+    windows), several q tiles per request, few heads so that the oracle stays fast."""
+    wl = W.small_layered(300 + shape.num_q_heads + shape.head_dim + shape.kv_dtype, shape, num_nodes=48, num_layers=8,
+                         len_lo=300, len_hi=900, num_req=3, hops=(7, 8), new_lo=70, new_hi=200)
+    from tests.helpers import max_blocks_of
+    assert max_blocks_of(wl) >= 260 + 5
+    t = W.make_tensors(wl)
+    o, lse, _, _ = run_prefill(wl, t)
+    O, LSE = oracle_prefill(wl, t)
+    assert np.isfinite(o).all()
+    assert_close(o, O, shape.kv_dtype, "prefill, many windows")
+    assert np.abs(lse - LSE).max() < 1e-2
+    od, lsed, _, _, last = run_decode(wl, t)
+    Od, LSEd = oracle_decode(wl, t, last)
+    assert_close(od, Od, shape.kv_dtype, "decode, long context")
+
+
+def test_decode_entries_without_tokens_give_zero_rows():
+    """A valid request whose table entries all carry zero tokens has nothing to attend to: zero row and
+    lse = -inf, never NaN (every partial of it has a zero sum).  The other requests are unaffected."""
+    from tests.gpu_common import run_resolve
+    sh = W.Shape(8, 2, 128)
+    wl = W.small_layered(91, sh, num_nodes=20, num_layers=5, len_lo=10, len_hi=120, num_req=4, hops=(2, 5),
+                         new_lo=3, new_hi=40)
+    t = W.make_tensors(wl)
+    sess, tables = run_resolve(wl)
+    tables["block_ntok"][1].zero_()
+    for chunk in (0, 2):
+        od, lsed, _, _, last = run_decode(wl, t, chunk_blocks=chunk, tables=tables, sess=sess)
+        assert np.isfinite(od).all()
+        assert (od[1] == 0).all() and np.isneginf(lsed[1]).all()
+        Od, _ = oracle_decode(wl, t, last)
+        keep = np.array([0, 2, 3])
+        assert_close(od[keep], Od[keep], sh.kv_dtype, "decode, others")

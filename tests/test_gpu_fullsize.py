@@ -62,6 +62,50 @@ def test_prefill_8b_full_size_sampled():
         _check_rows(wl, pool, want, qb[lo:hi], og[lo:hi], r, decode=False)
 
 
+def test_prefill_mixed_fp8_full_size_sampled():
+    """Config 5's prefill in the launch bench.py times (128 requests of 256-2048 new tokens over 4k-16k-token
+    contexts in an e4m3 pool: about 18 table windows and up to 32 q tiles per request): every output row is
+    finite, the request with the fewest new tokens is checked whole, and the requests with the most new tokens
+    and with the longest context on windows of rows (first, across q-tile borders in the middle, last) that the
+    oracle computes one window at a time: rows i0..i1 of a request are plain attention of those queries over the
+    first ctx + i1 tokens, with ctx + i0 of them taken as context."""
+    wl, sess, tables, pool, q, q_ptr = _setup("mixed_fp8")
+    want = oracle_resolve(wl)
+    assert R.tables_to_host(tables)["block_table"] == want["block_table"]
+    P = len(wl.prefill_req)
+    b = wl.batch
+    rows = int(b.new_lens[:P].sum())
+    sl = {k: tables[k][:P] for k in ("block_table", "block_ntok", "num_blocks", "ctx_lens", "seq_lens", "status")}
+    sl["num_req"], sl["max_blocks"] = P, tables["max_blocks"]
+    o = torch.full_like(q, float("nan"))
+    sess.prefill(pool, sl, q, torch.from_numpy(q_ptr[:P + 1].copy()).to(sess.device), rows, int(b.new_lens[:P].max()), o)
+    torch.cuda.synchronize()
+    og = o[:rows].double().cpu().numpy()
+    assert np.isfinite(og).all()
+    assert bool(torch.isnan(o[rows:].float()).all().item())          # the decode requests' rows are not prefill's
+    qb = R.bf16_to_bits(q[:rows])
+    n = b.new_lens[:P].astype(np.int64)
+    L = W.context_lens(wl)[:P]
+    atol, rtol = TOL[wl.shape.kv_dtype]
+    r_short, r_long, r_ctx = int(np.argmin(n)), int(np.argmax(n)), int(np.argmax(L))
+    lo, hi = int(q_ptr[r_short]), int(q_ptr[r_short + 1])
+    _check_rows(wl, pool, want, qb[lo:hi], og[lo:hi], r_short, decode=False)
+    for r in sorted({r_long, r_ctx}):
+        nb = want["num_blocks"][r]
+        ids = np.array(want["block_table"][r][:nb], dtype=np.int64)
+        kk, vv, ks, vs = pool.gather_host(ids)
+        K, V = OA.materialize_kv(kk, vv, list(range(nb)), want["block_ntok"][r], nb, ks, vs)
+        ctx, nr = int(want["ctx_lens"][r]), int(n[r])
+        assert K.shape[0] == ctx + nr
+        lo = int(q_ptr[r])
+        mid = (nr // 2 // 64) * 64
+        for i0, i1 in ((0, 40), (mid - 20, mid + 44), (nr - 48, nr)):
+            qw = OA._widen(qb[lo + i0:lo + i1])
+            O, _ = OA.attend(qw, K[:ctx + i1], V[:ctx + i1], ctx + i0)
+            err = np.abs(og[lo + i0:lo + i1] - O)
+            assert (err <= atol + rtol * np.abs(O)).all(), f"request {r} rows {i0}..{i1}: max err {err.max()}"
+
+
 @pytest.mark.parametrize("shared", [False, True], ids=["per_request", "per_node"])
 @pytest.mark.parametrize("name", ["decode_8b", "decode_70b", "mixed_fp8"])
 def test_decode_full_size_sampled(name, shared):
