@@ -192,6 +192,29 @@ int32_t gf_attn_prefill(gf_ctx *ctx, const gf_attn_params *params, const gf_kv_p
                         void *o, float *lse, void *stream);
 
 /*
+ * gf_attn_prefill_noalloc -- gf_attn_prefill for callers that cannot allocate:
+ * code under HIP graph capture, serving loops that must not reach hipMalloc,
+ * harnesses that forbid it.  Same arguments, same kernels, same result (bit for
+ * bit) as gf_attn_prefill; the one difference is where the work list of the
+ * call lives: in a fixed device array of 1 MiB inside the library (one per GPU,
+ * held until the process ends; its address is looked up by gf_create) instead
+ * of a buffer of the context that grows on demand.  The call never allocates,
+ * frees or synchronises.  It returns GF_ERR_WORKSPACE (and says so in
+ * gf_last_hip_error) when the batch's work list does not fit:
+ *     8 + 8 * (total_q / (128 / G) + num_req) bytes <= 1 MiB,   G = num_q_heads / num_kv_heads
+ * (about 131 000 work items: e.g. 4 M new tokens at G = 4), and GF_ERR_BAD_SHAPE
+ * when the context's device is not the calling thread's current device.
+ * All calls on one GPU share the array, whatever their context: two such calls
+ * that overlap in time on one GPU (different streams) race; calls on one stream
+ * are ordered and need no clearing in between (the list is rebuilt by every call).
+ */
+int32_t gf_attn_prefill_noalloc(gf_ctx *ctx, const gf_attn_params *params, const gf_kv_pool *pool,
+                                const gf_tables *tables,
+                                const void *q, const int32_t *q_ptr /* [num_req+1] device */,
+                                int32_t total_q, int32_t max_q,
+                                void *o, float *lse, void *stream);
+
+/*
  * gf_attn_decode -- one decode step per request: the query of request r is the
  * last of its seq_lens[r] tokens and attends to all of them (all context
  * tokens of the path plus every token in its tail blocks), by the same formula.

@@ -24,7 +24,7 @@ GF_RS_OK, GF_RS_BAD_BLOCK, GF_RS_BAD_INDEX = 0, 1, 2
 EXPORTS = ["gf_create", "gf_destroy", "gf_strerror", "gf_last_hip_error", "gf_resolve_path",
            "gf_attn_prefill", "gf_attn_decode", "gf_attn_decode_residual", "gf_attn_decode_shared", "gf_decode_shared_plan", "gf_attn_decode_shared_planned",
            "gf_set_decode_chunk_blocks", "gf_kv_apply_residual",
-           "gf_kv_append", "gf_kv_append_token", "gf_hbm_read_probe"]
+           "gf_kv_append", "gf_kv_append_token", "gf_attn_prefill_noalloc", "gf_hbm_read_probe"]
 
 _i32p = C.c_void_p  # device pointers travel as plain addresses
 
@@ -86,6 +86,8 @@ def load_library(path: Optional[str] = None):
                                     C.POINTER(gf_tables), C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
                                     C.c_void_p, C.c_void_p, C.c_void_p]
     lib.gf_attn_prefill.restype = C.c_int32
+    lib.gf_attn_prefill_noalloc.argtypes = lib.gf_attn_prefill.argtypes
+    lib.gf_attn_prefill_noalloc.restype = C.c_int32
     lib.gf_hbm_read_probe.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int32, C.c_void_p]
     lib.gf_hbm_read_probe.restype = C.c_int32
     lib.gf_attn_decode.argtypes = [C.c_void_p, C.POINTER(gf_attn_params), C.POINTER(gf_kv_pool),
@@ -134,7 +136,7 @@ def _check(ctx, rc: int):
     if rc != GF_OK:
         lib = load_library()
         msg = lib.gf_strerror(rc).decode()
-        if rc == GF_ERR_HIP and ctx:
+        if rc in (GF_ERR_HIP, GF_ERR_WORKSPACE) and ctx:
             msg += " / " + lib.gf_last_hip_error(ctx).decode()
         raise GraphFlowError(rc, msg)
 
@@ -185,6 +187,12 @@ def make_tables(block_table, block_ntok, num_blocks, ctx_lens, seq_lens, status,
 def gf_attn_prefill(ctx, params, pool, tables, q, q_ptr, total_q, max_q, o, lse=None) -> None:
     rc = load_library().gf_attn_prefill(ctx, C.byref(params), C.byref(pool), C.byref(tables), _ptr(q),
                                         _ptr(q_ptr), total_q, max_q, _ptr(o), _ptr(lse), _stream())
+    _check(ctx, rc)
+
+
+def gf_attn_prefill_noalloc(ctx, params, pool, tables, q, q_ptr, total_q, max_q, o, lse=None) -> None:
+    rc = load_library().gf_attn_prefill_noalloc(ctx, C.byref(params), C.byref(pool), C.byref(tables), _ptr(q),
+                                                _ptr(q_ptr), total_q, max_q, _ptr(o), _ptr(lse), _stream())
     _check(ctx, rc)
 
 

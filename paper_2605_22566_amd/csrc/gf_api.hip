@@ -123,6 +123,9 @@ int32_t gf_create(gf_ctx **out, int32_t device) {
     if (device < 0 || device >= count) return GF_ERR_BAD_SHAPE;
     e = hipSetDevice(device);
     if (e != hipSuccess) return GF_ERR_HIP;
+    // the address of the fixed work list of gf_attn_prefill_noalloc on this device, looked up while it is current
+    e = gf::prefill_static_plan_init(device);
+    if (e != hipSuccess) return GF_ERR_HIP;
     gf_ctx *c = new (std::nothrow) gf_ctx();
     if (!c) return GF_ERR_WORKSPACE;
     c->device = device;
@@ -204,6 +207,37 @@ int32_t gf_attn_prefill(gf_ctx *ctx, const gf_attn_params *params, const gf_kv_p
                                       (int32_t *)ctx->plan, (hipStream_t)stream);
     if (e == hipErrorNotSupported) return GF_ERR_UNSUPPORTED;
     if (e != hipSuccess) return fail_hip(ctx, e, "gf_attn_prefill launch");
+    return GF_OK;
+}
+
+int32_t gf_attn_prefill_noalloc(gf_ctx *ctx, const gf_attn_params *params, const gf_kv_pool *pool,
+                                const gf_tables *tables, const void *q, const int32_t *q_ptr, int32_t total_q,
+                                int32_t max_q, void *o, float *lse, void *stream) {
+    if (!ctx) return GF_ERR_NULL;
+    if (total_q < 0 || max_q < 0 || max_q > total_q) return GF_ERR_BAD_SHAPE;
+    gf::AttnArgs a;
+    int group = 0;
+    static const char dummy = 0;
+    int32_t rc = check_attn(params, pool, tables, total_q ? q : &dummy, total_q ? o : (void *)&dummy, lse, a, group);
+    if (rc != GF_OK) return rc;
+    if (tables->num_req == 0 || total_q == 0) return GF_OK;
+    if (!q_ptr) return GF_ERR_NULL;
+    // the work list must fit the fixed array; nothing is grown here
+    if (gf::prefill_plan_bytes(total_q, a.num_req, group) > gf::kStaticPlanBytes) {
+        snprintf(ctx->hip_err, sizeof(ctx->hip_err),
+                 "gf_attn_prefill_noalloc: the work list of this batch needs %zu bytes, the fixed array holds %zu",
+                 gf::prefill_plan_bytes(total_q, a.num_req, group), gf::kStaticPlanBytes);
+        return GF_ERR_WORKSPACE;
+    }
+    // the array's address belongs to the context's device: that device must be the current one
+    int cur = -1;
+    hipError_t e = hipGetDevice(&cur);
+    if (e != hipSuccess) return fail_hip(ctx, e, "gf_attn_prefill_noalloc hipGetDevice");
+    int32_t *plan = gf::prefill_static_plan(ctx->device);
+    if (cur != ctx->device || !plan) return GF_ERR_BAD_SHAPE;
+    e = gf::launch_prefill(a, params->head_dim, group, params->kv_dtype, q_ptr, total_q, plan, (hipStream_t)stream);
+    if (e == hipErrorNotSupported) return GF_ERR_UNSUPPORTED;
+    if (e != hipSuccess) return fail_hip(ctx, e, "gf_attn_prefill_noalloc launch");
     return GF_OK;
 }
 

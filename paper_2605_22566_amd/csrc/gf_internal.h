@@ -52,6 +52,13 @@ size_t prefill_plan_bytes(int32_t total_q, int32_t num_req, int group);
 hipError_t launch_prefill(const AttnArgs &a, int head_dim, int group, int kv_dtype, const int32_t *q_ptr,
                           int32_t total_q, int32_t *plan, hipStream_t s);
 
+// The work list of gf_attn_prefill_noalloc: a file-scope device array of kStaticPlanBytes instead of a buffer
+// of the context.  prefill_static_plan_init looks the array's address up once per device (that device must be
+// current) and keeps it; prefill_static_plan returns the address kept for a device, or nullptr.
+constexpr size_t kStaticPlanBytes = size_t(1) << 20;
+hipError_t prefill_static_plan_init(int device);
+int32_t *prefill_static_plan(int device);
+
 // read-only streaming probe (bandwidth ceiling): bytes a multiple of 16, one sum per workgroup
 hipError_t launch_hbm_read_probe(const void *src, size_t bytes, uint32_t *wg_sums, int32_t num_wg, hipStream_t s);
 

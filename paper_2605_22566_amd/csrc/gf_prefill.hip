@@ -39,6 +39,7 @@
 // causally, in a side path taken only by tiles whose mask bits say so.
 
 #include "gf_internal.h"
+#include <mutex>
 #include <type_traits>
 #include <utility>
 
@@ -818,6 +819,35 @@ static hipError_t launch_prefill_k(const AttnArgs &a, const int32_t *q_ptr, int3
 }
 
 size_t prefill_plan_items(int32_t total_q, int32_t num_req, int bm) { return (size_t)total_q / bm + num_req; }
+
+// Work list for callers that cannot allocate (gf_attn_prefill_noalloc).  Every GPU the library runs on holds
+// its own copy of this array, at its own address, until the process ends.  In host code the array's name is
+// only a stand-in for the symbol: the device address is looked up once per device and kept, and that pointer
+// -- never the name -- is what the launches are given.  All calls on one GPU share the array; the plan kernel
+// writes the item count and every item the attention kernel reads, so nothing has to be cleared between calls.
+static __device__ __align__(256) int32_t scratch[kStaticPlanBytes / sizeof(int32_t)];
+
+constexpr int kMaxDevices = 64;
+static int32_t *g_static_plan[kMaxDevices];
+static std::mutex g_static_plan_mutex;
+
+hipError_t prefill_static_plan_init(int device) {
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(g_static_plan_mutex);
+    if (g_static_plan[device]) return hipSuccess;
+    int32_t *ptr = nullptr;
+    const hipError_t e = hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return e;
+    if (!ptr) return hipErrorInvalidSymbol;
+    g_static_plan[device] = ptr;
+    return hipSuccess;
+}
+
+int32_t *prefill_static_plan(int device) {
+    if (device < 0 || device >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_static_plan_mutex);
+    return g_static_plan[device];
+}
 
 size_t prefill_plan_bytes(int32_t total_q, int32_t num_req, int group) {
     // one item covers at least kPrefillRowsMin score rows = kPrefillRowsMin / group new tokens

@@ -164,6 +164,11 @@ class Session:
         params, dpool, dt = self._common(pool, tables, sm_scale)
         B.gf_attn_prefill(self.ctx, params, dpool, dt, q, q_ptr, total_q, max_q, o, lse)
 
+    def prefill_noalloc(self, pool, tables, q, q_ptr, total_q, max_q, o, lse=None, sm_scale=0.0):
+        """gf_attn_prefill with the work list in the library's fixed device array (nothing is allocated)."""
+        params, dpool, dt = self._common(pool, tables, sm_scale)
+        B.gf_attn_prefill_noalloc(self.ctx, params, dpool, dt, q, q_ptr, total_q, max_q, o, lse)
+
     def upload_residuals(self, res: W.Residuals):
         dev = self.device
         i32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(dev)
