@@ -56,7 +56,9 @@ def _event_median_ms(fn, torch, iters, before=None):
 
 
 def _read_traffic(name):
-    """HBM bytes per launch from the committed rocprofv3 --pmc summary, if any."""
+    """HBM bytes per launch of a kernel (read + written) from the rocprofv3 --pmc summary kept under
+    profiles/ (TCC request counters at the memory side of L2, summed over channels: 32-byte DRAM read and
+    write requests x 32; no calibration factor), or None.  The file names the command that produced it."""
     p = os.path.join(ROOT, "profiles", f"{name}_traffic.txt")
     if not os.path.exists(p):
         return None
@@ -68,9 +70,32 @@ def _read_traffic(name):
                 vals[k.strip()] = float(v.split()[0])
             except ValueError:
                 pass
-    if "FETCH_BYTES_PER_LAUNCH" in vals and "WRITE_BYTES_PER_LAUNCH" in vals:
-        return vals["FETCH_BYTES_PER_LAUNCH"] + vals["WRITE_BYTES_PER_LAUNCH"]
+    if "DRAM_READ_BYTES_PER_LAUNCH" in vals and "DRAM_WRITE_BYTES_PER_LAUNCH" in vals:
+        return vals["DRAM_READ_BYTES_PER_LAUNCH"] + vals["DRAM_WRITE_BYTES_PER_LAUNCH"]
     return None
+
+
+def hbm_roofline(kernel, alg_bytes, ms, traffic, logical_bytes=None, unique_bytes=None):
+    """Roofline object of a bandwidth-bound kernel.  `achieved` counts only bytes that must cross the HBM pins:
+    the algorithmic bytes where nothing is shared between the kernel's work items (then they equal the unique
+    bytes), else the unique bytes the launch touches -- a lower bound, since a block shared by several requests
+    may be served from L2 or the Infinity Cache after its first read.  Request-centric logical bytes are a
+    rate, never a fraction; `traffic` is what the counters saw leaving L2 (requests to the memory fabric, which
+    the Infinity Cache may still serve), also a rate."""
+    sec = ms * 1e-3
+    shared = logical_bytes is not None
+    nbytes = unique_bytes if shared else alg_bytes
+    out = {"bound": "hbm", "kernel": kernel, "achieved": nbytes / sec / 1e9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+           "frac": nbytes / sec / 1e9 / PEAK_HBM_GBS, "traffic": traffic, "kernel_ms": ms,
+           "bytes_basis": "unique bytes touched (lower bound of the HBM traffic; shared blocks are re-read from cache)"
+           if shared else "algorithmic bytes (nothing shared: equal to the unique bytes)",
+           "algorithmic_bytes_per_launch": alg_bytes}
+    if traffic is not None:
+        out["l2_fabric_gbs"] = traffic / sec / 1e9              # L2 misses; the Infinity Cache serves part of them
+    if shared:
+        out["logical_gbs"] = logical_bytes / sec / 1e9          # request-centric rate, cache hits included
+        out["unique_bytes"] = unique_bytes
+    return out
 
 
 class Job:
@@ -78,7 +103,7 @@ class Job:
 
     def __init__(self, name, torch, R, W, decode_after_prefill=True):
         self.torch, self.R, self.W = torch, R, W
-        self.wl = wl = W.CONFIGS[name]()
+        self.wl = wl = (W.CONFIGS.get(name) or W.MEASUREMENT_CONFIGS[name])()
         self.name = name
         dev = torch.device("cuda:0")
         self.sess = R.Session(wl, dev)
@@ -275,7 +300,9 @@ def decode_shared_entry(job, m):
             "per_request_bytes_rate_gbs": job.decode_bytes() / sec / 1e9,
             "algorithmic_bytes_per_launch": alg["bytes"], "unique_blocks": alg["unique_blocks"],
             "partial_slots": alg["partial_slots"], "gbs_kernel": alg["bytes"] / sec / 1e9,
+            # every block is read once by design, so these algorithmic bytes are HBM bytes: a true fraction
             "frac_of_hbm_peak": alg["bytes"] / sec / 1e9 / PEAK_HBM_GBS,
+            "frac_of_hbm_peak_planned": alg["bytes"] / (m["decode_shared_planned_ms"] * 1e-3) / 1e9 / PEAK_HBM_GBS,
             "hbm_bytes_per_launch_rocprof": _read_traffic(f"decode_shared_{job.name}")}
 
 
@@ -311,8 +338,9 @@ def measure_decode_residual(job, decode_ms, share=0.25, density=(0.25, 0.30), it
             "slowdown_over_decode": ms / decode_ms, "entries_with_residual": num_items,
             "share_of_table_entries": num_items / max(1.0, float(nb.sum().item())), "residual_entries": nnz,
             "density_k_v": list(density),
-            "algorithmic_bytes_per_launch": nbytes, "gbs_kernel": nbytes / (ms * 1e-3) / 1e9,
-            "frac_of_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+            # request-centric bytes (shared blocks counted once per request) + the residual's own: a rate, cache
+            # hits included, not an HBM fraction
+            "logical_bytes_per_launch": nbytes, "logical_gbs": nbytes / (ms * 1e-3) / 1e9,
             # what the pool does not hold: the reconstructed copies of these blocks, against the sparse form kept
             "dense_instance_bytes": float(num_items) * blk, "sparse_residual_bytes": 4.0 * nnz,
             "max_abs_diff_to_base_decode": changed}
@@ -331,6 +359,34 @@ def measure_stream_copy(torch, iters=10):
     del src, dst
     torch.cuda.empty_cache()
     return {"kernel": "torch copy_ (1 GiB)", "kernel_ms": ms, "gbs_read_plus_write": 2.0 * (1 << 30) / (ms * 1e-3) / 1e9}
+
+
+def measure_stream_read(torch, R, W, iters=10, gib=2):
+    """The read-only ceiling of the box: gf_hbm_read_probe (hand-written, 16 B per lane, grid stride, one sum
+    per workgroup) over a buffer several times the 256 MB Infinity Cache, for a few grid sizes."""
+    from paper_2605_22566_amd import binding as B
+    dev = torch.device("cuda:0")
+    sess = R.Session(W.small_layered(1, W.Shape(8, 2, 128), num_req=1), dev)
+    nbytes = gib << 30
+    src = torch.ones(nbytes // 2, dtype=torch.bfloat16, device=dev)
+    best = None
+    for num_wg in (2048, 4096, 8192, 16384):
+        sums = torch.zeros(num_wg, dtype=torch.int32, device=dev)
+        fn = lambda: B.gf_hbm_read_probe(sess.ctx, src, nbytes, sums, num_wg)
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        ms = _event_ms(fn, torch, iters)
+        # every 32-bit word of the buffer is 0x3f803f80 (two bf16 ones): the sums must add up to that, mod 2^32
+        got = int(sums.to(torch.int64).sum().item()) & 0xffffffff
+        ent = {"workgroups": num_wg, "kernel_ms": ms, "gbs_read": nbytes / (ms * 1e-3) / 1e9,
+               "every_word_summed": got == ((nbytes // 4) * 0x3f803f80) & 0xffffffff}
+        if best is None or ent["gbs_read"] > best["gbs_read"]:
+            best = ent
+    del src
+    torch.cuda.empty_cache()
+    best.update({"kernel": "hbm_read_probe_kernel", "bytes": nbytes, "frac_of_hbm_peak": best["gbs_read"] / PEAK_HBM_GBS})
+    return best
 
 
 def measure_residual(torch, R, W, num_items=8192, iters=20):
@@ -383,9 +439,12 @@ def measure_residual(torch, R, W, num_items=8192, iters=20):
     return out
 
 
-def cpu_baseline(job, budget_s=20.0):
-    """Time the fp64 oracle on a bounded sample of the workload's requests and
-    check the GPU outputs of the sample against it."""
+def cpu_baseline(job, budget_s=20.0, mode=None, windows=False):
+    """Time the fp64 oracle on a bounded sample of the workload's requests and check the GPU outputs of the
+    sample against it.  mode: "prefill" or "decode" (default: what the workload's headline is).  With
+    `windows`, a prefill request is checked on its first and last 48 rows instead of whole (rows i0..i1 of a
+    request are plain attention of those queries over its first ctx + i1 tokens, ctx + i0 of them context), so
+    that long requests fit a small budget."""
     from oracle import attention as OA
     from oracle import resolve as ORS
     torch, R, W = job.torch, job.R, job.W
@@ -398,15 +457,14 @@ def cpu_baseline(job, budget_s=20.0):
     # GPU tables must be bit-exact
     dev_tables = R.tables_to_host(job.tables)
     tables_exact = all(dev_tables[k] == tables[k] for k in tables)
-    L = W.context_lens(wl)
-    n = b.new_lens.astype(np.int64)
-    prefill_mode = job.has_prefill
+    prefill_mode = job.has_prefill if mode is None else mode == "prefill"
     lo_r, hi_r = job.pf_rng if prefill_mode else job.dec_rng
     order = lo_r + np.random.default_rng(wl.seed + 9).permutation(hi_r - lo_r)
     q_host = R.bf16_to_bits(job.q)
     o_gpu = job.o.double().cpu().numpy() if prefill_mode else job.od.double().cpu().numpy()
     atol, rtol = (1e-2, 1e-2) if sh.kv_dtype == W.KV_BF16 else (5e-2, 5e-2)
     spent, work, used, max_err, ok = 0.0, 0.0, 0, 0.0, True
+    pair_flops = 4.0 * sh.head_dim * sh.num_q_heads
     for r in order:
         r = int(r)
         nb = tables["num_blocks"][r]
@@ -416,18 +474,27 @@ def cpu_baseline(job, budget_s=20.0):
         local["block_table"] = [list(range(nb))]
         lo, hi = int(job.q_ptr[r]), int(job.q_ptr[r + 1])
         t0 = time.perf_counter()
-        if prefill_mode:
+        checks = []
+        if prefill_mode and windows and hi - lo > 96:
+            K, V = OA.materialize_kv(kk, vv, local["block_table"][0], tables["block_ntok"][r], nb, ks, vs)
+            ctx, n_r = int(tables["ctx_lens"][r]), hi - lo
+            for i0, i1 in ((0, 48), (n_r - 48, n_r)):
+                O, _ = OA.attend(OA._widen(q_host[lo + i0:lo + i1]), K[:ctx + i1], V[:ctx + i1], ctx + i0)
+                checks.append((o_gpu[lo + i0:lo + i1], O))
+                work += pair_flops * sum(ctx + i + 1 for i in range(i0, i1))
+        elif prefill_mode:
             O, _ = OA.prefill(q_host[lo:hi], np.array([0, hi - lo]), kk, vv, local, ks, vs)
-            got = o_gpu[lo:hi]
+            checks.append((o_gpu[lo:hi], O))
             work += W.prefill_flops(wl, [r])
         else:
             O, _ = OA.decode(q_host[hi - 1:hi], kk, vv, local, ks, vs)
-            got = o_gpu[r:r + 1]
+            checks.append((o_gpu[r:r + 1], O))
             work += W.decode_bytes(wl, [r])
         spent += time.perf_counter() - t0
-        err = np.abs(got - O)
-        max_err = max(max_err, float(err.max()))
-        ok = ok and bool((err <= atol + rtol * np.abs(O)).all())
+        for got, O in checks:
+            err = np.abs(got - O)
+            max_err = max(max_err, float(err.max()))
+            ok = ok and bool((err <= atol + rtol * np.abs(O)).all())
         used += 1
         if spent > budget_s:
             break
@@ -438,9 +505,36 @@ def cpu_baseline(job, budget_s=20.0):
         threads = os.cpu_count()
     unit = "TFLOP/s" if prefill_mode else "GB/s"
     value = work / spent / (1e12 if prefill_mode else 1e9)
-    return {"value": value, "unit": unit, "cores": int(threads), "kind": "oracle",
-            "sample": f"{used} of {b.num_req} requests of {wl.name} (seeded order), {spent:.1f} s of numpy fp64",
+    what = "requests" if not (prefill_mode and windows) else "requests (first and last 48 rows of each)"
+    return {"value": value, "unit": unit, "cores": int(threads), "host_cpu_count": os.cpu_count(), "kind": "oracle",
+            "sample": f"{used} of {hi_r - lo_r} {'prefill' if prefill_mode else 'decode'} {what} of {wl.name} "
+                      f"(seeded order), {spent:.1f} s of numpy fp64",
             "gpu_matches_oracle_on_sample": ok, "max_abs_err": max_err, "tables_bit_exact": tables_exact}
+
+
+def prefill_roofline(job, m, workload):
+    return {"bound": "mfma", "kernel": "prefill_kernel", "achieved": m["prefill_tflops_kernel"],
+            "peak": PEAK_MFMA_BF16_TFLOPS, "unit": "TFLOP/s",
+            "frac": m["prefill_tflops_kernel"] / PEAK_MFMA_BF16_TFLOPS,
+            "traffic": _read_traffic(f"prefill_{workload}"),
+            "kernel_ms": m["prefill_ms"], "kernel_ms_median": m["prefill_median_ms"],
+            "kernel_ms_cold_cache_median": m["prefill_cold_median_ms"],
+            "algorithmic_flops_per_launch": job.prefill_flops()}
+
+
+def decode_roofline(job, m, workload):
+    """The per-request decode kernel (+ merge).  On a workload with shared nodes its request-centric bytes are
+    mostly cache hits: they are reported as a rate, the fraction rests on HBM bytes."""
+    stats = job.W.sharing_stats(job.wl)
+    shared = stats["sharing_factor"] > 1.0 + 1e-9
+    lo, hi = job.dec_rng
+    sh = job.wl.shape
+    unique = stats["shared_kv_bytes"] + 2.0 * (hi - lo) * sh.num_q_heads * sh.head_dim * 2
+    out = hbm_roofline("decode_split_kernel(+merge)", job.decode_bytes(), m["decode_ms"],
+                       _read_traffic(f"decode_{workload}"), job.decode_bytes() if shared else None,
+                       unique if shared else None)
+    out["kernel_ms_median"] = m["decode_median_ms"]
+    return out
 
 
 def main():
@@ -449,11 +543,14 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="prefill_8b",
-                    choices=["tiny", "prefill_8b", "decode_8b", "decode_70b", "mixed_fp8"])
+                    choices=["tiny", "prefill_8b", "decode_8b", "decode_70b", "mixed_fp8", "decode_8b_private"])
     ap.add_argument("--decode-chunk", type=int, default=0,
                     help="table entries per split-KV chunk of the decode kernels (0 = the library's choice)")
-    ap.add_argument("--extra", default="decode_8b,kv_residual,stream_copy",
-                    help="comma list of further workloads reported under 'extra' (the five configs, kv_residual, stream_copy)")
+    ap.add_argument("--extra", default="decode_8b,decode_70b,mixed_fp8,decode_8b_private,kv_residual,stream",
+                    help="comma list of further workloads reported under 'extra' (the five configs, decode_8b_private = "
+                         "config 3 with nothing shared, kv_residual, stream = the box's read-only and copy rates)")
+    ap.add_argument("--extra-cpu-budget", type=float, default=5.0,
+                    help="seconds of oracle time per extra workload and phase for the sampled output check")
     ap.add_argument("--residual-share", type=float, default=0.25,
                     help="decode_residual: share of every request's table entries (its last ones) that carry a residual")
     ap.add_argument("--residual-density", default="0.25,0.30",
@@ -495,21 +592,13 @@ def main():
     if job.has_prefill:
         metric, unit = "prefill_tflops", "TFLOP/s"
         value = job.prefill_flops() / (m["ms_per_step"] * 1e-3) / 1e12
-        roof = {"bound": "mfma", "kernel": "prefill_kernel", "achieved": m["prefill_tflops_kernel"],
-                "peak": PEAK_MFMA_BF16_TFLOPS, "unit": "TFLOP/s",
-                "frac": m["prefill_tflops_kernel"] / PEAK_MFMA_BF16_TFLOPS,
-                "traffic": _read_traffic(f"prefill_{args.workload}"),
-                "kernel_ms": m["prefill_ms"], "kernel_ms_median": m["prefill_median_ms"],
-                "kernel_ms_cold_cache_median": m["prefill_cold_median_ms"],
-                "algorithmic_flops_per_launch": job.prefill_flops()}
+        roof = prefill_roofline(job, m, args.workload)
     else:
-        metric, unit = "decode_hbm_gbs", "GB/s"
+        # whole-step rate of the request-centric bytes (what attention through per-request tables moves,
+        # cache hits on shared nodes included); the roofline fraction rests on HBM bytes
+        metric, unit = "decode_logical_gbs", "GB/s"
         value = job.decode_bytes() / (m["ms_per_step"] * 1e-3) / 1e9
-        roof = {"bound": "hbm", "kernel": "decode_split_kernel(+merge)", "achieved": m["decode_gbs_kernel"],
-                "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": m["decode_gbs_kernel"] / PEAK_HBM_GBS,
-                "traffic": _read_traffic(f"decode_{args.workload}"),
-                "kernel_ms": m["decode_ms"], "kernel_ms_median": m["decode_median_ms"],
-                "algorithmic_bytes_per_launch": job.decode_bytes()}
+        roof = decode_roofline(job, m, args.workload)
     res = {
         "metric": metric, "value": value, "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": m["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
@@ -527,7 +616,7 @@ def main():
         "breakdown_ms": {k: v for k, v in m.items() if k.endswith("_ms")},
     }
     if job.has_prefill and job.has_decode:
-        res["decode_gbs_kernel"] = m["decode_gbs_kernel"]
+        res["decode_roofline"] = decode_roofline(job, m, args.workload)
     if job.has_decode:
         res["decode_shared"] = decode_shared_entry(job, m)
     res["kv_append"] = {"kernel": "append_kernel", "kernel_ms": m["append_ms"], "gbs_kernel": m["append_gbs_kernel"],
@@ -546,8 +635,9 @@ def main():
     del job
     torch.cuda.empty_cache()
     names = [x for x in args.extra.split(",") if x and x != args.workload]
-    if "stream_copy" in names:
-        names.remove("stream_copy")
+    if "stream" in names:
+        names.remove("stream")
+        extra["stream_read"] = measure_stream_read(torch, R, W)
         extra["stream_copy"] = measure_stream_copy(torch)
     if "kv_residual" in names:
         names.remove("kv_residual")
@@ -556,23 +646,27 @@ def main():
     for name in names:
         j = Job(name, torch, R, W, decode_after_prefill=False)
         mm = measure(j, max(5, args.steps // 2), max(3, args.warmup // 2))
-        ent = {"ms_per_step": mm["ms_per_step"], "breakdown_ms": {k: v for k, v in mm.items() if k.endswith("_ms")}}
+        ent = {"ms_per_step": mm["ms_per_step"], "breakdown_ms": {k: v for k, v in mm.items() if k.endswith("_ms")},
+               "sharing_factor": W.sharing_stats(j.wl)["sharing_factor"]}
         if j.has_prefill:
             ent["prefill_tflops_kernel"] = mm["prefill_tflops_kernel"]
-            ent["prefill_frac_of_mfma_peak"] = mm["prefill_tflops_kernel"] / PEAK_MFMA_BF16_TFLOPS
+            ent["roofline"] = prefill_roofline(j, mm, name)
         if j.has_decode:
-            ent["decode_gbs_kernel"] = mm["decode_gbs_kernel"]
-            ent["decode_frac_of_hbm_peak"] = mm["decode_gbs_kernel"] / PEAK_HBM_GBS
-            ent["algorithmic_bytes_per_launch"] = j.decode_bytes()
-            # what a kernel that read every shared node once per batch would have to move, at the HBM peak
-            ent["unique_kv_bytes"] = W.sharing_stats(j.wl)["shared_kv_bytes"]
-            ent["unique_bytes_time_bound_ms"] = ent["unique_kv_bytes"] / (PEAK_HBM_GBS * 1e9) * 1e3
-            ent["hbm_bytes_per_launch_rocprof"] = _read_traffic(f"decode_{name}")
+            ent["decode_roofline" if j.has_prefill else "roofline"] = decode_roofline(j, mm, name)
             ent["decode_shared"] = decode_shared_entry(j, mm)
-            dr = measure_decode_residual(j, mm["decode_ms"], args.residual_share,
-                                         tuple(float(x) for x in args.residual_density.split(",")))
-            if dr is not None:
-                ent["decode_residual"] = dr
+            if name in ("decode_8b",):
+                dr = measure_decode_residual(j, mm["decode_ms"], args.residual_share,
+                                             tuple(float(x) for x in args.residual_density.split(",")))
+                if dr is not None:
+                    ent["decode_residual"] = dr
+        if not args.no_cpu_baseline:
+            # bounded oracle check of this workload's GPU outputs (a few seconds per call)
+            if j.has_prefill:
+                ent["oracle_check_prefill"] = cpu_baseline(j, args.extra_cpu_budget, "prefill", windows=True)
+            if j.has_decode:
+                ent["oracle_check_decode"] = cpu_baseline(j, args.extra_cpu_budget, "decode")
+            ent["gpu_matches_oracle_on_sample"] = all(
+                ent[k]["gpu_matches_oracle_on_sample"] for k in ("oracle_check_prefill", "oracle_check_decode") if k in ent)
         extra[name] = ent
         del j
         torch.cuda.empty_cache()

@@ -308,6 +308,111 @@ int32_t gf_attn_decode_residual(gf_ctx *ctx, const gf_attn_params *params, const
                                 const void *q, void *o, float *lse, void *stream);
 
 /*
+ * State-management policy (paper, "Differential-based KV Cache": the KV of operation v under prefix path P
+ * is the node's base KV plus a sparse residual that belongs to the pair (P, v); "Effective Path Pruning":
+ * execution statistics identify the frequently taken transitions, only their residuals stay stored, a pair
+ * without a stored residual falls back to on-the-fly KV computation).
+ *
+ * gf_residual_dir is the directory of the stored residuals: an open-addressing hash table (linear probing)
+ * over (prefix path, node) pairs in CALLER-OWNED device arrays of `capacity` slots (a power of two, at
+ * least twice the number of pairs is a good size).  A pair is the path (v_0 .. v_i), i >= 1, ending in the
+ * node v_i; its stored residual is one residual item (see gf_kv_apply_residual) per block of v_i, items
+ * first_item .. first_item + ceil(node_len/16) - 1 in block order; its transition is (v_{i-1}, v_i).  The
+ * first node of a path has an empty prefix: its base KV is exact and it never has a residual.
+ *   key[slot]         0 = empty, else gf_prefix_key of the pair's path
+ *   prev / node       v_{i-1} and v_i (a slot matches when key, node and prev all agree)
+ *   first_item        >= 0: stored; < 0: pruned, and the items it named were -2 - first_item .. (the caller
+ *                     owns the residual storage and may reuse those items)
+ *   uses              how many resolved requests walked this pair (kept by gf_resolve_path_residual)
+ */
+typedef struct {
+    uint64_t *key;
+    int32_t  *prev;
+    int32_t  *node;
+    int32_t  *first_item;
+    int32_t  *uses;
+    int32_t   capacity;
+} gf_residual_dir;
+
+/* per-pair status words written by gf_residual_dir_insert */
+#define GF_DIR_OK        0
+#define GF_DIR_FULL      1   /* no free slot: pair not inserted                 */
+#define GF_DIR_BAD_PAIR  2   /* key 0 or negative first_item: pair not inserted */
+
+/* Key of a prefix path (HOST function, host array): h = 0; for every node id v of the path, in order,
+ * h = mix(h ^ (uint64)(uint32)v) with mix = the splitmix64 finaliser (z += 0x9E3779B97F4A7C15;
+ * z = (z ^ z >> 30) * 0xBF58476D1CE4E5B9; z = (z ^ z >> 27) * 0x94D049BB133111EB; z ^= z >> 31); 0 maps to 1.
+ * Two different paths share a key with probability 2^-64; a slot also compares node and prev. */
+uint64_t gf_prefix_key(const int32_t *nodes, int32_t len);
+
+/* Empty every slot of the directory (device arrays; asynchronous). */
+int32_t gf_residual_dir_clear(gf_ctx *ctx, const gf_residual_dir *dir, void *stream);
+
+/* Insert num_pairs pairs (device arrays keys / prev / node / first_item of that length; the pairs of one call
+ * are distinct and not yet in the directory).  status [num_pairs] (device, out) or NULL: GF_DIR_* per pair. */
+int32_t gf_residual_dir_insert(gf_ctx *ctx, const gf_residual_dir *dir, int32_t num_pairs,
+                               const uint64_t *keys, const int32_t *prev, const int32_t *node,
+                               const int32_t *first_item, int32_t *status, void *stream);
+
+/*
+ * gf_resolve_path_residual -- gf_resolve_path (same arguments, same outputs) plus, for the residual-aware
+ * attention calls, the residual handle of every table entry:
+ *   res_handle[r][e]  the residual item table entry e of request r is read with (first_item of the pair
+ *                     that owns the entry + the entry's block index inside its node), or -1: tail entries,
+ *                     padding, the first node of the path, pairs that are not in the directory or pruned,
+ *                     and every entry of a request whose status is not GF_ST_OK
+ *   num_fallback[r]   how many nodes of the path (beyond the first) have no stored residual: their KV under
+ *                     this prefix has to be computed on the fly (gf_attn_prefill + gf_kv_append into blocks
+ *                     of an instance node) if the base KV is not good enough
+ * and the execution statistics of the requests with status GF_ST_OK: trans_count[e] += 1 per hop along
+ * edge e (position in graph->edge_dst; trans_count [number of edges] device, may be NULL, needs the graph's
+ * edge arrays) and dir->uses[slot] += 1 per walked pair that has a slot.  dir may have capacity 0.
+ */
+int32_t gf_resolve_path_residual(gf_ctx *ctx, const gf_graph *graph, int32_t num_req,
+                                 const int32_t *path_ptr, const int32_t *path_nodes, const int32_t *new_lens,
+                                 const int32_t *tail_ptr, const int32_t *tail_blocks,
+                                 int32_t max_blocks, int32_t num_pool_blocks,
+                                 int32_t *block_table, int32_t *block_ntok, int32_t *num_blocks,
+                                 int32_t *ctx_lens, int32_t *seq_lens, int32_t *status,
+                                 const gf_residual_dir *dir, int32_t *trans_count,
+                                 int32_t *res_handle /* [num_req][max_blocks] device, out */,
+                                 int32_t *num_fallback /* [num_req] device, out */, void *stream);
+
+/*
+ * gf_residual_dir_prune -- Effective Path Pruning: every stored pair whose transition (prev -> node) was
+ * taken fewer than min_count times according to trans_count (an edge the graph does not have counts as
+ * never taken) loses its residual: first_item becomes -2 - first_item.  pruned [2] (device, or NULL) is
+ * ADDED to: [0] += pairs pruned, [1] += residual items freed.  The graph's edge arrays are required.
+ */
+int32_t gf_residual_dir_prune(gf_ctx *ctx, const gf_graph *graph, const gf_residual_dir *dir,
+                              const int32_t *trans_count, int32_t min_count, int32_t *pruned, void *stream);
+
+/*
+ * gf_block_pool -- HOST-side owner of the physical block ids of a K/V pool (paper, "Topology-Aware State
+ * Management": a node's KV is stored once and shared by every workflow through it; "Effective Path Pruning":
+ * storage follows the working set).  A free list with reference counts; it never touches the pool tensors.
+ *   alloc    hands out n free blocks with one reference each (ids[n], host, out); all or nothing:
+ *            GF_ERR_WORKSPACE when fewer than n blocks are free
+ *   retain   one more reference on each listed block (a second workflow through the node, a request in flight)
+ *   release  one reference less on each listed block (a block listed k times loses k); a block whose count
+ *            reaches zero goes back to the free list; *num_freed (host, may be NULL) = blocks freed
+ *   retain / release fail with GF_ERR_BAD_SHAPE, changing nothing, when an id is outside the pool or a block
+ *   does not hold the references asked for
+ *   stats    free blocks, blocks in use, references in total, most blocks ever in use (any pointer may be NULL)
+ *   refcount references on one block (>= 0), or a negative GF_ERR_* code
+ * Calls on one pool are serialised internally.
+ */
+typedef struct gf_block_pool gf_block_pool;
+int32_t gf_block_pool_create(gf_block_pool **out, int32_t num_blocks);
+int32_t gf_block_pool_destroy(gf_block_pool *pool);
+int32_t gf_block_pool_alloc(gf_block_pool *pool, int32_t n, int32_t *ids);
+int32_t gf_block_pool_retain(gf_block_pool *pool, int32_t n, const int32_t *ids);
+int32_t gf_block_pool_release(gf_block_pool *pool, int32_t n, const int32_t *ids, int32_t *num_freed);
+int32_t gf_block_pool_stats(gf_block_pool *pool, int32_t *num_free, int32_t *num_in_use, int64_t *total_refs,
+                            int32_t *peak_in_use);
+int32_t gf_block_pool_refcount(gf_block_pool *pool, int32_t block);
+
+/*
  * gf_kv_append -- write the K/V of every request's new tokens into its private
  * tail blocks (paper, "Topology-Aware State Management": states produced at run
  * time extend the KV assembled from the operation nodes; "Effective Path
@@ -421,7 +526,7 @@ int32_t gf_hbm_read_probe(gf_ctx *ctx, const void *src, int64_t bytes, uint32_t 
                           void *stream);
 
 /* Tuning knob (host): table entries (16-token blocks) per split-KV chunk in
- * gf_attn_decode (built-in choice 32) and gf_attn_decode_shared (built-in choice and upper limit 64);
+ * gf_attn_decode and gf_attn_decode_residual (built-in choice 64) and gf_attn_decode_shared (built-in choice and upper limit 64);
  * 0 restores the built-in choice.  Must be even. */
 int32_t gf_set_decode_chunk_blocks(gf_ctx *ctx, int32_t chunk_blocks);
 

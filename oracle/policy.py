@@ -70,6 +70,20 @@ def transition_counts(status, edge_ptr, edge_dst, path_ptr, path_nodes, counts=N
     return counts
 
 
+def pair_uses(status, path_ptr, path_nodes, pairs):
+    """How many times requests with status 0 walk each of the given pairs (prefix tuples)."""
+    uses = {tuple(k): 0 for k in pairs}
+    for r in range(len(path_ptr) - 1):
+        if status[r] != 0:
+            continue
+        path = [int(v) for v in path_nodes[path_ptr[r]:path_ptr[r + 1]]]
+        for i in range(1, len(path)):
+            key = tuple(path[:i + 1])
+            if key in uses:
+                uses[key] += 1
+    return uses
+
+
 def prune(directory, node_len, edge_ptr, edge_dst, counts, min_count):
     """Drop the stored residual of every pair whose last hop was taken fewer than min_count times.
     Returns (kept directory, sorted list of pruned prefix tuples, number of residual items freed)."""

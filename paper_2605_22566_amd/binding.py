@@ -24,7 +24,11 @@ GF_RS_OK, GF_RS_BAD_BLOCK, GF_RS_BAD_INDEX = 0, 1, 2
 EXPORTS = ["gf_create", "gf_destroy", "gf_strerror", "gf_last_hip_error", "gf_resolve_path",
            "gf_attn_prefill", "gf_attn_decode", "gf_attn_decode_residual", "gf_attn_decode_shared", "gf_decode_shared_plan", "gf_attn_decode_shared_planned",
            "gf_set_decode_chunk_blocks", "gf_kv_apply_residual",
-           "gf_kv_append", "gf_kv_append_token", "gf_attn_prefill_noalloc", "gf_hbm_read_probe"]
+           "gf_kv_append", "gf_kv_append_token", "gf_attn_prefill_noalloc", "gf_hbm_read_probe",
+           "gf_prefix_key", "gf_residual_dir_clear", "gf_residual_dir_insert", "gf_resolve_path_residual",
+           "gf_residual_dir_prune", "gf_block_pool_create", "gf_block_pool_destroy", "gf_block_pool_alloc",
+           "gf_block_pool_retain", "gf_block_pool_release", "gf_block_pool_stats", "gf_block_pool_refcount"]
+GF_DIR_OK, GF_DIR_FULL, GF_DIR_BAD_PAIR = 0, 1, 2
 
 _i32p = C.c_void_p  # device pointers travel as plain addresses
 
@@ -47,6 +51,11 @@ class gf_kv_pool(C.Structure):
 class gf_tables(C.Structure):
     _fields_ = [("block_table", _i32p), ("block_ntok", _i32p), ("num_blocks", _i32p), ("ctx_lens", _i32p),
                 ("seq_lens", _i32p), ("status", _i32p), ("num_req", C.c_int32), ("max_blocks", C.c_int32)]
+
+
+class gf_residual_dir(C.Structure):
+    _fields_ = [("key", C.c_void_p), ("prev", _i32p), ("node", _i32p), ("first_item", _i32p), ("uses", _i32p),
+                ("capacity", C.c_int32)]
 
 
 class GraphFlowError(RuntimeError):
@@ -114,6 +123,28 @@ def load_library(path: Optional[str] = None):
     lib.gf_kv_append_token.argtypes = [C.c_void_p, C.POINTER(gf_attn_params)] + [C.c_void_p] * 4 + [C.c_int32,
                                        C.POINTER(gf_tables)] + [C.c_void_p] * 3
     lib.gf_kv_append_token.restype = C.c_int32
+    lib.gf_prefix_key.argtypes = [C.POINTER(C.c_int32), C.c_int32]
+    lib.gf_prefix_key.restype = C.c_uint64
+    lib.gf_residual_dir_clear.argtypes = [C.c_void_p, C.POINTER(gf_residual_dir), C.c_void_p]
+    lib.gf_residual_dir_clear.restype = C.c_int32
+    lib.gf_residual_dir_insert.argtypes = [C.c_void_p, C.POINTER(gf_residual_dir), C.c_int32] + [C.c_void_p] * 6
+    lib.gf_residual_dir_insert.restype = C.c_int32
+    lib.gf_resolve_path_residual.argtypes = [C.c_void_p, C.POINTER(gf_graph), C.c_int32] + [C.c_void_p] * 5 + \
+        [C.c_int32, C.c_int32] + [C.c_void_p] * 6 + [C.POINTER(gf_residual_dir)] + [C.c_void_p] * 4
+    lib.gf_resolve_path_residual.restype = C.c_int32
+    lib.gf_residual_dir_prune.argtypes = [C.c_void_p, C.POINTER(gf_graph), C.POINTER(gf_residual_dir), C.c_void_p,
+                                          C.c_int32, C.c_void_p, C.c_void_p]
+    lib.gf_residual_dir_prune.restype = C.c_int32
+    lib.gf_block_pool_create.argtypes = [C.POINTER(C.c_void_p), C.c_int32]
+    lib.gf_block_pool_destroy.argtypes = [C.c_void_p]
+    lib.gf_block_pool_alloc.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_int32)]
+    lib.gf_block_pool_retain.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_int32)]
+    lib.gf_block_pool_release.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+    lib.gf_block_pool_stats.argtypes = [C.c_void_p, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int64),
+                                        C.POINTER(C.c_int32)]
+    lib.gf_block_pool_refcount.argtypes = [C.c_void_p, C.c_int32]
+    for name in ("create", "destroy", "alloc", "retain", "release", "stats", "refcount"):
+        getattr(lib, "gf_block_pool_" + name).restype = C.c_int32
     if path is None:
         _lib = lib
     return lib
@@ -258,3 +289,84 @@ def gf_attn_decode_shared_planned(ctx, params, pool, graph: gf_graph, path_ptr, 
                                                       _ptr(path_ptr), _ptr(path_nodes), num_path_entries,
                                                       C.byref(tables), _ptr(q), _ptr(o), _ptr(lse), _stream())
     _check(ctx, rc)
+
+
+def gf_prefix_key(nodes) -> int:
+    """Key of a prefix path (host list of node ids)."""
+    arr = (C.c_int32 * len(nodes))(*[int(v) for v in nodes])
+    return int(load_library().gf_prefix_key(arr, len(nodes)))
+
+
+def make_residual_dir(key, prev, node, first_item, uses, capacity) -> gf_residual_dir:
+    return gf_residual_dir(_ptr(key), _ptr(prev), _ptr(node), _ptr(first_item), _ptr(uses), capacity)
+
+
+def gf_residual_dir_clear(ctx, d: gf_residual_dir) -> None:
+    _check(ctx, load_library().gf_residual_dir_clear(ctx, C.byref(d), _stream()))
+
+
+def gf_residual_dir_insert(ctx, d: gf_residual_dir, num_pairs, keys, prev, node, first_item, status=None) -> None:
+    rc = load_library().gf_residual_dir_insert(ctx, C.byref(d), num_pairs, _ptr(keys), _ptr(prev), _ptr(node),
+                                               _ptr(first_item), _ptr(status), _stream())
+    _check(ctx, rc)
+
+
+def gf_resolve_path_residual(ctx, graph: gf_graph, num_req, path_ptr, path_nodes, new_lens, tail_ptr, tail_blocks,
+                             max_blocks, num_pool_blocks, block_table, block_ntok, num_blocks, ctx_lens, seq_lens,
+                             status, d: gf_residual_dir, trans_count, res_handle, num_fallback) -> None:
+    rc = load_library().gf_resolve_path_residual(
+        ctx, C.byref(graph), num_req, _ptr(path_ptr), _ptr(path_nodes), _ptr(new_lens), _ptr(tail_ptr),
+        _ptr(tail_blocks), max_blocks, num_pool_blocks, _ptr(block_table), _ptr(block_ntok), _ptr(num_blocks),
+        _ptr(ctx_lens), _ptr(seq_lens), _ptr(status), C.byref(d), _ptr(trans_count), _ptr(res_handle),
+        _ptr(num_fallback), _stream())
+    _check(ctx, rc)
+
+
+def gf_residual_dir_prune(ctx, graph: gf_graph, d: gf_residual_dir, trans_count, min_count, pruned=None) -> None:
+    rc = load_library().gf_residual_dir_prune(ctx, C.byref(graph), C.byref(d), _ptr(trans_count), min_count,
+                                              _ptr(pruned), _stream())
+    _check(ctx, rc)
+
+
+class BlockPool:
+    """gf_block_pool: host-side free list with reference counts over the pool's block ids."""
+
+    def __init__(self, num_blocks: int):
+        h = C.c_void_p()
+        _check(None, load_library().gf_block_pool_create(C.byref(h), num_blocks))
+        self._h = h.value
+
+    def close(self):
+        if self._h:
+            load_library().gf_block_pool_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    @staticmethod
+    def _arr(ids):
+        return (C.c_int32 * len(ids))(*[int(b) for b in ids])
+
+    def alloc(self, n: int):
+        out = (C.c_int32 * max(n, 1))()
+        _check(None, load_library().gf_block_pool_alloc(self._h, n, out))
+        return list(out[:n])
+
+    def retain(self, ids):
+        _check(None, load_library().gf_block_pool_retain(self._h, len(ids), self._arr(ids)))
+
+    def release(self, ids) -> int:
+        freed = C.c_int32()
+        _check(None, load_library().gf_block_pool_release(self._h, len(ids), self._arr(ids), C.byref(freed)))
+        return freed.value
+
+    def stats(self) -> dict:
+        f, u, p, t = C.c_int32(), C.c_int32(), C.c_int32(), C.c_int64()
+        _check(None, load_library().gf_block_pool_stats(self._h, C.byref(f), C.byref(u), C.byref(t), C.byref(p)))
+        return {"free": f.value, "in_use": u.value, "total_refs": t.value, "peak_in_use": p.value}
+
+    def refcount(self, block: int) -> int:
+        rc = load_library().gf_block_pool_refcount(self._h, block)
+        if rc < 0:
+            _check(None, rc)
+        return rc

@@ -62,6 +62,9 @@ int32_t *prefill_static_plan(int device);
 // read-only streaming probe (bandwidth ceiling): bytes a multiple of 16, one sum per workgroup
 hipError_t launch_hbm_read_probe(const void *src, size_t bytes, uint32_t *wg_sums, int32_t num_wg, hipStream_t s);
 
+// built-in split-KV chunk sizes (table entries per work item) of gf_attn_decode and gf_attn_decode_residual
+constexpr int32_t kDecodeChunkBlocks = 64, kDecodeChunkBlocksResidual = 64;   // equal: the two calls are interchangeable bit for bit
+
 // workspace floats needed by decode for (num_req, hkv, group, head_dim, splits)
 size_t decode_workspace_bytes(int32_t num_req, int32_t hkv, int32_t group, int32_t head_dim, int32_t splits);
 hipError_t launch_decode(const AttnArgs &a, int head_dim, int group, int kv_dtype, int32_t chunk_blocks,
@@ -79,6 +82,17 @@ constexpr int kSharedBuildLists = 1, kSharedAttend = 2;
 hipError_t launch_decode_shared(const AttnArgs &a, int head_dim, int group, int kv_dtype, const gf_graph &g,
                                 const int32_t *path_ptr, const int32_t *path_nodes, int32_t num_entries,
                                 int32_t chunk_blocks, void *workspace, int phases, hipStream_t s);
+
+// state-management policy: residual directory, resolution with residual handles, statistics, pruning
+uint64_t prefix_key_host(const int32_t *nodes, int32_t len);
+hipError_t launch_dir_clear(const gf_residual_dir &d, hipStream_t s);
+hipError_t launch_dir_insert(const gf_residual_dir &d, int32_t num_pairs, const uint64_t *keys, const int32_t *prev,
+                             const int32_t *node, const int32_t *first_item, int32_t *status, hipStream_t s);
+hipError_t launch_resolve_residual(const gf_graph &g, int32_t num_req, const int32_t *path_ptr, const int32_t *path_nodes,
+                                   const int32_t *status, int32_t max_blocks, const gf_residual_dir &d,
+                                   int32_t *trans_count, int32_t *res_handle, int32_t *num_fallback, hipStream_t s);
+hipError_t launch_dir_prune(const gf_graph &g, const gf_residual_dir &d, const int32_t *trans_count, int32_t min_count,
+                            int32_t *pruned, hipStream_t s);
 
 // residual application: one workgroup per pool block
 hipError_t launch_residual(void *k_pool, void *v_pool, float *k_scale, float *v_scale, int32_t num_pool_blocks,

@@ -16,12 +16,12 @@ __global__ __launch_bounds__(kProbeThreads) void hbm_read_probe_kernel(const u32
     for (; i + 3 * stride < n16; i += 4 * stride) {
         const u32x4 a = __builtin_nontemporal_load(src + i), b = __builtin_nontemporal_load(src + i + stride);
         const u32x4 c = __builtin_nontemporal_load(src + i + 2 * stride), d = __builtin_nontemporal_load(src + i + 3 * stride);
-        acc += (a[0] ^ a[1]) + (a[2] ^ a[3]) + (b[0] ^ b[1]) + (b[2] ^ b[3]) + (c[0] ^ c[1]) + (c[2] ^ c[3]) +
-               (d[0] ^ d[1]) + (d[2] ^ d[3]);
+        acc += (a[0] + a[1]) + (a[2] + a[3]) + (b[0] + b[1]) + (b[2] + b[3]) + (c[0] + c[1]) + (c[2] + c[3]) +
+               (d[0] + d[1]) + (d[2] + d[3]);
     }
     for (; i < n16; i += stride) {
         const u32x4 a = __builtin_nontemporal_load(src + i);
-        acc += (a[0] ^ a[1]) + (a[2] ^ a[3]);
+        acc += (a[0] + a[1]) + (a[2] + a[3]);
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);

@@ -228,6 +228,56 @@ class Session:
                                         dbatch["num_path_entries"], dt, q, o, lse)
 
 
+class ResidualDirectory:
+    """Device arrays of a gf_residual_dir plus the execution statistics (one counter per edge of the graph)."""
+
+    def __init__(self, sess: "Session", capacity: int):
+        assert capacity & (capacity - 1) == 0
+        dev = sess.device
+        self.sess, self.capacity = sess, capacity
+        n = max(capacity, 1)
+        self.key = torch.empty(n, dtype=torch.int64, device=dev)
+        self.prev, self.node, self.first_item, self.uses = (torch.empty(n, dtype=torch.int32, device=dev) for _ in range(4))
+        self.trans_count = torch.zeros(max(int(sess.edge_dst.numel()), 1), dtype=torch.int32, device=dev)
+        self.pruned = torch.zeros(2, dtype=torch.int32, device=dev)
+        B.gf_residual_dir_clear(sess.ctx, self.struct())
+
+    def struct(self):
+        return B.make_residual_dir(self.key, self.prev, self.node, self.first_item, self.uses, self.capacity)
+
+    def insert(self, prefixes, first_items):
+        """prefixes: host lists of node ids (each of length >= 2); first_items: the pairs' first residual items."""
+        dev = self.sess.device
+        keys = np.array([B.gf_prefix_key(p) for p in prefixes], dtype=np.uint64)
+        i32 = lambda a: torch.from_numpy(np.asarray(a, dtype=np.int32)).to(dev)
+        status = torch.full((len(prefixes),), -77, dtype=torch.int32, device=dev)
+        B.gf_residual_dir_insert(self.sess.ctx, self.struct(), len(prefixes),
+                                 torch.from_numpy(keys.view(np.int64)).to(dev), i32([p[-2] for p in prefixes]),
+                                 i32([p[-1] for p in prefixes]), i32(first_items), status)
+        return status
+
+    def resolve(self, dbatch, tables, count=True):
+        """gf_resolve_path_residual: fills `tables` and returns (res_handle [R, max_blocks], num_fallback [R])."""
+        sess = self.sess
+        graph = B.make_graph(sess.wl.graph.num_nodes, sess.node_len, sess.node_block_ptr, sess.node_blocks,
+                             sess.edge_ptr, sess.edge_dst)
+        R_, mb = dbatch["num_req"], tables["max_blocks"]
+        handle = torch.full((R_, mb), -77, dtype=torch.int32, device=sess.device)
+        fallback = torch.full((R_,), -77, dtype=torch.int32, device=sess.device)
+        B.gf_resolve_path_residual(sess.ctx, graph, R_, dbatch["path_ptr"], dbatch["path_nodes"], dbatch["new_lens"],
+                                   dbatch["tail_ptr"], dbatch["tail_blocks"], mb, sess.wl.num_pool_blocks,
+                                   tables["block_table"], tables["block_ntok"], tables["num_blocks"],
+                                   tables["ctx_lens"], tables["seq_lens"], tables["status"], self.struct(),
+                                   self.trans_count if count else None, handle, fallback)
+        return handle, fallback
+
+    def prune(self, min_count):
+        sess = self.sess
+        graph = B.make_graph(sess.wl.graph.num_nodes, sess.node_len, sess.node_block_ptr, sess.node_blocks,
+                             sess.edge_ptr, sess.edge_dst)
+        B.gf_residual_dir_prune(sess.ctx, graph, self.struct(), self.trans_count, min_count, self.pruned)
+
+
 def tables_to_host(tables) -> dict:
     """Device tables -> dict of Python lists (the oracle resolver's format)."""
     out = {}

@@ -292,6 +292,8 @@ CONFIGS = {
     "decode_70b": config_decode_70b,
     "mixed_fp8": config_mixed_fp8,
 }
+# measurement workloads beside the five configurations (filled below)
+MEASUREMENT_CONFIGS = {}
 
 
 def small_layered(seed: int, shape: Shape, num_nodes=24, num_layers=6, len_lo=5, len_hi=70,
@@ -326,6 +328,9 @@ def config_decode_8b_private(seed: int = SEED_BASE + 2) -> Workload:
     """Config 3's requests with private copies of every node (no sharing): a measurement workload, not one of
     the five configurations."""
     return private_copies(config_decode_8b(seed))
+
+
+MEASUREMENT_CONFIGS["decode_8b_private"] = config_decode_8b_private
 
 
 def subset(wl: Workload, req_ids) -> Batch:

@@ -33,6 +33,9 @@ def test_example_dag_handles_statistics_and_pruning_match_the_hand_computed_valu
     assert fallback == pol["num_fallback"]
     counts = OP.transition_counts(tables["status"], a["edge_ptr"], a["edge_dst"], a["path_ptr"], a["path_nodes"])
     assert counts == pol["transition_counts"]
+    # every stored pair lies on exactly one of the two resolved walks; (OP_01, OP_03, OP_04) is walked but not stored
+    uses = OP.pair_uses(tables["status"], a["path_ptr"], a["path_nodes"], list(directory) + [(0, 2, 3), (0, 1, 2)])
+    assert [uses[k] for k in directory] == [1, 1, 1, 1, 1] and uses[(0, 2, 3)] == 1 and uses[(0, 1, 2)] == 0
     kept, pruned, freed = OP.prune(directory, a["node_len"], a["edge_ptr"], a["edge_dst"], counts, pol["min_count"])
     assert pruned == sorted(tuple(ids[v] for v in p) for p in pol["pruned"])
     assert freed == pol["items_freed"]
