@@ -31,6 +31,7 @@ namespace gf {
 constexpr int kSharedThreads = 256;
 constexpr int kScanThreads = 1024;
 constexpr int kXcds = 8;                 // workgroups are dealt to the XCDs round robin
+constexpr int kMaxChunk = 64;            // table entries per item: one per lane of a wave
 
 struct SharedPlan {
     // graph and batch (device, caller's)
@@ -39,6 +40,7 @@ struct SharedPlan {
     // scratch (device, context's)
     int32_t *cnt, *cursor, *node_ptr, *item_ptr, *entry_slot, *row_req, *row_slot, *tail_ptr, *totals;
     int4 *item_rec;   // two per item, see ItemRec
+    int32_t *perm;    // launch order of the items: node items by falling length, then the tail items
     int32_t chunk_blocks, item_cap, slot_cap;
 };
 
@@ -215,6 +217,39 @@ __global__ void shared_fill_kernel(SharedPlan p, AttnArgs a, int group, int item
     }
 }
 
+// Launch order of the items (one workgroup).  Items differ in length by a factor of 32 and a resident workgroup
+// only gets a handful of them, so the order decides how evenly the work spreads: node items are sorted by
+// falling number of table entries (counting sort, 64 classes; the order inside a class depends on the atomics,
+// the results do not), the tail items (one or two steps each) follow.  The attention kernel deals the list
+// out round by round, every other round backwards, so that a workgroup that drew a long item in one round
+// draws a short one in the next (measured with in-kernel timers on config 3: in node order the workgroups
+// finished between 133 and 244 us).
+__global__ __launch_bounds__(kScanThreads) void shared_order_kernel(SharedPlan p) {
+    __shared__ int hist[kMaxChunk + 2], start[kMaxChunk + 2];
+    const int tid = threadIdx.x;
+    const int n_node = p.totals[0], n_tail = p.totals[1];
+    for (int i = tid; i < kMaxChunk + 2; i += kScanThreads) hist[i] = 0;
+    __syncthreads();
+    auto klass = [&](int i) -> int { return min(max(p.item_rec[2 * (size_t)i].z, 0), kMaxChunk); };
+    for (int i = tid; i < n_node; i += kScanThreads) atomicAdd(&hist[klass(i)], 1);
+    __syncthreads();
+    if (tid == 0) {
+        int run = 0;
+        for (int c = kMaxChunk; c >= 0; --c) {
+            start[c] = run;
+            run += hist[c];
+        }
+    }
+    __syncthreads();
+    for (int i = tid; i < kMaxChunk + 2; i += kScanThreads) hist[i] = 0;
+    __syncthreads();
+    for (int i = tid; i < n_node; i += kScanThreads) {
+        const int c = klass(i);
+        p.perm[start[c] + atomicAdd(&hist[c], 1)] = i;
+    }
+    for (int i = tid; i < n_tail; i += kScanThreads) p.perm[n_node + i] = n_node + i;
+}
+
 // ---- the attention kernel -------------------------------------------------------------------------
 // One workgroup (4 waves) reduces one item: a chunk of one segment's blocks for one kv head and up to
 // 64 * col_groups(G) score columns.  The chunk's K/V blocks go HBM -> LDS once per workgroup through direct
@@ -223,14 +258,13 @@ __global__ void shared_fill_kernel(SharedPlan p, AttnArgs a, int group, int item
 // block read from HBM once serves up to 128 (request, head) columns.  Items are node items (columns = the
 // requests through the node; 16 columns = 16/G requests) followed by tail items (a request's own tail
 // blocks, G columns).  The grid is as large as fits on the device at once, and workgroups loop over the item
-// list with the grid as stride.
+// list (in the launch order shared_order_kernel left) with the grid as stride, every other round backwards.
 // groups of 16 columns per wave: two when a request brings 8 heads per kv head (its node lists are twice as
 // wide in columns, and a fragment read from LDS then feeds two MFMAs), else one (more workgroups per CU)
 constexpr int col_groups(int G) { return G >= 8 ? 2 : 1; }
 // workgroups per CU the kernel is built for: registers and the LDS ring are sized to it
 constexpr int wgs_per_cu(int G) { return col_groups(G) == 1 ? 4 : 3; }
 constexpr int kLdsPerCu = 160 * 1024;
-constexpr int kMaxChunk = 64;                        // table entries per item: one per lane of a wave
 
 template <int D, bool FP8, int WGS>
 struct StageCfg {
@@ -323,11 +357,10 @@ __global__ __launch_bounds__(kSharedThreads, wgs_per_cu(G)) void shared_attn_ker
         int col_req[kColGroups], col_head[kColGroups], col_slot[kColGroups];
         int my_groups;                                         // groups of this wave that hold columns
     };
-    // Work id w -> item record + kv head.  The ids of one (node, chunk) run kv head by kv head, the column quads
-    // of a kv head back to back: they read the same K/V blocks, and neighbouring ids run on the same XCD at
-    // the same time, so those blocks are fetched from HBM once per XCD at most.  All quads of a (node, chunk)
-    // share their record but for the quad number, so any of them serves: the one at w / hkv is read and the
-    // quad and kv head follow from w's position in the group.
+    // Work id w -> item record + kv head: position w / hkv of the launch order, kv head w % hkv.  The column
+    // quads of a (node, chunk) have equal length, so they stay neighbours in the launch order and run on the
+    // same XCD in the same round: the blocks they share come from HBM once.  In odd rounds the list is dealt
+    // backwards (whole rounds only: the last, partial round keeps its direction).
     struct Item : ItemRec {
         int kvh;
     };
@@ -335,17 +368,13 @@ __global__ __launch_bounds__(kSharedThreads, wgs_per_cu(G)) void shared_attn_ker
         Item r;
         r.seg = 0; r.tab_off = 0; r.entries = 0; r.tokens = 0; r.row0 = 0; r.cnt = 0; r.quad = 0; r.slot = 0; r.kvh = 0;
         if (w < total_w) {
-            const long idx = w / a.hkv;
+            const long round = w / grid, pos = w % grid;
+            if ((round & 1) && (round + 1) * grid <= total_w) w = round * grid + (grid - 1 - pos);
+            const long idx = min(max(p.perm[w / a.hkv], 0), p.totals[0] + p.totals[1] - 1);
             const int4 x = p.item_rec[2 * idx], y = p.item_rec[2 * idx + 1];
             r.seg = x.x; r.tab_off = x.y; r.entries = min(x.z, kMaxChunk); r.tokens = x.w;
             r.row0 = y.x; r.cnt = y.y; r.quad = y.z; r.slot = y.w;
             r.kvh = (int)(w % a.hkv);
-            if (r.seg >= 0) {
-                const int quads = max((r.cnt * G + 64 * kColGroups - 1) / (64 * kColGroups), 1);
-                const long local = w - (idx - r.quad) * a.hkv;             // position among the group's quads * hkv ids
-                r.kvh = (int)(local / quads) % a.hkv;
-                r.quad = (int)(local % quads);
-            }
         }
         return r;
     };
@@ -675,8 +704,8 @@ size_t shared_int_words(int32_t num_nodes, int32_t num_req, int32_t num_entries)
 size_t shared_workspace_bytes(int32_t num_nodes, int32_t num_req, int32_t num_entries, int32_t max_blocks,
                               int32_t chunk_blocks, int32_t hq, int32_t head_dim) {
     const size_t slots = shared_slot_cap(num_req, num_entries, max_blocks, chunk_blocks);
-    return shared_int_words(num_nodes, num_req, num_entries) * sizeof(int32_t) + 16 + slots * sizeof(ItemRec) + 256 +
-           slots * hq * ((size_t)head_dim + 2) * sizeof(float);
+    return shared_int_words(num_nodes, num_req, num_entries) * sizeof(int32_t) + 16 + slots * sizeof(ItemRec) +
+           slots * sizeof(int32_t) + 256 + slots * hq * ((size_t)head_dim + 2) * sizeof(float);
 }
 
 // resident workgroups of the attention kernel on the whole device (the item loop strides by the grid, so
@@ -709,6 +738,7 @@ static hipError_t launch_shared_t(const AttnArgs &a, int kv_dtype, SharedPlan p,
         hipLaunchKernelGGL(shared_scan_kernel, dim3(1), dim3(kScanThreads), 0, s, p, a, G, 64 * col_groups(G));
         const unsigned nf = (unsigned)(((size_t)p.num_entries + p.num_nodes + a.num_req + 255) / 256);
         hipLaunchKernelGGL(shared_fill_kernel, dim3(nf), dim3(256), 0, s, p, a, G, 64 * col_groups(G));
+        hipLaunchKernelGGL(shared_order_kernel, dim3(1), dim3(kScanThreads), 0, s, p);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
@@ -755,7 +785,8 @@ hipError_t launch_decode_shared(const AttnArgs &a, int head_dim, int group, int 
     p.item_cap = (int32_t)slots;
     p.slot_cap = (int32_t)slots;
     p.item_rec = (int4 *)(((uintptr_t)w + 15) & ~(uintptr_t)15);
-    float *part_o = (float *)(((uintptr_t)(p.item_rec + 2 * slots) + 255) & ~(uintptr_t)255);
+    p.perm = (int32_t *)(p.item_rec + 2 * slots);
+    float *part_o = (float *)(((uintptr_t)(p.perm + slots) + 255) & ~(uintptr_t)255);
     float *part_ml = part_o + slots * a.hq * (size_t)head_dim;
 #define GF_CASE(DD, GG) \
     if (head_dim == DD && group == GG) return launch_shared_t<DD, GG>(a, kv_dtype, p, part_o, part_ml, phases, s);
