@@ -543,12 +543,14 @@ def main():
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="prefill_8b",
-                    choices=["tiny", "prefill_8b", "decode_8b", "decode_70b", "mixed_fp8", "decode_8b_private"])
+                    choices=["tiny", "prefill_8b", "decode_8b", "decode_70b", "mixed_fp8", "decode_8b_private",
+                             "decode_8b_private_seq"])
     ap.add_argument("--decode-chunk", type=int, default=0,
                     help="table entries per split-KV chunk of the decode kernels (0 = the library's choice)")
-    ap.add_argument("--extra", default="decode_8b,decode_70b,mixed_fp8,decode_8b_private,kv_residual,stream",
+    ap.add_argument("--extra", default="decode_8b,decode_70b,mixed_fp8,decode_8b_private,decode_8b_private_seq,kv_residual,stream",
                     help="comma list of further workloads reported under 'extra' (the five configs, decode_8b_private = "
-                         "config 3 with nothing shared, kv_residual, stream = the box's read-only and copy rates)")
+                         "config 3 with nothing shared, decode_8b_private_seq = the same with an unshuffled pool, "
+                         "kv_residual, stream = the box's read-only and copy rates)")
     ap.add_argument("--extra-cpu-budget", type=float, default=5.0,
                     help="seconds of oracle time per extra workload and phase for the sampled output check")
     ap.add_argument("--residual-share", type=float, default=0.25,

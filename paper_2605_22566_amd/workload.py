@@ -331,6 +331,9 @@ def config_decode_8b_private(seed: int = SEED_BASE + 2) -> Workload:
 
 
 MEASUREMENT_CONFIGS["decode_8b_private"] = config_decode_8b_private
+# the same with every request's blocks laid out one after the other in the pool (no shuffle): what random block
+# placement costs at the DRAM shows as the difference between the two
+MEASUREMENT_CONFIGS["decode_8b_private_seq"] = lambda: private_copies(config_decode_8b(), shuffle=False)
 
 
 def subset(wl: Workload, req_ids) -> Batch:
