@@ -16,8 +16,8 @@ What is computed here, block by block of the paged pool:
     the oracle takes it in the kernel's precision (fp32), not in fp64.
   * select_by_energy(): the offline selection rule of the paper's appendix (keep the
     largest-magnitude entries that hold a given share, 95 %, of the Frobenius energy
-    of the dense difference).  Not on the GPU path; kept as the reference of how a
-    residual is obtained.
+    of the dense difference), and make_residual(), which applies it image by image to
+    the difference between a prefix-conditioned block and its base block and emits the CSR.
 
 Readings: the paper does not fix the storage format of a residual (coordinate list
 here, one CSR row per block, tensor and kv head, 16-bit element index), its value
@@ -39,7 +39,9 @@ random values, ties and extremes; an empty residual is the identity; the residua
 single entries land on the hand-indexed physical element of K and of V; a node
 reconstructed block by block equals base + delta formed on the [token][head][dim]
 segment without any block arithmetic; select_by_energy against brute force over all
-subsets on tiny inputs, plus its defining invariants.  reconstruct_e4m3: an empty residual
+subsets on tiny inputs, plus its defining invariants.  make_residual: with share 1 and differences that bf16 holds
+exactly, reconstruct(base, make_residual(base, full)) gives back `full` bit for bit; a hand-built image whose
+energy sits in three entries keeps exactly those; K and V entries land on the hand-indexed logical positions.  reconstruct_e4m3: an empty residual
 re-codes a block onto itself (same codes, same scale) when its largest code is the largest
 finite one; codes and scales against torch's float8 casts of the same fp32 sums; the
 dequantised result within half a code step of base + delta; bad blocks and indices reported.
@@ -137,6 +139,34 @@ def reconstruct_e4m3(k_pool, v_pool, k_scale, v_scale, src_blocks, dst_blocks, r
             pool[t] = f32_to_e4m3_codes(y)
             scale[t] = sc
     return k_out, v_out, ks_out, vs_out, status
+
+
+def make_residual(k_pool: np.ndarray, v_pool: np.ndarray, base_blocks, full_blocks, share: float = 0.95):
+    """From dense prefix-conditioned KV to the stored residual (the paper's sparsity appendix: of the difference
+    between the KV of an operation under a prefix and its base KV, keep the largest-magnitude entries that hold
+    `share` of its Frobenius energy).  Item b compares block full_blocks[b] (the KV under the prefix) with block
+    base_blocks[b]; per (item, tensor, kv head) image the difference is formed in fp32 (full - base, both
+    widened exactly), select_by_energy picks the entries, and the kept differences are rounded to bf16.
+    Returns the CSR of reconstruct(): (res_ptr, res_idx, res_val) with logical indices slot * D + d, every
+    row sorted by index.  Readings: energy is taken per image (the paper measures per layer and head), and the
+    stored value is the rounded difference itself, not a value re-fitted so that base + value rounds to full."""
+    nb, hkv, _, dim = k_pool.shape
+    ptr, idx, val = [0], [], []
+    for b in range(len(base_blocks)):
+        s, f = int(base_blocks[b]), int(full_blocks[b])
+        for tensor in (0, 1):
+            for h in range(hkv):
+                if tensor == 0:
+                    d = bf16_bits_to_f32(k_pool[f, h]) - bf16_bits_to_f32(k_pool[s, h])          # [16, D]
+                else:
+                    d = (bf16_bits_to_f32(v_pool[f, h]) - bf16_bits_to_f32(v_pool[s, h])).T      # [D, 16] -> [16, D]
+                d = np.ascontiguousarray(d, dtype=np.float32)
+                keep = select_by_energy(d, share)
+                idx.append(keep.astype(np.uint16))
+                val.append(f32_to_bf16_bits_rne(d.ravel()[keep]))
+                ptr.append(ptr[-1] + keep.size)
+    cat = lambda parts, dt: np.concatenate(parts).astype(dt) if parts else np.zeros(0, dt)
+    return np.asarray(ptr, dtype=np.int32), cat(idx, np.uint16), cat(val, np.uint16)
 
 
 def select_by_energy(delta: np.ndarray, share: float = 0.95) -> np.ndarray:

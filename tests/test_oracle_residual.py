@@ -250,3 +250,44 @@ def test_residual_handles_name_the_item_of_every_instance_block_and_nothing_else
     for r in range(wl.batch.num_req):
         cols = np.nonzero(named[r])[0]
         assert cols.size > 0 and (np.diff(cols) == 1).all()
+
+
+def test_make_residual_round_trip_hand_image_and_layouts():
+    """make_residual: (1) share 1 with exactly representable differences reproduces the prefix-conditioned blocks
+    bit for bit through reconstruct(); (2) an image whose energy sits in three hand-placed entries keeps exactly
+    those at 95 %; (3) a K difference at (slot, d) and a V difference at (d, slot) get the logical index slot*D+d."""
+    from oracle import residual as OR
+    rng = np.random.default_rng(17)
+    hkv, dim = 2, 64
+    f32 = lambda bits: OR.bf16_bits_to_f32(bits)
+    base_k = OR.f32_to_bf16_bits_rne(rng.integers(-8, 9, size=(4, hkv, 16, dim)).astype(np.float32))
+    base_v = OR.f32_to_bf16_bits_rne(rng.integers(-8, 9, size=(4, hkv, dim, 16)).astype(np.float32))
+    k, v = base_k.copy(), base_v.copy()
+    # blocks 2, 3 = blocks 0, 1 plus small-integer differences on a third of the elements (all sums exact in bf16)
+    for pool in (k, v):
+        d = rng.integers(-3, 4, size=pool[:2].shape).astype(np.float32) * (rng.random(pool[:2].shape) < 0.33)
+        pool[2:4] = OR.f32_to_bf16_bits_rne(f32(pool[:2]) + d)
+    ptr, idx, val = OR.make_residual(k, v, [0, 1], [2, 3], share=1.0)
+    assert ptr[0] == 0 and ptr[-1] == idx.size == val.size and np.all(np.diff(ptr) >= 0)
+    scratch_k, scratch_v = k.copy(), v.copy()
+    scratch_k[2:4] = 0
+    scratch_v[2:4] = 0
+    k2, v2, st = OR.reconstruct(scratch_k, scratch_v, [0, 1], [2, 3], ptr, idx, val)
+    assert (st == 0).all() and np.array_equal(k2[2:4], k[2:4]) and np.array_equal(v2[2:4], v[2:4])
+    # nothing kept where nothing differs; every kept entry is a non-zero difference
+    assert np.all(f32(val) != 0)
+    # (2) + (3): one block pair, differences by hand
+    k3, v3 = base_k[:2].copy(), base_v[:2].copy()
+    k3[1], v3[1] = k3[0], v3[0]
+    kf, vf = f32(k3), f32(v3)
+    kf[1, 1, 5, 9] += 16.0          # K head 1, slot 5, d 9
+    kf[1, 1, 0, 63] -= 16.0
+    kf[1, 1, 15, 0] += 8.0
+    kf[1, 1, 7, 7] += 0.5           # 0.25 of 576.25: below the 5 % that may be dropped
+    vf[1, 0, 20, 3] += 4.0          # V head 0, d 20, slot 3 -> logical 3 * 64 + 20
+    k3, v3 = OR.f32_to_bf16_bits_rne(kf), OR.f32_to_bf16_bits_rne(vf)
+    ptr, idx, val = OR.make_residual(k3, v3, [0], [1], share=0.95)
+    rows = {r: (idx[ptr[r]:ptr[r + 1]].tolist(), f32(val[ptr[r]:ptr[r + 1]]).tolist()) for r in range(2 * hkv)}
+    assert rows[0] == ([], []) and rows[3] == ([], [])
+    assert rows[1] == ([63, 5 * 64 + 9, 15 * 64], [-16.0, 16.0, 8.0])         # K head 1, by index; 0.5 dropped
+    assert rows[2] == ([3 * 64 + 20], [4.0])                                  # V head 0
