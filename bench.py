@@ -415,6 +415,19 @@ def measure_residual(torch, R, W, num_items=8192, iters=20):
            "algorithmic_bytes_per_launch": nbytes, "gbs_kernel": nbytes / (ms * 1e-3) / 1e9,
            "frac_of_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "all_items_ok": ok,
            "hbm_bytes_per_launch_rocprof": _read_traffic("residual_kv_residual")}
+    # the way back: gf_kv_make_residual recovers a residual from the reconstructed blocks against their base blocks
+    # (95 % energy rule; per image a sort in LDS, two passes over the blocks): an offline step, timed for the record
+    fnm = lambda: sess.make_residual(pool, dres["src"], dres["dst"], 0.95)
+    made = fnm()
+    torch.cuda.synchronize()
+    msm = _event_ms(fnm, torch, 3)
+    nnz_made = int(made["ptr"][-1].item())
+    out["make_residual"] = {"kernel": "make_residual_kernel (count + scan + fill)", "kernel_ms": msm, "blocks": num_items,
+                            "entries_kept_at_95pct_energy": nnz_made, "entries_of_the_source_residual": nnz,
+                            "algorithmic_bytes_per_launch": 2.0 * num_items * 2 * blk + 4.0 * nnz_made,
+                            "gbs_kernel": (2.0 * num_items * 2 * blk + 4.0 * nnz_made) / (msm * 1e-3) / 1e9,
+                            "all_items_ok": bool((made["status"] == 0).all().item())}
+    del made
     # the same items on an e4m3 pool (codes of N(0,1) blocks, scale amax / 448): half the block bytes, two passes
     del pool, k, v
     sh8 = W.Shape(32, 8, 128, W.KV_FP8_E4M3)

@@ -233,6 +233,7 @@ int32_t gf_attn_decode(gf_ctx *ctx, const gf_attn_params *params, const gf_kv_po
 #define GF_RS_OK         0
 #define GF_RS_BAD_BLOCK  1   /* source or destination block id outside the pool: block skipped */
 #define GF_RS_BAD_INDEX  2   /* a residual entry addresses an element outside its image: entry ignored */
+#define GF_RS_TRUNCATED  3   /* gf_kv_make_residual: entries of the item fell beyond `capacity` and were not written */
 
 /*
  * gf_kv_apply_residual -- reconstruct prefix-conditioned KV blocks from base
@@ -276,6 +277,32 @@ int32_t gf_kv_apply_residual(gf_ctx *ctx, const gf_attn_params *params,
                              const uint16_t *res_idx,    /* [res_ptr[last]] device */
                              const uint16_t *res_val,    /* [res_ptr[last]] device, bf16 bits */
                              int32_t *status, void *stream);
+
+/*
+ * gf_kv_make_residual -- from dense prefix-conditioned KV to the stored sparse residual (paper,
+ * "Differential-based KV Cache", Eq. 7, and the selection rule of its KV-sparsity appendix: of the difference
+ * between the KV of an operation under a prefix and its base KV, the largest-magnitude entries that hold a
+ * given share -- 95 % -- of the Frobenius energy are kept).  The inverse of gf_kv_apply_residual: item b
+ * compares pool block full_blocks[b] (the node's KV computed under the prefix, e.g. by the on-the-fly fallback)
+ * with pool block base_blocks[b] and writes the CSR rows (b * 2 + t) * num_kv_heads + h of that call's format:
+ * per (item, tensor, kv head) image, difference = full - base in fp32; the entries are ranked by magnitude
+ * (largest first, equal magnitudes by rising index); the squared magnitudes are summed in fp64 along that
+ * order and the shortest prefix whose sum reaches energy_share x total is kept (nothing for an all-zero
+ * difference); the kept differences are rounded to bf16 (nearest even) and written in rising index order.
+ *   energy_share  in (0, 1]; 1 keeps every non-zero difference
+ *   capacity      entries res_idx / res_val can hold.  res_ptr [num_items * 2 * num_kv_heads + 1] (device, out)
+ *                 always holds the full row pointers; entries at positions >= capacity are not written and
+ *                 their items report GF_RS_TRUNCATED (compare res_ptr[last] with capacity and call again)
+ *   status        [num_items] device, out, or NULL: GF_RS_OK, GF_RS_BAD_BLOCK (an id outside the pool: the
+ *                 item's rows are empty) or GF_RS_TRUNCATED
+ * GF_BF16 pools only.  num_items * 2 * num_kv_heads * 16 * head_dim must stay below 2^31.  The pool is only read.
+ */
+int32_t gf_kv_make_residual(gf_ctx *ctx, const gf_attn_params *params, const void *k_pool, const void *v_pool,
+                            int32_t num_pool_blocks, int32_t num_items,
+                            const int32_t *base_blocks,  /* [num_items] device */
+                            const int32_t *full_blocks,  /* [num_items] device */
+                            double energy_share, int32_t capacity,
+                            int32_t *res_ptr, uint16_t *res_idx, uint16_t *res_val, int32_t *status, void *stream);
 
 /*
  * gf_attn_decode_residual -- gf_attn_decode with the sparse residuals applied

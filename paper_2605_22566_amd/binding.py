@@ -19,14 +19,14 @@ GF_OK = 0
 GF_ERR_NULL, GF_ERR_BAD_SHAPE, GF_ERR_UNSUPPORTED, GF_ERR_WORKSPACE, GF_ERR_HIP = -1, -2, -3, -4, -5
 GF_ST_OK, GF_ST_BAD_NODE, GF_ST_BAD_EDGE, GF_ST_BAD_TAIL, GF_ST_BAD_BLOCK, GF_ST_OVERFLOW = 0, 1, 2, 3, 4, 5
 GF_BF16, GF_FP8_E4M3 = 0, 1
-GF_RS_OK, GF_RS_BAD_BLOCK, GF_RS_BAD_INDEX = 0, 1, 2
+GF_RS_OK, GF_RS_BAD_BLOCK, GF_RS_BAD_INDEX, GF_RS_TRUNCATED = 0, 1, 2, 3
 
 EXPORTS = ["gf_create", "gf_destroy", "gf_strerror", "gf_last_hip_error", "gf_resolve_path",
            "gf_attn_prefill", "gf_attn_decode", "gf_attn_decode_residual", "gf_attn_decode_shared", "gf_decode_shared_plan", "gf_attn_decode_shared_planned",
            "gf_set_decode_chunk_blocks", "gf_kv_apply_residual",
            "gf_kv_append", "gf_kv_append_token", "gf_attn_prefill_noalloc", "gf_hbm_read_probe",
            "gf_prefix_key", "gf_residual_dir_clear", "gf_residual_dir_insert", "gf_resolve_path_residual",
-           "gf_residual_dir_prune", "gf_block_pool_create", "gf_block_pool_destroy", "gf_block_pool_alloc",
+           "gf_residual_dir_prune", "gf_kv_make_residual", "gf_block_pool_create", "gf_block_pool_destroy", "gf_block_pool_alloc",
            "gf_block_pool_retain", "gf_block_pool_release", "gf_block_pool_stats", "gf_block_pool_refcount"]
 GF_DIR_OK, GF_DIR_FULL, GF_DIR_BAD_PAIR = 0, 1, 2
 
@@ -135,6 +135,9 @@ def load_library(path: Optional[str] = None):
     lib.gf_residual_dir_prune.argtypes = [C.c_void_p, C.POINTER(gf_graph), C.POINTER(gf_residual_dir), C.c_void_p,
                                           C.c_int32, C.c_void_p, C.c_void_p]
     lib.gf_residual_dir_prune.restype = C.c_int32
+    lib.gf_kv_make_residual.argtypes = [C.c_void_p, C.POINTER(gf_attn_params), C.c_void_p, C.c_void_p, C.c_int32,
+                                        C.c_int32, C.c_void_p, C.c_void_p, C.c_double, C.c_int32] + [C.c_void_p] * 5
+    lib.gf_kv_make_residual.restype = C.c_int32
     lib.gf_block_pool_create.argtypes = [C.POINTER(C.c_void_p), C.c_int32]
     lib.gf_block_pool_destroy.argtypes = [C.c_void_p]
     lib.gf_block_pool_alloc.argtypes = [C.c_void_p, C.c_int32, C.POINTER(C.c_int32)]
@@ -370,3 +373,11 @@ class BlockPool:
         if rc < 0:
             _check(None, rc)
         return rc
+
+
+def gf_kv_make_residual(ctx, params, k_pool, v_pool, num_pool_blocks, num_items, base_blocks, full_blocks, energy_share,
+                        capacity, res_ptr, res_idx, res_val, status=None) -> None:
+    rc = load_library().gf_kv_make_residual(ctx, C.byref(params), _ptr(k_pool), _ptr(v_pool), num_pool_blocks, num_items,
+                                            _ptr(base_blocks), _ptr(full_blocks), energy_share, capacity, _ptr(res_ptr),
+                                            _ptr(res_idx), _ptr(res_val), _ptr(status), _stream())
+    _check(ctx, rc)

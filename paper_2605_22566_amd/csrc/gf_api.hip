@@ -473,6 +473,30 @@ int32_t gf_kv_apply_residual(gf_ctx *ctx, const gf_attn_params *params, void *k_
     return GF_OK;
 }
 
+int32_t gf_kv_make_residual(gf_ctx *ctx, const gf_attn_params *params, const void *k_pool, const void *v_pool,
+                            int32_t num_pool_blocks, int32_t num_items, const int32_t *base_blocks,
+                            const int32_t *full_blocks, double energy_share, int32_t capacity, int32_t *res_ptr,
+                            uint16_t *res_idx, uint16_t *res_val, int32_t *status, void *stream) {
+    if (!ctx || !params) return GF_ERR_NULL;
+    if (num_items < 0 || num_pool_blocks < 0 || capacity < 0) return GF_ERR_BAD_SHAPE;
+    if (params->num_kv_heads <= 0 || params->head_dim <= 0) return GF_ERR_BAD_SHAPE;
+    if (!(energy_share > 0.0) || !(energy_share <= 1.0)) return GF_ERR_BAD_SHAPE;
+    if (params->block_size != gf::kBlock) return GF_ERR_UNSUPPORTED;
+    if (params->head_dim != 64 && params->head_dim != 128) return GF_ERR_UNSUPPORTED;
+    if (params->kv_dtype != GF_BF16) return GF_ERR_UNSUPPORTED;
+    if ((int64_t)num_items * 2 * params->num_kv_heads * gf::kBlock * params->head_dim >= 0x7fffffffLL)
+        return GF_ERR_UNSUPPORTED;
+    if (num_items == 0) return GF_OK;
+    if (!k_pool || !v_pool || !base_blocks || !full_blocks || !res_ptr) return GF_ERR_NULL;
+    if (capacity > 0 && (!res_idx || !res_val)) return GF_ERR_NULL;
+    hipError_t e = gf::launch_make_residual(k_pool, v_pool, num_pool_blocks, params->num_kv_heads, params->head_dim,
+                                            num_items, base_blocks, full_blocks, energy_share, capacity, res_ptr, res_idx,
+                                            res_val, status, (hipStream_t)stream);
+    if (e == hipErrorNotSupported) return GF_ERR_UNSUPPORTED;
+    if (e != hipSuccess) return fail_hip(ctx, e, "gf_kv_make_residual launch");
+    return GF_OK;
+}
+
 int32_t gf_kv_append(gf_ctx *ctx, const gf_attn_params *params, void *k_pool, void *v_pool, float *k_scale,
                      float *v_scale, int32_t num_pool_blocks, const gf_tables *tables, const void *k_new,
                      const void *v_new, const int32_t *q_ptr, int32_t total_q, int32_t max_q, void *stream) {

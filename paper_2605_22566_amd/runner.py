@@ -186,6 +186,24 @@ class Session:
                                dres["dst"], dres["ptr"], dres["idx"], dres["val"], dres["status"], pool.k_scale,
                                pool.v_scale)
 
+    def make_residual(self, pool, base_blocks, full_blocks, share=0.95, capacity=None):
+        """gf_kv_make_residual: the residual of blocks `full_blocks` against `base_blocks` (device int32 tensors) as
+        the dict apply_residual / decode_residual take (src = base, dst = full), plus the number of entries."""
+        sh = self.wl.shape
+        n = int(base_blocks.numel())
+        rows = n * 2 * sh.num_kv_heads
+        if capacity is None:
+            capacity = rows * W.BLOCK * sh.head_dim
+        dev = self.device
+        ptr = torch.full((rows + 1,), -77, dtype=torch.int32, device=dev)
+        idx = torch.zeros(max(capacity, 1), dtype=torch.int16, device=dev)
+        val = torch.zeros(max(capacity, 1), dtype=torch.int16, device=dev)
+        status = torch.full((max(n, 1),), -77, dtype=torch.int32, device=dev)
+        params = B.make_params(sh.num_q_heads, sh.num_kv_heads, sh.head_dim, sh.kv_dtype)
+        B.gf_kv_make_residual(self.ctx, params, pool.k, pool.v, pool.num_blocks, n, base_blocks, full_blocks, share,
+                              capacity, ptr, idx, val, status)
+        return dict(src=base_blocks, dst=full_blocks, ptr=ptr, idx=idx, val=val, num_items=n, status=status)
+
     def append(self, pool, tables, k_new, v_new, q_ptr, total_q, max_q):
         params, _, dt = self._common(pool, tables, 0.0)
         B.gf_kv_append(self.ctx, params, pool.k, pool.v, pool.k_scale, pool.v_scale, pool.num_blocks, dt, k_new,
