@@ -335,6 +335,25 @@ int32_t gf_attn_decode_residual(gf_ctx *ctx, const gf_attn_params *params, const
                                 const void *q, void *o, float *lse, void *stream);
 
 /*
+ * gf_attn_prefill_residual -- gf_attn_prefill with the sparse residuals applied while the blocks are read
+ * (paper, "Differential-based KV Cache", Eq. 7; with "Effective Path Pruning" this is also the on-the-fly
+ * fallback itself: the new node's tokens attend to ancestors whose KV under the current prefix is base +
+ * residual).  res_handle, num_items and the CSR are those of gf_attn_decode_residual: table entry e of request r
+ * with res_handle[r * max_blocks + e] = b in [0, num_items) is read as its base block plus residual item b,
+ * any other value reads the block as it is; each sum is taken in fp32 and rounded to bf16 before use, so the
+ * result equals, bit for bit, gf_attn_prefill over a table whose entries point at blocks reconstructed by
+ * gf_kv_apply_residual.  Entries outside their image are ignored; the entries of one row name distinct
+ * elements.  Tail entries (the new tokens' own blocks) normally carry no handle.
+ * GF_BF16 pools only (GF_ERR_UNSUPPORTED otherwise).  Everything else as in gf_attn_prefill.
+ */
+int32_t gf_attn_prefill_residual(gf_ctx *ctx, const gf_attn_params *params, const gf_kv_pool *pool,
+                                 const gf_tables *tables,
+                                 const int32_t *res_handle, int32_t num_items,
+                                 const int32_t *res_ptr, const uint16_t *res_idx, const uint16_t *res_val,
+                                 const void *q, const int32_t *q_ptr, int32_t total_q, int32_t max_q,
+                                 void *o, float *lse, void *stream);
+
+/*
  * State-management policy (paper, "Differential-based KV Cache": the KV of operation v under prefix path P
  * is the node's base KV plus a sparse residual that belongs to the pair (P, v); "Effective Path Pruning":
  * execution statistics identify the frequently taken transitions, only their residuals stay stored, a pair

@@ -22,7 +22,7 @@ GF_BF16, GF_FP8_E4M3 = 0, 1
 GF_RS_OK, GF_RS_BAD_BLOCK, GF_RS_BAD_INDEX, GF_RS_TRUNCATED = 0, 1, 2, 3
 
 EXPORTS = ["gf_create", "gf_destroy", "gf_strerror", "gf_last_hip_error", "gf_resolve_path",
-           "gf_attn_prefill", "gf_attn_decode", "gf_attn_decode_residual", "gf_attn_decode_shared", "gf_decode_shared_plan", "gf_attn_decode_shared_planned",
+           "gf_attn_prefill", "gf_attn_prefill_residual", "gf_attn_decode", "gf_attn_decode_residual", "gf_attn_decode_shared", "gf_decode_shared_plan", "gf_attn_decode_shared_planned",
            "gf_set_decode_chunk_blocks", "gf_kv_apply_residual",
            "gf_kv_append", "gf_kv_append_token", "gf_attn_prefill_noalloc", "gf_hbm_read_probe",
            "gf_prefix_key", "gf_residual_dir_clear", "gf_residual_dir_insert", "gf_resolve_path_residual",
@@ -96,6 +96,11 @@ def load_library(path: Optional[str] = None):
                                     C.c_void_p, C.c_void_p, C.c_void_p]
     lib.gf_attn_prefill.restype = C.c_int32
     lib.gf_attn_prefill_noalloc.argtypes = lib.gf_attn_prefill.argtypes
+    lib.gf_attn_prefill_residual.argtypes = [C.c_void_p, C.POINTER(gf_attn_params), C.POINTER(gf_kv_pool),
+                                             C.POINTER(gf_tables), C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
+                                             C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
+                                             C.c_void_p, C.c_void_p]
+    lib.gf_attn_prefill_residual.restype = C.c_int32
     lib.gf_attn_prefill_noalloc.restype = C.c_int32
     lib.gf_hbm_read_probe.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int32, C.c_void_p]
     lib.gf_hbm_read_probe.restype = C.c_int32
@@ -227,6 +232,15 @@ def gf_attn_prefill(ctx, params, pool, tables, q, q_ptr, total_q, max_q, o, lse=
 def gf_attn_prefill_noalloc(ctx, params, pool, tables, q, q_ptr, total_q, max_q, o, lse=None) -> None:
     rc = load_library().gf_attn_prefill_noalloc(ctx, C.byref(params), C.byref(pool), C.byref(tables), _ptr(q),
                                                 _ptr(q_ptr), total_q, max_q, _ptr(o), _ptr(lse), _stream())
+    _check(ctx, rc)
+
+
+def gf_attn_prefill_residual(ctx, params, pool, tables, res_handle, num_items, res_ptr, res_idx, res_val, q, q_ptr,
+                             total_q, max_q, o, lse=None) -> None:
+    rc = load_library().gf_attn_prefill_residual(ctx, C.byref(params), C.byref(pool), C.byref(tables),
+                                                 _ptr(res_handle), num_items, _ptr(res_ptr), _ptr(res_idx),
+                                                 _ptr(res_val), _ptr(q), _ptr(q_ptr), total_q, max_q, _ptr(o),
+                                                 _ptr(lse), _stream())
     _check(ctx, rc)
 
 

@@ -255,9 +255,10 @@ int32_t gf_residual_dir_prune(gf_ctx *ctx, const gf_graph *graph, const gf_resid
     return GF_OK;
 }
 
-int32_t gf_attn_prefill(gf_ctx *ctx, const gf_attn_params *params, const gf_kv_pool *pool,
-                        const gf_tables *tables, const void *q, const int32_t *q_ptr, int32_t total_q,
-                        int32_t max_q, void *o, float *lse, void *stream) {
+// gf_attn_prefill and its residual-reading form: the same checks, work-list buffer and launch
+static int32_t prefill_call(gf_ctx *ctx, const gf_attn_params *params, const gf_kv_pool *pool,
+                            const gf_tables *tables, const gf::ResidualRefs *rr, const void *q, const int32_t *q_ptr,
+                            int32_t total_q, int32_t max_q, void *o, float *lse, void *stream, const char *what) {
     if (!ctx) return GF_ERR_NULL;
     if (total_q < 0 || max_q < 0 || max_q > total_q) return GF_ERR_BAD_SHAPE;
     gf::AttnArgs a;
@@ -266,16 +267,38 @@ int32_t gf_attn_prefill(gf_ctx *ctx, const gf_attn_params *params, const gf_kv_p
     static const char dummy = 0;
     int32_t rc = check_attn(params, pool, tables, total_q ? q : &dummy, total_q ? o : (void *)&dummy, lse, a, group);
     if (rc != GF_OK) return rc;
+    if (rr) {
+        if (rr->num_items < 0) return GF_ERR_BAD_SHAPE;
+        if (params->kv_dtype != GF_BF16) return GF_ERR_UNSUPPORTED;
+    }
     if (tables->num_req == 0 || total_q == 0) return GF_OK;
     if (!q_ptr) return GF_ERR_NULL;
+    if (rr && (!rr->handle || (rr->num_items > 0 && (!rr->ptr || !rr->idx || !rr->val)))) return GF_ERR_NULL;
     rc = ensure_buffer(ctx, &ctx->plan, &ctx->plan_bytes, gf::prefill_plan_bytes(total_q, a.num_req, group),
-                       (hipStream_t)stream, "gf_attn_prefill work-list buffer");
+                       (hipStream_t)stream, "prefill work-list buffer");
     if (rc != GF_OK) return rc;
     hipError_t e = gf::launch_prefill(a, params->head_dim, group, params->kv_dtype, q_ptr, total_q,
-                                      (int32_t *)ctx->plan, (hipStream_t)stream);
+                                      (int32_t *)ctx->plan, rr, (hipStream_t)stream);
     if (e == hipErrorNotSupported) return GF_ERR_UNSUPPORTED;
-    if (e != hipSuccess) return fail_hip(ctx, e, "gf_attn_prefill launch");
+    if (e != hipSuccess) return fail_hip(ctx, e, what);
     return GF_OK;
+}
+
+int32_t gf_attn_prefill(gf_ctx *ctx, const gf_attn_params *params, const gf_kv_pool *pool,
+                        const gf_tables *tables, const void *q, const int32_t *q_ptr, int32_t total_q,
+                        int32_t max_q, void *o, float *lse, void *stream) {
+    return prefill_call(ctx, params, pool, tables, nullptr, q, q_ptr, total_q, max_q, o, lse, stream,
+                        "gf_attn_prefill launch");
+}
+
+int32_t gf_attn_prefill_residual(gf_ctx *ctx, const gf_attn_params *params, const gf_kv_pool *pool,
+                                 const gf_tables *tables, const int32_t *res_handle, int32_t num_items,
+                                 const int32_t *res_ptr, const uint16_t *res_idx, const uint16_t *res_val,
+                                 const void *q, const int32_t *q_ptr, int32_t total_q, int32_t max_q, void *o,
+                                 float *lse, void *stream) {
+    const gf::ResidualRefs rr = {res_handle, res_ptr, res_idx, res_val, num_items};
+    return prefill_call(ctx, params, pool, tables, &rr, q, q_ptr, total_q, max_q, o, lse, stream,
+                        "gf_attn_prefill_residual launch");
 }
 
 int32_t gf_attn_prefill_noalloc(gf_ctx *ctx, const gf_attn_params *params, const gf_kv_pool *pool,
@@ -303,7 +326,8 @@ int32_t gf_attn_prefill_noalloc(gf_ctx *ctx, const gf_attn_params *params, const
     if (e != hipSuccess) return fail_hip(ctx, e, "gf_attn_prefill_noalloc hipGetDevice");
     int32_t *plan = gf::prefill_static_plan(ctx->device);
     if (cur != ctx->device || !plan) return GF_ERR_BAD_SHAPE;
-    e = gf::launch_prefill(a, params->head_dim, group, params->kv_dtype, q_ptr, total_q, plan, (hipStream_t)stream);
+    e = gf::launch_prefill(a, params->head_dim, group, params->kv_dtype, q_ptr, total_q, plan, nullptr,
+                           (hipStream_t)stream);
     if (e == hipErrorNotSupported) return GF_ERR_UNSUPPORTED;
     if (e != hipSuccess) return fail_hip(ctx, e, "gf_attn_prefill_noalloc launch");
     return GF_OK;

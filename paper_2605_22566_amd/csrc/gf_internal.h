@@ -49,8 +49,9 @@ hipError_t launch_resolve(const gf_graph &g, int32_t num_req, const int32_t *pat
 
 // bytes of the work-list buffer a prefill call needs, and the launcher (plan kernel + attention kernel)
 size_t prefill_plan_bytes(int32_t total_q, int32_t num_req, int group);
+// `rr`: residual items read in place (bf16 pools), or nullptr for the plain call
 hipError_t launch_prefill(const AttnArgs &a, int head_dim, int group, int kv_dtype, const int32_t *q_ptr,
-                          int32_t total_q, int32_t *plan, hipStream_t s);
+                          int32_t total_q, int32_t *plan, const ResidualRefs *rr, hipStream_t s);
 
 // The work list of gf_attn_prefill_noalloc: a file-scope device array of kStaticPlanBytes instead of a buffer
 // of the context.  prefill_static_plan_init looks the array's address up once per device (that device must be

@@ -37,8 +37,16 @@
 // exceeds it by more than 2^8; the final normalisation uses the same reference, so the result is
 // unchanged.  Per-entry token counts mask partial blocks anywhere in the sequence and tail entries
 // causally, in a side path taken only by tiles whose mask bits say so.
+//
+// Differential KV read in place (RES; paper, "Differential-based KV Cache", Eq. 7: the KV of a node under a
+// prefix is its stored base KV plus that prefix's sparse residual).  A table entry may carry a residual item;
+// the wave that staged the entry's block adds the item's K row and V row for this kv head into the LDS image --
+// fp32 sum rounded to bf16, as gf_kv_apply_residual does -- between the wait for its own direct loads and the
+// barrier that publishes the tile, when no other wave reads or writes that part of LDS.  The operands then
+// equal a reconstructed block bit for bit.  bf16 pools.
 
 #include "gf_internal.h"
+#include "gf_residual_row.h"
 #include <mutex>
 #include <type_traits>
 #include <utility>
@@ -174,11 +182,33 @@ __device__ __forceinline__ void mma_out(f32x16 &d, bf16x8 vf, bf16x8 pf) {
     else asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+a"(d) : "v"(vf), "v"(pf));
 }
 
-template <int D, int G, int NW, int RS, bool FP8>
+// Where a residual entry (logical element slot * D + d of a block) sits in the staged images of a bf16 pool:
+// K keeps [slot][d] with the 16-byte pieces of a row at position piece ^ swizzle(tile row), V keeps [d][slot]
+// with the two 8-slot halves of a row swapped on every other group of 8 rows (see "Staging" above).
+template <int D, int TENSOR>
+struct StagedMap {
+    static constexpr bool kPredicated = true;        // LDS is full: there is no spare element to absorb strays
+    int entry;                                       // the block's place in the tile (sets the K swizzle for D < 128)
+    __device__ __forceinline__ uint32_t operator()(uint32_t i) const {
+        const uint32_t slot = i / D, d = i % D;
+        uint32_t at;
+        if constexpr (TENSOR == 0) {
+            const uint32_t rho = entry * kBlock + slot;
+            const uint32_t sw = D == 128 ? (rho & 15) : D == 64 ? ((rho >> 1) & 7) : ((rho >> 2) & 3);
+            at = slot * D + (((d >> 3) ^ sw) << 3) + (d & 7);
+        } else {
+            at = d * kBlock + ((((slot >> 3) ^ (d >> 3)) & 1) << 3) + (slot & 7);
+        }
+        return i < (uint32_t)(kBlock * D) ? at : kNoElem;
+    }
+};
+
+template <int D, int G, int NW, int RS, bool FP8, bool RES>
 __global__ __launch_bounds__(NW * 64, RS == 1 ? 2 : 1) void prefill_kernel(
     AttnArgs a, const int32_t *__restrict__ tab_base, const int32_t *__restrict__ ntk_base,
     const int32_t *__restrict__ q_ptr, const float *__restrict__ k_scale, const float *__restrict__ v_scale,
-    const int32_t *__restrict__ plan, int total_q) {
+    const int32_t *__restrict__ plan, int total_q, ResidualRefs rr) {
+    static_assert(!(RES && FP8), "residuals are read in place on bf16 pools only");
     constexpr int ES = FP8 ? 1 : 2;
     using C = PrefillCfg<D, G, NW, RS, ES>;
     extern __shared__ __attribute__((aligned(1024))) char lds[];
@@ -249,8 +279,9 @@ __global__ __launch_bounds__(NW * 64, RS == 1 ? 2 : 1) void prefill_kernel(
     struct Win {
         int idx, nt;
         float ks, lvs, ivs;
+        int item;                            // RES: residual item of the entry, or -1
     };
-    Win w_cur, w_nxt, w_new = {0, 0, 1.f, 0.f, 1.f};
+    Win w_cur, w_nxt, w_new = {0, 0, 1.f, 0.f, 1.f, -1};
     uint64_t mbits_cur, mbits_nxt;
     auto load_window = [&](int w, Win &x) {
         const int e = 64 * w + lane;
@@ -265,6 +296,10 @@ __global__ __launch_bounds__(NW * 64, RS == 1 ? 2 : 1) void prefill_kernel(
             x.ivs = 1.0f / vs;
         }
         x.idx = id;                          // block id until the window is adopted
+        if constexpr (RES) {
+            const int it = ok ? rr.handle[(size_t)r * a.max_blocks + (ok ? e : 0)] : -1;
+            x.item = (it >= 0 && it < rr.num_items) ? it : -1;
+        }
     };
     // block id (clamped into the pool) -> index of the (block, kv head) tile; mask bits of the window
     auto adopt_window = [&](int w, Win &x) -> uint64_t {
@@ -438,6 +473,29 @@ __global__ __launch_bounds__(NW * 64, RS == 1 ? 2 : 1) void prefill_kernel(
     issue_v(0, 0);
     if (ntiles > 1) issue_k(1, 1);
     dma_wait();
+    // RES: this wave adds the residual rows of the entry it staged (tile, entry `wave`) into the image it filled
+    auto patch = [&](auto tensor_c, int tile, char *image) {
+        constexpr int TENSOR = decltype(tensor_c)::value;
+        const int item = entry_i(&Win::item, tile * C::kEntries + wave);
+        if (item < 0) return;
+        const int32_t *rp = rr.ptr + ((size_t)item * 2 + TENSOR) * a.hkv + kvh;
+        const int first = __builtin_amdgcn_readfirstlane(rp[0]), end = __builtin_amdgcn_readfirstlane(rp[1]);
+        if (first >= end) return;
+        RowLoad<D, 1> row;
+        row.issue(rr, first, end, lane);
+        row.apply((uint16_t *)image, rr, lane, StagedMap<D, TENSOR>{wave});
+    };
+    auto patch_k = [&](int tile, int buf) {
+        patch(std::integral_constant<int, 0>{}, tile, kbuf + buf * C::kKTile + wave * C::kDmaPerWave * 1024);
+    };
+    auto patch_v = [&](int tile, int buf) {
+        patch(std::integral_constant<int, 1>{}, tile, vbuf + buf * C::kVTile + wave * C::kDmaPerWave * 1024);
+    };
+    if constexpr (RES) {
+        patch_k(0, 0);
+        patch_v(0, 0);
+        if (ntiles > 1) patch_k(1, 1);
+    }
     __syncthreads();
     {
         const TileScale t0 = tile_scale(0);
@@ -578,6 +636,12 @@ __global__ __launch_bounds__(NW * 64, RS == 1 ? 2 : 1) void prefill_kernel(
                 dma_wait();                      // this wave's direct loads have landed ...
                 // (the window fetch is waited for here, nowhere earlier)
                 asm volatile("" : "+v"(w_new.idx), "+v"(w_new.nt), "+v"(w_new.ks), "+v"(w_new.lvs), "+v"(w_new.ivs));
+                if constexpr (RES) {
+                    // the tiles staged in this iteration are still this wave's alone (their windows are the
+                    // ones cached before the slide below)
+                    if (k2) patch_k(t + 2, t & 1);
+                    if (has_next) patch_v(t + 1, (t + 1) % C::kVBufs);
+                }
                 if (slide) {
                     w_cur = w_nxt;
                     mbits_cur = mbits_nxt;
@@ -780,24 +844,27 @@ __global__ __launch_bounds__(kPlanThreads) void prefill_plan_kernel(
     }
 }
 
-template <int D, int G, int NW, bool FP8>
+template <int D, int G, int NW, bool FP8, bool RES>
 static hipError_t launch_prefill_k(const AttnArgs &a, const int32_t *q_ptr, int32_t total_q, int32_t *plan,
-                                   hipStream_t s);
+                                   const ResidualRefs &rr, hipStream_t s);
 
 template <int D, int G, int NW>
 static hipError_t launch_prefill_t(const AttnArgs &a, int kv_dtype, const int32_t *q_ptr, int32_t total_q,
-                                   int32_t *plan, hipStream_t s) {
-    if (kv_dtype == GF_FP8_E4M3) return launch_prefill_k<D, G, NW, true>(a, q_ptr, total_q, plan, s);
-    return launch_prefill_k<D, G, NW, false>(a, q_ptr, total_q, plan, s);
+                                   int32_t *plan, const ResidualRefs *rr, hipStream_t s) {
+    const ResidualRefs none = {nullptr, nullptr, nullptr, nullptr, 0};
+    if (kv_dtype == GF_FP8_E4M3)
+        return rr ? hipErrorNotSupported : launch_prefill_k<D, G, NW, true, false>(a, q_ptr, total_q, plan, none, s);
+    if (rr) return launch_prefill_k<D, G, NW, false, true>(a, q_ptr, total_q, plan, *rr, s);
+    return launch_prefill_k<D, G, NW, false, false>(a, q_ptr, total_q, plan, none, s);
 }
 
-template <int D, int G, int NW, bool FP8>
+template <int D, int G, int NW, bool FP8, bool RES>
 static hipError_t launch_prefill_k(const AttnArgs &a, const int32_t *q_ptr, int32_t total_q, int32_t *plan,
-                                   hipStream_t s) {
+                                   const ResidualRefs &rr, hipStream_t s) {
     constexpr int RS = prefill_row_sets(FP8);
     using C = PrefillCfg<D, G, NW, RS, FP8 ? 1 : 2>;
     static_assert(C::kRows >= kPrefillRowsMin, "the work list is sized for the smallest tile height");
-    auto kern = prefill_kernel<D, G, NW, RS, FP8>;
+    auto kern = prefill_kernel<D, G, NW, RS, FP8, RES>;
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)kern, hipFuncAttributeMaxDynamicSharedMemorySize, C::kLds);
@@ -814,7 +881,7 @@ static hipError_t launch_prefill_k(const AttnArgs &a, const int32_t *q_ptr, int3
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(C::kThreads), C::kLds, s, a, a.block_table, a.block_ntok,
-                       q_ptr, a.k_scale, a.v_scale, plan, total_q);
+                       q_ptr, a.k_scale, a.v_scale, plan, total_q, rr);
     return hipGetLastError();
 }
 
@@ -855,12 +922,12 @@ size_t prefill_plan_bytes(int32_t total_q, int32_t num_req, int group) {
 }
 
 hipError_t launch_prefill(const AttnArgs &a, int head_dim, int group, int kv_dtype, const int32_t *q_ptr,
-                          int32_t total_q, int32_t *plan, hipStream_t s) {
+                          int32_t total_q, int32_t *plan, const ResidualRefs *rr, hipStream_t s) {
     if (a.num_req == 0 || total_q == 0) return hipSuccess;
     // 4-wave workgroups, two resident per CU: their barriers stay local to one wave per SIMD and
     // the two workgroups drift apart, so one's vector phases fall under the other's MFMAs
 #define GF_CASE(DD, GG) \
-    if (head_dim == DD && group == GG) return launch_prefill_t<DD, GG, kPrefillWaves>(a, kv_dtype, q_ptr, total_q, plan, s);
+    if (head_dim == DD && group == GG) return launch_prefill_t<DD, GG, kPrefillWaves>(a, kv_dtype, q_ptr, total_q, plan, rr, s);
     GF_CASE(64, 1) GF_CASE(64, 2) GF_CASE(64, 4) GF_CASE(64, 8)
     GF_CASE(128, 1) GF_CASE(128, 2) GF_CASE(128, 4) GF_CASE(128, 8)
 #undef GF_CASE

@@ -169,6 +169,12 @@ class Session:
         params, dpool, dt = self._common(pool, tables, sm_scale)
         B.gf_attn_prefill_noalloc(self.ctx, params, dpool, dt, q, q_ptr, total_q, max_q, o, lse)
 
+    def prefill_residual(self, pool, tables, res_handle, dres, q, q_ptr, total_q, max_q, o, lse=None, sm_scale=0.0):
+        """Prefill with residuals applied as the blocks are read (`res_handle`, `dres` as in decode_residual)."""
+        params, dpool, dt = self._common(pool, tables, sm_scale)
+        B.gf_attn_prefill_residual(self.ctx, params, dpool, dt, res_handle, dres["num_items"], dres["ptr"],
+                                   dres["idx"], dres["val"], q, q_ptr, total_q, max_q, o, lse)
+
     def upload_residuals(self, res: W.Residuals):
         dev = self.device
         i32 = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(dev)
