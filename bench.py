@@ -346,6 +346,45 @@ def measure_decode_residual(job, decode_ms, share=0.25, density=(0.25, 0.30), it
             "max_abs_diff_to_base_decode": changed}
 
 
+def measure_prefill_residual(job, prefill_ms, shares=(0.25, 1.0), density=(0.25, 0.30), iters=10):
+    """gf_attn_prefill_residual beside gf_attn_prefill on the same prefill: the last `share` of every request's
+    CONTEXT entries (ancestor blocks; the new tokens' own blocks carry none) are read as base block + a residual
+    item of their own at the density the paper reports.  share 1 is the paper's regime: every ancestor block under
+    a prefix has a residual.  bf16 pools."""
+    torch, R, W = job.torch, job.R, job.W
+    sh = job.wl.shape
+    if sh.kv_dtype != W.KV_BF16 or not job.has_prefill:
+        return None
+    lo, hi = job.pf_rng
+    t = job._slice(lo, hi)
+    dev = job.q.device
+    nb = t["num_blocks"].to(torch.int64)
+    new = (t["seq_lens"] - t["ctx_lens"]).to(torch.int64)
+    ncb = nb - (new + 15) // 16                       # context entries
+    ar = torch.arange(job.max_blocks, device=dev)[None, :]
+    o = torch.zeros_like(job.o)
+    out = {"kernel": "prefill_kernel<RES>", "prefill_ms": prefill_ms, "density_k_v": list(density), "runs": []}
+    for share in shares:
+        first = ncb - (ncb.to(torch.float64) * share).to(torch.int64)
+        mask = (ar >= first[:, None]) & (ar < ncb[:, None])
+        num_items = int(mask.sum().item())
+        handles = torch.full(mask.shape, -1, dtype=torch.int32, device=dev)
+        handles[mask] = torch.arange(num_items, dtype=torch.int32, device=dev)
+        dres, nnz = R.random_residuals(sh, num_items, dev, density_k=density[0], density_v=density[1])
+        fn = lambda: job.sess.prefill_residual(job.pool, t, handles, dres, job.q, job.q_ptr[lo:hi + 1], job.pf_rows,
+                                               job.pf_max_q, o)
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        ms = _event_ms(fn, torch, iters)
+        out["runs"].append({"share_of_context_entries": share, "entries_with_residual": num_items,
+                            "residual_entries": nnz, "kernel_ms": ms, "slowdown_over_prefill": ms / prefill_ms,
+                            "tflops": job.prefill_flops() / (ms * 1e-3) / 1e12,
+                            "max_abs_diff_to_base_prefill": float((o.float() - job.o.float()).abs().max().item())})
+        del dres, handles
+    return out
+
+
 def measure_stream_copy(torch, iters=10):
     """What a plain device-to-device copy of 1 GiB reaches on this machine (bytes read + bytes written
     per second): the practical streaming ceiling next to the 8 TB/s on paper."""
@@ -634,6 +673,9 @@ def main():
         res["decode_roofline"] = decode_roofline(job, m, args.workload)
     if job.has_decode:
         res["decode_shared"] = decode_shared_entry(job, m)
+    pr = measure_prefill_residual(job, m["prefill_ms"]) if job.has_prefill else None
+    if pr is not None:
+        res["prefill_residual"] = pr
     res["kv_append"] = {"kernel": "append_kernel", "kernel_ms": m["append_ms"], "gbs_kernel": m["append_gbs_kernel"],
                         "frac_of_hbm_peak": m["append_gbs_kernel"] / PEAK_HBM_GBS,
                         "algorithmic_bytes_per_launch": job.append_bytes(),

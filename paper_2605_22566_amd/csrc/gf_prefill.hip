@@ -473,28 +473,29 @@ __global__ __launch_bounds__(NW * 64, RS == 1 ? 2 : 1) void prefill_kernel(
     issue_v(0, 0);
     if (ntiles > 1) issue_k(1, 1);
     dma_wait();
-    // RES: this wave adds the residual rows of the entry it staged (tile, entry `wave`) into the image it filled
-    auto patch = [&](auto tensor_c, int tile, char *image) {
-        constexpr int TENSOR = decltype(tensor_c)::value;
-        const int item = entry_i(&Win::item, tile * C::kEntries + wave);
-        if (item < 0) return;
-        const int32_t *rp = rr.ptr + ((size_t)item * 2 + TENSOR) * a.hkv + kvh;
-        const int first = __builtin_amdgcn_readfirstlane(rp[0]), end = __builtin_amdgcn_readfirstlane(rp[1]);
-        if (first >= end) return;
-        RowLoad<D, 1> row;
-        row.issue(rr, first, end, lane);
-        row.apply((uint16_t *)image, rr, lane, StagedMap<D, TENSOR>{wave});
+    // RES: this wave adds the residual rows of the entries it staged (entry `wave` of a tile) into the images it
+    // filled.  The rows of one call are requested together, so a K tile and a V tile cost one memory round trip.
+    auto row_issue = [&](auto &row, int tensor, int tile) {
+        const int item = tile >= 0 ? entry_i(&Win::item, tile * C::kEntries + wave) : -1;
+        int first = 0, end = 0;
+        if (item >= 0) {
+            const int32_t *rp = rr.ptr + ((size_t)item * 2 + tensor) * a.hkv + kvh;
+            first = __builtin_amdgcn_readfirstlane(rp[0]);
+            end = __builtin_amdgcn_readfirstlane(rp[1]);
+        }
+        row.issue(rr, first, end, lane);             // an empty range loads nothing
     };
-    auto patch_k = [&](int tile, int buf) {
-        patch(std::integral_constant<int, 0>{}, tile, kbuf + buf * C::kKTile + wave * C::kDmaPerWave * 1024);
-    };
-    auto patch_v = [&](int tile, int buf) {
-        patch(std::integral_constant<int, 1>{}, tile, vbuf + buf * C::kVTile + wave * C::kDmaPerWave * 1024);
+    // K of `ktile` in K buffer `kb_i`, V of `vtile` in V buffer `vb_i`; a tile of -1 is skipped
+    auto patch_tiles = [&](int ktile, int kb_i, int vtile, int vb_i) {
+        RowLoad<D, 1> krow, vrow;                    // (two groups per lane for V would not fit the register budget)
+        row_issue(krow, 0, ktile);
+        row_issue(vrow, 1, vtile);
+        krow.apply((uint16_t *)(kbuf + kb_i * C::kKTile + wave * C::kDmaPerWave * 1024), rr, lane, StagedMap<D, 0>{wave});
+        vrow.apply((uint16_t *)(vbuf + vb_i * C::kVTile + wave * C::kDmaPerWave * 1024), rr, lane, StagedMap<D, 1>{wave});
     };
     if constexpr (RES) {
-        patch_k(0, 0);
-        patch_v(0, 0);
-        if (ntiles > 1) patch_k(1, 1);
+        patch_tiles(0, 0, 0, 0);
+        if (ntiles > 1) patch_tiles(1, 1, -1, 0);
     }
     __syncthreads();
     {
@@ -639,8 +640,7 @@ __global__ __launch_bounds__(NW * 64, RS == 1 ? 2 : 1) void prefill_kernel(
                 if constexpr (RES) {
                     // the tiles staged in this iteration are still this wave's alone (their windows are the
                     // ones cached before the slide below)
-                    if (k2) patch_k(t + 2, t & 1);
-                    if (has_next) patch_v(t + 1, (t + 1) % C::kVBufs);
+                    patch_tiles(k2 ? t + 2 : -1, t & 1, has_next ? t + 1 : -1, (t + 1) % C::kVBufs);
                 }
                 if (slide) {
                     w_cur = w_nxt;

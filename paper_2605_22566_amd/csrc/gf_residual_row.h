@@ -97,19 +97,43 @@ struct RowLoad {
                 uint16_t sum[8];
 #pragma unroll
                 for (int j = 0; j < 8; ++j) at[j] = map((gi[n][j / 2] >> (16 * (j % 2))) & 0xFFFFu);
+                if constexpr (!MAP::kPredicated) {
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    const uint32_t rd = MAP::kPredicated && at[j] == kNoElem ? 0u : at[j];
-                    const float base = __uint_as_float((uint32_t)img[rd] << 16);
-                    const float delta = __uint_as_float((gv[n][j / 2] >> (16 * (j % 2))) << 16);
-                    sum[j] = __builtin_bit_cast(uint16_t, (__bf16)(base + delta));
-                }
+                    for (int j = 0; j < 8; ++j) {
+                        const float base = __uint_as_float((uint32_t)img[at[j]] << 16);
+                        const float delta = __uint_as_float((gv[n][j / 2] >> (16 * (j % 2))) << 16);
+                        sum[j] = __builtin_bit_cast(uint16_t, (__bf16)(base + delta));
+                    }
 #pragma unroll
-                for (int j = 0; j < 8; ++j) {
-                    if constexpr (MAP::kPredicated) {
-                        if (at[j] != kNoElem) img[at[j]] = sum[j];
+                    for (int j = 0; j < 8; ++j) img[at[j]] = sum[j];
+                } else {
+                    // a lane either holds 8 entries of the row or none; entries outside the image are rare, so
+                    // the group is written under one lane mask unless some lane of the wave holds a stray
+                    const bool mine = g + 512 * n < a1;
+                    bool stray = false;
+#pragma unroll
+                    for (int j = 0; j < 8; ++j) stray |= at[j] == kNoElem;
+                    if (__builtin_amdgcn_ballot_w64(mine && stray) == 0) {
+                        if (mine) {
+#pragma unroll
+                            for (int j = 0; j < 8; ++j) {
+                                const float base = __uint_as_float((uint32_t)img[at[j]] << 16);
+                                const float delta = __uint_as_float((gv[n][j / 2] >> (16 * (j % 2))) << 16);
+                                sum[j] = __builtin_bit_cast(uint16_t, (__bf16)(base + delta));
+                            }
+#pragma unroll
+                            for (int j = 0; j < 8; ++j) img[at[j]] = sum[j];
+                        }
                     } else {
-                        img[at[j]] = sum[j];
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) {
+                            const float base = __uint_as_float((uint32_t)img[at[j] == kNoElem ? 0u : at[j]] << 16);
+                            const float delta = __uint_as_float((gv[n][j / 2] >> (16 * (j % 2))) << 16);
+                            sum[j] = __builtin_bit_cast(uint16_t, (__bf16)(base + delta));
+                        }
+#pragma unroll
+                        for (int j = 0; j < 8; ++j)
+                            if (at[j] != kNoElem) img[at[j]] = sum[j];
                     }
                 }
             }
