@@ -541,6 +541,28 @@ int32_t gf_attn_decode_shared(gf_ctx *ctx, const gf_attn_params *params, const g
                               const gf_tables *tables, const void *q, void *o, float *lse, void *stream);
 
 /*
+ * gf_attn_decode_shared_residual -- gf_attn_decode_shared with the sparse residuals applied while the blocks
+ * are read (paper, "Differential-based KV Cache", Eq. 7).  The KV of node v under prefix P is base(v) + the
+ * residual of the pair (P, v), so requests share a read of v exactly when they reach it through the same
+ * prefix: the lists are kept per (node, residual) pair instead of per node, and requests without a residual on
+ * v share the base read as before.  res_handle, num_items and the CSR are those of gf_attn_decode_residual,
+ * with one more rule, which gf_resolve_path_residual's output obeys: the handle b0 at a node's FIRST table
+ * entry names the residual of the whole node for that request -- block j of the node reads item b0 + j -- and
+ * a b0 outside [0, num_items - node blocks] (e.g. -1) reads every block of the node as stored; a residual's
+ * items belong to one node.  Each sum is taken in fp32 and rounded to bf16 before use, so the result is
+ * gf_attn_decode_shared's over a graph whose nodes are blocks reconstructed by gf_kv_apply_residual (same
+ * tolerance against gf_attn_decode_residual as gf_attn_decode_shared has against gf_attn_decode).
+ * GF_BF16 pools only (GF_ERR_UNSUPPORTED otherwise).  The lists of this call are not kept for
+ * gf_attn_decode_shared_planned.  Everything else as in gf_attn_decode_shared.
+ */
+int32_t gf_attn_decode_shared_residual(gf_ctx *ctx, const gf_attn_params *params, const gf_kv_pool *pool,
+                                       const gf_graph *graph, const int32_t *path_ptr, const int32_t *path_nodes,
+                                       int32_t num_path_entries, const gf_tables *tables,
+                                       const int32_t *res_handle, int32_t num_items,
+                                       const int32_t *res_ptr, const uint16_t *res_idx, const uint16_t *res_val,
+                                       const void *q, void *o, float *lse, void *stream);
+
+/*
  * gf_decode_shared_plan / gf_attn_decode_shared_planned -- gf_attn_decode_shared in two parts, for callers
  * that run the same batch through many layers: the node -> requests lists and item records depend on the
  * batch (graph, paths, tables) only, not on the pool or the queries, so they are built once

@@ -22,7 +22,7 @@ GF_BF16, GF_FP8_E4M3 = 0, 1
 GF_RS_OK, GF_RS_BAD_BLOCK, GF_RS_BAD_INDEX, GF_RS_TRUNCATED = 0, 1, 2, 3
 
 EXPORTS = ["gf_create", "gf_destroy", "gf_strerror", "gf_last_hip_error", "gf_resolve_path",
-           "gf_attn_prefill", "gf_attn_prefill_residual", "gf_attn_decode", "gf_attn_decode_residual", "gf_attn_decode_shared", "gf_decode_shared_plan", "gf_attn_decode_shared_planned",
+           "gf_attn_prefill", "gf_attn_prefill_residual", "gf_attn_decode", "gf_attn_decode_residual", "gf_attn_decode_shared", "gf_attn_decode_shared_residual", "gf_decode_shared_plan", "gf_attn_decode_shared_planned",
            "gf_set_decode_chunk_blocks", "gf_kv_apply_residual",
            "gf_kv_append", "gf_kv_append_token", "gf_attn_prefill_noalloc", "gf_hbm_read_probe",
            "gf_prefix_key", "gf_residual_dir_clear", "gf_residual_dir_insert", "gf_resolve_path_residual",
@@ -110,6 +110,10 @@ def load_library(path: Optional[str] = None):
     lib.gf_attn_decode_residual.argtypes = [C.c_void_p, C.POINTER(gf_attn_params), C.POINTER(gf_kv_pool),
                                             C.POINTER(gf_tables), C.c_void_p, C.c_int32] + [C.c_void_p] * 7
     lib.gf_attn_decode_residual.restype = C.c_int32
+    lib.gf_attn_decode_shared_residual.argtypes = [C.c_void_p, C.POINTER(gf_attn_params), C.POINTER(gf_kv_pool),
+                                                   C.POINTER(gf_graph), C.c_void_p, C.c_void_p, C.c_int32,
+                                                   C.POINTER(gf_tables), C.c_void_p, C.c_int32] + [C.c_void_p] * 7
+    lib.gf_attn_decode_shared_residual.restype = C.c_int32
     lib.gf_attn_decode_shared.argtypes = [C.c_void_p, C.POINTER(gf_attn_params), C.POINTER(gf_kv_pool),
                                           C.POINTER(gf_graph), C.c_void_p, C.c_void_p, C.c_int32,
                                           C.POINTER(gf_tables), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -260,6 +264,16 @@ def gf_attn_decode_residual(ctx, params, pool, tables, res_handle, num_items, re
     rc = load_library().gf_attn_decode_residual(ctx, C.byref(params), C.byref(pool), C.byref(tables), _ptr(res_handle),
                                                 num_items, _ptr(res_ptr), _ptr(res_idx), _ptr(res_val), _ptr(q),
                                                 _ptr(o), _ptr(lse), _stream())
+    _check(ctx, rc)
+
+
+def gf_attn_decode_shared_residual(ctx, params, pool, graph: gf_graph, path_ptr, path_nodes, num_path_entries, tables,
+                                   res_handle, num_items, res_ptr, res_idx, res_val, q, o, lse=None) -> None:
+    rc = load_library().gf_attn_decode_shared_residual(ctx, C.byref(params), C.byref(pool), C.byref(graph),
+                                                       _ptr(path_ptr), _ptr(path_nodes), num_path_entries,
+                                                       C.byref(tables), _ptr(res_handle), num_items, _ptr(res_ptr),
+                                                       _ptr(res_idx), _ptr(res_val), _ptr(q), _ptr(o), _ptr(lse),
+                                                       _stream())
     _check(ctx, rc)
 
 

@@ -402,9 +402,13 @@ int32_t gf_attn_decode_residual(gf_ctx *ctx, const gf_attn_params *params, const
 static int32_t decode_shared_call(gf_ctx *ctx, const gf_attn_params *params, const gf_kv_pool *pool,
                                   const gf_graph *graph, const int32_t *path_ptr, const int32_t *path_nodes,
                                   int32_t num_path_entries, const gf_tables *tables, const void *q, void *o, float *lse,
-                                  int phases, void *stream, const char *what) {
+                                  int phases, void *stream, const char *what, const gf::ResidualRefs *rr = nullptr) {
     if (!ctx || !graph) return GF_ERR_NULL;
     if (num_path_entries < 0 || graph->num_nodes < 0) return GF_ERR_BAD_SHAPE;
+    if (rr) {
+        if (rr->num_items < 0) return GF_ERR_BAD_SHAPE;
+        if (params && params->kv_dtype != GF_BF16) return GF_ERR_UNSUPPORTED;
+    }
     gf::AttnArgs a;
     int group = 0;
     // list building touches neither the pool nor q / o: stand-ins pass the shared checks
@@ -423,11 +427,12 @@ static int32_t decode_shared_call(gf_ctx *ctx, const gf_attn_params *params, con
     if (!path_ptr || !path_nodes) return GF_ERR_NULL;
     if (graph->num_nodes > 0 && (!graph->node_len || !graph->node_block_ptr || !graph->node_blocks))
         return GF_ERR_NULL;
+    if (rr && (!rr->handle || (rr->num_items > 0 && (!rr->ptr || !rr->idx || !rr->val)))) return GF_ERR_NULL;
     // the node-centric kernel keeps a chunk's table entries in one wave's lanes: 64 at most, and by default
     int32_t chunk = ctx->decode_chunk_blocks;
     if (chunk <= 0 || chunk > 64) chunk = 64;
-    const size_t need = gf::shared_workspace_bytes(graph->num_nodes, a.num_req, num_path_entries, a.max_blocks, chunk,
-                                                   a.hq, params->head_dim);
+    const size_t need = gf::shared_workspace_bytes(graph->num_nodes, rr ? rr->num_items : 0, a.num_req, num_path_entries,
+                                                   a.max_blocks, chunk, a.hq, params->head_dim);
     if (phases & gf::kSharedBuildLists) {
         ctx->shared_planned = false;
         rc = ensure_buffer(ctx, &ctx->shared_ws, &ctx->shared_ws_bytes, need, (hipStream_t)stream, what);
@@ -439,10 +444,11 @@ static int32_t decode_shared_call(gf_ctx *ctx, const gf_attn_params *params, con
     if (!(phases & gf::kSharedBuildLists) && !(ctx->shared_planned && ctx->shared_key == key && need <= ctx->shared_ws_bytes))
         return GF_ERR_BAD_SHAPE;                               // no lists, or lists of another batch / shape
     hipError_t e = gf::launch_decode_shared(a, params->head_dim, group, params->kv_dtype, *graph, path_ptr, path_nodes,
-                                            num_path_entries, chunk, ctx->shared_ws, phases, (hipStream_t)stream);
+                                            num_path_entries, chunk, ctx->shared_ws, phases, rr, (hipStream_t)stream);
     if (e == hipErrorNotSupported || e == hipErrorInvalidValue) return GF_ERR_UNSUPPORTED;
     if (e != hipSuccess) return fail_hip(ctx, e, what);
-    if (phases & gf::kSharedBuildLists) {
+    // lists built with residual handles are keyed by (node, residual): the plain attention call must not reuse them
+    if ((phases & gf::kSharedBuildLists) && !rr) {
         ctx->shared_key = key;
         ctx->shared_planned = true;
     }
@@ -455,6 +461,16 @@ int32_t gf_attn_decode_shared(gf_ctx *ctx, const gf_attn_params *params, const g
                               void *stream) {
     return decode_shared_call(ctx, params, pool, graph, path_ptr, path_nodes, num_path_entries, tables, q, o, lse,
                               gf::kSharedBuildLists | gf::kSharedAttend, stream, "gf_attn_decode_shared");
+}
+
+int32_t gf_attn_decode_shared_residual(gf_ctx *ctx, const gf_attn_params *params, const gf_kv_pool *pool,
+                                       const gf_graph *graph, const int32_t *path_ptr, const int32_t *path_nodes,
+                                       int32_t num_path_entries, const gf_tables *tables, const int32_t *res_handle,
+                                       int32_t num_items, const int32_t *res_ptr, const uint16_t *res_idx,
+                                       const uint16_t *res_val, const void *q, void *o, float *lse, void *stream) {
+    const gf::ResidualRefs rr = {res_handle, res_ptr, res_idx, res_val, num_items};
+    return decode_shared_call(ctx, params, pool, graph, path_ptr, path_nodes, num_path_entries, tables, q, o, lse,
+                              gf::kSharedBuildLists | gf::kSharedAttend, stream, "gf_attn_decode_shared_residual", &rr);
 }
 
 int32_t gf_decode_shared_plan(gf_ctx *ctx, const gf_attn_params *params, const gf_graph *graph,

@@ -24,7 +24,15 @@
 //           per node and per request: the item records
 // The order in which requests land in a node's list depends on the atomics, the values do not:
 // a column's result does not depend on which column it is.
+//
+// Differential KV (paper, "Differential-based KV Cache", Eq. 7: the KV of a node under a prefix is its base KV
+// plus that prefix's sparse residual).  With residual handles the lists are kept per KEY instead of per node: a
+// request that reads node v with the residual whose first item is b0 is listed under key num_nodes + b0, one
+// that reads v as stored under key v.  Requests that reach v through the same prefix carry the same residual
+// and still share one read of it; the workgroup that stages a block adds the residual rows into the LDS
+// image -- fp32 sum rounded to bf16, as gf_kv_apply_residual does -- before the barrier that publishes it.
 #include "gf_internal.h"
+#include "gf_residual_row.h"
 
 namespace gf {
 
@@ -37,9 +45,15 @@ struct SharedPlan {
     // graph and batch (device, caller's)
     const int32_t *node_len, *node_block_ptr, *node_blocks, *path_ptr, *path_nodes;
     int32_t num_nodes, num_entries;
-    // scratch (device, context's)
+    // residual handles of the table entries ([num_req][max_blocks], or nullptr) and the number of residual items;
+    // num_keys = num_nodes + num_items lists are kept (see the file header)
+    const int32_t *res_handle;
+    int32_t num_items, num_keys;
+    // scratch (device, context's); cnt, cursor, node_ptr, item_ptr are per key
     int32_t *cnt, *cursor, *node_ptr, *item_ptr, *entry_slot, *row_req, *row_slot, *tail_ptr, *totals;
-    int4 *item_rec;   // two per item, see ItemRec
+    int32_t *key_node;    // [num_items]: the node whose list key num_nodes + b is, -1 while unused
+    int32_t *entry_key;   // [num_entries]: list key of a path entry, -1 if the entry does not take part
+    int4 *item_rec;   // three per item, see ItemRec
     int32_t *perm;    // launch order of the items: node items by falling length, then the tail items
     int32_t chunk_blocks, item_cap, slot_cap;
 };
@@ -66,12 +80,18 @@ __device__ __forceinline__ int tail_blocks_of(const AttnArgs &a, int r) {
     return min((n + kBlock - 1) / kBlock, max(min(a.num_blocks[r], a.max_blocks), 0));
 }
 
+// node a list key stands for (-1 for a residual key nothing uses)
+__device__ __forceinline__ int key_base(const SharedPlan &p, int key) {
+    return key < p.num_nodes ? key : p.key_node[key - p.num_nodes];
+}
+
 __global__ void shared_zero_kernel(SharedPlan p) {
     const int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < p.num_nodes) {
+    if (i < p.num_keys) {
         p.cnt[i] = 0;
         p.cursor[i] = 0;
     }
+    if (i < p.num_items) p.key_node[i] = -1;
 }
 
 // request that owns path entry e: the last r with path_ptr[r] <= e (-1 if none does)
@@ -91,50 +111,70 @@ __global__ void shared_count_kernel(SharedPlan p, AttnArgs a) {
     if (e >= p.num_entries) return;
     const int r = request_of_entry(p, a, e);
     const int v = p.path_nodes[e];
-    int chunks = 0;
+    int chunks = 0, key = -1;
     if (r >= 0 && request_ok(a, r) && v >= 0 && v < p.num_nodes) {
-        atomicAdd(&p.cnt[v], 1);
+        key = v;
+        const int nblk = node_blocks_of(p, v);
+        if (p.res_handle && nblk > 0) {
+            // the node's first table entry: the blocks of the path entries before it (the order gf_resolve_path
+            // writes).  Its handle b0 names the residual of the whole node: block j of the node reads item b0 + j.
+            int pos = 0;
+            for (int x = path_lo(p, r); x < e; ++x) pos += node_blocks_of(p, p.path_nodes[x]);
+            if (pos + nblk <= a.max_blocks) {
+                const int b0 = p.res_handle[(size_t)r * a.max_blocks + pos];
+                if (b0 >= 0 && b0 <= p.num_items - nblk) {
+                    // a residual belongs to one node; a second node that claims the same items is read as stored
+                    const int old = atomicCAS(&p.key_node[b0], -1, v);
+                    if (old == -1 || old == v) key = p.num_nodes + b0;
+                }
+            }
+        }
+        atomicAdd(&p.cnt[key], 1);
         chunks = node_chunks_of(p, v);
     }
+    p.entry_key[e] = key;
     p.row_slot[e] = chunks;            // scratch until the fill kernel writes the rows
 }
 
-// exclusive scan of f(i), i in [0, n), by one workgroup; out[n] = total
+// exclusive scan of f(i), i in [0, n), by one workgroup; out[n] = total.  Every thread sums a contiguous run
+// of the range, the run totals are scanned across the workgroup, and the thread walks its run again.
 template <class F>
 __device__ void block_exscan(int n, F f, int32_t *out, int32_t *sh) {
     const int tid = threadIdx.x;
-    int carry = 0;
-    for (int base = 0; base < n; base += kScanThreads) {
-        const int i = base + tid;
-        const int x = i < n ? f(i) : 0;
-        sh[tid] = x;
+    const int per = (n + kScanThreads - 1) / kScanThreads;
+    const int i0 = min(tid * per, n), i1 = min(i0 + per, n);
+    int sum = 0;
+    for (int i = i0; i < i1; ++i) sum += f(i);
+    sh[tid] = sum;
+    __syncthreads();
+    for (int o = 1; o < kScanThreads; o <<= 1) {
+        const int y = tid >= o ? sh[tid - o] : 0;
         __syncthreads();
-        for (int o = 1; o < kScanThreads; o <<= 1) {
-            const int y = tid >= o ? sh[tid - o] : 0;
-            __syncthreads();
-            sh[tid] += y;
-            __syncthreads();
-        }
-        if (i < n) out[i] = carry + sh[tid] - x;
-        carry += sh[kScanThreads - 1];
+        sh[tid] += y;
         __syncthreads();
     }
-    if (tid == 0) out[n] = carry;
+    int run = sh[tid] - sum;
+    for (int i = i0; i < i1; ++i) {
+        out[i] = run;
+        run += f(i);
+    }
+    if (tid == kScanThreads - 1) out[n] = sh[tid];
     __syncthreads();
 }
 
 __global__ __launch_bounds__(kScanThreads) void shared_scan_kernel(SharedPlan p, AttnArgs a, int group, int item_cols) {
     __shared__ int32_t sh[kScanThreads];
-    block_exscan(p.num_nodes, [&](int v) { return p.cnt[v]; }, p.node_ptr, sh);
-    block_exscan(p.num_nodes, [&](int v) {
-        return node_chunks_of(p, v) * ((p.cnt[v] * group + item_cols - 1) / item_cols);
+    block_exscan(p.num_keys, [&](int k) { return p.cnt[k]; }, p.node_ptr, sh);
+    block_exscan(p.num_keys, [&](int k) {
+        const int n = p.cnt[k];
+        return n > 0 ? node_chunks_of(p, key_base(p, k)) * ((n * group + item_cols - 1) / item_cols) : 0;
     }, p.item_ptr, sh);
     block_exscan(p.num_entries, [&](int e) { return p.row_slot[e]; }, p.entry_slot, sh);
     block_exscan(a.num_req, [&](int r) {
         return request_ok(a, r) ? (tail_blocks_of(a, r) + p.chunk_blocks - 1) / p.chunk_blocks : 0;
     }, p.tail_ptr, sh);
     if (threadIdx.x == 0) {
-        p.totals[0] = min(p.item_ptr[p.num_nodes], p.item_cap);                  // node items
+        p.totals[0] = min(p.item_ptr[p.num_keys], p.item_cap);                   // node items
         p.totals[1] = min(p.tail_ptr[a.num_req], p.item_cap - p.totals[0]);       // tail items
         p.totals[2] = min(p.entry_slot[p.num_entries], p.slot_cap);              // node slots; tail slots follow
     }
@@ -150,24 +190,28 @@ struct ItemRec {
     int32_t cnt;        // node: requests in that list
     int32_t quad;       // node: which group of 64 * col_groups columns
     int32_t slot;       // node: chunk index, added to a row's first slot; tail: the partial slot itself
+    int32_t res0;       // residual item of the chunk's first block (block j reads item res0 + j), or -1
+    int32_t pad[3];
 };
-static_assert(sizeof(ItemRec) == 2 * sizeof(int4), "item record = two 16-byte words");
+constexpr int kRecWords = 3;
+static_assert(sizeof(ItemRec) == kRecWords * sizeof(int4), "item record = three 16-byte words");
 
 __device__ __forceinline__ void store_rec(const SharedPlan &p, int item, const ItemRec &r) {
-    p.item_rec[2 * (size_t)item] = make_int4(r.seg, r.tab_off, r.entries, r.tokens);
-    p.item_rec[2 * (size_t)item + 1] = make_int4(r.row0, r.cnt, r.quad, r.slot);
+    p.item_rec[kRecWords * (size_t)item] = make_int4(r.seg, r.tab_off, r.entries, r.tokens);
+    p.item_rec[kRecWords * (size_t)item + 1] = make_int4(r.row0, r.cnt, r.quad, r.slot);
+    p.item_rec[kRecWords * (size_t)item + 2] = make_int4(r.res0, 0, 0, 0);
 }
 
-// Threads [0, E): the rows of the node lists (request and first partial slot of every path entry).
-// Threads [E, E + N): a node's item records.  Threads [E + N, E + N + R): a request's tail item records.
+// Threads [0, E): the rows of the lists (request and first partial slot of every path entry).
+// Threads [E, E + K): a key's item records.  Threads [E + K, E + K + R): a request's tail item records.
 __global__ void shared_fill_kernel(SharedPlan p, AttnArgs a, int group, int item_cols) {
     int i = blockIdx.x * blockDim.x + threadIdx.x;
     if (i < p.num_entries) {
         const int e = i;
         const int r = request_of_entry(p, a, e);
-        const int v = p.path_nodes[e];
-        if (r < 0 || !request_ok(a, r) || v < 0 || v >= p.num_nodes) return;
-        const int row = p.node_ptr[v] + atomicAdd(&p.cursor[v], 1);
+        const int key = p.entry_key[e];
+        if (r < 0 || key < 0) return;
+        const int row = p.node_ptr[key] + atomicAdd(&p.cursor[key], 1);
         if (row < p.num_entries) {                             // always, unless paths overlap
             p.row_req[row] = r;
             p.row_slot[row] = p.entry_slot[e];
@@ -175,10 +219,12 @@ __global__ void shared_fill_kernel(SharedPlan p, AttnArgs a, int group, int item
         return;
     }
     i -= p.num_entries;
-    if (i < p.num_nodes) {
-        const int v = i, base = p.item_ptr[v], n = p.item_ptr[v + 1] - base;
+    if (i < p.num_keys) {
+        const int key = i, base = p.item_ptr[key], n = p.item_ptr[key + 1] - base;
         if (n <= 0) return;
-        const int cnt = p.cnt[v], nblk = node_blocks_of(p, v);
+        const int v = key_base(p, key);
+        if (v < 0 || v >= p.num_nodes) return;
+        const int cnt = p.cnt[key], nblk = node_blocks_of(p, v);
         const int quads = max((cnt * group + item_cols - 1) / item_cols, 1);
         for (int j = 0; j < n && base + j < p.totals[0]; ++j) {
             const int chunk = j / quads, e0 = chunk * p.chunk_blocks, e1 = min(nblk, e0 + p.chunk_blocks);
@@ -187,15 +233,16 @@ __global__ void shared_fill_kernel(SharedPlan p, AttnArgs a, int group, int item
             rec.tab_off = p.node_block_ptr[v] + e0;
             rec.entries = max(e1 - e0, 0);
             rec.tokens = max(min(p.node_len[v] - kBlock * e0, kBlock * (e1 - e0)), 0);
-            rec.row0 = p.node_ptr[v];
+            rec.row0 = p.node_ptr[key];
             rec.cnt = cnt;
             rec.quad = j % quads;
             rec.slot = chunk;
+            rec.res0 = key >= p.num_nodes ? key - p.num_nodes + e0 : -1;
             store_rec(p, base + j, rec);
         }
         return;
     }
-    i -= p.num_nodes;
+    i -= p.num_keys;
     if (i < a.num_req) {
         const int r = i, base = p.totals[0] + p.tail_ptr[r], n = p.tail_ptr[r + 1] - p.tail_ptr[r];
         if (n <= 0) return;
@@ -212,6 +259,7 @@ __global__ void shared_fill_kernel(SharedPlan p, AttnArgs a, int group, int item
             rec.cnt = 0;
             rec.quad = 0;
             rec.slot = p.totals[2] + p.tail_ptr[r] + j;
+            rec.res0 = -1;
             store_rec(p, base + j, rec);
         }
     }
@@ -230,7 +278,7 @@ __global__ __launch_bounds__(kScanThreads) void shared_order_kernel(SharedPlan p
     const int n_node = p.totals[0], n_tail = p.totals[1];
     for (int i = tid; i < kMaxChunk + 2; i += kScanThreads) hist[i] = 0;
     __syncthreads();
-    auto klass = [&](int i) -> int { return min(max(p.item_rec[2 * (size_t)i].z, 0), kMaxChunk); };
+    auto klass = [&](int i) -> int { return min(max(p.item_rec[kRecWords * (size_t)i].z, 0), kMaxChunk); };
     for (int i = tid; i < n_node; i += kScanThreads) atomicAdd(&hist[klass(i)], 1);
     __syncthreads();
     if (tid == 0) {
@@ -297,9 +345,32 @@ __device__ __forceinline__ void dma_wait() {
     asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
 }
 
-template <int D, int G, bool FP8>
+// Where a residual entry (logical element slot * D + d of a block) sits in a staged image of a bf16 pool (see the
+// staging constants in the kernel): K keeps [slot][d] with the 16-byte pieces of a row at position
+// piece ^ k_swz(block of the step, slot), V keeps [d][slot] with the two 8-slot halves of a row swapped on
+// every other group of 8 rows.
+template <int D, int TENSOR>
+struct SharedStagedMap {
+    static constexpr bool kPredicated = true;
+    int blk;                                         // which of the step's two blocks (sets the K swizzle)
+    __device__ __forceinline__ uint32_t operator()(uint32_t i) const {
+        const uint32_t slot = i / D, d = i % D;
+        uint32_t at;
+        if constexpr (TENSOR == 0) {
+            const uint32_t bits = (slot & 3) | (((slot >> 3) & 1) << 2) | ((uint32_t)blk << 3);
+            const uint32_t sw = D == 128 ? bits : D == 64 ? bits >> 1 : bits >> 2;
+            at = slot * D + (((d >> 3) ^ sw) << 3) + (d & 7);
+        } else {
+            at = d * kBlock + ((((slot >> 3) ^ (d >> 3)) & 1) << 3) + (slot & 7);
+        }
+        return i < (uint32_t)(kBlock * D) ? at : kNoElem;
+    }
+};
+
+template <int D, int G, bool FP8, bool RES>
 __global__ __launch_bounds__(kSharedThreads, wgs_per_cu(G)) void shared_attn_kernel(AttnArgs a, SharedPlan p, float *__restrict__ part_o,
-                                                                      float *__restrict__ part_ml) {
+                                                                      float *__restrict__ part_ml, ResidualRefs rr) {
+    static_assert(!(RES && FP8), "residuals are read in place on bf16 pools only");
     constexpr int kColGroups = col_groups(G);
     using C = StageCfg<D, FP8, wgs_per_cu(G)>;
     __shared__ __attribute__((aligned(1024))) char lds[C::kLds];
@@ -367,13 +438,18 @@ __global__ __launch_bounds__(kSharedThreads, wgs_per_cu(G)) void shared_attn_ker
     auto load_rec = [&](long w) -> Item {
         Item r;
         r.seg = 0; r.tab_off = 0; r.entries = 0; r.tokens = 0; r.row0 = 0; r.cnt = 0; r.quad = 0; r.slot = 0; r.kvh = 0;
+        r.res0 = -1;
         if (w < total_w) {
             const long round = w / grid, pos = w % grid;
             if ((round & 1) && (round + 1) * grid <= total_w) w = round * grid + (grid - 1 - pos);
             const long idx = min(max(p.perm[w / a.hkv], 0), p.totals[0] + p.totals[1] - 1);
-            const int4 x = p.item_rec[2 * idx], y = p.item_rec[2 * idx + 1];
+            const int4 x = p.item_rec[kRecWords * idx], y = p.item_rec[kRecWords * idx + 1];
             r.seg = x.x; r.tab_off = x.y; r.entries = min(x.z, kMaxChunk); r.tokens = x.w;
             r.row0 = y.x; r.cnt = y.y; r.quad = y.z; r.slot = y.w;
+            if constexpr (RES) {
+                const int b0 = p.item_rec[kRecWords * idx + 2].x;
+                r.res0 = (b0 >= 0 && b0 <= rr.num_items - r.entries) ? b0 : -1;
+            }
             r.kvh = (int)(w % a.hkv);
         }
         return r;
@@ -426,6 +502,7 @@ __global__ __launch_bounds__(kSharedThreads, wgs_per_cu(G)) void shared_attn_ker
     for (long w = first; w < total_w; w += grid) {
         const int kvh = rec.kvh;
         const int entries = rec.entries;
+        const int res0 = __builtin_amdgcn_readfirstlane(rec.res0);
         const int nsteps = (entries + 1) / 2;
         const int lane_blk = cur.blk, lane_ntok = cur.ntok;
         const float lane_ks = cur.ks, lane_vs = cur.vs;
@@ -487,6 +564,24 @@ __global__ __launch_bounds__(kSharedThreads, wgs_per_cu(G)) void shared_attn_ker
             // this wave's image of `step` has landed when at most its younger requests are outstanding
             if (step + C::kRing - 2 < nsteps) dma_wait<(C::kRing - 2) * C::kLoads>();
             else dma_wait<0>();
+            if constexpr (RES) {
+                // the image this wave staged for `step` is still its own: add the block's residual row for this
+                // kv head (K for waves 0 and 1, V for waves 2 and 3)
+                const int j = 2 * step + (wave & 1);
+                if (res0 >= 0 && j < entries) {
+                    constexpr int kK = 0, kV = 1;
+                    const int tensor = wave < 2 ? kK : kV;
+                    const int32_t *rp = rr.ptr + ((size_t)(res0 + j) * 2 + tensor) * a.hkv + kvh;
+                    const int e_first = __builtin_amdgcn_readfirstlane(rp[0]), e_end = __builtin_amdgcn_readfirstlane(rp[1]);
+                    if (e_first < e_end) {
+                        uint16_t *img = (uint16_t *)(lds + (wave < 2 ? 0 : C::kVBase) + slot * C::kPair + (wave & 1) * C::kBlkB);
+                        RowLoad<D, 1> row;
+                        row.issue(rr, e_first, e_end, lane);
+                        if (wave < 2) row.apply(img, rr, lane, SharedStagedMap<D, kK>{wave & 1});
+                        else row.apply(img, rr, lane, SharedStagedMap<D, kV>{wave & 1});
+                    }
+                }
+            }
             __syncthreads();           // all four images of `step` are in LDS; everybody is done with step - 1
             if (step + my_ring - 1 < nsteps) {
                 issue(step + my_ring - 1, slot == 0 ? my_ring - 1 : slot - 1);
@@ -696,16 +791,16 @@ size_t shared_slot_cap(int32_t num_req, int32_t num_entries, int32_t max_blocks,
     return (size_t)num_req * ((size_t)(max_blocks + chunk_blocks - 1) / chunk_blocks + 1) + (size_t)num_entries;
 }
 
-size_t shared_int_words(int32_t num_nodes, int32_t num_req, int32_t num_entries) {
-    return 4 * ((size_t)num_nodes + 1) + 3 * ((size_t)num_entries + 1) + ((size_t)num_req + 2) + 8;
+size_t shared_int_words(int32_t num_keys, int32_t num_items, int32_t num_req, int32_t num_entries) {
+    return 4 * ((size_t)num_keys + 1) + 4 * ((size_t)num_entries + 1) + (size_t)num_items + ((size_t)num_req + 2) + 8;
 }
-// + one 32-byte item record per partial slot (items <= slots: a node item serves at least one request)
+// + one item record per partial slot (items <= slots: a node item serves at least one request)
 
-size_t shared_workspace_bytes(int32_t num_nodes, int32_t num_req, int32_t num_entries, int32_t max_blocks,
-                              int32_t chunk_blocks, int32_t hq, int32_t head_dim) {
+size_t shared_workspace_bytes(int32_t num_nodes, int32_t num_items, int32_t num_req, int32_t num_entries,
+                              int32_t max_blocks, int32_t chunk_blocks, int32_t hq, int32_t head_dim) {
     const size_t slots = shared_slot_cap(num_req, num_entries, max_blocks, chunk_blocks);
-    return shared_int_words(num_nodes, num_req, num_entries) * sizeof(int32_t) + 16 + slots * sizeof(ItemRec) +
-           slots * sizeof(int32_t) + 256 + slots * hq * ((size_t)head_dim + 2) * sizeof(float);
+    return shared_int_words(num_nodes + num_items, num_items, num_req, num_entries) * sizeof(int32_t) + 16 +
+           slots * sizeof(ItemRec) + slots * sizeof(int32_t) + 256 + slots * hq * ((size_t)head_dim + 2) * sizeof(float);
 }
 
 // resident workgroups of the attention kernel on the whole device (the item loop strides by the grid, so
@@ -720,31 +815,36 @@ static int resident_grid(K kernel) {
     return g >= kXcds ? g / kXcds * kXcds : g;
 }
 
-template <int D, int G, bool FP8>
-static hipError_t launch_attn(const AttnArgs &a, SharedPlan p, float *part_o, float *part_ml, hipStream_t s) {
-    static int grid = resident_grid(shared_attn_kernel<D, G, FP8>);       // one device per process
+template <int D, int G, bool FP8, bool RES>
+static hipError_t launch_attn(const AttnArgs &a, SharedPlan p, float *part_o, float *part_ml, const ResidualRefs &rr,
+                              hipStream_t s) {
+    static int grid = resident_grid(shared_attn_kernel<D, G, FP8, RES>);  // one device per process
     if (grid <= 0) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((shared_attn_kernel<D, G, FP8>), dim3(grid), dim3(kSharedThreads), 0, s, a, p, part_o, part_ml);
+    hipLaunchKernelGGL((shared_attn_kernel<D, G, FP8, RES>), dim3(grid), dim3(kSharedThreads), 0, s, a, p, part_o,
+                       part_ml, rr);
     return hipGetLastError();
 }
 
 template <int D, int G>
 static hipError_t launch_shared_t(const AttnArgs &a, int kv_dtype, SharedPlan p, float *part_o, float *part_ml,
-                                  int phases, hipStream_t s) {
+                                  int phases, const ResidualRefs *rr, hipStream_t s) {
+    if (rr && kv_dtype == GF_FP8_E4M3) return hipErrorNotSupported;
     if (phases & kSharedBuildLists) {
-        const unsigned nz = (unsigned)((p.num_nodes + 255) / 256), ne = (unsigned)((p.num_entries + 255) / 256);
+        const unsigned nz = (unsigned)((p.num_keys + 255) / 256), ne = (unsigned)((p.num_entries + 255) / 256);
         hipLaunchKernelGGL(shared_zero_kernel, dim3(nz ? nz : 1), dim3(256), 0, s, p);
         if (ne) hipLaunchKernelGGL(shared_count_kernel, dim3(ne), dim3(256), 0, s, p, a);
         hipLaunchKernelGGL(shared_scan_kernel, dim3(1), dim3(kScanThreads), 0, s, p, a, G, 64 * col_groups(G));
-        const unsigned nf = (unsigned)(((size_t)p.num_entries + p.num_nodes + a.num_req + 255) / 256);
+        const unsigned nf = (unsigned)(((size_t)p.num_entries + p.num_keys + a.num_req + 255) / 256);
         hipLaunchKernelGGL(shared_fill_kernel, dim3(nf), dim3(256), 0, s, p, a, G, 64 * col_groups(G));
         hipLaunchKernelGGL(shared_order_kernel, dim3(1), dim3(kScanThreads), 0, s, p);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
     }
     if (phases & kSharedAttend) {
-        const hipError_t e = kv_dtype == GF_FP8_E4M3 ? launch_attn<D, G, true>(a, p, part_o, part_ml, s)
-                                                     : launch_attn<D, G, false>(a, p, part_o, part_ml, s);
+        const ResidualRefs none = {nullptr, nullptr, nullptr, nullptr, 0};
+        const hipError_t e = kv_dtype == GF_FP8_E4M3 ? launch_attn<D, G, true, false>(a, p, part_o, part_ml, none, s)
+                             : rr                    ? launch_attn<D, G, false, true>(a, p, part_o, part_ml, *rr, s)
+                                                     : launch_attn<D, G, false, false>(a, p, part_o, part_ml, none, s);
         if (e != hipSuccess) return e;
         const size_t rows = (size_t)a.num_req * a.hq;
         hipLaunchKernelGGL((shared_merge_kernel<D>), dim3((unsigned)((rows + 3) / 4)), dim3(256), 0, s, a, p, part_o,
@@ -755,9 +855,14 @@ static hipError_t launch_shared_t(const AttnArgs &a, int kv_dtype, SharedPlan p,
 
 hipError_t launch_decode_shared(const AttnArgs &a, int head_dim, int group, int kv_dtype, const gf_graph &g,
                                 const int32_t *path_ptr, const int32_t *path_nodes, int32_t num_entries,
-                                int32_t chunk_blocks, void *workspace, int phases, hipStream_t s) {
+                                int32_t chunk_blocks, void *workspace, int phases, const ResidualRefs *rr,
+                                hipStream_t s) {
     if (a.num_req == 0) return hipSuccess;
     SharedPlan p;
+    p.res_handle = rr ? rr->handle : nullptr;
+    p.num_items = rr ? rr->num_items : 0;
+    if ((size_t)g.num_nodes + (size_t)p.num_items > 0x7ffffff0u) return hipErrorInvalidValue;
+    p.num_keys = g.num_nodes + p.num_items;
     p.node_len = g.node_len;
     p.node_block_ptr = g.node_block_ptr;
     p.node_blocks = g.node_blocks;
@@ -767,7 +872,7 @@ hipError_t launch_decode_shared(const AttnArgs &a, int head_dim, int group, int 
     p.num_entries = num_entries;
     p.chunk_blocks = chunk_blocks < kMaxChunk ? chunk_blocks : kMaxChunk;
     int32_t *w = (int32_t *)workspace;
-    const size_t n1 = (size_t)g.num_nodes + 1, e1 = (size_t)num_entries + 1;
+    const size_t n1 = (size_t)p.num_keys + 1, e1 = (size_t)num_entries + 1;
     p.cnt = w;            w += n1;
     p.cursor = w;         w += n1;
     p.node_ptr = w;       w += n1;
@@ -775,6 +880,8 @@ hipError_t launch_decode_shared(const AttnArgs &a, int head_dim, int group, int 
     p.entry_slot = w;     w += e1;
     p.row_req = w;        w += e1;
     p.row_slot = w;       w += e1;
+    p.entry_key = w;      w += e1;
+    p.key_node = w;       w += (size_t)p.num_items;
     p.tail_ptr = w;       w += (size_t)a.num_req + 2;
     p.totals = w;         w += 8;
     const size_t slots = shared_slot_cap(a.num_req, num_entries, a.max_blocks, chunk_blocks);
@@ -785,11 +892,11 @@ hipError_t launch_decode_shared(const AttnArgs &a, int head_dim, int group, int 
     p.item_cap = (int32_t)slots;
     p.slot_cap = (int32_t)slots;
     p.item_rec = (int4 *)(((uintptr_t)w + 15) & ~(uintptr_t)15);
-    p.perm = (int32_t *)(p.item_rec + 2 * slots);
+    p.perm = (int32_t *)(p.item_rec + kRecWords * slots);
     float *part_o = (float *)(((uintptr_t)(p.perm + slots) + 255) & ~(uintptr_t)255);
     float *part_ml = part_o + slots * a.hq * (size_t)head_dim;
 #define GF_CASE(DD, GG) \
-    if (head_dim == DD && group == GG) return launch_shared_t<DD, GG>(a, kv_dtype, p, part_o, part_ml, phases, s);
+    if (head_dim == DD && group == GG) return launch_shared_t<DD, GG>(a, kv_dtype, p, part_o, part_ml, phases, rr, s);
     GF_CASE(64, 1) GF_CASE(64, 2) GF_CASE(64, 4) GF_CASE(64, 8)
     GF_CASE(128, 1) GF_CASE(128, 2) GF_CASE(128, 4) GF_CASE(128, 8)
 #undef GF_CASE

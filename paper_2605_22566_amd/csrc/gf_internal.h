@@ -75,14 +75,16 @@ hipError_t launch_decode_residual(const AttnArgs &a, const ResidualRefs &rr, int
                                   int32_t chunk_blocks, int32_t splits, void *workspace, hipStream_t s);
 
 // node-centric decode: workspace bytes and the launcher (list building + node, tail and merge kernels)
-size_t shared_workspace_bytes(int32_t num_nodes, int32_t num_req, int32_t num_entries, int32_t max_blocks,
-                              int32_t chunk_blocks, int32_t hq, int32_t head_dim);
+// (`num_items`: residual items the call may be given, 0 for the plain call)
+size_t shared_workspace_bytes(int32_t num_nodes, int32_t num_items, int32_t num_req, int32_t num_entries,
+                              int32_t max_blocks, int32_t chunk_blocks, int32_t hq, int32_t head_dim);
 // `phases`: build the lists and item records, run attention + merge over them, or both; the two phases of one
 // batch must be given the same workspace and the same sizes
 constexpr int kSharedBuildLists = 1, kSharedAttend = 2;
 hipError_t launch_decode_shared(const AttnArgs &a, int head_dim, int group, int kv_dtype, const gf_graph &g,
                                 const int32_t *path_ptr, const int32_t *path_nodes, int32_t num_entries,
-                                int32_t chunk_blocks, void *workspace, int phases, hipStream_t s);
+                                int32_t chunk_blocks, void *workspace, int phases, const ResidualRefs *rr,
+                                hipStream_t s);
 
 // state-management policy: residual directory, resolution with residual handles, statistics, pruning
 uint64_t prefix_key_host(const int32_t *nodes, int32_t len);

@@ -238,6 +238,15 @@ class Session:
         B.gf_attn_decode_shared(self.ctx, params, dpool, graph, dbatch["path_ptr"], dbatch["path_nodes"],
                                 dbatch["num_path_entries"], dt, q, o, lse)
 
+    def decode_shared_residual(self, pool, dbatch, tables, res_handle, dres, q, o, lse=None, sm_scale=0.0):
+        """Node-centric decode with residuals applied as the blocks are read (`res_handle`, `dres` as in
+        decode_residual; a node's first handle names the residual of the whole node)."""
+        params, dpool, dt = self._common(pool, tables, sm_scale)
+        graph = B.make_graph(self.wl.graph.num_nodes, self.node_len, self.node_block_ptr, self.node_blocks)
+        B.gf_attn_decode_shared_residual(self.ctx, params, dpool, graph, dbatch["path_ptr"], dbatch["path_nodes"],
+                                         dbatch["num_path_entries"], dt, res_handle, dres["num_items"], dres["ptr"],
+                                         dres["idx"], dres["val"], q, o, lse)
+
     def decode_shared_plan(self, pool, dbatch, tables):
         """Build the node lists of a batch once; decode_shared_planned() then runs any number of layers on them."""
         params, _, dt = self._common(pool, tables, 0.0)

@@ -491,7 +491,7 @@ class Residuals:
 
 
 def add_residual_instances(wl: Workload, last_nodes: int = 1, density_k: float = 0.25, density_v: float = 0.30,
-                           std: float = 0.3, seed: int = 11) -> tuple:
+                           std: float = 0.3, seed: int = 11, by_prefix: bool = False) -> tuple:
     """Give every request private, prefix-conditioned instances of the last
     ``last_nodes`` nodes of its path: new node ids with their own (new) pool
     blocks, an edge from the predecessor, and a sparse residual against the
@@ -500,7 +500,9 @@ def add_residual_instances(wl: Workload, last_nodes: int = 1, density_k: float =
     the paper reports that more than 75 % of key and 70 % of value entries of a
     prefix-induced difference are negligible).  Returns (workload', Residuals);
     the pool of the new workload is larger by the instance blocks, which hold
-    nothing until the residuals are applied."""
+    nothing until the residuals are applied.  With by_prefix the instances belong to (prefix path, node) pairs
+    instead of requests: requests that reach a node through the same prefix share one instance and its residual
+    (the paper's KV(P, v)); the first node of a path, whose prefix is empty, then keeps its base KV."""
     rng = np.random.default_rng([wl.seed, seed])
     g, b, sh = wl.graph, wl.batch, wl.shape
     hkv, dim = sh.num_kv_heads, sh.head_dim
@@ -510,11 +512,20 @@ def add_residual_instances(wl: Workload, last_nodes: int = 1, density_k: float =
     path_nodes = b.path_nodes.copy()
     next_block = wl.num_pool_blocks
     src, dst, ptr, idx, val = [], [], [0], [], []
+    inst_of = {}
     for r in range(b.num_req):
         p0, p1 = int(b.path_ptr[r]), int(b.path_ptr[r + 1])
-        for pos in range(max(p0, p1 - last_nodes), p1):
+        for pos in range(max(p0 + (1 if by_prefix else 0), p1 - last_nodes), p1):
             v = int(path_nodes[pos])
+            pair = tuple(int(x) for x in b.path_nodes[p0:pos + 1])
+            if by_prefix and pair in inst_of:
+                inst = inst_of[pair]
+                if pos > p0:
+                    edges.append((int(path_nodes[pos - 1]), inst))
+                path_nodes[pos] = inst
+                continue
             inst = len(node_len)
+            inst_of[pair] = inst
             node_len.append(node_len[v])
             nb = _nblk(node_len[v])
             blocks = list(range(next_block, next_block + nb))
