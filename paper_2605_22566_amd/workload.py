@@ -576,6 +576,32 @@ def residual_handles(base_table: np.ndarray, inst_table: np.ndarray, res: Residu
     return h
 
 
+def prefix_pair_handles(wl: Workload, req_lo: int, req_hi: int, max_blocks: int, depth: int = 1 << 30) -> tuple:
+    """Residual handles for requests [req_lo, req_hi) with one stored residual per (prefix path, node) pair -- the
+    paper's KV(P, v): every node of a path beyond the first (at most the last ``depth`` of them) reads the
+    residual of its pair; pairs are numbered as they are met and a pair's items (one per block of its node) are
+    consecutive.  Returns (handles int32 [req_hi - req_lo, max_blocks], number of items, number of pairs,
+    number of (request, node) uses of a pair)."""
+    g, b = wl.graph, wl.batch
+    nbl = (g.node_len.astype(np.int64) + BLOCK - 1) // BLOCK
+    handles = np.full((req_hi - req_lo, max_blocks), -1, np.int32)
+    first_item, items, uses = {}, 0, 0
+    for r in range(req_lo, req_hi):
+        path = [int(v) for v in b.path_nodes[b.path_ptr[r]:b.path_ptr[r + 1]]]
+        pos = 0
+        for i, v in enumerate(path):
+            n = int(nbl[v])
+            if i >= 1 and i >= len(path) - depth:
+                key = tuple(path[:i + 1])
+                if key not in first_item:
+                    first_item[key] = items
+                    items += n
+                handles[r - req_lo, pos:pos + n] = first_item[key] + np.arange(n, dtype=np.int32)
+                uses += 1
+            pos += n
+    return handles, items, len(first_item), uses
+
+
 # --------------------------------------------------------------------------- #
 # accounting (pure counting; used by bench and docs)
 # --------------------------------------------------------------------------- #
