@@ -33,6 +33,12 @@ slots take part; the write path leaves them zero), 1.0 for an all-zero block, co
 e4m3(clamp(x / scale)), fp32 division, round to nearest even.  Reading: the paper keeps KV in
 16 bits; a quantised pool with a residual on top is this build's combination of the two.
 
+Packed form (pack_rows, unpack_rows, reconstruct_packed): the same residual stored as one bit mask per image (bit
+i of the image = logical element i = slot * D + d, kept in 32-bit words, bit i % 32 of word i // 32) plus the kept
+values alone, in rising element order; the row pointers are those of the CSR.  At the densities the paper reports
+this is 0.34 of a dense bf16 block where the CSR (2 B index + 2 B value) is 0.55.  Reading: the paper does not fix
+a storage format; the arithmetic of a reconstruction from either form is the same.
+
 Pins (tests/test_oracle_residual.py): the bf16 rounding against torch's cast on
 random values, ties and extremes; an empty residual is the identity; the residual
 -base gives all zeros; a full-density residual equals torch's element-wise bf16 add;
@@ -45,6 +51,9 @@ energy sits in three entries keeps exactly those; K and V entries land on the ha
 re-codes a block onto itself (same codes, same scale) when its largest code is the largest
 finite one; codes and scales against torch's float8 casts of the same fp32 sums; the
 dequantised result within half a code step of base + delta; bad blocks and indices reported.
+Packed form: a hand-written image (bits and value order typed in by hand); unpack(pack(x)) gives x with rows sorted
+by element; the mask's population count is the row length; reconstruct_packed equals reconstruct() on the CSR it
+was packed from (which is pinned above) and lands hand-indexed single entries on the same physical K / V elements.
 """
 import numpy as np
 
@@ -139,6 +148,82 @@ def reconstruct_e4m3(k_pool, v_pool, k_scale, v_scale, src_blocks, dst_blocks, r
             pool[t] = f32_to_e4m3_codes(y)
             scale[t] = sc
     return k_out, v_out, ks_out, vs_out, status
+
+
+def mask_words(dim: int) -> int:
+    """32-bit words of one image's bit mask."""
+    return BLOCK * dim // 32
+
+
+def pack_rows(res_ptr, res_idx, res_val, dim: int):
+    """CSR rows -> packed form: (mask uint32 [rows, 16 * dim / 32], values uint16 [nnz]) with the values of a
+    row in rising element order (the rows of the CSR may be in any order; they name distinct elements inside
+    the image)."""
+    rows = len(res_ptr) - 1
+    mask = np.zeros((rows, mask_words(dim)), dtype=np.uint32)
+    val = np.zeros(len(res_val), dtype=np.uint16)
+    for r in range(rows):
+        e0, e1 = int(res_ptr[r]), int(res_ptr[r + 1])
+        order = np.argsort(np.asarray(res_idx[e0:e1], dtype=np.int64), kind="stable")
+        for k, o in enumerate(order):
+            i = int(res_idx[e0 + o])
+            assert 0 <= i < BLOCK * dim and not (int(mask[r, i // 32]) >> (i % 32)) & 1
+            mask[r, i // 32] |= np.uint32(1 << (i % 32))
+            val[e0 + k] = res_val[e0 + o]
+    return mask, val
+
+
+def unpack_rows(res_ptr, mask, dim: int) -> np.ndarray:
+    """Element indices (uint16, rising inside a row) of a packed residual; row r must hold res_ptr[r+1] -
+    res_ptr[r] set bits."""
+    idx = np.zeros(int(res_ptr[-1]), dtype=np.uint16)
+    for r in range(len(res_ptr) - 1):
+        e = int(res_ptr[r])
+        for i in range(BLOCK * dim):
+            if (int(mask[r, i // 32]) >> (i % 32)) & 1:
+                idx[e] = i
+                e += 1
+        assert e == int(res_ptr[r + 1])
+    return idx
+
+
+def reconstruct_packed(k_pool: np.ndarray, v_pool: np.ndarray, src_blocks, dst_blocks, res_ptr, mask, val):
+    """reconstruct() from the packed form, read as the format is defined: the elements of an image are walked in
+    rising order and every set bit consumes the next value of its row.  Returns (k_pool', v_pool', status);
+    status is ST_BAD_INDEX for an item with a row whose bit count is not its row length (the row is applied as
+    far as its values reach)."""
+    k_out, v_out = k_pool.copy(), v_pool.copy()
+    nb, hkv, _, dim = k_pool.shape
+    status = np.zeros(len(src_blocks), dtype=np.int32)
+    for b in range(len(src_blocks)):
+        s, t = int(src_blocks[b]), int(dst_blocks[b])
+        if not (0 <= s < nb and 0 <= t < nb):
+            status[b] = ST_BAD_BLOCK
+            continue
+        kb = bf16_bits_to_f32(k_pool[s]).copy()          # [Hkv, 16, D]
+        vb = bf16_bits_to_f32(v_pool[s]).copy()          # [Hkv, D, 16]
+        for tensor in (0, 1):
+            for h in range(hkv):
+                r = (b * 2 + tensor) * hkv + h
+                e, e1 = int(res_ptr[r]), int(res_ptr[r + 1])
+                for i in range(BLOCK * dim):
+                    if not (int(mask[r, i // 32]) >> (i % 32)) & 1:
+                        continue
+                    if e >= e1:
+                        status[b] = ST_BAD_INDEX
+                        break
+                    delta = bf16_bits_to_f32(np.array([val[e]], dtype=np.uint16))[0]
+                    e += 1
+                    slot, d = divmod(i, dim)
+                    if tensor == 0:
+                        kb[h, slot, d] = np.float32(kb[h, slot, d]) + np.float32(delta)
+                    else:
+                        vb[h, d, slot] = np.float32(vb[h, d, slot]) + np.float32(delta)
+                if e != e1:
+                    status[b] = ST_BAD_INDEX
+        k_out[t] = f32_to_bf16_bits_rne(kb)
+        v_out[t] = f32_to_bf16_bits_rne(vb)
+    return k_out, v_out, status
 
 
 def make_residual(k_pool: np.ndarray, v_pool: np.ndarray, base_blocks, full_blocks, share: float = 0.95):

@@ -291,3 +291,78 @@ def test_make_residual_round_trip_hand_image_and_layouts():
     assert rows[0] == ([], []) and rows[3] == ([], [])
     assert rows[1] == ([63, 5 * 64 + 9, 15 * 64], [-16.0, 16.0, 8.0])         # K head 1, by index; 0.5 dropped
     assert rows[2] == ([3 * 64 + 20], [4.0])                                  # V head 0
+
+
+def test_packed_form_hand_image_round_trip_and_equivalence_to_the_csr():
+    dim = 64
+    # one image written out by hand: elements 0, 33, 64 (slot 1, d 0) and 1023 (slot 15, d 63), listed unsorted
+    ptr = np.array([0, 4], np.int32)
+    idx = np.array([1023, 0, 64, 33], np.uint16)
+    val = np.array([0x4080, 0x3F80, 0x4040, 0x4000], np.uint16)         # 4.0, 1.0, 3.0, 2.0
+    mask, pv = OR.pack_rows(ptr, idx, val, dim)
+    assert mask.shape == (1, 16 * dim // 32) and mask.dtype == np.uint32
+    want = np.zeros(32, np.uint32)
+    want[0] = 1            # element 0: word 0, bit 0
+    want[1] = 1 << 1       # element 33: word 1, bit 1
+    want[2] = 1            # element 64: word 2, bit 0
+    want[31] = 1 << 31     # element 1023: word 31, bit 31
+    assert (mask[0] == want).all()
+    assert pv.tolist() == [0x3F80, 0x4000, 0x4040, 0x4080]              # values follow the elements: 1, 2, 3, 4
+    assert OR.unpack_rows(ptr, mask, dim).tolist() == [0, 33, 64, 1023]
+    # random rows at both head dims: round trip, bit counts, and the reconstruction equals the CSR's
+    rng = np.random.default_rng(14)
+    for hkv, dim in ((2, 64), (1, 128)):
+        k, v = _pool(rng, 6, hkv, dim)
+        rows = 3 * 2 * hkv
+        parts, p = [], [0]
+        for r in range(rows):
+            n = int(rng.integers(0, 16 * dim // 3)) if r % 5 else 0     # some rows empty
+            parts.append(rng.permutation(16 * dim)[:n].astype(np.uint16))
+            p.append(p[-1] + n)
+        idx = np.concatenate(parts)
+        val = OR.f32_to_bf16_bits_rne(rng.standard_normal(idx.size).astype(np.float32))
+        p = np.asarray(p, np.int32)
+        mask, pv = OR.pack_rows(p, idx, val, dim)
+        bits = np.array([sum(bin(int(w)).count("1") for w in mask[r]) for r in range(rows)])
+        assert (bits == np.diff(p)).all()
+        got_idx = OR.unpack_rows(p, mask, dim)
+        for r in range(rows):
+            seg = slice(int(p[r]), int(p[r + 1]))
+            order = np.argsort(idx[seg].astype(np.int64))
+            assert (got_idx[seg] == idx[seg][order]).all() and (pv[seg] == val[seg][order]).all()
+        src, dst = [0, 2, 1], [3, 4, 5]
+        k1, v1, s1 = OR.reconstruct(k, v, src, dst, p, idx, val)
+        k2, v2, s2 = OR.reconstruct_packed(k, v, src, dst, p, mask, pv)
+        assert (k1 == k2).all() and (v1 == v2).all() and s1.tolist() == s2.tolist() == [0, 0, 0]
+
+
+def test_packed_single_entries_land_on_the_hand_indexed_physical_element_and_bad_rows_are_reported():
+    rng = np.random.default_rng(15)
+    hkv, dim = 4, 64
+    k, v = _pool(rng, 2, hkv, dim)
+    two = np.array([0x4000], np.uint16)
+    for (t, h, slot, d) in [(0, 0, 0, 0), (0, 3, 15, 63), (1, 0, 0, 0), (1, 2, 9, 33), (1, 3, 15, 63)]:
+        row = t * hkv + h
+        ptr = [0] * (row + 1) + [1] * (2 * hkv - row)
+        mask = np.zeros((2 * hkv, 16 * dim // 32), np.uint32)
+        i = slot * dim + d
+        mask[row, i // 32] = 1 << (i % 32)
+        k2, v2, st = OR.reconstruct_packed(k, v, [0], [1], ptr, mask, two)
+        assert st.tolist() == [0]
+        dk, dv = k2[1] != k[0], v2[1] != v[0]
+        if t == 0:
+            assert dk.sum() == 1 and dk[h, slot, d] and not dv.any()
+        else:
+            assert dv.sum() == 1 and dv[h, d, slot] and not dk.any()
+    # a row with more bits than values, a row with fewer, a block outside the pool
+    ptr = np.zeros(2 * hkv + 1, np.int32)
+    ptr[1:] = 1
+    mask = np.zeros((2 * hkv, 16 * dim // 32), np.uint32)
+    mask[0, 0] = 0b11
+    _, _, st = OR.reconstruct_packed(k, v, [0], [1], ptr, mask, two)
+    assert st.tolist() == [OR.ST_BAD_INDEX]
+    mask[0, 0] = 0
+    _, _, st = OR.reconstruct_packed(k, v, [0], [1], ptr, mask, two)
+    assert st.tolist() == [OR.ST_BAD_INDEX]
+    _, _, st = OR.reconstruct_packed(k, v, [0], [7], ptr, mask, two)
+    assert st.tolist() == [OR.ST_BAD_BLOCK]
