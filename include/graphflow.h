@@ -305,6 +305,40 @@ int32_t gf_kv_make_residual(gf_ctx *ctx, const gf_attn_params *params, const voi
                             int32_t *res_ptr, uint16_t *res_idx, uint16_t *res_val, int32_t *status, void *stream);
 
 /*
+ * The packed form of a residual -- what is kept at rest (paper, "Differential-based KV Cache", Eq. 7, and the
+ * KV-sparsity appendix: more than 75 % of key and 70 % of value entries of a prefix-induced difference are
+ * negligible).  The coordinate rows above cost 2 B of index + 2 B of value per kept element (0.55 of a dense
+ * bf16 block at those densities); the packed form keeps, per (item, tensor, kv head) image, one bit per element
+ *   res_mask[row][w]  bit (i % 32) of word w = i / 32 is set iff logical element i = slot * head_dim + d is kept
+ *                     (16 * head_dim / 32 words per row, rows as in gf_kv_apply_residual)
+ * and the kept values alone, in rising element order, row after row: packed_val[res_ptr[row] ..
+ * res_ptr[row + 1]) -- 0.34 of a dense block.  res_ptr is the same array in both forms.  A coordinate list whose
+ * rows are sorted by element (gf_kv_make_residual writes such rows) already has its values in packed order.
+ *   gf_kv_residual_pack          rows in any order -> res_mask, packed_val (not in place: packed_val != res_val).
+ *                                An item with an entry outside its image or an element named twice reports
+ *                                GF_RS_BAD_INDEX and its output is unspecified (all writes stay inside the item's
+ *                                rows).
+ *   gf_kv_residual_unpack        res_mask -> res_idx in rising order (the row's values are packed_val as they are).
+ *                                An item with a row whose bit count differs from its row length reports
+ *                                GF_RS_BAD_INDEX (indices are written as far as the row reaches).
+ *   gf_kv_apply_residual_packed  gf_kv_apply_residual from the packed form: same arithmetic, same contract, same
+ *                                result bit for bit.  GF_BF16 pools only.  A row whose bit count differs from its
+ *                                row length reports GF_RS_BAD_INDEX (it is applied as far as its values reach).
+ * All arrays device memory; status [num_items] or NULL.
+ */
+int32_t gf_kv_residual_pack(gf_ctx *ctx, const gf_attn_params *params, int32_t num_items,
+                            const int32_t *res_ptr, const uint16_t *res_idx, const uint16_t *res_val,
+                            uint32_t *res_mask, uint16_t *packed_val, int32_t *status, void *stream);
+int32_t gf_kv_residual_unpack(gf_ctx *ctx, const gf_attn_params *params, int32_t num_items,
+                              const int32_t *res_ptr, const uint32_t *res_mask, uint16_t *res_idx,
+                              int32_t *status, void *stream);
+int32_t gf_kv_apply_residual_packed(gf_ctx *ctx, const gf_attn_params *params, void *k_pool, void *v_pool,
+                                    int32_t num_pool_blocks, int32_t num_items,
+                                    const int32_t *src_blocks, const int32_t *dst_blocks,
+                                    const int32_t *res_ptr, const uint32_t *res_mask, const uint16_t *packed_val,
+                                    int32_t *status, void *stream);
+
+/*
  * gf_attn_decode_residual -- gf_attn_decode with the sparse residuals applied
  * while the blocks are read, instead of being reconstructed into pool blocks
  * first (paper, "Differential-based KV Cache", Eq. 7: only the base KV of a node

@@ -23,7 +23,8 @@ GF_RS_OK, GF_RS_BAD_BLOCK, GF_RS_BAD_INDEX, GF_RS_TRUNCATED = 0, 1, 2, 3
 
 EXPORTS = ["gf_create", "gf_destroy", "gf_strerror", "gf_last_hip_error", "gf_resolve_path",
            "gf_attn_prefill", "gf_attn_prefill_residual", "gf_attn_decode", "gf_attn_decode_residual", "gf_attn_decode_shared", "gf_attn_decode_shared_residual", "gf_decode_shared_plan", "gf_attn_decode_shared_planned",
-           "gf_set_decode_chunk_blocks", "gf_kv_apply_residual",
+           "gf_set_decode_chunk_blocks", "gf_kv_apply_residual", "gf_kv_residual_pack", "gf_kv_residual_unpack",
+           "gf_kv_apply_residual_packed",
            "gf_kv_append", "gf_kv_append_token", "gf_attn_prefill_noalloc", "gf_hbm_read_probe",
            "gf_prefix_key", "gf_residual_dir_clear", "gf_residual_dir_insert", "gf_resolve_path_residual",
            "gf_residual_dir_prune", "gf_kv_make_residual", "gf_block_pool_create", "gf_block_pool_destroy", "gf_block_pool_alloc",
@@ -96,6 +97,13 @@ def load_library(path: Optional[str] = None):
                                     C.c_void_p, C.c_void_p, C.c_void_p]
     lib.gf_attn_prefill.restype = C.c_int32
     lib.gf_attn_prefill_noalloc.argtypes = lib.gf_attn_prefill.argtypes
+    lib.gf_kv_residual_pack.argtypes = [C.c_void_p, C.POINTER(gf_attn_params), C.c_int32] + [C.c_void_p] * 7
+    lib.gf_kv_residual_pack.restype = C.c_int32
+    lib.gf_kv_residual_unpack.argtypes = [C.c_void_p, C.POINTER(gf_attn_params), C.c_int32] + [C.c_void_p] * 5
+    lib.gf_kv_residual_unpack.restype = C.c_int32
+    lib.gf_kv_apply_residual_packed.argtypes = [C.c_void_p, C.POINTER(gf_attn_params), C.c_void_p, C.c_void_p,
+                                                C.c_int32, C.c_int32] + [C.c_void_p] * 7
+    lib.gf_kv_apply_residual_packed.restype = C.c_int32
     lib.gf_attn_prefill_residual.argtypes = [C.c_void_p, C.POINTER(gf_attn_params), C.POINTER(gf_kv_pool),
                                              C.POINTER(gf_tables), C.c_void_p, C.c_int32, C.c_void_p, C.c_void_p,
                                              C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
@@ -236,6 +244,26 @@ def gf_attn_prefill(ctx, params, pool, tables, q, q_ptr, total_q, max_q, o, lse=
 def gf_attn_prefill_noalloc(ctx, params, pool, tables, q, q_ptr, total_q, max_q, o, lse=None) -> None:
     rc = load_library().gf_attn_prefill_noalloc(ctx, C.byref(params), C.byref(pool), C.byref(tables), _ptr(q),
                                                 _ptr(q_ptr), total_q, max_q, _ptr(o), _ptr(lse), _stream())
+    _check(ctx, rc)
+
+
+def gf_kv_residual_pack(ctx, params, num_items, res_ptr, res_idx, res_val, res_mask, packed_val, status=None) -> None:
+    rc = load_library().gf_kv_residual_pack(ctx, C.byref(params), num_items, _ptr(res_ptr), _ptr(res_idx),
+                                            _ptr(res_val), _ptr(res_mask), _ptr(packed_val), _ptr(status), _stream())
+    _check(ctx, rc)
+
+
+def gf_kv_residual_unpack(ctx, params, num_items, res_ptr, res_mask, res_idx, status=None) -> None:
+    rc = load_library().gf_kv_residual_unpack(ctx, C.byref(params), num_items, _ptr(res_ptr), _ptr(res_mask),
+                                              _ptr(res_idx), _ptr(status), _stream())
+    _check(ctx, rc)
+
+
+def gf_kv_apply_residual_packed(ctx, params, k_pool, v_pool, num_pool_blocks, num_items, src_blocks, dst_blocks,
+                                res_ptr, res_mask, packed_val, status=None) -> None:
+    rc = load_library().gf_kv_apply_residual_packed(ctx, C.byref(params), _ptr(k_pool), _ptr(v_pool), num_pool_blocks,
+                                                    num_items, _ptr(src_blocks), _ptr(dst_blocks), _ptr(res_ptr),
+                                                    _ptr(res_mask), _ptr(packed_val), _ptr(status), _stream())
     _check(ctx, rc)
 
 

@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libgraphflow.so")
-SOURCES = ["gf_api.hip", "gf_resolve.hip", "gf_prefill.hip", "gf_decode.hip", "gf_decode_shared.hip", "gf_residual.hip", "gf_append.hip",
+SOURCES = ["gf_api.hip", "gf_resolve.hip", "gf_prefill.hip", "gf_decode.hip", "gf_decode_shared.hip", "gf_residual.hip", "gf_residual_packed.hip", "gf_append.hip",
            "gf_probe.hip", "gf_policy.hip", "gf_pool.hip", "gf_make_residual.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # inputs are finite by contract: lets fmaxf lower to bare v_max / v_max3 (infinities stay honoured).

@@ -513,6 +513,60 @@ int32_t gf_kv_apply_residual(gf_ctx *ctx, const gf_attn_params *params, void *k_
     return GF_OK;
 }
 
+// shape checks shared by the three calls on the packed residual form
+static int32_t check_packed(const gf_ctx *ctx, const gf_attn_params *params, int32_t num_items) {
+    if (!ctx || !params) return GF_ERR_NULL;
+    if (num_items < 0 || params->num_kv_heads <= 0 || params->head_dim <= 0) return GF_ERR_BAD_SHAPE;
+    if (params->block_size != gf::kBlock) return GF_ERR_UNSUPPORTED;
+    if (params->head_dim != 64 && params->head_dim != 128) return GF_ERR_UNSUPPORTED;
+    if ((int64_t)num_items * 2 * params->num_kv_heads >= 0x7fffffffLL) return GF_ERR_UNSUPPORTED;
+    return GF_OK;
+}
+
+int32_t gf_kv_residual_pack(gf_ctx *ctx, const gf_attn_params *params, int32_t num_items, const int32_t *res_ptr,
+                            const uint16_t *res_idx, const uint16_t *res_val, uint32_t *res_mask,
+                            uint16_t *packed_val, int32_t *status, void *stream) {
+    int32_t rc = check_packed(ctx, params, num_items);
+    if (rc != GF_OK || num_items == 0) return rc;
+    if (!res_ptr || !res_idx || !res_val || !res_mask || !packed_val) return GF_ERR_NULL;
+    if (packed_val == res_val) return GF_ERR_BAD_SHAPE;              // the values are permuted: not in place
+    hipError_t e = gf::launch_residual_pack(params->num_kv_heads, params->head_dim, num_items, res_ptr, res_idx,
+                                            res_val, res_mask, packed_val, status, (hipStream_t)stream);
+    if (e == hipErrorNotSupported) return GF_ERR_UNSUPPORTED;
+    if (e != hipSuccess) return fail_hip(ctx, e, "gf_kv_residual_pack launch");
+    return GF_OK;
+}
+
+int32_t gf_kv_residual_unpack(gf_ctx *ctx, const gf_attn_params *params, int32_t num_items, const int32_t *res_ptr,
+                              const uint32_t *res_mask, uint16_t *res_idx, int32_t *status, void *stream) {
+    int32_t rc = check_packed(ctx, params, num_items);
+    if (rc != GF_OK || num_items == 0) return rc;
+    if (!res_ptr || !res_mask || !res_idx) return GF_ERR_NULL;
+    hipError_t e = gf::launch_residual_unpack(params->num_kv_heads, params->head_dim, num_items, res_ptr, res_mask,
+                                              res_idx, status, (hipStream_t)stream);
+    if (e == hipErrorNotSupported) return GF_ERR_UNSUPPORTED;
+    if (e != hipSuccess) return fail_hip(ctx, e, "gf_kv_residual_unpack launch");
+    return GF_OK;
+}
+
+int32_t gf_kv_apply_residual_packed(gf_ctx *ctx, const gf_attn_params *params, void *k_pool, void *v_pool,
+                                    int32_t num_pool_blocks, int32_t num_items, const int32_t *src_blocks,
+                                    const int32_t *dst_blocks, const int32_t *res_ptr, const uint32_t *res_mask,
+                                    const uint16_t *packed_val, int32_t *status, void *stream) {
+    int32_t rc = check_packed(ctx, params, num_items);
+    if (rc != GF_OK) return rc;
+    if (num_pool_blocks < 0) return GF_ERR_BAD_SHAPE;
+    if (params->kv_dtype != GF_BF16) return GF_ERR_UNSUPPORTED;
+    if (num_items == 0) return GF_OK;
+    if (!k_pool || !v_pool || !src_blocks || !dst_blocks || !res_ptr || !res_mask || !packed_val) return GF_ERR_NULL;
+    hipError_t e = gf::launch_residual_packed(k_pool, v_pool, num_pool_blocks, params->num_kv_heads, params->head_dim,
+                                              num_items, src_blocks, dst_blocks, res_ptr, res_mask, packed_val, status,
+                                              (hipStream_t)stream);
+    if (e == hipErrorNotSupported) return GF_ERR_UNSUPPORTED;
+    if (e != hipSuccess) return fail_hip(ctx, e, "gf_kv_apply_residual_packed launch");
+    return GF_OK;
+}
+
 int32_t gf_kv_make_residual(gf_ctx *ctx, const gf_attn_params *params, const void *k_pool, const void *v_pool,
                             int32_t num_pool_blocks, int32_t num_items, const int32_t *base_blocks,
                             const int32_t *full_blocks, double energy_share, int32_t capacity, int32_t *res_ptr,

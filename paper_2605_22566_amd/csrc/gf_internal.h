@@ -102,6 +102,16 @@ hipError_t launch_residual(void *k_pool, void *v_pool, float *k_scale, float *v_
                            int32_t hkv, int32_t head_dim, int kv_dtype, int32_t num_items, const int32_t *src_blocks,
                            const int32_t *dst_blocks, const int32_t *res_ptr, const uint16_t *res_idx,
                            const uint16_t *res_val, int32_t *status, hipStream_t s);
+// the packed form of a residual (bit mask per image + values in element order): converters and reconstruction
+hipError_t launch_residual_pack(int32_t hkv, int32_t head_dim, int32_t num_items, const int32_t *res_ptr,
+                                const uint16_t *res_idx, const uint16_t *res_val, uint32_t *res_mask,
+                                uint16_t *packed_val, int32_t *status, hipStream_t s);
+hipError_t launch_residual_unpack(int32_t hkv, int32_t head_dim, int32_t num_items, const int32_t *res_ptr,
+                                  const uint32_t *res_mask, uint16_t *res_idx, int32_t *status, hipStream_t s);
+hipError_t launch_residual_packed(void *k_pool, void *v_pool, int32_t num_pool_blocks, int32_t hkv, int32_t head_dim,
+                                  int32_t num_items, const int32_t *src_blocks, const int32_t *dst_blocks,
+                                  const int32_t *res_ptr, const uint32_t *res_mask, const uint16_t *packed_val,
+                                  int32_t *status, hipStream_t s);
 
 // residual producer: dense prefix-conditioned blocks -> CSR by the energy rule (count, scan, fill)
 hipError_t launch_make_residual(const void *k_pool, const void *v_pool, int32_t num_pool_blocks, int32_t hkv,

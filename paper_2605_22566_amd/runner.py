@@ -192,6 +192,38 @@ class Session:
                                dres["dst"], dres["ptr"], dres["idx"], dres["val"], dres["status"], pool.k_scale,
                                pool.v_scale)
 
+    def pack_residuals(self, dres):
+        """gf_kv_residual_pack: the packed form (bit masks + values in element order) of an uploaded residual;
+        returns the dict with `mask` and `pval` added (and a status of its own under `pack_status`)."""
+        sh = self.wl.shape
+        n = dres["num_items"]
+        rows = n * 2 * sh.num_kv_heads
+        words = W.BLOCK * sh.head_dim // 32
+        out = dict(dres)
+        out["mask"] = torch.full((max(rows, 1), words), -1, dtype=torch.int32, device=self.device)
+        out["pval"] = torch.zeros_like(dres["val"])
+        out["pack_status"] = torch.full((max(n, 1),), -77, dtype=torch.int32, device=self.device)
+        params = B.make_params(sh.num_q_heads, sh.num_kv_heads, sh.head_dim, sh.kv_dtype)
+        B.gf_kv_residual_pack(self.ctx, params, n, dres["ptr"], dres["idx"], dres["val"], out["mask"], out["pval"],
+                              out["pack_status"])
+        return out
+
+    def unpack_residuals(self, packed):
+        """gf_kv_residual_unpack: element indices (rising inside a row) of a packed residual."""
+        sh = self.wl.shape
+        idx = torch.full_like(packed["idx"], -1)
+        status = torch.full((max(packed["num_items"], 1),), -77, dtype=torch.int32, device=self.device)
+        params = B.make_params(sh.num_q_heads, sh.num_kv_heads, sh.head_dim, sh.kv_dtype)
+        B.gf_kv_residual_unpack(self.ctx, params, packed["num_items"], packed["ptr"], packed["mask"], idx, status)
+        return idx, status
+
+    def apply_residual_packed(self, pool, packed):
+        sh = self.wl.shape
+        params = B.make_params(sh.num_q_heads, sh.num_kv_heads, sh.head_dim, sh.kv_dtype)
+        B.gf_kv_apply_residual_packed(self.ctx, params, pool.k, pool.v, pool.num_blocks, packed["num_items"],
+                                      packed["src"], packed["dst"], packed["ptr"], packed["mask"], packed["pval"],
+                                      packed["status"])
+
     def make_residual(self, pool, base_blocks, full_blocks, share=0.95, capacity=None):
         """gf_kv_make_residual: the residual of blocks `full_blocks` against `base_blocks` (device int32 tensors) as
         the dict apply_residual / decode_residual take (src = base, dst = full), plus the number of entries."""
