@@ -485,6 +485,32 @@ def measure_residual(torch, R, W, num_items=8192, iters=20):
            "algorithmic_bytes_per_launch": nbytes, "gbs_kernel": nbytes / (ms * 1e-3) / 1e9,
            "frac_of_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS, "all_items_ok": ok,
            "hbm_bytes_per_launch_rocprof": _read_traffic("residual_kv_residual")}
+    # the packed form (bit mask per image + values in element order): what a residual costs at rest, the
+    # conversion, and the reconstruction straight from it
+    packed = sess.pack_residuals(dres)
+    torch.cuda.synchronize()
+    ms_pack = _event_ms(lambda: sess.pack_residuals(dres), torch, 5)
+    ms_unpack = _event_ms(lambda: sess.unpack_residuals(packed), torch, 5)
+    before = pool.k[num_items:].clone()
+    fnp = lambda: sess.apply_residual_packed(pool, packed)
+    fnp()
+    torch.cuda.synchronize()
+    same = bool(torch.equal(before.view(torch.int16), pool.k[num_items:].view(torch.int16)))
+    del before
+    ms_p = _event_ms(fnp, torch, iters)
+    rows = num_items * 2 * sh.num_kv_heads
+    mask_bytes = rows * (W.BLOCK * sh.head_dim // 8)
+    nbytes_p = num_items * (2 * blk + 8 + 4 * 2 * sh.num_kv_heads) + 2.0 * nnz + mask_bytes
+    out["packed"] = {"kernel": "residual_packed_kernel", "kernel_ms": ms_p, "algorithmic_bytes_per_launch": nbytes_p,
+                     "gbs_kernel": nbytes_p / (ms_p * 1e-3) / 1e9,
+                     "frac_of_hbm_peak": nbytes_p / (ms_p * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                     "same_blocks_as_coordinate_form": same, "pack_ms": ms_pack, "unpack_ms": ms_unpack,
+                     "coordinate_bytes": 4.0 * nnz + 4.0 * (rows + 1),
+                     "packed_bytes": 2.0 * nnz + mask_bytes + 4.0 * (rows + 1),
+                     "dense_bytes": float(num_items) * blk,
+                     "packed_over_dense": (2.0 * nnz + mask_bytes + 4.0 * (rows + 1)) / (float(num_items) * blk),
+                     "coordinate_over_dense": (4.0 * nnz + 4.0 * (rows + 1)) / (float(num_items) * blk)}
+    del packed
     # the way back: gf_kv_make_residual recovers a residual from the reconstructed blocks against their base blocks
     # (95 % energy rule; per image a sort in LDS, two passes over the blocks): an offline step, timed for the record
     fnm = lambda: sess.make_residual(pool, dres["src"], dres["dst"], 0.95)

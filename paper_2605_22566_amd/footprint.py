@@ -8,8 +8,10 @@ library (one layer; K and V; blocks of 16 tokens are allocated whole).
                 shared only between requests whose whole prefix up to the node is identical
   stateless     every node once (what the block pool holds when every residual is zero)
   differential  every node once + a sparse residual per distinct (prefix, node) pair with a non-empty
-                prefix: CSR rows per (block, tensor, kv head), 2 B index + 2 B value per kept element,
-                `density_k` / `density_v` of the elements kept
+                prefix, `density_k` / `density_v` of the elements kept, in the form it is stored in at rest
+                (`residual_form="packed"`: one bit per element of every (block, tensor, kv head) image + 2 B per
+                kept value) or in the form the attention kernels read (`"coordinate"`: 2 B index + 2 B value
+                per kept element)
   pruned        differential, but residuals only for pairs reached through a transition (previous node ->
                 node) seen at least `min_count` times in the execution statistics; the others fall back
                 to on-the-fly computation and store nothing
@@ -36,17 +38,28 @@ def transition_counts(batch: W.Batch) -> Dict[tuple, int]:
     return cnt
 
 
+def residual_block_bytes(shape: W.Shape, density_k: float, density_v: float, form: str = "packed") -> float:
+    """Bytes a residual holds per pool block of its node (all kv heads, K and V)."""
+    img_elems = W.BLOCK * shape.head_dim                               # one (tensor, kv head) image of a block
+    kept = shape.num_kv_heads * img_elems * (density_k + density_v)
+    rows = 2 * shape.num_kv_heads
+    if form == "packed":
+        return kept * 2.0 + rows * img_elems / 8.0 + rows * 4 + 8      # values, masks, row pointers, block ids
+    if form == "coordinate":
+        return kept * 4.0 + rows * 4 + 8                               # 2 B index + 2 B value
+    raise ValueError(form)
+
+
 def footprint(wl: W.Workload, requests: Optional[Iterable[int]] = None, density_k: float = 0.25,
-              density_v: float = 0.30, min_count: int = 2, stats: Optional[Dict[tuple, int]] = None) -> dict:
+              density_v: float = 0.30, min_count: int = 2, stats: Optional[Dict[tuple, int]] = None,
+              residual_form: str = "packed") -> dict:
     """Bytes held for the given requests (default: the whole batch) under each design.  `stats` are the
     transition counts pruning looks at (default: those of the whole batch)."""
     sh, g, b = wl.shape, wl.graph, wl.batch
     req = list(range(b.num_req)) if requests is None else [int(r) for r in requests]
     esz = 2 if sh.kv_dtype == W.KV_BF16 else 1
     blk_bytes = 2 * sh.num_kv_heads * W.BLOCK * sh.head_dim * esz + (8 if esz == 1 else 0)   # K + V (+ two scales)
-    img_elems = W.BLOCK * sh.head_dim                                  # one (tensor, kv head) image of a block
-    res_blk_bytes = (sh.num_kv_heads * img_elems * (density_k + density_v) * 4.0   # 2 B index + 2 B value
-                     + 2 * sh.num_kv_heads * 4 + 8)                    # row pointers, source / destination ids
+    res_blk_bytes = residual_block_bytes(sh, density_k, density_v, residual_form)
     stats = transition_counts(b) if stats is None else stats
     nblk = _blocks(g.node_len)
     nodes, pairs, pruned_pairs = set(), {}, {}
@@ -65,7 +78,7 @@ def footprint(wl: W.Workload, requests: Optional[Iterable[int]] = None, density_
     kept = sum(pruned_pairs.values())
     tails = tail_blocks * blk_bytes
     return {
-        "requests": len(req), "nodes": len(nodes), "prefix_node_pairs": len(pairs),
+        "requests": len(req), "residual_form": residual_form, "nodes": len(nodes), "prefix_node_pairs": len(pairs),
         "pairs_with_residual": sum(1 for k in pairs if len(k) > 1), "pairs_kept_by_pruning": len(pruned_pairs),
         "stateful_bytes": float(sum(pairs.values())) * blk_bytes + tails,
         "stateless_bytes": float(base) * blk_bytes + tails,
