@@ -185,6 +185,114 @@ def test_decode_8b_read_time_residual_full_size_sampled():
         assert np.abs(O0 - O).max() > 1e-3
 
 
+def _oracle_rows_with_handles(wl, pool, want, dres, handles_row, r, q_rows, decode):
+    """The oracle's answer for request r when table entry e reads block + residual item handles_row[e]: copies of
+    the request's blocks are reconstructed from copies of its CSR rows, then attended."""
+    from oracle import residual as OR
+    sh = wl.shape
+    rows = 2 * sh.num_kv_heads
+    ptr = dres["ptr"].cpu().numpy().astype(np.int64)
+    n = want["num_blocks"][r]
+    ids = np.array(want["block_table"][r][:n], dtype=np.int64)
+    kk, vv, _, _ = pool.gather_host(ids)
+    hr = handles_row[:n]
+    ents = np.nonzero(hr >= 0)[0]
+    assert ents.size > 0
+    lptr, lidx, lval = [0], [], []
+    for e in ents:
+        lo, hi = int(ptr[hr[e] * rows]), int(ptr[(hr[e] + 1) * rows])
+        lptr += list(ptr[hr[e] * rows + 1:(hr[e] + 1) * rows + 1] - lo + lptr[-1])
+        lidx.append(dres["idx"][lo:hi].cpu().numpy().view(np.uint16))
+        lval.append(dres["val"][lo:hi].cpu().numpy().view(np.uint16))
+    k2, v2, st = OR.reconstruct(kk, vv, ents, ents, np.array(lptr), np.concatenate(lidx), np.concatenate(lval))
+    assert (st == 0).all() and not np.array_equal(k2, kk)
+    local = {k: [v[r]] for k, v in want.items()}
+    local["block_table"] = [list(range(n))]
+    if decode:
+        return OA.decode(q_rows, k2, v2, local)[0]
+    return OA.prefill(q_rows, np.array([0, q_rows.shape[0]]), k2, v2, local)[0]
+
+
+def test_prefill_8b_read_time_residual_full_size():
+    """gf_attn_prefill_residual in the launch bench.py times (config 2), one stored residual per (prefix path, node)
+    pair on the last two nodes of every path: every row of every request equals, bit for bit, the plain prefill
+    over blocks reconstructed by gf_kv_apply_residual; one request is checked against the oracle."""
+    wl, sess, tables, pool, q, q_ptr = _setup("prefill_8b")
+    sh, dev = wl.shape, sess.device
+    want = oracle_resolve(wl)
+    mb = int(tables["max_blocks"])
+    handles_h, n_items, pairs, uses = W.prefix_pair_handles(wl, 0, wl.batch.num_req, mb, depth=2)
+    assert uses > pairs > 20 and n_items > 1000
+    handles = torch.from_numpy(handles_h).to(dev)
+    dres, nnz = R.random_residuals(sh, n_items, dev)
+    qp = torch.from_numpy(q_ptr).to(dev)
+    total_q, max_q = int(q.shape[0]), int(wl.batch.new_lens.max())
+    o = torch.full_like(q, float("nan"))
+    sess.prefill_residual(pool, tables, handles, dres, q, qp, total_q, max_q, o)
+    torch.cuda.synchronize()
+    og = o.double().cpu().numpy()
+    assert np.isfinite(og).all()
+    # the two-step form: item b reconstructs the base block of the table entry that names it into block nb + b
+    nb = pool.num_blocks
+    bt = tables["block_table"]
+    src = torch.zeros(n_items, dtype=torch.int32, device=dev)
+    src[handles[handles >= 0].long()] = bt[handles >= 0]
+    dres["src"], dres["dst"] = src, nb + torch.arange(n_items, dtype=torch.int32, device=dev)
+    big = R.DevicePool(torch.cat([pool.k, torch.zeros((n_items,) + pool.k.shape[1:], dtype=pool.k.dtype, device=dev)]),
+                       torch.cat([pool.v, torch.zeros((n_items,) + pool.v.shape[1:], dtype=pool.v.dtype, device=dev)]),
+                       nb + n_items)
+    sess.apply_residual(big, dres)
+    t2 = dict(tables)
+    t2["block_table"] = torch.where(handles >= 0, nb + handles, bt)
+    o2 = torch.full_like(q, float("nan"))
+    sess.prefill(big, t2, q, qp, total_q, max_q, o2)
+    torch.cuda.synchronize()
+    assert bool((dres["status"] == 0).all().item())
+    assert torch.equal(o.view(torch.int16), o2.view(torch.int16))
+    sess.prefill(pool, tables, q, qp, total_q, max_q, o2)
+    torch.cuda.synchronize()
+    assert not torch.equal(o.view(torch.int16), o2.view(torch.int16))       # and the residual matters
+    # oracle on the request with the least work among those with a residual
+    n, L = wl.batch.new_lens.astype(np.int64), W.context_lens(wl)
+    r = int(np.argsort(n * (L + n))[0])
+    assert (handles_h[r] >= 0).any()
+    qb = R.bf16_to_bits(q)
+    lo, hi = int(q_ptr[r]), int(q_ptr[r + 1])
+    O = _oracle_rows_with_handles(wl, pool, want, dres, handles_h[r], r, qb[lo:hi], decode=False)
+    atol, rtol = TOL[sh.kv_dtype]
+    err = np.abs(og[lo:hi] - O)
+    assert (err <= atol + rtol * np.abs(O)).all(), f"request {r}: max err {err.max()}"
+
+
+def test_decode_8b_node_centric_read_time_residual_full_size():
+    """gf_attn_decode_shared_residual in the launch bench.py times (config 3, one residual per (prefix path, node)
+    pair on every node beyond the first): all 256 requests against gf_attn_decode_residual on the same handles
+    (the tolerance the node-centric step has against the per-request one), two requests against the oracle."""
+    wl, sess, tables, pool, q, q_ptr = _setup("decode_8b")
+    sh, dev = wl.shape, sess.device
+    want = oracle_resolve(wl)
+    handles_h, n_items, pairs, uses = W.prefix_pair_handles(wl, 0, wl.batch.num_req, int(tables["max_blocks"]))
+    assert uses > pairs > 100
+    handles = torch.from_numpy(handles_h).to(dev)
+    dres, nnz = R.random_residuals(sh, n_items, dev)
+    last = torch.from_numpy((q_ptr[1:] - 1).astype(np.int64)).to(dev)
+    qd = q[last].contiguous()
+    od, od_req = torch.full_like(qd, float("nan")), torch.full_like(qd, float("nan"))
+    sess.decode_shared_residual(pool, sess.dbatch, tables, handles, dres, qd, od)
+    sess.decode_residual(pool, tables, handles, dres, qd, od_req)
+    torch.cuda.synchronize()
+    og, og_req = od.double().cpu().numpy(), od_req.double().cpu().numpy()
+    assert np.isfinite(og).all()
+    atol, rtol = TOL[sh.kv_dtype]
+    assert (np.abs(og - og_req) <= atol + rtol * np.abs(og_req)).all()
+    qb = R.bf16_to_bits(qd)
+    L = W.context_lens(wl)
+    for r in (int(np.argmin(L)), int(np.argsort(L)[5])):        # the entry-by-entry oracle bounds the sample
+        O = _oracle_rows_with_handles(wl, pool, want, dres, handles_h[r], r, qb[r:r + 1], decode=True)
+        err = np.abs(og[r:r + 1] - O)
+        assert (err <= atol + rtol * np.abs(O)).all(), f"request {r}: max err {err.max()}"
+
+
 def test_kv_residual_bench_size_sampled_blocks():
     """The residual launch bench.py times (8192 blocks of the 8B head shape, device-generated
     residuals): sampled items are reconstructed by the oracle from copies of their base blocks and
