@@ -405,10 +405,7 @@ static int32_t decode_shared_call(gf_ctx *ctx, const gf_attn_params *params, con
                                   int phases, void *stream, const char *what, const gf::ResidualRefs *rr = nullptr) {
     if (!ctx || !graph) return GF_ERR_NULL;
     if (num_path_entries < 0 || graph->num_nodes < 0) return GF_ERR_BAD_SHAPE;
-    if (rr) {
-        if (rr->num_items < 0) return GF_ERR_BAD_SHAPE;
-        if (params && params->kv_dtype != GF_BF16) return GF_ERR_UNSUPPORTED;
-    }
+    if (rr && rr->num_items < 0) return GF_ERR_BAD_SHAPE;
     gf::AttnArgs a;
     int group = 0;
     // list building touches neither the pool nor q / o: stand-ins pass the shared checks
@@ -423,6 +420,7 @@ static int32_t decode_shared_call(gf_ctx *ctx, const gf_attn_params *params, con
     int32_t rc = check_attn(params ? &checked : nullptr, attend ? pool : &no_pool, tables, attend ? q : &dummy,
                             attend ? o : (void *)&dummy, lse, a, group);
     if (rc != GF_OK) return rc;
+    if (rr && params->kv_dtype != GF_BF16) return GF_ERR_UNSUPPORTED;
     if (tables->num_req == 0) return GF_OK;
     if (!path_ptr || !path_nodes) return GF_ERR_NULL;
     if (graph->num_nodes > 0 && (!graph->node_len || !graph->node_block_ptr || !graph->node_blocks))

@@ -39,6 +39,9 @@ def test_unsupported_shapes_and_bad_sizes_are_rejected():
         "decode_residual": lambda p: B.gf_attn_decode_residual(sess.ctx, p, dpool, dt, hnd, 0, None, None, None, qd, od),
         "decode_shared": lambda p: B.gf_attn_decode_shared(sess.ctx, p, dpool, graph, db["path_ptr"], db["path_nodes"],
                                                            db["num_path_entries"], dt, qd, od),
+        "decode_shared_residual": lambda p: B.gf_attn_decode_shared_residual(
+            sess.ctx, p, dpool, graph, db["path_ptr"], db["path_nodes"], db["num_path_entries"], dt, hnd, 0, None,
+            None, None, qd, od),
     }
     for name, call in calls.items():
         assert _code(lambda: call(B.make_params(8, 2, 96))) == B.GF_ERR_UNSUPPORTED, name          # head_dim
@@ -63,6 +66,27 @@ def test_unsupported_shapes_and_bad_sizes_are_rejected():
     assert _code(lambda: B.gf_attn_decode_residual(sess.ctx, params, dpool, dt, hnd, -1, None, None, None, qd, od)) \
         == B.GF_ERR_BAD_SHAPE
     B.gf_attn_decode_residual(sess.ctx, params, dpool, dt, hnd, 0, None, None, None, qd, od)          # no items: fine
+    # the other two residual-reading calls check the same things
+    sh_args = (graph, db["path_ptr"], db["path_nodes"], db["num_path_entries"], dt)
+    assert _code(lambda: B.gf_attn_decode_shared_residual(sess.ctx, params, dpool, *sh_args, None, 0, None, None, None,
+                                                          qd, od)) == B.GF_ERR_NULL
+    assert _code(lambda: B.gf_attn_decode_shared_residual(sess.ctx, params, dpool, *sh_args, hnd, 2, None, None, None,
+                                                          qd, od)) == B.GF_ERR_NULL
+    assert _code(lambda: B.gf_attn_decode_shared_residual(sess.ctx, params, dpool, *sh_args, hnd, -1, None, None, None,
+                                                          qd, od)) == B.GF_ERR_BAD_SHAPE
+    B.gf_attn_decode_shared_residual(sess.ctx, params, dpool, *sh_args, hnd, 0, None, None, None, qd, od)
+    t = W.make_tensors(wl)
+    qp = R.bits_to_device(t.q, sess.device)
+    qptr = torch.from_numpy(t.q_ptr).to(sess.device)
+    op = torch.zeros_like(qp)
+    nq, mq = int(qp.shape[0]), int(wl.batch.new_lens.max())
+    pre = lambda h, n, p=params: B.gf_attn_prefill_residual(sess.ctx, p, dpool, dt, h, n, None, None, None, qp, qptr, nq,
+                                                            mq, op)
+    assert _code(lambda: pre(None, 0)) == B.GF_ERR_NULL
+    assert _code(lambda: pre(hnd, 2)) == B.GF_ERR_NULL
+    assert _code(lambda: pre(hnd, -1)) == B.GF_ERR_BAD_SHAPE
+    assert _code(lambda: pre(hnd, 0, B.make_params(8, 2, 96))) == B.GF_ERR_UNSUPPORTED
+    pre(hnd, 0)
     assert _code(lambda: B.gf_set_decode_chunk_blocks(sess.ctx, 3)) == B.GF_ERR_BAD_SHAPE            # odd
     assert _code(lambda: B.gf_attn_prefill(sess.ctx, params, dpool, dt, qd, None, 5, 9, od)) == B.GF_ERR_BAD_SHAPE
     # residual on an e4m3 pool needs the block scales
@@ -73,6 +97,19 @@ def test_unsupported_shapes_and_bad_sizes_are_rejected():
         == B.GF_ERR_NULL
     assert _code(lambda: B.gf_kv_apply_residual(sess.ctx, params, pool.k, pool.v, pool.num_blocks, -1, z, z, z, z16,
                                                 z16)) == B.GF_ERR_BAD_SHAPE
+    # the packed residual form
+    m = torch.zeros((4, 64), dtype=torch.int32, device=sess.device)
+    z5 = torch.zeros(5, dtype=torch.int32, device=sess.device)
+    assert _code(lambda: B.gf_kv_residual_pack(sess.ctx, params, 1, z5, z16, z16, m, z16)) == B.GF_ERR_BAD_SHAPE  # in place
+    assert _code(lambda: B.gf_kv_residual_pack(sess.ctx, params, 1, z5, z16, z16, None, z16.clone())) == B.GF_ERR_NULL
+    assert _code(lambda: B.gf_kv_residual_pack(sess.ctx, params, -1, z5, z16, z16, m, z16.clone())) == B.GF_ERR_BAD_SHAPE
+    assert _code(lambda: B.gf_kv_residual_pack(sess.ctx, B.make_params(8, 2, 96), 1, z5, z16, z16, m, z16.clone())) \
+        == B.GF_ERR_UNSUPPORTED
+    assert _code(lambda: B.gf_kv_residual_unpack(sess.ctx, params, 1, z5, None, z16)) == B.GF_ERR_NULL
+    assert _code(lambda: B.gf_kv_apply_residual_packed(sess.ctx, fp8, pool.k, pool.v, pool.num_blocks, 1, z, z, z5, m,
+                                                       z16)) == B.GF_ERR_UNSUPPORTED
+    assert _code(lambda: B.gf_kv_apply_residual_packed(sess.ctx, params, pool.k, pool.v, pool.num_blocks, 1, z, z, z5,
+                                                       None, z16)) == B.GF_ERR_NULL
 
 
 def test_empty_batches_are_accepted_everywhere():
@@ -84,6 +121,9 @@ def test_empty_batches_are_accepted_everywhere():
     B.gf_attn_decode_residual(sess.ctx, params, dpool, empty, None, 0, None, None, None, None, None)
     B.gf_attn_decode_shared(sess.ctx, params, dpool, graph, None, None, 0, empty, None, None)
     B.gf_attn_prefill(sess.ctx, params, dpool, empty, None, None, 0, 0, None)
+    B.gf_attn_prefill_residual(sess.ctx, params, dpool, empty, None, 0, None, None, None, None, None, 0, 0, None)
+    B.gf_attn_decode_shared_residual(sess.ctx, params, dpool, graph, None, None, 0, empty, None, 0, None, None, None,
+                                     None, None)
     B.gf_kv_append(sess.ctx, params, pool.k, pool.v, None, None, pool.num_blocks, empty, None, None, None, 0, 0)
     B.gf_kv_apply_residual(sess.ctx, params, pool.k, pool.v, pool.num_blocks, 0, None, None, None, None, None)
     B.gf_resolve_path(sess.ctx, graph, 0, None, None, None, None, None, 0, pool.num_blocks, None, None, None, None,
