@@ -136,29 +136,55 @@ __global__ void shared_count_kernel(SharedPlan p, AttnArgs a) {
     p.row_slot[e] = chunks;            // scratch until the fill kernel writes the rows
 }
 
-// exclusive scan of f(i), i in [0, n), by one workgroup; out[n] = total.  Every thread sums a contiguous run
-// of the range, the run totals are scanned across the workgroup, and the thread walks its run again.
+// exclusive scan of f(i), i in [0, n), by one workgroup; out[n] = total.  Every wave takes a contiguous run of
+// whole 64-element tiles, lane l reading element l of a tile (consecutive lanes read consecutive words: a large
+// range -- the key space of a call with residuals -- would otherwise cost one cache line per element): a first
+// walk sums the run, the run totals give every wave its offset, a second walk scans tile by tile with a carry.
+// Four tiles are fetched before the first is used (out may alias what f reads, so the compiler cannot batch
+// the loads by itself).
 template <class F>
 __device__ void block_exscan(int n, F f, int32_t *out, int32_t *sh) {
-    const int tid = threadIdx.x;
-    const int per = (n + kScanThreads - 1) / kScanThreads;
-    const int i0 = min(tid * per, n), i1 = min(i0 + per, n);
+    constexpr int kWaves = kScanThreads / 64, kBatch = 4;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int seg = ((n + kWaves - 1) / kWaves + 63) & ~63;
+    const int w0 = min(wave * seg, n), w1 = min(w0 + seg, n);
     int sum = 0;
-    for (int i = i0; i < i1; ++i) sum += f(i);
-    sh[tid] = sum;
+    for (int t0 = w0; t0 < w1; t0 += 64 * kBatch) {
+        int v[kBatch];
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) v[j] = t0 + 64 * j + lane < w1 ? f(t0 + 64 * j + lane) : 0;
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) sum += v[j];
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) sum += __shfl_xor(sum, o, 64);
+    if (lane == 0) sh[wave] = sum;
     __syncthreads();
-    for (int o = 1; o < kScanThreads; o <<= 1) {
-        const int y = tid >= o ? sh[tid - o] : 0;
-        __syncthreads();
-        sh[tid] += y;
-        __syncthreads();
+    int carry = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < kWaves; ++w) {
+        const int x = sh[w];
+        carry += w < wave ? x : 0;
+        total += x;
     }
-    int run = sh[tid] - sum;
-    for (int i = i0; i < i1; ++i) {
-        out[i] = run;
-        run += f(i);
+    for (int t0 = w0; t0 < w1; t0 += 64 * kBatch) {
+        int v[kBatch];
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) v[j] = t0 + 64 * j + lane < w1 ? f(t0 + 64 * j + lane) : 0;
+#pragma unroll
+        for (int j = 0; j < kBatch; ++j) {
+            int incl = v[j];
+#pragma unroll
+            for (int o = 1; o < 64; o <<= 1) {
+                const int y = __shfl_up(incl, o, 64);
+                if (lane >= o) incl += y;
+            }
+            if (t0 + 64 * j + lane < w1) out[t0 + 64 * j + lane] = carry + incl - v[j];
+            carry += __shfl(incl, 63, 64);
+        }
     }
-    if (tid == kScanThreads - 1) out[n] = sh[tid];
+    __syncthreads();
+    if (tid == 0) out[n] = total;
     __syncthreads();
 }
 
