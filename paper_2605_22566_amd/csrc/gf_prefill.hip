@@ -28,11 +28,12 @@
 // Pipeline.  Inside a wave the scores run one tile ahead of the softmax: iteration t issues, as
 // one straight-line stream of slots, the score MFMAs of tile t+1 and the P*V MFMAs of tile t, and
 // in the shadow of every MFMA a fixed share of the vector work (exponentials, row sums and bf16
-// packing of tile t; running maximum of tile t+1), the LDS operand fetches (grouped, one wait per
-// group), the direct loads of K(t+2) and V(t+1), and -- three quarters into the stream -- the wait
-// for those loads and the one workgroup barrier of the iteration; the first fragments of the
-// next iteration are fetched behind that barrier.  The slot schedule is fixed at compile time
-// (static_for / if constexpr) and pinned with scheduling barriers.
+// packing of tile t; running maximum of tile t+1) and the LDS operand fetches (grouped, one wait per
+// group).  Three quarters into the stream comes the wait for this wave's direct loads -- K(t+2) and
+// V(t+1), issued a whole iteration earlier -- and the one workgroup barrier of the iteration; right
+// behind it the direct loads of K(t+3) and V(t+2) are issued, into the buffers every wave has left by
+// then, and the first fragments of the next iteration are fetched.  The slot schedule is fixed at
+// compile time (static_for / if constexpr) and pinned with scheduling barriers.
 // The reference row maximum is refreshed (and O rescaled) only when some row's new maximum
 // exceeds it by more than 2^8; the final normalisation uses the same reference, so the result is
 // unchanged.  Per-entry token counts mask partial blocks anywhere in the sequence and tail entries
@@ -522,6 +523,11 @@ __global__ __launch_bounds__(NW * 64, RS == 1 ? 2 : 1) void prefill_kernel(
 #pragma unroll
         for (int rs = 0; rs < RS; ++rs) mx[rs] = row_max(s_a[rs], t0);
     }
+    // Every wave is done with K(0) before its buffer is staged again; from here on the loads of an iteration
+    // are issued right behind the barrier of the iteration before (K(2) and V(1) are the ones "iteration -1" owes).
+    __syncthreads();
+    if (ntiles > 2) issue_k(2, 0);
+    if (ntiles > 1) issue_v(1, 1 % C::kVBufs);
 
     // The reference maxima are refreshed (and O, l rescaled) only when some row's pending maximum
     // outgrew its reference by more than the slack: a cold path.
@@ -565,6 +571,7 @@ __global__ __launch_bounds__(NW * 64, RS == 1 ? 2 : 1) void prefill_kernel(
     auto body = [&](int t, f32x16 (&sc)[RS][2], f32x16 (&sn)[RS][2]) {
         const bool has_next = t + 1 < ntiles;
         const bool k2 = t + 2 < ntiles;
+        const bool k3 = t + 3 < ntiles;
         // operand stream of this iteration: the K fragments of tile t+1, then the V fragments of tile t,
         // fetched from LDS kAhead fragments ahead of their use;
         // every fragment feeds one MFMA per row set
@@ -572,19 +579,21 @@ __global__ __launch_bounds__(NW * 64, RS == 1 ? 2 : 1) void prefill_kernel(
         constexpr bool kHand = RS > 1;
         constexpr int kLdsPerFrag = 1;               // LDS operations per fragment
         // Pipeline of one iteration (slots of the MFMA stream):
-        //   kStageKSlot..  direct loads of K(t+2), one per slot, into the buffer K(t) left (its readers
-        //                  passed the barrier of the iteration before)
-        //   kStageVSlot..  direct loads of V(t+1) into the buffer V(t-2) left: V(t-1) may still be read
-        //                  by a wave that is behind this one's last barrier, hence three V buffers
-        //   kSyncSlot      wait for this wave's loads, workgroup barrier: K(t+2) and V(t+1) are published;
+        //   kSyncSlot      wait for this wave's loads -- K(t+2) and V(t+1), issued behind the barrier of the
+        //                  iteration before, a whole iteration ago -- and workgroup barrier: they are published;
         //                  it comes after the last read of K(t+1) and before the first read of K(t+2)
+        //   kStageKSlot..  behind that barrier: direct loads of K(t+3), one per slot, into the buffer K(t+1)
+        //                  left (every wave has passed its last read of it)
+        //   kStageVSlot..  direct loads of V(t+2) into the buffer V(t-1) left (read in the iteration before, which
+        //                  every wave has left); V(t) may still be read by a wave that is behind this barrier and
+        //                  V(t+1) has just landed, hence three V buffers
         //   from fragment kFirstNext on, the fetches are those of the next iteration's first fragments
-        constexpr int kStageKSlot = RS, kStageVSlot = RS * (1 + C::kDmaPerWave);
         constexpr int kFirstNext = C::kFrags - kAhead;
         constexpr int kSyncSlot = RS * (C::kQK + C::kPV / 2 < kFirstNext ? C::kQK + C::kPV / 2 : kFirstNext);
+        constexpr int kStageKSlot = kSyncSlot, kStageVSlot = kSyncSlot + RS * C::kDmaPerWave;
         static_assert(C::kFrags % kRing == 0 && kAhead <= C::kQK, "the ring position of a fragment is the same in every iteration");
         static_assert(kSyncSlot >= RS * C::kQK && kSyncSlot <= RS * kFirstNext, "barrier between the K reads");
-        static_assert(kStageVSlot + RS * C::kDmaPerWave <= kSyncSlot, "loads issued before the wait");
+        static_assert(kStageVSlot + RS * C::kDmaPerWave <= NSLOT, "loads issued inside the iteration");
         static_assert(C::kFrags % kFetch == 0, "whole wait groups");
         const char *kb = kbuf + ((t + 1) & 1) * C::kKTile;
         const char *vb = vbuf + (t % C::kVBufs) * C::kVTile + v_lane_off;
@@ -696,15 +705,15 @@ __global__ __launch_bounds__(NW * 64, RS == 1 ? 2 : 1) void prefill_kernel(
             // staging for the coming iterations rides in early slots, one direct load per slot
             if constexpr (i >= kStageKSlot && i < kStageKSlot + RS * C::kDmaPerWave && (i - kStageKSlot) % RS == 0) {
                 constexpr int j = (i - kStageKSlot) / RS;
-                if constexpr (j == 0) stage_src = block_of(a.k, t + 2);
-                if (k2)                                               // K(t+2) replaces K(t)
-                    dma_load<j>(stage_src, k_off[j], kbuf + (t & 1) * C::kKTile + wave * C::kDmaPerWave * 1024);
+                if constexpr (j == 0) stage_src = block_of(a.k, t + 3);
+                if (k3)                                               // K(t+3) replaces K(t+1)
+                    dma_load<j>(stage_src, k_off[j], kbuf + ((t + 1) & 1) * C::kKTile + wave * C::kDmaPerWave * 1024);
             }
             if constexpr (i >= kStageVSlot && i < kStageVSlot + RS * C::kDmaPerWave && (i - kStageVSlot) % RS == 0) {
                 constexpr int j = (i - kStageVSlot) / RS;
-                if constexpr (j == 0) stage_src = block_of(a.v, t + 1);
-                if (has_next)                                         // V(t+1) replaces V(t-2)
-                    dma_load<j>(stage_src, v_off[j], vbuf + ((t + 1) % C::kVBufs) * C::kVTile + wave * C::kDmaPerWave * 1024);
+                if constexpr (j == 0) stage_src = block_of(a.v, t + 2);
+                if (k2)                                               // V(t+2) replaces V(t-1)
+                    dma_load<j>(stage_src, v_off[j], vbuf + ((t + 2) % C::kVBufs) * C::kVTile + wave * C::kDmaPerWave * 1024);
             }
             // vector share of every slot: the exponentials of tile t are spread evenly over the
             // slots up to kExpEnd.  An exponential joins the row sum one step later (its consumer
