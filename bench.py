@@ -416,6 +416,42 @@ def measure_shared_residual(job, m, density=(0.25, 0.30), iters=10):
             "max_abs_diff_to_per_request_read_time": float((o.float() - o_req.float()).abs().max().item())}
 
 
+def measure_zero_data(torch, R, W, name="prefill_8b", iters=20):
+    """The prefill kernel on the same workload with the operands' values changed and nothing else: same launch,
+    same instruction stream, same tables and traffic.  What changes is what the MFMA and vector units draw, and
+    with it the clock the chip holds: the time on zeroed K/V is what this instruction stream costs when the chip
+    is not limited by power."""
+    job = Job(name, torch, R, W, decode_after_prefill=False)
+    if not job.has_prefill:
+        return None
+
+    def timed():
+        for _ in range(5):
+            job.prefill()
+        torch.cuda.synchronize()
+        return _event_ms(job.prefill, torch, iters)
+
+    out = {"kernel": "prefill_kernel", "workload": name, "kernel_ms_random": timed()}
+    k, v = job.pool.k.clone(), job.pool.v.clone()
+    job.pool.k.zero_()
+    job.pool.v.zero_()
+    out["kernel_ms_zero_kv"] = timed()
+    q = job.q.clone()
+    job.q.zero_()
+    out["kernel_ms_zero_kv_and_q"] = timed()
+    job.pool.k.copy_(k)
+    job.pool.v.copy_(v)
+    job.q.copy_(q)
+    out["kernel_ms_random_again"] = timed()
+    flops = job.prefill_flops()
+    out["tflops_random"] = flops / (out["kernel_ms_random"] * 1e-3) / 1e12
+    out["tflops_zero_kv"] = flops / (out["kernel_ms_zero_kv"] * 1e-3) / 1e12
+    out["frac_of_mfma_peak_zero_kv"] = out["tflops_zero_kv"] / PEAK_MFMA_BF16_TFLOPS
+    out["random_over_zero_kv"] = out["kernel_ms_random"] / out["kernel_ms_zero_kv"]
+    del job
+    return out
+
+
 def measure_stream_copy(torch, iters=10):
     """What a plain device-to-device copy of 1 GiB reaches on this machine (bytes read + bytes written
     per second): the practical streaming ceiling next to the 8 TB/s on paper."""
@@ -656,7 +692,7 @@ def main():
                              "decode_8b_private_seq"])
     ap.add_argument("--decode-chunk", type=int, default=0,
                     help="table entries per split-KV chunk of the decode kernels (0 = the library's choice)")
-    ap.add_argument("--extra", default="decode_8b,decode_70b,mixed_fp8,decode_8b_private,decode_8b_private_seq,kv_residual,stream",
+    ap.add_argument("--extra", default="decode_8b,decode_70b,mixed_fp8,decode_8b_private,decode_8b_private_seq,kv_residual,stream,zero_data",
                     help="comma list of further workloads reported under 'extra' (the five configs, decode_8b_private = "
                          "config 3 with nothing shared, decode_8b_private_seq = the same with an unshuffled pool, "
                          "kv_residual, stream = the box's read-only and copy rates)")
@@ -666,6 +702,9 @@ def main():
                     help="decode_residual: share of every request's table entries (its last ones) that carry a residual")
     ap.add_argument("--residual-density", default="0.25,0.30",
                     help="decode_residual: share of the K,V elements of such an entry that the residual names (> 0)")
+    ap.add_argument("--kv-data", choices=("random", "zeros"), default="random",
+                    help="zeros: the K/V pool is cleared before the timed region -- a measurement aid (same kernel, "
+                         "same instruction stream and traffic, operands that draw less power), never the metric")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-budget", type=float, default=20.0)
     ap.add_argument("--copy-calibration", action="store_true",
@@ -696,6 +735,10 @@ def main():
         torch.cuda.empty_cache()
 
     job = Job(args.workload, torch, R, W)
+    if args.kv_data == "zeros":
+        job.pool.k.zero_()
+        job.pool.v.zero_()
+        args.no_cpu_baseline = True          # the oracle sample would be checked against other data
     if args.decode_chunk:
         B.gf_set_decode_chunk_blocks(job.sess.ctx, args.decode_chunk)
     m = measure(job, args.steps, args.warmup)
@@ -714,7 +757,7 @@ def main():
         "metric": metric, "value": value, "unit": unit, "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": m["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if wl.shape.kv_dtype == W.KV_BF16 else "fp8_e4m3 KV / bf16 Q, fp32 accumulate",
-        "data": "synthetic",
+        "data": "synthetic" if args.kv_data == "random" else "synthetic, K/V pool zeroed (measurement aid, not the metric)",
         "config": {"workload": args.workload, "requests": wl.batch.num_req, "q_heads": wl.shape.num_q_heads,
                    "kv_heads": wl.shape.num_kv_heads, "head_dim": wl.shape.head_dim, "block": 16,
                    "nodes": wl.graph.num_nodes, "pool_blocks": wl.num_pool_blocks,
@@ -749,6 +792,12 @@ def main():
     del job
     torch.cuda.empty_cache()
     names = [x for x in args.extra.split(",") if x and x != args.workload]
+    if "zero_data" in names:
+        names.remove("zero_data")
+        zd = measure_zero_data(torch, R, W)
+        if zd is not None:
+            extra["prefill_zero_data"] = zd
+        torch.cuda.empty_cache()
     if "stream" in names:
         names.remove("stream")
         extra["stream_read"] = measure_stream_read(torch, R, W)
