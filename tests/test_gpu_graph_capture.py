@@ -1,5 +1,5 @@
 """The calls can be recorded into a HIP graph once a warm-up call has sized the context's buffers (no call
-allocates or synchronises after that): a captured resolve -> prefill -> decode (per request, per node, with read-time residuals) sequence, replayed
+allocates or synchronises after that): a captured resolve -> prefill -> decode (per request, per node, and the three residual-reading calls) sequence, replayed
 several times with inputs changed in place and eager work in between, gives the eager result bit for bit."""
 import numpy as np
 import pytest
@@ -29,7 +29,8 @@ def test_captured_sequence_replays_like_eager(shape):
     total_q, max_q = int(q.shape[0]), int(wl.batch.new_lens.max())
     o = torch.zeros_like(q)
     qd = q[last].contiguous()
-    od, ods, odr = torch.zeros_like(qd), torch.zeros_like(qd), torch.zeros_like(qd)
+    od, ods, odr, odsr = (torch.zeros_like(qd) for _ in range(4))
+    opr = torch.zeros_like(q)
     # bf16 pools: the read-time residual step too (the first two table entries of every request carry an item)
     bf16 = shape.kv_dtype == W.KV_BF16
     handles = torch.full((wl.batch.num_req, max_blocks_of(wl)), -1, dtype=torch.int32, device=dev)
@@ -43,6 +44,8 @@ def test_captured_sequence_replays_like_eager(shape):
         sess.decode_shared(pool, db, tables, qd, ods)
         if bf16:
             sess.decode_residual(pool, tables, handles, dres, qd, odr)
+            sess.prefill_residual(pool, tables, handles, dres, q, q_ptr, total_q, max_q, opr)
+            sess.decode_shared_residual(pool, db, tables, handles, dres, qd, odsr)
 
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
@@ -57,19 +60,21 @@ def test_captured_sequence_replays_like_eager(shape):
     for rep in range(3):
         q.mul_(-0.5 if rep == 1 else 1.5)               # new inputs in the same buffers
         qd.copy_(q[last])
-        for buf in (o, od, ods, odr):
+        bufs = (o, od, ods, odr, opr, odsr)
+        for buf in bufs:
             buf.fill_(float("nan"))
         graph.replay()
         torch.cuda.synchronize()
-        got = [x.clone() for x in (o, od, ods, odr)]
-        for buf in (o, od, ods, odr):
+        got = [x.clone() for x in bufs]
+        for buf in bufs:
             buf.fill_(float("nan"))
         sequence()                                      # the program's own eager work between replays
         torch.cuda.synchronize()
-        for name, g, e in zip(("prefill", "decode", "decode_shared", "decode_residual"), got, (o, od, ods, odr)):
-            if name == "decode_residual" and not bf16:
+        names = ("prefill", "decode", "decode_shared", "decode_residual", "prefill_residual", "decode_shared_residual")
+        for name, g, e in zip(names, got, bufs):
+            if name.endswith("residual") and not bf16:
                 continue
             assert torch.equal(g, e), f"{name}, replay {rep}"
             assert torch.isfinite(e.float()).all()
         if bf16:
-            assert not torch.equal(odr, od)             # the residuals are seen
+            assert not torch.equal(odr, od) and not torch.equal(opr, o)      # the residuals are seen
