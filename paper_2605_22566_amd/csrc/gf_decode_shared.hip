@@ -14,7 +14,8 @@
 // order, then tail -- with the log-sum-exp rule.  The result is the request-centric one up to
 // fp32 summation order.
 //
-// Integer preparation (all on the device, no host round trip):
+// Integer preparation (all on the device, no host round trip; "node" below reads "list key" when residual
+// handles are given, see the next paragraph):
 //   count   per path entry: cnt[node] (atomics) and the entry's number of chunks
 //   scan    one workgroup: node_ptr = scan(cnt); item_ptr = scan(chunks * column quads per node);
 //           entry_slot = scan(chunks per path entry): the partial slots of a request's nodes are
