@@ -24,7 +24,8 @@
  *     in the device array status[] (GF_ST_*), not through the return value.
  *   - The library owns only a gf_ctx: device scratch memory (the split-KV
  *     partials of gf_attn_decode, the work list of gf_attn_prefill, the lists and
- *     partials of gf_attn_decode_shared / gf_decode_shared_plan), grown on
+ *     partials of gf_attn_decode_shared / gf_decode_shared_plan; their
+ *     residual-reading forms use the same buffers), grown on
  *     demand -- these calls may therefore call hipMalloc, and hipFree after a
  *     stream synchronisation when it outgrows what it has -- and released by
  *     gf_destroy.  A gf_ctx must not be used from two streams at once.  Once a
