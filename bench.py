@@ -495,6 +495,44 @@ def measure_stream_read(torch, R, W, iters=10, gib=2):
     return best
 
 
+def measure_stream_tiles(torch, R, W, iters=10, gib=4):
+    """The read-only ceiling for the access pattern of a block table (gf_hbm_tile_probe): a 4 GiB buffer read once
+    as tiles in a random order -- 4 KB tiles (one (block, kv head) image of K or V at head_dim 128, what a wave of
+    the decode kernels requests at a time), 32 KB tiles (all kv heads of a block) and, for comparison, the same
+    tiles in rising order."""
+    from paper_2605_22566_amd import binding as B
+    dev = torch.device("cuda:0")
+    sess = R.Session(W.small_layered(1, W.Shape(8, 2, 128), num_req=1), dev)
+    nbytes = gib << 30
+    src = torch.ones(nbytes // 2, dtype=torch.bfloat16, device=dev)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(7)
+    out = {"kernel": "hbm_tile_probe_kernel", "bytes": nbytes, "runs": []}
+    for tile, order in ((4096, "random"), (32768, "random"), (4096, "rising")):
+        n = nbytes // tile
+        ids = (torch.randperm(n, generator=gen, device=dev) if order == "random"
+               else torch.arange(n, device=dev)).to(torch.int32)
+        best = None
+        for num_wg in (4096, 8192, 16384):
+            sums = torch.zeros(num_wg, dtype=torch.int32, device=dev)
+            fn = lambda: B.gf_hbm_tile_probe(sess.ctx, src, tile, n, ids, n, sums, num_wg)
+            for _ in range(2):
+                fn()
+            torch.cuda.synchronize()
+            ms = _event_ms(fn, torch, iters)
+            got = int(sums.to(torch.int64).sum().item()) & 0xffffffff
+            ent = {"tile_bytes": tile, "order": order, "workgroups": num_wg, "kernel_ms": ms,
+                   "gbs_read": nbytes / (ms * 1e-3) / 1e9, "frac_of_hbm_peak": nbytes / (ms * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                   "every_word_summed": got == ((nbytes // 4) * 0x3f803f80) & 0xffffffff}
+            if best is None or ent["gbs_read"] > best["gbs_read"]:
+                best = ent
+        out["runs"].append(best)
+        del ids
+    del src
+    torch.cuda.empty_cache()
+    return out
+
+
 def measure_residual(torch, R, W, num_items=8192, iters=20):
     """gf_kv_apply_residual on the 8B head shape: num_items pool blocks reconstructed from base
     blocks and residuals of the density the paper reports (25 % of K, 30 % of V elements)."""
@@ -801,6 +839,7 @@ def main():
     if "stream" in names:
         names.remove("stream")
         extra["stream_read"] = measure_stream_read(torch, R, W)
+        extra["stream_tiles"] = measure_stream_tiles(torch, R, W)
         extra["stream_copy"] = measure_stream_copy(torch)
     if "kv_residual" in names:
         names.remove("kv_residual")

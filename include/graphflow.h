@@ -628,6 +628,16 @@ int32_t gf_attn_decode_shared_planned(gf_ctx *ctx, const gf_attn_params *params,
 int32_t gf_hbm_read_probe(gf_ctx *ctx, const void *src, int64_t bytes, uint32_t *wg_sums, int32_t num_wg,
                           void *stream);
 
+/*
+ * gf_hbm_tile_probe -- measurement aid, no part of the method: the read-only ceiling for the access pattern of
+ * a block table.  The buffer at `src` (device) holds num_src_tiles tiles of tile_bytes bytes (a multiple of
+ * 1024, at most 1 MiB); tile_ids[num_tiles] (device) gives the order in which tiles are read (an id outside the
+ * buffer is folded into it), one wave per tile, 16 bytes per lane and load; wg_sums[num_wg] as above.
+ */
+int32_t gf_hbm_tile_probe(gf_ctx *ctx, const void *src, int32_t tile_bytes, int32_t num_src_tiles,
+                          const int32_t *tile_ids, int64_t num_tiles, uint32_t *wg_sums, int32_t num_wg,
+                          void *stream);
+
 /* Tuning knob (host): table entries (16-token blocks) per split-KV chunk in
  * gf_attn_decode and gf_attn_decode_residual (built-in choice 64) and gf_attn_decode_shared (built-in choice and upper limit 64);
  * 0 restores the built-in choice.  Must be even. */

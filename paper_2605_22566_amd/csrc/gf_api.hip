@@ -333,6 +333,21 @@ int32_t gf_attn_prefill_noalloc(gf_ctx *ctx, const gf_attn_params *params, const
     return GF_OK;
 }
 
+int32_t gf_hbm_tile_probe(gf_ctx *ctx, const void *src, int32_t tile_bytes, int32_t num_src_tiles,
+                          const int32_t *tile_ids, int64_t num_tiles, uint32_t *wg_sums, int32_t num_wg,
+                          void *stream) {
+    if (!ctx) return GF_ERR_NULL;
+    if (tile_bytes <= 0 || (tile_bytes & 1023) || tile_bytes > (1 << 20) || num_src_tiles <= 0 || num_tiles < 0 ||
+        num_wg < 0)
+        return GF_ERR_BAD_SHAPE;
+    if (num_wg == 0) return GF_OK;
+    if (!wg_sums || (num_tiles > 0 && (!src || !tile_ids))) return GF_ERR_NULL;
+    hipError_t e = gf::launch_hbm_tile_probe(src, tile_bytes, num_src_tiles, tile_ids, num_tiles, wg_sums, num_wg,
+                                             (hipStream_t)stream);
+    if (e != hipSuccess) return fail_hip(ctx, e, "gf_hbm_tile_probe launch");
+    return GF_OK;
+}
+
 int32_t gf_hbm_read_probe(gf_ctx *ctx, const void *src, int64_t bytes, uint32_t *wg_sums, int32_t num_wg,
                           void *stream) {
     if (!ctx) return GF_ERR_NULL;

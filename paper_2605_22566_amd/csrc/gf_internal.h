@@ -62,6 +62,8 @@ int32_t *prefill_static_plan(int device);
 
 // read-only streaming probe (bandwidth ceiling): bytes a multiple of 16, one sum per workgroup
 hipError_t launch_hbm_read_probe(const void *src, size_t bytes, uint32_t *wg_sums, int32_t num_wg, hipStream_t s);
+hipError_t launch_hbm_tile_probe(const void *src, int32_t tile_bytes, int32_t num_src_tiles, const int32_t *ids,
+                                 int64_t num_tiles, uint32_t *wg_sums, int32_t num_wg, hipStream_t s);
 
 // built-in split-KV chunk sizes (table entries per work item) of gf_attn_decode and gf_attn_decode_residual
 constexpr int32_t kDecodeChunkBlocks = 64, kDecodeChunkBlocksResidual = 64;   // equal: the two calls are interchangeable bit for bit

@@ -36,6 +36,57 @@ __global__ __launch_bounds__(kProbeThreads) void hbm_read_probe_kernel(const u32
     }
 }
 
+// The same ceiling for the access pattern of a block table: the buffer is read as tiles of `tile_bytes`
+// contiguous bytes (a multiple of 1 KB; 4 KB is one (block, kv head) image of K or V at head_dim 128) in the order
+// an index array gives.  One wave takes a tile at a time, 16 bytes per lane and load, two tiles in flight; ids
+// outside [0, num_src_tiles) are folded into the range, so every access stays inside the buffer.
+__global__ __launch_bounds__(kProbeThreads) void hbm_tile_probe_kernel(const char *__restrict__ src, int tile_bytes,
+                                                                      int num_src_tiles, const int32_t *__restrict__ ids,
+                                                                      long num_tiles, uint32_t *__restrict__ wg_sums) {
+    const int lane = threadIdx.x & 63;
+    const long wave = (long)blockIdx.x * (kProbeThreads / 64) + (threadIdx.x >> 6);
+    const long waves = (long)gridDim.x * (kProbeThreads / 64);
+    const int loads = tile_bytes / 1024;
+    uint32_t acc = 0;
+    auto tile_of = [&](long i) -> const u32x4 * {
+        const int t = (int)((uint32_t)ids[i] % (uint32_t)num_src_tiles);
+        return (const u32x4 *)(src + (size_t)t * tile_bytes) + lane;
+    };
+    long i = wave;
+    for (; i + waves < num_tiles; i += 2 * waves) {
+        const u32x4 *pa = tile_of(i), *pb = tile_of(i + waves);
+        for (int j = 0; j < loads; ++j) {
+            const u32x4 a = __builtin_nontemporal_load(pa + 64 * j), b = __builtin_nontemporal_load(pb + 64 * j);
+            acc += (a[0] + a[1]) + (a[2] + a[3]) + (b[0] + b[1]) + (b[2] + b[3]);
+        }
+    }
+    for (; i < num_tiles; i += waves) {
+        const u32x4 *pa = tile_of(i);
+        for (int j = 0; j < loads; ++j) {
+            const u32x4 a = __builtin_nontemporal_load(pa + 64 * j);
+            acc += (a[0] + a[1]) + (a[2] + a[3]);
+        }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
+    __shared__ uint32_t part[kProbeThreads / 64];
+    if (lane == 0) part[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t t = 0;
+#pragma unroll
+        for (int w = 0; w < kProbeThreads / 64; ++w) t += part[w];
+        wg_sums[blockIdx.x] = t;
+    }
+}
+
+hipError_t launch_hbm_tile_probe(const void *src, int32_t tile_bytes, int32_t num_src_tiles, const int32_t *ids,
+                                 int64_t num_tiles, uint32_t *wg_sums, int32_t num_wg, hipStream_t s) {
+    hipLaunchKernelGGL(hbm_tile_probe_kernel, dim3((unsigned)num_wg), dim3(kProbeThreads), 0, s, (const char *)src,
+                       tile_bytes, num_src_tiles, ids, (long)num_tiles, wg_sums);
+    return hipGetLastError();
+}
+
 hipError_t launch_hbm_read_probe(const void *src, size_t bytes, uint32_t *wg_sums, int32_t num_wg, hipStream_t s) {
     hipLaunchKernelGGL(hbm_read_probe_kernel, dim3((unsigned)num_wg), dim3(kProbeThreads), 0, s, (const u32x4 *)src,
                        bytes / 16, wg_sums);
