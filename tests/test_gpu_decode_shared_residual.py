@@ -159,3 +159,34 @@ def test_e4m3_pool_is_refused():
         sess.decode_shared_residual(pool, sess.upload_batch(wl.batch), tables, dh, sess.upload_residuals(empty), qd, o,
                                     lse)
     assert ei.value.code == B.GF_ERR_UNSUPPORTED
+
+
+def test_arbitrary_handles_stay_in_bounds_and_give_finite_rows():
+    """Handles that follow no rule at all (any value from below -1 to beyond the CSR, per table entry; nodes that
+    claim each other's items): every read stays inside the CSR and the pool, every output row is finite and inside
+    the hull of what base + residual values can reach -- for the node-centric call and for the two per-request
+    ones."""
+    shape = W.Shape(8, 2, 128)
+    wl, wl2, t, res, k2, v2, inst_tab, handles = _case(shape, 85, num_req=16)
+    rng = np.random.default_rng(85)
+    wild = rng.integers(-3, res.num_items + 3, handles.shape).astype(np.int32)
+    sess, tables = run_resolve(wl)
+    pool = R.DevicePool.from_host(t, sess.device)
+    dres = sess.upload_residuals(res)
+    dh = torch.from_numpy(wild).to(sess.device)
+    last, qd, o, lse = _queries(sess, t)
+    sess.decode_shared_residual(pool, sess.upload_batch(wl.batch), tables, dh, dres, qd, o, lse)
+    o2 = torch.full_like(o, float("nan"))
+    sess.decode_residual(pool, tables, dh, dres, qd, o2)
+    q = R.bits_to_device(t.q, sess.device)
+    op = torch.full(q.shape, float("nan"), dtype=torch.bfloat16, device=sess.device)
+    sess.prefill_residual(pool, tables, dh, dres, q, torch.from_numpy(t.q_ptr).to(sess.device), int(q.shape[0]),
+                          int(wl.batch.new_lens.max()), op)
+    torch.cuda.synchronize()
+    from oracle import residual as OR
+    vmax = float(np.abs(OR.bf16_bits_to_f32(t.v_pool)).max())
+    dmax = float(np.abs(OR.bf16_bits_to_f32(res.res_val)).max()) if res.res_val.size else 0.0
+    for out in (o, o2, op):
+        x = out.float()
+        assert bool(torch.isfinite(x).all())
+        assert float(x.abs().max()) <= (vmax + dmax) * 1.01 + 1e-2
