@@ -387,9 +387,11 @@ def measure_prefill_residual(job, prefill_ms, shares=(0.25, 1.0), density=(0.25,
 
 def measure_shared_residual(job, m, density=(0.25, 0.30), iters=10):
     """gf_attn_decode_shared_residual on the decode step with one stored residual per (prefix path, node) pair of
-    the batch -- the paper's regime: every node beyond the first of a path is read as base + the residual of its
-    pair, requests that reach a node through the same prefix share one read of it -- beside the per-request
-    read-time form on the same handles and the plain node-centric step.  bf16 pools."""
+    the batch, beside the per-request read-time form on the same handles and the plain node-centric step.  Two
+    regimes: every pair keeps its residual (every node beyond the first of a path is read as base + residual;
+    requests that reach a node through the same prefix share one read of it), and only the pairs that at least two
+    requests of the batch walk keep one (what Effective Path Pruning leaves stored; the others read the node as it
+    is, standing in for the dense blocks an on-the-fly fallback leaves).  bf16 pools."""
     torch, R, W = job.torch, job.R, job.W
     sh = job.wl.shape
     if sh.kv_dtype != W.KV_BF16 or not job.has_decode:
@@ -397,23 +399,29 @@ def measure_shared_residual(job, m, density=(0.25, 0.30), iters=10):
     lo, hi = job._shared_args()
     t = job._shared_tables
     dev = job.qd.device
-    handles_h, num_items, pairs, uses = W.prefix_pair_handles(job.wl, lo, hi, job.max_blocks)
-    handles = torch.from_numpy(handles_h).to(dev)
-    dres, nnz = R.random_residuals(sh, num_items, dev, density_k=density[0], density_v=density[1])
-    o = torch.zeros_like(job.od[lo:hi])
-    o_req = torch.zeros_like(o)
-    fn = lambda: job.sess.decode_shared_residual(job.pool, job._shared_db, t, handles, dres, job.qd[lo:hi], o)
-    fn_req = lambda: job.sess.decode_residual(job.pool, t, handles, dres, job.qd[lo:hi], o_req)
-    for f in (fn, fn_req):
-        f()
-    torch.cuda.synchronize()
-    ms, ms_req = _event_ms(fn, torch, iters), _event_ms(fn_req, torch, iters)
-    return {"kernel": "shared_attn_kernel<RES>(+list building, merge)", "kernel_ms": ms,
-            "per_request_read_time_ms": ms_req, "speedup_over_per_request_read_time": ms_req / ms,
-            "plain_node_centric_ms": m["decode_shared_ms"], "prefix_node_pairs": pairs, "request_node_uses": uses,
-            "residual_items": num_items, "residual_entries": nnz, "density_k_v": list(density),
-            "sparse_residual_bytes": 4.0 * nnz,
-            "max_abs_diff_to_per_request_read_time": float((o.float() - o_req.float()).abs().max().item())}
+    out = {"kernel": "shared_attn_kernel<RES>(+list building, merge)", "plain_node_centric_ms": m["decode_shared_ms"],
+           "density_k_v": list(density), "runs": []}
+    for regime, min_uses in (("every pair", 1), ("pairs walked by two requests or more", 2)):
+        handles_h, num_items, pairs, uses = W.prefix_pair_handles(job.wl, lo, hi, job.max_blocks, min_uses=min_uses)
+        handles = torch.from_numpy(handles_h).to(dev)
+        dres, nnz = R.random_residuals(sh, num_items, dev, density_k=density[0], density_v=density[1])
+        o = torch.zeros_like(job.od[lo:hi])
+        o_req = torch.zeros_like(o)
+        fn = lambda: job.sess.decode_shared_residual(job.pool, job._shared_db, t, handles, dres, job.qd[lo:hi], o)
+        fn_req = lambda: job.sess.decode_residual(job.pool, t, handles, dres, job.qd[lo:hi], o_req)
+        for f in (fn, fn_req):
+            f()
+        torch.cuda.synchronize()
+        ms, ms_req = _event_ms(fn, torch, iters), _event_ms(fn_req, torch, iters)
+        out["runs"].append({"pairs_with_residual": regime, "kernel_ms": ms, "per_request_read_time_ms": ms_req,
+                            "speedup_over_per_request_read_time": ms_req / ms, "prefix_node_pairs": pairs,
+                            "request_node_uses": uses, "residual_items": num_items, "residual_entries": nnz,
+                            "sparse_residual_bytes": 4.0 * nnz,
+                            "max_abs_diff_to_per_request_read_time":
+                                float((o.float() - o_req.float()).abs().max().item())})
+        del dres, handles
+        torch.cuda.empty_cache()
+    return out
 
 
 def measure_zero_data(torch, R, W, name="prefill_8b", iters=20):

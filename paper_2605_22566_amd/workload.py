@@ -576,23 +576,33 @@ def residual_handles(base_table: np.ndarray, inst_table: np.ndarray, res: Residu
     return h
 
 
-def prefix_pair_handles(wl: Workload, req_lo: int, req_hi: int, max_blocks: int, depth: int = 1 << 30) -> tuple:
+def prefix_pair_handles(wl: Workload, req_lo: int, req_hi: int, max_blocks: int, depth: int = 1 << 30,
+                        min_uses: int = 1) -> tuple:
     """Residual handles for requests [req_lo, req_hi) with one stored residual per (prefix path, node) pair -- the
     paper's KV(P, v): every node of a path beyond the first (at most the last ``depth`` of them) reads the
     residual of its pair; pairs are numbered as they are met and a pair's items (one per block of its node) are
-    consecutive.  Returns (handles int32 [req_hi - req_lo, max_blocks], number of items, number of pairs,
-    number of (request, node) uses of a pair)."""
+    consecutive.  With ``min_uses`` > 1 only the pairs that at least so many of these requests walk keep a
+    residual (what Effective Path Pruning leaves stored); the others read their node as it is.  Returns (handles
+    int32 [req_hi - req_lo, max_blocks], number of items, number of pairs, number of (request, node) uses of a
+    pair)."""
     g, b = wl.graph, wl.batch
     nbl = (g.node_len.astype(np.int64) + BLOCK - 1) // BLOCK
     handles = np.full((req_hi - req_lo, max_blocks), -1, np.int32)
     first_item, items, uses = {}, 0, 0
+    walked = {}
+    if min_uses > 1:
+        for r in range(req_lo, req_hi):
+            path = [int(v) for v in b.path_nodes[b.path_ptr[r]:b.path_ptr[r + 1]]]
+            for i in range(1, len(path)):
+                key = tuple(path[:i + 1])
+                walked[key] = walked.get(key, 0) + 1
     for r in range(req_lo, req_hi):
         path = [int(v) for v in b.path_nodes[b.path_ptr[r]:b.path_ptr[r + 1]]]
         pos = 0
         for i, v in enumerate(path):
             n = int(nbl[v])
-            if i >= 1 and i >= len(path) - depth:
-                key = tuple(path[:i + 1])
+            key = tuple(path[:i + 1])
+            if i >= 1 and i >= len(path) - depth and walked.get(key, min_uses) >= min_uses:
                 if key not in first_item:
                     first_item[key] = items
                     items += n
