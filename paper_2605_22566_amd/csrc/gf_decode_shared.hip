@@ -357,21 +357,6 @@ struct StageCfg {
     static_assert(kRing >= 2 && (kRing - 1) * kLoads < 64, "ring depth: two buffers at least, and wait counts that vmcnt can hold");
 };
 
-// 16-byte-per-lane global -> LDS direct load: lane l fetches the 16 bytes at base + off (uniform base, 32-bit
-// lane offset) and writes LDS bytes [dst + 16 l, +16).  Issued through inline assembly and waited for by
-// hand (dma_wait<N>: at most N of this wave's vector memory operations still in flight), so that several
-// steps can be in flight; the compiler's own waits do not know these loads and can only over-wait.
-typedef __attribute__((address_space(3))) void *lds_ptr_t;
-__device__ __forceinline__ void dma_load(const void *base, uint32_t off, void *lds_dst) {
-    const uint32_t dst = (uint32_t)(uintptr_t)(lds_ptr_t)lds_dst;
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %2, %1" ::"s"(dst), "s"(base), "v"(off) : "memory", "m0");
-}
-template <int N>
-__device__ __forceinline__ void dma_wait() {
-    static_assert(N >= 0 && N < 64, "vmcnt range");
-    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
-}
-
 // Where a residual entry (logical element slot * D + d of a block) sits in a staged image of a bf16 pool (see the
 // staging constants in the kernel): K keeps [slot][d] with the 16-byte pieces of a row at position
 // piece ^ k_swz(block of the step, slot), V keeps [d][slot] with the two 8-slot halves of a row swapped on

@@ -153,6 +153,27 @@ __device__ __forceinline__ void wave_lds_order() {
     __builtin_amdgcn_wave_barrier();
 }
 
+// 16-byte-per-lane global -> LDS direct load: lane l fetches the 16 bytes at base + off + IMM (uniform base in
+// scalar registers, 32-bit lane offset) and writes LDS bytes [lds_dst + IMM + 16 l, +16): the instruction's
+// immediate offset is added to both addresses, so one base and one M0 value serve all loads of an image.  Issued
+// through inline assembly and waited for by hand (dma_wait<N>: at most N of this wave's vector memory operations
+// still in flight; they complete in order), so that a kernel can keep several tiles in flight and wait for its
+// own loads right before the barrier that publishes a tile; the compiler's own waits do not know these loads and
+// can only over-wait.
+typedef __attribute__((address_space(3))) void *lds_ptr_t;
+template <int IMM = 0>
+__device__ __forceinline__ void dma_load(const void *base, uint32_t off, void *lds_dst) {
+    static_assert(IMM >= 0 && IMM < 4096, "immediate offset range of the instruction");
+    const uint32_t dst = (uint32_t)(uintptr_t)(lds_ptr_t)lds_dst;
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %2, %1 offset:%3"
+                 ::"s"(dst), "s"(base), "v"(off), "n"(IMM) : "memory", "m0");
+}
+template <int N = 0>
+__device__ __forceinline__ void dma_wait() {
+    static_assert(N >= 0 && N < 64, "vmcnt range");
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+
 // value held by the lane 32 away (the other half of the wave)
 __device__ __forceinline__ float other_half(float x) { return __shfl_xor(x, 32, 64); }
 

@@ -104,8 +104,6 @@ static_assert(kAhead % kFetch == 0 && kAhead + kFetch <= kRing, "a fetch never l
 // s_waitcnt lgkmcnt(n), other counters untouched
 constexpr int wait_lds(int n) { return 0xC07F | (n << 8); }
 
-typedef __attribute__((address_space(3))) void *lptr_t;
-
 // compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>), in order.
 // The slot schedule of the main loop is written with it, so that "which slot carries which piece
 // of vector work" is decided by if constexpr and never exists as a runtime branch.
@@ -117,20 +115,6 @@ template <int N, class F>
 __device__ __forceinline__ void static_for(F &&f) {
     static_for_impl(f, std::make_integer_sequence<int, N>{});
 }
-
-// 16-byte-per-lane global -> LDS direct load: lane l of load J of a block fetches the 16 bytes at
-// base + off + 1024 J (uniform base in SGPRs, 32-bit lane offset) and writes LDS bytes
-// [dst + 1024 J + 16 l, +16): the instruction's immediate offset is added to both addresses, so one
-// base and one M0 value serve all loads of a block.  Issued through inline assembly so that they
-// are ordered by hand: the kernel waits for its own direct loads (dma_wait) right before the
-// workgroup barrier that publishes a tile, instead of before every LDS read that follows them.
-template <int J>
-__device__ __forceinline__ void dma_load(const void *base, uint32_t off, void *lds_dst) {
-    const uint32_t dst = (uint32_t)(uintptr_t)(lptr_t)lds_dst;
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %2, %1 offset:%3"
-                 ::"s"(dst), "s"(base), "v"(off), "n"(1024 * J) : "memory", "m0");
-}
-__device__ __forceinline__ void dma_wait() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
 // MFMA issue of the main loop.  With one row set per wave the compiler's builtin is used.  With
 // two, the wave owns the whole register file of its SIMD lane (256 VGPRs + 256 accumulation
@@ -356,14 +340,14 @@ __global__ __launch_bounds__(NW * 64, RS == 1 ? 2 : 1) void prefill_kernel(
         const char *src = block_of(a.k, tile);
         static_for<C::kDmaPerWave>([&](auto j_c) {
             constexpr int j = decltype(j_c)::value;
-            dma_load<j>(src, k_off[j], kbuf + buf * C::kKTile + wave * C::kDmaPerWave * 1024);
+            dma_load<1024 * j>(src, k_off[j], kbuf + buf * C::kKTile + wave * C::kDmaPerWave * 1024);
         });
     };
     auto issue_v = [&](int tile, int buf) {
         const char *src = block_of(a.v, tile);
         static_for<C::kDmaPerWave>([&](auto j_c) {
             constexpr int j = decltype(j_c)::value;
-            dma_load<j>(src, v_off[j], vbuf + buf * C::kVTile + wave * C::kDmaPerWave * 1024);
+            dma_load<1024 * j>(src, v_off[j], vbuf + buf * C::kVTile + wave * C::kDmaPerWave * 1024);
         });
     };
 
@@ -707,13 +691,13 @@ __global__ __launch_bounds__(NW * 64, RS == 1 ? 2 : 1) void prefill_kernel(
                 constexpr int j = (i - kStageKSlot) / RS;
                 if constexpr (j == 0) stage_src = block_of(a.k, t + 3);
                 if (k3)                                               // K(t+3) replaces K(t+1)
-                    dma_load<j>(stage_src, k_off[j], kbuf + ((t + 1) & 1) * C::kKTile + wave * C::kDmaPerWave * 1024);
+                    dma_load<1024 * j>(stage_src, k_off[j], kbuf + ((t + 1) & 1) * C::kKTile + wave * C::kDmaPerWave * 1024);
             }
             if constexpr (i >= kStageVSlot && i < kStageVSlot + RS * C::kDmaPerWave && (i - kStageVSlot) % RS == 0) {
                 constexpr int j = (i - kStageVSlot) / RS;
                 if constexpr (j == 0) stage_src = block_of(a.v, t + 2);
                 if (k2)                                               // V(t+2) replaces V(t-1)
-                    dma_load<j>(stage_src, v_off[j], vbuf + ((t + 2) % C::kVBufs) * C::kVTile + wave * C::kDmaPerWave * 1024);
+                    dma_load<1024 * j>(stage_src, v_off[j], vbuf + ((t + 2) % C::kVBufs) * C::kVTile + wave * C::kDmaPerWave * 1024);
             }
             // vector share of every slot: the exponentials of tile t are spread evenly over the
             // slots up to kExpEnd.  An exponential joins the row sum one step later (its consumer
