@@ -25,7 +25,7 @@ EXPORTS = ["gf_create", "gf_destroy", "gf_strerror", "gf_last_hip_error", "gf_re
            "gf_attn_prefill", "gf_attn_prefill_residual", "gf_attn_decode", "gf_attn_decode_residual", "gf_attn_decode_shared", "gf_attn_decode_shared_residual", "gf_decode_shared_plan", "gf_attn_decode_shared_planned",
            "gf_set_decode_chunk_blocks", "gf_kv_apply_residual", "gf_kv_residual_pack", "gf_kv_residual_unpack",
            "gf_kv_apply_residual_packed",
-           "gf_kv_append", "gf_kv_append_token", "gf_attn_prefill_noalloc", "gf_hbm_read_probe", "gf_hbm_tile_probe",
+           "gf_kv_append", "gf_kv_append_token", "gf_attn_prefill_noalloc", "gf_hbm_read_probe", "gf_hbm_tile_probe", "gf_mfma_probe",
            "gf_prefix_key", "gf_residual_dir_clear", "gf_residual_dir_insert", "gf_resolve_path_residual",
            "gf_residual_dir_prune", "gf_kv_make_residual", "gf_block_pool_create", "gf_block_pool_destroy", "gf_block_pool_alloc",
            "gf_block_pool_retain", "gf_block_pool_release", "gf_block_pool_stats", "gf_block_pool_refcount"]
@@ -115,6 +115,8 @@ def load_library(path: Optional[str] = None):
     lib.gf_hbm_tile_probe.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p,
                                       C.c_int32, C.c_void_p]
     lib.gf_hbm_tile_probe.restype = C.c_int32
+    lib.gf_mfma_probe.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p]
+    lib.gf_mfma_probe.restype = C.c_int32
     lib.gf_attn_decode.argtypes = [C.c_void_p, C.POINTER(gf_attn_params), C.POINTER(gf_kv_pool),
                                    C.POINTER(gf_tables), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
     lib.gf_attn_decode.restype = C.c_int32
@@ -287,6 +289,11 @@ def gf_hbm_read_probe(ctx, src, nbytes, wg_sums, num_wg) -> None:
 def gf_hbm_tile_probe(ctx, src, tile_bytes, num_src_tiles, tile_ids, num_tiles, wg_sums, num_wg) -> None:
     rc = load_library().gf_hbm_tile_probe(ctx, _ptr(src), tile_bytes, num_src_tiles, _ptr(tile_ids), num_tiles,
                                           _ptr(wg_sums), num_wg, _stream())
+    _check(ctx, rc)
+
+
+def gf_mfma_probe(ctx, operands, operand_bytes, iters, lane_sums, num_wg) -> None:
+    rc = load_library().gf_mfma_probe(ctx, _ptr(operands), operand_bytes, iters, _ptr(lane_sums), num_wg, _stream())
     _check(ctx, rc)
 
 

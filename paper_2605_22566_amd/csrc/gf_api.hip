@@ -348,6 +348,18 @@ int32_t gf_hbm_tile_probe(gf_ctx *ctx, const void *src, int32_t tile_bytes, int3
     return GF_OK;
 }
 
+int32_t gf_mfma_probe(gf_ctx *ctx, const void *operands, int64_t operand_bytes, int32_t iters, float *lane_sums,
+                      int32_t num_wg, void *stream) {
+    if (!ctx) return GF_ERR_NULL;
+    if (operand_bytes < 1024 || (operand_bytes & 1023) || operand_bytes > ((int64_t)1 << 40) || iters < 0 || num_wg < 0)
+        return GF_ERR_BAD_SHAPE;
+    if (num_wg == 0) return GF_OK;
+    if (!operands || !lane_sums) return GF_ERR_NULL;
+    hipError_t e = gf::launch_mfma_probe(operands, operand_bytes, iters, lane_sums, num_wg, (hipStream_t)stream);
+    if (e != hipSuccess) return fail_hip(ctx, e, "gf_mfma_probe launch");
+    return GF_OK;
+}
+
 int32_t gf_hbm_read_probe(gf_ctx *ctx, const void *src, int64_t bytes, uint32_t *wg_sums, int32_t num_wg,
                           void *stream) {
     if (!ctx) return GF_ERR_NULL;

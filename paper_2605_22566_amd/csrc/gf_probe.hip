@@ -2,6 +2,10 @@
 // measured against on the same box.  Every lane reads 16 bytes per trip, a workgroup walks the buffer with a
 // grid stride (four independent loads in flight per lane), and the words read are folded into one sum per
 // workgroup so that the loads cannot be dropped.  Nothing of the method is computed here.
+//
+// gf_mfma_probe: the same kind of ceiling for the matrix pipes the prefill kernel is measured against -- nothing
+// but v_mfma_f32_32x32x16_bf16 (the prefill's instruction) on operands the caller supplies, so that the rate the
+// chip sustains can be read for zeroed operands and for operands distributed like K, V and Q.
 #include "gf_internal.h"
 
 namespace gf {
@@ -78,6 +82,50 @@ __global__ __launch_bounds__(kProbeThreads) void hbm_tile_probe_kernel(const cha
         for (int w = 0; w < kProbeThreads / 64; ++w) t += part[w];
         wg_sums[blockIdx.x] = t;
     }
+}
+
+// One wave per SIMD and workgroup (more waves per SIMD through more workgroups per CU).  A wave reads eight A
+// and four B fragments (64 lanes x 8 bf16 each) from `operands` once, then issues `iters` rounds of eight MFMAs
+// into four independent accumulators, every MFMA with another pair of fragments than the one before it, so the
+// multiplier inputs change at the rate they do in an attention tile.  The accumulators are folded into one float
+// per lane at the end so that nothing can be dropped.
+constexpr int kProbeA = 8, kProbeB = 4;
+
+__global__ __launch_bounds__(kProbeThreads) void mfma_probe_kernel(const u32x4 *__restrict__ operands, uint32_t n_chunks,
+                                                                  int iters, float *__restrict__ lane_sums) {
+    const int lane = threadIdx.x & 63;
+    const uint32_t wave = blockIdx.x * (kProbeThreads / 64) + (threadIdx.x >> 6);
+    bf16x8 a[kProbeA], b[kProbeB];
+#pragma unroll
+    for (int f = 0; f < kProbeA + kProbeB; ++f) {
+        const uint32_t chunk = (wave * (kProbeA + kProbeB) + f) % n_chunks;          // 1 KB chunks of the buffer
+        const bf16x8 x = __builtin_bit_cast(bf16x8, operands[(size_t)chunk * 64 + lane]);
+        if (f < kProbeA) a[f] = x;
+        else b[f - kProbeA] = x;
+    }
+    f32x16 acc[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[j][i] = 0.f;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int j = 0; j < kProbeA; ++j)
+            acc[j % 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j], b[(j + j / 4) % kProbeB], acc[j % 4], 0, 0, 0);
+    }
+    float sum = 0.f;
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sum += acc[j][i];
+    lane_sums[(size_t)blockIdx.x * kProbeThreads + threadIdx.x] = sum;
+}
+
+hipError_t launch_mfma_probe(const void *operands, int64_t operand_bytes, int32_t iters, float *lane_sums,
+                             int32_t num_wg, hipStream_t s) {
+    hipLaunchKernelGGL(mfma_probe_kernel, dim3((unsigned)num_wg), dim3(kProbeThreads), 0, s, (const u32x4 *)operands,
+                       (uint32_t)(operand_bytes / 1024), iters, lane_sums);
+    return hipGetLastError();
 }
 
 hipError_t launch_hbm_tile_probe(const void *src, int32_t tile_bytes, int32_t num_src_tiles, const int32_t *ids,
