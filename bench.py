@@ -542,10 +542,11 @@ def measure_stream_tiles(torch, R, W, iters=10, gib=4):
 
 
 def measure_mfma_probe(torch, R, W, iters=10, mfma_rounds=(4000, 32000)):
-    """The matrix-pipe ceiling of the box for the prefill's instruction (gf_mfma_probe: v_mfma_f32_32x32x16_bf16 and
-    nothing else), on zeroed operands and on N(0, 1) bf16 operands (what K, V and Q hold), at one and at two
-    waves per SIMD, in launches of about 0.5-1 ms and of about 4-10 ms: the instruction stream is the same, what
-    differs is what the datapaths toggle -- and with it the clock the chip's power management allows."""
+    """The matrix-pipe ceiling of the box for the prefill's instruction (gf_mfma_probe: v_mfma_f32_32x32x16_bf16 alone,
+    and with the six vector instructions -- one exponential -- that a softmax spends per MFMA at head_dim 128), on
+    zeroed operands and on N(0, 1) bf16 operands (what K, V and Q hold), at one and at two waves per SIMD, in
+    launches of about 0.5-1.5 ms and of about 4-12 ms: the instruction stream is the same, what differs is what the
+    datapaths toggle -- and with it the clock the chip's power management allows."""
     from paper_2605_22566_amd import binding as B
     dev = torch.device("cuda:0")
     sess = R.Session(W.small_layered(1, W.Shape(8, 2, 128), num_req=1), dev)
@@ -556,30 +557,34 @@ def measure_mfma_probe(torch, R, W, iters=10, mfma_rounds=(4000, 32000)):
     operands = {"zeros": torch.zeros(nbytes // 2, dtype=torch.bfloat16, device=dev),
                 "normal": torch.randn(nbytes // 2, generator=gen, device=dev).to(torch.bfloat16)}
     out = {"kernel": "mfma_probe_kernel", "instruction": "v_mfma_f32_32x32x16_bf16", "runs": []}
-    for rounds in mfma_rounds:
-        for what, buf in operands.items():
-            for waves_per_simd in (1, 2):
-                num_wg = cus * waves_per_simd
-                sums = torch.zeros(num_wg * 256, dtype=torch.float32, device=dev)
-                fn = lambda: B.gf_mfma_probe(sess.ctx, buf, nbytes, rounds, sums, num_wg)
-                for _ in range(3):
-                    fn()
-                torch.cuda.synchronize()
-                ms = _event_ms(fn, torch, iters)
-                flops = num_wg * 4 * rounds * 8 * 32768.0
-                tf = flops / (ms * 1e-3) / 1e12
-                out["runs"].append({"operands": what, "waves_per_simd": waves_per_simd, "mfma_per_wave": 8 * rounds,
-                                    "kernel_ms": ms, "tflops": tf, "frac_of_mfma_peak": tf / PEAK_MFMA_BF16_TFLOPS,
-                                    "sums_finite": bool(torch.isfinite(sums).all().item()),
-                                    "sums_zero": bool((sums == 0).all().item())})
-    operands_names = tuple(operands)
+    for mix in (0, 1):
+        for rounds in mfma_rounds:
+            for what, buf in operands.items():
+                for waves_per_simd in (1, 2):
+                    num_wg = cus * waves_per_simd
+                    sums = torch.zeros(num_wg * 256, dtype=torch.float32, device=dev)
+                    fn = lambda: B.gf_mfma_probe(sess.ctx, buf, nbytes, rounds, sums, num_wg, softmax_mix=mix)
+                    for _ in range(3):
+                        fn()
+                    torch.cuda.synchronize()
+                    ms = _event_ms(fn, torch, iters)
+                    flops = num_wg * 4 * rounds * 8 * 32768.0
+                    tf = flops / (ms * 1e-3) / 1e12
+                    out["runs"].append({"operands": what, "softmax_mix": mix, "waves_per_simd": waves_per_simd,
+                                        "mfma_per_wave": 8 * rounds, "kernel_ms": ms, "tflops": tf,
+                                        "frac_of_mfma_peak": tf / PEAK_MFMA_BF16_TFLOPS,
+                                        "sums_finite": bool(torch.isfinite(sums).all().item())})
     del operands
     torch.cuda.empty_cache()
-    best = {w: max(r["tflops"] for r in out["runs"] if r["operands"] == w and r["mfma_per_wave"] == 8 * mfma_rounds[-1])
-            for w in operands_names}
-    out["tflops_zeros"], out["tflops_normal"] = best["zeros"], best["normal"]      # the long launches
-    out["normal_over_zeros"] = best["normal"] / best["zeros"]
-    out["frac_of_mfma_peak_normal"] = best["normal"] / PEAK_MFMA_BF16_TFLOPS
+
+    def best(what, mix):                                   # the long launches
+        return max(r["tflops"] for r in out["runs"] if r["operands"] == what and r["softmax_mix"] == mix
+                   and r["mfma_per_wave"] == 8 * mfma_rounds[-1])
+    out["tflops_zeros"], out["tflops_normal"] = best("zeros", 0), best("normal", 0)
+    out["tflops_zeros_softmax_mix"], out["tflops_normal_softmax_mix"] = best("zeros", 1), best("normal", 1)
+    out["normal_over_zeros"] = out["tflops_normal"] / out["tflops_zeros"]
+    out["frac_of_mfma_peak_normal"] = out["tflops_normal"] / PEAK_MFMA_BF16_TFLOPS
+    out["frac_of_mfma_peak_normal_softmax_mix"] = out["tflops_normal_softmax_mix"] / PEAK_MFMA_BF16_TFLOPS
     return out
 
 

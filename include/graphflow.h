@@ -640,17 +640,20 @@ int32_t gf_hbm_tile_probe(gf_ctx *ctx, const void *src, int32_t tile_bytes, int3
 
 /*
  * gf_mfma_probe -- measurement aid, no part of the method: the rate at which the box issues the prefill kernel's
- * matrix instruction (v_mfma_f32_32x32x16_bf16) and nothing else, on operands the caller chooses.  `operands`
- * (device) holds operand_bytes bytes of bf16 values (a multiple of 1024, at least 1024); every wave takes twelve
- * 1 KB fragments from it (eight A, four B; wave w starts at fragment 12 w, wrapping round) and issues
- * iters x 8 MFMAs (32 x 32 x 16 each: 32 768 flop) into four independent accumulators, a different fragment pair
- * for every MFMA.  num_wg workgroups of 256 threads (one wave per SIMD each); lane_sums[num_wg * 256] (device,
- * out) receives one float per lane folded from its accumulators.  Timed by the benchmark on zeroed and on
- * normally distributed operands: the difference is what the chip's power management takes from the clock.
- * GF_ERR_BAD_SHAPE for sizes outside the above, GF_ERR_NULL for missing buffers.
+ * matrix instruction (v_mfma_f32_32x32x16_bf16) on operands the caller chooses, alone (softmax_mix = 0) or with
+ * the vector instructions a softmax spends per MFMA at head_dim 128 riding along (softmax_mix = 1: six per MFMA,
+ * one of them an exponential, on values that keep changing; no LDS or memory traffic in either form).
+ * `operands` (device) holds operand_bytes bytes of bf16 values (a multiple of 1024, at least 1024); every wave
+ * takes twelve 1 KB fragments from it (eight A, four B; wave w starts at fragment 12 w, wrapping round) and
+ * issues iters x 8 MFMAs (32 x 32 x 16 each: 32 768 flop) into four independent accumulators, a different
+ * fragment pair for every MFMA.  num_wg workgroups of 256 threads (one wave per SIMD each);
+ * lane_sums[num_wg * 256] (device, out) receives one float per lane folded from its accumulators (and, with
+ * softmax_mix, its vector values).  Timed by the benchmark on zeroed and on normally distributed operands: the
+ * difference is what the chip's power management takes from the clock.
+ * GF_ERR_BAD_SHAPE for sizes or a softmax_mix outside the above, GF_ERR_NULL for missing buffers.
  */
-int32_t gf_mfma_probe(gf_ctx *ctx, const void *operands, int64_t operand_bytes, int32_t iters, float *lane_sums,
-                      int32_t num_wg, void *stream);
+int32_t gf_mfma_probe(gf_ctx *ctx, const void *operands, int64_t operand_bytes, int32_t iters, int32_t softmax_mix,
+                      float *lane_sums, int32_t num_wg, void *stream);
 
 /* Tuning knob (host): table entries (16-token blocks) per split-KV chunk in
  * gf_attn_decode and gf_attn_decode_residual (built-in choice 64) and gf_attn_decode_shared (built-in choice and upper limit 64);

@@ -115,7 +115,8 @@ def load_library(path: Optional[str] = None):
     lib.gf_hbm_tile_probe.argtypes = [C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.c_int64, C.c_void_p,
                                       C.c_int32, C.c_void_p]
     lib.gf_hbm_tile_probe.restype = C.c_int32
-    lib.gf_mfma_probe.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p, C.c_int32, C.c_void_p]
+    lib.gf_mfma_probe.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_void_p, C.c_int32,
+                                  C.c_void_p]
     lib.gf_mfma_probe.restype = C.c_int32
     lib.gf_attn_decode.argtypes = [C.c_void_p, C.POINTER(gf_attn_params), C.POINTER(gf_kv_pool),
                                    C.POINTER(gf_tables), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
@@ -292,8 +293,9 @@ def gf_hbm_tile_probe(ctx, src, tile_bytes, num_src_tiles, tile_ids, num_tiles, 
     _check(ctx, rc)
 
 
-def gf_mfma_probe(ctx, operands, operand_bytes, iters, lane_sums, num_wg) -> None:
-    rc = load_library().gf_mfma_probe(ctx, _ptr(operands), operand_bytes, iters, _ptr(lane_sums), num_wg, _stream())
+def gf_mfma_probe(ctx, operands, operand_bytes, iters, lane_sums, num_wg, softmax_mix=0) -> None:
+    rc = load_library().gf_mfma_probe(ctx, _ptr(operands), operand_bytes, iters, softmax_mix, _ptr(lane_sums), num_wg,
+                                      _stream())
     _check(ctx, rc)
 
 

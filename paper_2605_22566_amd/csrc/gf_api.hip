@@ -348,14 +348,16 @@ int32_t gf_hbm_tile_probe(gf_ctx *ctx, const void *src, int32_t tile_bytes, int3
     return GF_OK;
 }
 
-int32_t gf_mfma_probe(gf_ctx *ctx, const void *operands, int64_t operand_bytes, int32_t iters, float *lane_sums,
-                      int32_t num_wg, void *stream) {
+int32_t gf_mfma_probe(gf_ctx *ctx, const void *operands, int64_t operand_bytes, int32_t iters, int32_t softmax_mix,
+                      float *lane_sums, int32_t num_wg, void *stream) {
     if (!ctx) return GF_ERR_NULL;
-    if (operand_bytes < 1024 || (operand_bytes & 1023) || operand_bytes > ((int64_t)1 << 40) || iters < 0 || num_wg < 0)
+    if (operand_bytes < 1024 || (operand_bytes & 1023) || operand_bytes > ((int64_t)1 << 40) || iters < 0 || num_wg < 0 ||
+        (softmax_mix != 0 && softmax_mix != 1))
         return GF_ERR_BAD_SHAPE;
     if (num_wg == 0) return GF_OK;
     if (!operands || !lane_sums) return GF_ERR_NULL;
-    hipError_t e = gf::launch_mfma_probe(operands, operand_bytes, iters, lane_sums, num_wg, (hipStream_t)stream);
+    hipError_t e = gf::launch_mfma_probe(operands, operand_bytes, iters, softmax_mix, lane_sums, num_wg,
+                                         (hipStream_t)stream);
     if (e != hipSuccess) return fail_hip(ctx, e, "gf_mfma_probe launch");
     return GF_OK;
 }

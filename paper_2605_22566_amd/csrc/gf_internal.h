@@ -65,8 +65,8 @@ hipError_t launch_hbm_read_probe(const void *src, size_t bytes, uint32_t *wg_sum
 hipError_t launch_hbm_tile_probe(const void *src, int32_t tile_bytes, int32_t num_src_tiles, const int32_t *ids,
                                  int64_t num_tiles, uint32_t *wg_sums, int32_t num_wg, hipStream_t s);
 // MFMA issue probe: operand_bytes a multiple of 1024, one float per lane of num_wg workgroups of 256 threads
-hipError_t launch_mfma_probe(const void *operands, int64_t operand_bytes, int32_t iters, float *lane_sums,
-                             int32_t num_wg, hipStream_t s);
+hipError_t launch_mfma_probe(const void *operands, int64_t operand_bytes, int32_t iters, int32_t softmax_mix,
+                             float *lane_sums, int32_t num_wg, hipStream_t s);
 
 // built-in split-KV chunk sizes (table entries per work item) of gf_attn_decode and gf_attn_decode_residual
 constexpr int32_t kDecodeChunkBlocks = 64, kDecodeChunkBlocksResidual = 64;   // equal: the two calls are interchangeable bit for bit

@@ -87,10 +87,13 @@ __global__ __launch_bounds__(kProbeThreads) void hbm_tile_probe_kernel(const cha
 // One wave per SIMD and workgroup (more waves per SIMD through more workgroups per CU).  A wave reads eight A
 // and four B fragments (64 lanes x 8 bf16 each) from `operands` once, then issues `iters` rounds of eight MFMAs
 // into four independent accumulators, every MFMA with another pair of fragments than the one before it, so the
-// multiplier inputs change at the rate they do in an attention tile.  The accumulators are folded into one float
-// per lane at the end so that nothing can be dropped.
+// multiplier inputs change at the rate they do in an attention tile.  With MIX every MFMA is followed by the
+// vector instructions a softmax spends per MFMA at head_dim 128 -- six, one of them an exponential -- on values
+// that keep changing (x <- fract(x * k + y) walks over [0, 1) without settling).  The accumulators and the
+// vector values are folded into one float per lane at the end so that nothing can be dropped.
 constexpr int kProbeA = 8, kProbeB = 4;
 
+template <bool MIX>
 __global__ __launch_bounds__(kProbeThreads) void mfma_probe_kernel(const u32x4 *__restrict__ operands, uint32_t n_chunks,
                                                                   int iters, float *__restrict__ lane_sums) {
     const int lane = threadIdx.x & 63;
@@ -108,12 +111,27 @@ __global__ __launch_bounds__(kProbeThreads) void mfma_probe_kernel(const u32x4 *
     for (int j = 0; j < 4; ++j)
 #pragma unroll
         for (int i = 0; i < 16; ++i) acc[j][i] = 0.f;
+    // vector state: four values in [0, 1) taken from the mantissas of the first fragment (zero operands: zeros)
+    float x[4], esum = 0.f;
+    {
+        const u32x4 w = __builtin_bit_cast(u32x4, a[0]);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) x[i] = __uint_as_float((w[i] & 0x007fffffu) | 0x3f800000u) - 1.0f;
+    }
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
-        for (int j = 0; j < kProbeA; ++j)
+        for (int j = 0; j < kProbeA; ++j) {
             acc[j % 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[j], b[(j + j / 4) % kProbeB], acc[j % 4], 0, 0, 0);
+            if constexpr (MIX) {
+                float &p = x[j % 4], &q = x[(j + 1) % 4];
+                p = __builtin_amdgcn_fractf(__builtin_fmaf(p, 1.6180340f, q));
+                q = __builtin_amdgcn_fractf(__builtin_fmaf(q, 2.4142137f, p));
+                esum = __builtin_fmaf(fast_exp2(p), 0.001f, esum);
+                __builtin_amdgcn_sched_barrier(0);                  // the vector work stays behind its MFMA
+            }
+        }
     }
-    float sum = 0.f;
+    float sum = MIX ? (x[0] + x[1]) + (x[2] + x[3]) + esum : 0.f;
 #pragma unroll
     for (int j = 0; j < 4; ++j)
 #pragma unroll
@@ -121,10 +139,15 @@ __global__ __launch_bounds__(kProbeThreads) void mfma_probe_kernel(const u32x4 *
     lane_sums[(size_t)blockIdx.x * kProbeThreads + threadIdx.x] = sum;
 }
 
-hipError_t launch_mfma_probe(const void *operands, int64_t operand_bytes, int32_t iters, float *lane_sums,
-                             int32_t num_wg, hipStream_t s) {
-    hipLaunchKernelGGL(mfma_probe_kernel, dim3((unsigned)num_wg), dim3(kProbeThreads), 0, s, (const u32x4 *)operands,
-                       (uint32_t)(operand_bytes / 1024), iters, lane_sums);
+hipError_t launch_mfma_probe(const void *operands, int64_t operand_bytes, int32_t iters, int32_t softmax_mix,
+                             float *lane_sums, int32_t num_wg, hipStream_t s) {
+    const dim3 grid((unsigned)num_wg), block(kProbeThreads);
+    if (softmax_mix)
+        hipLaunchKernelGGL(mfma_probe_kernel<true>, grid, block, 0, s, (const u32x4 *)operands,
+                           (uint32_t)(operand_bytes / 1024), iters, lane_sums);
+    else
+        hipLaunchKernelGGL(mfma_probe_kernel<false>, grid, block, 0, s, (const u32x4 *)operands,
+                           (uint32_t)(operand_bytes / 1024), iters, lane_sums);
     return hipGetLastError();
 }
 

@@ -65,6 +65,13 @@ def test_mfma_probe_issues_what_it_says():
     torch.cuda.synchronize()
     # every MFMA adds 16 (a contraction over 16 ones) to the 16 accumulator elements a lane holds; a round issues 8
     assert torch.equal(sums, torch.full_like(sums, 16.0 * 16 * 8 * rounds))
+    # with the softmax's vector instructions riding along: the same MFMAs, plus four values in [0, 1) and a sum of
+    # 8 * rounds exponentials of such values, each scaled by 0.001
+    mixed = torch.full_like(sums, -1.0)
+    B.gf_mfma_probe(sess.ctx, ones, ones.numel() * 2, rounds, mixed, num_wg, softmax_mix=1)
+    torch.cuda.synchronize()
+    extra = mixed - sums
+    assert bool(((extra > 0) & (extra < 4 + 0.002 * 8 * rounds + 0.1)).all())      # 0.1: rounding of the fold at 1e4
     zeros = torch.zeros(512, dtype=torch.bfloat16, device=dev)        # one 1 KB fragment, used by everybody
     B.gf_mfma_probe(sess.ctx, zeros, 1024, rounds, sums, num_wg)
     torch.cuda.synchronize()
@@ -89,6 +96,7 @@ def test_probe_argument_checks():
     assert _code(lambda: B.gf_mfma_probe(sess.ctx, buf, 1000, 1, fsums, 1)) == B.GF_ERR_BAD_SHAPE
     assert _code(lambda: B.gf_mfma_probe(sess.ctx, buf, 0, 1, fsums, 1)) == B.GF_ERR_BAD_SHAPE
     assert _code(lambda: B.gf_mfma_probe(sess.ctx, buf, 1024, -1, fsums, 1)) == B.GF_ERR_BAD_SHAPE
+    assert _code(lambda: B.gf_mfma_probe(sess.ctx, buf, 1024, 1, fsums, 1, softmax_mix=2)) == B.GF_ERR_BAD_SHAPE
     assert _code(lambda: B.gf_mfma_probe(sess.ctx, None, 1024, 1, fsums, 1)) == B.GF_ERR_NULL
     assert _code(lambda: B.gf_mfma_probe(sess.ctx, buf, 1024, 1, None, 1)) == B.GF_ERR_NULL
     B.gf_mfma_probe(sess.ctx, None, 1024, 1, None, 0)               # no workgroup: nothing read, nothing launched
