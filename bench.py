@@ -647,7 +647,7 @@ def measure_residual(torch, R, W, num_items=8192, iters=20):
     torch.cuda.synchronize()
     msm = _event_ms(fnm, torch, 3)
     nnz_made = int(made["ptr"][-1].item())
-    out["make_residual"] = {"kernel": "make_residual_kernel (count + scan + fill)", "kernel_ms": msm, "blocks": num_items,
+    out["make_residual"] = {"kernel": "make_residual_count_kernel + make_residual_scan_kernel + make_residual_fill_kernel", "kernel_ms": msm, "blocks": num_items,
                             "entries_kept_at_95pct_energy": nnz_made, "entries_of_the_source_residual": nnz,
                             "algorithmic_bytes_per_launch": 2.0 * num_items * 2 * blk + 4.0 * nnz_made,
                             "gbs_kernel": (2.0 * num_items * 2 * blk + 4.0 * nnz_made) / (msm * 1e-3) / 1e9,

@@ -25,7 +25,8 @@
  *   - The library owns only a gf_ctx: device scratch memory (the split-KV
  *     partials of gf_attn_decode, the work list of gf_attn_prefill, the lists and
  *     partials of gf_attn_decode_shared / gf_decode_shared_plan; their
- *     residual-reading forms use the same buffers), grown on
+ *     residual-reading forms use the same buffers; gf_kv_make_residual keeps
+ *     8 bytes per CSR row in the decode buffer between its passes), grown on
  *     demand -- these calls may therefore call hipMalloc, and hipFree after a
  *     stream synchronisation when it outgrows what it has -- and released by
  *     gf_destroy.  A gf_ctx must not be used from two streams at once.  Once a

@@ -610,9 +610,14 @@ int32_t gf_kv_make_residual(gf_ctx *ctx, const gf_attn_params *params, const voi
     if (num_items == 0) return GF_OK;
     if (!k_pool || !v_pool || !base_blocks || !full_blocks || !res_ptr) return GF_ERR_NULL;
     if (capacity > 0 && (!res_idx || !res_val)) return GF_ERR_NULL;
+    // one sort key per CSR row between the counting and the filling pass, in the context's workspace
+    const int32_t rc = ensure_buffer(ctx, &ctx->workspace, &ctx->workspace_bytes,
+                                     gf::make_residual_scratch_bytes(params->num_kv_heads, num_items), (hipStream_t)stream,
+                                     "gf_kv_make_residual workspace");
+    if (rc != GF_OK) return rc;
     hipError_t e = gf::launch_make_residual(k_pool, v_pool, num_pool_blocks, params->num_kv_heads, params->head_dim,
                                             num_items, base_blocks, full_blocks, energy_share, capacity, res_ptr, res_idx,
-                                            res_val, status, (hipStream_t)stream);
+                                            res_val, status, ctx->workspace, (hipStream_t)stream);
     if (e == hipErrorNotSupported) return GF_ERR_UNSUPPORTED;
     if (e != hipSuccess) return fail_hip(ctx, e, "gf_kv_make_residual launch");
     return GF_OK;

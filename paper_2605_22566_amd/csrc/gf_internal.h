@@ -118,11 +118,13 @@ hipError_t launch_residual_packed(void *k_pool, void *v_pool, int32_t num_pool_b
                                   const int32_t *res_ptr, const uint32_t *res_mask, const uint16_t *packed_val,
                                   int32_t *status, hipStream_t s);
 
-// residual producer: dense prefix-conditioned blocks -> CSR by the energy rule (count, scan, fill)
+// residual producer: dense prefix-conditioned blocks -> CSR by the energy rule (count, scan, fill); cut_keys is
+// device scratch of make_residual_scratch_bytes() bytes (one 8-byte sort key per CSR row)
+size_t make_residual_scratch_bytes(int32_t hkv, int32_t num_items);
 hipError_t launch_make_residual(const void *k_pool, const void *v_pool, int32_t num_pool_blocks, int32_t hkv,
                                 int32_t head_dim, int32_t num_items, const int32_t *base_blocks,
                                 const int32_t *full_blocks, double share, int32_t capacity, int32_t *res_ptr,
-                                uint16_t *res_idx, uint16_t *res_val, int32_t *status, hipStream_t s);
+                                uint16_t *res_idx, uint16_t *res_val, int32_t *status, void *cut_keys, hipStream_t s);
 
 // KV write path: one workgroup per (request, tail block); max_q bounds the new tokens of a request
 hipError_t launch_append(void *k_pool, void *v_pool, float *k_scale, float *v_scale, int32_t pool_blocks, int32_t hkv,
