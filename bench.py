@@ -933,6 +933,18 @@ def main():
         torch.cuda.empty_cache()
     if extra:
         res["extra"] = extra
+    # the headline beside the ceilings measured in this run: an MFMA-bound line against the probe on N(0, 1)
+    # operands with a softmax's vector work riding along (issued flops against issued flops would be fairer still:
+    # the kernel's masked pairs are not in `achieved`), an HBM-bound line against the tile-order read probe
+    rf = res.get("roofline") or {}
+    if rf.get("bound") == "mfma" and "mfma_probe" in extra:
+        rf["probe_tflops_normal_operands"] = extra["mfma_probe"]["tflops_normal"]
+        rf["probe_tflops_normal_operands_softmax_mix"] = extra["mfma_probe"]["tflops_normal_softmax_mix"]
+        rf["frac_of_probe_softmax_mix"] = rf["achieved"] / extra["mfma_probe"]["tflops_normal_softmax_mix"]
+    if rf.get("bound") == "hbm" and "stream_tiles" in extra:
+        best = max(r["gbs_read"] for r in extra["stream_tiles"]["runs"])
+        rf["probe_gbs_tile_reads"] = best
+        rf["frac_of_probe_tile_reads"] = rf["achieved"] / best
     print(json.dumps(res))
 
 
