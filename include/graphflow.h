@@ -28,7 +28,9 @@
  *     residual-reading forms use the same buffers; gf_kv_make_residual keeps
  *     8 bytes per CSR row in the decode buffer between its passes), grown on
  *     demand -- these calls may therefore call hipMalloc, and hipFree after a
- *     stream synchronisation when it outgrows what it has -- and released by
+ *     stream synchronisation when it outgrows what it has (a buffer that grows
+ *     again takes half as much more than it had, so a loop whose sizes creep up
+ *     drains its stream a few times, not at every step) -- and released by
  *     gf_destroy.  A gf_ctx must not be used from two streams at once.  Once a
  *     call has run with given sizes, repeating it allocates nothing, so a sequence
  *     of calls can be recorded into a HIP graph after one warm-up pass.

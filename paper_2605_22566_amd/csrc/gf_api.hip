@@ -89,9 +89,12 @@ int32_t check_attn(const gf_attn_params *p, const gf_kv_pool *pool, const gf_tab
 }
 
 // Make a context-owned device buffer at least `need` bytes.  Growing frees the old buffer, which
-// kernels already enqueued may still use: the stream is synchronised first.
+// kernels already enqueued may still use: the stream is synchronised first.  A buffer that grows again takes
+// half as much more than it had (a decode loop whose tails lengthen asks for a little more every few steps:
+// the stream is then drained a logarithmic number of times, not once per growth); the first allocation is exact.
 int32_t ensure_buffer(gf_ctx *ctx, void **buf, size_t *have, size_t need, hipStream_t stream, const char *what) {
     if (need <= *have) return GF_OK;
+    const size_t roomy = *have + *have / 2;
     hipError_t e = hipStreamSynchronize(stream);
     if (e != hipSuccess) return fail_hip(ctx, e, what);
     if (*buf) {
@@ -100,13 +103,19 @@ int32_t ensure_buffer(gf_ctx *ctx, void **buf, size_t *have, size_t need, hipStr
         *have = 0;
         if (e != hipSuccess) return fail_hip(ctx, e, what);
     }
-    e = hipMalloc(buf, need);
+    size_t want = need > roomy ? need : roomy;
+    e = hipMalloc(buf, want);
+    if (e != hipSuccess && want > need) {              // no room for the margin: take what is needed
+        (void)hipGetLastError();
+        want = need;
+        e = hipMalloc(buf, want);
+    }
     if (e != hipSuccess) {
         *buf = nullptr;
         fail_hip(ctx, e, what);
         return GF_ERR_WORKSPACE;
     }
-    *have = need;
+    *have = want;
     return GF_OK;
 }
 

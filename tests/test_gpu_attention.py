@@ -6,8 +6,10 @@ import numpy as np
 import pytest
 import torch
 
+from paper_2605_22566_amd import runner as R
 from paper_2605_22566_amd import workload as W
-from tests.gpu_common import (assert_close, oracle_decode, oracle_prefill, run_decode, run_prefill)
+from tests.gpu_common import (assert_close, bf16_out_to_f64, oracle_decode, oracle_prefill, run_decode, run_prefill,
+                              run_resolve)
 
 pytestmark = pytest.mark.gpu
 
@@ -188,3 +190,26 @@ def test_decode_entries_without_tokens_give_zero_rows():
         Od, _ = oracle_decode(wl, t, last)
         keep = np.array([0, 2, 3])
         assert_close(od[keep], Od[keep], sh.kv_dtype, "decode, others")
+
+
+def test_one_context_through_growing_batches():
+    """A context's workspace grows three times here (2, 5 and 12 requests through the same gf_ctx, then 3 again):
+    every call gives the rows a call on a fresh context gives."""
+    sh = W.Shape(8, 2, 128)
+    wl = W.small_layered(77, sh, num_nodes=24, num_layers=6, len_lo=20, len_hi=300, num_req=12, hops=(2, 5),
+                         new_lo=1, new_hi=4)
+    t = W.make_tensors(wl)
+    want = run_decode(wl, t)[0]
+    sess, tables = run_resolve(wl)
+    dev = sess.device
+    pool = R.DevicePool.from_host(t, dev)
+    last = (t.q_ptr[1:] - 1).astype(np.int64)
+    qd = R.bits_to_device(np.ascontiguousarray(t.q[last]), dev)
+    for n in (2, 5, 12, 3):
+        sub = {k: tables[k][:n] for k in ("block_table", "block_ntok", "num_blocks", "ctx_lens", "seq_lens", "status")}
+        sub["num_req"], sub["max_blocks"] = n, tables["max_blocks"]
+        o = torch.full((n,) + tuple(qd.shape[1:]), float("nan"), dtype=torch.bfloat16, device=dev)
+        sess.decode(pool, sub, qd[:n], o)
+        torch.cuda.synchronize()
+        assert np.array_equal(bf16_out_to_f64(o), want[:n]), n
+
