@@ -82,7 +82,9 @@ typedef struct gf_ctx gf_ctx;
 /* wGraph as CSR arrays (device).  Node v owns the token segment of length
  * node_len[v] stored in blocks node_blocks[node_block_ptr[v] .. node_block_ptr[v+1]).
  * edge_dst[edge_ptr[v] .. edge_ptr[v+1]) are v's valid successors; edge_ptr and
- * edge_dst may both be NULL, which skips edge validation. */
+ * edge_dst may both be NULL, which skips edge validation (one of them alone is
+ * GF_ERR_NULL: a graph that validates edges and has none still hands over an
+ * edge_dst address, which is never read). */
 typedef struct {
     int32_t        num_nodes;
     const int32_t *node_len;        /* [num_nodes]     */

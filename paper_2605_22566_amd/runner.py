@@ -115,7 +115,8 @@ class Session:
         g = wl.graph
         up = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(self.device)
         self.node_len, self.node_block_ptr, self.node_blocks = up(g.node_len), up(g.node_block_ptr), up(g.node_blocks)
-        self.edge_ptr, self.edge_dst = up(g.edge_ptr), up(g.edge_dst)
+        # a graph without edges still hands over an edge array (an empty tensor has no address)
+        self.edge_ptr, self.edge_dst = up(g.edge_ptr), up(g.edge_dst if len(g.edge_dst) else [0])
         self._up = up
 
     def close(self):
