@@ -257,13 +257,15 @@ def make_residual(k_pool: np.ndarray, v_pool: np.ndarray, base_blocks, full_bloc
 def select_by_energy(delta: np.ndarray, share: float = 0.95) -> np.ndarray:
     """Indices (into delta.ravel()) of the fewest largest-magnitude entries whose
     squared sum is at least `share` of the total; ties broken by lower index.
-    An all-zero difference keeps nothing."""
+    An all-zero difference keeps nothing.  The total is the end of the same running
+    sum the prefixes are taken from (one summation, along the ranking), so that
+    share = 1 keeps exactly the non-zero entries whatever the rounding."""
     flat = np.ascontiguousarray(delta, dtype=np.float64).ravel()
     energy = flat * flat
-    total = energy.sum()
-    if total == 0.0:
-        return np.zeros(0, dtype=np.int64)
     order = np.lexsort((np.arange(flat.size), -energy))    # by energy descending, then index
     cum = np.cumsum(energy[order])
+    total = cum[-1] if cum.size else 0.0
+    if total == 0.0:
+        return np.zeros(0, dtype=np.int64)
     keep = int(np.searchsorted(cum, share * total, side="left")) + 1
     return np.sort(order[:min(keep, flat.size)])

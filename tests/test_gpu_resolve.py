@@ -50,6 +50,15 @@ def test_all_benchmark_configs_bit_exact(cfg):
     assert all(s == 0 for s in want["status"])
 
 
+def test_single_layer_graph_has_no_edges_and_still_validates():
+    """One layer: every path is one node, the graph has no edge at all, and edge validation is on."""
+    wl = W.small_layered(61, W.Shape(4, 4, 64), num_nodes=9, num_layers=1, len_lo=3, len_hi=80, num_req=7, hops=(1, 4),
+                         new_lo=1, new_hi=30)
+    assert wl.graph.edge_dst.size == 0 and (np.diff(wl.batch.path_ptr) == 1).all()
+    sess, tables = run_resolve(wl)
+    assert_tables_equal(tables, oracle_resolve(wl))
+
+
 def test_long_path_spans_several_scan_chunks():
     """A 700-node chain (more than two 256-node chunks of the kernel's scan) with
     ragged lengths, zero-length nodes included."""

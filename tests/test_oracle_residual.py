@@ -160,6 +160,12 @@ def test_select_by_energy_matches_brute_force_and_its_invariants():
     assert e[keep].sum() - e[keep].min() < 0.95 * e.sum()      # dropping the smallest kept entry falls short
     assert e[keep].min() >= np.delete(e, keep).max()           # nothing larger was left out
     assert OR.select_by_energy(np.zeros(7)).size == 0
+    # the whole energy = every non-zero entry and nothing else, whatever the rounding of the sums (a total taken by
+    # another summation than the running sum can stay above every prefix and would keep the zeros too)
+    for seed in range(20):
+        r2 = np.random.default_rng(seed)
+        d = (r2.standard_normal((16, 128)) * (r2.random((16, 128)) < 0.6)).astype(np.float32)
+        assert np.array_equal(OR.select_by_energy(d, 1.0), np.flatnonzero(d.ravel()))
 
 
 # ---- e4m3 pools ---------------------------------------------------------------------------------
